@@ -1,0 +1,245 @@
+/*
+ * LongFlow decode-step ORACLE  --  test infrastructure, not product code.
+ *
+ * A plain, slow, double-precision CPU statement of what one LongFlow decode
+ * step computes over a fixed-budget static KV cache.  Only the tests, the
+ * smoke check and the benchmark's cpu_baseline leg may call it; the GPU
+ * library shares no code, header, table or helper with this file.
+ *
+ * What it computes, per (batch b, KV head g) unit and per decode step t
+ * (ordering: Fig. 2 left -- the new K/V first covers the slot chosen by the
+ * previous step, then the cache and the query go through attention):
+ *
+ *   1. insert    K[slot] <- k_t, V[slot] <- v_t, slot = pending
+ *                (pending = count while the cache is still filling)
+ *   2. logits    s_h^i = q_h . k^i / sqrt(d_k)              (eq. 1, eq. 4)
+ *   3. weights   alpha_h^i = exp(s_h^i) / sum_j exp(s_h^j)  (eq. 1, eq. 4)
+ *   4. output    o_h = sum_i alpha_h^i v^i                  (eq. 1)
+ *   5. score     LongFlowScore(i) = sum_{h in group} alpha_h^i * ||v^i||_1
+ *                (eq. 6 per head; the sum over the query heads that share
+ *                 the KV head is this build's reading -- the paper omits
+ *                 heads, Sec. 2.1)
+ *   6. evict     pending <- argmin_i score(i) once the cache is full,
+ *                lowest index on exact ties  (Sec. 3.2 last paragraph,
+ *                Alg. 1 post-processing); while filling, pending <- count.
+ *
+ * The method reaches these plain definitions exactly (the fused kernel of
+ * Alg. 1 is only a faster route), so the oracle IS the definitions written
+ * out.  Max-subtraction inside the softmax is the textbook, exact-arithmetic
+ * equivalent of the max-free form in Alg. 1 and keeps exp() in range.
+ *
+ * Pins (tests, CPU only): naive softmax attention via a library routine,
+ * sum(alpha)=1, eq. 6 at group size 1, closed-form argmin cases, the exact
+ * leave-one-out identity and bound of App. A.1, a literal numpy rendering of
+ * Alg. 1, brute-force argmin, slot-permutation equivariance, and the fill /
+ * one-row-changes-per-step invariants of the static cache (Sec. 3.4).
+ * The GQA head-sum (step 5 at group size > 1) has no value in the paper to
+ * pin it to: "parity unpinned" beyond its reduction to eq. 6 at G = 1.
+ *
+ * Layouts: every array is dense row-major double.
+ *   q [B][Hq][D]   k_new, v_new [B][Hkv][D]   out [B][Hq][D]
+ *   cache K, V [B][Hkv][N][D]   scores [B][Hkv][N]   evict_idx [B][Hkv]
+ * Query head h reads KV head h / (Hq/Hkv).
+ */
+#include <math.h>
+#include <stdint.h>
+#include <stdlib.h>
+#include <string.h>
+#ifdef _OPENMP
+#include <omp.h>
+#endif
+
+#define LFO_API __attribute__((visibility("default")))
+
+/* ------------------------------------------------------------------ */
+/* Pure per-unit mathematics                                           */
+/* ------------------------------------------------------------------ */
+
+/*
+ * Attention + LongFlowScore for one KV head and its G query heads over the
+ * n valid rows of K, V (each [n][D]).
+ *   out   [G][D]   eq. 1
+ *   alpha [G][n]   attention weights (may be NULL)
+ *   score [n]      sum_h alpha_h^i * sum_l |v^i_l|      eq. 6, summed over h
+ */
+LFO_API void lfo_attend_unit(int n, int D, int G, const double *q,
+                             const double *K, const double *V, double *out,
+                             double *alpha, double *score)
+{
+    double *a = (double *)malloc(sizeof(double) * (size_t)n);
+    for (int i = 0; i < n; ++i) score[i] = 0.0;
+    for (int h = 0; h < G; ++h) {
+        const double *qh = q + (size_t)h * D;
+        /* s^i = q . k^i / sqrt(d_k) */
+        double smax = -INFINITY;
+        for (int i = 0; i < n; ++i) {
+            double dot = 0.0;
+            for (int l = 0; l < D; ++l) dot += qh[l] * K[(size_t)i * D + l];
+            a[i] = dot / sqrt((double)D);
+            if (a[i] > smax) smax = a[i];
+        }
+        /* alpha^i = exp(s^i) / Z, Z = sum_j exp(s^j) */
+        double Z = 0.0;
+        for (int i = 0; i < n; ++i) {
+            a[i] = exp(a[i] - smax);
+            Z += a[i];
+        }
+        for (int i = 0; i < n; ++i) a[i] /= Z;
+        /* o = sum_i alpha^i v^i */
+        for (int l = 0; l < D; ++l) out[(size_t)h * D + l] = 0.0;
+        for (int i = 0; i < n; ++i)
+            for (int l = 0; l < D; ++l)
+                out[(size_t)h * D + l] += a[i] * V[(size_t)i * D + l];
+        /* group score accumulates alpha over the heads sharing this KV head */
+        for (int i = 0; i < n; ++i) score[i] += a[i];
+        if (alpha) memcpy(alpha + (size_t)h * n, a, sizeof(double) * (size_t)n);
+    }
+    /* LongFlowScore = alpha * ||v||_1 */
+    for (int i = 0; i < n; ++i) {
+        double l1 = 0.0;
+        for (int l = 0; l < D; ++l) l1 += fabs(V[(size_t)i * D + l]);
+        score[i] *= l1;
+    }
+    free(a);
+}
+
+/* argmin with lowest index on exact ties; n >= 1 */
+LFO_API int lfo_argmin(int n, const double *x)
+{
+    int best = 0;
+    for (int i = 1; i < n; ++i)
+        if (x[i] < x[best]) best = i;
+    return best;
+}
+
+/* ------------------------------------------------------------------ */
+/* Static cache state (Sec. 3.4 "Static Memory and Consistent Workload") */
+/* ------------------------------------------------------------------ */
+
+typedef struct lfo_cache {
+    int B, Hq, Hkv, D, N, G;
+    int count;        /* valid slots = min(tokens seen, N); shared by all units */
+    double *K, *V;    /* [B][Hkv][N][D] */
+    double *score;    /* [B][Hkv][N], last step; 0 for invalid slots */
+    int32_t *pending; /* [B][Hkv] slot the next token's K/V will cover; -1 = none */
+} lfo_cache;
+
+LFO_API lfo_cache *lfo_cache_create(int B, int Hq, int Hkv, int D, int N)
+{
+    if (B < 1 || Hq < 1 || Hkv < 1 || D < 1 || N < 1 || Hq % Hkv) return NULL;
+    lfo_cache *c = (lfo_cache *)calloc(1, sizeof(*c));
+    c->B = B; c->Hq = Hq; c->Hkv = Hkv; c->D = D; c->N = N; c->G = Hq / Hkv;
+    size_t units = (size_t)B * Hkv;
+    c->K = (double *)malloc(sizeof(double) * units * N * D);
+    c->V = (double *)malloc(sizeof(double) * units * N * D);
+    /* empty slots hold NaN so that any read of them poisons the result */
+    for (size_t i = 0; i < units * N * D; ++i) c->K[i] = c->V[i] = NAN;
+    c->score = (double *)calloc(units * N, sizeof(double));
+    c->pending = (int32_t *)malloc(sizeof(int32_t) * units);
+    for (size_t u = 0; u < units; ++u) c->pending[u] = 0;
+    c->count = 0;
+    return c;
+}
+
+LFO_API void lfo_cache_destroy(lfo_cache *c)
+{
+    if (!c) return;
+    free(c->K); free(c->V); free(c->score); free(c->pending); free(c);
+}
+
+/*
+ * Prefill: rows [0, n_init) of every unit come from k_init, v_init
+ * ([B][Hkv][n_init][D]).  A cache that is not yet full continues to fill at
+ * slot n_init; a cache born full has no pending slot until one is set.
+ */
+LFO_API int lfo_cache_init(lfo_cache *c, const double *k_init,
+                           const double *v_init, int n_init)
+{
+    if (n_init < 0 || n_init > c->N) return 1;
+    size_t units = (size_t)c->B * c->Hkv;
+    for (size_t u = 0; u < units; ++u) {
+        if (n_init) {
+            memcpy(c->K + u * c->N * c->D, k_init + u * n_init * c->D,
+                   sizeof(double) * (size_t)n_init * c->D);
+            memcpy(c->V + u * c->N * c->D, v_init + u * n_init * c->D,
+                   sizeof(double) * (size_t)n_init * c->D);
+        }
+        c->pending[u] = (n_init < c->N) ? n_init : -1;
+    }
+    c->count = n_init;
+    return 0;
+}
+
+/*
+ * One decode step for every unit (steps 1-6 of the header).
+ * Returns 0, or 2 if the cache is full and some unit has no pending slot.
+ */
+LFO_API int lfo_cache_step(lfo_cache *c, const double *q, const double *k_new,
+                           const double *v_new, double *out, int32_t *evict_idx)
+{
+    const int D = c->D, N = c->N, G = c->G;
+    const int units = c->B * c->Hkv;
+    for (int u = 0; u < units; ++u)
+        if (c->pending[u] < 0 || c->pending[u] >= N) return 2;
+    const int n = (c->count < N) ? c->count + 1 : N;
+#pragma omp parallel for schedule(dynamic, 1)
+    for (int u = 0; u < units; ++u) {
+        double *Ku = c->K + (size_t)u * N * D, *Vu = c->V + (size_t)u * N * D;
+        /* 1. the new token covers the slot selected by the previous step */
+        int slot = c->pending[u];
+        memcpy(Ku + (size_t)slot * D, k_new + (size_t)u * D, sizeof(double) * D);
+        memcpy(Vu + (size_t)slot * D, v_new + (size_t)u * D, sizeof(double) * D);
+        /* 2-5. attention and scores over the n valid rows (a prefix) */
+        double *sc = c->score + (size_t)u * N;
+        lfo_attend_unit(n, D, G, q + (size_t)u * G * D, Ku, Vu,
+                        out + (size_t)u * G * D, NULL, sc);
+        for (int i = n; i < N; ++i) sc[i] = 0.0;
+        /* 6. next slot: keep filling, else evict the minimum score */
+        c->pending[u] = (n < N) ? n : lfo_argmin(N, sc);
+        if (evict_idx) evict_idx[u] = c->pending[u];
+    }
+    c->count = n;
+    return 0;
+}
+
+LFO_API int lfo_cache_count(const lfo_cache *c) { return c->count; }
+
+LFO_API void lfo_cache_scores(const lfo_cache *c, double *scores)
+{
+    memcpy(scores, c->score, sizeof(double) * (size_t)c->B * c->Hkv * c->N);
+}
+
+LFO_API void lfo_cache_get_pending(const lfo_cache *c, int32_t *slots)
+{
+    memcpy(slots, c->pending, sizeof(int32_t) * (size_t)c->B * c->Hkv);
+}
+
+/* steering hook: after a reported near-tie the harness aligns the oracle's
+ * next slot with the other implementation so later steps stay comparable */
+LFO_API int lfo_cache_set_pending(lfo_cache *c, const int32_t *slots)
+{
+    size_t units = (size_t)c->B * c->Hkv;
+    for (size_t u = 0; u < units; ++u) {
+        if (slots[u] < 0 || slots[u] >= c->N) return 1;
+        /* while filling, valid rows stay a prefix: only slot == count is legal */
+        if (c->count < c->N && slots[u] != c->count) return 1;
+    }
+    memcpy(c->pending, slots, sizeof(int32_t) * units);
+    return 0;
+}
+
+LFO_API void lfo_cache_get_kv(const lfo_cache *c, double *K, double *V)
+{
+    size_t n = (size_t)c->B * c->Hkv * c->N * c->D;
+    memcpy(K, c->K, sizeof(double) * n);
+    memcpy(V, c->V, sizeof(double) * n);
+}
+
+LFO_API int lfo_num_threads(void)
+{
+#ifdef _OPENMP
+    return omp_get_max_threads();
+#else
+    return 1;
+#endif
+}

@@ -1,0 +1,261 @@
+"""Pins for the float64 oracle (CPU only): every check compares the oracle with
+something that is NOT the oracle -- a library routine, a closed form, an
+identity proved in the paper, brute force, or a second procedure (Alg. 1)."""
+import itertools
+import math
+
+import numpy as np
+import pytest
+from scipy.special import softmax as scipy_softmax
+
+from oracle import alg1_blockwise, longflow_oracle as oracle
+
+
+def _rand_unit(rng, n, D, G, kscale=1.0):
+    q = rng.standard_normal((G, D))
+    K = rng.standard_normal((n, D)) * kscale
+    V = rng.standard_normal((n, D))
+    return q, K, V
+
+
+# ---------------------------------------------------------------- attention output (eq. 1)
+
+@pytest.mark.parametrize("n,D,G", [(1, 64, 1), (7, 64, 4), (33, 128, 7), (256, 128, 5)])
+def test_out_matches_library_softmax_attention(n, D, G):
+    rng = np.random.default_rng(n * 1000 + D + G)
+    q, K, V = _rand_unit(rng, n, D, G, kscale=2.0)
+    out, _, alpha = oracle.attend_unit(q, K, V, want_alpha=True)
+    w = scipy_softmax(q @ K.T / math.sqrt(D), axis=1)      # textbook eq. 1
+    np.testing.assert_allclose(alpha, w, rtol=1e-12, atol=1e-300)
+    np.testing.assert_allclose(out, w @ V, rtol=1e-11, atol=1e-13)
+
+
+def test_closed_form_two_tokens():
+    # D = 4, q = (2,0,0,0): s_i = k_i[0].  exp(s) = (1, 3)  ->  alpha = (1/4, 3/4).
+    q = np.array([[2.0, 0, 0, 0]])
+    K = np.array([[0.0, 5, -1, 2], [math.log(3.0), 7, 7, 7]])
+    V = np.array([[4.0, 0, 0, 0], [-8.0, 0, 2, -2]])
+    out, score, alpha = oracle.attend_unit(q, K, V, want_alpha=True)
+    np.testing.assert_allclose(alpha[0], [0.25, 0.75], rtol=1e-15)
+    np.testing.assert_allclose(out[0], [1.0 - 6.0, 0.0, 1.5, -1.5], rtol=1e-14, atol=1e-15)
+    # eq. 6: alpha * ||v||_1 = 0.25*4, 0.75*12
+    np.testing.assert_allclose(score, [1.0, 9.0], rtol=1e-14)
+
+
+def test_uniform_keys_give_mean_of_values():
+    rng = np.random.default_rng(5)
+    q, K, V = _rand_unit(rng, 19, 64, 3)
+    K[:] = K[0]
+    out, score, _ = oracle.attend_unit(q, K, V)
+    np.testing.assert_allclose(out, np.broadcast_to(V.mean(0), out.shape), rtol=1e-12, atol=1e-14)
+    # all alpha equal -> the score orders tokens by ||v||_1 alone
+    assert oracle.argmin(score) == int(np.argmin(np.abs(V).sum(1)))
+
+
+def test_scale_is_one_over_sqrt_dk():
+    # doubling D by zero-padding must change the logits by sqrt(2): checks that the
+    # scale is 1/sqrt(d_k) and not 1/d_k or 1
+    rng = np.random.default_rng(6)
+    q, K, V = _rand_unit(rng, 9, 32, 1)
+    qp = np.concatenate([q, np.zeros_like(q)], 1)
+    Kp = np.concatenate([K, np.zeros_like(K)], 1)
+    Vp = np.concatenate([V, np.zeros_like(V)], 1)
+    _, _, a = oracle.attend_unit(q * math.sqrt(2.0), K, V, True)
+    _, _, ap = oracle.attend_unit(qp * 2.0, Kp, Vp, True)
+    np.testing.assert_allclose(a, ap, rtol=1e-12)
+
+
+# ---------------------------------------------------------------- score (eq. 6)
+
+def test_alpha_sums_and_score_mass():
+    rng = np.random.default_rng(7)
+    for G in (1, 4, 7):
+        q, K, V = _rand_unit(rng, 50, 128, G)
+        _, score, alpha = oracle.attend_unit(q, K, V, True)
+        np.testing.assert_allclose(alpha.sum(1), np.ones(G), rtol=1e-13)
+        # sum_i score_i / ||v_i||_1 = G   (a mean over heads would give 1, a max < G)
+        np.testing.assert_allclose((score / np.abs(V).sum(1)).sum(), G, rtol=1e-12)
+
+
+def test_score_is_eq6_at_group_one():
+    rng = np.random.default_rng(8)
+    q, K, V = _rand_unit(rng, 40, 64, 1, kscale=1.5)
+    _, score, _ = oracle.attend_unit(q, K, V)
+    alpha = scipy_softmax(K @ q[0] / 8.0)
+    c = alpha[:, None] * V                               # contribution vectors, eq. 5
+    np.testing.assert_allclose(score, np.abs(c).sum(1), rtol=1e-12)   # L1, not L2
+    assert not np.allclose(score, np.sqrt((c ** 2).sum(1)))
+
+
+def test_group_score_is_sum_of_head_scores():
+    rng = np.random.default_rng(9)
+    q, K, V = _rand_unit(rng, 31, 64, 5)
+    _, score, _ = oracle.attend_unit(q, K, V)
+    per_head = sum(oracle.attend_unit(q[h:h + 1], K, V)[1] for h in range(5))
+    np.testing.assert_allclose(score, per_head, rtol=1e-13)
+
+
+def test_equal_value_norms_argmin_is_lowest_logit():
+    rng = np.random.default_rng(10)
+    q, K, V = _rand_unit(rng, 64, 64, 1)
+    V = np.sign(V)                                       # every ||v||_1 = D exactly
+    _, score, _ = oracle.attend_unit(q, K, V)
+    assert oracle.argmin(score) == int(np.argmin(K @ q[0]))
+
+
+# ---------------------------------------------------------------- App. A.1: leave-one-out identity
+
+@pytest.mark.parametrize("n", [2, 5, 16])
+def test_leave_one_out_identity_and_bound(n):
+    rng = np.random.default_rng(100 + n)
+    D = 16
+    q, K, V = _rand_unit(rng, n, D, 1)
+    o, score, alpha = oracle.attend_unit(q, K, V, True)
+    o, alpha = o[0], alpha[0]
+    Vmax = np.linalg.norm(V, axis=1).max()
+    for i in range(n):
+        keep = [j for j in range(n) if j != i]
+        o_wo = oracle.attend_unit(q, K[keep], V[keep])[0][0]   # recomputed from scratch
+        c_i = alpha[i] * V[i]
+        R = (o - o_wo) - c_i
+        np.testing.assert_allclose(R, -alpha[i] / (1 - alpha[i]) * (o - c_i), rtol=1e-9, atol=1e-13)
+        assert np.linalg.norm(R) <= 2 * Vmax * alpha[i] / (1 - alpha[i]) * (1 + 1e-12)
+        # the score is the L1 norm of that same contribution vector
+        np.testing.assert_allclose(score[i], np.abs(c_i).sum(), rtol=1e-12)
+        # renormalisation identity alpha^{j,(\i)} = alpha^j / (1 - alpha^i)
+        a_wo = oracle.attend_unit(q, K[keep], V[keep], True)[2][0]
+        np.testing.assert_allclose(a_wo, alpha[keep] / (1 - alpha[i]), rtol=1e-10)
+
+
+# ---------------------------------------------------------------- Alg. 1 (blockwise, max-free, masked)
+
+@pytest.mark.parametrize("B_k", [1, 3, 16, 37])
+def test_blockwise_procedure_equals_definition(B_k):
+    rng = np.random.default_rng(200 + B_k)
+    n, D = 37, 64
+    q, K, V = _rand_unit(rng, n, D, 1)
+    o, score, _ = oracle.attend_unit(q, K, V)
+    o2, s2, i2 = alg1_blockwise.fused_blockwise(q[0], K, V, np.ones(n), B_k)
+    np.testing.assert_allclose(o2, o[0], rtol=1e-12, atol=1e-14)
+    np.testing.assert_allclose(s2, score, rtol=1e-12)
+    assert i2 == oracle.argmin(score)
+
+
+def test_blockwise_mask_equals_definition_on_live_rows():
+    rng = np.random.default_rng(300)
+    n, D, G = 48, 64, 4
+    q, K, V = _rand_unit(rng, n, D, G)
+    M = rng.random(n) < 0.6
+    M[0] = True
+    K2, V2 = K.copy(), V.copy()
+    K2[~M] = np.nan
+    V2[~M] = np.nan                                       # dead rows must not leak
+    o, score, _ = oracle.attend_unit(q, K[M], V[M])
+    o2, s2 = alg1_blockwise.fused_blockwise_group(q, K2, V2, M, 5)
+    np.testing.assert_allclose(o2, o, rtol=1e-12, atol=1e-14)
+    np.testing.assert_allclose(s2[M], score, rtol=1e-12)
+    assert np.all(s2[~M] == 0.0)
+
+
+# ---------------------------------------------------------------- argmin
+
+def test_argmin_brute_force_and_ties():
+    rng = np.random.default_rng(400)
+    for n in (1, 2, 3, 8):
+        for _ in range(20):
+            x = rng.integers(0, 4, size=n).astype(float)      # many exact ties
+            want = min(range(n), key=lambda i: (x[i], i))
+            assert oracle.argmin(x) == want
+            assert oracle.argmin(x) == int(np.argsort(x, kind="stable")[0])
+
+
+def test_permuting_slots_permutes_scores_only():
+    rng = np.random.default_rng(500)
+    n = 6
+    q, K, V = _rand_unit(rng, n, 16, 2)
+    o, score, _ = oracle.attend_unit(q, K, V)
+    for perm in itertools.islice(itertools.permutations(range(n)), 0, 720, 37):
+        perm = list(perm)
+        o2, s2, _ = oracle.attend_unit(q, K[perm], V[perm])
+        np.testing.assert_allclose(o2, o, rtol=1e-12, atol=1e-14)
+        np.testing.assert_allclose(s2, score[perm], rtol=1e-12)
+        assert perm[oracle.argmin(s2)] == oracle.argmin(score)
+
+
+# ---------------------------------------------------------------- static cache behaviour (Sec. 3.4, Fig. 2 left)
+
+def _run_cache(B, Hq, Hkv, D, N, steps, seed, n_init=0):
+    rng = np.random.default_rng(seed)
+    c = oracle.OracleCache(B, Hq, Hkv, D, N)
+    if n_init:
+        c.init(rng.standard_normal((B, Hkv, n_init, D)), rng.standard_normal((B, Hkv, n_init, D)))
+    else:
+        c.init()
+    return c, rng
+
+
+def test_fill_phase_never_evicts():
+    B, Hq, Hkv, D, N = 2, 4, 2, 16, 8
+    c, rng = _run_cache(B, Hq, Hkv, D, N, 8, 600)
+    toks_k = []
+    for t in range(N):
+        q = rng.standard_normal((B, Hq, D)); k = rng.standard_normal((B, Hkv, D)); v = rng.standard_normal((B, Hkv, D))
+        toks_k.append(k)
+        out, idx = c.step(q, k, v)
+        assert c.count == t + 1
+        K, _ = c.kv()
+        for s in range(t + 1):                            # token s sits in slot s, untouched
+            np.testing.assert_array_equal(K[:, :, s, :], toks_k[s])
+        assert np.isnan(K[:, :, t + 1:, :]).all()         # empty slots never written
+        assert np.isfinite(out).all()                     # ... and never read
+        if t + 1 < N:
+            assert (idx == t + 1).all()                   # next slot is the next empty one
+        else:
+            sc = c.scores()                               # first real decision: at the step that fills
+            assert (idx == sc.argmin(-1)).all()
+
+
+def test_exactly_one_row_changes_and_it_is_the_returned_slot():
+    B, Hq, Hkv, D, N = 2, 6, 2, 16, 12
+    c, rng = _run_cache(B, Hq, Hkv, D, N, 0, 700, n_init=N - 1)
+    q = rng.standard_normal((B, Hq, D)); k = rng.standard_normal((B, Hkv, D)); v = rng.standard_normal((B, Hkv, D))
+    _, idx_prev = c.step(q, k, v)                         # completes the fill, first argmin
+    for _ in range(30):
+        K0, V0 = c.kv()
+        q = rng.standard_normal((B, Hq, D)); k = rng.standard_normal((B, Hkv, D)); v = rng.standard_normal((B, Hkv, D))
+        _, idx = c.step(q, k, v)
+        K1, V1 = c.kv()
+        changed = (K0 != K1).any(-1) | (V0 != V1).any(-1)  # [B,Hkv,N]
+        assert (changed.sum(-1) == 1).all()
+        assert (changed.argmax(-1) == idx_prev).all()     # slot covered now = slot chosen last step
+        np.testing.assert_array_equal(np.take_along_axis(K1, idx_prev[..., None, None].astype(np.int64), 2)[:, :, 0], k)
+        assert c.count == N
+        idx_prev = idx
+
+
+def test_cache_step_equals_unit_function_on_cache_rows():
+    # the stateful driver adds nothing to the mathematics: the newest token is attended
+    # to (it is in the cache before attention) and is itself an eviction candidate
+    B, Hq, Hkv, D, N = 1, 3, 1, 16, 5
+    c, rng = _run_cache(B, Hq, Hkv, D, N, 0, 800)
+    for t in range(9):
+        q = rng.standard_normal((B, Hq, D)); k = rng.standard_normal((B, Hkv, D)); v = rng.standard_normal((B, Hkv, D))
+        out, idx = c.step(q, k, v)
+        K, V = c.kv()
+        n = c.count
+        o2, s2, _ = oracle.attend_unit(q[0], K[0, 0, :n], V[0, 0, :n])
+        np.testing.assert_array_equal(out[0], o2)
+        assert (K[0, 0, :n] == k[0, 0]).all(-1).any()     # new token is among the attended rows
+        if n == N:
+            assert idx[0, 0] == oracle.argmin(s2)
+
+
+def test_full_cache_without_pending_is_an_error_until_set():
+    c, rng = _run_cache(1, 2, 1, 8, 4, 0, 900, n_init=4)
+    q = rng.standard_normal((1, 2, 8)); k = rng.standard_normal((1, 1, 8)); v = rng.standard_normal((1, 1, 8))
+    with pytest.raises(RuntimeError):
+        c.step(q, k, v)
+    c.set_pending([[2]])
+    c.step(q, k, v)
+    K, _ = c.kv()
+    np.testing.assert_array_equal(K[0, 0, 2], k[0, 0])
