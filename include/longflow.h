@@ -1,0 +1,142 @@
+/*
+ * longflow.h -- C ABI of the LongFlow fused decode step for AMD MI355X (gfx950).
+ *
+ * One call of longflow_decode_step() is one pass of the paper's fused
+ * attention + importance + eviction operator (Sec. 3.4 "Fused Attention and
+ * Eviction Kernel", Alg. 1, Fig. 2) over a fixed-budget static KV cache
+ * (Sec. 3.4 "Static Memory and Consistent Workload"), for every
+ * (batch, KV head) pair of one layer:
+ *
+ *   insert   the new token's K/V covers the slot chosen by the previous call
+ *            (Fig. 2 left); while the cache is still filling, the next empty slot
+ *   attend   o_h = softmax(q_h K^T / sqrt(d_k)) V over the valid slots, for the
+ *            query heads h that share the KV head            (eq. 1, eq. 4)
+ *   score    LongFlowScore(i) = sum_h alpha_h^i * ||v^i||_1  (eq. 6; the sum over
+ *            the group's query heads is this library's reading, the paper
+ *            leaves heads out)
+ *   evict    next slot = argmin_i LongFlowScore(i), lowest index on ties
+ *            (Sec. 3.2, Alg. 1 post-processing); while filling: = valid count
+ *
+ * Conventions
+ *   - Every pointer marked "device" is HIP device memory on the current device;
+ *     the CALLER owns all of it (cache, workspace, inputs, outputs) and the
+ *     stream.  The library owns only the small host-side handle and never
+ *     allocates or frees device memory.
+ *   - All tensors are dense, row-major, innermost dimension head_dim, of the
+ *     dtype in lf_config (LF_F32 = IEEE binary32, LF_BF16 = bfloat16 bits),
+ *     except where a C type is given.  Query head h reads KV head
+ *     h / (q_heads / kv_heads).
+ *   - Calls are asynchronous on `hip_stream` (a hipStream_t passed as void*,
+ *     NULL = the default stream) and never synchronise with the host.  The
+ *     sequences of a cache advance in lock-step: one valid-slot count for all.
+ *   - Every function returns an lf_status.  Argument errors are detected on the
+ *     host before anything is launched and leave the cache untouched.  The text
+ *     of the last error of the calling thread is in longflow_last_error().
+ *   - Calls on one handle must be serialised by the caller; different handles
+ *     are independent (one handle = one layer's cache).
+ */
+#ifndef LONGFLOW_H
+#define LONGFLOW_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#if defined(__GNUC__) || defined(__clang__)
+#define LF_API __attribute__((visibility("default")))
+#else
+#define LF_API
+#endif
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef struct longflow_cache longflow_cache_t; /* opaque, host memory, library-owned */
+
+typedef enum {
+    LF_OK = 0,
+    LF_ERR_INVALID_ARG = 1, /* NULL pointer, size out of range                         */
+    LF_ERR_UNSUPPORTED = 2, /* geometry the kernels do not cover                       */
+    LF_ERR_WORKSPACE = 3,   /* workspace smaller than longflow_workspace_bytes()       */
+    LF_ERR_STATE = 4,       /* call out of order (e.g. full cache without pending slot)*/
+    LF_ERR_HIP = 5          /* a HIP runtime call or launch failed                      */
+} lf_status;
+
+typedef enum { LF_F32 = 0, LF_BF16 = 1 } lf_dtype;
+
+/* flags */
+#define LF_FLAG_ATTENTION_ONLY 1u /* plain decode attention: no insert, score or eviction
+                                     (the uncompressed comparison of Sec. 4.4)            */
+#define LF_FLAG_FORCE_VALU 2u     /* bf16 only: use the vector-ALU kernel instead of the
+                                     matrix-core kernel (for A/B measurement)              */
+
+typedef struct {
+    int32_t batch;    /* B   >= 1                                            */
+    int32_t q_heads;  /* Hq, a multiple of kv_heads; Hq/Hkv <= 16 (f32: <= 8) */
+    int32_t kv_heads; /* Hkv >= 1                                            */
+    int32_t head_dim; /* D: 64 or 128                                        */
+    int32_t budget;   /* N: slots of the static cache, 1 <= N <= 2^24        */
+    int32_t dtype;    /* lf_dtype                                            */
+    uint32_t flags;   /* LF_FLAG_*                                           */
+} lf_config;
+
+/* Bytes of device workspace a cache with this geometry needs (0 if cfg is invalid). */
+LF_API size_t longflow_workspace_bytes(const lf_config *cfg);
+
+/*
+ * Create a cache over caller-owned storage (prefill stage of Sec. 2.1).
+ *   k_cache, v_cache  device [B][Hkv][N][D]; mutated in place by later calls.
+ *                     Slots >= the valid count are never read.
+ *   k_init, v_init    device [B][Hkv][n_init][D] copied into slots [0, n_init);
+ *                     may be NULL iff n_init == 0.
+ *   n_init            0 <= n_init <= N.  If n_init < N the cache keeps filling
+ *                     from slot n_init.  If n_init == N there is no slot for the
+ *                     next token until longflow_set_pending() names one.
+ *   workspace         device, >= longflow_workspace_bytes(cfg), 256-byte aligned,
+ *                     kept alive and untouched by the caller until destroy.
+ * On success *out receives the handle.
+ */
+LF_API int longflow_init_cache(longflow_cache_t **out, const lf_config *cfg,
+                        void *k_cache, void *v_cache,
+                        const void *k_init, const void *v_init, int32_t n_init,
+                        void *workspace, size_t workspace_bytes, void *hip_stream);
+
+/*
+ * One fused decode step (Alg. 1 plus the slot write of Fig. 2 left).
+ *   q          device [B][Hq][D]
+ *   k_new,v_new device [B][Hkv][D]: the current token's key/value
+ *   out        device [B][Hq][D], attention output, rounded to nearest even
+ *   evict_idx  device int32 [B][Hkv] or NULL: the slot the NEXT call will
+ *              overwrite (= valid count while the cache is filling)
+ * With LF_FLAG_ATTENTION_ONLY k_new, v_new and evict_idx are ignored and the
+ * cache is not modified.
+ */
+LF_API int longflow_decode_step(longflow_cache_t *cache, const void *q,
+                         const void *k_new, const void *v_new,
+                         void *out, int32_t *evict_idx, void *hip_stream);
+
+/*
+ * LongFlowScore of every slot as of the most recent decode step (the vector
+ * S_final_loss of Alg. 1): device float [B][Hkv][N], 0 for invalid slots.
+ * Recomputed on demand from the cache and that step's query; not part of the
+ * per-step cost.  LF_ERR_STATE before the first step.
+ */
+LF_API int longflow_scores(longflow_cache_t *cache, float *scores, void *hip_stream);
+
+/* Name the slot the next call overwrites (resume, tests): device int32 [B][Hkv],
+ * each in [0, N).  Only legal once the cache is full. */
+LF_API int longflow_set_pending(longflow_cache_t *cache, const int32_t *slots, void *hip_stream);
+
+/* Valid slots = min(tokens seen, N); negative on a NULL handle. */
+LF_API int longflow_valid_count(const longflow_cache_t *cache);
+
+/* Frees the host handle only. */
+LF_API int longflow_destroy_cache(longflow_cache_t *cache);
+
+/* Text of the calling thread's last error ("" if none). Never NULL. */
+LF_API const char *longflow_last_error(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* LONGFLOW_H */

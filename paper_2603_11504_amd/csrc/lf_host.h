@@ -1,0 +1,55 @@
+// Internal host-side declarations shared by the C-ABI layer and the kernel launchers.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stddef.h>
+#include <stdint.h>
+
+namespace lf {
+
+constexpr int kTile = 16;      // slots per screening-stash tile (one MFMA tile of slots)
+constexpr int kMaxSplits = 64; // upper bound on split-K factor
+constexpr int kMaxGroup = 16;  // query heads per KV head
+
+// Everything a launch needs; filled by the API layer.
+struct Plan {
+    int B, Hq, Hkv, D, N, G, units;
+    int dtype;         // 0 = f32, 1 = bf16
+    uint32_t flags;
+    int L;             // slots per split (multiple of kTile)
+    int C;             // number of splits covering N
+    int ntiles;        // ceil(N / kTile)
+    bool use_mfma;
+    // device pointers (caller-owned)
+    void *k_cache, *v_cache;
+    // carved out of the caller's workspace
+    int32_t *pending;  // [units]
+    void *q_last;      // [B][Hq][D] copy of the last step's query (for longflow_scores)
+    float *part_m;     // [units][C][G]    split-local softmax reference (log2 domain)
+    float *part_l;     // [units][C][G]    split-local denominator
+    float *part_o;     // [units][C][G][D] split-local un-normalised output
+    float *fin_m;      // [units][G]       global reference of the last step
+    float *fin_l;      // [units][G]       global denominator of the last step
+    uint16_t *stash_w; // [units][ntiles][G][kTile] bf16 screening values ||v||_1 * p
+    float *stash_m;    // [units][ntiles][G]        reference each tile's p is relative to
+};
+
+struct Layout {
+    size_t off_pending, off_q, off_part_m, off_part_l, off_part_o, off_fin_m, off_fin_l,
+        off_stash_w, off_stash_m, total;
+};
+
+// Split-K geometry for a cache of `units` independent (batch, KV head) pairs.
+void choose_splits(int units, int N, int *L, int *C);
+Layout make_layout(int units, int Hq_total_elems_bytes, int G, int D, int C, int ntiles);
+
+// Kernel launchers (each returns the hipError_t of its launch).
+hipError_t launch_insert(const Plan &p, const void *q, const void *k_new, const void *v_new,
+                         hipStream_t s);
+hipError_t launch_split_valu(const Plan &p, const void *q, int n, hipStream_t s);
+hipError_t launch_split_mfma(const Plan &p, const void *q, int n, hipStream_t s);
+hipError_t launch_finish(const Plan &p, const void *q, int n, void *out, int32_t *evict_idx,
+                         hipStream_t s);
+hipError_t launch_scores(const Plan &p, int n, float *scores, hipStream_t s);
+hipError_t launch_fill_i32(int32_t *dst, int count, int32_t value, hipStream_t s);
+
+} // namespace lf

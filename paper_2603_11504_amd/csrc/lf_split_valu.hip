@@ -1,0 +1,203 @@
+// Split-K decode attention + score by-products on the vector ALUs (any dtype).
+//
+// Serves fp32 caches and is the A/B partner of the matrix-core kernel for bf16.
+// One workgroup = one (unit, split); a row of 16 lanes owns one 16-slot tile at a
+// time, so that tile's softmax reference is fixed while its 16 slots are scored:
+//   K phase  logits of the 16 slots for the G query heads       (eq. 1 numerator)
+//   V phase  p = 2^(t - m), o += p v, u = ||v||_1               (eq. 1, eq. 6)
+// and the tile's screening values bf16(u * p) go to the stash together with m.
+#include <utility>
+
+#include "lf_device.h"
+#include "lf_host.h"
+
+namespace lf {
+
+template <int... I, typename F>
+__device__ __forceinline__ void static_for_impl(std::integer_sequence<int, I...>, F &&f)
+{
+    (f(std::integral_constant<int, I>{}), ...);
+}
+template <int N, typename F> __device__ __forceinline__ void static_for(F &&f)
+{
+    static_for_impl(std::make_integer_sequence<int, N>{}, f);
+}
+
+// value held by lane JJ of each 16-lane row, seen by every lane of that row
+template <int JJ> __device__ __forceinline__ float row16_bcast(float x)
+{
+    return dpp_f32<0x150 + JJ>(x); // row_newbcast:JJ
+}
+
+template <typename T, int D, int G>
+__global__ __launch_bounds__(256) void split_valu_kernel(
+    const T *__restrict__ Kc, const T *__restrict__ Vc, const T *__restrict__ q,
+    int n, int N, int L, int C, int ntiles, int c_active,
+    float *__restrict__ part_m, float *__restrict__ part_l, float *__restrict__ part_o,
+    uint16_t *__restrict__ stash_w, float *__restrict__ stash_m, float scale_log2, int write_stash)
+{
+    constexpr int EPL = D / 16; // elements per lane of a 16-lane row
+    const int u = blockIdx.x / c_active, c = blockIdx.x % c_active;
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int rg = lane >> 4, j = lane & 15;
+    const int start = c * L;
+    const int end = min(start + L, n);
+    const int nt = (end - start + kTile - 1) / kTile;
+    const T *Ku = Kc + (size_t)u * N * D;
+    const T *Vu = Vc + (size_t)u * N * D;
+
+    float qf[G][EPL];
+#pragma unroll
+    for (int h = 0; h < G; ++h) {
+        RowChunk<T, EPL> r;
+        r.load(q + ((size_t)u * G + h) * D + j * EPL);
+#pragma unroll
+        for (int e = 0; e < EPL; ++e) qf[h][e] = r.v[e];
+    }
+    float m[G], l[G], o[G][EPL];
+#pragma unroll
+    for (int h = 0; h < G; ++h) {
+        m[h] = -INFINITY;
+        l[h] = 0.f;
+#pragma unroll
+        for (int e = 0; e < EPL; ++e) o[h][e] = 0.f;
+    }
+
+    for (int ti = wave * 4 + rg; ti < nt; ti += 16) {
+        const int base = start + ti * kTile;
+        // ---- K phase: lane j ends up with the logits of slot base+j (log2 domain)
+        float t[G];
+#pragma unroll
+        for (int h = 0; h < G; ++h) t[h] = -INFINITY;
+        static_for<kTile>([&](auto ic) {
+            constexpr int jj = decltype(ic)::value;
+            const int slot = base + jj;
+            const bool valid = slot < end;
+            RowChunk<T, EPL> kr;
+            if (valid) kr.load(Ku + (size_t)slot * D + j * EPL); else kr.zero();
+#pragma unroll
+            for (int h = 0; h < G; ++h) {
+                float part = 0.f;
+#pragma unroll
+                for (int e = 0; e < EPL; ++e) part = fmaf(qf[h][e], kr.v[e], part);
+                part = row16_sum(part);
+                if (jj == j) t[h] = valid ? part * scale_log2 : -INFINITY;
+            }
+        });
+        // ---- fix the tile's reference, rescale the running state once
+        float p[G];
+#pragma unroll
+        for (int h = 0; h < G; ++h) {
+            const float m_new = fmaxf(m[h], row16_max(t[h]));
+            const float a = merge_weight(m[h], m_new);
+            l[h] *= a;
+#pragma unroll
+            for (int e = 0; e < EPL; ++e) o[h][e] *= a;
+            m[h] = m_new;
+            p[h] = (t[h] == -INFINITY) ? 0.f : fast_exp2(t[h] - m_new);
+            l[h] += p[h]; // lane-partial; summed over the row at the end
+        }
+        // ---- V phase
+        float u_mine = 0.f;
+        static_for<kTile>([&](auto ic) {
+            constexpr int jj = decltype(ic)::value;
+            const int slot = base + jj;
+            const bool valid = slot < end;
+            RowChunk<T, EPL> vr;
+            if (valid) vr.load(Vu + (size_t)slot * D + j * EPL); else vr.zero();
+            float au = 0.f;
+#pragma unroll
+            for (int e = 0; e < EPL; ++e) au += fabsf(vr.v[e]);
+            au = row16_sum(au);
+            if (jj == j) u_mine = au;
+#pragma unroll
+            for (int h = 0; h < G; ++h) {
+                const float pj = row16_bcast<jj>(p[h]);
+#pragma unroll
+                for (int e = 0; e < EPL; ++e) o[h][e] = fmaf(pj, vr.v[e], o[h][e]);
+            }
+        });
+        if (write_stash) {
+            const size_t rec = (size_t)u * ntiles + (size_t)(base / kTile);
+#pragma unroll
+            for (int h = 0; h < G; ++h) {
+                stash_w[(rec * G + h) * kTile + j] = (uint16_t)f32_to_bf16_bits(u_mine * p[h]);
+                if (j == 0) stash_m[rec * G + h] = m[h];
+            }
+        }
+    }
+
+    // ---- merge: 4 rows of a wave, then the 4 waves through LDS
+    __shared__ float sm_m[4][G], sm_l[4][G], sm_o[4][G][D];
+#pragma unroll
+    for (int h = 0; h < G; ++h) {
+        float lh = row16_sum(l[h]);
+        float M = fmaxf(m[h], __shfl_xor(m[h], 16));
+        M = fmaxf(M, __shfl_xor(M, 32));
+        const float a = merge_weight(m[h], M);
+        lh *= a;
+        lh += __shfl_xor(lh, 16);
+        lh += __shfl_xor(lh, 32);
+#pragma unroll
+        for (int e = 0; e < EPL; ++e) {
+            float x = o[h][e] * a;
+            x += __shfl_xor(x, 16);
+            x += __shfl_xor(x, 32);
+            if (rg == 0) sm_o[wave][h][j * EPL + e] = x;
+        }
+        if (lane == 0) { sm_m[wave][h] = M; sm_l[wave][h] = lh; }
+    }
+    __syncthreads();
+    const size_t pbase = ((size_t)u * C + c) * G;
+    for (int idx = tid; idx < G * D; idx += 256) {
+        const int h = idx / D, d = idx % D;
+        float M = fmaxf(fmaxf(sm_m[0][h], sm_m[1][h]), fmaxf(sm_m[2][h], sm_m[3][h]));
+        float acc = 0.f, lacc = 0.f;
+#pragma unroll
+        for (int w = 0; w < 4; ++w) {
+            const float a = merge_weight(sm_m[w][h], M);
+            acc += a * sm_o[w][h][d];
+            lacc += a * sm_l[w][h];
+        }
+        part_o[(pbase + h) * D + d] = acc;
+        if (d == 0) { part_m[pbase + h] = M; part_l[pbase + h] = lacc; }
+    }
+}
+
+template <typename T, int D, int G>
+static hipError_t launch_one(const Plan &p, const void *q, int n, hipStream_t s)
+{
+    const int c_active = (n + p.L - 1) / p.L;
+    const float scale_log2 = 1.4426950408889634f / sqrtf((float)D);
+    const int write_stash = (p.flags & 1u) ? 0 : 1;
+    hipLaunchKernelGGL((split_valu_kernel<T, D, G>), dim3(p.units * c_active), dim3(256), 0, s,
+                       (const T *)p.k_cache, (const T *)p.v_cache, (const T *)q, n, p.N, p.L, p.C,
+                       p.ntiles, c_active, p.part_m, p.part_l, p.part_o, p.stash_w, p.stash_m,
+                       scale_log2, write_stash);
+    return hipGetLastError();
+}
+
+template <typename T, int D>
+static hipError_t launch_g(const Plan &p, const void *q, int n, hipStream_t s)
+{
+    switch (p.G) {
+    case 1: return launch_one<T, D, 1>(p, q, n, s);
+    case 2: return launch_one<T, D, 2>(p, q, n, s);
+    case 3: return launch_one<T, D, 3>(p, q, n, s);
+    case 4: return launch_one<T, D, 4>(p, q, n, s);
+    case 5: return launch_one<T, D, 5>(p, q, n, s);
+    case 6: return launch_one<T, D, 6>(p, q, n, s);
+    case 7: return launch_one<T, D, 7>(p, q, n, s);
+    case 8: return launch_one<T, D, 8>(p, q, n, s);
+    default: return hipErrorInvalidValue;
+    }
+}
+
+hipError_t launch_split_valu(const Plan &p, const void *q, int n, hipStream_t s)
+{
+    if (p.dtype == 0)
+        return p.D == 64 ? launch_g<float, 64>(p, q, n, s) : launch_g<float, 128>(p, q, n, s);
+    return p.D == 64 ? launch_g<bf16_t, 64>(p, q, n, s) : launch_g<bf16_t, 128>(p, q, n, s);
+}
+
+} // namespace lf

@@ -1,0 +1,267 @@
+// C ABI of the LongFlow decode step: argument checking, workspace carving, launch order.
+// All arithmetic lives in the kernels; nothing here touches cache contents on the host.
+#include "../../include/longflow.h"
+
+#include <cstdarg>
+#include <cstdio>
+#include <cstdlib>
+#include <cstring>
+
+#include "lf_host.h"
+
+namespace lf {
+
+static thread_local char g_err[512] = "";
+
+static int fail(int code, const char *fmt, ...)
+{
+    va_list ap;
+    va_start(ap, fmt);
+    vsnprintf(g_err, sizeof(g_err), fmt, ap);
+    va_end(ap);
+    return code;
+}
+
+static size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
+
+void choose_splits(int units, int N, int *L, int *C)
+{
+    // Enough workgroups to fill 256 CUs several times over, each streaming a span long
+    // enough to amortise its prologue/merge; spans are multiples of 256 slots.
+    long c = (2048 + units - 1) / units;
+    const long c_span = (N + 2047) / 2048;           // spans no longer than 2048 slots
+    if (c < c_span) c = c_span;
+    if (c > kMaxSplits) c = kMaxSplits;
+    if (c < 1) c = 1;
+    long l = (N + c - 1) / c;
+    if (const char *e = getenv("LONGFLOW_SPLIT_LEN")) {
+        const long v = atol(e);
+        if (v >= 16) l = v;
+    }
+    l = (l + 255) / 256 * 256;
+    while ((N + l - 1) / l > kMaxSplits) l += 256;
+    *L = (int)l;
+    *C = (int)((N + l - 1) / l);
+}
+
+static int validate(const lf_config *cfg)
+{
+    if (!cfg) return fail(LF_ERR_INVALID_ARG, "cfg is NULL");
+    if (cfg->batch < 1 || cfg->q_heads < 1 || cfg->kv_heads < 1 || cfg->budget < 1 ||
+        cfg->budget > (1 << 24))
+        return fail(LF_ERR_INVALID_ARG, "batch/heads/budget out of range");
+    if (cfg->dtype != LF_F32 && cfg->dtype != LF_BF16)
+        return fail(LF_ERR_INVALID_ARG, "unknown dtype %d", cfg->dtype);
+    if (cfg->flags & ~(LF_FLAG_ATTENTION_ONLY | LF_FLAG_FORCE_VALU))
+        return fail(LF_ERR_INVALID_ARG, "unknown flag bits 0x%x", cfg->flags);
+    if (cfg->q_heads % cfg->kv_heads)
+        return fail(LF_ERR_UNSUPPORTED, "q_heads %d is not a multiple of kv_heads %d", cfg->q_heads,
+                    cfg->kv_heads);
+    if (cfg->head_dim != 64 && cfg->head_dim != 128)
+        return fail(LF_ERR_UNSUPPORTED, "head_dim %d (supported: 64, 128)", cfg->head_dim);
+    const int G = cfg->q_heads / cfg->kv_heads;
+    if (G > kMaxGroup) return fail(LF_ERR_UNSUPPORTED, "group size %d > %d", G, kMaxGroup);
+    const bool mfma = cfg->dtype == LF_BF16 && cfg->head_dim == 128 && !(cfg->flags & LF_FLAG_FORCE_VALU);
+    if (!mfma && G > 8)
+        return fail(LF_ERR_UNSUPPORTED, "group size %d > 8 needs bf16, head_dim 128 and the matrix-core kernel", G);
+    if ((long long)cfg->batch * cfg->kv_heads > (1ll << 20))
+        return fail(LF_ERR_UNSUPPORTED, "batch*kv_heads > 2^20");
+    return LF_OK;
+}
+
+static void fill_plan(const lf_config *cfg, Plan *p)
+{
+    memset(p, 0, sizeof(*p));
+    p->B = cfg->batch; p->Hq = cfg->q_heads; p->Hkv = cfg->kv_heads; p->D = cfg->head_dim;
+    p->N = cfg->budget; p->G = cfg->q_heads / cfg->kv_heads; p->units = cfg->batch * cfg->kv_heads;
+    p->dtype = cfg->dtype; p->flags = cfg->flags;
+    choose_splits(p->units, p->N, &p->L, &p->C);
+    p->ntiles = (p->N + kTile - 1) / kTile;
+    p->use_mfma = cfg->dtype == LF_BF16 && cfg->head_dim == 128 && !(cfg->flags & LF_FLAG_FORCE_VALU);
+}
+
+static Layout layout_of(const Plan &p)
+{
+    Layout l;
+    const size_t esz = p.dtype == LF_F32 ? 4 : 2;
+    size_t off = 0;
+    auto take = [&](size_t bytes) { size_t o = off; off = align_up(off + bytes, 256); return o; };
+    l.off_pending = take(sizeof(int32_t) * p.units);
+    l.off_q = take(esz * (size_t)p.B * p.Hq * p.D);
+    l.off_part_m = take(sizeof(float) * (size_t)p.units * p.C * p.G);
+    l.off_part_l = take(sizeof(float) * (size_t)p.units * p.C * p.G);
+    l.off_part_o = take(sizeof(float) * (size_t)p.units * p.C * p.G * p.D);
+    l.off_fin_m = take(sizeof(float) * (size_t)p.units * p.G);
+    l.off_fin_l = take(sizeof(float) * (size_t)p.units * p.G);
+    const bool stash = !(p.flags & LF_FLAG_ATTENTION_ONLY);
+    l.off_stash_w = take(stash ? sizeof(uint16_t) * (size_t)p.units * p.ntiles * p.G * kTile : 0);
+    l.off_stash_m = take(stash ? sizeof(float) * (size_t)p.units * p.ntiles * p.G : 0);
+    l.total = off;
+    return l;
+}
+
+} // namespace lf
+
+struct longflow_cache {
+    uint32_t magic;
+    lf::Plan plan;
+    int count;         // valid slots
+    bool has_pending;  // a slot for the next token is known on the device
+    bool stepped;      // at least one decode step ran (scores are defined)
+};
+
+static const uint32_t kMagic = 0x4c46434bu;
+
+using namespace lf;
+
+static longflow_cache *checked(longflow_cache_t *c)
+{
+    return (c && c->magic == kMagic) ? c : nullptr;
+}
+
+extern "C" {
+
+size_t longflow_workspace_bytes(const lf_config *cfg)
+{
+    if (validate(cfg) != LF_OK) return 0;
+    Plan p;
+    fill_plan(cfg, &p);
+    return layout_of(p).total;
+}
+
+int longflow_init_cache(longflow_cache_t **out, const lf_config *cfg, void *k_cache, void *v_cache,
+                        const void *k_init, const void *v_init, int32_t n_init, void *workspace,
+                        size_t workspace_bytes, void *hip_stream)
+{
+    if (!out) return fail(LF_ERR_INVALID_ARG, "out is NULL");
+    *out = nullptr;
+    int rc = validate(cfg);
+    if (rc != LF_OK) return rc;
+    if (!k_cache || !v_cache) return fail(LF_ERR_INVALID_ARG, "k_cache/v_cache is NULL");
+    if (n_init < 0 || n_init > cfg->budget)
+        return fail(LF_ERR_INVALID_ARG, "n_init %d outside [0, %d]", n_init, cfg->budget);
+    if (n_init > 0 && (!k_init || !v_init)) return fail(LF_ERR_INVALID_ARG, "k_init/v_init is NULL");
+    if (!workspace) return fail(LF_ERR_INVALID_ARG, "workspace is NULL");
+    if (((uintptr_t)workspace & 255u) || ((uintptr_t)k_cache & 15u) || ((uintptr_t)v_cache & 15u))
+        return fail(LF_ERR_INVALID_ARG, "workspace must be 256-byte, caches 16-byte aligned");
+    Plan p;
+    fill_plan(cfg, &p);
+    const Layout l = layout_of(p);
+    if (workspace_bytes < l.total)
+        return fail(LF_ERR_WORKSPACE, "workspace has %zu bytes, %zu needed", workspace_bytes, l.total);
+    char *ws = (char *)workspace;
+    p.k_cache = k_cache; p.v_cache = v_cache;
+    p.pending = (int32_t *)(ws + l.off_pending);
+    p.q_last = ws + l.off_q;
+    p.part_m = (float *)(ws + l.off_part_m);
+    p.part_l = (float *)(ws + l.off_part_l);
+    p.part_o = (float *)(ws + l.off_part_o);
+    p.fin_m = (float *)(ws + l.off_fin_m);
+    p.fin_l = (float *)(ws + l.off_fin_l);
+    p.stash_w = (uint16_t *)(ws + l.off_stash_w);
+    p.stash_m = (float *)(ws + l.off_stash_m);
+
+    hipStream_t s = (hipStream_t)hip_stream;
+    if (n_init > 0) {
+        const size_t esz = p.dtype == LF_F32 ? 4 : 2;
+        const size_t row = esz * p.D;
+        hipError_t e = hipMemcpy2DAsync(k_cache, row * p.N, k_init, row * n_init, row * n_init, p.units,
+                                        hipMemcpyDeviceToDevice, s);
+        if (e == hipSuccess)
+            e = hipMemcpy2DAsync(v_cache, row * p.N, v_init, row * n_init, row * n_init, p.units,
+                                 hipMemcpyDeviceToDevice, s);
+        if (e != hipSuccess) return fail(LF_ERR_HIP, "prefill copy: %s", hipGetErrorString(e));
+    }
+    const bool filling = n_init < p.N;
+    if (filling) {
+        hipError_t e = launch_fill_i32(p.pending, p.units, n_init, s);
+        if (e != hipSuccess) return fail(LF_ERR_HIP, "pending init: %s", hipGetErrorString(e));
+    }
+    longflow_cache *c = new longflow_cache;
+    c->magic = kMagic;
+    c->plan = p;
+    c->count = n_init;
+    c->has_pending = filling;
+    c->stepped = false;
+    *out = c;
+    g_err[0] = 0;
+    return LF_OK;
+}
+
+int longflow_decode_step(longflow_cache_t *cache, const void *q, const void *k_new, const void *v_new,
+                         void *out, int32_t *evict_idx, void *hip_stream)
+{
+    longflow_cache *c = checked(cache);
+    if (!c) return fail(LF_ERR_STATE, "invalid or destroyed cache handle");
+    const Plan &p = c->plan;
+    const bool attention_only = p.flags & LF_FLAG_ATTENTION_ONLY;
+    if (!q || !out) return fail(LF_ERR_INVALID_ARG, "q/out is NULL");
+    if (!attention_only && (!k_new || !v_new)) return fail(LF_ERR_INVALID_ARG, "k_new/v_new is NULL");
+    if (((uintptr_t)q & 15u) || ((uintptr_t)out & 15u))
+        return fail(LF_ERR_INVALID_ARG, "q/out must be 16-byte aligned");
+    int n;
+    if (attention_only) {
+        if (c->count < 1) return fail(LF_ERR_STATE, "attention over an empty cache");
+        n = c->count;
+    } else {
+        if (!c->has_pending)
+            return fail(LF_ERR_STATE, "cache is full and no slot is pending: call longflow_set_pending");
+        n = c->count < p.N ? c->count + 1 : p.N;
+    }
+    hipStream_t s = (hipStream_t)hip_stream;
+    hipError_t e = launch_insert(p, q, k_new, v_new, s);
+    if (e != hipSuccess) return fail(LF_ERR_HIP, "insert launch: %s", hipGetErrorString(e));
+    e = p.use_mfma ? launch_split_mfma(p, q, n, s) : launch_split_valu(p, q, n, s);
+    if (e != hipSuccess) return fail(LF_ERR_HIP, "split launch: %s", hipGetErrorString(e));
+    e = launch_finish(p, q, n, out, evict_idx, s);
+    if (e != hipSuccess) return fail(LF_ERR_HIP, "finish launch: %s", hipGetErrorString(e));
+    c->count = n;
+    c->stepped = true;
+    return LF_OK;
+}
+
+int longflow_scores(longflow_cache_t *cache, float *scores, void *hip_stream)
+{
+    longflow_cache *c = checked(cache);
+    if (!c) return fail(LF_ERR_STATE, "invalid or destroyed cache handle");
+    if (!scores) return fail(LF_ERR_INVALID_ARG, "scores is NULL");
+    if (!c->stepped) return fail(LF_ERR_STATE, "no decode step has run yet");
+    if (c->plan.flags & LF_FLAG_ATTENTION_ONLY)
+        return fail(LF_ERR_STATE, "scores are not defined for an attention-only cache");
+    hipError_t e = launch_scores(c->plan, c->count, scores, (hipStream_t)hip_stream);
+    if (e != hipSuccess) return fail(LF_ERR_HIP, "scores launch: %s", hipGetErrorString(e));
+    return LF_OK;
+}
+
+int longflow_set_pending(longflow_cache_t *cache, const int32_t *slots, void *hip_stream)
+{
+    longflow_cache *c = checked(cache);
+    if (!c) return fail(LF_ERR_STATE, "invalid or destroyed cache handle");
+    if (!slots) return fail(LF_ERR_INVALID_ARG, "slots is NULL");
+    if (c->count < c->plan.N)
+        return fail(LF_ERR_STATE, "cache is still filling (%d of %d): the next slot is fixed", c->count,
+                    c->plan.N);
+    hipError_t e = hipMemcpyAsync(c->plan.pending, slots, sizeof(int32_t) * c->plan.units,
+                                  hipMemcpyDeviceToDevice, (hipStream_t)hip_stream);
+    if (e != hipSuccess) return fail(LF_ERR_HIP, "set_pending copy: %s", hipGetErrorString(e));
+    c->has_pending = true;
+    return LF_OK;
+}
+
+int longflow_valid_count(const longflow_cache_t *cache)
+{
+    return (cache && cache->magic == kMagic) ? cache->count : -1;
+}
+
+int longflow_destroy_cache(longflow_cache_t *cache)
+{
+    longflow_cache *c = checked(cache);
+    if (!c) return fail(LF_ERR_STATE, "invalid or destroyed cache handle");
+    c->magic = 0;
+    delete c;
+    return LF_OK;
+}
+
+const char *longflow_last_error(void) { return g_err; }
+
+} // extern "C"

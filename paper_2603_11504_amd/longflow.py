@@ -1,0 +1,156 @@
+"""Thin ctypes binding over ``liblongflow.so`` -- argument marshalling only.
+
+Same names as the C ABI (include/longflow.h).  PyTorch supplies device memory and the
+stream; every step of the decode path runs in the library's HIP kernels.  There is no
+fallback: if the library has not been built, importing a symbol raises.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+
+import torch
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "liblongflow.so")
+
+LF_OK, LF_ERR_INVALID_ARG, LF_ERR_UNSUPPORTED, LF_ERR_WORKSPACE, LF_ERR_STATE, LF_ERR_HIP = range(6)
+LF_F32, LF_BF16 = 0, 1
+LF_FLAG_ATTENTION_ONLY = 1
+LF_FLAG_FORCE_VALU = 2
+
+EXPORTS = ("longflow_workspace_bytes", "longflow_init_cache", "longflow_decode_step",
+           "longflow_scores", "longflow_set_pending", "longflow_valid_count",
+           "longflow_destroy_cache", "longflow_last_error")
+
+
+class lf_config(ctypes.Structure):
+    _fields_ = [("batch", ctypes.c_int32), ("q_heads", ctypes.c_int32), ("kv_heads", ctypes.c_int32),
+                ("head_dim", ctypes.c_int32), ("budget", ctypes.c_int32), ("dtype", ctypes.c_int32),
+                ("flags", ctypes.c_uint32)]
+
+
+class LongFlowError(RuntimeError):
+    def __init__(self, status, text):
+        super().__init__(f"longflow status {status}: {text}")
+        self.status = status
+
+
+_lib = None
+
+
+def lib():
+    """The loaded C library; raises if it was never built (no CPU fallback exists)."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(LIB_PATH):
+            raise ImportError(f"{LIB_PATH} is missing: run `python -c 'import __graft_entry__ as g; g.build()'`")
+        L = ctypes.CDLL(LIB_PATH)
+        vp, i32 = ctypes.c_void_p, ctypes.c_int32
+        L.longflow_workspace_bytes.argtypes = [ctypes.POINTER(lf_config)]
+        L.longflow_workspace_bytes.restype = ctypes.c_size_t
+        L.longflow_init_cache.argtypes = [ctypes.POINTER(vp), ctypes.POINTER(lf_config), vp, vp, vp, vp,
+                                          i32, vp, ctypes.c_size_t, vp]
+        L.longflow_init_cache.restype = ctypes.c_int
+        L.longflow_decode_step.argtypes = [vp] * 7
+        L.longflow_decode_step.restype = ctypes.c_int
+        L.longflow_scores.argtypes = [vp, vp, vp]
+        L.longflow_scores.restype = ctypes.c_int
+        L.longflow_set_pending.argtypes = [vp, vp, vp]
+        L.longflow_set_pending.restype = ctypes.c_int
+        L.longflow_valid_count.argtypes = [vp]
+        L.longflow_valid_count.restype = ctypes.c_int
+        L.longflow_destroy_cache.argtypes = [vp]
+        L.longflow_destroy_cache.restype = ctypes.c_int
+        L.longflow_last_error.argtypes = []
+        L.longflow_last_error.restype = ctypes.c_char_p
+        _lib = L
+    return _lib
+
+
+def _check(rc):
+    if rc != LF_OK:
+        raise LongFlowError(rc, lib().longflow_last_error().decode())
+
+
+def _ptr(t):
+    return None if t is None else ctypes.c_void_p(t.data_ptr())
+
+
+def _stream():
+    return ctypes.c_void_p(torch.cuda.current_stream().cuda_stream)
+
+
+def make_config(batch, q_heads, kv_heads, head_dim, budget, dtype, flags=0) -> lf_config:
+    code = {torch.float32: LF_F32, torch.bfloat16: LF_BF16, "f32": LF_F32, "bf16": LF_BF16}[dtype]
+    return lf_config(batch, q_heads, kv_heads, head_dim, budget, code, flags)
+
+
+def longflow_workspace_bytes(cfg: lf_config) -> int:
+    return int(lib().longflow_workspace_bytes(ctypes.byref(cfg)))
+
+
+class LongFlowCache:
+    """Owns the torch tensors behind one layer's static cache and its C handle."""
+
+    def __init__(self, batch, q_heads, kv_heads, head_dim, budget, dtype=torch.bfloat16, flags=0,
+                 device="cuda", k_init=None, v_init=None, k_cache=None, v_cache=None):
+        self.cfg = make_config(batch, q_heads, kv_heads, head_dim, budget, dtype, flags)
+        self.dtype = dtype
+        self.device = torch.device(device)
+        nbytes = longflow_workspace_bytes(self.cfg)
+        if nbytes == 0:
+            raise LongFlowError(LF_ERR_UNSUPPORTED, lib().longflow_last_error().decode())
+        shape = (batch, kv_heads, budget, head_dim)
+        # empty slots are never read: poison them so that a stray read shows up
+        self.k_cache = k_cache if k_cache is not None else torch.full(shape, float("nan"), dtype=dtype, device=self.device)
+        self.v_cache = v_cache if v_cache is not None else torch.full(shape, float("nan"), dtype=dtype, device=self.device)
+        self.workspace = torch.empty(nbytes, dtype=torch.uint8, device=self.device)
+        n_init = 0 if k_init is None else int(k_init.shape[2])
+        if k_init is not None:
+            k_init = k_init.contiguous()
+            v_init = v_init.contiguous()
+        h = ctypes.c_void_p()
+        _check(lib().longflow_init_cache(ctypes.byref(h), ctypes.byref(self.cfg), _ptr(self.k_cache),
+                                         _ptr(self.v_cache), _ptr(k_init), _ptr(v_init), n_init,
+                                         _ptr(self.workspace), nbytes, _stream()))
+        self._h = h
+        self.out = torch.empty((batch, q_heads, head_dim), dtype=dtype, device=self.device)
+        self.evict_idx = torch.empty((batch, kv_heads), dtype=torch.int32, device=self.device)
+
+    def decode_step(self, q, k_new=None, v_new=None, out=None, evict_idx=None):
+        """Asynchronous; returns (out, evict_idx) tensors owned by this object unless given."""
+        out = self.out if out is None else out
+        evict_idx = self.evict_idx if evict_idx is None else evict_idx
+        _check(lib().longflow_decode_step(self._h, _ptr(q), _ptr(k_new), _ptr(v_new), _ptr(out),
+                                          _ptr(evict_idx), _stream()))
+        return out, evict_idx
+
+    def scores(self):
+        s = torch.empty((self.cfg.batch, self.cfg.kv_heads, self.cfg.budget), dtype=torch.float32,
+                        device=self.device)
+        _check(lib().longflow_scores(self._h, _ptr(s), _stream()))
+        return s
+
+    def set_pending(self, slots):
+        slots = slots.to(device=self.device, dtype=torch.int32).contiguous()
+        _check(lib().longflow_set_pending(self._h, _ptr(slots), _stream()))
+        self._keep = slots  # alive until the async copy has run
+
+    @property
+    def valid_count(self):
+        return int(lib().longflow_valid_count(self._h))
+
+    def close(self):
+        if getattr(self, "_h", None):
+            torch.cuda.synchronize(self.device)
+            lib().longflow_destroy_cache(self._h)
+            self._h = None
+
+    def __del__(self):
+        try:
+            if getattr(self, "_h", None):
+                lib().longflow_destroy_cache(self._h)
+                self._h = None
+        except Exception:
+            pass

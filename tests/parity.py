@@ -1,0 +1,116 @@
+"""Lock-step comparison of the HIP decode path (through the C ABI) with the float64
+oracle on the same seeded inputs.  Helper for the GPU tests and the smoke check."""
+from __future__ import annotations
+
+from dataclasses import dataclass, field
+
+import numpy as np
+import torch
+
+from oracle import longflow_oracle as oracle
+from paper_2603_11504_amd import longflow as lf
+from paper_2603_11504_amd import workloads as W
+
+OUT_TOL = {"f32": 1e-5, "bf16": 2e-2}   # absolute, on the attention output
+NEAR_TIE_REL = 1e-6                     # oracle-score gap below which two slots count as tied
+
+
+@dataclass
+class ParityReport:
+    steps: int = 0
+    decisions: int = 0          # (unit, step) eviction decisions compared
+    near_ties: int = 0          # mismatches inside the near-tie allowance (oracle steered)
+    max_out_err: float = 0.0
+    max_score_rel: float = 0.0
+    notes: list = field(default_factory=list)
+
+
+def compare_indices(gpu_idx, ora_idx, ora_scores, full, rep, where=""):
+    """Bit-exact unless the oracle's own scores of the two slots are within 1e-6 relative.
+    Returns True if the oracle must be steered to the GPU's choice."""
+    gpu_idx = np.asarray(gpu_idx).reshape(-1)
+    ora_idx = np.asarray(ora_idx).reshape(-1)
+    rep.decisions += gpu_idx.size
+    bad = np.nonzero(gpu_idx != ora_idx)[0]
+    if bad.size == 0:
+        return False
+    assert full, f"{where}: fill-phase slot differs: gpu {gpu_idx[bad]} oracle {ora_idx[bad]}"
+    sc = ora_scores.reshape(gpu_idx.size, -1)
+    for u in bad:
+        sg, so = sc[u, gpu_idx[u]], sc[u, ora_idx[u]]
+        assert sg <= so * (1 + NEAR_TIE_REL), (
+            f"{where}: unit {u}: gpu evicts slot {gpu_idx[u]} (oracle score {sg:.17g}), "
+            f"oracle evicts {ora_idx[u]} (score {so:.17g}); gap {(sg - so) / so:.3e} is no near-tie")
+        rep.near_ties += 1
+        rep.notes.append(f"{where}: near-tie unit {u}: {gpu_idx[u]} vs {ora_idx[u]} gap {(sg - so) / max(so, 1e-300):.2e}")
+    return True
+
+
+def run_lockstep(wl: W.Workload, steps=None, flags=0, check_scores_every=0, units=None,
+                 device="cuda", layer=0, host_inputs=True, gpu_cache=None, report=None):
+    """Advance GPU cache and oracle together for `steps` decode steps, comparing each.
+
+    units: optional list of flat (batch*kv_head) unit indices the oracle follows (the GPU
+    always runs the whole workload); None = all of them.
+    """
+    rep = report or ParityReport()
+    steps = wl.steps if steps is None else steps
+    dt = W.torch_dtype(wl)
+    G, D, N = wl.group, wl.head_dim, wl.budget
+    all_units = np.arange(wl.units) if units is None else np.asarray(units)
+    nu = len(all_units)
+
+    # ---- prefill: same bits on both sides
+    if host_inputs:
+        k0, v0 = W.host_prefill(wl, layer)
+        k0_t = None if k0 is None else W.to_torch(k0, wl, device)
+        v0_t = None if v0 is None else W.to_torch(v0, wl, device)
+    else:
+        k0_t, v0_t = W.device_prefill(wl, device, layer)
+    gpu = gpu_cache or lf.LongFlowCache(wl.batch, wl.q_heads, wl.kv_heads, D, N, dtype=dt, flags=flags,
+                                        device=device, k_init=k0_t, v_init=v0_t)
+    ora = oracle.OracleCache(nu, G, 1, D, N)
+    if wl.n_init:
+        sel = torch.as_tensor(all_units, device=k0_t.device)
+        ku = k0_t.reshape(wl.units, wl.n_init, D)[sel].reshape(nu, 1, wl.n_init, D)
+        vu = v0_t.reshape(wl.units, wl.n_init, D)[sel].reshape(nu, 1, wl.n_init, D)
+        ora.init(W.to_f64(ku), W.to_f64(vu))
+    else:
+        ora.init()
+    del k0_t, v0_t
+
+    tol = OUT_TOL[wl.dtype]
+    for t in range(steps):
+        if host_inputs:
+            q, k, v = (W.to_torch(x, wl, device) for x in W.host_step(wl, t, layer))
+        else:
+            q, k, v = W.device_step(wl, t, device, layer)
+        out_t, idx_t = gpu.decode_step(q, k, v)
+        torch.cuda.synchronize()
+        sel = torch.as_tensor(all_units, device=q.device)
+        qu = W.to_f64(q.reshape(wl.units, G, D)[sel])
+        ku = W.to_f64(k.reshape(wl.units, 1, D)[sel])
+        vu = W.to_f64(v.reshape(wl.units, 1, D)[sel])
+        o_ref, i_ref = ora.step(qu, ku, vu)
+        o_gpu = W.to_f64(out_t.reshape(wl.units, G, D)[sel])
+        assert np.isfinite(o_gpu).all(), f"step {t}: non-finite attention output"
+        err = float(np.abs(o_gpu - o_ref).max())
+        rep.max_out_err = max(rep.max_out_err, err)
+        assert err <= tol, f"step {t}: max |out - oracle| = {err:.3e} > {tol}"
+        i_gpu = idx_t.reshape(-1)[sel].cpu().numpy()
+        full = ora.count == N
+        if compare_indices(i_gpu, i_ref, ora.scores(), full, rep, where=f"{wl.name} step {t}"):
+            ora.set_pending(i_gpu.reshape(nu, 1))
+        assert gpu.valid_count == ora.count
+        if check_scores_every and (t % check_scores_every == 0 or t == steps - 1):
+            s_gpu = gpu.scores().reshape(wl.units, N)[sel].cpu().numpy().astype(np.float64)
+            s_ref = ora.scores().reshape(nu, N)
+            n = ora.count
+            assert (s_gpu[:, n:] == 0).all()
+            rel = np.abs(s_gpu[:, :n] - s_ref[:, :n]) / np.maximum(s_ref[:, :n], 1e-30)
+            # fp32 result: 1e-5 relative, except where the score itself is below fp32 range
+            ok = (rel <= 1e-5) | (s_ref[:, :n] < 1e-35)
+            rep.max_score_rel = max(rep.max_score_rel, float(rel[s_ref[:, :n] >= 1e-35].max(initial=0.0)))
+            assert ok.all(), f"step {t}: score rel err {rel[~ok].max():.3e}"
+        rep.steps += 1
+    return rep, gpu, ora

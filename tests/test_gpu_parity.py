@@ -1,0 +1,193 @@
+"""GPU parity: the HIP decode path, called through the C ABI, against the float64 oracle."""
+import numpy as np
+import pytest
+import torch
+
+from oracle import longflow_oracle as oracle
+from paper_2603_11504_amd import longflow as lf
+from paper_2603_11504_amd import workloads as W
+
+from parity import ParityReport, compare_indices, run_lockstep
+
+pytestmark = pytest.mark.gpu
+
+
+def _small(name, dtype, B, Hq, Hkv, D, N, n_init=0, steps=0, **kw):
+    return W.Workload(name, dtype, B, Hq, Hkv, D, N, n_init, steps or 2 * N, **kw)
+
+
+# ------------------------------------------------------------------ BASELINE configs 0 and 1, every step
+
+def test_cfg0_fp32_every_step_with_scores():
+    wl = W.CONFIGS[0]
+    rep, _, _ = run_lockstep(wl, check_scores_every=16)
+    print(f"\ncfg0: steps {rep.steps} decisions {rep.decisions} near-ties {rep.near_ties} "
+          f"max|dout| {rep.max_out_err:.2e} max score rel {rep.max_score_rel:.2e}")
+    assert rep.steps == 512
+
+
+@pytest.mark.parametrize("flags", [0, lf.LF_FLAG_FORCE_VALU], ids=["default", "valu"])
+def test_cfg1_bf16_every_step(flags):
+    wl = W.CONFIGS[1]
+    rep, _, _ = run_lockstep(wl, flags=flags, check_scores_every=512)
+    print(f"\ncfg1[{flags}]: steps {rep.steps} decisions {rep.decisions} near-ties {rep.near_ties} "
+          f"max|dout| {rep.max_out_err:.2e} max score rel {rep.max_score_rel:.2e}")
+    assert rep.steps == 4096
+
+
+# ------------------------------------------------------------------ shapes: groups, head dims, ragged budgets
+
+@pytest.mark.parametrize("dtype,Hq,Hkv,D,N,flags", [
+    ("f32", 1, 1, 64, 37, 0), ("f32", 6, 2, 128, 100, 0), ("f32", 8, 1, 64, 333, 0),
+    ("bf16", 2, 2, 64, 50, 0), ("bf16", 3, 1, 64, 272, 0), ("bf16", 10, 2, 128, 129, 0),
+    ("bf16", 7, 1, 128, 1000, 0), ("bf16", 8, 1, 128, 515, lf.LF_FLAG_FORCE_VALU),
+    ("bf16", 16, 1, 128, 300, 0), ("bf16", 24, 2, 128, 2100, 0),
+])
+def test_shapes_fill_then_evict(dtype, Hq, Hkv, D, N, flags):
+    wl = _small(f"shape_{dtype}_{Hq}x{Hkv}_d{D}_n{N}", dtype, 3, Hq, Hkv, D, N, steps=N + 40,
+                sink_scale=4.0, seed=77 + N)
+    rep, _, _ = run_lockstep(wl, flags=flags, check_scores_every=97)
+    assert rep.steps == N + 40
+
+
+def test_prefilled_caches_of_every_fill_level():
+    # n_init from nearly empty to one short of full, ragged against tiles and splits
+    for n_init in (1, 15, 16, 17, 255, 256, 257, 599):
+        wl = _small(f"prefill_{n_init}", "bf16", 2, 14, 2, 128, 600, n_init=n_init, steps=12, seed=5 + n_init)
+        run_lockstep(wl, check_scores_every=5)
+
+
+# ------------------------------------------------------------------ larger configs at full size, sampled units
+
+def test_cfg2_full_size_all_units():
+    wl = W.CONFIGS[2]
+    rep, _, _ = run_lockstep(wl, steps=4, host_inputs=False, check_scores_every=3)
+    print(f"\ncfg2: decisions {rep.decisions} near-ties {rep.near_ties} max|dout| {rep.max_out_err:.2e}")
+
+
+def test_cfg3_full_size_sampled_units_two_layers():
+    wl = W.CONFIGS[3]
+    rng = np.random.default_rng(wl.seed)
+    for layer in (0, 27):
+        units = np.sort(rng.choice(wl.units, size=64, replace=False))
+        rep, gpu, _ = run_lockstep(wl, steps=4, host_inputs=False, units=units, layer=layer)
+        print(f"\ncfg3 layer {layer}: decisions {rep.decisions} near-ties {rep.near_ties} max|dout| {rep.max_out_err:.2e}")
+        gpu.close()
+        del gpu
+        torch.cuda.empty_cache()
+
+
+def test_cfg4_full_size_sampled_units():
+    wl = W.CONFIGS[4]
+    rng = np.random.default_rng(wl.seed)
+    units = np.sort(rng.choice(wl.units, size=64, replace=False))
+    rep, gpu, _ = run_lockstep(wl, steps=3, host_inputs=False, units=units)
+    print(f"\ncfg4: decisions {rep.decisions} near-ties {rep.near_ties} max|dout| {rep.max_out_err:.2e}")
+    gpu.close()
+    del gpu
+    torch.cuda.empty_cache()
+
+
+# ------------------------------------------------------------------ edge cases
+
+def test_deterministic_bitwise():
+    wl = _small("det", "bf16", 4, 28, 4, 128, 700, n_init=699, steps=20, seed=11)
+    runs = []
+    for _ in range(2):
+        k0, v0 = W.host_prefill(wl)
+        gpu = lf.LongFlowCache(wl.batch, wl.q_heads, wl.kv_heads, wl.head_dim, wl.budget,
+                               k_init=W.to_torch(k0, wl, "cuda"), v_init=W.to_torch(v0, wl, "cuda"))
+        outs, idxs = [], []
+        for t in range(wl.steps):
+            q, k, v = (W.to_torch(x, wl, "cuda") for x in W.host_step(wl, t))
+            o, i = gpu.decode_step(q, k, v)
+            outs.append(o.clone()); idxs.append(i.clone())
+        torch.cuda.synchronize()
+        runs.append((torch.stack(outs), torch.stack(idxs)))
+    assert torch.equal(runs[0][0].view(torch.int16), runs[1][0].view(torch.int16))
+    assert torch.equal(runs[0][1], runs[1][1])
+
+
+def test_insert_lands_in_named_slot_at_tile_and_split_edges():
+    wl = _small("edges", "bf16", 2, 7, 1, 128, 2048 + 256, n_init=2048 + 255, steps=1, seed=21)
+    rep, gpu, ora = run_lockstep(wl, steps=1)
+    N = wl.budget
+    for t, slot in enumerate([0, 15, 16, 255, 256, 1023, 1024, 2047, 2048, N - 1], start=1):
+        pend = np.full((wl.units, 1), slot, dtype=np.int32)
+        gpu.set_pending(torch.from_numpy(pend.reshape(wl.batch, wl.kv_heads)))
+        ora.set_pending(pend)
+        q, k, v = (W.to_torch(x, wl, "cuda") for x in W.host_step(wl, t))
+        out, idx = gpu.decode_step(q, k, v)
+        torch.cuda.synchronize()
+        assert torch.equal(gpu.k_cache[:, :, slot, :], k) and torch.equal(gpu.v_cache[:, :, slot, :], v)
+        o_ref, i_ref = ora.step(W.to_f64(q).reshape(wl.units, wl.group, -1), W.to_f64(k).reshape(wl.units, 1, -1),
+                                W.to_f64(v).reshape(wl.units, 1, -1))
+        assert np.abs(W.to_f64(out).reshape(o_ref.shape) - o_ref).max() <= 2e-2
+        compare_indices(idx.cpu().numpy(), i_ref, ora.scores(), True, rep, where=f"slot {slot}")
+        Kc, _ = ora.kv()
+        np.testing.assert_array_equal(W.to_f64(gpu.k_cache).reshape(Kc.shape), Kc)
+
+
+def test_exact_ties_evict_the_lowest_index():
+    # two bit-identical rows that are jointly the least important: the tie is exact in
+    # the oracle, and the screening + exact re-scoring must resolve it to the lower slot
+    wl = _small("ties", "bf16", 1, 7, 1, 128, 512, n_init=511, steps=1, seed=31)
+    k0, v0 = W.host_prefill(wl)
+    q, k, v = W.host_step(wl, 0)
+    low_k = W.round_to_storage(-0.5 * q.sum(1, keepdims=True), "bf16")   # every head's logit far below the rest
+    low_v = W.round_to_storage(np.full((1, 1, 128), 2.0 ** -6, np.float32), "bf16")
+    for s in (300, 77, 450):
+        k0[:, :, s] = low_k
+        v0[:, :, s] = low_v
+    gpu = lf.LongFlowCache(1, 7, 1, 128, 512, k_init=W.to_torch(k0, wl, "cuda"), v_init=W.to_torch(v0, wl, "cuda"))
+    ora = oracle.OracleCache(1, 7, 1, 128, 512)
+    ora.init(k0.astype(np.float64), v0.astype(np.float64))
+    _, idx = gpu.decode_step(*(W.to_torch(x, wl, "cuda") for x in (q, k, v)))
+    _, i_ref = ora.step(q.astype(np.float64), k.astype(np.float64), v.astype(np.float64))
+    sc = ora.scores()[0, 0]
+    assert sc[77] == sc[300] == sc[450] == sc.min()       # the construction worked
+    assert int(i_ref[0, 0]) == 77
+    assert int(idx.cpu()[0, 0]) == 77
+
+
+def test_wide_logit_range_underflow_is_resolved_exactly():
+    # logits spread over hundreds of nats: most fp32 probabilities underflow to zero, the
+    # screening sees many zeros, and the exact re-scoring must still find the oracle's slot
+    wl = _small("underflow", "bf16", 2, 4, 2, 64, 256, n_init=255, steps=6, seed=41,
+                channel_scale_range=(20.0, 40.0))
+    rep, _, _ = run_lockstep(wl, steps=6)
+    assert rep.near_ties == 0
+
+
+def test_attention_only_flag_leaves_cache_untouched():
+    wl = _small("attn_only", "bf16", 2, 10, 2, 128, 1500, n_init=1500, steps=1, seed=51)
+    k0, v0 = W.host_prefill(wl)
+    gpu = lf.LongFlowCache(2, 10, 2, 128, 1500, flags=lf.LF_FLAG_ATTENTION_ONLY,
+                           k_init=W.to_torch(k0, wl, "cuda"), v_init=W.to_torch(v0, wl, "cuda"))
+    before = gpu.k_cache.clone()
+    q, _, _ = W.host_step(wl, 0)
+    out, _ = gpu.decode_step(W.to_torch(q, wl, "cuda"))
+    torch.cuda.synchronize()
+    assert torch.equal(before.view(torch.int16), gpu.k_cache.view(torch.int16))
+    for u in range(4):
+        o_ref, _, _ = oracle.attend_unit(q.reshape(4, 5, 128)[u], k0.reshape(4, 1500, 128)[u], v0.reshape(4, 1500, 128)[u])
+        assert np.abs(W.to_f64(out).reshape(4, 5, 128)[u] - o_ref).max() <= 2e-2
+    with pytest.raises(lf.LongFlowError):
+        gpu.scores()
+
+
+def test_full_cache_needs_a_pending_slot():
+    wl = _small("born_full", "f32", 1, 4, 1, 64, 64, n_init=64, steps=1, seed=61)
+    k0, v0 = W.host_prefill(wl)
+    gpu = lf.LongFlowCache(1, 4, 1, 64, 64, dtype=torch.float32, k_init=W.to_torch(k0, wl, "cuda"),
+                           v_init=W.to_torch(v0, wl, "cuda"))
+    q, k, v = (W.to_torch(x, wl, "cuda") for x in W.host_step(wl, 0))
+    with pytest.raises(lf.LongFlowError) as e:
+        gpu.decode_step(q, k, v)
+    assert e.value.status == lf.LF_ERR_STATE
+    with pytest.raises(lf.LongFlowError):
+        gpu.scores()
+    gpu.set_pending(torch.tensor([[9]], dtype=torch.int32))
+    gpu.decode_step(q, k, v)
+    torch.cuda.synchronize()
+    assert torch.equal(gpu.k_cache[0, 0, 9], k[0, 0])
