@@ -1,0 +1,164 @@
+#!/usr/bin/env python3
+"""Benchmark of the LongFlow fused decode step on one MI355X.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload cfg3] [--valu]
+
+A "step" is one decode step of the whole workload: every layer's cache advances by
+one token (insert + attention + scores + eviction), i.e. `layers` C-ABI calls.  Inputs
+are seeded synthetic tensors already resident in HBM.  Prints ONE JSON line.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0  # MI355X published peak HBM3E bandwidth
+
+# HBM bytes per launch of the streaming kernel measured with rocprofv3 --pmc
+# (FETCH_SIZE / WRITE_SIZE, scaled by a copy kernel of known size); see profiles/.
+MEASURED_TRAFFIC = {}
+
+
+def parse():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=None)
+    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--workload", default="cfg3", help="cfg0..cfg4 (BASELINE.json configs)")
+    ap.add_argument("--valu", action="store_true", help="bf16: vector-ALU kernel instead of matrix cores")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--pool", type=int, default=4, help="distinct input steps cycled through")
+    return ap.parse_args()
+
+
+def cpu_baseline(wl, caches_layer0, target_s=12.0):
+    """The float64 oracle, as it stands, timed on this host on a bounded sample of units."""
+    import numpy as np
+    import torch
+    from oracle import longflow_oracle as oracle
+    from paper_2603_11504_amd import workloads as W
+
+    G, D, N = wl.group, wl.head_dim, wl.budget
+    threads = oracle.num_threads()
+    nu = min(wl.units, max(threads, 16))
+    rng = np.random.default_rng(wl.seed)
+    units = np.sort(rng.choice(wl.units, size=nu, replace=False))
+    sel = torch.as_tensor(units, device=caches_layer0.k_cache.device)
+    n = caches_layer0.valid_count
+    ku = caches_layer0.k_cache.reshape(wl.units, N, D)[sel][:, : n - 1].reshape(nu, 1, n - 1, D)
+    vu = caches_layer0.v_cache.reshape(wl.units, N, D)[sel][:, : n - 1].reshape(nu, 1, n - 1, D)
+    ora = oracle.OracleCache(nu, G, 1, D, N)
+    ora.init(W.to_f64(ku), W.to_f64(vu))
+    g = np.random.default_rng(1)
+    steps, t_total = 0, 0.0
+    while t_total < target_s and steps < 64:
+        q = g.standard_normal((nu, G, D)); k = g.standard_normal((nu, 1, D)); v = g.standard_normal((nu, 1, D))
+        t0 = time.perf_counter()
+        ora.step(q, k, v)
+        t_total += time.perf_counter() - t0
+        steps += 1
+    unit_steps = nu * steps
+    full_step_s = t_total / unit_steps * wl.units * wl.layers      # linear extrapolation
+    return {"value": wl.batch / full_step_s, "unit": "tokens/s", "cores": min(threads, nu), "kind": "oracle",
+            "sample": f"{nu} of {wl.units * wl.layers} (layer,batch,kv-head) units x {steps} steps at n={n}, "
+                      f"{t_total:.1f} s, scaled linearly to the full step",
+            "ms_per_step": full_step_s * 1e3}
+
+
+def main():
+    a = parse()
+    if a.gpus != 1:
+        print("bench.py: this build runs on ONE GPU (units are independent; see DESIGN.md on sharding); "
+              f"--gpus {a.gpus} is not supported", file=sys.stderr)
+        sys.exit(2)
+    import torch
+    from paper_2603_11504_amd import longflow as lf
+    from paper_2603_11504_amd import workloads as W
+
+    idx = int(a.workload.replace("cfg", ""))
+    wl = W.CONFIGS[idx]
+    steps = a.steps if a.steps is not None else {0: 512, 1: 1024, 2: 100, 3: 256, 4: 50}[idx]
+    dev = torch.device("cuda:0")
+    torch.cuda.set_device(dev)
+    flags = lf.LF_FLAG_FORCE_VALU if (a.valu and wl.dtype == "bf16") else 0
+    dt = W.torch_dtype(wl)
+
+    # ---- resident state: one cache per layer, pre-filled to N-1 rows where the workload says so
+    caches = []
+    for layer in range(wl.layers):
+        k0, v0 = W.device_prefill(wl, dev, layer)
+        caches.append(lf.LongFlowCache(wl.batch, wl.q_heads, wl.kv_heads, wl.head_dim, wl.budget, dtype=dt,
+                                       flags=flags, device=dev, k_init=k0, v_init=v0))
+        del k0, v0
+    pool = [[W.device_step(wl, t, dev, layer) for layer in range(wl.layers)] for t in range(a.pool)]
+    torch.cuda.synchronize()
+
+    def run(nsteps, t0=0):
+        for t in range(t0, t0 + nsteps):
+            inputs = pool[t % a.pool]
+            for layer, c in enumerate(caches):
+                q, k, v = inputs[layer]
+                c.decode_step(q, k, v)
+
+    # empty-start workloads fill first so that the timed steps are evicting steps
+    fill = wl.budget - wl.n_init - 1
+    warm = max(a.warmup, 1) + max(fill, 0)
+    run(warm)
+    torch.cuda.synchronize()
+    assert all(c.valid_count == wl.budget for c in caches)
+
+    t0 = time.perf_counter()
+    run(steps, warm)
+    torch.cuda.synchronize()
+    dt_s = time.perf_counter() - t0
+    ms_per_step = dt_s / steps * 1e3
+    calls = steps * wl.layers
+
+    # ---- same steps again with HIP events around each kernel (per-kernel durations)
+    for c in caches:
+        c.profile_begin(steps)
+    run(steps, warm + steps)
+    ksum = {"insert": 0.0, "split": 0.0, "finish": 0.0}
+    for c in caches:
+        ms, n = c.profile_end()
+        assert n == steps
+        for k in ksum:
+            ksum[k] += ms[k]
+    kavg_us = {k: v / calls * 1e3 for k, v in ksum.items()}
+
+    bytes_call = wl.kv_bytes_per_call()
+    split_name = "split_mfma_kernel" if (wl.dtype == "bf16" and wl.head_dim == 128 and not flags) else "split_valu_kernel"
+    achieved = bytes_call / (kavg_us["split"] * 1e-6) / 1e9
+    out = {
+        "metric": "decode_tokens_per_s",
+        "value": wl.batch / (ms_per_step * 1e-3),
+        "unit": "tokens/s",
+        "n_gpus": 1, "steps": steps, "warmup": warm, "ms_per_step": ms_per_step,
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "f32" if wl.dtype == "f32" else "bf16 storage, f32 accumulate",
+        "data": "synthetic",
+        "config": {"workload": wl.name, "batch": wl.batch, "q_heads": wl.q_heads, "kv_heads": wl.kv_heads,
+                   "head_dim": wl.head_dim, "budget": wl.budget, "layers": wl.layers,
+                   "calls_per_step": wl.layers, "kernel_path": "valu" if split_name.startswith("split_valu") else "mfma"},
+        "us_per_call": ms_per_step * 1e3 / wl.layers,
+        "step_hbm_GBs": bytes_call * wl.layers / (ms_per_step * 1e-3) / 1e9,
+        "step_hbm_frac": bytes_call * wl.layers / (ms_per_step * 1e-3) / 1e9 / HBM_PEAK_GBS,
+        "kernel_us": kavg_us,
+        "roofline": {"bound": "hbm", "kernel": split_name, "achieved": achieved, "peak": HBM_PEAK_GBS,
+                     "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS,
+                     "bytes_per_launch": bytes_call, "avg_launch_us": kavg_us["split"],
+                     "traffic": MEASURED_TRAFFIC.get((wl.name, split_name))},
+    }
+    if not a.no_cpu_baseline:
+        out["cpu_baseline"] = cpu_baseline(wl, caches[0])
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()

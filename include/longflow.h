@@ -133,6 +133,19 @@ LF_API int longflow_valid_count(const longflow_cache_t *cache);
 /* Frees the host handle only. */
 LF_API int longflow_destroy_cache(longflow_cache_t *cache);
 
+/*
+ * Measurement aid (not part of the paper's operator): while profiling is on, every
+ * decode step records HIP events on its stream around its three kernels.
+ *   longflow_profile_begin  creates events for up to max_steps steps and switches it on
+ *   longflow_profile_end    waits for the recorded events, writes the summed durations
+ *                           in milliseconds to kernel_ms[3] = {insert, streaming pass,
+ *                           finish} and the number of steps recorded to *steps (host
+ *                           pointers), destroys the events and switches it off.
+ * Steps beyond max_steps run untimed.  Synchronises the host with the stream.
+ */
+LF_API int longflow_profile_begin(longflow_cache_t *cache, int32_t max_steps);
+LF_API int longflow_profile_end(longflow_cache_t *cache, float *kernel_ms, int32_t *steps);
+
 /* Text of the calling thread's last error ("" if none). Never NULL. */
 LF_API const char *longflow_last_error(void);
 

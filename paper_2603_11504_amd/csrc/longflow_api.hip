@@ -6,6 +6,7 @@
 #include <cstdio>
 #include <cstdlib>
 #include <cstring>
+#include <vector>
 
 #include "lf_host.h"
 
@@ -108,6 +109,8 @@ struct longflow_cache {
     int count;         // valid slots
     bool has_pending;  // a slot for the next token is known on the device
     bool stepped;      // at least one decode step ran (scores are defined)
+    std::vector<hipEvent_t> prof_events; // 4 per recorded step while profiling
+    int prof_cap = 0, prof_used = 0;
 };
 
 static const uint32_t kMagic = 0x4c46434bu;
@@ -209,12 +212,18 @@ int longflow_decode_step(longflow_cache_t *cache, const void *q, const void *k_n
         n = c->count < p.N ? c->count + 1 : p.N;
     }
     hipStream_t s = (hipStream_t)hip_stream;
+    hipEvent_t *ev = nullptr;
+    if (c->prof_used < c->prof_cap) ev = &c->prof_events[4 * (size_t)c->prof_used++];
+    if (ev) (void)hipEventRecord(ev[0], s);
     hipError_t e = launch_insert(p, q, k_new, v_new, s);
     if (e != hipSuccess) return fail(LF_ERR_HIP, "insert launch: %s", hipGetErrorString(e));
+    if (ev) (void)hipEventRecord(ev[1], s);
     e = p.use_mfma ? launch_split_mfma(p, q, n, s) : launch_split_valu(p, q, n, s);
     if (e != hipSuccess) return fail(LF_ERR_HIP, "split launch: %s", hipGetErrorString(e));
+    if (ev) (void)hipEventRecord(ev[2], s);
     e = launch_finish(p, q, n, out, evict_idx, s);
     if (e != hipSuccess) return fail(LF_ERR_HIP, "finish launch: %s", hipGetErrorString(e));
+    if (ev) (void)hipEventRecord(ev[3], s);
     c->count = n;
     c->stepped = true;
     return LF_OK;
@@ -248,6 +257,55 @@ int longflow_set_pending(longflow_cache_t *cache, const int32_t *slots, void *hi
     return LF_OK;
 }
 
+static void drop_events(longflow_cache *c)
+{
+    for (hipEvent_t e : c->prof_events) (void)hipEventDestroy(e);
+    c->prof_events.clear();
+    c->prof_cap = c->prof_used = 0;
+}
+
+int longflow_profile_begin(longflow_cache_t *cache, int32_t max_steps)
+{
+    longflow_cache *c = checked(cache);
+    if (!c) return fail(LF_ERR_STATE, "invalid or destroyed cache handle");
+    if (max_steps < 1 || max_steps > (1 << 20)) return fail(LF_ERR_INVALID_ARG, "max_steps out of range");
+    drop_events(c);
+    c->prof_events.resize(4 * (size_t)max_steps);
+    for (size_t i = 0; i < c->prof_events.size(); ++i) {
+        hipError_t e = hipEventCreate(&c->prof_events[i]);
+        if (e != hipSuccess) {
+            c->prof_events.resize(i);
+            drop_events(c);
+            return fail(LF_ERR_HIP, "hipEventCreate: %s", hipGetErrorString(e));
+        }
+    }
+    c->prof_cap = max_steps;
+    c->prof_used = 0;
+    return LF_OK;
+}
+
+int longflow_profile_end(longflow_cache_t *cache, float *kernel_ms, int32_t *steps)
+{
+    longflow_cache *c = checked(cache);
+    if (!c) return fail(LF_ERR_STATE, "invalid or destroyed cache handle");
+    if (!kernel_ms || !steps) return fail(LF_ERR_INVALID_ARG, "kernel_ms/steps is NULL");
+    kernel_ms[0] = kernel_ms[1] = kernel_ms[2] = 0.f;
+    *steps = c->prof_used;
+    int rc = LF_OK;
+    for (int i = 0; i < c->prof_used && rc == LF_OK; ++i) {
+        hipEvent_t *ev = &c->prof_events[4 * (size_t)i];
+        hipError_t e = hipEventSynchronize(ev[3]);
+        for (int k = 0; k < 3 && e == hipSuccess; ++k) {
+            float ms = 0.f;
+            e = hipEventElapsedTime(&ms, ev[k], ev[k + 1]);
+            kernel_ms[k] += ms;
+        }
+        if (e != hipSuccess) rc = fail(LF_ERR_HIP, "event timing: %s", hipGetErrorString(e));
+    }
+    drop_events(c);
+    return rc;
+}
+
 int longflow_valid_count(const longflow_cache_t *cache)
 {
     return (cache && cache->magic == kMagic) ? cache->count : -1;
@@ -257,6 +315,7 @@ int longflow_destroy_cache(longflow_cache_t *cache)
 {
     longflow_cache *c = checked(cache);
     if (!c) return fail(LF_ERR_STATE, "invalid or destroyed cache handle");
+    drop_events(c);
     c->magic = 0;
     delete c;
     return LF_OK;

@@ -21,7 +21,8 @@ LF_FLAG_FORCE_VALU = 2
 
 EXPORTS = ("longflow_workspace_bytes", "longflow_init_cache", "longflow_decode_step",
            "longflow_scores", "longflow_set_pending", "longflow_valid_count",
-           "longflow_destroy_cache", "longflow_last_error")
+           "longflow_destroy_cache", "longflow_last_error", "longflow_profile_begin",
+           "longflow_profile_end")
 
 
 class lf_config(ctypes.Structure):
@@ -62,6 +63,10 @@ def lib():
         L.longflow_valid_count.restype = ctypes.c_int
         L.longflow_destroy_cache.argtypes = [vp]
         L.longflow_destroy_cache.restype = ctypes.c_int
+        L.longflow_profile_begin.argtypes = [vp, i32]
+        L.longflow_profile_begin.restype = ctypes.c_int
+        L.longflow_profile_end.argtypes = [vp, ctypes.POINTER(ctypes.c_float), ctypes.POINTER(i32)]
+        L.longflow_profile_end.restype = ctypes.c_int
         L.longflow_last_error.argtypes = []
         L.longflow_last_error.restype = ctypes.c_char_p
         _lib = L
@@ -136,6 +141,16 @@ class LongFlowCache:
         slots = slots.to(device=self.device, dtype=torch.int32).contiguous()
         _check(lib().longflow_set_pending(self._h, _ptr(slots), _stream()))
         self._keep = slots  # alive until the async copy has run
+
+    def profile_begin(self, max_steps):
+        _check(lib().longflow_profile_begin(self._h, max_steps))
+
+    def profile_end(self):
+        """-> ({"insert": ms, "split": ms, "finish": ms} summed over the recorded steps, steps)."""
+        ms = (ctypes.c_float * 3)()
+        n = ctypes.c_int32()
+        _check(lib().longflow_profile_end(self._h, ms, ctypes.byref(n)))
+        return {"insert": ms[0], "split": ms[1], "finish": ms[2]}, int(n.value)
 
     @property
     def valid_count(self):
