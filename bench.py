@@ -32,6 +32,8 @@ def parse():
     ap.add_argument("--warmup", type=int, default=3)
     ap.add_argument("--workload", default="cfg3", help="cfg0..cfg4 (BASELINE.json configs)")
     ap.add_argument("--valu", action="store_true", help="bf16: vector-ALU kernel instead of matrix cores")
+    ap.add_argument("--split", action="store_true", help="force the split-K (3-launch) path")
+    ap.add_argument("--unit", action="store_true", help="force the one-workgroup-per-unit fused path")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--pool", type=int, default=4, help="distinct input steps cycled through")
     return ap.parse_args()
@@ -87,6 +89,8 @@ def main():
     dev = torch.device("cuda:0")
     torch.cuda.set_device(dev)
     flags = lf.LF_FLAG_FORCE_VALU if (a.valu and wl.dtype == "bf16") else 0
+    flags |= lf.LF_FLAG_FORCE_SPLIT if a.split else 0
+    flags |= lf.LF_FLAG_FORCE_UNIT if a.unit else 0
     dt = W.torch_dtype(wl)
 
     # ---- resident state: one cache per layer, pre-filled to N-1 rows where the workload says so

@@ -69,6 +69,9 @@ typedef enum { LF_F32 = 0, LF_BF16 = 1 } lf_dtype;
                                      (the uncompressed comparison of Sec. 4.4)            */
 #define LF_FLAG_FORCE_VALU 2u     /* bf16 only: use the vector-ALU kernel instead of the
                                      matrix-core kernel (for A/B measurement)              */
+#define LF_FLAG_FORCE_SPLIT 4u    /* always split a unit over several workgroups (3 launches) */
+#define LF_FLAG_FORCE_UNIT 8u     /* always one workgroup per unit, one fused launch; needs the
+                                     matrix-core path and budget * group <= ~120k            */
 
 typedef struct {
     int32_t batch;    /* B   >= 1                                            */

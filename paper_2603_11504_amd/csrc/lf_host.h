@@ -18,7 +18,8 @@ struct Plan {
     int L;             // slots per split (multiple of kTile)
     int C;             // number of splits covering N
     int ntiles;        // ceil(N / kTile)
-    bool use_mfma;
+    bool use_mfma;     // bf16, head_dim 128: matrix-core kernels
+    bool use_unit;     // one workgroup per unit, whole step fused in one launch
     // device pointers (caller-owned)
     void *k_cache, *v_cache;
     // carved out of the caller's workspace
@@ -47,6 +48,9 @@ hipError_t launch_insert(const Plan &p, const void *q, const void *k_new, const 
                          hipStream_t s);
 hipError_t launch_split_valu(const Plan &p, const void *q, int n, hipStream_t s);
 hipError_t launch_split_mfma(const Plan &p, const void *q, int n, hipStream_t s);
+size_t unit_mfma_lds_bytes(int N, int G, bool stash);
+hipError_t launch_unit_mfma(const Plan &p, const void *q, const void *k_new, const void *v_new, int n,
+                            void *out, int32_t *evict_idx, hipStream_t s);
 hipError_t launch_finish(const Plan &p, const void *q, int n, void *out, int32_t *evict_idx,
                          hipStream_t s);
 hipError_t launch_scores(const Plan &p, int n, float *scores, hipStream_t s);

@@ -25,6 +25,11 @@ static int fail(int code, const char *fmt, ...)
 
 static size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
 
+// dynamic LDS one workgroup may ask for (160 KB per CU minus the kernels' static part)
+static const size_t kUnitLdsLimit = 160 * 1024 - 2048;
+// from this many units on, one workgroup per unit keeps the chip busy (256 CUs)
+static const int kUnitMinUnits = 192;
+
 void choose_splits(int units, int N, int *L, int *C)
 {
     // Enough workgroups to fill 256 CUs several times over, each streaming a span long
@@ -53,7 +58,7 @@ static int validate(const lf_config *cfg)
         return fail(LF_ERR_INVALID_ARG, "batch/heads/budget out of range");
     if (cfg->dtype != LF_F32 && cfg->dtype != LF_BF16)
         return fail(LF_ERR_INVALID_ARG, "unknown dtype %d", cfg->dtype);
-    if (cfg->flags & ~(LF_FLAG_ATTENTION_ONLY | LF_FLAG_FORCE_VALU))
+    if (cfg->flags & ~(LF_FLAG_ATTENTION_ONLY | LF_FLAG_FORCE_VALU | LF_FLAG_FORCE_SPLIT | LF_FLAG_FORCE_UNIT))
         return fail(LF_ERR_INVALID_ARG, "unknown flag bits 0x%x", cfg->flags);
     if (cfg->q_heads % cfg->kv_heads)
         return fail(LF_ERR_UNSUPPORTED, "q_heads %d is not a multiple of kv_heads %d", cfg->q_heads,
@@ -67,6 +72,13 @@ static int validate(const lf_config *cfg)
         return fail(LF_ERR_UNSUPPORTED, "group size %d > 8 needs bf16, head_dim 128 and the matrix-core kernel", G);
     if ((long long)cfg->batch * cfg->kv_heads > (1ll << 20))
         return fail(LF_ERR_UNSUPPORTED, "batch*kv_heads > 2^20");
+    if ((cfg->flags & LF_FLAG_FORCE_SPLIT) && (cfg->flags & LF_FLAG_FORCE_UNIT))
+        return fail(LF_ERR_INVALID_ARG, "FORCE_SPLIT and FORCE_UNIT exclude each other");
+    if (cfg->flags & LF_FLAG_FORCE_UNIT) {
+        if (!mfma) return fail(LF_ERR_UNSUPPORTED, "FORCE_UNIT needs bf16, head_dim 128 and the matrix-core kernel");
+        if (unit_mfma_lds_bytes(cfg->budget, G, !(cfg->flags & LF_FLAG_ATTENTION_ONLY)) > kUnitLdsLimit)
+            return fail(LF_ERR_UNSUPPORTED, "FORCE_UNIT: budget %d x group %d does not fit the per-unit LDS stash", cfg->budget, G);
+    }
     return LF_OK;
 }
 
@@ -79,6 +91,9 @@ static void fill_plan(const lf_config *cfg, Plan *p)
     choose_splits(p->units, p->N, &p->L, &p->C);
     p->ntiles = (p->N + kTile - 1) / kTile;
     p->use_mfma = cfg->dtype == LF_BF16 && cfg->head_dim == 128 && !(cfg->flags & LF_FLAG_FORCE_VALU);
+    const bool fits = unit_mfma_lds_bytes(p->N, p->G, !(cfg->flags & LF_FLAG_ATTENTION_ONLY)) <= kUnitLdsLimit;
+    p->use_unit = p->use_mfma && fits && !(cfg->flags & LF_FLAG_FORCE_SPLIT) &&
+                  ((cfg->flags & LF_FLAG_FORCE_UNIT) || p->units >= kUnitMinUnits);
 }
 
 static Layout layout_of(const Plan &p)
@@ -215,15 +230,24 @@ int longflow_decode_step(longflow_cache_t *cache, const void *q, const void *k_n
     hipEvent_t *ev = nullptr;
     if (c->prof_used < c->prof_cap) ev = &c->prof_events[4 * (size_t)c->prof_used++];
     if (ev) (void)hipEventRecord(ev[0], s);
-    hipError_t e = launch_insert(p, q, k_new, v_new, s);
-    if (e != hipSuccess) return fail(LF_ERR_HIP, "insert launch: %s", hipGetErrorString(e));
-    if (ev) (void)hipEventRecord(ev[1], s);
-    e = p.use_mfma ? launch_split_mfma(p, q, n, s) : launch_split_valu(p, q, n, s);
-    if (e != hipSuccess) return fail(LF_ERR_HIP, "split launch: %s", hipGetErrorString(e));
-    if (ev) (void)hipEventRecord(ev[2], s);
-    e = launch_finish(p, q, n, out, evict_idx, s);
-    if (e != hipSuccess) return fail(LF_ERR_HIP, "finish launch: %s", hipGetErrorString(e));
-    if (ev) (void)hipEventRecord(ev[3], s);
+    hipError_t e;
+    if (p.use_unit) {
+        // the whole step is one kernel: it is reported in the "streaming pass" slot
+        if (ev) { (void)hipEventRecord(ev[1], s); }
+        e = launch_unit_mfma(p, q, k_new, v_new, n, out, evict_idx, s);
+        if (e != hipSuccess) return fail(LF_ERR_HIP, "fused launch: %s", hipGetErrorString(e));
+        if (ev) { (void)hipEventRecord(ev[2], s); (void)hipEventRecord(ev[3], s); }
+    } else {
+        e = launch_insert(p, q, k_new, v_new, s);
+        if (e != hipSuccess) return fail(LF_ERR_HIP, "insert launch: %s", hipGetErrorString(e));
+        if (ev) (void)hipEventRecord(ev[1], s);
+        e = p.use_mfma ? launch_split_mfma(p, q, n, s) : launch_split_valu(p, q, n, s);
+        if (e != hipSuccess) return fail(LF_ERR_HIP, "split launch: %s", hipGetErrorString(e));
+        if (ev) (void)hipEventRecord(ev[2], s);
+        e = launch_finish(p, q, n, out, evict_idx, s);
+        if (e != hipSuccess) return fail(LF_ERR_HIP, "finish launch: %s", hipGetErrorString(e));
+        if (ev) (void)hipEventRecord(ev[3], s);
+    }
     c->count = n;
     c->stepped = true;
     return LF_OK;

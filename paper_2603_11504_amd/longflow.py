@@ -18,6 +18,8 @@ LF_OK, LF_ERR_INVALID_ARG, LF_ERR_UNSUPPORTED, LF_ERR_WORKSPACE, LF_ERR_STATE, L
 LF_F32, LF_BF16 = 0, 1
 LF_FLAG_ATTENTION_ONLY = 1
 LF_FLAG_FORCE_VALU = 2
+LF_FLAG_FORCE_SPLIT = 4
+LF_FLAG_FORCE_UNIT = 8
 
 EXPORTS = ("longflow_workspace_bytes", "longflow_init_cache", "longflow_decode_step",
            "longflow_scores", "longflow_set_pending", "longflow_valid_count",

@@ -42,6 +42,10 @@ def test_cfg1_bf16_every_step(flags):
     ("bf16", 2, 2, 64, 50, 0), ("bf16", 3, 1, 64, 272, 0), ("bf16", 10, 2, 128, 129, 0),
     ("bf16", 7, 1, 128, 1000, 0), ("bf16", 8, 1, 128, 515, lf.LF_FLAG_FORCE_VALU),
     ("bf16", 16, 1, 128, 300, 0), ("bf16", 24, 2, 128, 2100, 0),
+    # one fused launch per step, one workgroup per unit
+    ("bf16", 1, 1, 128, 61, lf.LF_FLAG_FORCE_UNIT), ("bf16", 14, 2, 128, 129, lf.LF_FLAG_FORCE_UNIT),
+    ("bf16", 7, 1, 128, 1000, lf.LF_FLAG_FORCE_UNIT), ("bf16", 16, 1, 128, 300, lf.LF_FLAG_FORCE_UNIT),
+    ("bf16", 10, 2, 128, 2100, lf.LF_FLAG_FORCE_UNIT),
 ])
 def test_shapes_fill_then_evict(dtype, Hq, Hkv, D, N, flags):
     wl = _small(f"shape_{dtype}_{Hq}x{Hkv}_d{D}_n{N}", dtype, 3, Hq, Hkv, D, N, steps=N + 40,
@@ -50,19 +54,32 @@ def test_shapes_fill_then_evict(dtype, Hq, Hkv, D, N, flags):
     assert rep.steps == N + 40
 
 
-def test_prefilled_caches_of_every_fill_level():
+@pytest.mark.parametrize("flags", [lf.LF_FLAG_FORCE_SPLIT, lf.LF_FLAG_FORCE_UNIT], ids=["split", "unit"])
+def test_prefilled_caches_of_every_fill_level(flags):
     # n_init from nearly empty to one short of full, ragged against tiles and splits
-    for n_init in (1, 15, 16, 17, 255, 256, 257, 599):
+    for n_init in (1, 15, 16, 17, 127, 128, 129, 255, 256, 257, 599):
         wl = _small(f"prefill_{n_init}", "bf16", 2, 14, 2, 128, 600, n_init=n_init, steps=12, seed=5 + n_init)
-        run_lockstep(wl, check_scores_every=5)
+        run_lockstep(wl, flags=flags, check_scores_every=5)
 
 
 # ------------------------------------------------------------------ larger configs at full size, sampled units
 
-def test_cfg2_full_size_all_units():
+@pytest.mark.parametrize("flags", [0, lf.LF_FLAG_FORCE_UNIT], ids=["default", "unit"])
+def test_cfg2_full_size_all_units(flags):
     wl = W.CONFIGS[2]
-    rep, _, _ = run_lockstep(wl, steps=4, host_inputs=False, check_scores_every=3)
-    print(f"\ncfg2: decisions {rep.decisions} near-ties {rep.near_ties} max|dout| {rep.max_out_err:.2e}")
+    rep, gpu, _ = run_lockstep(wl, steps=4, flags=flags, host_inputs=False, check_scores_every=3)
+    print(f"\ncfg2[{flags}]: decisions {rep.decisions} near-ties {rep.near_ties} max|dout| {rep.max_out_err:.2e}")
+    gpu.close()
+
+
+def test_cfg3_one_layer_split_path():
+    wl = W.CONFIGS[3]
+    units = np.arange(0, wl.units, 8)
+    rep, gpu, _ = run_lockstep(wl, steps=2, flags=lf.LF_FLAG_FORCE_SPLIT, host_inputs=False, units=units, layer=3)
+    print(f"\ncfg3 split path: decisions {rep.decisions} near-ties {rep.near_ties} max|dout| {rep.max_out_err:.2e}")
+    gpu.close()
+    del gpu
+    torch.cuda.empty_cache()
 
 
 def test_cfg3_full_size_sampled_units_two_layers():
@@ -90,12 +107,13 @@ def test_cfg4_full_size_sampled_units():
 
 # ------------------------------------------------------------------ edge cases
 
-def test_deterministic_bitwise():
+@pytest.mark.parametrize("flags", [lf.LF_FLAG_FORCE_SPLIT, lf.LF_FLAG_FORCE_UNIT], ids=["split", "unit"])
+def test_deterministic_bitwise(flags):
     wl = _small("det", "bf16", 4, 28, 4, 128, 700, n_init=699, steps=20, seed=11)
     runs = []
     for _ in range(2):
         k0, v0 = W.host_prefill(wl)
-        gpu = lf.LongFlowCache(wl.batch, wl.q_heads, wl.kv_heads, wl.head_dim, wl.budget,
+        gpu = lf.LongFlowCache(wl.batch, wl.q_heads, wl.kv_heads, wl.head_dim, wl.budget, flags=flags,
                                k_init=W.to_torch(k0, wl, "cuda"), v_init=W.to_torch(v0, wl, "cuda"))
         outs, idxs = [], []
         for t in range(wl.steps):
@@ -108,9 +126,10 @@ def test_deterministic_bitwise():
     assert torch.equal(runs[0][1], runs[1][1])
 
 
-def test_insert_lands_in_named_slot_at_tile_and_split_edges():
+@pytest.mark.parametrize("flags", [lf.LF_FLAG_FORCE_SPLIT, lf.LF_FLAG_FORCE_UNIT], ids=["split", "unit"])
+def test_insert_lands_in_named_slot_at_tile_and_split_edges(flags):
     wl = _small("edges", "bf16", 2, 7, 1, 128, 2048 + 256, n_init=2048 + 255, steps=1, seed=21)
-    rep, gpu, ora = run_lockstep(wl, steps=1)
+    rep, gpu, ora = run_lockstep(wl, steps=1, flags=flags)
     N = wl.budget
     for t, slot in enumerate([0, 15, 16, 255, 256, 1023, 1024, 2047, 2048, N - 1], start=1):
         pend = np.full((wl.units, 1), slot, dtype=np.int32)
@@ -128,7 +147,8 @@ def test_insert_lands_in_named_slot_at_tile_and_split_edges():
         np.testing.assert_array_equal(W.to_f64(gpu.k_cache).reshape(Kc.shape), Kc)
 
 
-def test_exact_ties_evict_the_lowest_index():
+@pytest.mark.parametrize("flags", [lf.LF_FLAG_FORCE_SPLIT, lf.LF_FLAG_FORCE_UNIT], ids=["split", "unit"])
+def test_exact_ties_evict_the_lowest_index(flags):
     # two bit-identical rows that are jointly the least important: the tie is exact in
     # the oracle, and the screening + exact re-scoring must resolve it to the lower slot
     wl = _small("ties", "bf16", 1, 7, 1, 128, 512, n_init=511, steps=1, seed=31)
@@ -139,7 +159,8 @@ def test_exact_ties_evict_the_lowest_index():
     for s in (300, 77, 450):
         k0[:, :, s] = low_k
         v0[:, :, s] = low_v
-    gpu = lf.LongFlowCache(1, 7, 1, 128, 512, k_init=W.to_torch(k0, wl, "cuda"), v_init=W.to_torch(v0, wl, "cuda"))
+    gpu = lf.LongFlowCache(1, 7, 1, 128, 512, flags=flags, k_init=W.to_torch(k0, wl, "cuda"),
+                           v_init=W.to_torch(v0, wl, "cuda"))
     ora = oracle.OracleCache(1, 7, 1, 128, 512)
     ora.init(k0.astype(np.float64), v0.astype(np.float64))
     _, idx = gpu.decode_step(*(W.to_torch(x, wl, "cuda") for x in (q, k, v)))
@@ -150,19 +171,22 @@ def test_exact_ties_evict_the_lowest_index():
     assert int(idx.cpu()[0, 0]) == 77
 
 
-def test_wide_logit_range_underflow_is_resolved_exactly():
+@pytest.mark.parametrize("D,flags", [(64, 0), (128, lf.LF_FLAG_FORCE_SPLIT), (128, lf.LF_FLAG_FORCE_UNIT)],
+                         ids=["valu", "split", "unit"])
+def test_wide_logit_range_underflow_is_resolved_exactly(D, flags):
     # logits spread over hundreds of nats: most fp32 probabilities underflow to zero, the
     # screening sees many zeros, and the exact re-scoring must still find the oracle's slot
-    wl = _small("underflow", "bf16", 2, 4, 2, 64, 256, n_init=255, steps=6, seed=41,
+    wl = _small("underflow", "bf16", 2, 4, 2, D, 256, n_init=255, steps=6, seed=41,
                 channel_scale_range=(20.0, 40.0))
-    rep, _, _ = run_lockstep(wl, steps=6)
+    rep, _, _ = run_lockstep(wl, steps=6, flags=flags)
     assert rep.near_ties == 0
 
 
-def test_attention_only_flag_leaves_cache_untouched():
+@pytest.mark.parametrize("flags", [lf.LF_FLAG_FORCE_SPLIT, lf.LF_FLAG_FORCE_UNIT], ids=["split", "unit"])
+def test_attention_only_flag_leaves_cache_untouched(flags):
     wl = _small("attn_only", "bf16", 2, 10, 2, 128, 1500, n_init=1500, steps=1, seed=51)
     k0, v0 = W.host_prefill(wl)
-    gpu = lf.LongFlowCache(2, 10, 2, 128, 1500, flags=lf.LF_FLAG_ATTENTION_ONLY,
+    gpu = lf.LongFlowCache(2, 10, 2, 128, 1500, flags=lf.LF_FLAG_ATTENTION_ONLY | flags,
                            k_init=W.to_torch(k0, wl, "cuda"), v_init=W.to_torch(v0, wl, "cuda"))
     before = gpu.k_cache.clone()
     q, _, _ = W.host_step(wl, 0)
