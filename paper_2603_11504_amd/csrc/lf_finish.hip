@@ -2,6 +2,7 @@
 // the eviction argmin, on-demand score read-back.
 #include "lf_device.h"
 #include "lf_host.h"
+#include "lf_mfma_stream.h"
 
 namespace lf {
 
@@ -15,17 +16,30 @@ __global__ __launch_bounds__(128) void insert_kernel(T *__restrict__ Kc, T *__re
                                                       const T *__restrict__ v_new,
                                                       const int32_t *__restrict__ pending,
                                                       const T *__restrict__ q, T *__restrict__ q_last,
-                                                      int units, int N, int D, int q_elems)
+                                                      int units, int N, int D, int q_elems,
+                                                      float *__restrict__ lu, int lu_stride)
 {
+    __shared__ float part[2];
     const int b = blockIdx.x;
     if (b < units) {
         const int slot = pending[b];
         if (slot < 0 || slot >= N) return; // never write outside the cache
         T *kd = Kc + ((size_t)b * N + slot) * D;
         T *vd = Vc + ((size_t)b * N + slot) * D;
+        float a1 = 0.f;
         for (int d = threadIdx.x; d < D; d += blockDim.x) {
             kd[d] = k_new[(size_t)b * D + d];
-            vd[d] = v_new[(size_t)b * D + d];
+            const T v = v_new[(size_t)b * D + d];
+            vd[d] = v;
+            a1 += fabsf(to_f32(v));
+        }
+        if (lu) { // side array of the matrix-core kernels: log2 ||v||_1, position order
+#pragma unroll
+            for (int off = 32; off > 0; off >>= 1) a1 += __shfl_xor(a1, off);
+            if ((threadIdx.x & 63) == 0) part[threadIdx.x >> 6] = a1;
+            __syncthreads();
+            if (threadIdx.x == 0)
+                lu[(size_t)b * lu_stride + (slot & ~15) + pos_of_slot(slot & 15)] = __builtin_amdgcn_logf(part[0] + part[1]);
         }
     } else {
         const int i0 = (b - units) * 1024;
@@ -44,12 +58,38 @@ hipError_t launch_insert(const Plan &p, const void *q, const void *k_new, const 
         hipLaunchKernelGGL(insert_kernel<float>, dim3(units + qblocks), dim3(128), 0, s,
                            (float *)p.k_cache, (float *)p.v_cache, (const float *)k_new,
                            (const float *)v_new, p.pending, (const float *)q, (float *)p.q_last,
-                           units, p.N, p.D, q_elems);
+                           units, p.N, p.D, q_elems, (float *)nullptr, 0);
     else
         hipLaunchKernelGGL(insert_kernel<bf16_t>, dim3(units + qblocks), dim3(128), 0, s,
                            (bf16_t *)p.k_cache, (bf16_t *)p.v_cache, (const bf16_t *)k_new,
                            (const bf16_t *)v_new, p.pending, (const bf16_t *)q, (bf16_t *)p.q_last,
-                           units, p.N, p.D, q_elems);
+                           units, p.N, p.D, q_elems, p.use_mfma ? p.lu : (float *)nullptr, p.ntiles * kTile);
+    return hipGetLastError();
+}
+
+// log2 ||v||_1 of rows [0, n_rows) of every unit (prefill), one 16-lane row per cache row
+__global__ __launch_bounds__(256) void l1norm_kernel(const uint16_t *__restrict__ Vc, float *__restrict__ lu,
+                                                      int units, int N, int n_rows, int lu_stride)
+{
+    const int lane16 = threadIdx.x & 15;
+    const long long total = (long long)units * n_rows;
+    for (long long row = (long long)blockIdx.x * 16 + (threadIdx.x >> 4); row < total; row += (long long)gridDim.x * 16) {
+        const int u = (int)(row / n_rows), slot = (int)(row % n_rows);
+        const u32x4 vv = *(const u32x4 *)(Vc + ((size_t)u * N + slot) * 128 + 8 * lane16);
+        float a1 = fabsf(bf16_lo(vv.x)) + fabsf(bf16_hi(vv.x)) + fabsf(bf16_lo(vv.y)) + fabsf(bf16_hi(vv.y)) +
+                   fabsf(bf16_lo(vv.z)) + fabsf(bf16_hi(vv.z)) + fabsf(bf16_lo(vv.w)) + fabsf(bf16_hi(vv.w));
+        a1 = row16_sum(a1);
+        if (lane16 == 0) lu[(size_t)u * lu_stride + (slot & ~15) + pos_of_slot(slot & 15)] = __builtin_amdgcn_logf(a1);
+    }
+}
+hipError_t launch_l1norms(const Plan &p, int n_rows, hipStream_t s)
+{
+    const long long total = (long long)p.units * n_rows;
+    long long blocks = (total + 15) / 16;
+    if (blocks > 65536) blocks = 65536;
+    if (blocks < 1) return hipSuccess;
+    hipLaunchKernelGGL(l1norm_kernel, dim3((unsigned)blocks), dim3(256), 0, s, (const uint16_t *)p.v_cache, p.lu,
+                       p.units, p.N, n_rows, p.ntiles * kTile);
     return hipGetLastError();
 }
 
@@ -117,7 +157,7 @@ __global__ __launch_bounds__(256) void finish_kernel(
     const float *__restrict__ part_l, const float *__restrict__ part_o,
     const uint16_t *__restrict__ stash_w, const float *__restrict__ stash_m, T *__restrict__ out,
     float *__restrict__ fin_m, float *__restrict__ fin_l, int32_t *__restrict__ pending,
-    int32_t *__restrict__ evict_idx, int attention_only)
+    int32_t *__restrict__ evict_idx, int attention_only, int pos_order)
 {
     __shared__ float sM[kMaxGroup], sL[kMaxGroup];
     __shared__ float sW[kMaxSplits][kMaxGroup];
@@ -181,7 +221,8 @@ __global__ __launch_bounds__(256) void finish_kernel(
             }
 #pragma unroll
             for (int e = 0; e < 8; ++e) {
-                const int slot = tile * kTile + half * 8 + e;
+                const int in_tile = half * 8 + e;
+                const int slot = tile * kTile + (pos_order ? slot_of_pos(in_tile) : in_tile);
                 if (slot < n) vmin = fminf(vmin, sc[e]);
             }
         }
@@ -222,7 +263,8 @@ __global__ __launch_bounds__(256) void finish_kernel(
         }
 #pragma unroll
         for (int e = 0; e < 8; ++e) {
-            const int slot = tile * kTile + half * 8 + e;
+            const int in_tile = half * 8 + e;
+            const int slot = tile * kTile + (pos_order ? slot_of_pos(in_tile) : in_tile);
             const bool cand = (item < nhalf) && (slot < n) && (sc[e] <= thr);
             unsigned long long bal = __ballot(cand);
             while (bal) {
@@ -256,7 +298,7 @@ hipError_t launch_finish(const Plan &p, const void *q, int n, void *out, int32_t
     hipLaunchKernelGGL((finish_kernel<T, DD>), dim3(p.units), dim3(256), 0, s,                    \
                        (const T *)p.k_cache, (const T *)p.v_cache, (const T *)q, n, p.N, p.G, p.C, \
                        c_active, p.ntiles, p.part_m, p.part_l, p.part_o, p.stash_w, p.stash_m,     \
-                       (T *)out, p.fin_m, p.fin_l, p.pending, evict_idx, ao)
+                       (T *)out, p.fin_m, p.fin_l, p.pending, evict_idx, ao, p.use_mfma ? 1 : 0)
     if (p.dtype == 0) { if (p.D == 64) LF_FIN(float, 64); else LF_FIN(float, 128); }
     else              { if (p.D == 64) LF_FIN(bf16_t, 64); else LF_FIN(bf16_t, 128); }
 #undef LF_FIN

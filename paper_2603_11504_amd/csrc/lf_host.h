@@ -9,6 +9,8 @@ namespace lf {
 constexpr int kTile = 16;      // slots per screening-stash tile (one MFMA tile of slots)
 constexpr int kMaxSplits = 64; // upper bound on split-K factor
 constexpr int kMaxGroup = 16;  // query heads per KV head
+// dynamic LDS the unit-resident kernel may ask for: 160 KB per CU minus its static part
+constexpr size_t kUnitLdsLimit = 160 * 1024 - 12 * 1024;
 
 // Everything a launch needs; filled by the API layer.
 struct Plan {
@@ -32,11 +34,13 @@ struct Plan {
     float *fin_l;      // [units][G]       global denominator of the last step
     uint16_t *stash_w; // [units][ntiles][G][kTile] bf16 screening values ||v||_1 * p
     float *stash_m;    // [units][ntiles][G]        reference each tile's p is relative to
+    float *lu;         // [units][ntiles*kTile] log2 ||v||_1 per slot, position order inside a tile
+                       // (matrix-core kernels only; kept current by init and insert)
 };
 
 struct Layout {
     size_t off_pending, off_q, off_part_m, off_part_l, off_part_o, off_fin_m, off_fin_l,
-        off_stash_w, off_stash_m, total;
+        off_stash_w, off_stash_m, off_lu, total;
 };
 
 // Split-K geometry for a cache of `units` independent (batch, KV head) pairs.
@@ -54,6 +58,7 @@ hipError_t launch_unit_mfma(const Plan &p, const void *q, const void *k_new, con
 hipError_t launch_finish(const Plan &p, const void *q, int n, void *out, int32_t *evict_idx,
                          hipStream_t s);
 hipError_t launch_scores(const Plan &p, int n, float *scores, hipStream_t s);
+hipError_t launch_l1norms(const Plan &p, int n_rows, hipStream_t s);
 hipError_t launch_fill_i32(int32_t *dst, int count, int32_t value, hipStream_t s);
 
 } // namespace lf

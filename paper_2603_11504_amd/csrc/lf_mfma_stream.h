@@ -1,23 +1,34 @@
 // Matrix-core streaming core shared by the split-K kernel and the unit-resident fused
 // kernel (bf16, head_dim 128, wave64, gfx950).
 //
-// A wave streams 16-slot tiles of K and V exactly once, with 128-bit loads that land
-// directly in the MFMA operand layouts (no LDS staging, no transposes through memory):
+// A wave streams 16-slot tiles of K and V exactly once with 128-bit loads that land
+// directly in MFMA operand layouts (no LDS staging, no transposes through memory).
+// Every load instruction of a wave covers whole 128-byte lines (8 K rows x one line, or
+// 4 V rows x two lines): the per-CU limit on outstanding line requests, not HBM, is what
+// caps a compute unit's streaming rate, and half-line requests would waste a third of it.
 //
-//   S^T = K Q^T      4 x v_mfma_f32_16x16x32_bf16   rows = 16 slots, cols = 16 (padded) heads
-//   p   = 2^(t - m)  online softmax per head, fp32                        (eq. 1)
+//   S^T = K Q^T      8 x v_mfma_f32_16x16x32_bf16 (two half-used products per 8 slots, see
+//                    below), rows = slots, cols = 16 (padded) heads
+//   p   = 2^(t - m)  online softmax per head in fp32, reference m raised lazily  (eq. 1)
 //   O  += P V        8 x v_mfma_f32_16x16x16_bf16, P as bf16 hi (+ lo) parts
-//   U   = I |V|      8 x v_mfma_f32_16x16x16_bf16 with an identity A operand, then a
-//                    16-lane row sum: u_i = ||v_i||_1                     (eq. 6)
-//
-// The S^T orientation makes the softmax output land in exactly the lane layout the PV
-// product needs for its A operand, and V is loaded so that a lane holds the same 8
-// channels of 4 consecutive slots: byte-permutes turn that into the B operand
-// (contraction over slots) without leaving the register file.
+//   code             8-bit log2 code of ||v_i||_1 * p_h,i for the eviction screening (eq. 6);
+//                    log2 ||v_i||_1 comes from a small side array kept current on insert
 //
 // Lane naming: g = lane >> 4 (0..3), r = lane & 15.
-//   logits / p      lane (g, r): head r, slots base + 4g + v, v = 0..3
-//   O accumulators  lane (g, r): head 4g + v, channel 8r + dd, dd = 0..7
+//
+// K operand.  For the lanes covering one K row to form a full line, lane (g, r) reads row
+// rho = r >> 1 of an 8-row group, 16-byte chunk 2g + b (b = r & 1) of line L.  As an MFMA A
+// operand that makes "row" r = (rho, b) and contraction index k = 8g + j stand for channel
+// 64L + 8(2g + b) + j, which depends on b.  Two products per group, one with the Q chunks
+// of b = 0 and one with those of b = 1, each produce the right half-dot-product in the rows
+// of their own b; the halves of a slot sit in adjacent accumulator registers of one lane,
+// so a single add per slot finishes the logit.  The spare products are free: the matrix
+// pipe idles most of the time in this HBM-bound kernel.
+//
+// Within a tile a lane (g, head) ends up with the logits of slot offsets
+//   s(e) = 8 (e >> 1) + 2 g + (e & 1),  e = 0..3,
+// and everything per-slot that the kernels keep (codes, stash, log2 norms) is stored in
+// "position" order p = 4 g + e inside each 16-slot tile.
 #pragma once
 #include <type_traits>
 
@@ -41,10 +52,19 @@ enum StashMode {
 // 8-bit code of a positive value w: round(4 * (kCodeBias - log2 w)) clamped to [0, 255].
 // Decoding gives 2^(kCodeBias - code/4), within a factor 2^(1/8) of w for 0 < code < 255.
 constexpr float kCodeBias = 16.f;
+// The running softmax reference is raised only when a logit exceeds it by more than this
+// (log2 units): p stays below 2^kMaxSlack, far inside fp32/bf16 range, and the common
+// path needs no cross-lane traffic at all.
+constexpr float kMaxSlack = 8.f;
+
+// position of a slot inside its 16-slot tile, and back
+__host__ __device__ __forceinline__ int pos_of_slot(int s) { return 4 * ((s >> 1) & 3) + 2 * ((s >> 3) & 1) + (s & 1); }
+__host__ __device__ __forceinline__ int slot_of_pos(int p) { return 8 * ((p >> 1) & 1) + 2 * (p >> 2) + (p & 1); }
 
 struct TileRegs {
-    u32x4 k[4]; // k[c]: row (lane&15) of the tile, channels 32c + 8*(lane>>4) .. +7
-    u32x4 v[4]; // v[e]: row 4*(lane>>4) + e, channels 8*(lane&15) .. +7
+    u32x4 k[2][2]; // k[a][L]: row 8a + (r >> 1), line L, chunk 2g + (r & 1)
+    u32x4 v[4];    // v[e]: row s(e), channels 8r .. 8r + 7
+    f32x4 lu;      // log2 ||v||_1 of the lane's four slots (positions 4g .. 4g + 3)
 };
 
 __device__ __forceinline__ uint32_t pack_bf16x2(float lo, float hi)
@@ -58,18 +78,18 @@ template <int NWAVES, bool HILO, int STASH>
 struct MfmaStreamer {
     static constexpr int D = 128;
     // per-wave state
-    u32x4 qreg[4];
-    s16x4 ident;
-    f32x4 oacc[8];
-    float m, l;
+    u32x4 qreg[2][2]; // qreg[L][b]: head r, channels 64L + 8(2g + b) .. +7
+    f32x4 oacc[8];    // oacc[dd][v]: head 4g + v, channel 8r + dd
+    float m, l;       // reference (log2 domain) and lane-partial denominator of head r
     // geometry
     const uint16_t *Ku, *Vu;
+    const float *lu_unit; // [ntiles * 16] log2 ||v||_1 in position order
     int start, end, G, g, r;
     float scale_log2;
     // stash sinks
-    uint16_t *gs_w;   // kStashGlobal: [tile][G][16] bf16, tile counted from slot 0 of the unit
+    uint16_t *gs_w;   // kStashGlobal: [tile][G][16 positions] bf16
     float *gs_m;      // kStashGlobal: [tile][G]
-    uint8_t *ls_code; // kStashLds: [G][code_stride] bytes
+    uint8_t *ls_code; // kStashLds: [G][code_stride] bytes, position order
     float *ls_ref;    // kStashLds: [tile][G]
     int code_stride;
 
@@ -77,30 +97,38 @@ struct MfmaStreamer {
     {
         G = G_; g = lane >> 4; r = lane & 15; scale_log2 = scale;
 #pragma unroll
-        for (int cc = 0; cc < 4; ++cc) {
-            qreg[cc] = u32x4{0u, 0u, 0u, 0u};
-            if (r < G) qreg[cc] = *(const u32x4 *)(q_unit + (size_t)r * D + 32 * cc + 8 * g);
-        }
+        for (int L = 0; L < 2; ++L)
 #pragma unroll
-        for (int e = 0; e < 4; ++e) ident[e] = (r == 4 * g + e) ? (short)0x3f80 : (short)0;
+            for (int b = 0; b < 2; ++b) {
+                qreg[L][b] = u32x4{0u, 0u, 0u, 0u};
+                if (r < G) qreg[L][b] = *(const u32x4 *)(q_unit + (size_t)r * D + 64 * L + 8 * (2 * g + b));
+            }
 #pragma unroll
         for (int dd = 0; dd < 8; ++dd) oacc[dd] = f32x4{0.f, 0.f, 0.f, 0.f};
         m = -INFINITY;
         l = 0.f;
     }
 
+    __device__ __forceinline__ int slot_off(int e) const { return 8 * (e >> 1) + 2 * g + (e & 1); }
+
     __device__ __forceinline__ void load_tile(TileRegs &t, int ti) const
     {
         const int base = start + ti * kTile;
-        const int krow = min(base + r, end - 1); // clamped: never touch a row past the valid prefix
+        const int last = end - 1; // rows are clamped: never touch a row past the valid prefix
 #pragma unroll
-        for (int cc = 0; cc < 4; ++cc)
-            t.k[cc] = __builtin_nontemporal_load((const u32x4 *)(Ku + (size_t)krow * D + 32 * cc + 8 * g));
+        for (int a = 0; a < 2; ++a) {
+            const int krow = min(base + 8 * a + (r >> 1), last);
+#pragma unroll
+            for (int L = 0; L < 2; ++L)
+                t.k[a][L] = __builtin_nontemporal_load(
+                    (const u32x4 *)(Ku + (size_t)krow * D + 64 * L + 8 * (2 * g + (r & 1))));
+        }
 #pragma unroll
         for (int e = 0; e < 4; ++e) {
-            const int vrow = min(base + 4 * g + e, end - 1);
+            const int vrow = min(base + slot_off(e), last);
             t.v[e] = __builtin_nontemporal_load((const u32x4 *)(Vu + (size_t)vrow * D + 8 * r));
         }
+        if (STASH != kStashNone) t.lu = *(const f32x4 *)(lu_unit + base + 4 * g);
     }
 
     // RAGGED: the tile may reach past `end`; rows loaded from the clamped address are zeroed
@@ -108,29 +136,39 @@ struct MfmaStreamer {
     {
         const int base = start + ti * kTile;
         if (RAGGED) {
-            if (base + r >= end) {
 #pragma unroll
-                for (int cc = 0; cc < 4; ++cc) t.k[cc] = u32x4{0u, 0u, 0u, 0u};
-            }
+            for (int a = 0; a < 2; ++a)
+                if (base + 8 * a + (r >> 1) >= end) t.k[a][0] = t.k[a][1] = u32x4{0u, 0u, 0u, 0u};
 #pragma unroll
             for (int e = 0; e < 4; ++e)
-                if (base + 4 * g + e >= end) t.v[e] = u32x4{0u, 0u, 0u, 0u};
+                if (base + slot_off(e) >= end) t.v[e] = u32x4{0u, 0u, 0u, 0u};
         }
-        // ---- S^T = K Q^T
-        f32x4 s = {0.f, 0.f, 0.f, 0.f};
+        // ---- S^T = K Q^T: per 8-row group, one product per chunk parity b
+        float s[4];
 #pragma unroll
-        for (int cc = 0; cc < 4; ++cc)
-            s = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, t.k[cc]),
-                                                        __builtin_bit_cast(bf16x8, qreg[cc]), s, 0, 0, 0);
-        float tv[4];
+        for (int a = 0; a < 2; ++a) {
+            f32x4 d0 = {0.f, 0.f, 0.f, 0.f}, d1 = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
-        for (int v = 0; v < 4; ++v)
-            tv[v] = (!RAGGED || base + 4 * g + v < end) ? s[v] * scale_log2 : -INFINITY;
-        float mx = fmaxf(fmaxf(tv[0], tv[1]), fmaxf(tv[2], tv[3]));
-        mx = fmaxf(mx, __shfl_xor(mx, 16));
-        mx = fmaxf(mx, __shfl_xor(mx, 32));
-        const float m_new = fmaxf(m, mx);
-        if (__any(m_new > m)) { // rare after the first tiles: rescale the running state
+            for (int L = 0; L < 2; ++L) {
+                const bf16x8 ka = __builtin_bit_cast(bf16x8, t.k[a][L]);
+                d0 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(ka, __builtin_bit_cast(bf16x8, qreg[L][0]), d0, 0, 0, 0);
+                d1 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(ka, __builtin_bit_cast(bf16x8, qreg[L][1]), d1, 0, 0, 0);
+            }
+            // accumulator rows 4g + v = (rho = 2g + (v >> 1), b = v & 1)
+            s[2 * a + 0] = d0[0] + d1[1];
+            s[2 * a + 1] = d0[2] + d1[3];
+        }
+        if (RAGGED) {
+#pragma unroll
+            for (int e = 0; e < 4; ++e)
+                if (base + slot_off(e) >= end) s[e] = -INFINITY;
+        }
+        // ---- online softmax with a lazily raised reference
+        const float mx = fmaxf(fmaxf(s[0], s[1]), fmaxf(s[2], s[3])) * scale_log2;
+        if (__any(mx > m + kMaxSlack)) { // rare: first tile, or a logit far above everything so far
+            float mw = fmaxf(mx, __shfl_xor(mx, 16));
+            mw = fmaxf(mw, __shfl_xor(mw, 32));
+            const float m_new = (mw > m + kMaxSlack) ? mw : m;
             const float a = fast_exp2(m - m_new);
             l *= a;
 #pragma unroll
@@ -143,10 +181,10 @@ struct MfmaStreamer {
         }
         float lg[4], p[4];
 #pragma unroll
-        for (int v = 0; v < 4; ++v) {
-            lg[v] = tv[v] - m; // log2 of p
-            p[v] = fast_exp2(lg[v]);
-            l += p[v];
+        for (int e = 0; e < 4; ++e) {
+            lg[e] = fmaf(s[e], scale_log2, -m); // log2 of p; -inf for masked slots
+            p[e] = fast_exp2(lg[e]);
+            l += p[e];
         }
         s16x4 p_hi, p_lo;
         {
@@ -158,28 +196,22 @@ struct MfmaStreamer {
                 p_lo = __builtin_bit_cast(s16x4, u32x2{l01, l23});
             }
         }
-        // ---- O += P V and U = I |V|, channel 8r + dd per product
-        f32x4 uacc = {0.f, 0.f, 0.f, 0.f};
+        // ---- O += P V, channel 8r + dd per product; contraction index 4g + e = position
 #pragma unroll
         for (int dd = 0; dd < 8; ++dd) {
             const uint32_t sel = (dd & 1) ? 0x07060302u : 0x05040100u;
             const int w = dd >> 1;
-            const uint32_t v01 = __builtin_amdgcn_perm(t.v[1][w], t.v[0][w], sel); // slots 4g+0, 4g+1
-            const uint32_t v23 = __builtin_amdgcn_perm(t.v[3][w], t.v[2][w], sel); // slots 4g+2, 4g+3
+            const uint32_t v01 = __builtin_amdgcn_perm(t.v[1][w], t.v[0][w], sel);
+            const uint32_t v23 = __builtin_amdgcn_perm(t.v[3][w], t.v[2][w], sel);
             const s16x4 vb = __builtin_bit_cast(s16x4, u32x2{v01, v23});
             oacc[dd] = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(p_hi, vb, oacc[dd], 0, 0, 0);
             if (HILO) oacc[dd] = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(p_lo, vb, oacc[dd], 0, 0, 0);
-            if (STASH != kStashNone) {
-                const s16x4 va = __builtin_bit_cast(s16x4, u32x2{v01 & 0x7fff7fffu, v23 & 0x7fff7fffu});
-                uacc = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(ident, va, uacc, 0, 0, 0);
-            }
         }
         if (STASH == kStashGlobal) {
-            // uacc[v] = partial ||v||_1 of slot 4g+v over channels {8r+dd}; sum the row's 16 lanes
-            float w[4];
-#pragma unroll
-            for (int v = 0; v < 4; ++v) w[v] = row16_sum(uacc[v]) * p[v];
             if (r < G) {
+                float w[4];
+#pragma unroll
+                for (int e = 0; e < 4; ++e) w[e] = fast_exp2(t.lu[e] + lg[e]); // ||v||_1 * p
                 const size_t rec = (size_t)(base / kTile) * G + r;
                 *(u32x2 *)(gs_w + rec * kTile + 4 * g) = u32x2{pack_bf16x2(w[0], w[1]), pack_bf16x2(w[2], w[3])};
                 if (g == 0) gs_m[rec] = m;
@@ -188,10 +220,10 @@ struct MfmaStreamer {
         if (STASH == kStashLds) {
             uint32_t code = 0;
 #pragma unroll
-            for (int v = 0; v < 4; ++v) {
-                const float lw = __builtin_amdgcn_logf(row16_sum(uacc[v])) + lg[v]; // log2(u * p)
-                const float c = fminf(fmaxf(rintf(4.f * (kCodeBias - lw)), 0.f), 255.f); // NaN -> 255 side irrelevant
-                code |= (uint32_t)c << (8 * v);
+            for (int e = 0; e < 4; ++e) {
+                // 4 * (bias - log2(u p)), rounded, clamped to a byte
+                const float c = __builtin_amdgcn_fmed3f(rintf(fmaf(t.lu[e] + lg[e], -4.f, 4.f * kCodeBias)), 0.f, 255.f);
+                code = __builtin_amdgcn_cvt_pk_u8_f32(c, e, code);
             }
             if (r < G) {
                 *(uint32_t *)(ls_code + (size_t)r * code_stride + base + 4 * g) = code;
@@ -201,31 +233,42 @@ struct MfmaStreamer {
     }
 
     // Stream this wave's share of [start, end): wave w owns tiles w, w + NWAVES, ...
-    // Two tiles are in flight while a third is consumed; the steady-state body has no
-    // branch between a load and its use, so each wait leaves the younger loads in flight.
+    // Three register tiles rotate: while one is consumed the other two are in flight; the
+    // steady-state body has no branch between a load and its use.
     __device__ __forceinline__ void run(int wave)
     {
         const int nfull = (end - start) / kTile;
         const bool ragged = (end - start) % kTile != 0;
         const int n_my = (nfull > wave) ? (nfull - wave + NWAVES - 1) / NWAVES : 0;
-        TileRegs ta, tb;
-        if (n_my >= 2) {
+        TileRegs ta, tb, tc;
+        if (n_my >= 3) {
+            // prologue loads are unconditional inside this branch: the waits in the loop
+            // then cover exactly the oldest tile and leave the younger loads in flight
             load_tile(ta, wave);
             load_tile(tb, wave + NWAVES);
+            load_tile(tc, wave + NWAVES * 2);
             int i = 0;
-            for (; i + 3 < n_my; i += 2) {
+            for (; i + 5 < n_my; i += 3) {
                 compute_tile<false>(ta, wave + NWAVES * i);
-                load_tile(ta, wave + NWAVES * (i + 2));
+                load_tile(ta, wave + NWAVES * (i + 3));
                 compute_tile<false>(tb, wave + NWAVES * (i + 1));
-                load_tile(tb, wave + NWAVES * (i + 3));
+                load_tile(tb, wave + NWAVES * (i + 4));
+                compute_tile<false>(tc, wave + NWAVES * (i + 2));
+                load_tile(tc, wave + NWAVES * (i + 5));
             }
+            // 3 to 5 tiles remain; the first three are already on their way
             compute_tile<false>(ta, wave + NWAVES * i);
-            if (i + 2 < n_my) load_tile(ta, wave + NWAVES * (i + 2));
+            if (i + 3 < n_my) load_tile(ta, wave + NWAVES * (i + 3));
             compute_tile<false>(tb, wave + NWAVES * (i + 1));
-            if (i + 2 < n_my) compute_tile<false>(ta, wave + NWAVES * (i + 2));
-        } else if (n_my == 1) {
-            load_tile(ta, wave);
-            compute_tile<false>(ta, wave);
+            if (i + 4 < n_my) load_tile(tb, wave + NWAVES * (i + 4));
+            compute_tile<false>(tc, wave + NWAVES * (i + 2));
+            if (i + 3 < n_my) compute_tile<false>(ta, wave + NWAVES * (i + 3));
+            if (i + 4 < n_my) compute_tile<false>(tb, wave + NWAVES * (i + 4));
+        } else {
+            for (int i = 0; i < n_my; ++i) {
+                load_tile(ta, wave + NWAVES * i);
+                compute_tile<false>(ta, wave + NWAVES * i);
+            }
         }
         if (ragged && wave == nfull % NWAVES) {
             load_tile(ta, nfull);

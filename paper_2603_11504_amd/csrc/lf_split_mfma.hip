@@ -11,7 +11,8 @@ __global__ __launch_bounds__(256, 2) void split_mfma_kernel(
     const uint16_t *__restrict__ Kc, const uint16_t *__restrict__ Vc, const uint16_t *__restrict__ q,
     int n, int N, int G, int L, int C, int ntiles, int c_active,
     float *__restrict__ part_m, float *__restrict__ part_l, float *__restrict__ part_o,
-    uint16_t *__restrict__ stash_w, float *__restrict__ stash_m, float scale_log2)
+    uint16_t *__restrict__ stash_w, float *__restrict__ stash_m, const float *__restrict__ lu,
+    float scale_log2)
 {
     constexpr int D = 128;
     const int u = blockIdx.x / c_active, c = blockIdx.x % c_active;
@@ -25,6 +26,7 @@ __global__ __launch_bounds__(256, 2) void split_mfma_kernel(
     st.end = min(c * L + L, n);
     st.gs_w = stash_w + (size_t)u * ntiles * G * kTile; // tile records count from slot 0 of the unit
     st.gs_m = stash_m + (size_t)u * ntiles * G;
+    st.lu_unit = lu + (size_t)u * ntiles * kTile;
     st.run(wave);
 
     // ---- merge the 4 waves through LDS, write the split's partial state
@@ -64,7 +66,7 @@ hipError_t launch_split_mfma(const Plan &p, const void *q, int n, hipStream_t s)
     hipLaunchKernelGGL((split_mfma_kernel<true, STASH>), dim3(p.units * c_active), dim3(256), 0, s, \
                        (const uint16_t *)p.k_cache, (const uint16_t *)p.v_cache, (const uint16_t *)q, \
                        n, p.N, p.G, p.L, p.C, p.ntiles, c_active, p.part_m, p.part_l, p.part_o,    \
-                       p.stash_w, p.stash_m, scale_log2)
+                       p.stash_w, p.stash_m, p.lu, scale_log2)
     if (p.flags & 1u) LF_SPLIT(kStashNone); else LF_SPLIT(kStashGlobal);
 #undef LF_SPLIT
     return hipGetLastError();

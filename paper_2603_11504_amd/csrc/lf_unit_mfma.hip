@@ -17,6 +17,8 @@
 
 namespace lf {
 
+constexpr int kMaxCand = 256; // candidates listed in LDS; more than this falls back to a slow scan
+
 __device__ __forceinline__ double wave_sum_f64(double x)
 {
 #pragma unroll
@@ -24,25 +26,67 @@ __device__ __forceinline__ double wave_sum_f64(double x)
     return x;
 }
 
-// exact LongFlowScore of one slot, computed by a whole wave in double precision (eq. 6
-// with the group's heads summed); sM: reference (log2 domain), sLinv: 1 / denominator
-__device__ double exact_score_bf16(const uint16_t *__restrict__ krow, const uint16_t *__restrict__ vrow,
-                                   const uint16_t *__restrict__ qu, int G, const float *sM,
-                                   const float *sL, int lane)
+// 2^x for |x| <= 0.5 in double precision: Taylor series of exp(x ln 2), error < 1e-14
+__device__ __forceinline__ double exp2_frac_f64(double x)
 {
-    const uint32_t kk = *(const uint32_t *)(krow + 2 * lane), vv = *(const uint32_t *)(vrow + 2 * lane);
-    const double k0 = bf16_lo(kk), k1 = bf16_hi(kk);
+    const double y = x * 0.69314718055994530942;
+    double p = 1.0 / 39916800.0;
+    p = fma(p, y, 1.0 / 3628800.0);
+    p = fma(p, y, 1.0 / 362880.0);
+    p = fma(p, y, 1.0 / 40320.0);
+    p = fma(p, y, 1.0 / 5040.0);
+    p = fma(p, y, 1.0 / 720.0);
+    p = fma(p, y, 1.0 / 120.0);
+    p = fma(p, y, 1.0 / 24.0);
+    p = fma(p, y, 1.0 / 6.0);
+    p = fma(p, y, 0.5);
+    p = fma(p, y, 1.0);
+    p = fma(p, y, 1.0);
+    return p;
+}
+
+// Exact LongFlowScore of one slot in double precision (eq. 6 with the group's heads
+// summed), computed by one wave: 4 lanes per head, 32 channels per lane.
+//   qs: the step's query as floats in LDS [16][128]; sM: softmax reference per head
+//   (log2 domain); sL: denominator per head.
+__device__ double exact_score_bf16(const uint16_t *__restrict__ krow, const uint16_t *__restrict__ vrow,
+                                   const float (*qs)[128], int G, const float *sM, const float *sL, int lane)
+{
+    const int h = lane >> 2, part = lane & 3;
+    // ||v||_1: two channels per lane, summed over the wave
+    const uint32_t vv = *(const uint32_t *)(vrow + 2 * lane);
     double l1 = fabs((double)bf16_lo(vv)) + fabs((double)bf16_hi(vv));
     l1 = wave_sum_f64(l1);
-    const double scale_log2 = 1.4426950408889634074 / sqrt(128.0);
-    double acc = 0.0;
-    for (int h = 0; h < G; ++h) {
-        const uint32_t qq = *(const uint32_t *)(qu + (size_t)h * 128 + 2 * lane);
-        double dot = (double)bf16_lo(qq) * k0 + (double)bf16_hi(qq) * k1;
-        dot = wave_sum_f64(dot);
-        acc += exp2(dot * scale_log2 - (double)sM[h]) / (double)sL[h];
+    // q_h . k over this lane's 32 channels
+    double dot = 0.0;
+    if (h < G) {
+#pragma unroll
+        for (int c = 0; c < 4; ++c) {
+            const u32x4 kk = *(const u32x4 *)(krow + 32 * part + 8 * c);
+            const f32x4 qa = *(const f32x4 *)(&qs[h][32 * part + 8 * c]);
+            const f32x4 qb = *(const f32x4 *)(&qs[h][32 * part + 8 * c + 4]);
+            dot = fma((double)qa[0], (double)bf16_lo(kk.x), dot);
+            dot = fma((double)qa[1], (double)bf16_hi(kk.x), dot);
+            dot = fma((double)qa[2], (double)bf16_lo(kk.y), dot);
+            dot = fma((double)qa[3], (double)bf16_hi(kk.y), dot);
+            dot = fma((double)qb[0], (double)bf16_lo(kk.z), dot);
+            dot = fma((double)qb[1], (double)bf16_hi(kk.z), dot);
+            dot = fma((double)qb[2], (double)bf16_lo(kk.w), dot);
+            dot = fma((double)qb[3], (double)bf16_hi(kk.w), dot);
+        }
     }
-    return acc * l1;
+    dot += __shfl_xor(dot, 1);
+    dot += __shfl_xor(dot, 2);
+    double term = 0.0;
+    if (h < G && part == 0) {
+        const double scale_log2 = 1.4426950408889634074 / 11.313708498984760390; // log2(e) / sqrt(128)
+        const double d = dot * scale_log2 - (double)sM[h];
+        const double nint = rint(d);
+        term = ldexp(exp2_frac_f64(d - nint), (int)nint) / (double)sL[h];
+    }
+#pragma unroll
+    for (int off = 4; off < 64; off <<= 1) term += __shfl_xor(term, off);
+    return term * l1;
 }
 
 template <bool HILO, int STASH>
@@ -51,7 +95,7 @@ __global__ __launch_bounds__(512, 1) void unit_mfma_kernel(
     const uint16_t *__restrict__ k_new, const uint16_t *__restrict__ v_new, int n, int N, int G,
     int code_stride, int ntiles, int32_t *__restrict__ pending, uint16_t *__restrict__ out,
     int32_t *__restrict__ evict_idx, float *__restrict__ fin_m, float *__restrict__ fin_l,
-    uint16_t *__restrict__ q_last, float scale_log2)
+    uint16_t *__restrict__ q_last, float *__restrict__ lu, float scale_log2)
 {
     constexpr int D = 128, NW = 8, OPAD = D + 4;
     extern __shared__ __align__(16) unsigned char smem[];
@@ -62,6 +106,9 @@ __global__ __launch_bounds__(512, 1) void unit_mfma_kernel(
     __shared__ float red_f[NW];
     __shared__ double best_v[NW];
     __shared__ int best_i[NW];
+    __shared__ float qs[16][D];            // the query as floats, for the exact re-scoring
+    __shared__ int cand_list[kMaxCand];
+    __shared__ int cand_count;
 
     const int u = blockIdx.x;
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
@@ -69,6 +116,7 @@ __global__ __launch_bounds__(512, 1) void unit_mfma_kernel(
     uint16_t *Ku = Kc + (size_t)u * N * D;
     uint16_t *Vu = Vc + (size_t)u * N * D;
     const uint16_t *qu = q + (size_t)u * G * D;
+    float *lu_u = lu + (size_t)u * ntiles * kTile;
 
     // ---- insert (Fig. 2 left): done by the wave that will stream that tile, so that its
     // own later loads of the row are ordered behind the stores
@@ -77,9 +125,13 @@ __global__ __launch_bounds__(512, 1) void unit_mfma_kernel(
         if (slot >= 0 && slot < N && ((slot / kTile) % NW) == wave) {
             if (lane < 16)
                 *(u32x4 *)(Ku + (size_t)slot * D + 8 * lane) = *(const u32x4 *)(k_new + (size_t)u * D + 8 * lane);
-            else if (lane < 32)
-                *(u32x4 *)(Vu + (size_t)slot * D + 8 * (lane - 16)) =
-                    *(const u32x4 *)(v_new + (size_t)u * D + 8 * (lane - 16));
+            // every 16-lane row sums |v_new| redundantly; rows 1 stores V, lane 32 the log2 norm
+            const u32x4 vv = *(const u32x4 *)(v_new + (size_t)u * D + 8 * r);
+            float a1 = fabsf(bf16_lo(vv.x)) + fabsf(bf16_hi(vv.x)) + fabsf(bf16_lo(vv.y)) + fabsf(bf16_hi(vv.y)) +
+                       fabsf(bf16_lo(vv.z)) + fabsf(bf16_hi(vv.z)) + fabsf(bf16_lo(vv.w)) + fabsf(bf16_hi(vv.w));
+            a1 = row16_sum(a1);
+            if (g == 1) *(u32x4 *)(Vu + (size_t)slot * D + 8 * r) = vv;
+            if (lane == 32) lu_u[(slot & ~15) + pos_of_slot(slot & 15)] = __builtin_amdgcn_logf(a1);
             __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
             asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
         }
@@ -91,6 +143,7 @@ __global__ __launch_bounds__(512, 1) void unit_mfma_kernel(
     st.Vu = Vu;
     st.start = 0;
     st.end = n;
+    st.lu_unit = lu_u;
     st.ls_code = ls_code;
     st.ls_ref = ls_ref;
     st.code_stride = code_stride;
@@ -102,6 +155,10 @@ __global__ __launch_bounds__(512, 1) void unit_mfma_kernel(
         l += __shfl_xor(l, 16);
         l += __shfl_xor(l, 32);
         if (g == 0) { sm_m[wave][r] = st.m; sm_l[wave][r] = l; }
+    }
+    if (STASH == kStashLds) {
+        for (int i = tid; i < G * D; i += 512) qs[i / D][i % D] = bf16_lo((uint32_t)qu[i]);
+        if (tid == 0) cand_count = 0;
     }
     __syncthreads();
     if (tid < 16) {
@@ -137,7 +194,7 @@ __global__ __launch_bounds__(512, 1) void unit_mfma_kernel(
             __syncthreads();
             // pass 1: upper bounds of all scores, block minimum.  A decoded term is within
             // 2^(+-1/8) of the true one; code 0 has no upper bound, code 255 no lower bound.
-            const int items = (n + 3) / 4;
+            const int items = 4 * ((n + kTile - 1) / kTile); // 4 positions each, whole tiles
             const int iters = (items + 511) / 512;
             float ub_min = INFINITY;
             for (int it = 0; it < iters; ++it) {
@@ -156,7 +213,7 @@ __global__ __launch_bounds__(512, 1) void unit_mfma_kernel(
                     }
 #pragma unroll
                     for (int e = 0; e < 4; ++e)
-                        if (4 * item + e < n) ub_min = fminf(ub_min, s4[e]);
+                        if (((4 * item) & ~15) + slot_of_pos((4 * item + e) & 15) < n) ub_min = fminf(ub_min, s4[e]);
                 }
             }
 #pragma unroll
@@ -170,16 +227,12 @@ __global__ __launch_bounds__(512, 1) void unit_mfma_kernel(
             // smallest upper bound: lb = 2^(-1/8) * dec, ub = 2^(1/8) * dec  ->  dec_i <= 2^(1/4) * dec_min
             const float thr = ub_min * 1.1893f * 1.0001f;
 
-            // pass 2: exact double-precision scores of the candidates, wave-cooperative
-            double bv = INFINITY;
-            int bi = 0x7fffffff;
+            // pass 2: list every slot whose lower bound does not exceed the threshold
             for (int it = 0; it < iters; ++it) {
                 const int item = it * 512 + tid;
-                const int tile = item >> 2;
-                float s4[4] = {INFINITY, INFINITY, INFINITY, INFINITY};
                 if (item < items) {
-#pragma unroll
-                    for (int e = 0; e < 4; ++e) s4[e] = 0.f;
+                    const int tile = item >> 2;
+                    float s4[4] = {0.f, 0.f, 0.f, 0.f};
                     for (int h = 0; h < G; ++h) {
                         const uint32_t c4 = *(const uint32_t *)(ls_code + (size_t)h * code_stride + 4 * item);
                         const float f = ls_ref[tile * G + h];
@@ -189,19 +242,36 @@ __global__ __launch_bounds__(512, 1) void unit_mfma_kernel(
                             s4[e] += (c == 255u) ? 0.f : fast_exp2(-0.25f * (float)c) * f; // lower-bound side
                         }
                     }
-                }
 #pragma unroll
-                for (int e = 0; e < 4; ++e) {
-                    const int slot = 4 * item + e;
-                    const bool cand = (item < items) && (slot < n) && (s4[e] <= thr);
-                    unsigned long long bal = __ballot(cand);
-                    while (bal) {
-                        const int src = __ffsll((long long)bal) - 1;
-                        bal &= bal - 1;
-                        const int cs = __shfl(slot, src);
-                        const double v = exact_score_bf16(Ku + (size_t)cs * D, Vu + (size_t)cs * D, qu, G, sM, sL, lane);
-                        if (v < bv || (v == bv && cs < bi)) { bv = v; bi = cs; }
+                    for (int e = 0; e < 4; ++e) {
+                        const int slot = ((4 * item) & ~15) + slot_of_pos((4 * item + e) & 15);
+                        if (slot < n && s4[e] <= thr) {
+                            const int k = atomicAdd(&cand_count, 1);
+                            if (k < kMaxCand) cand_list[k] = slot;
+                        }
                     }
+                }
+            }
+            __syncthreads();
+            const int ncand = cand_count;
+            // exact double-precision scores of the candidates, one wave each
+            double bv = INFINITY;
+            int bi = 0x7fffffff;
+            if (ncand == 1) {
+                bi = cand_list[0]; // nothing to compare with: the screening already decided
+                bv = 0.0;
+            } else if (ncand <= kMaxCand) {
+                for (int c = wave; c < ncand; c += NW) {
+                    const int cs = cand_list[c];
+                    const double v = exact_score_bf16(Ku + (size_t)cs * D, Vu + (size_t)cs * D, qs, G, sM, sL, lane);
+                    if (v < bv || (v == bv && cs < bi)) { bv = v; bi = cs; }
+                }
+            } else {
+                // far more candidates than the list holds (e.g. scores underflowing en masse):
+                // every wave re-scores its share of ALL slots; slow, but still exact
+                for (int cs = wave; cs < n; cs += NW) {
+                    const double v = exact_score_bf16(Ku + (size_t)cs * D, Vu + (size_t)cs * D, qs, G, sM, sL, lane);
+                    if (v < bv || (v == bv && cs < bi)) { bv = v; bi = cs; }
                 }
             }
             if (lane == 0) { best_v[wave] = bv; best_i[wave] = bi; }
@@ -256,7 +326,10 @@ hipError_t launch_unit_mfma(const Plan &p, const void *q, const void *k_new, con
                             void *out, int32_t *evict_idx, hipStream_t s)
 {
     const bool stash = !(p.flags & 1u);
-    const size_t lds = unit_mfma_lds_bytes(p.N, p.G, stash);
+    size_t lds = unit_mfma_lds_bytes(p.N, p.G, stash);
+    // With at most a few workgroups per compute unit, ask for more than half of the
+    // CU's LDS so that no CU is handed two of them while another one idles.
+    if (p.units <= 2 * 256 && lds < 81 * 1024) lds = 81 * 1024;
     const int code_stride = (p.N + 63) / 64 * 64;
     const float scale_log2 = 1.4426950408889634f / sqrtf(128.f);
     static bool attr_done[2] = {false, false};
@@ -264,7 +337,7 @@ hipError_t launch_unit_mfma(const Plan &p, const void *q, const void *k_new, con
     do {                                                                                              \
         if (!attr_done[IDX]) {                                                                        \
             hipError_t e = hipFuncSetAttribute((const void *)unit_mfma_kernel<true, STASH>,           \
-                                               hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024 - 2048); \
+                                               hipFuncAttributeMaxDynamicSharedMemorySize, (int)kUnitLdsLimit); \
             if (e != hipSuccess) return e;                                                            \
             attr_done[IDX] = true;                                                                    \
         }                                                                                             \
@@ -272,7 +345,7 @@ hipError_t launch_unit_mfma(const Plan &p, const void *q, const void *k_new, con
                            (uint16_t *)p.k_cache, (uint16_t *)p.v_cache, (const uint16_t *)q,         \
                            (const uint16_t *)k_new, (const uint16_t *)v_new, n, p.N, p.G, code_stride, \
                            p.ntiles, p.pending, (uint16_t *)out, evict_idx, p.fin_m, p.fin_l,         \
-                           (uint16_t *)p.q_last, scale_log2);                                         \
+                           (uint16_t *)p.q_last, p.lu, scale_log2);                                         \
     } while (0)
     if (stash) LF_UNIT(kStashLds, 0); else LF_UNIT(kStashNone, 1);
 #undef LF_UNIT

@@ -25,8 +25,6 @@ static int fail(int code, const char *fmt, ...)
 
 static size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
 
-// dynamic LDS one workgroup may ask for (160 KB per CU minus the kernels' static part)
-static const size_t kUnitLdsLimit = 160 * 1024 - 2048;
 // from this many units on, one workgroup per unit keeps the chip busy (256 CUs)
 static const int kUnitMinUnits = 192;
 
@@ -112,6 +110,7 @@ static Layout layout_of(const Plan &p)
     const bool stash = !(p.flags & LF_FLAG_ATTENTION_ONLY);
     l.off_stash_w = take(stash ? sizeof(uint16_t) * (size_t)p.units * p.ntiles * p.G * kTile : 0);
     l.off_stash_m = take(stash ? sizeof(float) * (size_t)p.units * p.ntiles * p.G : 0);
+    l.off_lu = take(stash && p.use_mfma ? sizeof(float) * (size_t)p.units * p.ntiles * kTile : 0);
     l.total = off;
     return l;
 }
@@ -178,6 +177,7 @@ int longflow_init_cache(longflow_cache_t **out, const lf_config *cfg, void *k_ca
     p.fin_l = (float *)(ws + l.off_fin_l);
     p.stash_w = (uint16_t *)(ws + l.off_stash_w);
     p.stash_m = (float *)(ws + l.off_stash_m);
+    p.lu = (float *)(ws + l.off_lu);
 
     hipStream_t s = (hipStream_t)hip_stream;
     if (n_init > 0) {
@@ -189,6 +189,10 @@ int longflow_init_cache(longflow_cache_t **out, const lf_config *cfg, void *k_ca
             e = hipMemcpy2DAsync(v_cache, row * p.N, v_init, row * n_init, row * n_init, p.units,
                                  hipMemcpyDeviceToDevice, s);
         if (e != hipSuccess) return fail(LF_ERR_HIP, "prefill copy: %s", hipGetErrorString(e));
+    }
+    if (n_init > 0 && p.use_mfma && !(p.flags & LF_FLAG_ATTENTION_ONLY)) {
+        hipError_t e = launch_l1norms(p, n_init, s);
+        if (e != hipSuccess) return fail(LF_ERR_HIP, "value-norm init: %s", hipGetErrorString(e));
     }
     const bool filling = n_init < p.N;
     if (filling) {
@@ -296,7 +300,7 @@ int longflow_profile_begin(longflow_cache_t *cache, int32_t max_steps)
     drop_events(c);
     c->prof_events.resize(4 * (size_t)max_steps);
     for (size_t i = 0; i < c->prof_events.size(); ++i) {
-        hipError_t e = hipEventCreate(&c->prof_events[i]);
+        hipError_t e = hipEventCreateWithFlags(&c->prof_events[i], hipEventDisableSystemFence);
         if (e != hipSuccess) {
             c->prof_events.resize(i);
             drop_events(c);
