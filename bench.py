@@ -35,7 +35,8 @@ def parse():
     ap.add_argument("--split", action="store_true", help="force the split-K (3-launch) path")
     ap.add_argument("--unit", action="store_true", help="force the one-workgroup-per-unit fused path")
     ap.add_argument("--no-cpu-baseline", action="store_true")
-    ap.add_argument("--pool", type=int, default=4, help="distinct input steps cycled through")
+    ap.add_argument("--pool", type=int, default=0,
+                    help="distinct input steps cycled through (0 = one per executed step, no repeats)")
     return ap.parse_args()
 
 
@@ -100,19 +101,22 @@ def main():
         caches.append(lf.LongFlowCache(wl.batch, wl.q_heads, wl.kv_heads, wl.head_dim, wl.budget, dtype=dt,
                                        flags=flags, device=dev, k_init=k0, v_init=v0))
         del k0, v0
-    pool = [[W.device_step(wl, t, dev, layer) for layer in range(wl.layers)] for t in range(a.pool)]
+    # empty-start workloads fill first so that the timed steps are evicting steps
+    fill = wl.budget - wl.n_init - 1
+    warm = max(a.warmup, 1) + max(fill, 0)
+    # every executed step gets its own q/k/v (repeating inputs would plant bit-identical
+    # rows in the cache, i.e. exact score ties that the real workload does not have)
+    npool = a.pool if a.pool > 0 else warm + 2 * steps
+    pool = [[W.device_step(wl, t, dev, layer) for layer in range(wl.layers)] for t in range(npool)]
     torch.cuda.synchronize()
 
     def run(nsteps, t0=0):
         for t in range(t0, t0 + nsteps):
-            inputs = pool[t % a.pool]
+            inputs = pool[t % npool]
             for layer, c in enumerate(caches):
                 q, k, v = inputs[layer]
                 c.decode_step(q, k, v)
 
-    # empty-start workloads fill first so that the timed steps are evicting steps
-    fill = wl.budget - wl.n_init - 1
-    warm = max(a.warmup, 1) + max(fill, 0)
     run(warm)
     torch.cuda.synchronize()
     assert all(c.valid_count == wl.budget for c in caches)

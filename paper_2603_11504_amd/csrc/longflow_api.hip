@@ -26,7 +26,7 @@ static int fail(int code, const char *fmt, ...)
 static size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
 
 // from this many units on, one workgroup per unit keeps the chip busy (256 CUs)
-static const int kUnitMinUnits = 192;
+static const int kUnitMinUnits = 96;
 
 void choose_splits(int units, int N, int *L, int *C)
 {
@@ -233,15 +233,15 @@ int longflow_decode_step(longflow_cache_t *cache, const void *q, const void *k_n
     hipStream_t s = (hipStream_t)hip_stream;
     hipEvent_t *ev = nullptr;
     if (c->prof_used < c->prof_cap) ev = &c->prof_events[4 * (size_t)c->prof_used++];
-    if (ev) (void)hipEventRecord(ev[0], s);
     hipError_t e;
     if (p.use_unit) {
         // the whole step is one kernel: it is reported in the "streaming pass" slot
-        if (ev) { (void)hipEventRecord(ev[1], s); }
+        if (ev) (void)hipEventRecord(ev[1], s);
         e = launch_unit_mfma(p, q, k_new, v_new, n, out, evict_idx, s);
         if (e != hipSuccess) return fail(LF_ERR_HIP, "fused launch: %s", hipGetErrorString(e));
-        if (ev) { (void)hipEventRecord(ev[2], s); (void)hipEventRecord(ev[3], s); }
+        if (ev) (void)hipEventRecord(ev[2], s);
     } else {
+        if (ev) (void)hipEventRecord(ev[0], s);
         e = launch_insert(p, q, k_new, v_new, s);
         if (e != hipSuccess) return fail(LF_ERR_HIP, "insert launch: %s", hipGetErrorString(e));
         if (ev) (void)hipEventRecord(ev[1], s);
@@ -320,10 +320,11 @@ int longflow_profile_end(longflow_cache_t *cache, float *kernel_ms, int32_t *ste
     kernel_ms[0] = kernel_ms[1] = kernel_ms[2] = 0.f;
     *steps = c->prof_used;
     int rc = LF_OK;
+    const int k0 = c->plan.use_unit ? 1 : 0, k1 = c->plan.use_unit ? 2 : 3; // events recorded per step
     for (int i = 0; i < c->prof_used && rc == LF_OK; ++i) {
         hipEvent_t *ev = &c->prof_events[4 * (size_t)i];
-        hipError_t e = hipEventSynchronize(ev[3]);
-        for (int k = 0; k < 3 && e == hipSuccess; ++k) {
+        hipError_t e = hipEventSynchronize(ev[k1]);
+        for (int k = k0; k < k1 && e == hipSuccess; ++k) {
             float ms = 0.f;
             e = hipEventElapsedTime(&ms, ev[k], ev[k + 1]);
             kernel_ms[k] += ms;
