@@ -22,7 +22,12 @@ HBM_PEAK_GBS = 8000.0  # MI355X published peak HBM3E bandwidth
 
 # HBM bytes per launch of the streaming kernel measured with rocprofv3 --pmc
 # (FETCH_SIZE / WRITE_SIZE, scaled by a copy kernel of known size); see profiles/.
-MEASURED_TRAFFIC = {}
+MEASURED_TRAFFIC = {
+    ("cfg3_bf16_b64_28x4_d128_n8192_l28", "unit_mfma_kernel"): {"read_bytes": 1058323 * 1024, "write_bytes": 1076 * 1024,
+                                                                "source": "profiles/unit_mfma_kernel_cfg3.txt"},
+    ("cfg4_bf16_b128_40x8_d128_n16384", "unit_mfma_kernel"): {"read_bytes": 8458816 * 1024, "write_bytes": 3264 * 1024,
+                                                              "source": "profiles/unit_mfma_kernel_cfg4.txt"},
+}
 
 
 def parse():
@@ -35,6 +40,8 @@ def parse():
     ap.add_argument("--split", action="store_true", help="force the split-K (3-launch) path")
     ap.add_argument("--unit", action="store_true", help="force the one-workgroup-per-unit fused path")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--calibrate-copy", action="store_true",
+                    help="also run one 1 GiB device copy (a kernel of known traffic, to scale rocprofv3 byte counters)")
     ap.add_argument("--pool", type=int, default=0,
                     help="distinct input steps cycled through (0 = one per executed step, no repeats)")
     return ap.parse_args()
@@ -49,7 +56,7 @@ def cpu_baseline(wl, caches_layer0, target_s=12.0):
 
     G, D, N = wl.group, wl.head_dim, wl.budget
     threads = oracle.num_threads()
-    nu = min(wl.units, max(threads, 16))
+    nu = min(wl.units, max(4 * threads, 64))
     rng = np.random.default_rng(wl.seed)
     units = np.sort(rng.choice(wl.units, size=nu, replace=False))
     sel = torch.as_tensor(units, device=caches_layer0.k_cache.device)
@@ -60,7 +67,7 @@ def cpu_baseline(wl, caches_layer0, target_s=12.0):
     ora.init(W.to_f64(ku), W.to_f64(vu))
     g = np.random.default_rng(1)
     steps, t_total = 0, 0.0
-    while t_total < target_s and steps < 64:
+    while t_total < target_s and steps < 4096:
         q = g.standard_normal((nu, G, D)); k = g.standard_normal((nu, 1, D)); v = g.standard_normal((nu, 1, D))
         t0 = time.perf_counter()
         ora.step(q, k, v)
@@ -120,6 +127,12 @@ def main():
     run(warm)
     torch.cuda.synchronize()
     assert all(c.valid_count == wl.budget for c in caches)
+    if a.calibrate_copy:
+        src = torch.empty(1 << 30, dtype=torch.uint8, device=dev).random_()   # elementwise kernel: writes 1 GiB
+        dst = torch.empty_like(src)
+        dst.copy_(src)                                                        # blit kernel: reads 1 GiB, writes 1 GiB
+        torch.cuda.synchronize()
+        del src, dst
 
     t0 = time.perf_counter()
     run(steps, warm)
@@ -141,7 +154,9 @@ def main():
     kavg_us = {k: v / calls * 1e3 for k, v in ksum.items()}
 
     bytes_call = wl.kv_bytes_per_call()
-    split_name = "split_mfma_kernel" if (wl.dtype == "bf16" and wl.head_dim == 128 and not flags) else "split_valu_kernel"
+    mfma = wl.dtype == "bf16" and wl.head_dim == 128 and not (flags & lf.LF_FLAG_FORCE_VALU)
+    fused = mfma and not (flags & lf.LF_FLAG_FORCE_SPLIT) and ((flags & lf.LF_FLAG_FORCE_UNIT) or wl.units >= 96)
+    split_name = "unit_mfma_kernel" if fused else ("split_mfma_kernel" if mfma else "split_valu_kernel")
     achieved = bytes_call / (kavg_us["split"] * 1e-6) / 1e9
     out = {
         "metric": "decode_tokens_per_s",
@@ -153,7 +168,9 @@ def main():
         "data": "synthetic",
         "config": {"workload": wl.name, "batch": wl.batch, "q_heads": wl.q_heads, "kv_heads": wl.kv_heads,
                    "head_dim": wl.head_dim, "budget": wl.budget, "layers": wl.layers,
-                   "calls_per_step": wl.layers, "kernel_path": "valu" if split_name.startswith("split_valu") else "mfma"},
+                   "calls_per_step": wl.layers, "kernel_path": {"unit_mfma_kernel": "fused one-launch, matrix cores",
+                                   "split_mfma_kernel": "split-K, matrix cores",
+                                   "split_valu_kernel": "split-K, vector ALU"}[split_name]},
         "us_per_call": ms_per_step * 1e3 / wl.layers,
         "step_hbm_GBs": bytes_call * wl.layers / (ms_per_step * 1e-3) / 1e9,
         "step_hbm_frac": bytes_call * wl.layers / (ms_per_step * 1e-3) / 1e9 / HBM_PEAK_GBS,
