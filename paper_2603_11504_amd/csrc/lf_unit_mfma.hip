@@ -192,63 +192,88 @@ __global__ __launch_bounds__(512, 1) void unit_mfma_kernel(
                 ls_ref[i] = fast_exp2(kCodeBias + ls_ref[i] - sM[h]) / sL[h];
             }
             __syncthreads();
-            // pass 1: upper bounds of all scores, block minimum.  A decoded term is within
-            // 2^(+-1/8) of the true one; code 0 has no upper bound, code 255 no lower bound.
-            const int items = 4 * ((n + kTile - 1) / kTile); // 4 positions each, whole tiles
+            // Decode every (head, slot) code once.  A decoded term is within 2^(+-1/8) of the
+            // true one; code 0 has no upper bound, code 255 no lower bound.  Each thread keeps
+            // the lower-bound sums of its slots in registers, the block finds the smallest
+            // upper bound, and a slot can be the true minimum only if
+            //   2^(-1/8) * lb_sum <= 2^(1/8) * min ub_sum.
+            const int items = 4 * nt; // 4 positions each, whole tiles
+            constexpr int kRegIters = 8; // 512 threads x 4 positions x 8 = 16384 slots held in registers
             const int iters = (items + 511) / 512;
-            float ub_min = INFINITY;
-            for (int it = 0; it < iters; ++it) {
-                const int item = it * 512 + tid;
-                if (item < items) {
-                    const int tile = item >> 2;
-                    float s4[4] = {0.f, 0.f, 0.f, 0.f};
-                    for (int h = 0; h < G; ++h) {
-                        const uint32_t c4 = *(const uint32_t *)(ls_code + (size_t)h * code_stride + 4 * item);
-                        const float f = ls_ref[tile * G + h];
+            auto decode_item = [&](int item, float *ub4, float *lb4) {
+                const int tile = item >> 2;
 #pragma unroll
-                        for (int e = 0; e < 4; ++e) {
-                            const uint32_t c = (c4 >> (8 * e)) & 255u;
-                            s4[e] += (c == 0u) ? INFINITY : fast_exp2(-0.25f * (float)c) * f;
-                        }
-                    }
-#pragma unroll
-                    for (int e = 0; e < 4; ++e)
-                        if (((4 * item) & ~15) + slot_of_pos((4 * item + e) & 15) < n) ub_min = fminf(ub_min, s4[e]);
-                }
-            }
-#pragma unroll
-            for (int off = 32; off > 0; off >>= 1) ub_min = fminf(ub_min, __shfl_xor(ub_min, off));
-            if (lane == 0) red_f[wave] = ub_min;
-            __syncthreads();
-            ub_min = red_f[0];
-#pragma unroll
-            for (int w = 1; w < NW; ++w) ub_min = fminf(ub_min, red_f[w]);
-            // a slot can be the true minimum only if its lower bound does not exceed the
-            // smallest upper bound: lb = 2^(-1/8) * dec, ub = 2^(1/8) * dec  ->  dec_i <= 2^(1/4) * dec_min
-            const float thr = ub_min * 1.1893f * 1.0001f;
-
-            // pass 2: list every slot whose lower bound does not exceed the threshold
-            for (int it = 0; it < iters; ++it) {
-                const int item = it * 512 + tid;
-                if (item < items) {
-                    const int tile = item >> 2;
-                    float s4[4] = {0.f, 0.f, 0.f, 0.f};
-                    for (int h = 0; h < G; ++h) {
-                        const uint32_t c4 = *(const uint32_t *)(ls_code + (size_t)h * code_stride + 4 * item);
-                        const float f = ls_ref[tile * G + h];
-#pragma unroll
-                        for (int e = 0; e < 4; ++e) {
-                            const uint32_t c = (c4 >> (8 * e)) & 255u;
-                            s4[e] += (c == 255u) ? 0.f : fast_exp2(-0.25f * (float)c) * f; // lower-bound side
-                        }
-                    }
+                for (int e = 0; e < 4; ++e) ub4[e] = lb4[e] = 0.f;
+                for (int h = 0; h < G; ++h) {
+                    const uint32_t c4 = *(const uint32_t *)(ls_code + (size_t)h * code_stride + 4 * item);
+                    const float f = ls_ref[tile * G + h];
 #pragma unroll
                     for (int e = 0; e < 4; ++e) {
-                        const int slot = ((4 * item) & ~15) + slot_of_pos((4 * item + e) & 15);
-                        if (slot < n && s4[e] <= thr) {
-                            const int k = atomicAdd(&cand_count, 1);
-                            if (k < kMaxCand) cand_list[k] = slot;
-                        }
+                        const uint32_t c = (c4 >> (8 * e)) & 255u;
+                        const float d = fast_exp2(-0.25f * (float)c) * f;
+                        ub4[e] += (c == 0u) ? INFINITY : d;
+                        lb4[e] += (c == 255u) ? 0.f : d;
+                    }
+                }
+#pragma unroll
+                for (int e = 0; e < 4; ++e) {
+                    const int slot = ((4 * item) & ~15) + slot_of_pos((4 * item + e) & 15);
+                    if (slot >= n) { ub4[e] = INFINITY; lb4[e] = INFINITY; }
+                }
+            };
+            auto list_candidates = [&](int item, const float *lb4, float thr) {
+#pragma unroll
+                for (int e = 0; e < 4; ++e) {
+                    if (lb4[e] <= thr) {
+                        const int k = atomicAdd(&cand_count, 1);
+                        if (k < kMaxCand) cand_list[k] = ((4 * item) & ~15) + slot_of_pos((4 * item + e) & 15);
+                    }
+                }
+            };
+            auto block_min = [&](float x) {
+#pragma unroll
+                for (int off = 32; off > 0; off >>= 1) x = fminf(x, __shfl_xor(x, off));
+                if (lane == 0) red_f[wave] = x;
+                __syncthreads();
+                x = red_f[0];
+#pragma unroll
+                for (int w = 1; w < NW; ++w) x = fminf(x, red_f[w]);
+                return x;
+            };
+            float ub_min = INFINITY;
+            if (iters <= kRegIters) {
+                float lbs[kRegIters][4];
+#pragma unroll
+                for (int it = 0; it < kRegIters; ++it) {
+                    const int item = it * 512 + tid;
+#pragma unroll
+                    for (int e = 0; e < 4; ++e) lbs[it][e] = INFINITY;
+                    if (it < iters && item < items) {
+                        float ub4[4];
+                        decode_item(item, ub4, lbs[it]);
+                        ub_min = fminf(ub_min, fminf(fminf(ub4[0], ub4[1]), fminf(ub4[2], ub4[3])));
+                    }
+                }
+                const float thr = block_min(ub_min) * 1.1893f * 1.0001f;
+#pragma unroll
+                for (int it = 0; it < kRegIters; ++it)
+                    if (it < iters) list_candidates(it * 512 + tid, lbs[it], thr);
+            } else { // budgets beyond the register window: decode twice
+                for (int it = 0; it < iters; ++it) {
+                    const int item = it * 512 + tid;
+                    if (item < items) {
+                        float ub4[4], lb4[4];
+                        decode_item(item, ub4, lb4);
+                        ub_min = fminf(ub_min, fminf(fminf(ub4[0], ub4[1]), fminf(ub4[2], ub4[3])));
+                    }
+                }
+                const float thr = block_min(ub_min) * 1.1893f * 1.0001f;
+                for (int it = 0; it < iters; ++it) {
+                    const int item = it * 512 + tid;
+                    if (item < items) {
+                        float ub4[4], lb4[4];
+                        decode_item(item, ub4, lb4);
+                        list_candidates(item, lb4, thr);
                     }
                 }
             }
