@@ -69,7 +69,7 @@ typedef enum { LF_F32 = 0, LF_BF16 = 1 } lf_dtype;
                                      (the uncompressed comparison of Sec. 4.4)            */
 #define LF_FLAG_FORCE_VALU 2u     /* bf16 only: use the vector-ALU kernel instead of the
                                      matrix-core kernel (for A/B measurement)              */
-#define LF_FLAG_FORCE_SPLIT 4u    /* always split a unit over several workgroups (3 launches) */
+#define LF_FLAG_FORCE_SPLIT 4u    /* always split a unit over several workgroups              */
 #define LF_FLAG_FORCE_UNIT 8u     /* always one workgroup per unit, one fused launch; needs the
                                      matrix-core path and budget * group <= ~120k            */
 
@@ -138,12 +138,13 @@ LF_API int longflow_destroy_cache(longflow_cache_t *cache);
 
 /*
  * Measurement aid (not part of the paper's operator): while profiling is on, every
- * decode step records HIP events on its stream around its three kernels.
+ * decode step records two HIP events on its stream around its kernel launches (one
+ * launch per step, two on the split-K path when its grid is large).
  *   longflow_profile_begin  creates events for up to max_steps steps and switches it on
- *   longflow_profile_end    waits for the recorded events, writes the summed durations
- *                           in milliseconds to kernel_ms[3] = {insert, streaming pass,
- *                           finish} and the number of steps recorded to *steps (host
- *                           pointers), destroys the events and switches it off.
+ *   longflow_profile_end    waits for the recorded events, writes the summed kernel
+ *                           duration in milliseconds to *kernel_ms and the number of steps
+ *                           recorded to *steps (host pointers), destroys the events and
+ *                           switches it off.
  * Steps beyond max_steps run untimed.  Synchronises the host with the stream.
  */
 LF_API int longflow_profile_begin(longflow_cache_t *cache, int32_t max_steps);

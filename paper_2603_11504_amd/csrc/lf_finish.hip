@@ -1,71 +1,10 @@
-// Small kernels around the streaming pass: slot insert, cross-split combine fused with
-// the eviction argmin, on-demand score read-back.
+// Kernels off the per-step path: value-norm side array at cache init, on-demand score
+// read-back, small fills.
 #include "lf_device.h"
 #include "lf_host.h"
-#include "lf_mfma_stream.h"
+#include "lf_split_tail.h"
 
 namespace lf {
-
-// ---------------------------------------------------------------------------------------
-// Insert (Fig. 2 left): the current token's K/V covers the slot chosen by the previous
-// step.  One block per unit; extra blocks keep a copy of q for longflow_scores().
-// ---------------------------------------------------------------------------------------
-template <typename T>
-__global__ __launch_bounds__(128) void insert_kernel(T *__restrict__ Kc, T *__restrict__ Vc,
-                                                      const T *__restrict__ k_new,
-                                                      const T *__restrict__ v_new,
-                                                      const int32_t *__restrict__ pending,
-                                                      const T *__restrict__ q, T *__restrict__ q_last,
-                                                      int units, int N, int D, int q_elems,
-                                                      float *__restrict__ lu, int lu_stride)
-{
-    __shared__ float part[2];
-    const int b = blockIdx.x;
-    if (b < units) {
-        const int slot = pending[b];
-        if (slot < 0 || slot >= N) return; // never write outside the cache
-        T *kd = Kc + ((size_t)b * N + slot) * D;
-        T *vd = Vc + ((size_t)b * N + slot) * D;
-        float a1 = 0.f;
-        for (int d = threadIdx.x; d < D; d += blockDim.x) {
-            kd[d] = k_new[(size_t)b * D + d];
-            const T v = v_new[(size_t)b * D + d];
-            vd[d] = v;
-            a1 += fabsf(to_f32(v));
-        }
-        if (lu) { // side array of the matrix-core kernels: log2 ||v||_1, position order
-#pragma unroll
-            for (int off = 32; off > 0; off >>= 1) a1 += __shfl_xor(a1, off);
-            if ((threadIdx.x & 63) == 0) part[threadIdx.x >> 6] = a1;
-            __syncthreads();
-            if (threadIdx.x == 0)
-                lu[(size_t)b * lu_stride + (slot & ~15) + pos_of_slot(slot & 15)] = __builtin_amdgcn_logf(part[0] + part[1]);
-        }
-    } else {
-        const int i0 = (b - units) * 1024;
-        for (int i = i0 + threadIdx.x; i < min(i0 + 1024, q_elems); i += blockDim.x) q_last[i] = q[i];
-    }
-}
-
-hipError_t launch_insert(const Plan &p, const void *q, const void *k_new, const void *v_new,
-                         hipStream_t s)
-{
-    const int q_elems = p.B * p.Hq * p.D;
-    const int qblocks = (q_elems + 1023) / 1024;
-    const bool do_insert = !(p.flags & 1u);
-    const int units = do_insert ? p.units : 0;
-    if (p.dtype == 0)
-        hipLaunchKernelGGL(insert_kernel<float>, dim3(units + qblocks), dim3(128), 0, s,
-                           (float *)p.k_cache, (float *)p.v_cache, (const float *)k_new,
-                           (const float *)v_new, p.pending, (const float *)q, (float *)p.q_last,
-                           units, p.N, p.D, q_elems, (float *)nullptr, 0);
-    else
-        hipLaunchKernelGGL(insert_kernel<bf16_t>, dim3(units + qblocks), dim3(128), 0, s,
-                           (bf16_t *)p.k_cache, (bf16_t *)p.v_cache, (const bf16_t *)k_new,
-                           (const bf16_t *)v_new, p.pending, (const bf16_t *)q, (bf16_t *)p.q_last,
-                           units, p.N, p.D, q_elems, p.use_mfma ? p.lu : (float *)nullptr, p.ntiles * kTile);
-    return hipGetLastError();
-}
 
 // log2 ||v||_1 of rows [0, n_rows) of every unit (prefill), one 16-lane row per cache row
 __global__ __launch_bounds__(256) void l1norm_kernel(const uint16_t *__restrict__ Vc, float *__restrict__ lu,
@@ -79,7 +18,7 @@ __global__ __launch_bounds__(256) void l1norm_kernel(const uint16_t *__restrict_
         float a1 = fabsf(bf16_lo(vv.x)) + fabsf(bf16_hi(vv.x)) + fabsf(bf16_lo(vv.y)) + fabsf(bf16_hi(vv.y)) +
                    fabsf(bf16_lo(vv.z)) + fabsf(bf16_hi(vv.z)) + fabsf(bf16_lo(vv.w)) + fabsf(bf16_hi(vv.w));
         a1 = row16_sum(a1);
-        if (lane16 == 0) lu[(size_t)u * lu_stride + (slot & ~15) + pos_of_slot(slot & 15)] = __builtin_amdgcn_logf(a1);
+        if (lane16 == 0) lu[(size_t)u * lu_stride + (slot & ~15) + tail_pos_of_slot(slot & 15)] = __builtin_amdgcn_logf(a1);
     }
 }
 hipError_t launch_l1norms(const Plan &p, int n_rows, hipStream_t s)
@@ -105,207 +44,6 @@ hipError_t launch_fill_i32(int32_t *dst, int count, int32_t value, hipStream_t s
 }
 
 // ---------------------------------------------------------------------------------------
-// Exact LongFlowScore of one slot in double precision, computed by a whole wave
-// (eq. 6 with the heads of the group summed).  M, Linv: the step's softmax reference
-// (log2 domain) and reciprocal denominator per head.
-// ---------------------------------------------------------------------------------------
-__device__ __forceinline__ double wave_sum(double x)
-{
-#pragma unroll
-    for (int off = 32; off > 0; off >>= 1) x += __shfl_xor(x, off);
-    return x;
-}
-
-template <typename T, int D>
-__device__ double exact_score(const T *__restrict__ krow, const T *__restrict__ vrow,
-                              const T *__restrict__ qu, int G, const float *sM, const float *sL,
-                              int lane)
-{
-    constexpr int PER = D / 64;
-    double kd[PER], l1 = 0.0;
-#pragma unroll
-    for (int e = 0; e < PER; ++e) {
-        kd[e] = (double)to_f32(krow[lane * PER + e]);
-        l1 += fabs((double)to_f32(vrow[lane * PER + e]));
-    }
-    l1 = wave_sum(l1);
-    const double scale_log2 = 1.4426950408889634074 / sqrt((double)D);
-    double acc = 0.0;
-    for (int h = 0; h < G; ++h) {
-        double dot = 0.0;
-#pragma unroll
-        for (int e = 0; e < PER; ++e) dot += (double)to_f32(qu[(size_t)h * D + lane * PER + e]) * kd[e];
-        dot = wave_sum(dot);
-        acc += exp2(dot * scale_log2 - (double)sM[h]) / (double)sL[h];
-    }
-    return acc * l1;
-}
-
-// ---------------------------------------------------------------------------------------
-// Finish: one block per unit.
-//   1. merge the split partials -> global reference M_h, denominator L_h, out   (eq. 1)
-//   2. while filling: next slot = valid count
-//   3. full cache: screen all slots with the bf16 stash (relative error < 2^-8), then
-//      re-score every slot within the screening margin of the minimum exactly, in
-//      double precision, and take the argmin with the lowest index on ties
-//      (Sec. 3.2 last paragraph; Alg. 1 post-processing)
-// ---------------------------------------------------------------------------------------
-template <typename T, int D>
-__global__ __launch_bounds__(256) void finish_kernel(
-    const T *__restrict__ Kc, const T *__restrict__ Vc, const T *__restrict__ q, int n, int N, int G,
-    int C, int c_active, int ntiles, const float *__restrict__ part_m,
-    const float *__restrict__ part_l, const float *__restrict__ part_o,
-    const uint16_t *__restrict__ stash_w, const float *__restrict__ stash_m, T *__restrict__ out,
-    float *__restrict__ fin_m, float *__restrict__ fin_l, int32_t *__restrict__ pending,
-    int32_t *__restrict__ evict_idx, int attention_only, int pos_order)
-{
-    __shared__ float sM[kMaxGroup], sL[kMaxGroup];
-    __shared__ float sW[kMaxSplits][kMaxGroup];
-    __shared__ float red_v[4];
-    __shared__ double best_v[4];
-    __shared__ int best_i[4];
-
-    const int u = blockIdx.x, tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-    const size_t pb = (size_t)u * C * G;
-
-    if (tid < G) {
-        float M = -INFINITY;
-        for (int c = 0; c < c_active; ++c) M = fmaxf(M, part_m[pb + (size_t)c * G + tid]);
-        float Ls = 0.f;
-        for (int c = 0; c < c_active; ++c) {
-            const float w = merge_weight(part_m[pb + (size_t)c * G + tid], M);
-            sW[c][tid] = w;
-            Ls += w * part_l[pb + (size_t)c * G + tid];
-        }
-        sM[tid] = M;
-        sL[tid] = Ls;
-        fin_m[(size_t)u * G + tid] = M;
-        fin_l[(size_t)u * G + tid] = Ls;
-    }
-    __syncthreads();
-    for (int idx = tid; idx < G * D; idx += 256) {
-        const int h = idx / D, d = idx % D;
-        float acc = 0.f;
-        for (int c = 0; c < c_active; ++c) acc += sW[c][h] * part_o[(pb + (size_t)c * G + h) * D + d];
-        store_elem(out + ((size_t)u * G + h) * D + d, acc / sL[h]);
-    }
-    if (attention_only) return;
-    if (n < N) {
-        if (tid == 0) {
-            pending[u] = n;
-            if (evict_idx) evict_idx[u] = n;
-        }
-        return;
-    }
-
-    // ---- screening pass 1: approximate scores from the stash, block minimum
-    const int nhalf = 2 * ((n + kTile - 1) / kTile);
-    const int iters = (nhalf + 255) / 256;
-    const uint16_t *sw = stash_w + (size_t)u * ntiles * G * kTile;
-    const float *smt = stash_m + (size_t)u * ntiles * G;
-    float vmin = INFINITY;
-    for (int it = 0; it < iters; ++it) {
-        const int item = it * 256 + tid;
-        if (item < nhalf) {
-            const int tile = item >> 1, half = item & 1;
-            float sc[8];
-#pragma unroll
-            for (int e = 0; e < 8; ++e) sc[e] = 0.f;
-            for (int h = 0; h < G; ++h) {
-                const u32x4 w = *(const u32x4 *)(sw + ((size_t)tile * G + h) * kTile + half * 8);
-                const float f = fast_exp2(smt[(size_t)tile * G + h] - sM[h]) / sL[h];
-                sc[0] = fmaf(bf16_lo(w.x), f, sc[0]); sc[1] = fmaf(bf16_hi(w.x), f, sc[1]);
-                sc[2] = fmaf(bf16_lo(w.y), f, sc[2]); sc[3] = fmaf(bf16_hi(w.y), f, sc[3]);
-                sc[4] = fmaf(bf16_lo(w.z), f, sc[4]); sc[5] = fmaf(bf16_hi(w.z), f, sc[5]);
-                sc[6] = fmaf(bf16_lo(w.w), f, sc[6]); sc[7] = fmaf(bf16_hi(w.w), f, sc[7]);
-            }
-#pragma unroll
-            for (int e = 0; e < 8; ++e) {
-                const int in_tile = half * 8 + e;
-                const int slot = tile * kTile + (pos_order ? slot_of_pos(in_tile) : in_tile);
-                if (slot < n) vmin = fminf(vmin, sc[e]);
-            }
-        }
-    }
-#pragma unroll
-    for (int off = 32; off > 0; off >>= 1) vmin = fminf(vmin, __shfl_xor(vmin, off));
-    if (lane == 0) red_v[wave] = vmin;
-    __syncthreads();
-    const float smin = fminf(fminf(red_v[0], red_v[1]), fminf(red_v[2], red_v[3]));
-    // stash values carry relative error <= 2^-9 (bf16 rounding) plus fp32 noise, and an
-    // absolute error <= 2^-121 where they underflow: everything that could be the true
-    // minimum lies below this threshold
-    const float thr = smin * (1.0f + 0.0078125f) + 7.5e-37f;
-
-    // ---- pass 2: exact scores of the candidates, wave-cooperative
-    double bv = INFINITY;
-    int bi = 0x7fffffff;
-    const T *Ku = Kc + (size_t)u * N * D;
-    const T *Vu = Vc + (size_t)u * N * D;
-    const T *qu = q + (size_t)u * G * D;
-    for (int it = 0; it < iters; ++it) {
-        const int item = it * 256 + tid;
-        const int tile = item >> 1, half = item & 1;
-        float sc[8];
-#pragma unroll
-        for (int e = 0; e < 8; ++e) sc[e] = INFINITY;
-        if (item < nhalf) {
-#pragma unroll
-            for (int e = 0; e < 8; ++e) sc[e] = 0.f;
-            for (int h = 0; h < G; ++h) {
-                const u32x4 w = *(const u32x4 *)(sw + ((size_t)tile * G + h) * kTile + half * 8);
-                const float f = fast_exp2(smt[(size_t)tile * G + h] - sM[h]) / sL[h];
-                sc[0] = fmaf(bf16_lo(w.x), f, sc[0]); sc[1] = fmaf(bf16_hi(w.x), f, sc[1]);
-                sc[2] = fmaf(bf16_lo(w.y), f, sc[2]); sc[3] = fmaf(bf16_hi(w.y), f, sc[3]);
-                sc[4] = fmaf(bf16_lo(w.z), f, sc[4]); sc[5] = fmaf(bf16_hi(w.z), f, sc[5]);
-                sc[6] = fmaf(bf16_lo(w.w), f, sc[6]); sc[7] = fmaf(bf16_hi(w.w), f, sc[7]);
-            }
-        }
-#pragma unroll
-        for (int e = 0; e < 8; ++e) {
-            const int in_tile = half * 8 + e;
-            const int slot = tile * kTile + (pos_order ? slot_of_pos(in_tile) : in_tile);
-            const bool cand = (item < nhalf) && (slot < n) && (sc[e] <= thr);
-            unsigned long long bal = __ballot(cand);
-            while (bal) {
-                const int src = __ffsll((long long)bal) - 1;
-                bal &= bal - 1;
-                const int cs = __shfl(slot, src);
-                const double v = exact_score<T, D>(Ku + (size_t)cs * D, Vu + (size_t)cs * D, qu, G, sM, sL, lane);
-                if (v < bv || (v == bv && cs < bi)) { bv = v; bi = cs; }
-            }
-        }
-    }
-    if (lane == 0) { best_v[wave] = bv; best_i[wave] = bi; }
-    __syncthreads();
-    if (tid == 0) {
-        double v = best_v[0];
-        int i = best_i[0];
-        for (int w = 1; w < 4; ++w)
-            if (best_v[w] < v || (best_v[w] == v && best_i[w] < i)) { v = best_v[w]; i = best_i[w]; }
-        if (i < 0 || i >= N) i = 0; // non-finite scores: keep the slot in range
-        pending[u] = i;
-        if (evict_idx) evict_idx[u] = i;
-    }
-}
-
-hipError_t launch_finish(const Plan &p, const void *q, int n, void *out, int32_t *evict_idx,
-                         hipStream_t s)
-{
-    const int c_active = (n + p.L - 1) / p.L;
-    const int ao = (p.flags & 1u) ? 1 : 0;
-#define LF_FIN(T, DD)                                                                              \
-    hipLaunchKernelGGL((finish_kernel<T, DD>), dim3(p.units), dim3(256), 0, s,                    \
-                       (const T *)p.k_cache, (const T *)p.v_cache, (const T *)q, n, p.N, p.G, p.C, \
-                       c_active, p.ntiles, p.part_m, p.part_l, p.part_o, p.stash_w, p.stash_m,     \
-                       (T *)out, p.fin_m, p.fin_l, p.pending, evict_idx, ao, p.use_mfma ? 1 : 0)
-    if (p.dtype == 0) { if (p.D == 64) LF_FIN(float, 64); else LF_FIN(float, 128); }
-    else              { if (p.D == 64) LF_FIN(bf16_t, 64); else LF_FIN(bf16_t, 128); }
-#undef LF_FIN
-    return hipGetLastError();
-}
-
-// ---------------------------------------------------------------------------------------
 // Score read-back (S_final_loss of Alg. 1), off the per-step path: one wave per slot,
 // double-precision arithmetic, fp32 result.
 // ---------------------------------------------------------------------------------------
@@ -326,7 +64,7 @@ __global__ __launch_bounds__(256) void scores_kernel(const T *__restrict__ Kc, c
     for (int slot = lo + wave; slot < hi; slot += 4) {
         float r = 0.f;
         if (slot < n) {
-            const double v = exact_score<T, D>(Kc + ((size_t)u * N + slot) * D, Vc + ((size_t)u * N + slot) * D,
+            const double v = tail_exact_score<T, D>(Kc + ((size_t)u * N + slot) * D, Vc + ((size_t)u * N + slot) * D,
                                                q_last + (size_t)u * G * D, G, sM, sL, lane);
             r = (float)v;
         }

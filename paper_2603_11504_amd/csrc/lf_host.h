@@ -26,6 +26,7 @@ struct Plan {
     void *k_cache, *v_cache;
     // carved out of the caller's workspace
     int32_t *pending;  // [units]
+    int32_t *arrive;   // [units] split-path arrival counters, zero between steps
     void *q_last;      // [B][Hq][D] copy of the last step's query (for longflow_scores)
     float *part_m;     // [units][C][G]    split-local softmax reference (log2 domain)
     float *part_l;     // [units][C][G]    split-local denominator
@@ -39,7 +40,7 @@ struct Plan {
 };
 
 struct Layout {
-    size_t off_pending, off_q, off_part_m, off_part_l, off_part_o, off_fin_m, off_fin_l,
+    size_t off_pending, off_arrive, off_q, off_part_m, off_part_l, off_part_o, off_fin_m, off_fin_l,
         off_stash_w, off_stash_m, off_lu, total;
 };
 
@@ -48,15 +49,17 @@ void choose_splits(int units, int N, int *L, int *C);
 Layout make_layout(int units, int Hq_total_elems_bytes, int G, int D, int C, int ntiles);
 
 // Kernel launchers (each returns the hipError_t of its launch).
-hipError_t launch_insert(const Plan &p, const void *q, const void *k_new, const void *v_new,
-                         hipStream_t s);
-hipError_t launch_split_valu(const Plan &p, const void *q, int n, hipStream_t s);
-hipError_t launch_split_mfma(const Plan &p, const void *q, int n, hipStream_t s);
+// One decode step on a split-K path (single launch: insert, stream, last-arriver finish).
+struct StepIo {
+    const void *q, *k_new, *v_new;
+    void *out;
+    int32_t *evict_idx;
+};
+hipError_t launch_split_valu(const Plan &p, const StepIo &io, int n, hipStream_t s);
+hipError_t launch_split_mfma(const Plan &p, const StepIo &io, int n, hipStream_t s);
 size_t unit_mfma_lds_bytes(int N, int G, bool stash);
 hipError_t launch_unit_mfma(const Plan &p, const void *q, const void *k_new, const void *v_new, int n,
                             void *out, int32_t *evict_idx, hipStream_t s);
-hipError_t launch_finish(const Plan &p, const void *q, int n, void *out, int32_t *evict_idx,
-                         hipStream_t s);
 hipError_t launch_scores(const Plan &p, int n, float *scores, hipStream_t s);
 hipError_t launch_l1norms(const Plan &p, int n_rows, hipStream_t s);
 hipError_t launch_fill_i32(int32_t *dst, int count, int32_t value, hipStream_t s);

@@ -3,20 +3,24 @@
 // to give every compute unit a whole one.  Writes the split's partial softmax state and
 // the bf16 screening stash to device memory; the finish kernel merges and decides.
 #include "lf_mfma_stream.h"
+#include "lf_split_tail.h"
 
 namespace lf {
 
 template <bool HILO, int STASH>
-__global__ __launch_bounds__(256, 2) void split_mfma_kernel(
-    const uint16_t *__restrict__ Kc, const uint16_t *__restrict__ Vc, const uint16_t *__restrict__ q,
-    int n, int N, int G, int L, int C, int ntiles, int c_active,
-    float *__restrict__ part_m, float *__restrict__ part_l, float *__restrict__ part_o,
-    uint16_t *__restrict__ stash_w, float *__restrict__ stash_m, const float *__restrict__ lu,
-    float scale_log2)
+__global__ __launch_bounds__(256, 2) void split_mfma_kernel(const SplitTailArgs<bf16_t> ta, float scale_log2)
 {
     constexpr int D = 128;
+    const int n = ta.n, N = ta.N, G = ta.G, L = ta.L, C = ta.C, ntiles = ta.ntiles, c_active = ta.c_active;
+    const uint16_t *Kc = (const uint16_t *)ta.Kc, *Vc = (const uint16_t *)ta.Vc, *q = (const uint16_t *)ta.q;
+    float *part_m = ta.part_m, *part_l = ta.part_l, *part_o = ta.part_o;
+    uint16_t *stash_w = ta.stash_w;
+    float *stash_m = ta.stash_m;
+    const float *lu = ta.lu;
     const int u = blockIdx.x / c_active, c = blockIdx.x % c_active;
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+
+    split_head_insert<bf16_t, D>(ta, u, c);
 
     MfmaStreamer<4, HILO, STASH> st;
     st.init(q + (size_t)u * G * D, G, lane, scale_log2);
@@ -56,20 +60,20 @@ __global__ __launch_bounds__(256, 2) void split_mfma_kernel(
         part_o[(pbase + h) * D + d] = acc;
         if (d == 0) { part_m[pbase + h] = M; part_l[pbase + h] = lacc; }
     }
+    split_tail<bf16_t, D>(ta, u);
 }
 
-hipError_t launch_split_mfma(const Plan &p, const void *q, int n, hipStream_t s)
+hipError_t launch_split_mfma(const Plan &p, const StepIo &io, int n, hipStream_t s)
 {
-    const int c_active = (n + p.L - 1) / p.L;
+    const SplitTailArgs<bf16_t> ta = make_tail_args<bf16_t>(p, io, n);
     const float scale_log2 = 1.4426950408889634f / sqrtf(128.f);
-#define LF_SPLIT(STASH)                                                                             \
-    hipLaunchKernelGGL((split_mfma_kernel<true, STASH>), dim3(p.units * c_active), dim3(256), 0, s, \
-                       (const uint16_t *)p.k_cache, (const uint16_t *)p.v_cache, (const uint16_t *)q, \
-                       n, p.N, p.G, p.L, p.C, p.ntiles, c_active, p.part_m, p.part_l, p.part_o,    \
-                       p.stash_w, p.stash_m, p.lu, scale_log2)
-    if (p.flags & 1u) LF_SPLIT(kStashNone); else LF_SPLIT(kStashGlobal);
-#undef LF_SPLIT
-    return hipGetLastError();
+    if (p.flags & 1u)
+        hipLaunchKernelGGL((split_mfma_kernel<true, kStashNone>), dim3(p.units * ta.c_active), dim3(256), 0, s, ta, scale_log2);
+    else
+        hipLaunchKernelGGL((split_mfma_kernel<true, kStashGlobal>), dim3(p.units * ta.c_active), dim3(256), 0, s, ta, scale_log2);
+    hipError_t e = hipGetLastError();
+    if (e == hipSuccess && !ta.fused_tail) e = launch_split_finish<bf16_t, 128>(ta, p.units, s);
+    return e;
 }
 
 } // namespace lf

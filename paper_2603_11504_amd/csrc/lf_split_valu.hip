@@ -10,6 +10,7 @@
 
 #include "lf_device.h"
 #include "lf_host.h"
+#include "lf_split_tail.h"
 
 namespace lf {
 
@@ -30,14 +31,17 @@ template <int JJ> __device__ __forceinline__ float row16_bcast(float x)
 }
 
 template <typename T, int D, int G>
-__global__ __launch_bounds__(256) void split_valu_kernel(
-    const T *__restrict__ Kc, const T *__restrict__ Vc, const T *__restrict__ q,
-    int n, int N, int L, int C, int ntiles, int c_active,
-    float *__restrict__ part_m, float *__restrict__ part_l, float *__restrict__ part_o,
-    uint16_t *__restrict__ stash_w, float *__restrict__ stash_m, float scale_log2, int write_stash)
+__global__ __launch_bounds__(256) void split_valu_kernel(const SplitTailArgs<T> ta, float scale_log2)
 {
     constexpr int EPL = D / 16; // elements per lane of a 16-lane row
+    const int n = ta.n, N = ta.N, L = ta.L, C = ta.C, ntiles = ta.ntiles, c_active = ta.c_active;
+    const T *Kc = ta.Kc, *Vc = ta.Vc, *q = ta.q;
+    float *part_m = ta.part_m, *part_l = ta.part_l, *part_o = ta.part_o;
+    uint16_t *stash_w = ta.stash_w;
+    float *stash_m = ta.stash_m;
+    const int write_stash = !ta.attention_only;
     const int u = blockIdx.x / c_active, c = blockIdx.x % c_active;
+    split_head_insert<T, D>(ta, u, c);
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int rg = lane >> 4, j = lane & 15;
     const int start = c * L;
@@ -162,42 +166,41 @@ __global__ __launch_bounds__(256) void split_valu_kernel(
         part_o[(pbase + h) * D + d] = acc;
         if (d == 0) { part_m[pbase + h] = M; part_l[pbase + h] = lacc; }
     }
+    split_tail<T, D>(ta, u);
 }
 
 template <typename T, int D, int G>
-static hipError_t launch_one(const Plan &p, const void *q, int n, hipStream_t s)
+static hipError_t launch_one(const Plan &p, const StepIo &io, int n, hipStream_t s)
 {
-    const int c_active = (n + p.L - 1) / p.L;
+    const SplitTailArgs<T> ta = make_tail_args<T>(p, io, n);
     const float scale_log2 = 1.4426950408889634f / sqrtf((float)D);
-    const int write_stash = (p.flags & 1u) ? 0 : 1;
-    hipLaunchKernelGGL((split_valu_kernel<T, D, G>), dim3(p.units * c_active), dim3(256), 0, s,
-                       (const T *)p.k_cache, (const T *)p.v_cache, (const T *)q, n, p.N, p.L, p.C,
-                       p.ntiles, c_active, p.part_m, p.part_l, p.part_o, p.stash_w, p.stash_m,
-                       scale_log2, write_stash);
-    return hipGetLastError();
+    hipLaunchKernelGGL((split_valu_kernel<T, D, G>), dim3(p.units * ta.c_active), dim3(256), 0, s, ta, scale_log2);
+    hipError_t e = hipGetLastError();
+    if (e == hipSuccess && !ta.fused_tail) e = launch_split_finish<T, D>(ta, p.units, s);
+    return e;
 }
 
 template <typename T, int D>
-static hipError_t launch_g(const Plan &p, const void *q, int n, hipStream_t s)
+static hipError_t launch_g(const Plan &p, const StepIo &io, int n, hipStream_t s)
 {
     switch (p.G) {
-    case 1: return launch_one<T, D, 1>(p, q, n, s);
-    case 2: return launch_one<T, D, 2>(p, q, n, s);
-    case 3: return launch_one<T, D, 3>(p, q, n, s);
-    case 4: return launch_one<T, D, 4>(p, q, n, s);
-    case 5: return launch_one<T, D, 5>(p, q, n, s);
-    case 6: return launch_one<T, D, 6>(p, q, n, s);
-    case 7: return launch_one<T, D, 7>(p, q, n, s);
-    case 8: return launch_one<T, D, 8>(p, q, n, s);
+    case 1: return launch_one<T, D, 1>(p, io, n, s);
+    case 2: return launch_one<T, D, 2>(p, io, n, s);
+    case 3: return launch_one<T, D, 3>(p, io, n, s);
+    case 4: return launch_one<T, D, 4>(p, io, n, s);
+    case 5: return launch_one<T, D, 5>(p, io, n, s);
+    case 6: return launch_one<T, D, 6>(p, io, n, s);
+    case 7: return launch_one<T, D, 7>(p, io, n, s);
+    case 8: return launch_one<T, D, 8>(p, io, n, s);
     default: return hipErrorInvalidValue;
     }
 }
 
-hipError_t launch_split_valu(const Plan &p, const void *q, int n, hipStream_t s)
+hipError_t launch_split_valu(const Plan &p, const StepIo &io, int n, hipStream_t s)
 {
     if (p.dtype == 0)
-        return p.D == 64 ? launch_g<float, 64>(p, q, n, s) : launch_g<float, 128>(p, q, n, s);
-    return p.D == 64 ? launch_g<bf16_t, 64>(p, q, n, s) : launch_g<bf16_t, 128>(p, q, n, s);
+        return p.D == 64 ? launch_g<float, 64>(p, io, n, s) : launch_g<float, 128>(p, io, n, s);
+    return p.D == 64 ? launch_g<bf16_t, 64>(p, io, n, s) : launch_g<bf16_t, 128>(p, io, n, s);
 }
 
 } // namespace lf

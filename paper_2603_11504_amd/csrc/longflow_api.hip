@@ -101,6 +101,7 @@ static Layout layout_of(const Plan &p)
     size_t off = 0;
     auto take = [&](size_t bytes) { size_t o = off; off = align_up(off + bytes, 256); return o; };
     l.off_pending = take(sizeof(int32_t) * p.units);
+    l.off_arrive = take(sizeof(int32_t) * p.units);
     l.off_q = take(esz * (size_t)p.B * p.Hq * p.D);
     l.off_part_m = take(sizeof(float) * (size_t)p.units * p.C * p.G);
     l.off_part_l = take(sizeof(float) * (size_t)p.units * p.C * p.G);
@@ -123,7 +124,7 @@ struct longflow_cache {
     int count;         // valid slots
     bool has_pending;  // a slot for the next token is known on the device
     bool stepped;      // at least one decode step ran (scores are defined)
-    std::vector<hipEvent_t> prof_events; // 4 per recorded step while profiling
+    std::vector<hipEvent_t> prof_events; // 2 per recorded step while profiling
     int prof_cap = 0, prof_used = 0;
 };
 
@@ -169,6 +170,7 @@ int longflow_init_cache(longflow_cache_t **out, const lf_config *cfg, void *k_ca
     char *ws = (char *)workspace;
     p.k_cache = k_cache; p.v_cache = v_cache;
     p.pending = (int32_t *)(ws + l.off_pending);
+    p.arrive = (int32_t *)(ws + l.off_arrive);
     p.q_last = ws + l.off_q;
     p.part_m = (float *)(ws + l.off_part_m);
     p.part_l = (float *)(ws + l.off_part_l);
@@ -193,6 +195,10 @@ int longflow_init_cache(longflow_cache_t **out, const lf_config *cfg, void *k_ca
     if (n_init > 0 && p.use_mfma && !(p.flags & LF_FLAG_ATTENTION_ONLY)) {
         hipError_t e = launch_l1norms(p, n_init, s);
         if (e != hipSuccess) return fail(LF_ERR_HIP, "value-norm init: %s", hipGetErrorString(e));
+    }
+    {
+        hipError_t e = launch_fill_i32(p.arrive, p.units, 0, s);
+        if (e != hipSuccess) return fail(LF_ERR_HIP, "counter init: %s", hipGetErrorString(e));
     }
     const bool filling = n_init < p.N;
     if (filling) {
@@ -232,26 +238,17 @@ int longflow_decode_step(longflow_cache_t *cache, const void *q, const void *k_n
     }
     hipStream_t s = (hipStream_t)hip_stream;
     hipEvent_t *ev = nullptr;
-    if (c->prof_used < c->prof_cap) ev = &c->prof_events[4 * (size_t)c->prof_used++];
+    if (c->prof_used < c->prof_cap) ev = &c->prof_events[2 * (size_t)c->prof_used++];
+    if (ev) (void)hipEventRecord(ev[0], s);
     hipError_t e;
     if (p.use_unit) {
-        // the whole step is one kernel: it is reported in the "streaming pass" slot
-        if (ev) (void)hipEventRecord(ev[1], s);
         e = launch_unit_mfma(p, q, k_new, v_new, n, out, evict_idx, s);
-        if (e != hipSuccess) return fail(LF_ERR_HIP, "fused launch: %s", hipGetErrorString(e));
-        if (ev) (void)hipEventRecord(ev[2], s);
     } else {
-        if (ev) (void)hipEventRecord(ev[0], s);
-        e = launch_insert(p, q, k_new, v_new, s);
-        if (e != hipSuccess) return fail(LF_ERR_HIP, "insert launch: %s", hipGetErrorString(e));
-        if (ev) (void)hipEventRecord(ev[1], s);
-        e = p.use_mfma ? launch_split_mfma(p, q, n, s) : launch_split_valu(p, q, n, s);
-        if (e != hipSuccess) return fail(LF_ERR_HIP, "split launch: %s", hipGetErrorString(e));
-        if (ev) (void)hipEventRecord(ev[2], s);
-        e = launch_finish(p, q, n, out, evict_idx, s);
-        if (e != hipSuccess) return fail(LF_ERR_HIP, "finish launch: %s", hipGetErrorString(e));
-        if (ev) (void)hipEventRecord(ev[3], s);
+        const StepIo io = {q, k_new, v_new, out, evict_idx};
+        e = p.use_mfma ? launch_split_mfma(p, io, n, s) : launch_split_valu(p, io, n, s);
     }
+    if (e != hipSuccess) return fail(LF_ERR_HIP, "decode launch: %s", hipGetErrorString(e));
+    if (ev) (void)hipEventRecord(ev[1], s);
     c->count = n;
     c->stepped = true;
     return LF_OK;
@@ -298,7 +295,7 @@ int longflow_profile_begin(longflow_cache_t *cache, int32_t max_steps)
     if (!c) return fail(LF_ERR_STATE, "invalid or destroyed cache handle");
     if (max_steps < 1 || max_steps > (1 << 20)) return fail(LF_ERR_INVALID_ARG, "max_steps out of range");
     drop_events(c);
-    c->prof_events.resize(4 * (size_t)max_steps);
+    c->prof_events.resize(2 * (size_t)max_steps);
     for (size_t i = 0; i < c->prof_events.size(); ++i) {
         hipError_t e = hipEventCreateWithFlags(&c->prof_events[i], hipEventDisableSystemFence);
         if (e != hipSuccess) {
@@ -317,18 +314,15 @@ int longflow_profile_end(longflow_cache_t *cache, float *kernel_ms, int32_t *ste
     longflow_cache *c = checked(cache);
     if (!c) return fail(LF_ERR_STATE, "invalid or destroyed cache handle");
     if (!kernel_ms || !steps) return fail(LF_ERR_INVALID_ARG, "kernel_ms/steps is NULL");
-    kernel_ms[0] = kernel_ms[1] = kernel_ms[2] = 0.f;
+    *kernel_ms = 0.f;
     *steps = c->prof_used;
     int rc = LF_OK;
-    const int k0 = c->plan.use_unit ? 1 : 0, k1 = c->plan.use_unit ? 2 : 3; // events recorded per step
     for (int i = 0; i < c->prof_used && rc == LF_OK; ++i) {
-        hipEvent_t *ev = &c->prof_events[4 * (size_t)i];
-        hipError_t e = hipEventSynchronize(ev[k1]);
-        for (int k = k0; k < k1 && e == hipSuccess; ++k) {
-            float ms = 0.f;
-            e = hipEventElapsedTime(&ms, ev[k], ev[k + 1]);
-            kernel_ms[k] += ms;
-        }
+        hipEvent_t *ev = &c->prof_events[2 * (size_t)i];
+        hipError_t e = hipEventSynchronize(ev[1]);
+        float ms = 0.f;
+        if (e == hipSuccess) e = hipEventElapsedTime(&ms, ev[0], ev[1]);
+        *kernel_ms += ms;
         if (e != hipSuccess) rc = fail(LF_ERR_HIP, "event timing: %s", hipGetErrorString(e));
     }
     drop_events(c);

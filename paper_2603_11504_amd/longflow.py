@@ -148,11 +148,11 @@ class LongFlowCache:
         _check(lib().longflow_profile_begin(self._h, max_steps))
 
     def profile_end(self):
-        """-> ({"insert": ms, "split": ms, "finish": ms} summed over the recorded steps, steps)."""
-        ms = (ctypes.c_float * 3)()
+        """-> (kernel milliseconds summed over the recorded steps, number of steps)."""
+        ms = ctypes.c_float()
         n = ctypes.c_int32()
-        _check(lib().longflow_profile_end(self._h, ms, ctypes.byref(n)))
-        return {"insert": ms[0], "split": ms[1], "finish": ms[2]}, int(n.value)
+        _check(lib().longflow_profile_end(self._h, ctypes.byref(ms), ctypes.byref(n)))
+        return float(ms.value), int(n.value)
 
     @property
     def valid_count(self):
