@@ -1,11 +1,12 @@
 #!/usr/bin/env python3
 """Benchmark of the LongFlow fused decode step on one MI355X.
 
-    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload cfg3] [--valu]
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload cfg3] [--valu|--split|--unit]
+    python bench.py --report            # every workload + the uncompressed twin, as a table
 
-A "step" is one decode step of the whole workload: every layer's cache advances by
-one token (insert + attention + scores + eviction), i.e. `layers` C-ABI calls.  Inputs
-are seeded synthetic tensors already resident in HBM.  Prints ONE JSON line.
+A "step" is one decode step of the whole workload: every layer's cache advances by one
+token (insert + attention + scores + eviction), i.e. `layers` C-ABI calls.  Inputs are
+seeded synthetic tensors already resident in HBM.  Default mode prints ONE JSON line.
 """
 from __future__ import annotations
 
@@ -19,9 +20,10 @@ ROOT = os.path.dirname(os.path.abspath(__file__))
 sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBS = 8000.0  # MI355X published peak HBM3E bandwidth
+DEFAULT_STEPS = {0: 512, 1: 1024, 2: 100, 3: 256, 4: 50}
 
 # HBM bytes per launch of the streaming kernel measured with rocprofv3 --pmc
-# (FETCH_SIZE / WRITE_SIZE, scaled by a copy kernel of known size); see profiles/.
+# (FETCH_SIZE / WRITE_SIZE, scaled by copy kernels of known size); see profiles/.
 MEASURED_TRAFFIC = {
     ("cfg3_bf16_b64_28x4_d128_n8192_l28", "unit_mfma_kernel"): {"read_bytes": 1058323 * 1024, "write_bytes": 1076 * 1024,
                                                                 "source": "profiles/unit_mfma_kernel_cfg3.txt"},
@@ -37,17 +39,25 @@ def parse():
     ap.add_argument("--warmup", type=int, default=3)
     ap.add_argument("--workload", default="cfg3", help="cfg0..cfg4 (BASELINE.json configs)")
     ap.add_argument("--valu", action="store_true", help="bf16: vector-ALU kernel instead of matrix cores")
-    ap.add_argument("--split", action="store_true", help="force the split-K (3-launch) path")
+    ap.add_argument("--split", action="store_true", help="force the split-K path")
     ap.add_argument("--unit", action="store_true", help="force the one-workgroup-per-unit fused path")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run one 1 GiB device copy (a kernel of known traffic, to scale rocprofv3 byte counters)")
     ap.add_argument("--pool", type=int, default=0,
                     help="distinct input steps cycled through (0 = one per executed step, no repeats)")
+    ap.add_argument("--report", action="store_true", help="all workloads and the uncompressed twin, as a table")
     return ap.parse_args()
 
 
-def cpu_baseline(wl, caches_layer0, target_s=12.0):
+def kernel_name(wl, flags):
+    from paper_2603_11504_amd import longflow as lf
+    mfma = wl.dtype == "bf16" and wl.head_dim == 128 and not (flags & lf.LF_FLAG_FORCE_VALU)
+    fused = mfma and not (flags & lf.LF_FLAG_FORCE_SPLIT) and ((flags & lf.LF_FLAG_FORCE_UNIT) or wl.units >= 96)
+    return "unit_mfma_kernel" if fused else ("split_mfma_kernel" if mfma else "split_valu_kernel")
+
+
+def cpu_baseline(wl, cache0, target_s=12.0):
     """The float64 oracle, as it stands, timed on this host on a bounded sample of units."""
     import numpy as np
     import torch
@@ -59,10 +69,10 @@ def cpu_baseline(wl, caches_layer0, target_s=12.0):
     nu = min(wl.units, max(4 * threads, 64))
     rng = np.random.default_rng(wl.seed)
     units = np.sort(rng.choice(wl.units, size=nu, replace=False))
-    sel = torch.as_tensor(units, device=caches_layer0.k_cache.device)
-    n = caches_layer0.valid_count
-    ku = caches_layer0.k_cache.reshape(wl.units, N, D)[sel][:, : n - 1].reshape(nu, 1, n - 1, D)
-    vu = caches_layer0.v_cache.reshape(wl.units, N, D)[sel][:, : n - 1].reshape(nu, 1, n - 1, D)
+    sel = torch.as_tensor(units, device=cache0.k_cache.device)
+    n = cache0.valid_count
+    ku = cache0.k_cache.reshape(wl.units, N, D)[sel][:, : n - 1].reshape(nu, 1, n - 1, D)
+    vu = cache0.v_cache.reshape(wl.units, N, D)[sel][:, : n - 1].reshape(nu, 1, n - 1, D)
     ora = oracle.OracleCache(nu, G, 1, D, N)
     ora.init(W.to_f64(ku), W.to_f64(vu))
     g = np.random.default_rng(1)
@@ -73,35 +83,25 @@ def cpu_baseline(wl, caches_layer0, target_s=12.0):
         ora.step(q, k, v)
         t_total += time.perf_counter() - t0
         steps += 1
-    unit_steps = nu * steps
-    full_step_s = t_total / unit_steps * wl.units * wl.layers      # linear extrapolation
+    full_step_s = t_total / (nu * steps) * wl.units * wl.layers      # linear extrapolation
     return {"value": wl.batch / full_step_s, "unit": "tokens/s", "cores": min(threads, nu), "kind": "oracle",
             "sample": f"{nu} of {wl.units * wl.layers} (layer,batch,kv-head) units x {steps} steps at n={n}, "
                       f"{t_total:.1f} s, scaled linearly to the full step",
             "ms_per_step": full_step_s * 1e3}
 
 
-def main():
-    a = parse()
-    if a.gpus != 1:
-        print("bench.py: this build runs on ONE GPU (units are independent; see DESIGN.md on sharding); "
-              f"--gpus {a.gpus} is not supported", file=sys.stderr)
-        sys.exit(2)
+def measure(wl, flags, steps, warmup, pool=0, with_cpu=False, calibrate_copy=False, per_step_times=False):
+    """Build the resident state, warm up, time `steps` steps, then the same again with kernel events."""
     import torch
     from paper_2603_11504_amd import longflow as lf
     from paper_2603_11504_amd import workloads as W
 
-    idx = int(a.workload.replace("cfg", ""))
-    wl = W.CONFIGS[idx]
-    steps = a.steps if a.steps is not None else {0: 512, 1: 1024, 2: 100, 3: 256, 4: 50}[idx]
     dev = torch.device("cuda:0")
     torch.cuda.set_device(dev)
-    flags = lf.LF_FLAG_FORCE_VALU if (a.valu and wl.dtype == "bf16") else 0
-    flags |= lf.LF_FLAG_FORCE_SPLIT if a.split else 0
-    flags |= lf.LF_FLAG_FORCE_UNIT if a.unit else 0
     dt = W.torch_dtype(wl)
+    attention_only = bool(flags & lf.LF_FLAG_ATTENTION_ONLY)
 
-    # ---- resident state: one cache per layer, pre-filled to N-1 rows where the workload says so
+    # one cache per layer, pre-filled to N-1 rows where the workload says so (to N for plain attention)
     caches = []
     for layer in range(wl.layers):
         k0, v0 = W.device_prefill(wl, dev, layer)
@@ -109,25 +109,28 @@ def main():
                                        flags=flags, device=dev, k_init=k0, v_init=v0))
         del k0, v0
     # empty-start workloads fill first so that the timed steps are evicting steps
-    fill = wl.budget - wl.n_init - 1
-    warm = max(a.warmup, 1) + max(fill, 0)
+    fill = 0 if attention_only else wl.budget - wl.n_init - 1
+    warm = max(warmup, 1) + max(fill, 0)
     # every executed step gets its own q/k/v (repeating inputs would plant bit-identical
     # rows in the cache, i.e. exact score ties that the real workload does not have)
-    npool = a.pool if a.pool > 0 else warm + 2 * steps
-    pool = [[W.device_step(wl, t, dev, layer) for layer in range(wl.layers)] for t in range(npool)]
+    npool = pool if pool > 0 else warm + 2 * steps
+    inputs = [[W.device_step(wl, t, dev, layer) for layer in range(wl.layers)] for t in range(npool)]
     torch.cuda.synchronize()
 
-    def run(nsteps, t0=0):
+    def run(nsteps, t0=0, events=None):
         for t in range(t0, t0 + nsteps):
-            inputs = pool[t % npool]
+            if events is not None:
+                events[t - t0][0].record()
             for layer, c in enumerate(caches):
-                q, k, v = inputs[layer]
+                q, k, v = inputs[t % npool][layer]
                 c.decode_step(q, k, v)
+            if events is not None:
+                events[t - t0][1].record()
 
     run(warm)
     torch.cuda.synchronize()
     assert all(c.valid_count == wl.budget for c in caches)
-    if a.calibrate_copy:
+    if calibrate_copy:
         src = torch.empty(1 << 30, dtype=torch.uint8, device=dev).random_()   # elementwise kernel: writes 1 GiB
         dst = torch.empty_like(src)
         dst.copy_(src)                                                        # blit kernel: reads 1 GiB, writes 1 GiB
@@ -137,50 +140,107 @@ def main():
     t0 = time.perf_counter()
     run(steps, warm)
     torch.cuda.synchronize()
-    dt_s = time.perf_counter() - t0
-    ms_per_step = dt_s / steps * 1e3
+    ms_per_step = (time.perf_counter() - t0) / steps * 1e3
     calls = steps * wl.layers
 
-    # ---- same number of steps again with HIP events around each launch (kernel durations)
+    # same number of steps again with HIP events around each launch (kernel durations)
     for c in caches:
         c.profile_begin(steps)
-    run(steps, warm + steps)
+    evs = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(steps)] \
+        if per_step_times else None
+    run(steps, warm + steps, evs)
     ksum = 0.0
     for c in caches:
         ms, n = c.profile_end()
         assert n == steps
         ksum += ms
     kernel_us = ksum / calls * 1e3
+    step_us = sorted(a.elapsed_time(b) * 1e3 for a, b in evs) if evs else None
 
     bytes_call = wl.kv_bytes_per_call()
-    mfma = wl.dtype == "bf16" and wl.head_dim == 128 and not (flags & lf.LF_FLAG_FORCE_VALU)
-    fused = mfma and not (flags & lf.LF_FLAG_FORCE_SPLIT) and ((flags & lf.LF_FLAG_FORCE_UNIT) or wl.units >= 96)
-    split_name = "unit_mfma_kernel" if fused else ("split_mfma_kernel" if mfma else "split_valu_kernel")
-    achieved = bytes_call / (kernel_us * 1e-6) / 1e9
+    kname = kernel_name(wl, flags)
+    res = {
+        "ms_per_step": ms_per_step, "warm": warm, "calls": calls, "kernel_us": kernel_us, "kernel": kname,
+        "bytes_call": bytes_call, "tokens_per_s": wl.batch / (ms_per_step * 1e-3),
+        "step_GBs": bytes_call * wl.layers / (ms_per_step * 1e-3) / 1e9,
+        "kernel_GBs": bytes_call / (kernel_us * 1e-6) / 1e9, "step_us_sorted": step_us,
+    }
+    if with_cpu:
+        res["cpu_baseline"] = cpu_baseline(wl, caches[0])
+    for c in caches:
+        c.close()
+    del caches, inputs
+    torch.cuda.empty_cache()
+    return res
+
+
+def report(a):
+    """Table over all BASELINE workloads plus the uncompressed twin of cfg4 (plain attention
+    over all 81920 tokens, the kernel-level analogue of the paper's FullKV comparison)."""
+    from paper_2603_11504_amd import longflow as lf
+    from paper_2603_11504_amd import workloads as W
+    rows = [(W.CONFIGS[i], 0, DEFAULT_STEPS[i]) for i in range(5)]
+    twin = W.scaled(W.CONFIGS[4], name="cfg4_uncompressed_twin_n81920", budget=81920, n_init=81920)
+    rows.append((twin, lf.LF_FLAG_ATTENTION_ONLY, 10))
+    print(f"{'workload':38s} {'kernel':18s} {'us/step p10':>11s} {'median':>9s} {'p90':>9s} {'us/call':>9s} "
+          f"{'GB/s step':>10s} {'% peak':>7s} {'GB/s kernel':>11s} {'% peak':>7s} {'tokens/s':>10s}")
+    for wl, flags, steps in rows:
+        if a.steps:
+            steps = a.steps
+        r = measure(wl, flags, steps, a.warmup, per_step_times=True)
+        s = r["step_us_sorted"]
+        p10, med, p90 = s[len(s) // 10], s[len(s) // 2], s[(9 * len(s)) // 10]
+        print(f"{wl.name:38s} {r['kernel']:18s} {p10:11.1f} {med:9.1f} {p90:9.1f} {r['ms_per_step'] * 1e3 / wl.layers:9.1f} "
+              f"{r['step_GBs']:10.1f} {100 * r['step_GBs'] / HBM_PEAK_GBS:7.1f} {r['kernel_GBs']:11.1f} "
+              f"{100 * r['kernel_GBs'] / HBM_PEAK_GBS:7.1f} {r['tokens_per_s']:10.0f}", flush=True)
+
+
+def main():
+    a = parse()
+    if a.gpus != 1:
+        print("bench.py: this build runs on ONE GPU (units are independent; see DESIGN.md on sharding); "
+              f"--gpus {a.gpus} is not supported", file=sys.stderr)
+        sys.exit(2)
+    from paper_2603_11504_amd import longflow as lf
+    from paper_2603_11504_amd import workloads as W
+
+    if a.report:
+        report(a)
+        return
+    idx = int(a.workload.replace("cfg", ""))
+    wl = W.CONFIGS[idx]
+    steps = a.steps if a.steps is not None else DEFAULT_STEPS[idx]
+    flags = lf.LF_FLAG_FORCE_VALU if (a.valu and wl.dtype == "bf16") else 0
+    flags |= lf.LF_FLAG_FORCE_SPLIT if a.split else 0
+    flags |= lf.LF_FLAG_FORCE_UNIT if a.unit else 0
+    r = measure(wl, flags, steps, a.warmup, pool=a.pool, with_cpu=not a.no_cpu_baseline,
+                calibrate_copy=a.calibrate_copy)
+    kname = r["kernel"]
     out = {
         "metric": "decode_tokens_per_s",
-        "value": wl.batch / (ms_per_step * 1e-3),
+        "value": r["tokens_per_s"],
         "unit": "tokens/s",
-        "n_gpus": 1, "steps": steps, "warmup": warm, "ms_per_step": ms_per_step,
+        "n_gpus": 1, "steps": steps, "warmup": r["warm"], "ms_per_step": r["ms_per_step"],
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "f32" if wl.dtype == "f32" else "bf16 storage, f32 accumulate",
         "data": "synthetic",
         "config": {"workload": wl.name, "batch": wl.batch, "q_heads": wl.q_heads, "kv_heads": wl.kv_heads,
                    "head_dim": wl.head_dim, "budget": wl.budget, "layers": wl.layers,
-                   "calls_per_step": wl.layers, "kernel_path": {"unit_mfma_kernel": "fused one-launch, matrix cores",
+                   "calls_per_step": wl.layers,
+                   "kernel_path": {"unit_mfma_kernel": "fused one-launch, matrix cores",
                                    "split_mfma_kernel": "split-K, matrix cores",
-                                   "split_valu_kernel": "split-K, vector ALU"}[split_name]},
-        "us_per_call": ms_per_step * 1e3 / wl.layers,
-        "step_hbm_GBs": bytes_call * wl.layers / (ms_per_step * 1e-3) / 1e9,
-        "step_hbm_frac": bytes_call * wl.layers / (ms_per_step * 1e-3) / 1e9 / HBM_PEAK_GBS,
-        "kernel_us": kernel_us,
-        "roofline": {"bound": "hbm", "kernel": split_name, "achieved": achieved, "peak": HBM_PEAK_GBS,
-                     "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS,
-                     "bytes_per_launch": bytes_call, "avg_launch_us": kernel_us,
-                     "traffic": MEASURED_TRAFFIC.get((wl.name, split_name))},
+                                   "split_valu_kernel": "split-K, vector ALU"}[kname]},
+        "us_per_call": r["ms_per_step"] * 1e3 / wl.layers,
+        "step_hbm_GBs": r["step_GBs"],
+        "step_hbm_frac": r["step_GBs"] / HBM_PEAK_GBS,
+        "kernel_us": r["kernel_us"],
+        "roofline": {"bound": "hbm", "kernel": kname, "achieved": r["kernel_GBs"], "peak": HBM_PEAK_GBS,
+                     "unit": "GB/s", "frac": r["kernel_GBs"] / HBM_PEAK_GBS,
+                     "bytes_per_launch": r["bytes_call"], "avg_launch_us": r["kernel_us"],
+                     "traffic": MEASURED_TRAFFIC.get((wl.name, kname))},
     }
-    if not a.no_cpu_baseline:
-        out["cpu_baseline"] = cpu_baseline(wl, caches[0])
+    if "cpu_baseline" in r:
+        out["cpu_baseline"] = r["cpu_baseline"]
     print(json.dumps(out))
 
 

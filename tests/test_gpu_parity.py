@@ -215,3 +215,39 @@ def test_full_cache_needs_a_pending_slot():
     gpu.decode_step(q, k, v)
     torch.cuda.synchronize()
     assert torch.equal(gpu.k_cache[0, 0, 9], k[0, 0])
+
+
+# ------------------------------------------------------------------ HIP graph capture
+
+@pytest.mark.parametrize("flags", [lf.LF_FLAG_FORCE_SPLIT, lf.LF_FLAG_FORCE_UNIT], ids=["split", "unit"])
+def test_decode_steps_replayed_from_a_hip_graph_match_eager(flags):
+    # a full cache advances by pure kernel launches (no allocation, no memset, no host sync), so a
+    # caller may capture steady-state steps in a HIP graph; every replay must equal the eager path
+    wl = _small("graph", "bf16", 4, 28, 4, 128, 1024, n_init=1023, steps=8, seed=71)
+    k0, v0 = W.host_prefill(wl)
+    mk = lambda: lf.LongFlowCache(wl.batch, wl.q_heads, wl.kv_heads, wl.head_dim, wl.budget, flags=flags,
+                                  k_init=W.to_torch(k0, wl, "cuda"), v_init=W.to_torch(v0, wl, "cuda"))
+    eager, graphed = mk(), mk()
+    qs, ks, vs = (torch.empty_like(W.to_torch(x, wl, "cuda")) for x in W.host_step(wl, 0))
+    for t in range(2):                                   # fill completes, kernels are loaded
+        for dst, src in zip((qs, ks, vs), W.host_step(wl, t)):
+            dst.copy_(W.to_torch(src, wl, "cuda"))
+        eager.decode_step(qs, ks, vs)
+        graphed.decode_step(qs, ks, vs)
+    torch.cuda.synchronize()
+    g = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(g):
+        graphed.decode_step(qs, ks, vs)
+    # capturing does not execute: eager has to catch up with nothing
+    for t in range(2, 8):
+        for dst, src in zip((qs, ks, vs), W.host_step(wl, t)):
+            dst.copy_(W.to_torch(src, wl, "cuda"))
+        o_e, i_e = eager.decode_step(qs, ks, vs)
+        o_e, i_e = o_e.clone(), i_e.clone()
+        g.replay()
+        torch.cuda.synchronize()
+        assert torch.equal(o_e.view(torch.int16), graphed.out.view(torch.int16)), f"replay {t}"
+        assert torch.equal(i_e, graphed.evict_idx), f"replay {t}"
+        junk = torch.randn(1 << 20, device="cuda").sum().item()   # unrelated eager work between replays
+        assert junk == junk
+    assert torch.equal(eager.k_cache.view(torch.int16), graphed.k_cache.view(torch.int16))
