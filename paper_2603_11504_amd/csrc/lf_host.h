@@ -21,12 +21,14 @@ struct Plan {
     int C;             // number of splits covering N
     int ntiles;        // ceil(N / kTile)
     bool use_mfma;     // bf16, head_dim 128: matrix-core kernels
-    bool use_unit;     // one workgroup per unit, whole step fused in one launch
+    bool use_unit;     // unit-resident fused kernel: whole step in one launch
+    int unit_S;        // ... with this many cooperating workgroups per unit
     // device pointers (caller-owned)
     void *k_cache, *v_cache;
     // carved out of the caller's workspace
     int32_t *pending;  // [units]
-    int32_t *arrive;   // [units] split-path arrival counters, zero between steps
+    int32_t *arrive;   // [units] arrival counters of cooperating workgroups, zero between steps
+    int32_t *dumped;   // [units] code-dump counters of the unit-resident kernel, zero between steps
     void *q_last;      // [B][Hq][D] copy of the last step's query (for longflow_scores)
     float *part_m;     // [units][C][G]    split-local softmax reference (log2 domain)
     float *part_l;     // [units][C][G]    split-local denominator
@@ -40,7 +42,7 @@ struct Plan {
 };
 
 struct Layout {
-    size_t off_pending, off_arrive, off_q, off_part_m, off_part_l, off_part_o, off_fin_m, off_fin_l,
+    size_t off_pending, off_arrive, off_dumped, off_q, off_part_m, off_part_l, off_part_o, off_fin_m, off_fin_l,
         off_stash_w, off_stash_m, off_lu, total;
 };
 
@@ -57,7 +59,9 @@ struct StepIo {
 };
 hipError_t launch_split_valu(const Plan &p, const StepIo &io, int n, hipStream_t s);
 hipError_t launch_split_mfma(const Plan &p, const StepIo &io, int n, hipStream_t s);
-size_t unit_mfma_lds_bytes(int N, int G, bool stash);
+int unit_mfma_splits(int units, int N);
+int unit_mfma_split_len(int N, int S);
+size_t unit_mfma_lds_bytes(int N, int G, bool stash, int S);
 hipError_t launch_unit_mfma(const Plan &p, const void *q, const void *k_new, const void *v_new, int n,
                             void *out, int32_t *evict_idx, hipStream_t s);
 hipError_t launch_scores(const Plan &p, int n, float *scores, hipStream_t s);

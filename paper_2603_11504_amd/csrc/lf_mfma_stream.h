@@ -89,8 +89,8 @@ struct MfmaStreamer {
     // stash sinks
     uint16_t *gs_w;   // kStashGlobal: [tile][G][16 positions] bf16
     float *gs_m;      // kStashGlobal: [tile][G]
-    uint8_t *ls_code; // kStashLds: [G][code_stride] bytes, position order
-    float *ls_ref;    // kStashLds: [tile][G]
+    uint8_t *ls_code; // kStashLds: [G][code_stride] bytes, position order, counted from `start`
+    float *ls_ref;    // kStashLds: [tile][G], tiles counted from `start`
     int code_stride;
 
     __device__ __forceinline__ void init(const uint16_t *q_unit, int G_, int lane, float scale)
@@ -226,8 +226,8 @@ struct MfmaStreamer {
                 code = __builtin_amdgcn_cvt_pk_u8_f32(c, e, code);
             }
             if (r < G) {
-                *(uint32_t *)(ls_code + (size_t)r * code_stride + base + 4 * g) = code;
-                if (g == 0) ls_ref[(base / kTile) * G + r] = m;
+                *(uint32_t *)(ls_code + (size_t)r * code_stride + (base - start) + 4 * g) = code;
+                if (g == 0) ls_ref[((base - start) / kTile) * G + r] = m;
             }
         }
     }

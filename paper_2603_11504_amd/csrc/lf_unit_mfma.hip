@@ -1,23 +1,70 @@
 // Unit-resident fused decode step on the matrix cores (bf16, head_dim 128).
 //
-// One workgroup of 8 waves owns one (batch, KV head) unit for the whole call and does
-// every step of the path in a single launch, with no intermediate in device memory:
+// A (batch, KV head) unit is owned for the whole call by S workgroups of 8 waves
+// (S = 1 when there are enough units to fill the chip, else up to 8), and every step of
+// the path happens in ONE launch with no per-slot intermediate in device memory:
 //
-//   insert   the wave that owns the pending slot's tile writes k_new / v_new into it
-//   stream   all valid slots once: logits, online softmax, P V, ||v||_1     (eq. 1, eq. 6)
-//            leaving an 8-bit log2 code of u_i * p_h,i per (head, slot) in LDS
-//   merge    the 8 waves' softmax states -> M_h, L_h
-//   evict    screen every slot with the codes (bounds within a factor 2^(1/8)), re-score
-//            the few that can still be the minimum exactly in double precision, argmin
-//   output   merge the 8 waves' O through LDS, normalise, round to bf16
+//   insert   the wave that will stream the pending slot's tile writes k_new / v_new into it
+//   stream   this workgroup's share of the valid slots, once: logits, online softmax,
+//            P V (eq. 1), leaving an 8-bit log2 code of ||v_i||_1 * p_h,i per (head, slot)
+//            in LDS (eq. 6)
+//   merge    the 8 waves' softmax states; with S > 1 the workgroup publishes its partial
+//            (m, l, O) and the LAST workgroup of the unit to arrive merges the S partials
+//   evict    screen every slot with the codes (bounds within a factor 2^(1/8)), re-score the
+//            few that can still be the minimum exactly in double precision, argmin
+//   output   normalise, round to bf16
 //
-// Keeping the per-slot by-products in LDS matters on this chip: even a few percent of
-// HBM writes interleaved with the K/V read stream cost a quarter of the read bandwidth.
+// Keeping the per-slot by-products in LDS matters on this chip: even a few percent of HBM
+// writes interleaved with the K/V read stream cost a quarter of the read bandwidth.
+//
+// Cooperation protocol for S > 1 (no workgroup ever waits for one that is not already
+// running): each workgroup publishes its partial, fences, and bumps arrive[u].  All but
+// the last then copy their codes to a small (L2-resident) dump area, fence, and bump
+// dumped[u].  The last one merges the partials, waits (bounded) until S-1 dumps are
+// in -- their authors passed arrive[u] before it did, so they are running or done -- and
+// decides the eviction from its own LDS codes plus the dumps.  If the bounded wait ever
+// expired it would re-score every slot exactly instead of trusting incomplete dumps.
 #include "lf_mfma_stream.h"
 
 namespace lf {
 
 constexpr int kMaxCand = 256; // candidates listed in LDS; more than this falls back to a slow scan
+
+struct UnitArgs {
+    uint16_t *Kc, *Vc;                 // caches [units][N][128]
+    const uint16_t *q, *k_new, *v_new;
+    uint16_t *out, *q_last;
+    int32_t *pending, *evict_idx;
+    float *fin_m, *fin_l;              // [units][G] reference / denominator of the step
+    float *lu;                         // [units][ntiles*16] log2 ||v||_1, position order
+    // cooperation of S workgroups per unit (untouched when s_active == 1)
+    float *part_m, *part_l, *part_o;   // [units][S][16], [units][S][16], [units][S][G][128]
+    int32_t *arrive, *dumped;          // [units], zero between steps
+    uint8_t *gcode;                    // [units][G][gstride] dumped codes, absolute positions
+    float *gref;                       // [units][ntiles][G] dumped references
+    int n, N, G, ntiles;
+    int S, s_active, split_len;        // split_len: slots per workgroup, a multiple of 128
+    int code_stride, gstride;          // LDS / dump row strides in bytes
+    int merge_off;                     // byte offset of the O-merge area in dynamic LDS
+    float scale_log2;
+};
+
+// Device-scope coherent accesses for the little data that cooperating workgroups exchange.
+// Stores write through to the coherence point and loads bypass stale cached copies, so
+// publishing needs only "wait for my stores, then bump the counter": no L2 write-back
+// (buffer_wbl2) and no invalidate, which on this 8-XCD part cost far more than the
+// exchange itself (measured: 160 us with per-thread fences, 70 us with one fence pair
+// per workgroup, versus the numbers in the design notes for this scheme).
+template <typename T> __device__ __forceinline__ void st_agent(T *p, T v)
+{
+    __hip_atomic_store(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+template <typename T> __device__ __forceinline__ T ld_agent(const T *p)
+{
+    return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+// all of this thread's device-scope stores have reached the coherence point
+__device__ __forceinline__ void wait_stores() { asm volatile("s_waitcnt vmcnt(0)" ::: "memory"); }
 
 __device__ __forceinline__ double wave_sum_f64(double x)
 {
@@ -90,43 +137,45 @@ __device__ double exact_score_bf16(const uint16_t *__restrict__ krow, const uint
 }
 
 template <bool HILO, int STASH>
-__global__ __launch_bounds__(512, 1) void unit_mfma_kernel(
-    uint16_t *__restrict__ Kc, uint16_t *__restrict__ Vc, const uint16_t *__restrict__ q,
-    const uint16_t *__restrict__ k_new, const uint16_t *__restrict__ v_new, int n, int N, int G,
-    int code_stride, int ntiles, int32_t *__restrict__ pending, uint16_t *__restrict__ out,
-    int32_t *__restrict__ evict_idx, float *__restrict__ fin_m, float *__restrict__ fin_l,
-    uint16_t *__restrict__ q_last, float *__restrict__ lu, float scale_log2)
+__global__ __launch_bounds__(512, 1) void unit_mfma_kernel(const UnitArgs a)
 {
     constexpr int D = 128, NW = 8, OPAD = D + 4;
     extern __shared__ __align__(16) unsigned char smem[];
-    // LDS map: [codes G*code_stride][refs ntiles*G floats] ... later aliased by the O merge
+    // dynamic LDS: [codes G*code_stride][refs (split_len/16)*G floats]; the O-merge area
+    // [NW][16][OPAD] floats starts at merge_off (0 = aliases the codes, used after them)
     uint8_t *ls_code = smem;
-    float *ls_ref = (float *)(smem + (size_t)G * code_stride);
+    float *ls_ref = (float *)(smem + (size_t)a.G * a.code_stride);
+    float *sm_o = (float *)(smem + a.merge_off);
     __shared__ float sm_m[NW][16], sm_l[NW][16], sM[16], sL[16];
+    __shared__ float sW[8][16]; // weights of the S partials under the unit-wide reference
     __shared__ float red_f[NW];
     __shared__ double best_v[NW];
     __shared__ int best_i[NW];
-    __shared__ float qs[16][D];            // the query as floats, for the exact re-scoring
+    __shared__ float qs[16][D]; // the query as floats, for the exact re-scoring
     __shared__ int cand_list[kMaxCand];
-    __shared__ int cand_count;
+    __shared__ int cand_count, s_flag;
 
-    const int u = blockIdx.x;
+    const int n = a.n, N = a.N, G = a.G, s_active = a.s_active;
+    const int u = blockIdx.x / s_active, sp = blockIdx.x % s_active;
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int g = lane >> 4, r = lane & 15;
-    uint16_t *Ku = Kc + (size_t)u * N * D;
-    uint16_t *Vu = Vc + (size_t)u * N * D;
-    const uint16_t *qu = q + (size_t)u * G * D;
-    float *lu_u = lu + (size_t)u * ntiles * kTile;
+    const int start = sp * a.split_len;
+    const int end = min(start + a.split_len, n);
+    uint16_t *Ku = a.Kc + (size_t)u * N * D;
+    uint16_t *Vu = a.Vc + (size_t)u * N * D;
+    const uint16_t *qu = a.q + (size_t)u * G * D;
+    float *lu_u = a.lu + (size_t)u * a.ntiles * kTile;
+    const bool evicting = (STASH == kStashLds) && n == N;
 
     // ---- insert (Fig. 2 left): done by the wave that will stream that tile, so that its
     // own later loads of the row are ordered behind the stores
     if (STASH != kStashNone) {
-        const int slot = pending[u];
-        if (slot >= 0 && slot < N && ((slot / kTile) % NW) == wave) {
+        const int slot = a.pending[u];
+        if (slot >= start && slot < start + a.split_len && slot < N && (((slot - start) / kTile) % NW) == wave) {
             if (lane < 16)
-                *(u32x4 *)(Ku + (size_t)slot * D + 8 * lane) = *(const u32x4 *)(k_new + (size_t)u * D + 8 * lane);
-            // every 16-lane row sums |v_new| redundantly; rows 1 stores V, lane 32 the log2 norm
-            const u32x4 vv = *(const u32x4 *)(v_new + (size_t)u * D + 8 * r);
+                *(u32x4 *)(Ku + (size_t)slot * D + 8 * lane) = *(const u32x4 *)(a.k_new + (size_t)u * D + 8 * lane);
+            // every 16-lane row sums |v_new| redundantly; row 1 stores V, lane 32 the log2 norm
+            const u32x4 vv = *(const u32x4 *)(a.v_new + (size_t)u * D + 8 * r);
             float a1 = fabsf(bf16_lo(vv.x)) + fabsf(bf16_hi(vv.x)) + fabsf(bf16_lo(vv.y)) + fabsf(bf16_hi(vv.y)) +
                        fabsf(bf16_lo(vv.z)) + fabsf(bf16_hi(vv.z)) + fabsf(bf16_lo(vv.w)) + fabsf(bf16_hi(vv.w));
             a1 = row16_sum(a1);
@@ -138,15 +187,15 @@ __global__ __launch_bounds__(512, 1) void unit_mfma_kernel(
     }
 
     MfmaStreamer<NW, HILO, STASH> st;
-    st.init(qu, G, lane, scale_log2);
+    st.init(qu, G, lane, a.scale_log2);
     st.Ku = Ku;
     st.Vu = Vu;
-    st.start = 0;
-    st.end = n;
+    st.start = start;
+    st.end = end;
     st.lu_unit = lu_u;
     st.ls_code = ls_code;
     st.ls_ref = ls_ref;
-    st.code_stride = code_stride;
+    st.code_stride = a.code_stride;
     st.run(wave);
 
     // ---- merge the softmax states of the 8 waves
@@ -168,26 +217,114 @@ __global__ __launch_bounds__(512, 1) void unit_mfma_kernel(
         float Ls = 0.f;
 #pragma unroll
         for (int w = 0; w < NW; ++w) Ls += merge_weight(sm_m[w][tid], M) * sm_l[w][tid];
-        sM[tid] = M;
+        sM[tid] = M; // this workgroup's reference and denominator
         sL[tid] = Ls;
-        if (tid < G) {
-            fin_m[(size_t)u * G + tid] = M;
-            fin_l[(size_t)u * G + tid] = Ls;
-        }
     }
     __syncthreads();
+
+    // O of the 8 waves -> LDS, each under this workgroup's reference
+    auto stage_o = [&]() {
+        float a4[4];
+#pragma unroll
+        for (int v = 0; v < 4; ++v) a4[v] = merge_weight(sm_m[wave][4 * g + v], sM[4 * g + v]);
+#pragma unroll
+        for (int dd = 0; dd < 8; ++dd)
+#pragma unroll
+            for (int v = 0; v < 4; ++v)
+                sm_o[((size_t)wave * 16 + 4 * g + v) * OPAD + 8 * r + dd] = st.oacc[dd][v] * a4[v];
+    };
+
+    bool dumps_ok = true;
+    if (s_active > 1) {
+        // ---- publish this workgroup's partial (m, l, O) and count the arrival
+        stage_o();
+        __syncthreads();
+        const size_t pb = (size_t)u * a.S + sp;
+        for (int idx = tid; idx < G * D; idx += 512) {
+            const int h = idx / D, d = idx % D;
+            float acc = 0.f;
+#pragma unroll
+            for (int w = 0; w < NW; ++w) acc += sm_o[((size_t)w * 16 + h) * OPAD + d];
+            st_agent(&a.part_o[(pb * G + h) * D + d], acc);
+        }
+        if (tid < 16) { st_agent(&a.part_m[pb * 16 + tid], sM[tid]); st_agent(&a.part_l[pb * 16 + tid], sL[tid]); }
+        wait_stores();
+        __syncthreads(); // every thread's partials are visible device-wide before the arrival counts
+        if (tid == 0)
+            s_flag = (__hip_atomic_fetch_add(&a.arrive[u], 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) == s_active - 1);
+        __syncthreads();
+        if (!s_flag) {
+            if (evicting) { // leave the codes where the last workgroup will find them
+                const int len = (end - start + kTile - 1) / kTile * kTile; // whole tiles
+                for (int i = tid; i < G * (len / 4); i += 512) {
+                    const int h = i / (len / 4), j = i % (len / 4);
+                    st_agent((uint32_t *)(a.gcode + ((size_t)u * G + h) * a.gstride + start + 4 * j),
+                             *(const uint32_t *)(ls_code + (size_t)h * a.code_stride + 4 * j));
+                }
+                for (int i = tid; i < (len / kTile) * G; i += 512)
+                    st_agent(&a.gref[((size_t)u * a.ntiles + start / kTile) * G + i], ls_ref[i]);
+                wait_stores();
+                __syncthreads();
+                if (tid == 0) __hip_atomic_fetch_add(&a.dumped[u], 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            }
+            return;
+        }
+        // ---- last arriver: merge the S partials into the unit-wide softmax state.
+        // Device-scope loads are issued in batches (all first, then used): each one is a
+        // round trip to the coherence point, and an acquire fence instead (an L2 invalidate
+        // for the whole XCD) measured slower still.
+        if (tid < 16) {
+            float pm[8], pl[8];
+#pragma unroll
+            for (int s2 = 0; s2 < 8; ++s2) {
+                pm[s2] = -INFINITY;
+                pl[s2] = 0.f;
+                if (s2 < s_active) {
+                    pm[s2] = ld_agent(&a.part_m[((size_t)u * a.S + s2) * 16 + tid]);
+                    pl[s2] = ld_agent(&a.part_l[((size_t)u * a.S + s2) * 16 + tid]);
+                }
+            }
+            float M = -INFINITY;
+#pragma unroll
+            for (int s2 = 0; s2 < 8; ++s2) M = fmaxf(M, pm[s2]);
+            float Ls = 0.f;
+#pragma unroll
+            for (int s2 = 0; s2 < 8; ++s2) {
+                const float w = merge_weight(pm[s2], M);
+                sW[s2][tid] = w;
+                Ls += w * pl[s2];
+            }
+            sM[tid] = M;
+            sL[tid] = Ls;
+        }
+        if (evicting && tid == 0) { // bounded wait for the S-1 dumps (their authors are running or done)
+            int seen = 0;
+            for (int it = 0; it < (1 << 22); ++it) {
+                seen = __hip_atomic_load(&a.dumped[u], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                if (seen >= s_active - 1) break;
+                __builtin_amdgcn_s_sleep(8);
+            }
+            s_flag = (seen >= s_active - 1);
+        }
+        __syncthreads();
+        if (evicting) dumps_ok = s_flag != 0;
+    }
+    if (tid < G) {
+        a.fin_m[(size_t)u * G + tid] = sM[tid];
+        a.fin_l[(size_t)u * G + tid] = sL[tid];
+    }
 
     // ---- eviction decision (Sec. 3.2 last paragraph; Alg. 1 post-processing)
     if (STASH == kStashLds) {
         if (n < N) {
             if (tid == 0) {
-                pending[u] = n;
-                if (evict_idx) evict_idx[u] = n;
+                a.pending[u] = n;
+                if (a.evict_idx) a.evict_idx[u] = n;
             }
         } else {
-            // per (tile, head): factor that turns a decoded code into a normalised score term
-            const int nt = (n + kTile - 1) / kTile;
-            for (int i = tid; i < nt * G; i += 512) {
+            // own codes: per (tile, head) factor that turns a decoded code into a score term
+            const int my_tiles = (end - start + kTile - 1) / kTile;
+            for (int i = tid; i < my_tiles * G; i += 512) {
                 const int h = i % G;
                 ls_ref[i] = fast_exp2(kCodeBias + ls_ref[i] - sM[h]) / sL[h];
             }
@@ -197,22 +334,45 @@ __global__ __launch_bounds__(512, 1) void unit_mfma_kernel(
             // the lower-bound sums of its slots in registers, the block finds the smallest
             // upper bound, and a slot can be the true minimum only if
             //   2^(-1/8) * lb_sum <= 2^(1/8) * min ub_sum.
-            const int items = 4 * nt; // 4 positions each, whole tiles
+            const int items = 4 * ((n + kTile - 1) / kTile); // 4 positions each, whole tiles
             constexpr int kRegIters = 8; // 512 threads x 4 positions x 8 = 16384 slots held in registers
             const int iters = (items + 511) / 512;
             auto decode_item = [&](int item, float *ub4, float *lb4) {
                 const int tile = item >> 2;
+                const bool mine = tile * kTile >= start && tile * kTile < start + a.split_len;
 #pragma unroll
                 for (int e = 0; e < 4; ++e) ub4[e] = lb4[e] = 0.f;
-                for (int h = 0; h < G; ++h) {
-                    const uint32_t c4 = *(const uint32_t *)(ls_code + (size_t)h * code_stride + 4 * item);
-                    const float f = ls_ref[tile * G + h];
+                uint32_t c4s[kMaxGroup];
+                float fs[kMaxGroup];
+                if (mine) {
 #pragma unroll
-                    for (int e = 0; e < 4; ++e) {
-                        const uint32_t c = (c4 >> (8 * e)) & 255u;
-                        const float d = fast_exp2(-0.25f * (float)c) * f;
-                        ub4[e] += (c == 0u) ? INFINITY : d;
-                        lb4[e] += (c == 255u) ? 0.f : d;
+                    for (int h = 0; h < kMaxGroup; ++h)
+                        if (h < G) {
+                            c4s[h] = *(const uint32_t *)(ls_code + (size_t)h * a.code_stride + (4 * item - start));
+                            fs[h] = ls_ref[(tile - start / kTile) * G + h];
+                        }
+                } else { // another workgroup's dump: batch the device-scope loads, then use them
+                    float refs[kMaxGroup];
+#pragma unroll
+                    for (int h = 0; h < kMaxGroup; ++h)
+                        if (h < G) {
+                            c4s[h] = ld_agent((const uint32_t *)(a.gcode + ((size_t)u * G + h) * a.gstride + 4 * item));
+                            refs[h] = ld_agent(&a.gref[((size_t)u * a.ntiles + tile) * G + h]);
+                        }
+#pragma unroll
+                    for (int h = 0; h < kMaxGroup; ++h)
+                        if (h < G) fs[h] = fast_exp2(kCodeBias + refs[h] - sM[h]) / sL[h];
+                }
+#pragma unroll
+                for (int h = 0; h < kMaxGroup; ++h) {
+                    if (h < G) {
+#pragma unroll
+                        for (int e = 0; e < 4; ++e) {
+                            const uint32_t c = (c4s[h] >> (8 * e)) & 255u;
+                            const float d = fast_exp2(-0.25f * (float)c) * fs[h];
+                            ub4[e] += (c == 0u) ? INFINITY : d;
+                            lb4[e] += (c == 255u) ? 0.f : d;
+                        }
                     }
                 }
 #pragma unroll
@@ -241,7 +401,9 @@ __global__ __launch_bounds__(512, 1) void unit_mfma_kernel(
                 return x;
             };
             float ub_min = INFINITY;
-            if (iters <= kRegIters) {
+            if (!dumps_ok) {
+                if (tid == 0) cand_count = kMaxCand + 1; // distrust the codes: re-score everything
+            } else if (iters <= kRegIters) {
                 float lbs[kRegIters][4];
 #pragma unroll
                 for (int it = 0; it < kRegIters; ++it) {
@@ -307,56 +469,102 @@ __global__ __launch_bounds__(512, 1) void unit_mfma_kernel(
                 for (int w = 1; w < NW; ++w)
                     if (best_v[w] < v || (best_v[w] == v && best_i[w] < i)) { v = best_v[w]; i = best_i[w]; }
                 if (i < 0 || i >= N) i = 0; // non-finite scores: keep the slot in range
-                pending[u] = i;
-                if (evict_idx) evict_idx[u] = i;
+                a.pending[u] = i;
+                if (a.evict_idx) a.evict_idx[u] = i;
             }
         }
-        __syncthreads(); // the codes are dead from here on: their LDS is reused below
+        __syncthreads(); // the codes are dead from here on: their LDS may be reused below
     }
 
-    // ---- merge O of the 8 waves through LDS (aliases the code area), normalise, store
-    float *sm_o = (float *)smem; // [NW][16][OPAD]
-    {
-        float a4[4];
+    // ---- output: normalise, round to bf16, keep a copy of q for longflow_scores()
+    if (s_active == 1) {
+        stage_o();
+        __syncthreads();
+        for (int idx = tid; idx < G * D; idx += 512) {
+            const int h = idx / D, d = idx % D;
+            float acc = 0.f;
 #pragma unroll
-        for (int v = 0; v < 4; ++v) a4[v] = merge_weight(sm_m[wave][4 * g + v], sM[4 * g + v]);
+            for (int w = 0; w < NW; ++w) acc += sm_o[((size_t)w * 16 + h) * OPAD + d];
+            a.out[((size_t)u * G + h) * D + d] = (uint16_t)f32_to_bf16_bits(acc / sL[h]);
+            a.q_last[((size_t)u * G + h) * D + d] = qu[idx];
+        }
+    } else {
+        for (int idx = tid; idx < G * D; idx += 512) {
+            const int h = idx / D, d = idx % D;
+            float po[8];
 #pragma unroll
-        for (int dd = 0; dd < 8; ++dd)
+            for (int s2 = 0; s2 < 8; ++s2)
+                po[s2] = (s2 < s_active) ? ld_agent(&a.part_o[(((size_t)u * a.S + s2) * G + h) * D + d]) : 0.f;
+            float acc = 0.f;
 #pragma unroll
-            for (int v = 0; v < 4; ++v)
-                sm_o[((size_t)wave * 16 + 4 * g + v) * OPAD + 8 * r + dd] = st.oacc[dd][v] * a4[v];
-    }
-    __syncthreads();
-    for (int idx = tid; idx < G * D; idx += 512) {
-        const int h = idx / D, d = idx % D;
-        float acc = 0.f;
-#pragma unroll
-        for (int w = 0; w < NW; ++w) acc += sm_o[((size_t)w * 16 + h) * OPAD + d];
-        out[((size_t)u * G + h) * D + d] = (uint16_t)f32_to_bf16_bits(acc / sL[h]);
-        q_last[((size_t)u * G + h) * D + d] = qu[idx];
+            for (int s2 = 0; s2 < 8; ++s2) acc += (s2 < s_active) ? sW[s2][h] * po[s2] : 0.f;
+            a.out[((size_t)u * G + h) * D + d] = (uint16_t)f32_to_bf16_bits(acc / sL[h]);
+            a.q_last[((size_t)u * G + h) * D + d] = qu[idx];
+        }
+        if (tid == 0) { st_agent(&a.arrive[u], 0); st_agent(&a.dumped[u], 0); } // ready for the next step
     }
 }
 
-size_t unit_mfma_lds_bytes(int N, int G, bool stash)
+// ---------------------------------------------------------------------------------------
+// host side
+// ---------------------------------------------------------------------------------------
+static const size_t kMergeBytes = (size_t)8 * 16 * (128 + 4) * sizeof(float);
+
+static size_t code_bytes(int slots, int G)
 {
-    const size_t merge = (size_t)8 * 16 * (128 + 4) * sizeof(float);
-    if (!stash) return merge;
-    const size_t code_stride = ((size_t)N + 63) / 64 * 64;
-    const size_t ntiles = ((size_t)N + kTile - 1) / kTile;
-    const size_t codes = (size_t)G * code_stride + ntiles * G * sizeof(float);
-    return codes > merge ? codes : merge;
+    const size_t stride = ((size_t)slots + 63) / 64 * 64;
+    return (size_t)G * stride + ((size_t)slots / kTile + 1) * G * sizeof(float);
+}
+
+// workgroups per unit: one when the units alone fill the chip, else enough to put a
+// workgroup on (about) every compute unit, each with at least 512 slots
+int unit_mfma_splits(int units, int N)
+{
+    if (units >= 192) return 1;
+    int S = 256 / units;
+    if (S > 8) S = 8;
+    while (S > 1 && (N + S - 1) / S < 512) --S;
+    return S < 1 ? 1 : S;
+}
+
+int unit_mfma_split_len(int N, int S)
+{
+    const int per = (N + S - 1) / S;
+    return (per + 127) / 128 * 128;
+}
+
+size_t unit_mfma_lds_bytes(int N, int G, bool stash, int S)
+{
+    if (!stash) return kMergeBytes;
+    const size_t codes = code_bytes(unit_mfma_split_len(N, S), G);
+    if (S == 1) return codes > kMergeBytes ? codes : kMergeBytes; // merge area aliases the codes
+    return (codes + 255) / 256 * 256 + kMergeBytes;
 }
 
 hipError_t launch_unit_mfma(const Plan &p, const void *q, const void *k_new, const void *v_new, int n,
                             void *out, int32_t *evict_idx, hipStream_t s)
 {
     const bool stash = !(p.flags & 1u);
-    size_t lds = unit_mfma_lds_bytes(p.N, p.G, stash);
+    UnitArgs a;
+    a.Kc = (uint16_t *)p.k_cache; a.Vc = (uint16_t *)p.v_cache;
+    a.q = (const uint16_t *)q; a.k_new = (const uint16_t *)k_new; a.v_new = (const uint16_t *)v_new;
+    a.out = (uint16_t *)out; a.q_last = (uint16_t *)p.q_last;
+    a.pending = p.pending; a.evict_idx = evict_idx;
+    a.fin_m = p.fin_m; a.fin_l = p.fin_l; a.lu = p.lu;
+    a.part_m = p.part_m; a.part_l = p.part_l; a.part_o = p.part_o;
+    a.arrive = p.arrive; a.dumped = p.dumped;
+    a.gcode = (uint8_t *)p.stash_w; a.gref = p.stash_m;
+    a.n = n; a.N = p.N; a.G = p.G; a.ntiles = p.ntiles;
+    a.S = p.unit_S; a.split_len = unit_mfma_split_len(p.N, p.unit_S);
+    a.s_active = (n + a.split_len - 1) / a.split_len;
+    a.code_stride = (a.split_len + 63) / 64 * 64;
+    a.gstride = p.ntiles * kTile;
+    size_t lds = unit_mfma_lds_bytes(p.N, p.G, stash, p.unit_S);
+    a.merge_off = (stash && p.unit_S > 1) ? (int)(lds - kMergeBytes) : 0;
+    a.scale_log2 = 1.4426950408889634f / sqrtf(128.f);
     // With at most a few workgroups per compute unit, ask for more than half of the
     // CU's LDS so that no CU is handed two of them while another one idles.
-    if (p.units <= 2 * 256 && lds < 81 * 1024) lds = 81 * 1024;
-    const int code_stride = (p.N + 63) / 64 * 64;
-    const float scale_log2 = 1.4426950408889634f / sqrtf(128.f);
+    if ((long)p.units * a.s_active <= 2 * 256 && lds < 81 * 1024) lds = 81 * 1024;
     static bool attr_done[2] = {false, false};
 #define LF_UNIT(STASH, IDX)                                                                          \
     do {                                                                                              \
@@ -366,11 +574,7 @@ hipError_t launch_unit_mfma(const Plan &p, const void *q, const void *k_new, con
             if (e != hipSuccess) return e;                                                            \
             attr_done[IDX] = true;                                                                    \
         }                                                                                             \
-        hipLaunchKernelGGL((unit_mfma_kernel<true, STASH>), dim3(p.units), dim3(512), lds, s,         \
-                           (uint16_t *)p.k_cache, (uint16_t *)p.v_cache, (const uint16_t *)q,         \
-                           (const uint16_t *)k_new, (const uint16_t *)v_new, n, p.N, p.G, code_stride, \
-                           p.ntiles, p.pending, (uint16_t *)out, evict_idx, p.fin_m, p.fin_l,         \
-                           (uint16_t *)p.q_last, p.lu, scale_log2);                                         \
+        hipLaunchKernelGGL((unit_mfma_kernel<true, STASH>), dim3(p.units * a.s_active), dim3(512), lds, s, a); \
     } while (0)
     if (stash) LF_UNIT(kStashLds, 0); else LF_UNIT(kStashNone, 1);
 #undef LF_UNIT

@@ -25,8 +25,6 @@ static int fail(int code, const char *fmt, ...)
 
 static size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
 
-// from this many units on, one workgroup per unit keeps the chip busy (256 CUs)
-static const int kUnitMinUnits = 96;
 
 void choose_splits(int units, int N, int *L, int *C)
 {
@@ -74,8 +72,8 @@ static int validate(const lf_config *cfg)
         return fail(LF_ERR_INVALID_ARG, "FORCE_SPLIT and FORCE_UNIT exclude each other");
     if (cfg->flags & LF_FLAG_FORCE_UNIT) {
         if (!mfma) return fail(LF_ERR_UNSUPPORTED, "FORCE_UNIT needs bf16, head_dim 128 and the matrix-core kernel");
-        if (unit_mfma_lds_bytes(cfg->budget, G, !(cfg->flags & LF_FLAG_ATTENTION_ONLY)) > kUnitLdsLimit)
-            return fail(LF_ERR_UNSUPPORTED, "FORCE_UNIT: budget %d x group %d does not fit the per-unit LDS stash", cfg->budget, G);
+        if (unit_mfma_lds_bytes(cfg->budget, G, !(cfg->flags & LF_FLAG_ATTENTION_ONLY), 1) > kUnitLdsLimit)
+            return fail(LF_ERR_UNSUPPORTED, "FORCE_UNIT: budget %d x group %d does not fit one workgroup's LDS", cfg->budget, G);
     }
     return LF_OK;
 }
@@ -89,9 +87,15 @@ static void fill_plan(const lf_config *cfg, Plan *p)
     choose_splits(p->units, p->N, &p->L, &p->C);
     p->ntiles = (p->N + kTile - 1) / kTile;
     p->use_mfma = cfg->dtype == LF_BF16 && cfg->head_dim == 128 && !(cfg->flags & LF_FLAG_FORCE_VALU);
-    const bool fits = unit_mfma_lds_bytes(p->N, p->G, !(cfg->flags & LF_FLAG_ATTENTION_ONLY)) <= kUnitLdsLimit;
-    p->use_unit = p->use_mfma && fits && !(cfg->flags & LF_FLAG_FORCE_SPLIT) &&
-                  ((cfg->flags & LF_FLAG_FORCE_UNIT) || p->units >= kUnitMinUnits);
+    // unit-resident kernel: as many cooperating workgroups per unit as it takes to fill the
+    // chip, more if one workgroup's share of the codes would not fit its LDS
+    const bool stash = !(cfg->flags & LF_FLAG_ATTENTION_ONLY);
+    int S = (cfg->flags & LF_FLAG_FORCE_UNIT) ? 1 : unit_mfma_splits(p->units, p->N);
+    while (S < 8 && unit_mfma_lds_bytes(p->N, p->G, stash, S) > kUnitLdsLimit) ++S;
+    const bool fits = unit_mfma_lds_bytes(p->N, p->G, stash, S) <= kUnitLdsLimit;
+    p->unit_S = S;
+    p->use_unit = p->use_mfma && fits && !(cfg->flags & LF_FLAG_FORCE_SPLIT);
+    if (p->use_unit && S > p->C) p->C = S; // the partial buffers are shared with the split path
 }
 
 static Layout layout_of(const Plan &p)
@@ -102,16 +106,20 @@ static Layout layout_of(const Plan &p)
     auto take = [&](size_t bytes) { size_t o = off; off = align_up(off + bytes, 256); return o; };
     l.off_pending = take(sizeof(int32_t) * p.units);
     l.off_arrive = take(sizeof(int32_t) * p.units);
+    l.off_dumped = take(sizeof(int32_t) * p.units);
     l.off_q = take(esz * (size_t)p.B * p.Hq * p.D);
-    l.off_part_m = take(sizeof(float) * (size_t)p.units * p.C * p.G);
-    l.off_part_l = take(sizeof(float) * (size_t)p.units * p.C * p.G);
+    l.off_part_m = take(sizeof(float) * (size_t)p.units * p.C * kMaxGroup);
+    l.off_part_l = take(sizeof(float) * (size_t)p.units * p.C * kMaxGroup);
     l.off_part_o = take(sizeof(float) * (size_t)p.units * p.C * p.G * p.D);
     l.off_fin_m = take(sizeof(float) * (size_t)p.units * p.G);
     l.off_fin_l = take(sizeof(float) * (size_t)p.units * p.G);
-    const bool stash = !(p.flags & LF_FLAG_ATTENTION_ONLY);
-    l.off_stash_w = take(stash ? sizeof(uint16_t) * (size_t)p.units * p.ntiles * p.G * kTile : 0);
+    // per-slot screening data in device memory: bf16 stash on the split path, 1-byte code
+    // dumps when several workgroups share a unit, nothing when one workgroup owns it
+    const bool stash = !(p.flags & LF_FLAG_ATTENTION_ONLY) && !(p.use_unit && p.unit_S == 1);
+    const size_t per_slot = p.use_unit ? 1 : sizeof(uint16_t);
+    l.off_stash_w = take(stash ? per_slot * (size_t)p.units * p.ntiles * p.G * kTile : 0);
     l.off_stash_m = take(stash ? sizeof(float) * (size_t)p.units * p.ntiles * p.G : 0);
-    l.off_lu = take(stash && p.use_mfma ? sizeof(float) * (size_t)p.units * p.ntiles * kTile : 0);
+    l.off_lu = take(p.use_mfma && !(p.flags & LF_FLAG_ATTENTION_ONLY) ? sizeof(float) * (size_t)p.units * p.ntiles * kTile : 0);
     l.total = off;
     return l;
 }
@@ -171,6 +179,7 @@ int longflow_init_cache(longflow_cache_t **out, const lf_config *cfg, void *k_ca
     p.k_cache = k_cache; p.v_cache = v_cache;
     p.pending = (int32_t *)(ws + l.off_pending);
     p.arrive = (int32_t *)(ws + l.off_arrive);
+    p.dumped = (int32_t *)(ws + l.off_dumped);
     p.q_last = ws + l.off_q;
     p.part_m = (float *)(ws + l.off_part_m);
     p.part_l = (float *)(ws + l.off_part_l);
@@ -198,6 +207,7 @@ int longflow_init_cache(longflow_cache_t **out, const lf_config *cfg, void *k_ca
     }
     {
         hipError_t e = launch_fill_i32(p.arrive, p.units, 0, s);
+        if (e == hipSuccess) e = launch_fill_i32(p.dumped, p.units, 0, s);
         if (e != hipSuccess) return fail(LF_ERR_HIP, "counter init: %s", hipGetErrorString(e));
     }
     const bool filling = n_init < p.N;
