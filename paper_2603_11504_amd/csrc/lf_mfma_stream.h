@@ -111,13 +111,15 @@ struct MfmaStreamer {
 
     __device__ __forceinline__ int slot_off(int e) const { return 8 * (e >> 1) + 2 * g + (e & 1); }
 
-    __device__ __forceinline__ void load_tile(TileRegs &t, int ti) const
+    // RAGGED clamps rows to the valid prefix (a full tile needs no clamp)
+    template <bool RAGGED> __device__ __forceinline__ void load_tile(TileRegs &t, int ti) const
     {
         const int base = start + ti * kTile;
-        const int last = end - 1; // rows are clamped: never touch a row past the valid prefix
+        const int last = end - 1;
 #pragma unroll
         for (int a = 0; a < 2; ++a) {
-            const int krow = min(base + 8 * a + (r >> 1), last);
+            int krow = base + 8 * a + (r >> 1);
+            if (RAGGED) krow = min(krow, last);
 #pragma unroll
             for (int L = 0; L < 2; ++L)
                 t.k[a][L] = __builtin_nontemporal_load(
@@ -125,7 +127,8 @@ struct MfmaStreamer {
         }
 #pragma unroll
         for (int e = 0; e < 4; ++e) {
-            const int vrow = min(base + slot_off(e), last);
+            int vrow = base + slot_off(e);
+            if (RAGGED) vrow = min(vrow, last);
             t.v[e] = __builtin_nontemporal_load((const u32x4 *)(Vu + (size_t)vrow * D + 8 * r));
         }
         if (STASH != kStashNone) t.lu = *(const f32x4 *)(lu_unit + base + 4 * g);
@@ -233,8 +236,13 @@ struct MfmaStreamer {
     }
 
     // Stream this wave's share of [start, end): wave w owns tiles w, w + NWAVES, ...
+    // (A static split keeps every sum in a fixed order: results are bit-reproducible.
+    // Handing tiles out dynamically was tried -- the older wave of a SIMD finishes ~40 %
+    // ahead of the younger one -- and bought nothing: the compute unit's request rate, not
+    // the number of waves still streaming, sets the pace.)
     // Three register tiles rotate: while one is consumed the other two are in flight; the
-    // steady-state body has no branch between a load and its use.
+    // steady-state body has no branch between a load and its use, so each wait covers
+    // exactly the oldest tile.
     __device__ __forceinline__ void run(int wave)
     {
         const int nfull = (end - start) / kTile;
@@ -244,34 +252,34 @@ struct MfmaStreamer {
         if (n_my >= 3) {
             // prologue loads are unconditional inside this branch: the waits in the loop
             // then cover exactly the oldest tile and leave the younger loads in flight
-            load_tile(ta, wave);
-            load_tile(tb, wave + NWAVES);
-            load_tile(tc, wave + NWAVES * 2);
+            load_tile<false>(ta, wave);
+            load_tile<false>(tb, wave + NWAVES);
+            load_tile<false>(tc, wave + NWAVES * 2);
             int i = 0;
             for (; i + 5 < n_my; i += 3) {
                 compute_tile<false>(ta, wave + NWAVES * i);
-                load_tile(ta, wave + NWAVES * (i + 3));
+                load_tile<false>(ta, wave + NWAVES * (i + 3));
                 compute_tile<false>(tb, wave + NWAVES * (i + 1));
-                load_tile(tb, wave + NWAVES * (i + 4));
+                load_tile<false>(tb, wave + NWAVES * (i + 4));
                 compute_tile<false>(tc, wave + NWAVES * (i + 2));
-                load_tile(tc, wave + NWAVES * (i + 5));
+                load_tile<false>(tc, wave + NWAVES * (i + 5));
             }
             // 3 to 5 tiles remain; the first three are already on their way
             compute_tile<false>(ta, wave + NWAVES * i);
-            if (i + 3 < n_my) load_tile(ta, wave + NWAVES * (i + 3));
+            if (i + 3 < n_my) load_tile<false>(ta, wave + NWAVES * (i + 3));
             compute_tile<false>(tb, wave + NWAVES * (i + 1));
-            if (i + 4 < n_my) load_tile(tb, wave + NWAVES * (i + 4));
+            if (i + 4 < n_my) load_tile<false>(tb, wave + NWAVES * (i + 4));
             compute_tile<false>(tc, wave + NWAVES * (i + 2));
             if (i + 3 < n_my) compute_tile<false>(ta, wave + NWAVES * (i + 3));
             if (i + 4 < n_my) compute_tile<false>(tb, wave + NWAVES * (i + 4));
         } else {
             for (int i = 0; i < n_my; ++i) {
-                load_tile(ta, wave + NWAVES * i);
+                load_tile<false>(ta, wave + NWAVES * i);
                 compute_tile<false>(ta, wave + NWAVES * i);
             }
         }
         if (ragged && wave == nfull % NWAVES) {
-            load_tile(ta, nfull);
+            load_tile<true>(ta, nfull);
             compute_tile<true>(ta, nfull);
         }
     }

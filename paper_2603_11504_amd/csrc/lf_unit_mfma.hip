@@ -96,12 +96,14 @@ __device__ __forceinline__ double exp2_frac_f64(double x)
 // summed), computed by one wave: 4 lanes per head, 32 channels per lane.
 //   qs: the step's query as floats in LDS [16][128]; sM: softmax reference per head
 //   (log2 domain); sL: denominator per head.
-__device__ double exact_score_bf16(const uint16_t *__restrict__ krow, const uint16_t *__restrict__ vrow,
-                                   const float (*qs)[128], int G, const float *sM, const float *sL, int lane)
+//   coherent: read the row with device-scope loads (it was written during this launch by
+//   another workgroup)
+__device__ double exact_score_bf16(const uint16_t *krow, const uint16_t *vrow, const float (*qs)[128], int G,
+                                   const float *sM, const float *sL, int lane, bool coherent)
 {
     const int h = lane >> 2, part = lane & 3;
     // ||v||_1: two channels per lane, summed over the wave
-    const uint32_t vv = *(const uint32_t *)(vrow + 2 * lane);
+    const uint32_t vv = coherent ? ld_agent((const uint32_t *)vrow + lane) : *(const uint32_t *)(vrow + 2 * lane);
     double l1 = fabs((double)bf16_lo(vv)) + fabs((double)bf16_hi(vv));
     l1 = wave_sum_f64(l1);
     // q_h . k over this lane's 32 channels
@@ -109,7 +111,13 @@ __device__ double exact_score_bf16(const uint16_t *__restrict__ krow, const uint
     if (h < G) {
 #pragma unroll
         for (int c = 0; c < 4; ++c) {
-            const u32x4 kk = *(const u32x4 *)(krow + 32 * part + 8 * c);
+            u32x4 kk;
+            if (coherent) {
+                const uint32_t *kp = (const uint32_t *)(krow + 32 * part + 8 * c);
+                kk = u32x4{ld_agent(kp), ld_agent(kp + 1), ld_agent(kp + 2), ld_agent(kp + 3)};
+            } else {
+                kk = *(const u32x4 *)(krow + 32 * part + 8 * c);
+            }
             const f32x4 qa = *(const f32x4 *)(&qs[h][32 * part + 8 * c]);
             const f32x4 qb = *(const f32x4 *)(&qs[h][32 * part + 8 * c + 4]);
             dot = fma((double)qa[0], (double)bf16_lo(kk.x), dot);
@@ -167,20 +175,22 @@ __global__ __launch_bounds__(512, 1) void unit_mfma_kernel(const UnitArgs a)
     float *lu_u = a.lu + (size_t)u * a.ntiles * kTile;
     const bool evicting = (STASH == kStashLds) && n == N;
 
-    // ---- insert (Fig. 2 left): done by the wave that will stream that tile, so that its
-    // own later loads of the row are ordered behind the stores
+    // ---- insert (Fig. 2 left): done by the wave that will stream that tile, so that its own
+    // later loads of the row are ordered behind the stores.  The row is written through to
+    // the device-wide coherence point: with several workgroups per unit, the one that ends
+    // up re-scoring candidates may sit on another XCD and must not see the old row.
+    const int ins_slot = (STASH != kStashNone) ? a.pending[u] : -1;
     if (STASH != kStashNone) {
-        const int slot = a.pending[u];
+        const int slot = ins_slot;
         if (slot >= start && slot < start + a.split_len && slot < N && (((slot - start) / kTile) % NW) == wave) {
-            if (lane < 16)
-                *(u32x4 *)(Ku + (size_t)slot * D + 8 * lane) = *(const u32x4 *)(a.k_new + (size_t)u * D + 8 * lane);
-            // every 16-lane row sums |v_new| redundantly; row 1 stores V, lane 32 the log2 norm
+            st_agent((uint32_t *)(Ku + (size_t)slot * D) + lane, *((const uint32_t *)(a.k_new + (size_t)u * D) + lane));
+            st_agent((uint32_t *)(Vu + (size_t)slot * D) + lane, *((const uint32_t *)(a.v_new + (size_t)u * D) + lane));
+            // every 16-lane row sums |v_new| redundantly; lane 0 stores the log2 norm
             const u32x4 vv = *(const u32x4 *)(a.v_new + (size_t)u * D + 8 * r);
             float a1 = fabsf(bf16_lo(vv.x)) + fabsf(bf16_hi(vv.x)) + fabsf(bf16_lo(vv.y)) + fabsf(bf16_hi(vv.y)) +
                        fabsf(bf16_lo(vv.z)) + fabsf(bf16_hi(vv.z)) + fabsf(bf16_lo(vv.w)) + fabsf(bf16_hi(vv.w));
             a1 = row16_sum(a1);
-            if (g == 1) *(u32x4 *)(Vu + (size_t)slot * D + 8 * r) = vv;
-            if (lane == 32) lu_u[(slot & ~15) + pos_of_slot(slot & 15)] = __builtin_amdgcn_logf(a1);
+            if (lane == 0) lu_u[(slot & ~15) + pos_of_slot(slot & 15)] = __builtin_amdgcn_logf(a1);
             __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
             asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
         }
@@ -450,14 +460,16 @@ __global__ __launch_bounds__(512, 1) void unit_mfma_kernel(const UnitArgs a)
             } else if (ncand <= kMaxCand) {
                 for (int c = wave; c < ncand; c += NW) {
                     const int cs = cand_list[c];
-                    const double v = exact_score_bf16(Ku + (size_t)cs * D, Vu + (size_t)cs * D, qs, G, sM, sL, lane);
+                    const double v = exact_score_bf16(Ku + (size_t)cs * D, Vu + (size_t)cs * D, qs, G, sM, sL, lane,
+                                                      s_active > 1 && cs == ins_slot);
                     if (v < bv || (v == bv && cs < bi)) { bv = v; bi = cs; }
                 }
             } else {
                 // far more candidates than the list holds (e.g. scores underflowing en masse):
                 // every wave re-scores its share of ALL slots; slow, but still exact
                 for (int cs = wave; cs < n; cs += NW) {
-                    const double v = exact_score_bf16(Ku + (size_t)cs * D, Vu + (size_t)cs * D, qs, G, sM, sL, lane);
+                    const double v = exact_score_bf16(Ku + (size_t)cs * D, Vu + (size_t)cs * D, qs, G, sM, sL, lane,
+                                                      s_active > 1 && cs == ins_slot);
                     if (v < bv || (v == bv && cs < bi)) { bv = v; bi = cs; }
                 }
             }

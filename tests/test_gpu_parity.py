@@ -251,3 +251,43 @@ def test_decode_steps_replayed_from_a_hip_graph_match_eager(flags):
         junk = torch.randn(1 << 20, device="cuda").sum().item()   # unrelated eager work between replays
         assert junk == junk
     assert torch.equal(eager.k_cache.view(torch.int16), graphed.k_cache.view(torch.int16))
+
+
+# ------------------------------------------------------------------ newest token as eviction candidate
+
+@pytest.mark.parametrize("flags,B", [(0, 1), (lf.LF_FLAG_FORCE_UNIT, 1), (lf.LF_FLAG_FORCE_SPLIT, 1), (0, 40)],
+                         ids=["coop", "single", "split", "coop-many"])
+def test_just_inserted_row_competes_for_eviction(flags, B):
+    # Every new token is built to score within a few percent of a decoy row, so the exact
+    # re-scoring must read the row that was written moments ago in the same launch -- with
+    # several workgroups per unit, by a different workgroup than the one deciding.
+    Hq, Hkv, D, N = 14, 2, 128, 2048
+    wl = _small("fresh", "bf16", B, Hq, Hkv, D, N, n_init=N - 1, steps=1, seed=91)
+    rng = np.random.default_rng(7)
+    k0, v0 = W.host_prefill(wl)
+    q = W.round_to_storage(rng.standard_normal((B, Hq, D)).astype(np.float32), "bf16")   # same query every step
+    qsum = q.reshape(B, Hkv, Hq // Hkv, D).sum(2)
+    low_k = W.round_to_storage(-0.5 * qsum, "bf16")                                       # every head's logit far down
+    base_v = np.full((B, Hkv, D), 2.0 ** -4, np.float32)
+    k0[:, :, 100] = low_k
+    v0[:, :, 100] = base_v                                                                # the decoy
+    gpu = lf.LongFlowCache(B, Hq, Hkv, D, N, flags=flags, k_init=W.to_torch(k0, wl, "cuda"),
+                           v_init=W.to_torch(v0, wl, "cuda"))
+    ora = oracle.OracleCache(B * Hkv, Hq // Hkv, 1, D, N)
+    ora.init(k0.reshape(B * Hkv, 1, N - 1, D).astype(np.float64), v0.reshape(B * Hkv, 1, N - 1, D).astype(np.float64))
+    rep = ParityReport()
+    fresh_evicted = 0
+    for t in range(16):
+        scale = 1.0 + 0.03 * ((-1) ** t) * (1 + t % 3)            # a little above / below the decoy
+        v_new = W.round_to_storage(base_v * np.float32(scale), "bf16")
+        out, idx = gpu.decode_step(W.to_torch(q, wl, "cuda"), W.to_torch(low_k, wl, "cuda"), W.to_torch(v_new, wl, "cuda"))
+        torch.cuda.synchronize()
+        pend_before = ora.pending().reshape(-1).copy()
+        o_ref, i_ref = ora.step(q.reshape(B * Hkv, -1, D).astype(np.float64), low_k.reshape(B * Hkv, 1, D).astype(np.float64),
+                                v_new.reshape(B * Hkv, 1, D).astype(np.float64))
+        assert np.abs(W.to_f64(out).reshape(o_ref.shape) - o_ref).max() <= 2e-2
+        i_gpu = idx.cpu().numpy().reshape(-1)
+        if compare_indices(i_gpu, i_ref, ora.scores(), True, rep, where=f"fresh step {t}"):
+            ora.set_pending(i_gpu.reshape(-1, 1))
+        fresh_evicted += int((i_ref.reshape(-1) == pend_before).sum())
+    assert fresh_evicted > 0          # the construction does make the newest row the minimum at times
