@@ -53,7 +53,7 @@ def parse():
 def kernel_name(wl, flags):
     from paper_2603_11504_amd import longflow as lf
     mfma = wl.dtype == "bf16" and wl.head_dim == 128 and not (flags & lf.LF_FLAG_FORCE_VALU)
-    fused = mfma and not (flags & lf.LF_FLAG_FORCE_SPLIT) and ((flags & lf.LF_FLAG_FORCE_UNIT) or wl.units >= 96)
+    fused = mfma and not (flags & lf.LF_FLAG_FORCE_SPLIT)   # every BASELINE geometry fits the unit-resident kernel's LDS
     return "unit_mfma_kernel" if fused else ("split_mfma_kernel" if mfma else "split_valu_kernel")
 
 

@@ -144,7 +144,8 @@ __device__ double exact_score_bf16(const uint16_t *krow, const uint16_t *vrow, c
     return term * l1;
 }
 
-template <bool HILO, int STASH>
+// COOP: several workgroups may share a unit (s_active can exceed 1)
+template <bool HILO, int STASH, bool COOP>
 __global__ __launch_bounds__(512, 1) void unit_mfma_kernel(const UnitArgs a)
 {
     constexpr int D = 128, NW = 8, OPAD = D + 4;
@@ -163,7 +164,7 @@ __global__ __launch_bounds__(512, 1) void unit_mfma_kernel(const UnitArgs a)
     __shared__ int cand_list[kMaxCand];
     __shared__ int cand_count, s_flag;
 
-    const int n = a.n, N = a.N, G = a.G, s_active = a.s_active;
+    const int n = a.n, N = a.N, G = a.G, s_active = COOP ? a.s_active : 1;
     const int u = blockIdx.x / s_active, sp = blockIdx.x % s_active;
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int g = lane >> 4, r = lane & 15;
@@ -245,7 +246,7 @@ __global__ __launch_bounds__(512, 1) void unit_mfma_kernel(const UnitArgs a)
     };
 
     bool dumps_ok = true;
-    if (s_active > 1) {
+    if (COOP && s_active > 1) {
         // ---- publish this workgroup's partial (m, l, O) and count the arrival
         stage_o();
         __syncthreads();
@@ -352,9 +353,23 @@ __global__ __launch_bounds__(512, 1) void unit_mfma_kernel(const UnitArgs a)
                 const bool mine = tile * kTile >= start && tile * kTile < start + a.split_len;
 #pragma unroll
                 for (int e = 0; e < 4; ++e) ub4[e] = lb4[e] = 0.f;
+                if (!COOP) { // everything is in this workgroup's LDS
+                    for (int h = 0; h < G; ++h) {
+                        const uint32_t c4 = *(const uint32_t *)(ls_code + (size_t)h * a.code_stride + 4 * item);
+                        const float f = ls_ref[tile * G + h];
+#pragma unroll
+                        for (int e = 0; e < 4; ++e) {
+                            const uint32_t c = (c4 >> (8 * e)) & 255u;
+                            const float d = fast_exp2(-0.25f * (float)c) * f;
+                            ub4[e] += (c == 0u) ? INFINITY : d;
+                            lb4[e] += (c == 255u) ? 0.f : d;
+                        }
+                    }
+                }
                 uint32_t c4s[kMaxGroup];
                 float fs[kMaxGroup];
-                if (mine) {
+                if (!COOP) {
+                } else if (mine) {
 #pragma unroll
                     for (int h = 0; h < kMaxGroup; ++h)
                         if (h < G) {
@@ -375,7 +390,7 @@ __global__ __launch_bounds__(512, 1) void unit_mfma_kernel(const UnitArgs a)
                 }
 #pragma unroll
                 for (int h = 0; h < kMaxGroup; ++h) {
-                    if (h < G) {
+                    if (COOP && h < G) {
 #pragma unroll
                         for (int e = 0; e < 4; ++e) {
                             const uint32_t c = (c4s[h] >> (8 * e)) & 255u;
@@ -461,7 +476,7 @@ __global__ __launch_bounds__(512, 1) void unit_mfma_kernel(const UnitArgs a)
                 for (int c = wave; c < ncand; c += NW) {
                     const int cs = cand_list[c];
                     const double v = exact_score_bf16(Ku + (size_t)cs * D, Vu + (size_t)cs * D, qs, G, sM, sL, lane,
-                                                      s_active > 1 && cs == ins_slot);
+                                                      COOP && s_active > 1 && cs == ins_slot);
                     if (v < bv || (v == bv && cs < bi)) { bv = v; bi = cs; }
                 }
             } else {
@@ -469,7 +484,7 @@ __global__ __launch_bounds__(512, 1) void unit_mfma_kernel(const UnitArgs a)
                 // every wave re-scores its share of ALL slots; slow, but still exact
                 for (int cs = wave; cs < n; cs += NW) {
                     const double v = exact_score_bf16(Ku + (size_t)cs * D, Vu + (size_t)cs * D, qs, G, sM, sL, lane,
-                                                      s_active > 1 && cs == ins_slot);
+                                                      COOP && s_active > 1 && cs == ins_slot);
                     if (v < bv || (v == bv && cs < bi)) { bv = v; bi = cs; }
                 }
             }
@@ -489,7 +504,7 @@ __global__ __launch_bounds__(512, 1) void unit_mfma_kernel(const UnitArgs a)
     }
 
     // ---- output: normalise, round to bf16, keep a copy of q for longflow_scores()
-    if (s_active == 1) {
+    if (!COOP || s_active == 1) {
         stage_o();
         __syncthreads();
         for (int idx = tid; idx < G * D; idx += 512) {
@@ -577,18 +592,20 @@ hipError_t launch_unit_mfma(const Plan &p, const void *q, const void *k_new, con
     // With at most a few workgroups per compute unit, ask for more than half of the
     // CU's LDS so that no CU is handed two of them while another one idles.
     if ((long)p.units * a.s_active <= 2 * 256 && lds < 81 * 1024) lds = 81 * 1024;
-    static bool attr_done[2] = {false, false};
-#define LF_UNIT(STASH, IDX)                                                                          \
+    static bool attr_done[4] = {false, false, false, false};
+#define LF_UNIT(STASH, COOP, IDX)                                                                    \
     do {                                                                                              \
         if (!attr_done[IDX]) {                                                                        \
-            hipError_t e = hipFuncSetAttribute((const void *)unit_mfma_kernel<true, STASH>,           \
+            hipError_t e = hipFuncSetAttribute((const void *)unit_mfma_kernel<true, STASH, COOP>,     \
                                                hipFuncAttributeMaxDynamicSharedMemorySize, (int)kUnitLdsLimit); \
             if (e != hipSuccess) return e;                                                            \
             attr_done[IDX] = true;                                                                    \
         }                                                                                             \
-        hipLaunchKernelGGL((unit_mfma_kernel<true, STASH>), dim3(p.units * a.s_active), dim3(512), lds, s, a); \
+        hipLaunchKernelGGL((unit_mfma_kernel<true, STASH, COOP>), dim3(p.units * a.s_active), dim3(512), lds, s, a); \
     } while (0)
-    if (stash) LF_UNIT(kStashLds, 0); else LF_UNIT(kStashNone, 1);
+    const bool coop = p.unit_S > 1;
+    if (stash) { if (coop) LF_UNIT(kStashLds, true, 0); else LF_UNIT(kStashLds, false, 1); }
+    else       { if (coop) LF_UNIT(kStashNone, true, 2); else LF_UNIT(kStashNone, false, 3); }
 #undef LF_UNIT
     return hipGetLastError();
 }
