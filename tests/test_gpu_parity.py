@@ -291,3 +291,36 @@ def test_just_inserted_row_competes_for_eviction(flags, B):
             ora.set_pending(i_gpu.reshape(-1, 1))
         fresh_evicted += int((i_ref.reshape(-1) == pend_before).sum())
     assert fresh_evicted > 0          # the construction does make the newest row the minimum at times
+
+
+# ------------------------------------------------------------------ random geometries
+
+def _random_cases(count, seed):
+    rng = np.random.default_rng(seed)
+    cases = []
+    while len(cases) < count:
+        dtype = "bf16" if rng.random() < 0.7 else "f32"
+        D = 128 if rng.random() < 0.7 else 64
+        mfma_ok = dtype == "bf16" and D == 128
+        flags = 0
+        if mfma_ok:
+            flags = int(rng.choice([0, 0, lf.LF_FLAG_FORCE_SPLIT, lf.LF_FLAG_FORCE_UNIT, lf.LF_FLAG_FORCE_VALU]))
+        gmax = 16 if (mfma_ok and not flags & lf.LF_FLAG_FORCE_VALU) else 8
+        G = int(rng.integers(1, gmax + 1))
+        Hkv = int(rng.integers(1, 4))
+        B = int(rng.integers(1, 6))
+        N = int(rng.choice([int(rng.integers(17, 200)), int(rng.integers(200, 1200)), int(rng.integers(1200, 3000))]))
+        n_init = int(rng.choice([max(0, N - int(rng.integers(1, 40))), N - 1, int(rng.integers(0, N))]))
+        steps = int(min(N - n_init + 12, 48))
+        cases.append((dtype, B, G * Hkv, Hkv, D, N, n_init, steps, flags, int(rng.integers(1 << 30))))
+    return cases
+
+
+@pytest.mark.parametrize("case", _random_cases(28, 20260311), ids=lambda c: "-".join(str(x) for x in c[:9]))
+def test_random_geometries(case):
+    dtype, B, Hq, Hkv, D, N, n_init, steps, flags, seed = case
+    wl = W.Workload("rand", dtype, B, Hq, Hkv, D, N, n_init, steps, sink_scale=4.0 if seed & 1 else 1.0,
+                    outlier_channels=4 if seed & 2 else 0, outlier_scale=8.0, seed=seed)
+    rep, gpu, _ = run_lockstep(wl, flags=flags, check_scores_every=7)
+    assert rep.steps == steps
+    gpu.close()
