@@ -47,6 +47,9 @@ def parse():
     ap.add_argument("--pool", type=int, default=0,
                     help="distinct input steps cycled through (0 = one per executed step, no repeats)")
     ap.add_argument("--report", action="store_true", help="all workloads and the uncompressed twin, as a table")
+    ap.add_argument("--streams", type=int, default=1,
+                    help="HIP streams the independent layer caches are spread over in the timed pass (default 1: "
+                         "all calls back-to-back on one stream)")
     return ap.parse_args()
 
 
@@ -90,7 +93,8 @@ def cpu_baseline(wl, cache0, target_s=12.0):
             "ms_per_step": full_step_s * 1e3}
 
 
-def measure(wl, flags, steps, warmup, pool=0, with_cpu=False, calibrate_copy=False, per_step_times=False):
+def measure(wl, flags, steps, warmup, pool=0, with_cpu=False, calibrate_copy=False, per_step_times=False,
+            streams=1, also_streams=0):
     """Build the resident state, warm up, time `steps` steps, then the same again with kernel events."""
     import torch
     from paper_2603_11504_amd import longflow as lf
@@ -113,19 +117,32 @@ def measure(wl, flags, steps, warmup, pool=0, with_cpu=False, calibrate_copy=Fal
     warm = max(warmup, 1) + max(fill, 0)
     # every executed step gets its own q/k/v (repeating inputs would plant bit-identical
     # rows in the cache, i.e. exact score ties that the real workload does not have)
-    npool = pool if pool > 0 else warm + 2 * steps
+    npool = pool if pool > 0 else warm + (3 if also_streams > 1 else 2) * steps
     inputs = [[W.device_step(wl, t, dev, layer) for layer in range(wl.layers)] for t in range(npool)]
     torch.cuda.synchronize()
 
-    def run(nsteps, t0=0, events=None):
+    def run(nsteps, t0=0, events=None, nstreams=1):
+        # the layer caches are independent: with nstreams > 1 their calls go round-robin to
+        # several streams, so one call's tail overlaps the next call's start
+        pool_s = [torch.cuda.Stream(device=dev) for _ in range(nstreams)] if nstreams > 1 else None
+        if pool_s:
+            for s_ in pool_s:
+                s_.wait_stream(torch.cuda.current_stream())
         for t in range(t0, t0 + nsteps):
             if events is not None:
                 events[t - t0][0].record()
             for layer, c in enumerate(caches):
                 q, k, v = inputs[t % npool][layer]
-                c.decode_step(q, k, v)
+                if pool_s:
+                    with torch.cuda.stream(pool_s[layer % nstreams]):
+                        c.decode_step(q, k, v)
+                else:
+                    c.decode_step(q, k, v)
             if events is not None:
                 events[t - t0][1].record()
+        if pool_s:
+            for s_ in pool_s:
+                torch.cuda.current_stream().wait_stream(s_)
 
     run(warm)
     torch.cuda.synchronize()
@@ -138,7 +155,7 @@ def measure(wl, flags, steps, warmup, pool=0, with_cpu=False, calibrate_copy=Fal
         del src, dst
 
     t0 = time.perf_counter()
-    run(steps, warm)
+    run(steps, warm, nstreams=streams)
     torch.cuda.synchronize()
     ms_per_step = (time.perf_counter() - t0) / steps * 1e3
     calls = steps * wl.layers
@@ -156,6 +173,12 @@ def measure(wl, flags, steps, warmup, pool=0, with_cpu=False, calibrate_copy=Fal
         ksum += ms
     kernel_us = ksum / calls * 1e3
     step_us = sorted(a.elapsed_time(b) * 1e3 for a, b in evs) if evs else None
+    ms_per_step_multi = None
+    if also_streams > 1 and wl.layers > 1 and npool >= warm + 3 * steps:
+        t0 = time.perf_counter()
+        run(steps, warm + 2 * steps, nstreams=also_streams)
+        torch.cuda.synchronize()
+        ms_per_step_multi = (time.perf_counter() - t0) / steps * 1e3
 
     bytes_call = wl.kv_bytes_per_call()
     kname = kernel_name(wl, flags)
@@ -164,6 +187,7 @@ def measure(wl, flags, steps, warmup, pool=0, with_cpu=False, calibrate_copy=Fal
         "bytes_call": bytes_call, "tokens_per_s": wl.batch / (ms_per_step * 1e-3),
         "step_GBs": bytes_call * wl.layers / (ms_per_step * 1e-3) / 1e9,
         "kernel_GBs": bytes_call / (kernel_us * 1e-6) / 1e9, "step_us_sorted": step_us,
+        "ms_per_step_multi": ms_per_step_multi,
     }
     if with_cpu:
         res["cpu_baseline"] = cpu_baseline(wl, caches[0])
@@ -214,7 +238,7 @@ def main():
     flags |= lf.LF_FLAG_FORCE_SPLIT if a.split else 0
     flags |= lf.LF_FLAG_FORCE_UNIT if a.unit else 0
     r = measure(wl, flags, steps, a.warmup, pool=a.pool, with_cpu=not a.no_cpu_baseline,
-                calibrate_copy=a.calibrate_copy)
+                calibrate_copy=a.calibrate_copy, streams=a.streams, also_streams=4 if a.streams == 1 else 0)
     kname = r["kernel"]
     out = {
         "metric": "decode_tokens_per_s",
@@ -226,7 +250,7 @@ def main():
         "data": "synthetic",
         "config": {"workload": wl.name, "batch": wl.batch, "q_heads": wl.q_heads, "kv_heads": wl.kv_heads,
                    "head_dim": wl.head_dim, "budget": wl.budget, "layers": wl.layers,
-                   "calls_per_step": wl.layers,
+                   "calls_per_step": wl.layers, "streams": a.streams,
                    "kernel_path": {"unit_mfma_kernel": "fused one-launch, matrix cores",
                                    "split_mfma_kernel": "split-K, matrix cores",
                                    "split_valu_kernel": "split-K, vector ALU"}[kname]},
@@ -239,6 +263,10 @@ def main():
                      "bytes_per_launch": r["bytes_call"], "avg_launch_us": r["kernel_us"],
                      "traffic": MEASURED_TRAFFIC.get((wl.name, kname))},
     }
+    if r.get("ms_per_step_multi"):
+        # the same steps with the independent layer calls spread over 4 streams (tails overlap)
+        out["ms_per_step_4_streams"] = r["ms_per_step_multi"]
+        out["step_hbm_frac_4_streams"] = r["bytes_call"] * wl.layers / (r["ms_per_step_multi"] * 1e-3) / 1e9 / HBM_PEAK_GBS
     if "cpu_baseline" in r:
         out["cpu_baseline"] = r["cpu_baseline"]
     print(json.dumps(out))

@@ -324,3 +324,37 @@ def test_random_geometries(case):
     rep, gpu, _ = run_lockstep(wl, flags=flags, check_scores_every=7)
     assert rep.steps == steps
     gpu.close()
+
+
+# ------------------------------------------------------------------ independent caches on several streams
+
+def test_independent_caches_on_two_streams_match_serial_execution():
+    # handles share no mutable state: driving them from different streams gives the same bits
+    wl = _small("streams", "bf16", 8, 28, 4, 128, 1024, n_init=1023, steps=6, seed=81)
+    outs = {}
+    for mode in ("serial", "streams"):
+        caches = []
+        for layer in range(4):
+            k0, v0 = W.host_prefill(wl, layer)
+            caches.append(lf.LongFlowCache(wl.batch, wl.q_heads, wl.kv_heads, wl.head_dim, wl.budget,
+                                           k_init=W.to_torch(k0, wl, "cuda"), v_init=W.to_torch(v0, wl, "cuda")))
+        streams = [torch.cuda.Stream(), torch.cuda.Stream()]
+        torch.cuda.synchronize()
+        res = []
+        for t in range(wl.steps):
+            for layer, c in enumerate(caches):
+                q, k, v = (W.to_torch(x, wl, "cuda") for x in W.host_step(wl, t, layer))
+                if mode == "streams":
+                    streams[layer % 2].wait_stream(torch.cuda.current_stream())
+                    with torch.cuda.stream(streams[layer % 2]):
+                        o, i = c.decode_step(q, k, v)
+                        res.append((o.clone(), i.clone()))
+                else:
+                    o, i = c.decode_step(q, k, v)
+                    res.append((o.clone(), i.clone()))
+        torch.cuda.synchronize()
+        outs[mode] = res
+        for c in caches:
+            c.close()
+    for (o1, i1), (o2, i2) in zip(outs["serial"], outs["streams"]):
+        assert torch.equal(o1.view(torch.int16), o2.view(torch.int16)) and torch.equal(i1, i2)
