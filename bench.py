@@ -94,7 +94,7 @@ def cpu_baseline(wl, cache0, target_s=12.0):
 
 
 def measure(wl, flags, steps, warmup, pool=0, with_cpu=False, calibrate_copy=False, per_step_times=False,
-            streams=1, also_streams=0):
+            streams=1, also_streams=0, also_grouped=False):
     """Build the resident state, warm up, time `steps` steps, then the same again with kernel events."""
     import torch
     from paper_2603_11504_amd import longflow as lf
@@ -117,8 +117,15 @@ def measure(wl, flags, steps, warmup, pool=0, with_cpu=False, calibrate_copy=Fal
     warm = max(warmup, 1) + max(fill, 0)
     # every executed step gets its own q/k/v (repeating inputs would plant bit-identical
     # rows in the cache, i.e. exact score ties that the real workload does not have)
-    npool = pool if pool > 0 else warm + (3 if also_streams > 1 else 2) * steps
-    inputs = [[W.device_step(wl, t, dev, layer) for layer in range(wl.layers)] for t in range(npool)]
+    passes = 2 + (1 if also_streams > 1 else 0) + (1 if also_grouped else 0)
+    npool = pool if pool > 0 else warm + passes * steps
+    # per step one stacked tensor per kind, [layers, ...]: a layer's call takes its slice,
+    # the grouped call takes the whole
+    inputs = []
+    for t in range(npool):
+        per_layer = [W.device_step(wl, t, dev, layer) for layer in range(wl.layers)]
+        inputs.append(tuple(torch.stack([x[i] for x in per_layer]) for i in range(3)))
+        del per_layer
     torch.cuda.synchronize()
 
     def run(nsteps, t0=0, events=None, nstreams=1):
@@ -132,7 +139,7 @@ def measure(wl, flags, steps, warmup, pool=0, with_cpu=False, calibrate_copy=Fal
             if events is not None:
                 events[t - t0][0].record()
             for layer, c in enumerate(caches):
-                q, k, v = inputs[t % npool][layer]
+                q, k, v = (x[layer] for x in inputs[t % npool])
                 if pool_s:
                     with torch.cuda.stream(pool_s[layer % nstreams]):
                         c.decode_step(q, k, v)
@@ -180,6 +187,20 @@ def measure(wl, flags, steps, warmup, pool=0, with_cpu=False, calibrate_copy=Fal
         torch.cuda.synchronize()
         ms_per_step_multi = (time.perf_counter() - t0) / steps * 1e3
 
+    ms_per_step_grouped = None
+    if also_grouped and npool >= warm + passes * steps:
+        # all layer caches in one launch per step (they are independent in this benchmark)
+        group = lf.LongFlowGroup(caches)
+        base = warm + (passes - 1) * steps
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for t in range(base, base + steps):
+            q, k, v = inputs[t % npool]
+            group.decode_step(q, None if attention_only else k, None if attention_only else v)
+        torch.cuda.synchronize()
+        ms_per_step_grouped = (time.perf_counter() - t0) / steps * 1e3
+        group.close()
+
     bytes_call = wl.kv_bytes_per_call()
     kname = kernel_name(wl, flags)
     res = {
@@ -187,7 +208,7 @@ def measure(wl, flags, steps, warmup, pool=0, with_cpu=False, calibrate_copy=Fal
         "bytes_call": bytes_call, "tokens_per_s": wl.batch / (ms_per_step * 1e-3),
         "step_GBs": bytes_call * wl.layers / (ms_per_step * 1e-3) / 1e9,
         "kernel_GBs": bytes_call / (kernel_us * 1e-6) / 1e9, "step_us_sorted": step_us,
-        "ms_per_step_multi": ms_per_step_multi,
+        "ms_per_step_multi": ms_per_step_multi, "ms_per_step_grouped": ms_per_step_grouped,
     }
     if with_cpu:
         res["cpu_baseline"] = cpu_baseline(wl, caches[0])
@@ -206,17 +227,23 @@ def report(a):
     rows = [(W.CONFIGS[i], 0, DEFAULT_STEPS[i]) for i in range(5)]
     twin = W.scaled(W.CONFIGS[4], name="cfg4_uncompressed_twin_n81920", budget=81920, n_init=81920)
     rows.append((twin, lf.LF_FLAG_ATTENTION_ONLY, 10))
+    # the small workloads again as 28 independent caches, for the one-launch-per-step column
+    for i in range(3):
+        rows.append((W.scaled(W.CONFIGS[i], name=W.CONFIGS[i].name + "_x28", layers=28), 0, DEFAULT_STEPS[i]))
     print(f"{'workload':38s} {'kernel':18s} {'us/step p10':>11s} {'median':>9s} {'p90':>9s} {'us/call':>9s} "
-          f"{'GB/s step':>10s} {'% peak':>7s} {'GB/s kernel':>11s} {'% peak':>7s} {'tokens/s':>10s}")
+          f"{'GB/s step':>10s} {'% peak':>7s} {'GB/s kernel':>11s} {'% peak':>7s} {'tokens/s':>10s} "
+          f"{'grouped us/call':>15s} {'% peak':>7s}")
     for wl, flags, steps in rows:
         if a.steps:
             steps = a.steps
-        r = measure(wl, flags, steps, a.warmup, per_step_times=True)
+        r = measure(wl, flags, steps, a.warmup, per_step_times=True, also_grouped=wl.layers > 1)
         s = r["step_us_sorted"]
         p10, med, p90 = s[len(s) // 10], s[len(s) // 2], s[(9 * len(s)) // 10]
         print(f"{wl.name:38s} {r['kernel']:18s} {p10:11.1f} {med:9.1f} {p90:9.1f} {r['ms_per_step'] * 1e3 / wl.layers:9.1f} "
               f"{r['step_GBs']:10.1f} {100 * r['step_GBs'] / HBM_PEAK_GBS:7.1f} {r['kernel_GBs']:11.1f} "
-              f"{100 * r['kernel_GBs'] / HBM_PEAK_GBS:7.1f} {r['tokens_per_s']:10.0f}", flush=True)
+              f"{100 * r['kernel_GBs'] / HBM_PEAK_GBS:7.1f} {r['tokens_per_s']:10.0f} " + (
+                  f"{g * 1e3 / wl.layers:15.1f} {100 * r['bytes_call'] * wl.layers / (g * 1e-3) / 1e9 / HBM_PEAK_GBS:7.1f}"
+                  if (g := r.get('ms_per_step_grouped')) else f"{'-':>15s} {'-':>7s}"), flush=True)
 
 
 def main():
@@ -238,7 +265,8 @@ def main():
     flags |= lf.LF_FLAG_FORCE_SPLIT if a.split else 0
     flags |= lf.LF_FLAG_FORCE_UNIT if a.unit else 0
     r = measure(wl, flags, steps, a.warmup, pool=a.pool, with_cpu=not a.no_cpu_baseline,
-                calibrate_copy=a.calibrate_copy, streams=a.streams, also_streams=4 if a.streams == 1 else 0)
+                calibrate_copy=a.calibrate_copy, streams=a.streams, also_streams=4 if a.streams == 1 else 0,
+                also_grouped=a.streams == 1 and wl.layers > 1)
     kname = r["kernel"]
     out = {
         "metric": "decode_tokens_per_s",
@@ -267,6 +295,10 @@ def main():
         # the same steps with the independent layer calls spread over 4 streams (tails overlap)
         out["ms_per_step_4_streams"] = r["ms_per_step_multi"]
         out["step_hbm_frac_4_streams"] = r["bytes_call"] * wl.layers / (r["ms_per_step_multi"] * 1e-3) / 1e9 / HBM_PEAK_GBS
+    if r.get("ms_per_step_grouped"):
+        # the same steps with all layer caches served by one launch per step
+        out["ms_per_step_grouped"] = r["ms_per_step_grouped"]
+        out["step_hbm_frac_grouped"] = r["bytes_call"] * wl.layers / (r["ms_per_step_grouped"] * 1e-3) / 1e9 / HBM_PEAK_GBS
     if "cpu_baseline" in r:
         out["cpu_baseline"] = r["cpu_baseline"]
     print(json.dumps(out))

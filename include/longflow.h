@@ -133,8 +133,37 @@ LF_API int longflow_set_pending(longflow_cache_t *cache, const int32_t *slots, v
 /* Valid slots = min(tokens seen, N); negative on a NULL handle. */
 LF_API int longflow_valid_count(const longflow_cache_t *cache);
 
-/* Frees the host handle only. */
+/* Frees the host handle only.  LF_ERR_STATE while a group still holds the cache. */
 LF_API int longflow_destroy_cache(longflow_cache_t *cache);
+
+/*
+ * Several caches in one launch.  The method's workload is the same every step (Sec. 3.4:
+ * static memory, one fused kernel), so caches that are independent of each other --
+ * micro-batches, or the layers of a synthetic benchmark -- can share one grid: the launch
+ * and the drain between kernels are paid once per group, and a small cache no longer
+ * leaves most of the chip idle.  Each member computes exactly what longflow_decode_step
+ * computes for it (same kernels, same arithmetic, same order).
+ *
+ *   longflow_group_workspace_bytes  device bytes a group of n_caches needs (0 if n_caches < 1)
+ *   longflow_group_create   caches: host array of n_caches handles with identical lf_config
+ *                           and the same valid count; workspace: device, 256-byte aligned,
+ *                           owned by the caller, must outlive the group.  Copies a table of
+ *                           per-cache pointers into it on hip_stream.
+ *   longflow_group_decode_step  one decode step of every member.  q/out are device
+ *                           [n_caches][B][Hq][D], k_new/v_new [n_caches][B][Hkv][D],
+ *                           evict_idx int32 [n_caches][B][Hkv] or NULL; otherwise as
+ *                           longflow_decode_step.  Members may also be stepped one by one
+ *                           between group steps; LF_ERR_STATE if their counts then differ.
+ *   longflow_group_destroy  frees the host handle only.  longflow_destroy_cache refuses
+ *                           (LF_ERR_STATE) a cache that is still a member of a live group.
+ */
+typedef struct longflow_group longflow_group_t;
+LF_API size_t longflow_group_workspace_bytes(int32_t n_caches);
+LF_API int longflow_group_create(longflow_group_t **group, longflow_cache_t *const *caches, int32_t n_caches,
+                                 void *workspace, size_t workspace_bytes, void *hip_stream);
+LF_API int longflow_group_decode_step(longflow_group_t *group, const void *q, const void *k_new,
+                                      const void *v_new, void *out, int32_t *evict_idx, void *hip_stream);
+LF_API int longflow_group_destroy(longflow_group_t *group);
 
 /*
  * Measurement aid (not part of the paper's operator): while profiling is on, every

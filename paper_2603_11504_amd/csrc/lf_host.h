@@ -64,6 +64,14 @@ int unit_mfma_split_len(int N, int S);
 size_t unit_mfma_lds_bytes(int N, int G, bool stash, int S);
 hipError_t launch_unit_mfma(const Plan &p, const void *q, const void *k_new, const void *v_new, int n,
                             void *out, int32_t *evict_idx, hipStream_t s);
+// Several caches of one geometry in one grid: `table` is a device array with one entry
+// (unit_mfma_table_entry_bytes() each, written by unit_mfma_table_entry on the host and
+// copied over) per cache; io holds base pointers, cache i's tensors follow at i times the
+// tensor's size.
+size_t unit_mfma_table_entry_bytes();
+void unit_mfma_table_entry(const Plan &p, void *dst);
+hipError_t launch_unit_mfma_group(const Plan &p, const StepIo &io, int n, const void *table, int n_caches,
+                                  hipStream_t s);
 hipError_t launch_scores(const Plan &p, int n, float *scores, hipStream_t s);
 hipError_t launch_l1norms(const Plan &p, int n_rows, hipStream_t s);
 hipError_t launch_fill_i32(int32_t *dst, int count, int32_t value, hipStream_t s);

@@ -24,6 +24,8 @@
 // in -- their authors passed arrive[u] before it did, so they are running or done -- and
 // decides the eviction from its own LDS codes plus the dumps.  If the bounded wait ever
 // expired it would re-score every slot exactly instead of trusting incomplete dumps.
+#include <cstring>
+
 #include "lf_mfma_stream.h"
 
 namespace lf {
@@ -47,6 +49,15 @@ struct UnitArgs {
     int code_stride, gstride;          // LDS / dump row strides in bytes
     int merge_off;                     // byte offset of the O-merge area in dynamic LDS
     float scale_log2;
+};
+
+// One launch over several caches of identical geometry and fill level: the per-cache
+// pointers come from a device-resident table of UnitArgs, the step's tensors from base
+// pointers with a per-cache stride (in elements).
+struct GroupArgs {
+    const UnitArgs *table;
+    int wgs_per_cache;
+    long long q_stride, kv_stride, ev_stride;
 };
 
 // Device-scope coherent accesses for the little data that cooperating workgroups exchange.
@@ -145,9 +156,26 @@ __device__ double exact_score_bf16(const uint16_t *krow, const uint16_t *vrow, c
 }
 
 // COOP: several workgroups may share a unit (s_active can exceed 1)
-template <bool HILO, int STASH, bool COOP>
-__global__ __launch_bounds__(512, 1) void unit_mfma_kernel(const UnitArgs a)
+template <bool HILO, int STASH, bool COOP, bool GROUPED>
+__global__ __launch_bounds__(512, 1) void unit_mfma_kernel(const UnitArgs a_in, const GroupArgs ga)
 {
+    UnitArgs a = a_in;
+    int blk = blockIdx.x;
+    if (GROUPED) {
+        // which cache this workgroup serves; the geometry and the step's scalars are common
+        const int ci = blk / ga.wgs_per_cache;
+        blk -= ci * ga.wgs_per_cache;
+        const UnitArgs *t = ga.table + ci;
+        a.Kc = t->Kc; a.Vc = t->Vc; a.q_last = t->q_last; a.pending = t->pending;
+        a.fin_m = t->fin_m; a.fin_l = t->fin_l; a.lu = t->lu;
+        a.part_m = t->part_m; a.part_l = t->part_l; a.part_o = t->part_o;
+        a.arrive = t->arrive; a.dumped = t->dumped; a.gcode = t->gcode; a.gref = t->gref;
+        a.q += ci * ga.q_stride;
+        a.out += ci * ga.q_stride;
+        if (a.k_new) a.k_new += ci * ga.kv_stride;
+        if (a.v_new) a.v_new += ci * ga.kv_stride;
+        if (a.evict_idx) a.evict_idx += ci * ga.ev_stride;
+    }
     constexpr int D = 128, NW = 8, OPAD = D + 4;
     extern __shared__ __align__(16) unsigned char smem[];
     // dynamic LDS: [codes G*code_stride][refs (split_len/16)*G floats]; the O-merge area
@@ -165,7 +193,7 @@ __global__ __launch_bounds__(512, 1) void unit_mfma_kernel(const UnitArgs a)
     __shared__ int cand_count, s_flag;
 
     const int n = a.n, N = a.N, G = a.G, s_active = COOP ? a.s_active : 1;
-    const int u = blockIdx.x / s_active, sp = blockIdx.x % s_active;
+    const int u = blk / s_active, sp = blk % s_active;
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int g = lane >> 4, r = lane & 15;
     const int start = sp * a.split_len;
@@ -568,15 +596,14 @@ size_t unit_mfma_lds_bytes(int N, int G, bool stash, int S)
     return (codes + 255) / 256 * 256 + kMergeBytes;
 }
 
-hipError_t launch_unit_mfma(const Plan &p, const void *q, const void *k_new, const void *v_new, int n,
-                            void *out, int32_t *evict_idx, hipStream_t s)
+// everything of a step's kernel arguments that depends on the cache and the fill level only
+static UnitArgs unit_args_of(const Plan &p, int n)
 {
-    const bool stash = !(p.flags & 1u);
     UnitArgs a;
+    memset(&a, 0, sizeof(a));
     a.Kc = (uint16_t *)p.k_cache; a.Vc = (uint16_t *)p.v_cache;
-    a.q = (const uint16_t *)q; a.k_new = (const uint16_t *)k_new; a.v_new = (const uint16_t *)v_new;
-    a.out = (uint16_t *)out; a.q_last = (uint16_t *)p.q_last;
-    a.pending = p.pending; a.evict_idx = evict_idx;
+    a.q_last = (uint16_t *)p.q_last;
+    a.pending = p.pending;
     a.fin_m = p.fin_m; a.fin_l = p.fin_l; a.lu = p.lu;
     a.part_m = p.part_m; a.part_l = p.part_l; a.part_o = p.part_o;
     a.arrive = p.arrive; a.dumped = p.dumped;
@@ -586,28 +613,76 @@ hipError_t launch_unit_mfma(const Plan &p, const void *q, const void *k_new, con
     a.s_active = (n + a.split_len - 1) / a.split_len;
     a.code_stride = (a.split_len + 63) / 64 * 64;
     a.gstride = p.ntiles * kTile;
-    size_t lds = unit_mfma_lds_bytes(p.N, p.G, stash, p.unit_S);
+    const bool stash = !(p.flags & 1u);
+    const size_t lds = unit_mfma_lds_bytes(p.N, p.G, stash, p.unit_S);
     a.merge_off = (stash && p.unit_S > 1) ? (int)(lds - kMergeBytes) : 0;
     a.scale_log2 = 1.4426950408889634f / sqrtf(128.f);
+    return a;
+}
+
+size_t unit_mfma_table_entry_bytes() { return sizeof(UnitArgs); }
+
+void unit_mfma_table_entry(const Plan &p, void *dst)
+{
+    const UnitArgs a = unit_args_of(p, p.N);
+    memcpy(dst, &a, sizeof(a));
+}
+
+// `table` == nullptr: one cache, arguments by value.  Otherwise `n_caches` caches of p's
+// geometry, all holding n - 1 (or N) rows, served by one grid; io holds the base pointers.
+static hipError_t launch_unit(const Plan &p, const StepIo &io, int n, const void *table, int n_caches,
+                              hipStream_t s)
+{
+    const bool stash = !(p.flags & 1u);
+    UnitArgs a = unit_args_of(p, n);
+    a.q = (const uint16_t *)io.q; a.k_new = (const uint16_t *)io.k_new; a.v_new = (const uint16_t *)io.v_new;
+    a.out = (uint16_t *)io.out; a.evict_idx = io.evict_idx;
+    GroupArgs ga;
+    ga.table = (const UnitArgs *)table;
+    ga.wgs_per_cache = p.units * a.s_active;
+    ga.q_stride = (long long)p.units * p.G * 128;
+    ga.kv_stride = (long long)p.units * 128;
+    ga.ev_stride = p.units;
+    size_t lds = unit_mfma_lds_bytes(p.N, p.G, stash, p.unit_S);
     // With at most a few workgroups per compute unit, ask for more than half of the
     // CU's LDS so that no CU is handed two of them while another one idles.
-    if ((long)p.units * a.s_active <= 2 * 256 && lds < 81 * 1024) lds = 81 * 1024;
-    static bool attr_done[4] = {false, false, false, false};
-#define LF_UNIT(STASH, COOP, IDX)                                                                    \
+    const long long wgs = (long long)ga.wgs_per_cache * n_caches;
+    if (wgs <= 2 * 256 && lds < 81 * 1024) lds = 81 * 1024;
+    if (wgs > 0x7fffffffll) return hipErrorInvalidValue;
+    static bool attr_done[8] = {false, false, false, false, false, false, false, false};
+#define LF_UNIT(STASH, COOP, GROUPED, IDX)                                                            \
     do {                                                                                              \
         if (!attr_done[IDX]) {                                                                        \
-            hipError_t e = hipFuncSetAttribute((const void *)unit_mfma_kernel<true, STASH, COOP>,     \
+            hipError_t e = hipFuncSetAttribute((const void *)unit_mfma_kernel<true, STASH, COOP, GROUPED>, \
                                                hipFuncAttributeMaxDynamicSharedMemorySize, (int)kUnitLdsLimit); \
             if (e != hipSuccess) return e;                                                            \
             attr_done[IDX] = true;                                                                    \
         }                                                                                             \
-        hipLaunchKernelGGL((unit_mfma_kernel<true, STASH, COOP>), dim3(p.units * a.s_active), dim3(512), lds, s, a); \
+        hipLaunchKernelGGL((unit_mfma_kernel<true, STASH, COOP, GROUPED>), dim3((unsigned)wgs), dim3(512), lds, s, a, ga); \
     } while (0)
     const bool coop = p.unit_S > 1;
-    if (stash) { if (coop) LF_UNIT(kStashLds, true, 0); else LF_UNIT(kStashLds, false, 1); }
-    else       { if (coop) LF_UNIT(kStashNone, true, 2); else LF_UNIT(kStashNone, false, 3); }
+    if (table) {
+        if (stash) { if (coop) LF_UNIT(kStashLds, true, true, 4); else LF_UNIT(kStashLds, false, true, 5); }
+        else       { if (coop) LF_UNIT(kStashNone, true, true, 6); else LF_UNIT(kStashNone, false, true, 7); }
+    } else {
+        if (stash) { if (coop) LF_UNIT(kStashLds, true, false, 0); else LF_UNIT(kStashLds, false, false, 1); }
+        else       { if (coop) LF_UNIT(kStashNone, true, false, 2); else LF_UNIT(kStashNone, false, false, 3); }
+    }
 #undef LF_UNIT
     return hipGetLastError();
+}
+
+hipError_t launch_unit_mfma(const Plan &p, const void *q, const void *k_new, const void *v_new, int n,
+                            void *out, int32_t *evict_idx, hipStream_t s)
+{
+    const StepIo io = {q, k_new, v_new, out, evict_idx};
+    return launch_unit(p, io, n, nullptr, 1, s);
+}
+
+hipError_t launch_unit_mfma_group(const Plan &p, const StepIo &io, int n, const void *table, int n_caches,
+                                  hipStream_t s)
+{
+    return launch_unit(p, io, n, table, n_caches, s);
 }
 
 } // namespace lf

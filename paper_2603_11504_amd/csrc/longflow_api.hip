@@ -134,9 +134,17 @@ struct longflow_cache {
     bool stepped;      // at least one decode step ran (scores are defined)
     std::vector<hipEvent_t> prof_events; // 2 per recorded step while profiling
     int prof_cap = 0, prof_used = 0;
+    int groups = 0;    // live groups this cache is a member of
 };
 
 static const uint32_t kMagic = 0x4c46434bu;
+static const uint32_t kGroupMagic = 0x4c464752u;
+
+struct longflow_group {
+    uint32_t magic;
+    std::vector<longflow_cache *> members;
+    void *table; // device: one kernel-argument entry per member (unit-resident path only)
+};
 
 using namespace lf;
 
@@ -292,6 +300,110 @@ int longflow_set_pending(longflow_cache_t *cache, const int32_t *slots, void *hi
     return LF_OK;
 }
 
+size_t longflow_group_workspace_bytes(int32_t n_caches)
+{
+    if (n_caches < 1) return 0;
+    return align_up(unit_mfma_table_entry_bytes() * (size_t)n_caches, 256);
+}
+
+int longflow_group_create(longflow_group_t **group, longflow_cache_t *const *caches, int32_t n_caches,
+                          void *workspace, size_t workspace_bytes, void *hip_stream)
+{
+    if (!group) return fail(LF_ERR_INVALID_ARG, "group is NULL");
+    *group = nullptr;
+    if (!caches || n_caches < 1) return fail(LF_ERR_INVALID_ARG, "no caches given");
+    if (!workspace || ((uintptr_t)workspace & 255u))
+        return fail(LF_ERR_INVALID_ARG, "workspace is NULL or not 256-byte aligned");
+    if (workspace_bytes < longflow_group_workspace_bytes(n_caches))
+        return fail(LF_ERR_WORKSPACE, "group workspace has %zu bytes, %zu needed", workspace_bytes,
+                    longflow_group_workspace_bytes(n_caches));
+    std::vector<longflow_cache *> members;
+    for (int i = 0; i < n_caches; ++i) {
+        longflow_cache *c = checked(caches[i]);
+        if (!c) return fail(LF_ERR_STATE, "member %d: invalid or destroyed cache handle", i);
+        for (longflow_cache *m : members)
+            if (m == c) return fail(LF_ERR_INVALID_ARG, "member %d appears twice", i);
+        const Plan &a = c->plan, &b = (members.empty() ? c : members[0])->plan;
+        if (a.B != b.B || a.Hq != b.Hq || a.Hkv != b.Hkv || a.D != b.D || a.N != b.N || a.dtype != b.dtype ||
+            a.flags != b.flags)
+            return fail(LF_ERR_INVALID_ARG, "member %d differs from member 0 in its configuration", i);
+        members.push_back(c);
+    }
+    const size_t eb = unit_mfma_table_entry_bytes();
+    std::vector<char> host(eb * (size_t)n_caches);
+    for (int i = 0; i < n_caches; ++i) unit_mfma_table_entry(members[i]->plan, host.data() + eb * i);
+    hipError_t e = hipMemcpyAsync(workspace, host.data(), host.size(), hipMemcpyHostToDevice, (hipStream_t)hip_stream);
+    if (e == hipSuccess) e = hipStreamSynchronize((hipStream_t)hip_stream); // `host` goes out of scope
+    if (e != hipSuccess) return fail(LF_ERR_HIP, "group table copy: %s", hipGetErrorString(e));
+    longflow_group *g = new longflow_group;
+    g->magic = kGroupMagic;
+    g->members = members;
+    g->table = workspace;
+    for (longflow_cache *m : members) ++m->groups;
+    *group = g;
+    return LF_OK;
+}
+
+int longflow_group_decode_step(longflow_group_t *group, const void *q, const void *k_new, const void *v_new,
+                               void *out, int32_t *evict_idx, void *hip_stream)
+{
+    if (!group || group->magic != kGroupMagic) return fail(LF_ERR_STATE, "invalid or destroyed group handle");
+    longflow_cache *c0 = group->members[0];
+    const Plan &p = c0->plan;
+    const bool attention_only = p.flags & LF_FLAG_ATTENTION_ONLY;
+    if (!q || !out) return fail(LF_ERR_INVALID_ARG, "q/out is NULL");
+    if (!attention_only && (!k_new || !v_new)) return fail(LF_ERR_INVALID_ARG, "k_new/v_new is NULL");
+    if (((uintptr_t)q & 15u) || ((uintptr_t)out & 15u))
+        return fail(LF_ERR_INVALID_ARG, "q/out must be 16-byte aligned");
+    for (size_t i = 0; i < group->members.size(); ++i) {
+        const longflow_cache *c = group->members[i];
+        if (c->count != c0->count)
+            return fail(LF_ERR_STATE, "member %zu holds %d rows, member 0 holds %d", i, c->count, c0->count);
+        if (!attention_only && !c->has_pending)
+            return fail(LF_ERR_STATE, "member %zu is full and no slot is pending: call longflow_set_pending", i);
+    }
+    int n;
+    if (attention_only) {
+        if (c0->count < 1) return fail(LF_ERR_STATE, "attention over an empty cache");
+        n = c0->count;
+    } else {
+        n = c0->count < p.N ? c0->count + 1 : p.N;
+    }
+    hipStream_t s = (hipStream_t)hip_stream;
+    const int nc = (int)group->members.size();
+    const StepIo io = {q, k_new, v_new, out, evict_idx};
+    if (p.use_unit) {
+        hipError_t e = launch_unit_mfma_group(p, io, n, group->table, nc, s);
+        if (e != hipSuccess) return fail(LF_ERR_HIP, "group decode launch: %s", hipGetErrorString(e));
+    } else {
+        // the split-K kernels take one cache per launch
+        const size_t esz = p.dtype == LF_F32 ? 4 : 2;
+        const size_t qb = esz * (size_t)p.B * p.Hq * p.D, kb = esz * (size_t)p.units * p.D;
+        for (int i = 0; i < nc; ++i) {
+            const Plan &pi = group->members[i]->plan;
+            const StepIo ii = {(const char *)q + qb * i, k_new ? (const char *)k_new + kb * i : nullptr,
+                               v_new ? (const char *)v_new + kb * i : nullptr, (char *)out + qb * i,
+                               evict_idx ? evict_idx + (size_t)p.units * i : nullptr};
+            hipError_t e = pi.use_mfma ? launch_split_mfma(pi, ii, n, s) : launch_split_valu(pi, ii, n, s);
+            if (e != hipSuccess) return fail(LF_ERR_HIP, "group decode launch %d: %s", i, hipGetErrorString(e));
+        }
+    }
+    for (longflow_cache *c : group->members) {
+        c->count = n;
+        c->stepped = true;
+    }
+    return LF_OK;
+}
+
+int longflow_group_destroy(longflow_group_t *group)
+{
+    if (!group || group->magic != kGroupMagic) return fail(LF_ERR_STATE, "invalid or destroyed group handle");
+    for (longflow_cache *m : group->members) --m->groups;
+    group->magic = 0;
+    delete group;
+    return LF_OK;
+}
+
 static void drop_events(longflow_cache *c)
 {
     for (hipEvent_t e : c->prof_events) (void)hipEventDestroy(e);
@@ -348,6 +460,7 @@ int longflow_destroy_cache(longflow_cache_t *cache)
 {
     longflow_cache *c = checked(cache);
     if (!c) return fail(LF_ERR_STATE, "invalid or destroyed cache handle");
+    if (c->groups > 0) return fail(LF_ERR_STATE, "cache is a member of %d live group(s): destroy them first", c->groups);
     drop_events(c);
     c->magic = 0;
     delete c;

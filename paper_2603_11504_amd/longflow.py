@@ -24,7 +24,8 @@ LF_FLAG_FORCE_UNIT = 8
 EXPORTS = ("longflow_workspace_bytes", "longflow_init_cache", "longflow_decode_step",
            "longflow_scores", "longflow_set_pending", "longflow_valid_count",
            "longflow_destroy_cache", "longflow_last_error", "longflow_profile_begin",
-           "longflow_profile_end")
+           "longflow_profile_end", "longflow_group_workspace_bytes", "longflow_group_create",
+           "longflow_group_decode_step", "longflow_group_destroy")
 
 
 class lf_config(ctypes.Structure):
@@ -69,6 +70,14 @@ def lib():
         L.longflow_profile_begin.restype = ctypes.c_int
         L.longflow_profile_end.argtypes = [vp, ctypes.POINTER(ctypes.c_float), ctypes.POINTER(i32)]
         L.longflow_profile_end.restype = ctypes.c_int
+        L.longflow_group_workspace_bytes.argtypes = [i32]
+        L.longflow_group_workspace_bytes.restype = ctypes.c_size_t
+        L.longflow_group_create.argtypes = [ctypes.POINTER(vp), ctypes.POINTER(vp), i32, vp, ctypes.c_size_t, vp]
+        L.longflow_group_create.restype = ctypes.c_int
+        L.longflow_group_decode_step.argtypes = [vp] * 7
+        L.longflow_group_decode_step.restype = ctypes.c_int
+        L.longflow_group_destroy.argtypes = [vp]
+        L.longflow_group_destroy.restype = ctypes.c_int
         L.longflow_last_error.argtypes = []
         L.longflow_last_error.restype = ctypes.c_char_p
         _lib = L
@@ -168,6 +177,47 @@ class LongFlowCache:
         try:
             if getattr(self, "_h", None):
                 lib().longflow_destroy_cache(self._h)
+                self._h = None
+        except Exception:
+            pass
+
+
+class LongFlowGroup:
+    """Caches of one configuration and fill level that take their decode step in one launch."""
+
+    def __init__(self, caches):
+        self.caches = list(caches)
+        n = len(self.caches)
+        c0 = self.caches[0]
+        self.device = c0.device
+        nbytes = int(lib().longflow_group_workspace_bytes(n))
+        self.workspace = torch.empty(max(nbytes, 1), dtype=torch.uint8, device=self.device)
+        handles = (ctypes.c_void_p * n)(*[c._h for c in self.caches])
+        h = ctypes.c_void_p()
+        _check(lib().longflow_group_create(ctypes.byref(h), handles, n, _ptr(self.workspace), nbytes, _stream()))
+        self._h = h
+        cfg = c0.cfg
+        self.out = torch.empty((n, cfg.batch, cfg.q_heads, cfg.head_dim), dtype=c0.dtype, device=self.device)
+        self.evict_idx = torch.empty((n, cfg.batch, cfg.kv_heads), dtype=torch.int32, device=self.device)
+
+    def decode_step(self, q, k_new=None, v_new=None, out=None, evict_idx=None):
+        """q/out: [n_caches, B, Hq, D]; k_new/v_new: [n_caches, B, Hkv, D], all contiguous."""
+        out = self.out if out is None else out
+        evict_idx = self.evict_idx if evict_idx is None else evict_idx
+        _check(lib().longflow_group_decode_step(self._h, _ptr(q), _ptr(k_new), _ptr(v_new), _ptr(out),
+                                                _ptr(evict_idx), _stream()))
+        return out, evict_idx
+
+    def close(self):
+        if getattr(self, "_h", None):
+            torch.cuda.synchronize(self.device)
+            lib().longflow_group_destroy(self._h)
+            self._h = None
+
+    def __del__(self):
+        try:
+            if getattr(self, "_h", None):
+                lib().longflow_group_destroy(self._h)
                 self._h = None
         except Exception:
             pass

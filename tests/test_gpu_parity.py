@@ -358,3 +358,117 @@ def test_independent_caches_on_two_streams_match_serial_execution():
             c.close()
     for (o1, i1), (o2, i2) in zip(outs["serial"], outs["streams"]):
         assert torch.equal(o1.view(torch.int16), o2.view(torch.int16)) and torch.equal(i1, i2)
+
+
+# ------------------------------------------------------------------ several caches in one launch
+
+class _GroupMember:
+    """Looks like one LongFlowCache to run_lockstep; every step runs the whole group."""
+
+    def __init__(self, group, j, wl, seed):
+        self.group, self.j, self.wl = group, j, wl
+        self.gen = torch.Generator(device="cuda").manual_seed(seed)
+
+    def decode_step(self, q, k, v):
+        n = len(self.group.caches)
+        dt = W.torch_dtype(self.wl)
+        qa = torch.randn((n,) + tuple(q.shape), device="cuda", dtype=torch.float32, generator=self.gen).to(dt)
+        ka = torch.randn((n,) + tuple(k.shape), device="cuda", dtype=torch.float32, generator=self.gen).to(dt)
+        va = torch.randn((n,) + tuple(v.shape), device="cuda", dtype=torch.float32, generator=self.gen).to(dt)
+        qa[self.j], ka[self.j], va[self.j] = q, k, v
+        out, idx = self.group.decode_step(qa, ka, va)
+        return out[self.j], idx[self.j]
+
+    @property
+    def valid_count(self):
+        return self.group.caches[self.j].valid_count
+
+    def scores(self):
+        return self.group.caches[self.j].scores()
+
+
+def _make_caches(wl, n, flags=0):
+    dt = W.torch_dtype(wl)
+    caches = []
+    for layer in range(n):
+        k0, v0 = W.host_prefill(wl, layer)
+        caches.append(lf.LongFlowCache(wl.batch, wl.q_heads, wl.kv_heads, wl.head_dim, wl.budget, dtype=dt, flags=flags,
+                                       k_init=None if k0 is None else W.to_torch(k0, wl, "cuda"),
+                                       v_init=None if v0 is None else W.to_torch(v0, wl, "cuda")))
+    return caches
+
+
+@pytest.mark.parametrize("name,dtype,B,Hq,Hkv,D,N,flags", [
+    ("coop", "bf16", 2, 28, 4, 128, 2048, 0),            # several workgroups per unit
+    ("single", "bf16", 48, 32, 8, 128, 300, 0),           # one workgroup per unit, ragged tail
+    ("split", "bf16", 4, 8, 2, 128, 1024, lf.LF_FLAG_FORCE_SPLIT),  # falls back to one launch per member
+    ("fp32", "f32", 2, 8, 2, 64, 200, 0),
+])
+def test_group_step_equals_member_steps(name, dtype, B, Hq, Hkv, D, N, flags):
+    # fill phase into eviction phase; the group must give every member the bits it gets alone
+    wl = _small("group-" + name, dtype, B, Hq, Hkv, D, N, n_init=N - 3, steps=8, seed=91)
+    alone, members = _make_caches(wl, 3, flags), _make_caches(wl, 3, flags)
+    group = lf.LongFlowGroup(members)
+    view = torch.int16 if dtype == "bf16" else torch.int32
+    for t in range(wl.steps):
+        qs, ks, vs = zip(*[[W.to_torch(x, wl, "cuda") for x in W.host_step(wl, t, layer)] for layer in range(3)])
+        out, idx = group.decode_step(torch.stack(qs), torch.stack(ks), torch.stack(vs))
+        for j, c in enumerate(alone):
+            o1, i1 = c.decode_step(qs[j], ks[j], vs[j])
+            assert torch.equal(o1.view(view), out[j].view(view)), f"{name} step {t} member {j}: out differs"
+            assert torch.equal(i1, idx[j]), f"{name} step {t} member {j}: eviction index differs"
+            assert members[j].valid_count == c.valid_count
+    torch.cuda.synchronize()
+    group.close()
+    for c in alone + members:
+        c.close()
+
+
+def test_group_member_against_oracle():
+    wl = _small("group-oracle", "bf16", 2, 28, 4, 128, 640, n_init=600, steps=120, seed=92)
+    members = _make_caches(wl, 3)
+    # run_lockstep prefills its oracle from layer 0: follow member 0, the others carry noise
+    group = lf.LongFlowGroup(members)
+    rep, _, _ = run_lockstep(wl, gpu_cache=_GroupMember(group, 0, wl, seed=5), check_scores_every=40)
+    assert rep.steps == 120 and rep.decisions > 0
+    group.close()
+    for c in members:
+        c.close()
+
+
+def test_group_attention_only_and_errors():
+    wl = _small("group-att", "bf16", 4, 16, 4, 128, 512, n_init=512, steps=2, seed=93)
+    att = _make_caches(wl, 2, lf.LF_FLAG_ATTENTION_ONLY)
+    twin = _make_caches(wl, 2, lf.LF_FLAG_ATTENTION_ONLY)
+    g = lf.LongFlowGroup(att)
+    qs = [W.to_torch(W.host_step(wl, 0, layer)[0], wl, "cuda") for layer in range(2)]
+    out, _ = g.decode_step(torch.stack(qs))
+    for j in range(2):
+        o1, _ = twin[j].decode_step(qs[j])
+        assert torch.equal(o1.view(torch.int16), out[j].view(torch.int16))
+    # a member cannot be destroyed under a live group
+    assert lf.lib().longflow_destroy_cache(att[0]._h) == lf.LF_ERR_STATE
+    g.close()
+    # members that differ in configuration or in fill level are refused
+    other = _make_caches(_small("group-att2", "bf16", 4, 16, 4, 128, 256, n_init=256, steps=2, seed=94), 1,
+                         lf.LF_FLAG_ATTENTION_ONLY)
+    with pytest.raises(lf.LongFlowError) as e:
+        lf.LongFlowGroup([att[0], other[0]])
+    assert e.value.status == lf.LF_ERR_INVALID_ARG
+    with pytest.raises(lf.LongFlowError) as e:
+        lf.LongFlowGroup([att[0], att[0]])
+    assert e.value.status == lf.LF_ERR_INVALID_ARG
+    wl2 = _small("group-fill", "bf16", 4, 16, 4, 128, 512, n_init=100, steps=2, seed=95)
+    fill = _make_caches(wl2, 2)
+    g2 = lf.LongFlowGroup(fill)
+    q, k, v = (W.to_torch(x, wl2, "cuda") for x in W.host_step(wl2, 0, 0))
+    fill[0].decode_step(q, k, v)  # member 0 runs ahead
+    with pytest.raises(lf.LongFlowError) as e:
+        g2.decode_step(torch.stack([q, q]), torch.stack([k, k]), torch.stack([v, v]))
+    assert e.value.status == lf.LF_ERR_STATE
+    fill[1].decode_step(q, k, v)  # level again: the group works
+    g2.decode_step(torch.stack([q, q]), torch.stack([k, k]), torch.stack([v, v]))
+    torch.cuda.synchronize()
+    g2.close()
+    for c in att + twin + other + fill:
+        c.close()
