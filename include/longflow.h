@@ -141,8 +141,11 @@ LF_API int longflow_destroy_cache(longflow_cache_t *cache);
  * static memory, one fused kernel), so caches that are independent of each other --
  * micro-batches, or the layers of a synthetic benchmark -- can share one grid: the launch
  * and the drain between kernels are paid once per group, and a small cache no longer
- * leaves most of the chip idle.  Each member computes exactly what longflow_decode_step
- * computes for it (same kernels, same arithmetic, same order).
+ * leaves most of the chip idle.  Each member gets what longflow_decode_step computes for
+ * it, from the same kernels.  Where the group serves a (batch, KV head) pair with fewer
+ * cooperating workgroups than the cache would use on its own, the partial sums of `out`
+ * are merged in another order and may differ from a lone call's in the last bits; the
+ * eviction index comes from the same exact re-scoring either way.
  *
  *   longflow_group_workspace_bytes  device bytes a group of n_caches needs (0 if n_caches < 1)
  *   longflow_group_create   caches: host array of n_caches handles with identical lf_config

@@ -24,6 +24,7 @@
 // in -- their authors passed arrive[u] before it did, so they are running or done -- and
 // decides the eviction from its own LDS codes plus the dumps.  If the bounded wait ever
 // expired it would re-score every slot exactly instead of trusting incomplete dumps.
+#include <algorithm>
 #include <cstring>
 
 #include "lf_mfma_stream.h"
@@ -109,7 +110,7 @@ __device__ __forceinline__ double exp2_frac_f64(double x)
 //   (log2 domain); sL: denominator per head.
 //   coherent: read the row with device-scope loads (it was written during this launch by
 //   another workgroup)
-__device__ double exact_score_bf16(const uint16_t *krow, const uint16_t *vrow, const float (*qs)[128], int G,
+__device__ double exact_score_bf16(const uint16_t *krow, const uint16_t *vrow, const uint16_t (*qs)[128], int G,
                                    const float *sM, const float *sL, int lane, bool coherent)
 {
     const int h = lane >> 2, part = lane & 3;
@@ -129,16 +130,15 @@ __device__ double exact_score_bf16(const uint16_t *krow, const uint16_t *vrow, c
             } else {
                 kk = *(const u32x4 *)(krow + 32 * part + 8 * c);
             }
-            const f32x4 qa = *(const f32x4 *)(&qs[h][32 * part + 8 * c]);
-            const f32x4 qb = *(const f32x4 *)(&qs[h][32 * part + 8 * c + 4]);
-            dot = fma((double)qa[0], (double)bf16_lo(kk.x), dot);
-            dot = fma((double)qa[1], (double)bf16_hi(kk.x), dot);
-            dot = fma((double)qa[2], (double)bf16_lo(kk.y), dot);
-            dot = fma((double)qa[3], (double)bf16_hi(kk.y), dot);
-            dot = fma((double)qb[0], (double)bf16_lo(kk.z), dot);
-            dot = fma((double)qb[1], (double)bf16_hi(kk.z), dot);
-            dot = fma((double)qb[2], (double)bf16_lo(kk.w), dot);
-            dot = fma((double)qb[3], (double)bf16_hi(kk.w), dot);
+            const u32x4 qq = *(const u32x4 *)(&qs[h][32 * part + 8 * c]);
+            dot = fma((double)bf16_lo(qq.x), (double)bf16_lo(kk.x), dot);
+            dot = fma((double)bf16_hi(qq.x), (double)bf16_hi(kk.x), dot);
+            dot = fma((double)bf16_lo(qq.y), (double)bf16_lo(kk.y), dot);
+            dot = fma((double)bf16_hi(qq.y), (double)bf16_hi(kk.y), dot);
+            dot = fma((double)bf16_lo(qq.z), (double)bf16_lo(kk.z), dot);
+            dot = fma((double)bf16_hi(qq.z), (double)bf16_hi(kk.z), dot);
+            dot = fma((double)bf16_lo(qq.w), (double)bf16_lo(kk.w), dot);
+            dot = fma((double)bf16_hi(qq.w), (double)bf16_hi(kk.w), dot);
         }
     }
     dot += __shfl_xor(dot, 1);
@@ -188,7 +188,7 @@ __global__ __launch_bounds__(512, 1) void unit_mfma_kernel(const UnitArgs a_in, 
     __shared__ float red_f[NW];
     __shared__ double best_v[NW];
     __shared__ int best_i[NW];
-    __shared__ float qs[16][D]; // the query as floats, for the exact re-scoring
+    __shared__ __align__(16) uint16_t qs[16][D]; // the query, for the exact re-scoring
     __shared__ int cand_list[kMaxCand];
     __shared__ int cand_count, s_flag;
 
@@ -245,7 +245,7 @@ __global__ __launch_bounds__(512, 1) void unit_mfma_kernel(const UnitArgs a_in, 
         if (g == 0) { sm_m[wave][r] = st.m; sm_l[wave][r] = l; }
     }
     if (STASH == kStashLds) {
-        for (int i = tid; i < G * D; i += 512) qs[i / D][i % D] = bf16_lo((uint32_t)qu[i]);
+        for (int i = tid; i < G * D; i += 512) qs[i / D][i % D] = qu[i];
         if (tid == 0) cand_count = 0;
     }
     __syncthreads();
@@ -597,7 +597,7 @@ size_t unit_mfma_lds_bytes(int N, int G, bool stash, int S)
 }
 
 // everything of a step's kernel arguments that depends on the cache and the fill level only
-static UnitArgs unit_args_of(const Plan &p, int n)
+static UnitArgs unit_args_of(const Plan &p, int n, int S)
 {
     UnitArgs a;
     memset(&a, 0, sizeof(a));
@@ -609,13 +609,13 @@ static UnitArgs unit_args_of(const Plan &p, int n)
     a.arrive = p.arrive; a.dumped = p.dumped;
     a.gcode = (uint8_t *)p.stash_w; a.gref = p.stash_m;
     a.n = n; a.N = p.N; a.G = p.G; a.ntiles = p.ntiles;
-    a.S = p.unit_S; a.split_len = unit_mfma_split_len(p.N, p.unit_S);
+    a.S = S; a.split_len = unit_mfma_split_len(p.N, S);
     a.s_active = (n + a.split_len - 1) / a.split_len;
     a.code_stride = (a.split_len + 63) / 64 * 64;
     a.gstride = p.ntiles * kTile;
     const bool stash = !(p.flags & 1u);
-    const size_t lds = unit_mfma_lds_bytes(p.N, p.G, stash, p.unit_S);
-    a.merge_off = (stash && p.unit_S > 1) ? (int)(lds - kMergeBytes) : 0;
+    const size_t lds = unit_mfma_lds_bytes(p.N, p.G, stash, S);
+    a.merge_off = (stash && S > 1) ? (int)(lds - kMergeBytes) : 0;
     a.scale_log2 = 1.4426950408889634f / sqrtf(128.f);
     return a;
 }
@@ -624,7 +624,7 @@ size_t unit_mfma_table_entry_bytes() { return sizeof(UnitArgs); }
 
 void unit_mfma_table_entry(const Plan &p, void *dst)
 {
-    const UnitArgs a = unit_args_of(p, p.N);
+    const UnitArgs a = unit_args_of(p, p.N, p.unit_S);
     memcpy(dst, &a, sizeof(a));
 }
 
@@ -634,7 +634,16 @@ static hipError_t launch_unit(const Plan &p, const StepIo &io, int n, const void
                               hipStream_t s)
 {
     const bool stash = !(p.flags & 1u);
-    UnitArgs a = unit_args_of(p, n);
+    // Workgroups per unit: the cache's own choice, made for it alone.  A group brings
+    // n_caches times the units, so it needs fewer (never more: the cache's partial and
+    // dump buffers are sized for its own choice) -- as long as the codes still fit LDS.
+    int S = p.unit_S;
+    if (table && S > 1) {
+        int Sg = unit_mfma_splits((int)std::min<long long>((long long)p.units * n_caches, 1 << 20), p.N);
+        while (Sg < S && unit_mfma_lds_bytes(p.N, p.G, stash, Sg) > kUnitLdsLimit) ++Sg;
+        if (Sg < S) S = Sg;
+    }
+    UnitArgs a = unit_args_of(p, n, S);
     a.q = (const uint16_t *)io.q; a.k_new = (const uint16_t *)io.k_new; a.v_new = (const uint16_t *)io.v_new;
     a.out = (uint16_t *)io.out; a.evict_idx = io.evict_idx;
     GroupArgs ga;
@@ -643,7 +652,7 @@ static hipError_t launch_unit(const Plan &p, const StepIo &io, int n, const void
     ga.q_stride = (long long)p.units * p.G * 128;
     ga.kv_stride = (long long)p.units * 128;
     ga.ev_stride = p.units;
-    size_t lds = unit_mfma_lds_bytes(p.N, p.G, stash, p.unit_S);
+    size_t lds = unit_mfma_lds_bytes(p.N, p.G, stash, S);
     // With at most a few workgroups per compute unit, ask for more than half of the
     // CU's LDS so that no CU is handed two of them while another one idles.
     const long long wgs = (long long)ga.wgs_per_cache * n_caches;
@@ -660,7 +669,7 @@ static hipError_t launch_unit(const Plan &p, const StepIo &io, int n, const void
         }                                                                                             \
         hipLaunchKernelGGL((unit_mfma_kernel<true, STASH, COOP, GROUPED>), dim3((unsigned)wgs), dim3(512), lds, s, a, ga); \
     } while (0)
-    const bool coop = p.unit_S > 1;
+    const bool coop = S > 1;
     if (table) {
         if (stash) { if (coop) LF_UNIT(kStashLds, true, true, 4); else LF_UNIT(kStashLds, false, true, 5); }
         else       { if (coop) LF_UNIT(kStashNone, true, true, 6); else LF_UNIT(kStashNone, false, true, 7); }

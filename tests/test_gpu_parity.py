@@ -424,12 +424,17 @@ def test_group_step_equals_member_steps(name, dtype, B, Hq, Hkv, D, N, flags):
         c.close()
 
 
-def test_group_member_against_oracle():
-    wl = _small("group-oracle", "bf16", 2, 28, 4, 128, 640, n_init=600, steps=120, seed=92)
+@pytest.mark.parametrize("B,Hq,Hkv,N", [
+    (2, 28, 4, 640),     # few units: the group keeps the cooperating workgroups
+    (16, 16, 4, 1024),   # 64 units take 2 workgroups each alone, 1 each in a group of 3
+])
+def test_group_member_against_oracle(B, Hq, Hkv, N):
+    wl = _small(f"group-oracle-{B}", "bf16", B, Hq, Hkv, 128, N, n_init=N - 40, steps=120, seed=92)
     members = _make_caches(wl, 3)
     # run_lockstep prefills its oracle from layer 0: follow member 0, the others carry noise
     group = lf.LongFlowGroup(members)
-    rep, _, _ = run_lockstep(wl, gpu_cache=_GroupMember(group, 0, wl, seed=5), check_scores_every=40)
+    rep, _, _ = run_lockstep(wl, gpu_cache=_GroupMember(group, 0, wl, seed=5), check_scores_every=40,
+                             units=None if wl.units <= 16 else list(range(0, wl.units, 5)))
     assert rep.steps == 120 and rep.decisions > 0
     group.close()
     for c in members:
