@@ -105,6 +105,22 @@ def test_cfg4_full_size_sampled_units():
     torch.cuda.empty_cache()
 
 
+@pytest.mark.parametrize("B,Hq,Hkv,N,sample", [
+    (48, 8, 4, 20000, 8),    # one workgroup per unit, more slots than its register window screens in one pass
+    (1, 8, 2, 60000, None),  # eight workgroups per unit
+    (1, 7, 1, 200000, None), # codes exceed LDS even eight ways: the split-K path is chosen by itself
+])
+def test_long_budgets(B, Hq, Hkv, N, sample):
+    wl = _small(f"long_{N}", "bf16", B, Hq, Hkv, 128, N, n_init=N - 2, steps=5, sink_scale=4.0, seed=N)
+    units = None if sample is None else np.arange(0, wl.units, wl.units // sample)
+    rep, gpu, _ = run_lockstep(wl, host_inputs=False, units=units, check_scores_every=4)
+    print(f"\nlong budget {N}: decisions {rep.decisions} near-ties {rep.near_ties} max|dout| {rep.max_out_err:.2e}")
+    assert rep.steps == 5
+    gpu.close()
+    del gpu
+    torch.cuda.empty_cache()
+
+
 # ------------------------------------------------------------------ edge cases
 
 @pytest.mark.parametrize("flags", [lf.LF_FLAG_FORCE_SPLIT, lf.LF_FLAG_FORCE_UNIT], ids=["split", "unit"])
