@@ -25,9 +25,9 @@ DEFAULT_STEPS = {0: 512, 1: 1024, 2: 100, 3: 256, 4: 50}
 # HBM bytes per launch of the streaming kernel measured with rocprofv3 --pmc
 # (FETCH_SIZE / WRITE_SIZE, scaled by copy kernels of known size); see profiles/.
 MEASURED_TRAFFIC = {
-    ("cfg3_bf16_b64_28x4_d128_n8192_l28", "unit_mfma_kernel"): {"read_bytes": 1058323 * 1024, "write_bytes": 1076 * 1024,
+    ("cfg3_bf16_b64_28x4_d128_n8192_l28", "unit_mfma_kernel"): {"read_bytes": 1058518 * 1024, "write_bytes": 1076 * 1024,
                                                                 "source": "profiles/unit_mfma_kernel_cfg3.txt"},
-    ("cfg4_bf16_b128_40x8_d128_n16384", "unit_mfma_kernel"): {"read_bytes": 8458816 * 1024, "write_bytes": 3264 * 1024,
+    ("cfg4_bf16_b128_40x8_d128_n16384", "unit_mfma_kernel"): {"read_bytes": 8459015 * 1024, "write_bytes": 3264 * 1024,
                                                               "source": "profiles/unit_mfma_kernel_cfg4.txt"},
 }
 
@@ -50,6 +50,10 @@ def parse():
     ap.add_argument("--streams", type=int, default=1,
                     help="HIP streams the independent layer caches are spread over in the timed pass (default 1: "
                          "all calls back-to-back on one stream)")
+    ap.add_argument("--also-streams", type=int, default=0,
+                    help="time the same steps once more with the layer calls spread over this many streams "
+                         "(extra JSON fields; off by default so that a kernel trace of the default run holds "
+                         "no overlapped launches)")
     return ap.parse_args()
 
 
@@ -265,7 +269,7 @@ def main():
     flags |= lf.LF_FLAG_FORCE_SPLIT if a.split else 0
     flags |= lf.LF_FLAG_FORCE_UNIT if a.unit else 0
     r = measure(wl, flags, steps, a.warmup, pool=a.pool, with_cpu=not a.no_cpu_baseline,
-                calibrate_copy=a.calibrate_copy, streams=a.streams, also_streams=4 if a.streams == 1 else 0,
+                calibrate_copy=a.calibrate_copy, streams=a.streams, also_streams=a.also_streams if a.streams == 1 else 0,
                 also_grouped=a.streams == 1 and wl.layers > 1)
     kname = r["kernel"]
     out = {
@@ -274,7 +278,7 @@ def main():
         "unit": "tokens/s",
         "n_gpus": 1, "steps": steps, "warmup": r["warm"], "ms_per_step": r["ms_per_step"],
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
-        "dtype": "f32" if wl.dtype == "f32" else "bf16 storage, f32 accumulate",
+        "dtype": "f32" if wl.dtype == "f32" else "bf16",   # bf16 operands, f32 accumulation
         "data": "synthetic",
         "config": {"workload": wl.name, "batch": wl.batch, "q_heads": wl.q_heads, "kv_heads": wl.kv_heads,
                    "head_dim": wl.head_dim, "budget": wl.budget, "layers": wl.layers,
@@ -292,9 +296,10 @@ def main():
                      "traffic": MEASURED_TRAFFIC.get((wl.name, kname))},
     }
     if r.get("ms_per_step_multi"):
-        # the same steps with the independent layer calls spread over 4 streams (tails overlap)
-        out["ms_per_step_4_streams"] = r["ms_per_step_multi"]
-        out["step_hbm_frac_4_streams"] = r["bytes_call"] * wl.layers / (r["ms_per_step_multi"] * 1e-3) / 1e9 / HBM_PEAK_GBS
+        # the same steps with the independent layer calls spread over several streams (tails overlap)
+        out["also_streams"] = a.also_streams
+        out["ms_per_step_multi_stream"] = r["ms_per_step_multi"]
+        out["step_hbm_frac_multi_stream"] = r["bytes_call"] * wl.layers / (r["ms_per_step_multi"] * 1e-3) / 1e9 / HBM_PEAK_GBS
     if r.get("ms_per_step_grouped"):
         # the same steps with all layer caches served by one launch per step
         out["ms_per_step_grouped"] = r["ms_per_step_grouped"]
