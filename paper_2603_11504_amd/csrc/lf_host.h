@@ -57,8 +57,13 @@ struct StepIo {
     void *out;
     int32_t *evict_idx;
 };
-hipError_t launch_split_valu(const Plan &p, const StepIo &io, int n, hipStream_t s);
-hipError_t launch_split_mfma(const Plan &p, const StepIo &io, int n, hipStream_t s);
+// table/n_caches: several caches in one grid (see split_table_entry); nullptr/1 = one cache
+hipError_t launch_split_valu(const Plan &p, const StepIo &io, int n, hipStream_t s, const void *table = nullptr,
+                             int n_caches = 1);
+hipError_t launch_split_mfma(const Plan &p, const StepIo &io, int n, hipStream_t s, const void *table = nullptr,
+                             int n_caches = 1);
+size_t split_table_entry_bytes();
+void split_table_entry(const Plan &p, void *dst);
 int unit_mfma_splits(int units, int N);
 int unit_mfma_split_len(int N, int S);
 size_t unit_mfma_lds_bytes(int N, int G, bool stash, int S);

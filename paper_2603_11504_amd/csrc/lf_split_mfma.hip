@@ -8,16 +8,19 @@
 namespace lf {
 
 template <bool HILO, int STASH>
-__global__ __launch_bounds__(256, 2) void split_mfma_kernel(const SplitTailArgs<bf16_t> ta, float scale_log2)
+__global__ __launch_bounds__(256, 2) void split_mfma_kernel(const SplitTailArgs<bf16_t> ta_in, float scale_log2,
+                                                             const SplitGroup gr)
 {
     constexpr int D = 128;
+    SplitTailArgs<bf16_t> ta = ta_in;
+    const int blk = split_group_select(ta, gr);
     const int n = ta.n, N = ta.N, G = ta.G, L = ta.L, C = ta.C, ntiles = ta.ntiles, c_active = ta.c_active;
     const uint16_t *Kc = (const uint16_t *)ta.Kc, *Vc = (const uint16_t *)ta.Vc, *q = (const uint16_t *)ta.q;
     float *part_m = ta.part_m, *part_l = ta.part_l, *part_o = ta.part_o;
     uint16_t *stash_w = ta.stash_w;
     float *stash_m = ta.stash_m;
     const float *lu = ta.lu;
-    const int u = blockIdx.x / c_active, c = blockIdx.x % c_active;
+    const int u = blk / c_active, c = blk % c_active;
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
 
     split_head_insert<bf16_t, D>(ta, u, c);
@@ -63,16 +66,18 @@ __global__ __launch_bounds__(256, 2) void split_mfma_kernel(const SplitTailArgs<
     split_tail<bf16_t, D>(ta, u);
 }
 
-hipError_t launch_split_mfma(const Plan &p, const StepIo &io, int n, hipStream_t s)
+hipError_t launch_split_mfma(const Plan &p, const StepIo &io, int n, hipStream_t s, const void *table, int n_caches)
 {
-    const SplitTailArgs<bf16_t> ta = make_tail_args<bf16_t>(p, io, n);
+    const SplitTailArgs<bf16_t> ta = make_tail_args<bf16_t>(p, io, n, n_caches);
+    const SplitGroup gr = make_split_group(p, table, p.units * ta.c_active);
     const float scale_log2 = 1.4426950408889634f / sqrtf(128.f);
+    const dim3 grid(p.units * ta.c_active * n_caches);
     if (p.flags & 1u)
-        hipLaunchKernelGGL((split_mfma_kernel<true, kStashNone>), dim3(p.units * ta.c_active), dim3(256), 0, s, ta, scale_log2);
+        hipLaunchKernelGGL((split_mfma_kernel<true, kStashNone>), grid, dim3(256), 0, s, ta, scale_log2, gr);
     else
-        hipLaunchKernelGGL((split_mfma_kernel<true, kStashGlobal>), dim3(p.units * ta.c_active), dim3(256), 0, s, ta, scale_log2);
+        hipLaunchKernelGGL((split_mfma_kernel<true, kStashGlobal>), grid, dim3(256), 0, s, ta, scale_log2, gr);
     hipError_t e = hipGetLastError();
-    if (e == hipSuccess && !ta.fused_tail) e = launch_split_finish<bf16_t, 128>(ta, p.units, s);
+    if (e == hipSuccess && !ta.fused_tail) e = launch_split_finish<bf16_t, 128>(ta, p.units, gr, n_caches, s);
     return e;
 }
 

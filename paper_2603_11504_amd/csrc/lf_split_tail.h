@@ -37,14 +37,23 @@ template <typename T> struct SplitTailArgs {
 // The fused tail needs a device-wide release/acquire per workgroup, which on this chip
 // writes back each XCD's L2: cheap for a few dozen workgroups, ruinous for thousands
 // (measured: 82 -> 517 us at 2048 workgroups).  Large grids take a separate finish launch.
-inline bool split_uses_fused_tail(const Plan &p, int n)
+inline bool split_uses_fused_tail(const Plan &p, int n, int n_caches = 1)
 {
-    const long wgs = (long)p.units * ((n + p.L - 1) / p.L);
+    const long long wgs = (long long)p.units * ((n + p.L - 1) / p.L) * n_caches;
     return wgs <= 256;
 }
 
+// Several caches of one geometry and fill level in one grid: per-cache pointers come from a
+// device table of SplitTailArgs, the step's tensors from base pointers plus a stride per
+// cache (in elements).  table == nullptr: a single cache, arguments as passed.
+struct SplitGroup {
+    const void *table;
+    int per_cache;     // workgroups per cache in this launch
+    long long q_stride, kv_stride, ev_stride;
+};
+
 template <typename T>
-inline SplitTailArgs<T> make_tail_args(const Plan &p, const StepIo &io, int n)
+inline SplitTailArgs<T> make_tail_args(const Plan &p, const StepIo &io, int n, int n_caches = 1)
 {
     SplitTailArgs<T> a;
     a.Kc = (T *)p.k_cache; a.Vc = (T *)p.v_cache;
@@ -58,8 +67,42 @@ inline SplitTailArgs<T> make_tail_args(const Plan &p, const StepIo &io, int n)
     a.n = n; a.N = p.N; a.G = p.G; a.C = p.C; a.c_active = (n + p.L - 1) / p.L; a.ntiles = p.ntiles; a.L = p.L;
     a.attention_only = (p.flags & 1u) ? 1 : 0;
     a.pos_order = p.use_mfma ? 1 : 0;
-    a.fused_tail = split_uses_fused_tail(p, n) ? 1 : 0;
+    a.fused_tail = split_uses_fused_tail(p, n, n_caches) ? 1 : 0;
     return a;
+}
+
+inline SplitGroup make_split_group(const Plan &p, const void *table, int per_cache)
+{
+    SplitGroup g;
+    g.table = table;
+    g.per_cache = per_cache;
+    g.q_stride = (long long)p.units * p.G * p.D;
+    g.kv_stride = (long long)p.units * p.D;
+    g.ev_stride = p.units;
+    return g;
+}
+
+// Workgroup's index within its cache; for a group, `a` is switched to that cache first.
+template <typename T>
+__device__ __forceinline__ int split_group_select(SplitTailArgs<T> &a, const SplitGroup &gr)
+{
+    int blk = blockIdx.x;
+    if (gr.table) {
+        const int ci = blk / gr.per_cache;
+        blk -= ci * gr.per_cache;
+        const SplitTailArgs<T> *t = (const SplitTailArgs<T> *)gr.table + ci;
+        a.Kc = t->Kc; a.Vc = t->Vc; a.q_last = t->q_last;
+        a.pending = t->pending; a.arrive = t->arrive;
+        a.part_m = t->part_m; a.part_l = t->part_l; a.part_o = t->part_o;
+        a.stash_w = t->stash_w; a.stash_m = t->stash_m;
+        a.fin_m = t->fin_m; a.fin_l = t->fin_l; a.lu = t->lu;
+        a.q += ci * gr.q_stride;
+        a.out += ci * gr.q_stride;
+        if (a.k_new) a.k_new += ci * gr.kv_stride;
+        if (a.v_new) a.v_new += ci * gr.kv_stride;
+        if (a.evict_idx) a.evict_idx += ci * gr.ev_stride;
+    }
+    return blk;
 }
 
 // ---- head: executed by all 256 threads of the workgroup (unit u, split c)
@@ -274,15 +317,19 @@ __device__ __forceinline__ void split_tail(const SplitTailArgs<T> &a, int u)
 
 // stand-alone finish for large grids: one workgroup per unit
 template <typename T, int D>
-__global__ __launch_bounds__(256) void split_finish_kernel(const SplitTailArgs<T> a)
+__global__ __launch_bounds__(256) void split_finish_kernel(const SplitTailArgs<T> a_in, const SplitGroup gr)
 {
-    split_finish_unit<T, D>(a, blockIdx.x);
+    SplitTailArgs<T> a = a_in;
+    const int u = split_group_select(a, gr);
+    split_finish_unit<T, D>(a, u);
 }
 
+// gr.per_cache of the main launch is units * c_active; the finish grid has one workgroup per unit
 template <typename T, int D>
-inline hipError_t launch_split_finish(const SplitTailArgs<T> &a, int units, hipStream_t s)
+inline hipError_t launch_split_finish(const SplitTailArgs<T> &a, int units, SplitGroup gr, int n_caches, hipStream_t s)
 {
-    hipLaunchKernelGGL((split_finish_kernel<T, D>), dim3(units), dim3(256), 0, s, a);
+    gr.per_cache = units;
+    hipLaunchKernelGGL((split_finish_kernel<T, D>), dim3(units * n_caches), dim3(256), 0, s, a, gr);
     return hipGetLastError();
 }
 

@@ -10,6 +10,8 @@
 
 #include "lf_device.h"
 #include "lf_host.h"
+#include <cstring>
+
 #include "lf_split_tail.h"
 
 namespace lf {
@@ -31,16 +33,18 @@ template <int JJ> __device__ __forceinline__ float row16_bcast(float x)
 }
 
 template <typename T, int D, int G>
-__global__ __launch_bounds__(256) void split_valu_kernel(const SplitTailArgs<T> ta, float scale_log2)
+__global__ __launch_bounds__(256) void split_valu_kernel(const SplitTailArgs<T> ta_in, float scale_log2, const SplitGroup gr)
 {
     constexpr int EPL = D / 16; // elements per lane of a 16-lane row
+    SplitTailArgs<T> ta = ta_in;
+    const int blk = split_group_select(ta, gr);
     const int n = ta.n, N = ta.N, L = ta.L, C = ta.C, ntiles = ta.ntiles, c_active = ta.c_active;
     const T *Kc = ta.Kc, *Vc = ta.Vc, *q = ta.q;
     float *part_m = ta.part_m, *part_l = ta.part_l, *part_o = ta.part_o;
     uint16_t *stash_w = ta.stash_w;
     float *stash_m = ta.stash_m;
     const int write_stash = !ta.attention_only;
-    const int u = blockIdx.x / c_active, c = blockIdx.x % c_active;
+    const int u = blk / c_active, c = blk % c_active;
     split_head_insert<T, D>(ta, u, c);
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int rg = lane >> 4, j = lane & 15;
@@ -170,37 +174,54 @@ __global__ __launch_bounds__(256) void split_valu_kernel(const SplitTailArgs<T> 
 }
 
 template <typename T, int D, int G>
-static hipError_t launch_one(const Plan &p, const StepIo &io, int n, hipStream_t s)
+static hipError_t launch_one(const Plan &p, const StepIo &io, int n, hipStream_t s, const void *table, int n_caches)
 {
-    const SplitTailArgs<T> ta = make_tail_args<T>(p, io, n);
+    const SplitTailArgs<T> ta = make_tail_args<T>(p, io, n, n_caches);
+    const SplitGroup gr = make_split_group(p, table, p.units * ta.c_active);
     const float scale_log2 = 1.4426950408889634f / sqrtf((float)D);
-    hipLaunchKernelGGL((split_valu_kernel<T, D, G>), dim3(p.units * ta.c_active), dim3(256), 0, s, ta, scale_log2);
+    hipLaunchKernelGGL((split_valu_kernel<T, D, G>), dim3(p.units * ta.c_active * n_caches), dim3(256), 0, s, ta,
+                       scale_log2, gr);
     hipError_t e = hipGetLastError();
-    if (e == hipSuccess && !ta.fused_tail) e = launch_split_finish<T, D>(ta, p.units, s);
+    if (e == hipSuccess && !ta.fused_tail) e = launch_split_finish<T, D>(ta, p.units, gr, n_caches, s);
     return e;
 }
 
 template <typename T, int D>
-static hipError_t launch_g(const Plan &p, const StepIo &io, int n, hipStream_t s)
+static hipError_t launch_g(const Plan &p, const StepIo &io, int n, hipStream_t s, const void *table, int n_caches)
 {
     switch (p.G) {
-    case 1: return launch_one<T, D, 1>(p, io, n, s);
-    case 2: return launch_one<T, D, 2>(p, io, n, s);
-    case 3: return launch_one<T, D, 3>(p, io, n, s);
-    case 4: return launch_one<T, D, 4>(p, io, n, s);
-    case 5: return launch_one<T, D, 5>(p, io, n, s);
-    case 6: return launch_one<T, D, 6>(p, io, n, s);
-    case 7: return launch_one<T, D, 7>(p, io, n, s);
-    case 8: return launch_one<T, D, 8>(p, io, n, s);
+    case 1: return launch_one<T, D, 1>(p, io, n, s, table, n_caches);
+    case 2: return launch_one<T, D, 2>(p, io, n, s, table, n_caches);
+    case 3: return launch_one<T, D, 3>(p, io, n, s, table, n_caches);
+    case 4: return launch_one<T, D, 4>(p, io, n, s, table, n_caches);
+    case 5: return launch_one<T, D, 5>(p, io, n, s, table, n_caches);
+    case 6: return launch_one<T, D, 6>(p, io, n, s, table, n_caches);
+    case 7: return launch_one<T, D, 7>(p, io, n, s, table, n_caches);
+    case 8: return launch_one<T, D, 8>(p, io, n, s, table, n_caches);
     default: return hipErrorInvalidValue;
     }
 }
 
-hipError_t launch_split_valu(const Plan &p, const StepIo &io, int n, hipStream_t s)
+hipError_t launch_split_valu(const Plan &p, const StepIo &io, int n, hipStream_t s, const void *table, int n_caches)
 {
     if (p.dtype == 0)
-        return p.D == 64 ? launch_g<float, 64>(p, io, n, s) : launch_g<float, 128>(p, io, n, s);
-    return p.D == 64 ? launch_g<bf16_t, 64>(p, io, n, s) : launch_g<bf16_t, 128>(p, io, n, s);
+        return p.D == 64 ? launch_g<float, 64>(p, io, n, s, table, n_caches) : launch_g<float, 128>(p, io, n, s, table, n_caches);
+    return p.D == 64 ? launch_g<bf16_t, 64>(p, io, n, s, table, n_caches) : launch_g<bf16_t, 128>(p, io, n, s, table, n_caches);
+}
+
+size_t split_table_entry_bytes() { return sizeof(SplitTailArgs<float>); }
+
+void split_table_entry(const Plan &p, void *dst)
+{
+    static_assert(sizeof(SplitTailArgs<float>) == sizeof(SplitTailArgs<bf16_t>), "one table layout for both element types");
+    const StepIo none = {nullptr, nullptr, nullptr, nullptr, nullptr};
+    if (p.dtype == 0) {
+        const SplitTailArgs<float> a = make_tail_args<float>(p, none, p.N);
+        memcpy(dst, &a, sizeof(a));
+    } else {
+        const SplitTailArgs<bf16_t> a = make_tail_args<bf16_t>(p, none, p.N);
+        memcpy(dst, &a, sizeof(a));
+    }
 }
 
 } // namespace lf

@@ -2,6 +2,7 @@
 // All arithmetic lives in the kernels; nothing here touches cache contents on the host.
 #include "../../include/longflow.h"
 
+#include <algorithm>
 #include <cstdarg>
 #include <cstdio>
 #include <cstdlib>
@@ -143,7 +144,7 @@ static const uint32_t kGroupMagic = 0x4c464752u;
 struct longflow_group {
     uint32_t magic;
     std::vector<longflow_cache *> members;
-    void *table; // device: one kernel-argument entry per member (unit-resident path only)
+    void *table; // device: one kernel-argument entry per member
 };
 
 using namespace lf;
@@ -303,7 +304,7 @@ int longflow_set_pending(longflow_cache_t *cache, const int32_t *slots, void *hi
 size_t longflow_group_workspace_bytes(int32_t n_caches)
 {
     if (n_caches < 1) return 0;
-    return align_up(unit_mfma_table_entry_bytes() * (size_t)n_caches, 256);
+    return align_up(std::max(unit_mfma_table_entry_bytes(), split_table_entry_bytes()) * (size_t)n_caches, 256);
 }
 
 int longflow_group_create(longflow_group_t **group, longflow_cache_t *const *caches, int32_t n_caches,
@@ -329,9 +330,14 @@ int longflow_group_create(longflow_group_t **group, longflow_cache_t *const *cac
             return fail(LF_ERR_INVALID_ARG, "member %d differs from member 0 in its configuration", i);
         members.push_back(c);
     }
-    const size_t eb = unit_mfma_table_entry_bytes();
+    // one entry per member, in the layout of the kernel family its plan uses
+    const bool unit = members[0]->plan.use_unit;
+    const size_t eb = unit ? unit_mfma_table_entry_bytes() : split_table_entry_bytes();
     std::vector<char> host(eb * (size_t)n_caches);
-    for (int i = 0; i < n_caches; ++i) unit_mfma_table_entry(members[i]->plan, host.data() + eb * i);
+    for (int i = 0; i < n_caches; ++i) {
+        if (unit) unit_mfma_table_entry(members[i]->plan, host.data() + eb * i);
+        else      split_table_entry(members[i]->plan, host.data() + eb * i);
+    }
     hipError_t e = hipMemcpyAsync(workspace, host.data(), host.size(), hipMemcpyHostToDevice, (hipStream_t)hip_stream);
     if (e == hipSuccess) e = hipStreamSynchronize((hipStream_t)hip_stream); // `host` goes out of scope
     if (e != hipSuccess) return fail(LF_ERR_HIP, "group table copy: %s", hipGetErrorString(e));
@@ -372,22 +378,11 @@ int longflow_group_decode_step(longflow_group_t *group, const void *q, const voi
     hipStream_t s = (hipStream_t)hip_stream;
     const int nc = (int)group->members.size();
     const StepIo io = {q, k_new, v_new, out, evict_idx};
-    if (p.use_unit) {
-        hipError_t e = launch_unit_mfma_group(p, io, n, group->table, nc, s);
-        if (e != hipSuccess) return fail(LF_ERR_HIP, "group decode launch: %s", hipGetErrorString(e));
-    } else {
-        // the split-K kernels take one cache per launch
-        const size_t esz = p.dtype == LF_F32 ? 4 : 2;
-        const size_t qb = esz * (size_t)p.B * p.Hq * p.D, kb = esz * (size_t)p.units * p.D;
-        for (int i = 0; i < nc; ++i) {
-            const Plan &pi = group->members[i]->plan;
-            const StepIo ii = {(const char *)q + qb * i, k_new ? (const char *)k_new + kb * i : nullptr,
-                               v_new ? (const char *)v_new + kb * i : nullptr, (char *)out + qb * i,
-                               evict_idx ? evict_idx + (size_t)p.units * i : nullptr};
-            hipError_t e = pi.use_mfma ? launch_split_mfma(pi, ii, n, s) : launch_split_valu(pi, ii, n, s);
-            if (e != hipSuccess) return fail(LF_ERR_HIP, "group decode launch %d: %s", i, hipGetErrorString(e));
-        }
-    }
+    hipError_t e;
+    if (p.use_unit) e = launch_unit_mfma_group(p, io, n, group->table, nc, s);
+    else if (p.use_mfma) e = launch_split_mfma(p, io, n, s, group->table, nc);
+    else e = launch_split_valu(p, io, n, s, group->table, nc);
+    if (e != hipSuccess) return fail(LF_ERR_HIP, "group decode launch: %s", hipGetErrorString(e));
     for (longflow_cache *c : group->members) {
         c->count = n;
         c->stepped = true;

@@ -417,8 +417,10 @@ def _make_caches(wl, n, flags=0):
 @pytest.mark.parametrize("name,dtype,B,Hq,Hkv,D,N,flags", [
     ("coop", "bf16", 2, 28, 4, 128, 2048, 0),            # several workgroups per unit
     ("single", "bf16", 48, 32, 8, 128, 300, 0),           # one workgroup per unit, ragged tail
-    ("split", "bf16", 4, 8, 2, 128, 1024, lf.LF_FLAG_FORCE_SPLIT),  # falls back to one launch per member
+    ("split", "bf16", 4, 8, 2, 128, 1024, lf.LF_FLAG_FORCE_SPLIT),      # split-K, last arriver finishes
+    ("split-big", "bf16", 40, 8, 2, 128, 2048, lf.LF_FLAG_FORCE_SPLIT), # split-K, separate (grouped) finish launch
     ("fp32", "f32", 2, 8, 2, 64, 200, 0),
+    ("fp32-big", "f32", 24, 6, 2, 128, 1500, 0),
 ])
 def test_group_step_equals_member_steps(name, dtype, B, Hq, Hkv, D, N, flags):
     # fill phase into eviction phase; the group must give every member the bits it gets alone
