@@ -58,10 +58,10 @@ def parse():
 
 
 def kernel_name(wl, flags):
+    """Which kernel family the library will run for this workload (asked of the library itself)."""
     from paper_2603_11504_amd import longflow as lf
-    mfma = wl.dtype == "bf16" and wl.head_dim == 128 and not (flags & lf.LF_FLAG_FORCE_VALU)
-    fused = mfma and not (flags & lf.LF_FLAG_FORCE_SPLIT)   # every BASELINE geometry fits the unit-resident kernel's LDS
-    return "unit_mfma_kernel" if fused else ("split_mfma_kernel" if mfma else "split_valu_kernel")
+    cfg = lf.make_config(wl.batch, wl.q_heads, wl.kv_heads, wl.head_dim, wl.budget, wl.dtype, flags)
+    return lf.PATH_KERNELS[lf.longflow_plan_info(cfg).path]
 
 
 def cpu_baseline(wl, cache0, target_s=12.0):

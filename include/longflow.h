@@ -137,6 +137,26 @@ LF_API int longflow_valid_count(const longflow_cache_t *cache);
 LF_API int longflow_destroy_cache(longflow_cache_t *cache);
 
 /*
+ * How a configuration will be executed (host-only query; launches nothing, needs no GPU).
+ * The kernels all compute the same step (Alg. 1 with the post-processing of Sec. 3.4); the
+ * choice below is about filling the chip, not about the result.
+ */
+typedef enum {
+    LF_PATH_SPLIT_VALU = 0, /* split-K, vector ALU (fp32, head_dim 64, LF_FLAG_FORCE_VALU)       */
+    LF_PATH_SPLIT_MFMA = 1, /* split-K, matrix cores (codes exceed LDS, LF_FLAG_FORCE_SPLIT)     */
+    LF_PATH_UNIT_MFMA = 2   /* fused kernel, 1..8 cooperating workgroups per (batch, KV head)    */
+} lf_path;
+typedef struct {
+    int32_t path;                /* lf_path                                                        */
+    int32_t workgroups_per_unit; /* at a full cache                                                 */
+    int32_t slots_per_workgroup; /* slot range one workgroup streams                                */
+    int32_t launches_per_step;   /* 1, or 2 when a large split-K grid takes a separate finish launch */
+    int32_t threads_per_workgroup;
+    uint32_t lds_bytes;          /* dynamic LDS per workgroup (0 on the split-K paths: static only) */
+} lf_plan_info;
+LF_API int longflow_plan_info(const lf_config *cfg, lf_plan_info *info);
+
+/*
  * Several caches in one launch.  The method's workload is the same every step (Sec. 3.4:
  * static memory, one fused kernel), so caches that are independent of each other --
  * micro-batches, or the layers of a synthetic benchmark -- can share one grid: the launch

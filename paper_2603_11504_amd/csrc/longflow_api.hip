@@ -301,6 +301,33 @@ int longflow_set_pending(longflow_cache_t *cache, const int32_t *slots, void *hi
     return LF_OK;
 }
 
+int longflow_plan_info(const lf_config *cfg, lf_plan_info *info)
+{
+    if (!info) return fail(LF_ERR_INVALID_ARG, "info is NULL");
+    memset(info, 0, sizeof(*info));
+    const int rc = validate(cfg);
+    if (rc != LF_OK) return rc;
+    Plan p;
+    fill_plan(cfg, &p);
+    if (p.use_unit) {
+        const int len = unit_mfma_split_len(p.N, p.unit_S);
+        info->path = LF_PATH_UNIT_MFMA;
+        info->workgroups_per_unit = (p.N + len - 1) / len;
+        info->slots_per_workgroup = len;
+        info->launches_per_step = 1;
+        info->threads_per_workgroup = 512;
+        info->lds_bytes = (uint32_t)unit_mfma_lds_bytes(p.N, p.G, !(p.flags & LF_FLAG_ATTENTION_ONLY), p.unit_S);
+    } else {
+        info->path = p.use_mfma ? LF_PATH_SPLIT_MFMA : LF_PATH_SPLIT_VALU;
+        info->workgroups_per_unit = (p.N + p.L - 1) / p.L;
+        info->slots_per_workgroup = p.L;
+        info->launches_per_step = (long long)p.units * info->workgroups_per_unit <= 256 ? 1 : 2;
+        info->threads_per_workgroup = 256;
+        info->lds_bytes = 0;
+    }
+    return LF_OK;
+}
+
 size_t longflow_group_workspace_bytes(int32_t n_caches)
 {
     if (n_caches < 1) return 0;

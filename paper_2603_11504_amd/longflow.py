@@ -24,7 +24,7 @@ LF_FLAG_FORCE_UNIT = 8
 EXPORTS = ("longflow_workspace_bytes", "longflow_init_cache", "longflow_decode_step",
            "longflow_scores", "longflow_set_pending", "longflow_valid_count",
            "longflow_destroy_cache", "longflow_last_error", "longflow_profile_begin",
-           "longflow_profile_end", "longflow_group_workspace_bytes", "longflow_group_create",
+           "longflow_profile_end", "longflow_plan_info", "longflow_group_workspace_bytes", "longflow_group_create",
            "longflow_group_decode_step", "longflow_group_destroy")
 
 
@@ -32,6 +32,16 @@ class lf_config(ctypes.Structure):
     _fields_ = [("batch", ctypes.c_int32), ("q_heads", ctypes.c_int32), ("kv_heads", ctypes.c_int32),
                 ("head_dim", ctypes.c_int32), ("budget", ctypes.c_int32), ("dtype", ctypes.c_int32),
                 ("flags", ctypes.c_uint32)]
+
+
+class lf_plan_info(ctypes.Structure):
+    _fields_ = [("path", ctypes.c_int32), ("workgroups_per_unit", ctypes.c_int32),
+                ("slots_per_workgroup", ctypes.c_int32), ("launches_per_step", ctypes.c_int32),
+                ("threads_per_workgroup", ctypes.c_int32), ("lds_bytes", ctypes.c_uint32)]
+
+
+LF_PATH_SPLIT_VALU, LF_PATH_SPLIT_MFMA, LF_PATH_UNIT_MFMA = range(3)
+PATH_KERNELS = ("split_valu_kernel", "split_mfma_kernel", "unit_mfma_kernel")
 
 
 class LongFlowError(RuntimeError):
@@ -70,6 +80,8 @@ def lib():
         L.longflow_profile_begin.restype = ctypes.c_int
         L.longflow_profile_end.argtypes = [vp, ctypes.POINTER(ctypes.c_float), ctypes.POINTER(i32)]
         L.longflow_profile_end.restype = ctypes.c_int
+        L.longflow_plan_info.argtypes = [ctypes.POINTER(lf_config), ctypes.POINTER(lf_plan_info)]
+        L.longflow_plan_info.restype = ctypes.c_int
         L.longflow_group_workspace_bytes.argtypes = [i32]
         L.longflow_group_workspace_bytes.restype = ctypes.c_size_t
         L.longflow_group_create.argtypes = [ctypes.POINTER(vp), ctypes.POINTER(vp), i32, vp, ctypes.c_size_t, vp]
@@ -104,6 +116,12 @@ def make_config(batch, q_heads, kv_heads, head_dim, budget, dtype, flags=0) -> l
 
 def longflow_workspace_bytes(cfg: lf_config) -> int:
     return int(lib().longflow_workspace_bytes(ctypes.byref(cfg)))
+
+
+def longflow_plan_info(cfg: lf_config) -> lf_plan_info:
+    info = lf_plan_info()
+    _check(lib().longflow_plan_info(ctypes.byref(cfg), ctypes.byref(info)))
+    return info
 
 
 class LongFlowCache:

@@ -75,3 +75,89 @@ def test_missing_library_fails_loudly(monkeypatch):
     monkeypatch.setattr(lf, "LIB_PATH", "/nonexistent/liblongflow.so")
     with pytest.raises(ImportError):
         lf.lib()
+
+
+# ------------------------------------------------------------------ execution plan (host logic)
+
+LDS_PER_CU = 160 * 1024
+
+
+def _plans():
+    import itertools
+    for dtype, D, G, Hkv, B, N, flags in itertools.product(
+            ("bf16", "f32"), (64, 128), (1, 4, 7, 8, 16), (1, 8), (1, 3, 32, 64, 300),
+            (1, 16, 17, 255, 2048, 8192, 16384, 81920, 500000),
+            (0, lf.LF_FLAG_ATTENTION_ONLY, lf.LF_FLAG_FORCE_SPLIT, lf.LF_FLAG_FORCE_VALU)):
+        cfg = lf.make_config(B, G * Hkv, Hkv, D, N, dtype, flags)
+        if lf.longflow_workspace_bytes(cfg) == 0:
+            continue
+        yield (dtype, D, G, Hkv, B, N, flags), cfg, lf.longflow_plan_info(cfg)
+
+
+def test_every_accepted_configuration_has_a_consistent_plan():
+    seen = set()
+    count = 0
+    for key, cfg, info in _plans():
+        dtype, D, G, Hkv, B, N, flags = key
+        count += 1
+        seen.add(info.path)
+        # the workgroups of a unit cover its slots, none of them idle at a full cache
+        assert info.workgroups_per_unit >= 1
+        assert info.workgroups_per_unit * info.slots_per_workgroup >= N, key
+        assert (info.workgroups_per_unit - 1) * info.slots_per_workgroup < N, key
+        assert info.launches_per_step in (1, 2)
+        mfma_ok = dtype == "bf16" and D == 128 and not flags & lf.LF_FLAG_FORCE_VALU
+        if info.path == lf.LF_PATH_UNIT_MFMA:
+            assert mfma_ok and not flags & lf.LF_FLAG_FORCE_SPLIT
+            assert info.workgroups_per_unit <= 8 and info.launches_per_step == 1
+            assert info.threads_per_workgroup == 512
+            # dynamic LDS plus the kernel's static arrays must fit one compute unit
+            assert 0 < info.lds_bytes <= LDS_PER_CU - 12 * 1024, key
+            if not flags & lf.LF_FLAG_ATTENTION_ONLY:
+                # one byte per (head, slot) of the workgroup's share, plus per-tile references
+                assert info.lds_bytes >= G * min(info.slots_per_workgroup, N), key
+            if B * Hkv >= 192 and info.workgroups_per_unit > 1:
+                # plenty of units: more than one workgroup only when the codes demand it
+                one = G * N + (N // 16 + 1) * G * 4
+                assert flags & lf.LF_FLAG_ATTENTION_ONLY == 0 and one > LDS_PER_CU - 12 * 1024, key
+        else:
+            assert info.path == (lf.LF_PATH_SPLIT_MFMA if mfma_ok else lf.LF_PATH_SPLIT_VALU), key
+            assert info.workgroups_per_unit <= 64 and info.slots_per_workgroup % 256 == 0
+            big = B * Hkv * info.workgroups_per_unit > 256
+            assert info.launches_per_step == (2 if big else 1), key
+    assert count > 1000 and seen == {0, 1, 2}
+
+
+def test_plan_of_the_baseline_workloads():
+    from paper_2603_11504_amd import workloads as W
+    got = []
+    for wl in W.CONFIGS:
+        i = lf.longflow_plan_info(lf.make_config(wl.batch, wl.q_heads, wl.kv_heads, wl.head_dim, wl.budget, wl.dtype, 0))
+        got.append((lf.PATH_KERNELS[i.path], i.workgroups_per_unit, i.slots_per_workgroup))
+    assert got == [("split_valu_kernel", 1, 256), ("unit_mfma_kernel", 4, 512), ("unit_mfma_kernel", 2, 2048),
+                   ("unit_mfma_kernel", 1, 8192), ("unit_mfma_kernel", 1, 16384)]
+
+
+def test_plan_info_rejects_what_init_rejects():
+    L = lf.lib()
+    info = lf.lf_plan_info()
+    bad = lf.make_config(2, 7, 2, 128, 512, "bf16", 0)
+    assert L.longflow_plan_info(ctypes.byref(bad), ctypes.byref(info)) == lf.LF_ERR_UNSUPPORTED
+    assert L.longflow_plan_info(ctypes.byref(bad), None) == lf.LF_ERR_INVALID_ARG
+    assert L.longflow_plan_info(None, ctypes.byref(info)) == lf.LF_ERR_INVALID_ARG
+
+
+def test_group_calls_reject_bad_arguments_on_the_host():
+    L = lf.lib()
+    assert L.longflow_group_workspace_bytes(0) == 0
+    assert L.longflow_group_workspace_bytes(3) % 256 == 0 and L.longflow_group_workspace_bytes(3) > 0
+    g = ctypes.c_void_p()
+    fake = ctypes.c_void_p(0x1000)
+    assert L.longflow_group_create(ctypes.byref(g), None, 2, fake, 1 << 20, None) == lf.LF_ERR_INVALID_ARG
+    none = (ctypes.c_void_p * 2)(None, None)
+    assert L.longflow_group_create(ctypes.byref(g), none, 2, None, 1 << 20, None) == lf.LF_ERR_INVALID_ARG
+    assert L.longflow_group_create(ctypes.byref(g), none, 2, fake, 16, None) == lf.LF_ERR_WORKSPACE
+    assert L.longflow_group_create(ctypes.byref(g), none, 2, fake, 1 << 20, None) == lf.LF_ERR_STATE  # NULL members
+    assert not g.value
+    assert L.longflow_group_decode_step(None, fake, fake, fake, fake, None, None) == lf.LF_ERR_STATE
+    assert L.longflow_group_destroy(None) == lf.LF_ERR_STATE
