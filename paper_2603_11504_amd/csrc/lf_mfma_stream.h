@@ -239,7 +239,11 @@ struct MfmaStreamer {
     // (A static split keeps every sum in a fixed order: results are bit-reproducible.
     // Handing tiles out dynamically was tried -- the older wave of a SIMD finishes ~40 %
     // ahead of the younger one -- and bought nothing: the compute unit's request rate, not
-    // the number of waves still streaming, sets the pace.)
+    // the number of waves still streaming, sets the pace.  Starting every workgroup at a
+    // different, hashed position of its tile list was tried as well, against memory-channel
+    // hot spots: it is 12-15 % slower (173 -> 195 us at 256 units x 8192 slots).  Workgroups
+    // that walk their units in step, at equal offsets of 2 MiB-strided units, are the
+    // pattern the channel hashing spreads best.)
     // Three register tiles rotate: while one is consumed the other two are in flight; the
     // steady-state body has no branch between a load and its use, so each wait covers
     // exactly the oldest tile.
