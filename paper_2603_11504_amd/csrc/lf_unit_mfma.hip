@@ -658,7 +658,13 @@ static hipError_t launch_unit(const Plan &p, const StepIo &io, int n, const void
     const long long wgs = (long long)ga.wgs_per_cache * n_caches;
     if (wgs <= 2 * 256 && lds < 81 * 1024) lds = 81 * 1024;
     if (wgs > 0x7fffffffll) return hipErrorInvalidValue;
-    static bool attr_done[8] = {false, false, false, false, false, false, false, false};
+    // the dynamic-LDS ceiling is a per-device function attribute: raise it once per device
+    // and kernel instance (a benign race if two host threads get here together: both set it)
+    constexpr int kMaxDevices = 64;
+    static bool attr_done_all[kMaxDevices][8] = {};
+    int dev = 0;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) return hipErrorInvalidDevice;
+    bool *attr_done = attr_done_all[dev];
 #define LF_UNIT(STASH, COOP, GROUPED, IDX)                                                            \
     do {                                                                                              \
         if (!attr_done[IDX]) {                                                                        \
