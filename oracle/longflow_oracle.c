@@ -23,6 +23,13 @@
  *                lowest index on exact ties  (Sec. 3.2 last paragraph,
  *                Alg. 1 post-processing); while filling, pending <- count.
  *
+ * Valid slots are a prefix [0, count) by default.  With an explicit mask
+ * (the vector M of Alg. 1: masked logits are -inf, so a masked slot has
+ * weight and score 0) any subset of slots may be valid, per unit; steps 2-5
+ * then run over the valid slots only, and step 6 hands out the lowest
+ * invalid slot while there is one (the same "fill before evicting" reading
+ * as the prefix case), else the argmin.
+ *
  * The method reaches these plain definitions exactly (the fused kernel of
  * Alg. 1 is only a faster route), so the oracle IS the definitions written
  * out.  Max-subtraction inside the softmax is the textbook, exact-arithmetic
@@ -122,6 +129,7 @@ typedef struct lfo_cache {
     double *K, *V;    /* [B][Hkv][N][D] */
     double *score;    /* [B][Hkv][N], last step; 0 for invalid slots */
     int32_t *pending; /* [B][Hkv] slot the next token's K/V will cover; -1 = none */
+    uint8_t *mask;    /* NULL: valid slots are the prefix [0, count); else [B][Hkv][N], 1 = valid */
 } lfo_cache;
 
 LFO_API lfo_cache *lfo_cache_create(int B, int Hq, int Hkv, int D, int N)
@@ -144,7 +152,7 @@ LFO_API lfo_cache *lfo_cache_create(int B, int Hq, int Hkv, int D, int N)
 LFO_API void lfo_cache_destroy(lfo_cache *c)
 {
     if (!c) return;
-    free(c->K); free(c->V); free(c->score); free(c->pending); free(c);
+    free(c->K); free(c->V); free(c->score); free(c->pending); free(c->mask); free(c);
 }
 
 /*
@@ -171,6 +179,73 @@ LFO_API int lfo_cache_init(lfo_cache *c, const double *k_init,
 }
 
 /*
+ * Explicit validity mask (Alg. 1's M), [B][Hkv][N], 1 = valid.  From here on
+ * the cache is in mask mode: every step looks at all N slots of a unit.  A
+ * unit with an invalid slot gets its lowest one as pending slot; a unit
+ * without keeps the pending slot it has.
+ */
+LFO_API int lfo_cache_set_mask(lfo_cache *c, const uint8_t *mask)
+{
+    size_t units = (size_t)c->B * c->Hkv;
+    if (!c->mask) c->mask = (uint8_t *)malloc(units * c->N);
+    for (size_t i = 0; i < units * c->N; ++i) c->mask[i] = mask[i] ? 1 : 0;
+    for (size_t u = 0; u < units; ++u)
+        for (int i = 0; i < c->N; ++i)
+            if (!c->mask[u * c->N + i]) { c->pending[u] = i; break; }
+    c->count = c->N;
+    return 0;
+}
+
+LFO_API int lfo_cache_get_mask(const lfo_cache *c, uint8_t *mask)
+{
+    size_t units = (size_t)c->B * c->Hkv;
+    for (size_t u = 0; u < units; ++u)
+        for (int i = 0; i < c->N; ++i)
+            mask[u * c->N + i] = c->mask ? c->mask[u * c->N + i] : (uint8_t)(i < c->count);
+    return 0;
+}
+
+/* one unit's step in mask mode: steps 1-6 over an arbitrary valid set */
+static void step_masked_unit(lfo_cache *c, int u, const double *q, const double *k_new,
+                             const double *v_new, double *out, int32_t *evict_idx)
+{
+    const int D = c->D, N = c->N, G = c->G;
+    double *Ku = c->K + (size_t)u * N * D, *Vu = c->V + (size_t)u * N * D;
+    uint8_t *m = c->mask + (size_t)u * N;
+    double *sc = c->score + (size_t)u * N;
+    /* 1. insert; the slot becomes valid */
+    const int slot = c->pending[u];
+    memcpy(Ku + (size_t)slot * D, k_new + (size_t)u * D, sizeof(double) * D);
+    memcpy(Vu + (size_t)slot * D, v_new + (size_t)u * D, sizeof(double) * D);
+    m[slot] = 1;
+    /* 2-5. attention over the valid rows, gathered side by side */
+    int nv = 0;
+    for (int i = 0; i < N; ++i) nv += m[i];
+    int *idx = (int *)malloc(sizeof(int) * (size_t)nv);
+    double *Kg = (double *)malloc(sizeof(double) * (size_t)nv * D);
+    double *Vg = (double *)malloc(sizeof(double) * (size_t)nv * D);
+    double *sg = (double *)malloc(sizeof(double) * (size_t)nv);
+    for (int i = 0, j = 0; i < N; ++i)
+        if (m[i]) {
+            idx[j] = i;
+            memcpy(Kg + (size_t)j * D, Ku + (size_t)i * D, sizeof(double) * D);
+            memcpy(Vg + (size_t)j * D, Vu + (size_t)i * D, sizeof(double) * D);
+            ++j;
+        }
+    lfo_attend_unit(nv, D, G, q + (size_t)u * G * D, Kg, Vg, out + (size_t)u * G * D, NULL, sg);
+    for (int i = 0; i < N; ++i) sc[i] = 0.0;
+    for (int j = 0; j < nv; ++j) sc[idx[j]] = sg[j];
+    /* 6. fill the lowest hole if there is one, else evict the minimum score */
+    int next = -1;
+    for (int i = 0; i < N && next < 0; ++i)
+        if (!m[i]) next = i;
+    if (next < 0) next = lfo_argmin(N, sc);
+    c->pending[u] = next;
+    if (evict_idx) evict_idx[u] = next;
+    free(idx); free(Kg); free(Vg); free(sg);
+}
+
+/*
  * One decode step for every unit (steps 1-6 of the header).
  * Returns 0, or 2 if the cache is full and some unit has no pending slot.
  */
@@ -181,6 +256,11 @@ LFO_API int lfo_cache_step(lfo_cache *c, const double *q, const double *k_new,
     const int units = c->B * c->Hkv;
     for (int u = 0; u < units; ++u)
         if (c->pending[u] < 0 || c->pending[u] >= N) return 2;
+    if (c->mask) {
+#pragma omp parallel for schedule(dynamic, 1)
+        for (int u = 0; u < units; ++u) step_masked_unit(c, u, q, k_new, v_new, out, evict_idx);
+        return 0;
+    }
     const int n = (c->count < N) ? c->count + 1 : N;
 #pragma omp parallel for schedule(dynamic, 1)
     for (int u = 0; u < units; ++u) {
@@ -222,7 +302,7 @@ LFO_API int lfo_cache_set_pending(lfo_cache *c, const int32_t *slots)
     for (size_t u = 0; u < units; ++u) {
         if (slots[u] < 0 || slots[u] >= c->N) return 1;
         /* while filling, valid rows stay a prefix: only slot == count is legal */
-        if (c->count < c->N && slots[u] != c->count) return 1;
+        if (!c->mask && c->count < c->N && slots[u] != c->count) return 1;
     }
     memcpy(c->pending, slots, sizeof(int32_t) * units);
     return 0;

@@ -62,6 +62,11 @@ def lib():
         L.lfo_cache_set_pending.restype = ctypes.c_int
         L.lfo_cache_get_kv.argtypes = [ctypes.c_void_p, _dp, _dp]
         L.lfo_cache_get_kv.restype = None
+        _bp = ctypes.POINTER(ctypes.c_uint8)
+        L.lfo_cache_set_mask.argtypes = [ctypes.c_void_p, _bp]
+        L.lfo_cache_set_mask.restype = ctypes.c_int
+        L.lfo_cache_get_mask.argtypes = [ctypes.c_void_p, _bp]
+        L.lfo_cache_get_mask.restype = ctypes.c_int
         L.lfo_num_threads.argtypes = []
         L.lfo_num_threads.restype = ctypes.c_int
         _lib = L
@@ -163,3 +168,13 @@ class OracleCache:
         K = np.empty(shape); V = np.empty(shape)
         lib().lfo_cache_get_kv(self._h, _ptr(K), _ptr(V))
         return K, V
+
+    def set_mask(self, mask):
+        """Explicit validity mask [B,Hkv,N] (nonzero = valid); switches the cache to mask mode."""
+        m = np.ascontiguousarray(np.asarray(mask) != 0, dtype=np.uint8).reshape(self.B, self.Hkv, self.N)
+        lib().lfo_cache_set_mask(self._h, m.ctypes.data_as(ctypes.POINTER(ctypes.c_uint8)))
+
+    def mask(self):
+        m = np.empty((self.B, self.Hkv, self.N), dtype=np.uint8)
+        lib().lfo_cache_get_mask(self._h, m.ctypes.data_as(ctypes.POINTER(ctypes.c_uint8)))
+        return m

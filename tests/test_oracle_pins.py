@@ -259,3 +259,102 @@ def test_full_cache_without_pending_is_an_error_until_set():
     c.step(q, k, v)
     K, _ = c.kv()
     np.testing.assert_array_equal(K[0, 0, 2], k[0, 0])
+
+
+# ---------------------------------------------------------------- explicit mask (Alg. 1's M)
+
+def _masked_cache(B, Hq, Hkv, D, N, seed, density):
+    """A full-size cache whose valid slots are a random subset; invalid rows stay NaN."""
+    rng = np.random.default_rng(seed)
+    c = oracle.OracleCache(B, Hq, Hkv, D, N)
+    K0 = rng.standard_normal((B, Hkv, N, D)); V0 = rng.standard_normal((B, Hkv, N, D))
+    mask = rng.random((B, Hkv, N)) < density
+    mask[..., N // 2] = True                              # never an empty unit
+    K0[~mask] = np.nan; V0[~mask] = np.nan
+    c.init(K0, V0)
+    c.set_mask(mask)
+    return c, rng, mask
+
+
+def test_prefix_mask_equals_count_mode():
+    B, Hq, Hkv, D, N, n0 = 2, 4, 2, 16, 10, 4
+    ca, rng = _run_cache(B, Hq, Hkv, D, N, 0, 1000, n_init=n0)
+    Ka, Va = ca.kv()
+    cb = oracle.OracleCache(B, Hq, Hkv, D, N)
+    cb.init(Ka, Va)                                        # rows >= n0 are NaN: the mask must hide them
+    cb.set_mask(np.arange(N)[None, None, :] < n0 + np.zeros((B, Hkv, 1), dtype=int))
+    for t in range(25):                                   # through the fill and well into eviction
+        q = rng.standard_normal((B, Hq, D)); k = rng.standard_normal((B, Hkv, D)); v = rng.standard_normal((B, Hkv, D))
+        oa, ia = ca.step(q, k, v)
+        ob, ib = cb.step(q, k, v)
+        np.testing.assert_array_equal(oa, ob)
+        np.testing.assert_array_equal(ia, ib)
+        np.testing.assert_array_equal(ca.scores(), cb.scores())
+        np.testing.assert_array_equal(cb.mask()[0, 0], np.arange(N) < min(n0 + t + 1, N))
+
+
+def test_masked_step_is_library_attention_over_the_valid_rows():
+    B, Hq, Hkv, D, N = 2, 6, 2, 16, 24
+    c, rng, mask = _masked_cache(B, Hq, Hkv, D, N, 1100, 0.5)
+    G = Hq // Hkv
+    for t in range(6):
+        pend = c.pending()
+        q = rng.standard_normal((B, Hq, D)); k = rng.standard_normal((B, Hkv, D)); v = rng.standard_normal((B, Hkv, D))
+        out, idx = c.step(q, k, v)
+        K, V = c.kv()
+        m = c.mask().astype(bool)
+        sc = c.scores()
+        for b in range(B):
+            for g in range(Hkv):
+                assert m[b, g, pend[b, g]]                            # the covered slot became valid
+                live = np.flatnonzero(m[b, g])
+                assert np.isfinite(K[b, g, live]).all() and np.isnan(K[b, g, ~m[b, g]]).all()
+                for h in range(G):
+                    a = scipy_softmax(K[b, g, live] @ q[b, g * G + h] / math.sqrt(D))
+                    np.testing.assert_allclose(out[b, g * G + h], a @ V[b, g, live], rtol=1e-12, atol=1e-14)
+                assert (sc[b, g, ~m[b, g]] == 0).all() and (sc[b, g, live] > 0).all()
+                # the blockwise procedure of Alg. 1 with the same mask agrees on everything
+                o2, s2 = alg1_blockwise.fused_blockwise_group(q[b, g * G:(g + 1) * G], K[b, g], V[b, g], m[b, g], 7)
+                np.testing.assert_allclose(o2, out[b, g * G:(g + 1) * G], rtol=1e-12, atol=1e-14)
+                np.testing.assert_allclose(s2, sc[b, g], rtol=1e-12)
+
+
+def test_holes_are_filled_lowest_first_then_the_minimum_is_evicted():
+    B, Hq, Hkv, D, N = 1, 2, 2, 8, 12
+    c, rng, mask = _masked_cache(B, Hq, Hkv, D, N, 1200, 0.4)
+    holes = [sorted(np.flatnonzero(~mask[0, g]).tolist()) for g in range(Hkv)]
+    np.testing.assert_array_equal(c.pending()[0], [h[0] for h in holes])   # set_mask names the first hole
+    for t in range(N + 6):
+        q = rng.standard_normal((B, Hq, D)); k = rng.standard_normal((B, Hkv, D)); v = rng.standard_normal((B, Hkv, D))
+        pend = c.pending()[0].copy()
+        _, idx = c.step(q, k, v)
+        for g in range(Hkv):
+            if holes[g]:
+                assert pend[g] == holes[g].pop(0)                      # holes go in ascending order
+            want = holes[g][0] if holes[g] else int(np.argmin(c.scores()[0, g]))
+            assert idx[0, g] == want
+    assert c.mask().all()
+
+
+def test_scattering_valid_rows_over_slots_changes_nothing_but_their_places():
+    rng = np.random.default_rng(1300)
+    D, G, n, N = 16, 3, 7, 20
+    q, K, V = _rand_unit(rng, n, D, G)
+    o, score, _ = oracle.attend_unit(q, K, V)
+    for trial in range(5):
+        slots = np.sort(rng.choice(N, size=n, replace=False))
+        c = oracle.OracleCache(1, G, 1, D, N)
+        K0 = np.full((1, 1, N, D), np.nan); V0 = np.full((1, 1, N, D), np.nan)
+        # the step inserts one token itself: pre-place the other n-1 at slots[1:]; the
+        # inserted one goes to the lowest free slot, wherever that is
+        order = rng.permutation(n)
+        K0[0, 0, slots[1:]] = K[order[1:]]; V0[0, 0, slots[1:]] = V[order[1:]]
+        m = np.zeros((1, 1, N), dtype=bool); m[0, 0, slots[1:]] = True
+        last_slot = int(np.flatnonzero(~m[0, 0])[0])
+        c.init(K0, V0); c.set_mask(m)
+        out, _ = c.step(q[None], K[order[0]][None, None], V[order[0]][None, None])
+        np.testing.assert_allclose(out[0], o, rtol=1e-12, atol=1e-14)
+        sc = c.scores()[0, 0]
+        np.testing.assert_allclose(sc[last_slot], score[order[0]], rtol=1e-12)
+        np.testing.assert_allclose(sc[slots[1:]], score[order[1:]], rtol=1e-12)
+        assert np.count_nonzero(sc) == n
