@@ -130,6 +130,21 @@ LF_API int longflow_scores(longflow_cache_t *cache, float *scores, void *hip_str
  * each in [0, N).  Only legal once the cache is full. */
 LF_API int longflow_set_pending(longflow_cache_t *cache, const int32_t *slots, void *hip_stream);
 
+/*
+ * Explicit validity mask, the vector M of Alg. 1: device uint8 [B][Hkv][N], nonzero = the
+ * slot holds a token.  Any subset may be valid, separately per (batch, KV head): ragged
+ * batches, sequences restarted in place, slots dropped by the caller.  As in Alg. 1 an
+ * invalid slot has logit -inf, weight 0 and score 0.  From this call on every step looks
+ * at all N slots; the slot handed out for the next token is the lowest invalid one while
+ * there is one (nothing is evicted before the holes are used up), else the argmin.
+ * Effects, in stream order: the K/V rows of invalid slots are overwritten with zeros; a
+ * (batch, KV head) that has an invalid slot gets its lowest one as pending slot, one that
+ * has none keeps the pending slot it had (a cache created full still needs
+ * longflow_set_pending first).  longflow_valid_count then reports N.  Not available
+ * with LF_FLAG_ATTENTION_ONLY (LF_ERR_UNSUPPORTED).  May be called again at any time.
+ */
+LF_API int longflow_set_mask(longflow_cache_t *cache, const uint8_t *mask, void *hip_stream);
+
 /* Valid slots = min(tokens seen, N); negative on a NULL handle. */
 LF_API int longflow_valid_count(const longflow_cache_t *cache);
 

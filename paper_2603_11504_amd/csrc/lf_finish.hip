@@ -44,6 +44,66 @@ hipError_t launch_fill_i32(int32_t *dst, int count, int32_t value, hipStream_t s
 }
 
 // ---------------------------------------------------------------------------------------
+// Explicit validity mask (the vector M of Alg. 1), off the per-step path.  One 16-lane row
+// per cache row: an invalid slot gets NaN in the side array and zeroed K/V rows (a zero
+// weight times a non-finite value would still poison the P V product), a valid one gets
+// log2 ||v||_1.  The lowest invalid slot of each unit becomes its pending slot.
+// ---------------------------------------------------------------------------------------
+template <typename T, int D>
+__global__ __launch_bounds__(256) void mask_kernel(T *__restrict__ Kc, T *__restrict__ Vc,
+                                                    const uint8_t *__restrict__ mask, float *__restrict__ lu,
+                                                    int32_t *__restrict__ first_hole, int units, int N, int lu_stride)
+{
+    constexpr int EPL = D / 16;
+    const int lane16 = threadIdx.x & 15;
+    const long long total = (long long)units * N;
+    for (long long row = (long long)blockIdx.x * 16 + (threadIdx.x >> 4); row < total; row += (long long)gridDim.x * 16) {
+        const int u = (int)(row / N), slot = (int)(row % N);
+        T *kr = Kc + (size_t)row * D + lane16 * EPL;
+        T *vr = Vc + (size_t)row * D + lane16 * EPL;
+        float val;
+        if (mask[row]) {
+            float a1 = 0.f;
+#pragma unroll
+            for (int e = 0; e < EPL; ++e) a1 += fabsf(to_f32(vr[e]));
+            val = __builtin_amdgcn_logf(row16_sum(a1));
+        } else {
+#pragma unroll
+            for (int e = 0; e < EPL; ++e) { store_elem(kr + e, 0.f); store_elem(vr + e, 0.f); }
+            val = __builtin_nanf("");
+            if (lane16 == 0) atomicMin(&first_hole[u], slot);
+        }
+        if (lane16 == 0) lu[(size_t)u * lu_stride + (slot & ~15) + tail_pos_of_slot(slot & 15)] = val;
+    }
+}
+
+__global__ void mask_pending_kernel(const int32_t *first_hole, int32_t *pending, int units, int N)
+{
+    const int u = blockIdx.x * blockDim.x + threadIdx.x;
+    if (u < units && first_hole[u] < N) pending[u] = first_hole[u];
+}
+
+hipError_t launch_set_mask(const Plan &p, const uint8_t *mask, hipStream_t s)
+{
+    hipError_t e = launch_fill_i32(p.first_hole, p.units, 0x7fffffff, s);
+    if (e != hipSuccess) return e;
+    const long long total = (long long)p.units * p.N;
+    long long blocks = (total + 15) / 16;
+    if (blocks > 65536) blocks = 65536;
+#define LF_MK(T, DD)                                                                              \
+    hipLaunchKernelGGL((mask_kernel<T, DD>), dim3((unsigned)blocks), dim3(256), 0, s, (T *)p.k_cache, \
+                       (T *)p.v_cache, mask, p.lu, p.first_hole, p.units, p.N, p.ntiles * kTile)
+    if (p.dtype == 0) { if (p.D == 64) LF_MK(float, 64); else LF_MK(float, 128); }
+    else              { if (p.D == 64) LF_MK(bf16_t, 64); else LF_MK(bf16_t, 128); }
+#undef LF_MK
+    e = hipGetLastError();
+    if (e != hipSuccess) return e;
+    hipLaunchKernelGGL(mask_pending_kernel, dim3((p.units + 255) / 256), dim3(256), 0, s, p.first_hole, p.pending,
+                       p.units, p.N);
+    return hipGetLastError();
+}
+
+// ---------------------------------------------------------------------------------------
 // Score read-back (S_final_loss of Alg. 1), off the per-step path: one wave per slot,
 // double-precision arithmetic, fp32 result.
 // ---------------------------------------------------------------------------------------
@@ -52,7 +112,8 @@ __global__ __launch_bounds__(256) void scores_kernel(const T *__restrict__ Kc, c
                                                       const T *__restrict__ q_last, int n, int N, int G,
                                                       const float *__restrict__ fin_m,
                                                       const float *__restrict__ fin_l,
-                                                      float *__restrict__ scores, int chunks)
+                                                      float *__restrict__ scores, int chunks,
+                                                      const float *__restrict__ lu_mask, int lu_stride)
 {
     __shared__ float sM[kMaxGroup], sL[kMaxGroup];
     const int u = blockIdx.x / chunks, ch = blockIdx.x % chunks;
@@ -63,7 +124,13 @@ __global__ __launch_bounds__(256) void scores_kernel(const T *__restrict__ Kc, c
     const int lo = ch * per, hi = min(lo + per, N);
     for (int slot = lo + wave; slot < hi; slot += 4) {
         float r = 0.f;
-        if (slot < n) {
+        // lu_mask: explicit mask in force, NaN marks an invalid slot (score 0, as in Alg. 1)
+        bool valid = slot < n;
+        if (valid && lu_mask) {
+            const float x = lu_mask[(size_t)u * lu_stride + (slot & ~15) + tail_pos_of_slot(slot & 15)];
+            valid = x == x;
+        }
+        if (valid) {
             const double v = tail_exact_score<T, D>(Kc + ((size_t)u * N + slot) * D, Vc + ((size_t)u * N + slot) * D,
                                                q_last + (size_t)u * G * D, G, sM, sL, lane);
             r = (float)v;
@@ -80,7 +147,7 @@ hipError_t launch_scores(const Plan &p, int n, float *scores, hipStream_t s)
 #define LF_SC(T, DD)                                                                            \
     hipLaunchKernelGGL((scores_kernel<T, DD>), dim3(p.units * chunks), dim3(256), 0, s,         \
                        (const T *)p.k_cache, (const T *)p.v_cache, (const T *)p.q_last, n, p.N, \
-                       p.G, p.fin_m, p.fin_l, scores, chunks)
+                       p.G, p.fin_m, p.fin_l, scores, chunks, p.masked ? p.lu : nullptr, p.ntiles * kTile)
     if (p.dtype == 0) { if (p.D == 64) LF_SC(float, 64); else LF_SC(float, 128); }
     else              { if (p.D == 64) LF_SC(bf16_t, 64); else LF_SC(bf16_t, 128); }
 #undef LF_SC

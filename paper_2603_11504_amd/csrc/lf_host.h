@@ -23,6 +23,7 @@ struct Plan {
     bool use_mfma;     // bf16, head_dim 128: matrix-core kernels
     bool use_unit;     // unit-resident fused kernel: whole step in one launch
     int unit_S;        // ... with this many cooperating workgroups per unit
+    bool masked;       // an explicit validity mask is in force (state, set by longflow_set_mask)
     // device pointers (caller-owned)
     void *k_cache, *v_cache;
     // carved out of the caller's workspace
@@ -38,11 +39,13 @@ struct Plan {
     uint16_t *stash_w; // [units][ntiles][G][kTile] bf16 screening values ||v||_1 * p
     float *stash_m;    // [units][ntiles][G]        reference each tile's p is relative to
     float *lu;         // [units][ntiles*kTile] log2 ||v||_1 per slot, position order inside a tile
-                       // (matrix-core kernels only; kept current by init and insert)
+                       // (kept current by init and insert; NaN = slot invalid under an explicit
+                       // mask; the vector-ALU kernels use it for validity only)
+    int32_t *first_hole; // [units] scratch of the mask setter
 };
 
 struct Layout {
-    size_t off_pending, off_arrive, off_dumped, off_q, off_part_m, off_part_l, off_part_o, off_fin_m, off_fin_l,
+    size_t off_pending, off_arrive, off_dumped, off_hole, off_q, off_part_m, off_part_l, off_part_o, off_fin_m, off_fin_l,
         off_stash_w, off_stash_m, off_lu, total;
 };
 
@@ -80,5 +83,9 @@ hipError_t launch_unit_mfma_group(const Plan &p, const StepIo &io, int n, const 
 hipError_t launch_scores(const Plan &p, int n, float *scores, hipStream_t s);
 hipError_t launch_l1norms(const Plan &p, int n_rows, hipStream_t s);
 hipError_t launch_fill_i32(int32_t *dst, int count, int32_t value, hipStream_t s);
+// Explicit mask (device uint8 [units][N], nonzero = valid): rewrites the side array, zeroes
+// the K/V rows of invalid slots and points `pending` of every unit that has an invalid
+// slot at its lowest one.
+hipError_t launch_set_mask(const Plan &p, const uint8_t *mask, hipStream_t s);
 
 } // namespace lf

@@ -56,6 +56,10 @@ constexpr float kCodeBias = 16.f;
 // (log2 units): p stays below 2^kMaxSlack, far inside fp32/bf16 range, and the common
 // path needs no cross-lane traffic at all.
 constexpr float kMaxSlack = 8.f;
+// Reference of a softmax state that has seen no valid slot yet: finite, so that a tile of
+// masked slots only (logits -inf) gives p = 2^(-inf - kNoRef) = 0 rather than NaN, and so
+// far below any logit that the first valid one replaces it (weights 2^(kNoRef - m) = 0).
+constexpr float kNoRef = -3.0e38f;
 
 // position of a slot inside its 16-slot tile, and back
 __host__ __device__ __forceinline__ int pos_of_slot(int s) { return 4 * ((s >> 1) & 3) + 2 * ((s >> 3) & 1) + (s & 1); }
@@ -74,7 +78,8 @@ __device__ __forceinline__ uint32_t pack_bf16x2(float lo, float hi)
     return __builtin_bit_cast(uint32_t, b);
 }
 
-template <int NWAVES, bool HILO, int STASH>
+// MASKED: an explicit validity mask may be in force (NaN entries of the side array)
+template <int NWAVES, bool HILO, int STASH, bool MASKED = false>
 struct MfmaStreamer {
     static constexpr int D = 128;
     // per-wave state
@@ -105,7 +110,7 @@ struct MfmaStreamer {
             }
 #pragma unroll
         for (int dd = 0; dd < 8; ++dd) oacc[dd] = f32x4{0.f, 0.f, 0.f, 0.f};
-        m = -INFINITY;
+        m = kNoRef;
         l = 0.f;
     }
 
@@ -116,6 +121,9 @@ struct MfmaStreamer {
     {
         const int base = start + ti * kTile;
         const int last = end - 1;
+        // side array first: loads return in order, and its first use (the mask test right
+        // after the logits) must not have to wait for this tile's V rows
+        if (STASH != kStashNone) t.lu = *(const f32x4 *)(lu_unit + base + 4 * g);
 #pragma unroll
         for (int a = 0; a < 2; ++a) {
             int krow = base + 8 * a + (r >> 1);
@@ -131,7 +139,6 @@ struct MfmaStreamer {
             if (RAGGED) vrow = min(vrow, last);
             t.v[e] = __builtin_nontemporal_load((const u32x4 *)(Vu + (size_t)vrow * D + 8 * r));
         }
-        if (STASH != kStashNone) t.lu = *(const f32x4 *)(lu_unit + base + 4 * g);
     }
 
     // RAGGED: the tile may reach past `end`; rows loaded from the clamped address are zeroed
@@ -165,6 +172,12 @@ struct MfmaStreamer {
 #pragma unroll
             for (int e = 0; e < 4; ++e)
                 if (base + slot_off(e) >= end) s[e] = -INFINITY;
+        }
+        // ---- explicit mask (Alg. 1's M): a slot whose side-array entry is NaN is invalid;
+        // its logit becomes -inf, hence p = 0 (its V row is kept finite by the mask setter)
+        if (MASKED && STASH != kStashNone) {
+#pragma unroll
+            for (int e = 0; e < 4; ++e) s[e] = (t.lu[e] != t.lu[e]) ? -INFINITY : s[e];
         }
         // ---- online softmax with a lazily raised reference
         const float mx = fmaxf(fmaxf(s[0], s[1]), fmaxf(s[2], s[3])) * scale_log2;

@@ -7,7 +7,7 @@
 
 namespace lf {
 
-template <bool HILO, int STASH>
+template <bool HILO, int STASH, bool MASKED>
 __global__ __launch_bounds__(256, 2) void split_mfma_kernel(const SplitTailArgs<bf16_t> ta_in, float scale_log2,
                                                              const SplitGroup gr)
 {
@@ -25,7 +25,7 @@ __global__ __launch_bounds__(256, 2) void split_mfma_kernel(const SplitTailArgs<
 
     split_head_insert<bf16_t, D>(ta, u, c);
 
-    MfmaStreamer<4, HILO, STASH> st;
+    MfmaStreamer<4, HILO, STASH, MASKED> st;
     st.init(q + (size_t)u * G * D, G, lane, scale_log2);
     st.Ku = Kc + (size_t)u * N * D;
     st.Vu = Vc + (size_t)u * N * D;
@@ -73,9 +73,11 @@ hipError_t launch_split_mfma(const Plan &p, const StepIo &io, int n, hipStream_t
     const float scale_log2 = 1.4426950408889634f / sqrtf(128.f);
     const dim3 grid(p.units * ta.c_active * n_caches);
     if (p.flags & 1u)
-        hipLaunchKernelGGL((split_mfma_kernel<true, kStashNone>), grid, dim3(256), 0, s, ta, scale_log2, gr);
+        hipLaunchKernelGGL((split_mfma_kernel<true, kStashNone, false>), grid, dim3(256), 0, s, ta, scale_log2, gr);
+    else if (p.masked)
+        hipLaunchKernelGGL((split_mfma_kernel<true, kStashGlobal, true>), grid, dim3(256), 0, s, ta, scale_log2, gr);
     else
-        hipLaunchKernelGGL((split_mfma_kernel<true, kStashGlobal>), grid, dim3(256), 0, s, ta, scale_log2, gr);
+        hipLaunchKernelGGL((split_mfma_kernel<true, kStashGlobal, false>), grid, dim3(256), 0, s, ta, scale_log2, gr);
     hipError_t e = hipGetLastError();
     if (e == hipSuccess && !ta.fused_tail) e = launch_split_finish<bf16_t, 128>(ta, p.units, gr, n_caches, s);
     return e;

@@ -16,8 +16,8 @@
 
 namespace lf {
 
-__host__ __device__ __forceinline__ int tail_pos_of_slot(int s) { return 4 * ((s >> 1) & 3) + 2 * ((s >> 3) & 1) + (s & 1); }
-__host__ __device__ __forceinline__ int tail_slot_of_pos(int p) { return 8 * ((p >> 1) & 1) + 2 * (p >> 2) + (p & 1); }
+__host__ __device__ constexpr __forceinline__ int tail_pos_of_slot(int s) { return 4 * ((s >> 1) & 3) + 2 * ((s >> 3) & 1) + (s & 1); }
+__host__ __device__ constexpr __forceinline__ int tail_slot_of_pos(int p) { return 8 * ((p >> 1) & 1) + 2 * (p >> 2) + (p & 1); }
 
 template <typename T> struct SplitTailArgs {
     T *Kc, *Vc;               // caches [units][N][D]
@@ -28,10 +28,11 @@ template <typename T> struct SplitTailArgs {
     uint16_t *stash_w;                     // [units][ntiles][G][16] bf16
     float *stash_m;                        // [units][ntiles][G]
     float *fin_m, *fin_l;                  // [units][G]
-    float *lu;                             // [units][ntiles*16] log2 ||v||_1 (position order) or null
+    float *lu;                             // [units][ntiles*16] log2 ||v||_1 (position order); null if attention-only
     int n, N, G, C, c_active, ntiles, L;
     int attention_only, pos_order;
     int fused_tail; // 1: the last workgroup of a unit to arrive finishes it; 0: a finish launch follows
+    int masked;     // explicit mask in force: NaN entries of lu mark invalid slots
 };
 
 // The fused tail needs a device-wide release/acquire per workgroup, which on this chip
@@ -63,7 +64,8 @@ inline SplitTailArgs<T> make_tail_args(const Plan &p, const StepIo &io, int n, i
     a.part_m = p.part_m; a.part_l = p.part_l; a.part_o = p.part_o;
     a.stash_w = p.stash_w; a.stash_m = p.stash_m;
     a.fin_m = p.fin_m; a.fin_l = p.fin_l;
-    a.lu = (p.use_mfma && !(p.flags & 1u)) ? p.lu : nullptr;
+    a.lu = !(p.flags & 1u) ? p.lu : nullptr;
+    a.masked = p.masked ? 1 : 0;
     a.n = n; a.N = p.N; a.G = p.G; a.C = p.C; a.c_active = (n + p.L - 1) / p.L; a.ntiles = p.ntiles; a.L = p.L;
     a.attention_only = (p.flags & 1u) ? 1 : 0;
     a.pos_order = p.use_mfma ? 1 : 0;
@@ -121,7 +123,7 @@ __device__ __forceinline__ void split_head_insert(const SplitTailArgs<T> &a, int
         a.Vc[((size_t)u * a.N + slot) * D + tid] = v;
         a1 = fabsf(to_f32(v));
     }
-    if (a.lu) { // side array of the matrix-core kernels
+    if (a.lu) { // side array: log2 ||v||_1 for the matrix-core kernels; any non-NaN value says "valid"
 #pragma unroll
         for (int off = 32; off > 0; off >>= 1) a1 += __shfl_xor(a1, off);
         if ((tid & 63) == 0) part[tid >> 6] = a1;
@@ -227,6 +229,32 @@ __device__ void split_finish_unit(const SplitTailArgs<T> &a, int u)
             if (a.evict_idx) a.evict_idx[u] = n;
         }
         return;
+    }
+
+    // ---- explicit mask: an invalid slot (NaN in the side array) takes the next token before
+    // anything is evicted; the slot this step filled may still read stale and is skipped
+    if (a.masked) {
+        __shared__ int hole_w[4];
+        const float *lu_u = a.lu + (size_t)u * a.ntiles * kTile;
+        const int ins_slot = a.pending[u];
+        int best = 0x7fffffff;
+        for (int p = tid; p < a.ntiles * kTile; p += 256) {
+            const float x = lu_u[p];
+            const int slot = (p & ~15) + tail_slot_of_pos(p & 15);
+            if (x != x && slot < N && slot != ins_slot) best = min(best, slot);
+        }
+#pragma unroll
+        for (int off = 32; off > 0; off >>= 1) best = min(best, __shfl_xor(best, off));
+        if (lane == 0) hole_w[wave] = best;
+        __syncthreads();
+        best = min(min(hole_w[0], hole_w[1]), min(hole_w[2], hole_w[3]));
+        if (best != 0x7fffffff) {
+            if (tid == 0) {
+                a.pending[u] = best;
+                if (a.evict_idx) a.evict_idx[u] = best;
+            }
+            return;
+        }
     }
 
     // ---- screening pass 1: approximate scores from the stash, block minimum

@@ -77,10 +77,15 @@ __global__ __launch_bounds__(256) void split_valu_kernel(const SplitTailArgs<T> 
         float t[G];
 #pragma unroll
         for (int h = 0; h < G; ++h) t[h] = -INFINITY;
+        // explicit mask (Alg. 1's M): lane j holds the side-array entry of tile position j;
+        // NaN marks an invalid slot, which is then treated like a slot past the end
+        float lu_mine = 0.f;
+        if (ta.masked) lu_mine = ta.lu[(size_t)u * ntiles * kTile + base + j];
         static_for<kTile>([&](auto ic) {
             constexpr int jj = decltype(ic)::value;
             const int slot = base + jj;
-            const bool valid = slot < end;
+            const float lu_jj = row16_bcast<tail_pos_of_slot(jj)>(lu_mine);
+            const bool valid = slot < end && lu_jj == lu_jj;
             RowChunk<T, EPL> kr;
             if (valid) kr.load(Ku + (size_t)slot * D + j * EPL); else kr.zero();
 #pragma unroll
@@ -110,7 +115,8 @@ __global__ __launch_bounds__(256) void split_valu_kernel(const SplitTailArgs<T> 
         static_for<kTile>([&](auto ic) {
             constexpr int jj = decltype(ic)::value;
             const int slot = base + jj;
-            const bool valid = slot < end;
+            const float lu_jj = row16_bcast<tail_pos_of_slot(jj)>(lu_mine);
+            const bool valid = slot < end && lu_jj == lu_jj;
             RowChunk<T, EPL> vr;
             if (valid) vr.load(Vu + (size_t)slot * D + j * EPL); else vr.zero();
             float au = 0.f;

@@ -155,8 +155,33 @@ __device__ double exact_score_bf16(const uint16_t *krow, const uint16_t *vrow, c
     return term * l1;
 }
 
+// Explicit-mask mode: the lowest invalid slot of the unit (NaN in the side array), not
+// counting the slot this step has just filled (its entry may still read stale here).
+// All 512 threads call; true if there is one, then it is in red[0].
+__device__ bool fill_lowest_hole(const float *lu_u, int npos, int N, int ins_slot, int *red, int tid, int lane,
+                                 int wave)
+{
+    int best = 0x7fffffff;
+    for (int p = tid; p < npos; p += 512) {
+        const float x = lu_u[p];
+        const int slot = (p & ~15) + slot_of_pos(p & 15);
+        if (x != x && slot < N && slot != ins_slot) best = min(best, slot);
+    }
+#pragma unroll
+    for (int off = 32; off > 0; off >>= 1) best = min(best, __shfl_xor(best, off));
+    if (lane == 0) red[1 + wave] = best;
+    __syncthreads();
+    if (tid == 0) {
+        int b = red[1];
+        for (int w = 1; w < 8; ++w) b = min(b, red[1 + w]);
+        red[0] = b;
+    }
+    __syncthreads();
+    return red[0] != 0x7fffffff;
+}
+
 // COOP: several workgroups may share a unit (s_active can exceed 1)
-template <bool HILO, int STASH, bool COOP, bool GROUPED>
+template <bool HILO, int STASH, bool COOP, bool GROUPED, bool MASKED>
 __global__ __launch_bounds__(512, 1) void unit_mfma_kernel(const UnitArgs a_in, const GroupArgs ga)
 {
     UnitArgs a = a_in;
@@ -191,6 +216,7 @@ __global__ __launch_bounds__(512, 1) void unit_mfma_kernel(const UnitArgs a_in, 
     __shared__ __align__(16) uint16_t qs[16][D]; // the query, for the exact re-scoring
     __shared__ int cand_list[kMaxCand];
     __shared__ int cand_count, s_flag;
+    __shared__ int red_i[NW + 1];
 
     const int n = a.n, N = a.N, G = a.G, s_active = COOP ? a.s_active : 1;
     const int u = blk / s_active, sp = blk % s_active;
@@ -225,7 +251,7 @@ __global__ __launch_bounds__(512, 1) void unit_mfma_kernel(const UnitArgs a_in, 
         }
     }
 
-    MfmaStreamer<NW, HILO, STASH> st;
+    MfmaStreamer<NW, HILO, STASH, MASKED> st;
     st.init(qu, G, lane, a.scale_log2);
     st.Ku = Ku;
     st.Vu = Vu;
@@ -359,6 +385,12 @@ __global__ __launch_bounds__(512, 1) void unit_mfma_kernel(const UnitArgs a_in, 
             if (tid == 0) {
                 a.pending[u] = n;
                 if (a.evict_idx) a.evict_idx[u] = n;
+            }
+        } else if (MASKED && fill_lowest_hole(lu_u, a.gstride, N, ins_slot, red_i, tid, lane, wave)) {
+            // an invalid slot exists: it takes the next token, nothing is evicted
+            if (tid == 0) {
+                a.pending[u] = red_i[0];
+                if (a.evict_idx) a.evict_idx[u] = red_i[0];
             }
         } else {
             // own codes: per (tile, head) factor that turns a decoded code into a score term
@@ -661,19 +693,25 @@ static hipError_t launch_unit(const Plan &p, const StepIo &io, int n, const void
     // the dynamic-LDS ceiling is a per-device function attribute: raise it once per device
     // and kernel instance (a benign race if two host threads get here together: both set it)
     constexpr int kMaxDevices = 64;
-    static bool attr_done_all[kMaxDevices][8] = {};
+    static bool attr_done_all[kMaxDevices][16] = {};
     int dev = 0;
     if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) return hipErrorInvalidDevice;
     bool *attr_done = attr_done_all[dev];
-#define LF_UNIT(STASH, COOP, GROUPED, IDX)                                                            \
+#define LF_UNIT4(STASH, COOP, GROUPED, MASKED, IDX)                                                   \
     do {                                                                                              \
         if (!attr_done[IDX]) {                                                                        \
-            hipError_t e = hipFuncSetAttribute((const void *)unit_mfma_kernel<true, STASH, COOP, GROUPED>, \
+            hipError_t e = hipFuncSetAttribute((const void *)unit_mfma_kernel<true, STASH, COOP, GROUPED, MASKED>, \
                                                hipFuncAttributeMaxDynamicSharedMemorySize, (int)kUnitLdsLimit); \
             if (e != hipSuccess) return e;                                                            \
             attr_done[IDX] = true;                                                                    \
         }                                                                                             \
-        hipLaunchKernelGGL((unit_mfma_kernel<true, STASH, COOP, GROUPED>), dim3((unsigned)wgs), dim3(512), lds, s, a, ga); \
+        hipLaunchKernelGGL((unit_mfma_kernel<true, STASH, COOP, GROUPED, MASKED>), dim3((unsigned)wgs), dim3(512), lds, s, a, ga); \
+    } while (0)
+    // the mask only matters where slots are scored (an attention-only cache takes none)
+#define LF_UNIT(STASH, COOP, GROUPED, IDX)                                                            \
+    do {                                                                                              \
+        if (p.masked && STASH == kStashLds) LF_UNIT4(STASH, COOP, GROUPED, true, 8 + IDX);            \
+        else LF_UNIT4(STASH, COOP, GROUPED, false, IDX);                                              \
     } while (0)
     const bool coop = S > 1;
     if (table) {
@@ -683,6 +721,7 @@ static hipError_t launch_unit(const Plan &p, const StepIo &io, int n, const void
         if (stash) { if (coop) LF_UNIT(kStashLds, true, false, 0); else LF_UNIT(kStashLds, false, false, 1); }
         else       { if (coop) LF_UNIT(kStashNone, true, false, 2); else LF_UNIT(kStashNone, false, false, 3); }
     }
+#undef LF_UNIT4
 #undef LF_UNIT
     return hipGetLastError();
 }

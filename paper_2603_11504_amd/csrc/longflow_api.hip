@@ -108,6 +108,7 @@ static Layout layout_of(const Plan &p)
     l.off_pending = take(sizeof(int32_t) * p.units);
     l.off_arrive = take(sizeof(int32_t) * p.units);
     l.off_dumped = take(sizeof(int32_t) * p.units);
+    l.off_hole = take(sizeof(int32_t) * p.units);
     l.off_q = take(esz * (size_t)p.B * p.Hq * p.D);
     l.off_part_m = take(sizeof(float) * (size_t)p.units * p.C * kMaxGroup);
     l.off_part_l = take(sizeof(float) * (size_t)p.units * p.C * kMaxGroup);
@@ -120,7 +121,8 @@ static Layout layout_of(const Plan &p)
     const size_t per_slot = p.use_unit ? 1 : sizeof(uint16_t);
     l.off_stash_w = take(stash ? per_slot * (size_t)p.units * p.ntiles * p.G * kTile : 0);
     l.off_stash_m = take(stash ? sizeof(float) * (size_t)p.units * p.ntiles * p.G : 0);
-    l.off_lu = take(p.use_mfma && !(p.flags & LF_FLAG_ATTENTION_ONLY) ? sizeof(float) * (size_t)p.units * p.ntiles * kTile : 0);
+    // per-slot side array: log2 ||v||_1 for the matrix-core kernels, validity under an explicit mask for all
+    l.off_lu = take(!(p.flags & LF_FLAG_ATTENTION_ONLY) ? sizeof(float) * (size_t)p.units * p.ntiles * kTile : 0);
     l.total = off;
     return l;
 }
@@ -189,6 +191,7 @@ int longflow_init_cache(longflow_cache_t **out, const lf_config *cfg, void *k_ca
     p.pending = (int32_t *)(ws + l.off_pending);
     p.arrive = (int32_t *)(ws + l.off_arrive);
     p.dumped = (int32_t *)(ws + l.off_dumped);
+    p.first_hole = (int32_t *)(ws + l.off_hole);
     p.q_last = ws + l.off_q;
     p.part_m = (float *)(ws + l.off_part_m);
     p.part_l = (float *)(ws + l.off_part_l);
@@ -355,6 +358,8 @@ int longflow_group_create(longflow_group_t **group, longflow_cache_t *const *cac
         if (a.B != b.B || a.Hq != b.Hq || a.Hkv != b.Hkv || a.D != b.D || a.N != b.N || a.dtype != b.dtype ||
             a.flags != b.flags)
             return fail(LF_ERR_INVALID_ARG, "member %d differs from member 0 in its configuration", i);
+        if (a.masked != b.masked)
+            return fail(LF_ERR_STATE, "member %d differs from member 0 in whether a mask is in force", i);
         members.push_back(c);
     }
     // one entry per member, in the layout of the kernel family its plan uses
@@ -392,6 +397,8 @@ int longflow_group_decode_step(longflow_group_t *group, const void *q, const voi
         const longflow_cache *c = group->members[i];
         if (c->count != c0->count)
             return fail(LF_ERR_STATE, "member %zu holds %d rows, member 0 holds %d", i, c->count, c0->count);
+        if (c->plan.masked != c0->plan.masked)
+            return fail(LF_ERR_STATE, "member %zu differs from member 0 in whether a mask is in force", i);
         if (!attention_only && !c->has_pending)
             return fail(LF_ERR_STATE, "member %zu is full and no slot is pending: call longflow_set_pending", i);
     }
@@ -423,6 +430,20 @@ int longflow_group_destroy(longflow_group_t *group)
     for (longflow_cache *m : group->members) --m->groups;
     group->magic = 0;
     delete group;
+    return LF_OK;
+}
+
+int longflow_set_mask(longflow_cache_t *cache, const uint8_t *mask, void *hip_stream)
+{
+    longflow_cache *c = checked(cache);
+    if (!c) return fail(LF_ERR_STATE, "invalid or destroyed cache handle");
+    if (!mask) return fail(LF_ERR_INVALID_ARG, "mask is NULL");
+    if (c->plan.flags & LF_FLAG_ATTENTION_ONLY)
+        return fail(LF_ERR_UNSUPPORTED, "an attention-only cache takes no mask");
+    hipError_t e = launch_set_mask(c->plan, mask, (hipStream_t)hip_stream);
+    if (e != hipSuccess) return fail(LF_ERR_HIP, "mask launch: %s", hipGetErrorString(e));
+    c->plan.masked = true;
+    c->count = c->plan.N; // every step now looks at all N slots
     return LF_OK;
 }
 

@@ -22,7 +22,7 @@ LF_FLAG_FORCE_SPLIT = 4
 LF_FLAG_FORCE_UNIT = 8
 
 EXPORTS = ("longflow_workspace_bytes", "longflow_init_cache", "longflow_decode_step",
-           "longflow_scores", "longflow_set_pending", "longflow_valid_count",
+           "longflow_scores", "longflow_set_pending", "longflow_set_mask", "longflow_valid_count",
            "longflow_destroy_cache", "longflow_last_error", "longflow_profile_begin",
            "longflow_profile_end", "longflow_plan_info", "longflow_group_workspace_bytes", "longflow_group_create",
            "longflow_group_decode_step", "longflow_group_destroy")
@@ -72,6 +72,8 @@ def lib():
         L.longflow_scores.restype = ctypes.c_int
         L.longflow_set_pending.argtypes = [vp, vp, vp]
         L.longflow_set_pending.restype = ctypes.c_int
+        L.longflow_set_mask.argtypes = [vp, vp, vp]
+        L.longflow_set_mask.restype = ctypes.c_int
         L.longflow_valid_count.argtypes = [vp]
         L.longflow_valid_count.restype = ctypes.c_int
         L.longflow_destroy_cache.argtypes = [vp]
@@ -170,6 +172,13 @@ class LongFlowCache:
         slots = slots.to(device=self.device, dtype=torch.int32).contiguous()
         _check(lib().longflow_set_pending(self._h, _ptr(slots), _stream()))
         self._keep = slots  # alive until the async copy has run
+
+    def set_mask(self, mask):
+        """mask: [B, Hkv, N], nonzero = valid slot (the vector M of Alg. 1)."""
+        mask = (mask != 0).to(device=self.device, dtype=torch.uint8).contiguous()
+        assert tuple(mask.shape) == (self.cfg.batch, self.cfg.kv_heads, self.cfg.budget)
+        _check(lib().longflow_set_mask(self._h, _ptr(mask), _stream()))
+        self._keep_mask = mask  # alive until the kernels that read it have run
 
     def profile_begin(self, max_steps):
         _check(lib().longflow_profile_begin(self._h, max_steps))

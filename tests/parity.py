@@ -34,7 +34,8 @@ def compare_indices(gpu_idx, ora_idx, ora_scores, full, rep, where=""):
     bad = np.nonzero(gpu_idx != ora_idx)[0]
     if bad.size == 0:
         return False
-    assert full, f"{where}: fill-phase slot differs: gpu {gpu_idx[bad]} oracle {ora_idx[bad]}"
+    full = np.broadcast_to(np.asarray(full, dtype=bool).reshape(-1), gpu_idx.shape)   # per unit, or one for all
+    assert full[bad].all(), f"{where}: fill-phase slot differs: gpu {gpu_idx[bad]} oracle {ora_idx[bad]}"
     sc = ora_scores.reshape(gpu_idx.size, -1)
     for u in bad:
         sg, so = sc[u, gpu_idx[u]], sc[u, ora_idx[u]]
@@ -47,11 +48,14 @@ def compare_indices(gpu_idx, ora_idx, ora_scores, full, rep, where=""):
 
 
 def run_lockstep(wl: W.Workload, steps=None, flags=0, check_scores_every=0, units=None,
-                 device="cuda", layer=0, host_inputs=True, gpu_cache=None, report=None):
+                 device="cuda", layer=0, host_inputs=True, gpu_cache=None, report=None, mask=None):
     """Advance GPU cache and oracle together for `steps` decode steps, comparing each.
 
     units: optional list of flat (batch*kv_head) unit indices the oracle follows (the GPU
     always runs the whole workload); None = all of them.
+    mask: optional bool array [B, Hkv, N], the explicit validity mask both sides are given
+    after the prefill (a cache prefilled to N rows first gets slot 0 as pending slot, which
+    units without an invalid slot then keep).
     """
     rep = report or ParityReport()
     steps = wl.steps if steps is None else steps
@@ -78,6 +82,13 @@ def run_lockstep(wl: W.Workload, steps=None, flags=0, check_scores_every=0, unit
     else:
         ora.init()
     del k0_t, v0_t
+    if mask is not None:
+        mask = np.asarray(mask, dtype=bool).reshape(wl.units, N)
+        if wl.n_init == N:
+            gpu.set_pending(torch.zeros((wl.batch, wl.kv_heads), dtype=torch.int32))
+            ora.set_pending(np.zeros((nu, 1), dtype=np.int32))
+        gpu.set_mask(torch.as_tensor(mask.reshape(wl.batch, wl.kv_heads, N)))
+        ora.set_mask(mask[all_units].reshape(nu, 1, N))
 
     tol = OUT_TOL[wl.dtype]
     for t in range(steps):
@@ -98,7 +109,8 @@ def run_lockstep(wl: W.Workload, steps=None, flags=0, check_scores_every=0, unit
         rep.max_out_err = max(rep.max_out_err, err)
         assert err <= tol, f"step {t}: max |out - oracle| = {err:.3e} > {tol}"
         i_gpu = idx_t.reshape(-1)[sel].cpu().numpy()
-        full = ora.count == N
+        # with an explicit mask the index is a hole (exact) until the holes are used up
+        full = (ora.count == N) if mask is None else ora.mask().reshape(nu, N).all(-1)
         if compare_indices(i_gpu, i_ref, ora.scores(), full, rep, where=f"{wl.name} step {t}"):
             ora.set_pending(i_gpu.reshape(nu, 1))
         assert gpu.valid_count == ora.count
@@ -107,6 +119,8 @@ def run_lockstep(wl: W.Workload, steps=None, flags=0, check_scores_every=0, unit
             s_ref = ora.scores().reshape(nu, N)
             n = ora.count
             assert (s_gpu[:, n:] == 0).all()
+            if mask is not None:
+                assert (s_gpu[ora.mask().reshape(nu, N) == 0] == 0).all()     # invalid slots score 0
             rel = np.abs(s_gpu[:, :n] - s_ref[:, :n]) / np.maximum(s_ref[:, :n], 1e-30)
             # fp32 result: 1e-5 relative, except where the score itself is below fp32 range
             ok = (rel <= 1e-5) | (s_ref[:, :n] < 1e-35)

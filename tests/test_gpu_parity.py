@@ -495,3 +495,76 @@ def test_group_attention_only_and_errors():
     g2.close()
     for c in att + twin + other + fill:
         c.close()
+
+
+# ------------------------------------------------------------------ explicit validity mask (Alg. 1's M)
+
+def _random_mask(wl, seed, density):
+    rng = np.random.default_rng(seed)
+    m = rng.random((wl.batch, wl.kv_heads, wl.budget)) < density
+    m[..., wl.budget // 3] = True                      # no unit is ever empty
+    if wl.units > 1:
+        m.reshape(wl.units, -1)[0, :] = True           # one unit without a hole: it evicts from the start
+    return m
+
+
+@pytest.mark.parametrize("name,dtype,B,Hq,Hkv,D,N,flags,density", [
+    ("single", "bf16", 48, 16, 4, 128, 300, 0, 0.9),            # one workgroup per unit
+    ("coop", "bf16", 2, 28, 4, 128, 2048, 0, 0.98),             # several workgroups per unit
+    ("coop-sparse", "bf16", 1, 8, 2, 128, 1100, 0, 0.3),        # whole tiles and workgroup shares invalid
+    ("split", "bf16", 3, 8, 2, 128, 700, lf.LF_FLAG_FORCE_SPLIT, 0.9),
+    ("split-big", "bf16", 40, 8, 2, 128, 2048, lf.LF_FLAG_FORCE_SPLIT, 0.97),
+    ("valu-bf16", "bf16", 2, 6, 2, 128, 333, lf.LF_FLAG_FORCE_VALU, 0.8),
+    ("fp32", "f32", 2, 8, 2, 64, 200, 0, 0.7),
+])
+def test_explicit_mask_holes_fill_first_then_eviction(name, dtype, B, Hq, Hkv, D, N, flags, density):
+    # a full cache of which a random subset is valid: the holes take the next tokens lowest
+    # first, then the argmin takes over; attention never sees an invalid slot
+    wl = _small("mask-" + name, dtype, B, Hq, Hkv, D, N, n_init=N, steps=1, sink_scale=4.0, seed=120)
+    mask = _random_mask(wl, 7, density)
+    holes = int((~mask).reshape(wl.units, -1).sum(-1).max())
+    steps = holes + 12
+    units = None if wl.units <= 24 else list(range(0, wl.units, wl.units // 12))
+    rep, gpu, ora = run_lockstep(wl, steps=steps, flags=flags, mask=mask, check_scores_every=max(steps // 4, 1),
+                                 units=units)
+    assert rep.steps == steps and ora.mask().all()
+    gpu.close()
+
+
+def test_ragged_batch_through_a_prefix_mask():
+    # sequences of different lengths in one batch: rows past a sequence's length are masked
+    wl = _small("mask-ragged", "bf16", 6, 16, 4, 128, 256, n_init=200, steps=1, seed=121)
+    lens = np.array([200, 1, 17, 128, 199, 64])
+    mask = np.arange(wl.budget)[None, None, :] < lens[:, None, None] + np.zeros((1, wl.kv_heads, 1), dtype=int)
+    rep, gpu, ora = run_lockstep(wl, steps=300, mask=mask, check_scores_every=50)
+    assert ora.mask().all()                            # even the shortest sequence has filled its cache
+    gpu.close()
+
+
+def test_mask_can_be_set_again_mid_run_and_needs_a_compressing_cache():
+    wl = _small("mask-again", "bf16", 2, 8, 2, 128, 160, n_init=100, steps=1, seed=122)
+    mask = np.arange(wl.budget)[None, None, :] < np.array([100, 40])[:, None, None] + np.zeros((1, 2, 1), dtype=int)
+    rep, gpu, ora = run_lockstep(wl, steps=30, mask=mask)
+    # drop every third slot of the second sequence, keep going on both sides
+    m2 = ora.mask().reshape(wl.batch, wl.kv_heads, wl.budget).astype(bool)
+    m2[1, :, ::3] = False
+    gpu.set_mask(torch.as_tensor(m2))
+    ora.set_mask(m2.reshape(wl.units, 1, wl.budget))
+    for t in range(30, 180):
+        q, k, v = (W.to_torch(x, wl, "cuda") for x in W.host_step(wl, t, 0))
+        out, idx = gpu.decode_step(q, k, v)
+        o_ref, i_ref = ora.step(W.to_f64(q).reshape(wl.units, -1, wl.head_dim), W.to_f64(k).reshape(wl.units, 1, -1),
+                                W.to_f64(v).reshape(wl.units, 1, -1))
+        assert np.abs(W.to_f64(out).reshape(o_ref.shape) - o_ref).max() <= 2e-2
+        if compare_indices(idx.cpu().numpy(), i_ref, ora.scores(), ora.mask().reshape(wl.units, -1).all(-1), rep,
+                           where=f"re-mask step {t}"):
+            ora.set_pending(idx.cpu().numpy().reshape(wl.units, 1))
+    assert ora.mask().all()
+    gpu.close()
+    att = lf.LongFlowCache(2, 8, 2, 128, 64, flags=lf.LF_FLAG_ATTENTION_ONLY,
+                           k_init=torch.zeros(2, 2, 64, 128, device="cuda", dtype=torch.bfloat16),
+                           v_init=torch.zeros(2, 2, 64, 128, device="cuda", dtype=torch.bfloat16))
+    with pytest.raises(lf.LongFlowError) as e:
+        att.set_mask(torch.ones(2, 2, 64))
+    assert e.value.status == lf.LF_ERR_UNSUPPORTED
+    att.close()
