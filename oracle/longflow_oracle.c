@@ -205,6 +205,42 @@ LFO_API int lfo_cache_get_mask(const lfo_cache *c, uint8_t *mask)
     return 0;
 }
 
+/*
+ * Batch eviction, the "compress every k steps" regime the paper contrasts
+ * its per-step eviction with (Sec. 4.4): drop the k valid slots with the
+ * lowest LongFlowScore of the last step (eq. 6; lowest index first among
+ * equal scores) at once.  They become holes of an explicit mask, which the
+ * next k tokens fill lowest-first.  evicted [B][Hkv][k] receives the slots in
+ * the order chosen (-1 once a unit has no valid slot left).  k = 1 drops the
+ * slot the last step chose anyway.
+ */
+LFO_API int lfo_cache_evict_lowest(lfo_cache *c, int k, int32_t *evicted)
+{
+    size_t units = (size_t)c->B * c->Hkv;
+    const int N = c->N;
+    if (k < 1 || k >= N) return 1;
+    if (!c->mask) { /* the prefix becomes an explicit mask */
+        c->mask = (uint8_t *)malloc(units * N);
+        for (size_t u = 0; u < units; ++u)
+            for (int i = 0; i < N; ++i) c->mask[u * N + i] = (uint8_t)(i < c->count);
+    }
+    for (size_t u = 0; u < units; ++u) {
+        uint8_t *m = c->mask + u * N;
+        const double *sc = c->score + u * N;
+        for (int j = 0; j < k; ++j) {
+            int best = -1;
+            for (int i = 0; i < N; ++i)
+                if (m[i] && (best < 0 || sc[i] < sc[best])) best = i;
+            if (best >= 0) m[best] = 0;
+            if (evicted) evicted[u * k + j] = best;
+        }
+        for (int i = 0; i < N; ++i)
+            if (!m[i]) { c->pending[u] = i; break; }
+    }
+    c->count = N;
+    return 0;
+}
+
 /* one unit's step in mask mode: steps 1-6 over an arbitrary valid set */
 static void step_masked_unit(lfo_cache *c, int u, const double *q, const double *k_new,
                              const double *v_new, double *out, int32_t *evict_idx)

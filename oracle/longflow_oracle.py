@@ -67,6 +67,8 @@ def lib():
         L.lfo_cache_set_mask.restype = ctypes.c_int
         L.lfo_cache_get_mask.argtypes = [ctypes.c_void_p, _bp]
         L.lfo_cache_get_mask.restype = ctypes.c_int
+        L.lfo_cache_evict_lowest.argtypes = [ctypes.c_void_p, ctypes.c_int, _ip]
+        L.lfo_cache_evict_lowest.restype = ctypes.c_int
         L.lfo_num_threads.argtypes = []
         L.lfo_num_threads.restype = ctypes.c_int
         _lib = L
@@ -178,3 +180,10 @@ class OracleCache:
         m = np.empty((self.B, self.Hkv, self.N), dtype=np.uint8)
         lib().lfo_cache_get_mask(self._h, m.ctypes.data_as(ctypes.POINTER(ctypes.c_uint8)))
         return m
+
+    def evict_lowest(self, k):
+        """Drop the k lowest-scoring valid slots of every unit at once -> their slots [B,Hkv,k]."""
+        ev = np.empty((self.B, self.Hkv, k), dtype=np.int32)
+        if lib().lfo_cache_evict_lowest(self._h, int(k), ev.ctypes.data_as(_ip)):
+            raise ValueError("k out of range")
+        return ev

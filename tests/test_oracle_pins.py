@@ -358,3 +358,50 @@ def test_scattering_valid_rows_over_slots_changes_nothing_but_their_places():
         np.testing.assert_allclose(sc[last_slot], score[order[0]], rtol=1e-12)
         np.testing.assert_allclose(sc[slots[1:]], score[order[1:]], rtol=1e-12)
         assert np.count_nonzero(sc) == n
+
+
+# ---------------------------------------------------------------- batch eviction of the k lowest scores
+
+def test_evict_lowest_is_a_stable_sort_of_the_last_scores():
+    B, Hq, Hkv, D, N = 2, 4, 2, 16, 20
+    c, rng = _run_cache(B, Hq, Hkv, D, N, 0, 1400, n_init=N - 1)
+    for t in range(5):
+        q = rng.standard_normal((B, Hq, D)); k = rng.standard_normal((B, Hkv, D)); v = rng.standard_normal((B, Hkv, D))
+        _, idx = c.step(q, k, v)
+    sc = c.scores()
+    ev = c.evict_lowest(6)
+    for b in range(B):
+        for g in range(Hkv):
+            order = np.lexsort((np.arange(N), sc[b, g]))          # by score, then by index
+            np.testing.assert_array_equal(ev[b, g], order[:6])
+            assert ev[b, g, 0] == idx[b, g]                      # the slot the step chose goes first
+            assert (c.mask()[b, g] == 0).sum() == 6 and not c.mask()[b, g, ev[b, g]].any()
+            assert c.pending()[b, g] == ev[b, g].min()            # holes are refilled lowest slot first
+    # the next six tokens land in exactly those slots, ascending; then the argmin is back
+    for t in range(8):
+        pend = c.pending().copy()
+        q = rng.standard_normal((B, Hq, D)); k = rng.standard_normal((B, Hkv, D)); v = rng.standard_normal((B, Hkv, D))
+        _, idx = c.step(q, k, v)
+        if t < 6:
+            np.testing.assert_array_equal(pend, np.sort(ev, -1)[..., t])
+        else:
+            assert c.mask().all()
+            np.testing.assert_array_equal(pend, prev_idx)
+        prev_idx = idx
+
+
+def test_evict_lowest_on_a_filling_cache_and_with_ties():
+    B, Hq, Hkv, D, N = 1, 2, 1, 8, 12
+    c, rng = _run_cache(B, Hq, Hkv, D, N, 0, 1500, n_init=5)
+    q = rng.standard_normal((B, Hq, D)); k = rng.standard_normal((B, Hkv, D)); v = np.zeros((B, Hkv, D))
+    c.step(q, k, v)                                               # 6 valid rows, the newest with zero value norm
+    k2 = rng.standard_normal((B, Hkv, D))
+    c.step(q, k2, np.zeros((B, Hkv, D)))                          # 7 valid, two of them score exactly 0
+    sc = c.scores()[0, 0]
+    assert (sc[5:7] == 0).all() and (sc[:5] > 0).all() and (sc[7:] == 0).all()
+    ev = c.evict_lowest(3)[0, 0]
+    # only valid slots compete (the empty ones also hold score 0); equal scores go lowest index first
+    np.testing.assert_array_equal(ev, [5, 6, int(np.argmin(sc[:5]))])
+    np.testing.assert_array_equal(c.mask()[0, 0], np.isin(np.arange(N), [0, 1, 2, 3, 4]) & (np.arange(N) != ev[2]))
+    with pytest.raises(ValueError):
+        c.evict_lowest(N)
