@@ -145,6 +145,26 @@ LF_API int longflow_set_pending(longflow_cache_t *cache, const int32_t *slots, v
  */
 LF_API int longflow_set_mask(longflow_cache_t *cache, const uint8_t *mask, void *hip_stream);
 
+/*
+ * Batch eviction: the "compress every k steps" regime that Sec. 4.4 sets against the
+ * method's own one-slot-per-step eviction, served from the same score (eq. 6).  Drops the
+ * k valid slots of every (batch, KV head) with the lowest LongFlowScore of the most recent
+ * decode step (double precision; lowest slot first among equal scores); with k = 1 that is
+ * the slot the step itself chose.  The dropped slots, and the unfilled ones of a cache that
+ * is still filling, become invalid slots of the explicit mask (see longflow_set_mask: rows
+ * zeroed, every later step looks at all N slots), so the next tokens refill them lowest
+ * slot first and per-step eviction resumes once they are used up.
+ *   k        1 <= k < N; a unit with fewer valid slots loses all of them
+ *   scratch  device, >= longflow_evict_scratch_bytes(cfg), 8-byte aligned, free for reuse
+ *            once the call's work on hip_stream has run
+ *   evicted  device int32 [B][Hkv][k], the dropped slots in the order chosen (-1 where a
+ *            unit ran out of valid slots), or NULL
+ * LF_ERR_STATE before the first decode step; LF_ERR_UNSUPPORTED with LF_FLAG_ATTENTION_ONLY.
+ */
+LF_API size_t longflow_evict_scratch_bytes(const lf_config *cfg);
+LF_API int longflow_evict_lowest(longflow_cache_t *cache, int32_t k, void *scratch, size_t scratch_bytes,
+                                 int32_t *evicted, void *hip_stream);
+
 /* Valid slots = min(tokens seen, N); negative on a NULL handle. */
 LF_API int longflow_valid_count(const longflow_cache_t *cache);
 

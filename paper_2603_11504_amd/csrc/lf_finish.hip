@@ -105,14 +105,15 @@ hipError_t launch_set_mask(const Plan &p, const uint8_t *mask, hipStream_t s)
 
 // ---------------------------------------------------------------------------------------
 // Score read-back (S_final_loss of Alg. 1), off the per-step path: one wave per slot,
-// double-precision arithmetic, fp32 result.
+// double-precision arithmetic; fp32 result with 0 for invalid slots (longflow_scores), or
+// the double itself with +inf for invalid slots (input of the batch eviction below).
 // ---------------------------------------------------------------------------------------
-template <typename T, int D>
+template <typename T, int D, typename OUT>
 __global__ __launch_bounds__(256) void scores_kernel(const T *__restrict__ Kc, const T *__restrict__ Vc,
                                                       const T *__restrict__ q_last, int n, int N, int G,
                                                       const float *__restrict__ fin_m,
                                                       const float *__restrict__ fin_l,
-                                                      float *__restrict__ scores, int chunks,
+                                                      OUT *__restrict__ scores, int chunks,
                                                       const float *__restrict__ lu_mask, int lu_stride)
 {
     __shared__ float sM[kMaxGroup], sL[kMaxGroup];
@@ -123,7 +124,7 @@ __global__ __launch_bounds__(256) void scores_kernel(const T *__restrict__ Kc, c
     const int per = (N + chunks - 1) / chunks;
     const int lo = ch * per, hi = min(lo + per, N);
     for (int slot = lo + wave; slot < hi; slot += 4) {
-        float r = 0.f;
+        OUT r = sizeof(OUT) == 8 ? (OUT)INFINITY : (OUT)0;
         // lu_mask: explicit mask in force, NaN marks an invalid slot (score 0, as in Alg. 1)
         bool valid = slot < n;
         if (valid && lu_mask) {
@@ -133,24 +134,128 @@ __global__ __launch_bounds__(256) void scores_kernel(const T *__restrict__ Kc, c
         if (valid) {
             const double v = tail_exact_score<T, D>(Kc + ((size_t)u * N + slot) * D, Vc + ((size_t)u * N + slot) * D,
                                                q_last + (size_t)u * G * D, G, sM, sL, lane);
-            r = (float)v;
+            r = (OUT)v;
         }
         if (lane == 0) scores[(size_t)u * N + slot] = r;
     }
 }
 
-hipError_t launch_scores(const Plan &p, int n, float *scores, hipStream_t s)
+template <typename OUT> static hipError_t launch_scores_as(const Plan &p, int n, OUT *scores, hipStream_t s)
 {
     int chunks = (2048 + p.units - 1) / p.units;
     if (chunks < 1) chunks = 1;
     if (chunks > (p.N + 3) / 4) chunks = (p.N + 3) / 4;
 #define LF_SC(T, DD)                                                                            \
-    hipLaunchKernelGGL((scores_kernel<T, DD>), dim3(p.units * chunks), dim3(256), 0, s,         \
+    hipLaunchKernelGGL((scores_kernel<T, DD, OUT>), dim3(p.units * chunks), dim3(256), 0, s,    \
                        (const T *)p.k_cache, (const T *)p.v_cache, (const T *)p.q_last, n, p.N, \
                        p.G, p.fin_m, p.fin_l, scores, chunks, p.masked ? p.lu : nullptr, p.ntiles * kTile)
     if (p.dtype == 0) { if (p.D == 64) LF_SC(float, 64); else LF_SC(float, 128); }
     else              { if (p.D == 64) LF_SC(bf16_t, 64); else LF_SC(bf16_t, 128); }
 #undef LF_SC
+    return hipGetLastError();
+}
+
+hipError_t launch_scores(const Plan &p, int n, float *scores, hipStream_t s) { return launch_scores_as(p, n, scores, s); }
+
+// ---------------------------------------------------------------------------------------
+// Batch eviction (the every-k-steps regime, Sec. 4.4): one workgroup per unit picks the k
+// lowest double-precision scores in ascending (score, slot) order -- round j takes the
+// smallest pair above round j-1's, so nothing is written between rounds -- then turns those
+// slots, and any not yet filled, into holes of the explicit mask.
+// ---------------------------------------------------------------------------------------
+template <typename T, int D>
+__global__ __launch_bounds__(256) void evict_lowest_kernel(T *__restrict__ Kc, T *__restrict__ Vc,
+                                                            const double *__restrict__ sc, float *__restrict__ lu,
+                                                            int32_t *__restrict__ pending, int32_t *__restrict__ evicted,
+                                                            int n, int N, int k, int lu_stride, int init_lu)
+{
+    __shared__ double red_v[4];
+    __shared__ int red_i[4];
+    __shared__ double last_v;
+    __shared__ int last_i;
+    const int u = blockIdx.x, tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const double *su = sc + (size_t)u * N;
+    float *lu_u = lu + (size_t)u * lu_stride;
+    if (tid == 0) { last_v = -INFINITY; last_i = -1; }
+    // a cache whose kernels never kept the side array (vector-ALU path, prefix mode so far)
+    // gets "valid" entries for its filled prefix before the holes are marked
+    if (init_lu)
+        for (int slot = tid; slot < n; slot += 256) lu_u[(slot & ~15) + tail_pos_of_slot(slot & 15)] = 0.f;
+    __syncthreads();
+    for (int j = 0; j < k; ++j) {
+        const double lv = last_v;
+        const int li = last_i;
+        double bv = INFINITY;
+        int bi = 0x7fffffff;
+        for (int i = tid; i < N; i += 256) {
+            const double v = su[i]; // +inf marks an invalid slot
+            const bool after = v > lv || (v == lv && i > li);
+            if (after && v < INFINITY && (v < bv || (v == bv && i < bi))) { bv = v; bi = i; }
+        }
+#pragma unroll
+        for (int off = 32; off > 0; off >>= 1) {
+            const double ov = __shfl_xor(bv, off);
+            const int oi = __shfl_xor(bi, off);
+            if (ov < bv || (ov == bv && oi < bi)) { bv = ov; bi = oi; }
+        }
+        if (lane == 0) { red_v[wave] = bv; red_i[wave] = bi; }
+        __syncthreads();
+        if (tid == 0) {
+            for (int w = 1; w < 4; ++w)
+                if (red_v[w] < bv || (red_v[w] == bv && red_i[w] < bi)) { bv = red_v[w]; bi = red_i[w]; }
+            const bool found = bi != 0x7fffffff;
+            if (evicted) evicted[(size_t)u * k + j] = found ? bi : -1;
+            last_v = found ? bv : INFINITY; // nothing valid is left: later rounds find nothing either
+            last_i = found ? bi : 0x7fffffff;
+        }
+        __syncthreads();
+        const int victim = last_i;
+        if (victim != 0x7fffffff) { // uniform: the slot becomes a hole with finite (zero) rows
+            for (int d = tid; d < D; d += 256) {
+                store_elem(Kc + ((size_t)u * N + victim) * D + d, 0.f);
+                store_elem(Vc + ((size_t)u * N + victim) * D + d, 0.f);
+            }
+            if (tid == 0) lu_u[(victim & ~15) + tail_pos_of_slot(victim & 15)] = __builtin_nanf("");
+        }
+    }
+    // slots past a filling cache's prefix become holes of the mask as well
+    for (int slot = n + wave; slot < N; slot += 4) {
+        for (int d = lane; d < D; d += 64) {
+            store_elem(Kc + ((size_t)u * N + slot) * D + d, 0.f);
+            store_elem(Vc + ((size_t)u * N + slot) * D + d, 0.f);
+        }
+        if (lane == 0) lu_u[(slot & ~15) + tail_pos_of_slot(slot & 15)] = __builtin_nanf("");
+    }
+    __threadfence_block();
+    __syncthreads();
+    // the next token goes to the lowest hole
+    int best = 0x7fffffff;
+    for (int p = tid; p < lu_stride; p += 256) {
+        const float x = lu_u[p];
+        const int slot = (p & ~15) + tail_slot_of_pos(p & 15);
+        if (x != x && slot < N) best = min(best, slot);
+    }
+#pragma unroll
+    for (int off = 32; off > 0; off >>= 1) best = min(best, __shfl_xor(best, off));
+    if (lane == 0) red_i[wave] = best;
+    __syncthreads();
+    if (tid == 0) {
+        best = min(min(red_i[0], red_i[1]), min(red_i[2], red_i[3]));
+        if (best != 0x7fffffff) pending[u] = best;
+    }
+}
+
+hipError_t launch_evict_lowest(const Plan &p, int n, int k, double *scratch, int32_t *evicted, hipStream_t s)
+{
+    hipError_t e = launch_scores_as(p, n, scratch, s);
+    if (e != hipSuccess) return e;
+#define LF_EV(T, DD)                                                                             \
+    hipLaunchKernelGGL((evict_lowest_kernel<T, DD>), dim3(p.units), dim3(256), 0, s, (T *)p.k_cache, \
+                       (T *)p.v_cache, scratch, p.lu, p.pending, evicted, n, p.N, k, p.ntiles * kTile,     \
+                       (!p.masked && !p.use_mfma) ? 1 : 0)
+    if (p.dtype == 0) { if (p.D == 64) LF_EV(float, 64); else LF_EV(float, 128); }
+    else              { if (p.D == 64) LF_EV(bf16_t, 64); else LF_EV(bf16_t, 128); }
+#undef LF_EV
     return hipGetLastError();
 }
 

@@ -81,6 +81,9 @@ void unit_mfma_table_entry(const Plan &p, void *dst);
 hipError_t launch_unit_mfma_group(const Plan &p, const StepIo &io, int n, const void *table, int n_caches,
                                   hipStream_t s);
 hipError_t launch_scores(const Plan &p, int n, float *scores, hipStream_t s);
+// Drop the k lowest-scoring valid slots of every unit (scores of the last step, in double
+// precision via `scratch`, device double [units][N]); they become holes of the explicit mask.
+hipError_t launch_evict_lowest(const Plan &p, int n, int k, double *scratch, int32_t *evicted, hipStream_t s);
 hipError_t launch_l1norms(const Plan &p, int n_rows, hipStream_t s);
 hipError_t launch_fill_i32(int32_t *dst, int count, int32_t value, hipStream_t s);
 // Explicit mask (device uint8 [units][N], nonzero = valid): rewrites the side array, zeroes

@@ -447,6 +447,32 @@ int longflow_set_mask(longflow_cache_t *cache, const uint8_t *mask, void *hip_st
     return LF_OK;
 }
 
+size_t longflow_evict_scratch_bytes(const lf_config *cfg)
+{
+    if (validate(cfg) != LF_OK) return 0;
+    return align_up(sizeof(double) * (size_t)cfg->batch * cfg->kv_heads * cfg->budget, 256);
+}
+
+int longflow_evict_lowest(longflow_cache_t *cache, int32_t k, void *scratch, size_t scratch_bytes,
+                          int32_t *evicted, void *hip_stream)
+{
+    longflow_cache *c = checked(cache);
+    if (!c) return fail(LF_ERR_STATE, "invalid or destroyed cache handle");
+    const Plan &p = c->plan;
+    if (p.flags & LF_FLAG_ATTENTION_ONLY) return fail(LF_ERR_UNSUPPORTED, "an attention-only cache evicts nothing");
+    if (!c->stepped) return fail(LF_ERR_STATE, "no decode step has run yet: there are no scores");
+    if (k < 1 || k >= p.N) return fail(LF_ERR_INVALID_ARG, "k = %d outside [1, %d)", k, p.N);
+    const size_t need = sizeof(double) * (size_t)p.units * p.N;
+    if (!scratch || ((uintptr_t)scratch & 7u)) return fail(LF_ERR_INVALID_ARG, "scratch is NULL or misaligned");
+    if (scratch_bytes < need) return fail(LF_ERR_WORKSPACE, "scratch has %zu bytes, %zu needed", scratch_bytes, need);
+    hipError_t e = launch_evict_lowest(p, c->count, k, (double *)scratch, evicted, (hipStream_t)hip_stream);
+    if (e != hipSuccess) return fail(LF_ERR_HIP, "batch eviction launch: %s", hipGetErrorString(e));
+    c->plan.masked = true;
+    c->count = p.N;
+    c->has_pending = true; // every unit now has a hole, and its lowest one is pending
+    return LF_OK;
+}
+
 static void drop_events(longflow_cache *c)
 {
     for (hipEvent_t e : c->prof_events) (void)hipEventDestroy(e);

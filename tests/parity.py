@@ -48,7 +48,8 @@ def compare_indices(gpu_idx, ora_idx, ora_scores, full, rep, where=""):
 
 
 def run_lockstep(wl: W.Workload, steps=None, flags=0, check_scores_every=0, units=None,
-                 device="cuda", layer=0, host_inputs=True, gpu_cache=None, report=None, mask=None):
+                 device="cuda", layer=0, host_inputs=True, gpu_cache=None, report=None, mask=None,
+                 oracle_cache=None, t0=0):
     """Advance GPU cache and oracle together for `steps` decode steps, comparing each.
 
     units: optional list of flat (batch*kv_head) unit indices the oracle follows (the GPU
@@ -56,6 +57,8 @@ def run_lockstep(wl: W.Workload, steps=None, flags=0, check_scores_every=0, unit
     mask: optional bool array [B, Hkv, N], the explicit validity mask both sides are given
     after the prefill (a cache prefilled to N rows first gets slot 0 as pending slot, which
     units without an invalid slot then keep).
+    oracle_cache, t0: continue an earlier run (its gpu_cache and oracle, both already
+    prefilled) with the inputs of steps t0, t0 + 1, ...
     """
     rep = report or ParityReport()
     steps = wl.steps if steps is None else steps
@@ -64,6 +67,9 @@ def run_lockstep(wl: W.Workload, steps=None, flags=0, check_scores_every=0, unit
     all_units = np.arange(wl.units) if units is None else np.asarray(units)
     nu = len(all_units)
 
+    if oracle_cache is not None:
+        return _advance(wl, gpu_cache, oracle_cache, rep, t0, steps, all_units, device, layer, host_inputs,
+                        check_scores_every)
     # ---- prefill: same bits on both sides
     if host_inputs:
         k0, v0 = W.host_prefill(wl, layer)
@@ -90,8 +96,14 @@ def run_lockstep(wl: W.Workload, steps=None, flags=0, check_scores_every=0, unit
         gpu.set_mask(torch.as_tensor(mask.reshape(wl.batch, wl.kv_heads, N)))
         ora.set_mask(mask[all_units].reshape(nu, 1, N))
 
+    return _advance(wl, gpu, ora, rep, t0, steps, all_units, device, layer, host_inputs, check_scores_every)
+
+
+def _advance(wl, gpu, ora, rep, t0, steps, all_units, device, layer, host_inputs, check_scores_every):
+    G, D, N = wl.group, wl.head_dim, wl.budget
+    nu = len(all_units)
     tol = OUT_TOL[wl.dtype]
-    for t in range(steps):
+    for t in range(t0, t0 + steps):
         if host_inputs:
             q, k, v = (W.to_torch(x, wl, device) for x in W.host_step(wl, t, layer))
         else:
@@ -109,18 +121,17 @@ def run_lockstep(wl: W.Workload, steps=None, flags=0, check_scores_every=0, unit
         rep.max_out_err = max(rep.max_out_err, err)
         assert err <= tol, f"step {t}: max |out - oracle| = {err:.3e} > {tol}"
         i_gpu = idx_t.reshape(-1)[sel].cpu().numpy()
-        # with an explicit mask the index is a hole (exact) until the holes are used up
-        full = (ora.count == N) if mask is None else ora.mask().reshape(nu, N).all(-1)
+        # per unit: while it has a free slot the index is that slot, exactly
+        full = ora.mask().reshape(nu, N).all(-1)
         if compare_indices(i_gpu, i_ref, ora.scores(), full, rep, where=f"{wl.name} step {t}"):
             ora.set_pending(i_gpu.reshape(nu, 1))
         assert gpu.valid_count == ora.count
-        if check_scores_every and (t % check_scores_every == 0 or t == steps - 1):
+        if check_scores_every and (t % check_scores_every == 0 or t == t0 + steps - 1):
             s_gpu = gpu.scores().reshape(wl.units, N)[sel].cpu().numpy().astype(np.float64)
             s_ref = ora.scores().reshape(nu, N)
             n = ora.count
             assert (s_gpu[:, n:] == 0).all()
-            if mask is not None:
-                assert (s_gpu[ora.mask().reshape(nu, N) == 0] == 0).all()     # invalid slots score 0
+            assert (s_gpu[ora.mask().reshape(nu, N) == 0] == 0).all()     # invalid slots score 0
             rel = np.abs(s_gpu[:, :n] - s_ref[:, :n]) / np.maximum(s_ref[:, :n], 1e-30)
             # fp32 result: 1e-5 relative, except where the score itself is below fp32 range
             ok = (rel <= 1e-5) | (s_ref[:, :n] < 1e-35)

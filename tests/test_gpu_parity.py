@@ -568,3 +568,54 @@ def test_mask_can_be_set_again_mid_run_and_needs_a_compressing_cache():
         att.set_mask(torch.ones(2, 2, 64))
     assert e.value.status == lf.LF_ERR_UNSUPPORTED
     att.close()
+
+
+# ------------------------------------------------------------------ batch eviction of the k lowest scores
+
+@pytest.mark.parametrize("name,dtype,B,Hq,Hkv,D,N,n_init,flags,k", [
+    ("single", "bf16", 48, 16, 4, 128, 300, 299, 0, 17),
+    ("coop", "bf16", 2, 28, 4, 128, 2048, 2047, 0, 128),
+    ("filling", "bf16", 2, 8, 2, 128, 600, 200, 0, 50),             # prefix not yet full: the rest turns into holes too
+    ("split", "bf16", 3, 8, 2, 128, 700, 699, lf.LF_FLAG_FORCE_SPLIT, 33),
+    ("fp32", "f32", 2, 8, 2, 64, 200, 150, 0, 60),                  # vector-ALU path, side array first used here
+])
+def test_batch_eviction_of_the_k_lowest_scores(name, dtype, B, Hq, Hkv, D, N, n_init, flags, k):
+    wl = _small("evict-" + name, dtype, B, Hq, Hkv, D, N, n_init=n_init, steps=1, sink_scale=4.0, seed=130)
+    units = None if wl.units <= 24 else list(range(0, wl.units, wl.units // 12))
+    rep, gpu, ora = run_lockstep(wl, steps=5, flags=flags, units=units)
+    sel = np.arange(wl.units) if units is None else np.asarray(units)
+    sc = ora.scores().reshape(len(sel), N)                         # scores of the last step, float64
+    valid = ora.mask().reshape(len(sel), N).astype(bool)
+    pend = ora.pending().reshape(-1)
+    ev_gpu = gpu.evict_lowest(k).cpu().numpy().reshape(wl.units, k)[sel]
+    ev_ref = ora.evict_lowest(k).reshape(len(sel), k)
+    steer = ora.mask().reshape(len(sel), N).astype(bool)
+    for u in range(len(sel)):
+        g = ev_gpu[u]
+        assert len(set(g.tolist())) == k and valid[u, g].all()     # k distinct valid slots
+        if valid[u].all():
+            assert g[0] == pend[u]                                 # the slot the last step chose goes first
+        s_g = sc[u, g]
+        assert (np.diff(s_g) >= -1e-6 * np.abs(s_g[1:])).all()      # ascending score, up to near-ties
+        if set(g.tolist()) != set(ev_ref[u].tolist()):             # differing sets: only across a near-tie
+            kth = np.sort(sc[u, valid[u]])[k - 1]
+            odd = np.array(sorted(set(g.tolist()) ^ set(ev_ref[u].tolist())))
+            assert (np.abs(sc[u, odd] - kth) <= 1e-6 * kth).all(), f"unit {u}: {odd} are no near-ties of the k-th score"
+            rep.near_ties += 1
+            steer[u] = valid[u]
+            steer[u, g] = False
+    ora.set_mask(steer.reshape(len(sel), 1, N))                     # same holes on both sides from here on
+    holes = int((~steer).sum(-1).max())
+    rep, gpu, ora = run_lockstep(wl, steps=holes + 8, gpu_cache=gpu, oracle_cache=ora, t0=5, units=units, report=rep,
+                                 check_scores_every=holes // 2)
+    assert ora.mask().all()
+    # argument checks
+    with pytest.raises(lf.LongFlowError) as e:
+        gpu.evict_lowest(N)
+    assert e.value.status == lf.LF_ERR_INVALID_ARG
+    fresh = lf.LongFlowCache(1, 2, 1, 128, 64)
+    with pytest.raises(lf.LongFlowError) as e:
+        fresh.evict_lowest(3)
+    assert e.value.status == lf.LF_ERR_STATE
+    fresh.close()
+    gpu.close()
