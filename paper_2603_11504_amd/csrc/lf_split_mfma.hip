@@ -38,16 +38,19 @@ __global__ __launch_bounds__(256, 2) void split_mfma_kernel(const SplitTailArgs<
 
     // ---- merge the 4 waves through LDS, write the split's partial state
     __shared__ float sm_m[4][16], sm_l[4][16];
-    __shared__ float sm_o[4][16][D + 4];
+    __shared__ __align__(16) float sm_o[4][16][D + 4];
     const int g = lane >> 4, r = lane & 15;
     float l = st.l;
     l += __shfl_xor(l, 16);
     l += __shfl_xor(l, 32);
     if (g == 0) { sm_m[wave][r] = st.m; sm_l[wave][r] = l; }
+    // a lane holds channels 8r .. 8r+7 of heads 4g .. 4g+3: two 16-byte stores per head
 #pragma unroll
-    for (int dd = 0; dd < 8; ++dd)
-#pragma unroll
-        for (int v = 0; v < 4; ++v) sm_o[wave][4 * g + v][8 * r + dd] = st.oacc[dd][v];
+    for (int v = 0; v < 4; ++v) {
+        float *row = &sm_o[wave][4 * g + v][8 * r];
+        *(f32x4 *)row = f32x4{st.oacc[0][v], st.oacc[1][v], st.oacc[2][v], st.oacc[3][v]};
+        *(f32x4 *)(row + 4) = f32x4{st.oacc[4][v], st.oacc[5][v], st.oacc[6][v], st.oacc[7][v]};
+    }
     __syncthreads();
     const size_t pbase = ((size_t)u * C + c) * G;
     for (int idx = tid; idx < G * D; idx += 256) {

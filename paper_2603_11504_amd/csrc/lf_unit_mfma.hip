@@ -251,6 +251,14 @@ __global__ __launch_bounds__(512, 1) void unit_mfma_kernel(const UnitArgs a_in, 
         }
     }
 
+    // Copies of the query -- LDS for the exact re-scoring, device memory for a later
+    // longflow_scores() -- are made now: their load latency hides behind the streaming
+    // instead of standing in the serial tail of the kernel.
+    if (STASH == kStashLds)
+        for (int i = tid; i < G * D; i += 512) qs[i / D][i % D] = qu[i];
+    if (sp == 0)
+        for (int i = tid; i < G * D; i += 512) a.q_last[(size_t)u * G * D + i] = qu[i];
+
     MfmaStreamer<NW, HILO, STASH, MASKED> st;
     st.init(qu, G, lane, a.scale_log2);
     st.Ku = Ku;
@@ -270,10 +278,7 @@ __global__ __launch_bounds__(512, 1) void unit_mfma_kernel(const UnitArgs a_in, 
         l += __shfl_xor(l, 32);
         if (g == 0) { sm_m[wave][r] = st.m; sm_l[wave][r] = l; }
     }
-    if (STASH == kStashLds) {
-        for (int i = tid; i < G * D; i += 512) qs[i / D][i % D] = qu[i];
-        if (tid == 0) cand_count = 0;
-    }
+    if (STASH == kStashLds && tid == 0) cand_count = 0;
     __syncthreads();
     if (tid < 16) {
         float M = -INFINITY;
@@ -292,11 +297,14 @@ __global__ __launch_bounds__(512, 1) void unit_mfma_kernel(const UnitArgs a_in, 
         float a4[4];
 #pragma unroll
         for (int v = 0; v < 4; ++v) a4[v] = merge_weight(sm_m[wave][4 * g + v], sM[4 * g + v]);
+        // a lane holds channels 8r .. 8r+7 of heads 4g .. 4g+3: two 16-byte stores per head
+        // (single floats at this stride would pile 64 lanes onto a handful of LDS banks)
 #pragma unroll
-        for (int dd = 0; dd < 8; ++dd)
-#pragma unroll
-            for (int v = 0; v < 4; ++v)
-                sm_o[((size_t)wave * 16 + 4 * g + v) * OPAD + 8 * r + dd] = st.oacc[dd][v] * a4[v];
+        for (int v = 0; v < 4; ++v) {
+            float *row = sm_o + ((size_t)wave * 16 + 4 * g + v) * OPAD + 8 * r;
+            *(f32x4 *)row = f32x4{st.oacc[0][v] * a4[v], st.oacc[1][v] * a4[v], st.oacc[2][v] * a4[v], st.oacc[3][v] * a4[v]};
+            *(f32x4 *)(row + 4) = f32x4{st.oacc[4][v] * a4[v], st.oacc[5][v] * a4[v], st.oacc[6][v] * a4[v], st.oacc[7][v] * a4[v]};
+        }
     };
 
     bool dumps_ok = true;
@@ -414,15 +422,34 @@ __global__ __launch_bounds__(512, 1) void unit_mfma_kernel(const UnitArgs a_in, 
 #pragma unroll
                 for (int e = 0; e < 4; ++e) ub4[e] = lb4[e] = 0.f;
                 if (!COOP) { // everything is in this workgroup's LDS
+                    // Common case first: no code of the item sits at a clamp (0x00 or 0xff),
+                    // so upper and lower bound share one sum.  The byte tests are the usual
+                    // word-at-a-time ones; a hit anywhere sends the item through the exact
+                    // two-sided sums below.
+                    uint32_t clamped = 0u;
                     for (int h = 0; h < G; ++h) {
                         const uint32_t c4 = *(const uint32_t *)(ls_code + (size_t)h * a.code_stride + 4 * item);
                         const float f = ls_ref[tile * G + h];
+                        clamped |= ((c4 - 0x01010101u) & ~c4) | ((~c4 - 0x01010101u) & c4);
 #pragma unroll
-                        for (int e = 0; e < 4; ++e) {
-                            const uint32_t c = (c4 >> (8 * e)) & 255u;
-                            const float d = fast_exp2(-0.25f * (float)c) * f;
-                            ub4[e] += (c == 0u) ? INFINITY : d;
-                            lb4[e] += (c == 255u) ? 0.f : d;
+                        for (int e = 0; e < 4; ++e)
+                            ub4[e] = fmaf(fast_exp2(-0.25f * (float)((c4 >> (8 * e)) & 255u)), f, ub4[e]);
+                    }
+#pragma unroll
+                    for (int e = 0; e < 4; ++e) lb4[e] = ub4[e];
+                    if (clamped & 0x80808080u) {
+#pragma unroll
+                        for (int e = 0; e < 4; ++e) ub4[e] = lb4[e] = 0.f;
+                        for (int h = 0; h < G; ++h) {
+                            const uint32_t c4 = *(const uint32_t *)(ls_code + (size_t)h * a.code_stride + 4 * item);
+                            const float f = ls_ref[tile * G + h];
+#pragma unroll
+                            for (int e = 0; e < 4; ++e) {
+                                const uint32_t c = (c4 >> (8 * e)) & 255u;
+                                const float d = fast_exp2(-0.25f * (float)c) * f;
+                                ub4[e] += (c == 0u) ? INFINITY : d;
+                                lb4[e] += (c == 255u) ? 0.f : d;
+                            }
                         }
                     }
                 }
@@ -563,7 +590,7 @@ __global__ __launch_bounds__(512, 1) void unit_mfma_kernel(const UnitArgs a_in, 
         __syncthreads(); // the codes are dead from here on: their LDS may be reused below
     }
 
-    // ---- output: normalise, round to bf16, keep a copy of q for longflow_scores()
+    // ---- output: normalise, round to bf16
     if (!COOP || s_active == 1) {
         stage_o();
         __syncthreads();
@@ -573,7 +600,6 @@ __global__ __launch_bounds__(512, 1) void unit_mfma_kernel(const UnitArgs a_in, 
 #pragma unroll
             for (int w = 0; w < NW; ++w) acc += sm_o[((size_t)w * 16 + h) * OPAD + d];
             a.out[((size_t)u * G + h) * D + d] = (uint16_t)f32_to_bf16_bits(acc / sL[h]);
-            a.q_last[((size_t)u * G + h) * D + d] = qu[idx];
         }
     } else {
         for (int idx = tid; idx < G * D; idx += 512) {
@@ -586,7 +612,6 @@ __global__ __launch_bounds__(512, 1) void unit_mfma_kernel(const UnitArgs a_in, 
 #pragma unroll
             for (int s2 = 0; s2 < 8; ++s2) acc += (s2 < s_active) ? sW[s2][h] * po[s2] : 0.f;
             a.out[((size_t)u * G + h) * D + d] = (uint16_t)f32_to_bf16_bits(acc / sL[h]);
-            a.q_last[((size_t)u * G + h) * D + d] = qu[idx];
         }
         if (tid == 0) { st_agent(&a.arrive[u], 0); st_agent(&a.dumped[u], 0); } // ready for the next step
     }
