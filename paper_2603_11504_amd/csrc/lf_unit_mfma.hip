@@ -217,6 +217,7 @@ __global__ __launch_bounds__(512, 1) void unit_mfma_kernel(const UnitArgs a_in, 
     __shared__ int cand_list[kMaxCand];
     __shared__ int cand_count, s_flag;
     __shared__ int red_i[NW + 1];
+    __shared__ float exp_tab[256]; // 2^(-c/4) of every code value (screening pass)
 
     const int n = a.n, N = a.N, G = a.G, s_active = COOP ? a.s_active : 1;
     const int u = blk / s_active, sp = blk % s_active;
@@ -254,8 +255,10 @@ __global__ __launch_bounds__(512, 1) void unit_mfma_kernel(const UnitArgs a_in, 
     // Copies of the query -- LDS for the exact re-scoring, device memory for a later
     // longflow_scores() -- are made now: their load latency hides behind the streaming
     // instead of standing in the serial tail of the kernel.
-    if (STASH == kStashLds)
+    if (STASH == kStashLds) {
         for (int i = tid; i < G * D; i += 512) qs[i / D][i % D] = qu[i];
+        if (tid < 256) exp_tab[tid] = fast_exp2(-0.25f * (float)tid);
+    }
     if (sp == 0)
         for (int i = tid; i < G * D; i += 512) a.q_last[(size_t)u * G * D + i] = qu[i];
 
@@ -433,7 +436,7 @@ __global__ __launch_bounds__(512, 1) void unit_mfma_kernel(const UnitArgs a_in, 
                         clamped |= ((c4 - 0x01010101u) & ~c4) | ((~c4 - 0x01010101u) & c4);
 #pragma unroll
                         for (int e = 0; e < 4; ++e)
-                            ub4[e] = fmaf(fast_exp2(-0.25f * (float)((c4 >> (8 * e)) & 255u)), f, ub4[e]);
+                            ub4[e] = fmaf(exp_tab[(c4 >> (8 * e)) & 255u], f, ub4[e]);
                     }
 #pragma unroll
                     for (int e = 0; e < 4; ++e) lb4[e] = ub4[e];
