@@ -145,6 +145,11 @@ LF_API int longflow_set_pending(longflow_cache_t *cache, const int32_t *slots, v
  */
 LF_API int longflow_set_mask(longflow_cache_t *cache, const uint8_t *mask, void *hip_stream);
 
+/* Which slots hold a token right now: device uint8 [B][Hkv][N], 1 = valid.  Without an
+ * explicit mask that is the prefix [0, valid count).  Together with the K/V buffers and
+ * the last evict_idx this is the whole state of a cache (save / resume). */
+LF_API int longflow_get_mask(longflow_cache_t *cache, uint8_t *mask, void *hip_stream);
+
 /*
  * Batch eviction: the "compress every k steps" regime that Sec. 4.4 sets against the
  * method's own one-slot-per-step eviction, served from the same score (eq. 6).  Drops the

@@ -83,6 +83,30 @@ __global__ void mask_pending_kernel(const int32_t *first_hole, int32_t *pending,
     if (u < units && first_hole[u] < N) pending[u] = first_hole[u];
 }
 
+// validity of every slot as bytes: the prefix [0, n) without an explicit mask, else the
+// non-NaN entries of the side array
+__global__ void get_mask_kernel(const float *__restrict__ lu, uint8_t *__restrict__ mask, int units, int N, int n,
+                                int lu_stride, int masked)
+{
+    const long long i = (long long)blockIdx.x * blockDim.x + threadIdx.x;
+    if (i >= (long long)units * N) return;
+    const int u = (int)(i / N), slot = (int)(i % N);
+    bool valid = slot < n;
+    if (valid && masked) {
+        const float x = lu[(size_t)u * lu_stride + (slot & ~15) + tail_pos_of_slot(slot & 15)];
+        valid = x == x;
+    }
+    mask[i] = valid ? 1 : 0;
+}
+
+hipError_t launch_get_mask(const Plan &p, int n, uint8_t *mask, hipStream_t s)
+{
+    const long long total = (long long)p.units * p.N;
+    hipLaunchKernelGGL(get_mask_kernel, dim3((unsigned)((total + 255) / 256)), dim3(256), 0, s, p.lu, mask, p.units,
+                       p.N, n, p.ntiles * kTile, p.masked ? 1 : 0);
+    return hipGetLastError();
+}
+
 hipError_t launch_set_mask(const Plan &p, const uint8_t *mask, hipStream_t s)
 {
     hipError_t e = launch_fill_i32(p.first_hole, p.units, 0x7fffffff, s);

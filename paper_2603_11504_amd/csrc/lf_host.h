@@ -90,5 +90,6 @@ hipError_t launch_fill_i32(int32_t *dst, int count, int32_t value, hipStream_t s
 // the K/V rows of invalid slots and points `pending` of every unit that has an invalid
 // slot at its lowest one.
 hipError_t launch_set_mask(const Plan &p, const uint8_t *mask, hipStream_t s);
+hipError_t launch_get_mask(const Plan &p, int n, uint8_t *mask, hipStream_t s);
 
 } // namespace lf

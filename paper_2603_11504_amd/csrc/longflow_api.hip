@@ -447,6 +447,16 @@ int longflow_set_mask(longflow_cache_t *cache, const uint8_t *mask, void *hip_st
     return LF_OK;
 }
 
+int longflow_get_mask(longflow_cache_t *cache, uint8_t *mask, void *hip_stream)
+{
+    longflow_cache *c = checked(cache);
+    if (!c) return fail(LF_ERR_STATE, "invalid or destroyed cache handle");
+    if (!mask) return fail(LF_ERR_INVALID_ARG, "mask is NULL");
+    hipError_t e = launch_get_mask(c->plan, c->count, mask, (hipStream_t)hip_stream);
+    if (e != hipSuccess) return fail(LF_ERR_HIP, "mask read-back launch: %s", hipGetErrorString(e));
+    return LF_OK;
+}
+
 size_t longflow_evict_scratch_bytes(const lf_config *cfg)
 {
     if (validate(cfg) != LF_OK) return 0;

@@ -22,7 +22,7 @@ LF_FLAG_FORCE_SPLIT = 4
 LF_FLAG_FORCE_UNIT = 8
 
 EXPORTS = ("longflow_workspace_bytes", "longflow_init_cache", "longflow_decode_step",
-           "longflow_scores", "longflow_set_pending", "longflow_set_mask", "longflow_evict_scratch_bytes",
+           "longflow_scores", "longflow_set_pending", "longflow_set_mask", "longflow_get_mask", "longflow_evict_scratch_bytes",
            "longflow_evict_lowest", "longflow_valid_count",
            "longflow_destroy_cache", "longflow_last_error", "longflow_profile_begin",
            "longflow_profile_end", "longflow_plan_info", "longflow_group_workspace_bytes", "longflow_group_create",
@@ -75,6 +75,8 @@ def lib():
         L.longflow_set_pending.restype = ctypes.c_int
         L.longflow_set_mask.argtypes = [vp, vp, vp]
         L.longflow_set_mask.restype = ctypes.c_int
+        L.longflow_get_mask.argtypes = [vp, vp, vp]
+        L.longflow_get_mask.restype = ctypes.c_int
         L.longflow_evict_scratch_bytes.argtypes = [ctypes.POINTER(lf_config)]
         L.longflow_evict_scratch_bytes.restype = ctypes.c_size_t
         L.longflow_evict_lowest.argtypes = [vp, i32, vp, ctypes.c_size_t, vp, vp]
@@ -184,6 +186,12 @@ class LongFlowCache:
         assert tuple(mask.shape) == (self.cfg.batch, self.cfg.kv_heads, self.cfg.budget)
         _check(lib().longflow_set_mask(self._h, _ptr(mask), _stream()))
         self._keep_mask = mask  # alive until the kernels that read it have run
+
+    def mask(self):
+        """-> uint8 [B, Hkv, N], 1 where the slot holds a token."""
+        m = torch.empty((self.cfg.batch, self.cfg.kv_heads, self.cfg.budget), dtype=torch.uint8, device=self.device)
+        _check(lib().longflow_get_mask(self._h, _ptr(m), _stream()))
+        return m
 
     def evict_lowest(self, k):
         """Drop the k lowest-scoring valid slots per (batch, KV head) -> their slots [B, Hkv, k] int32."""

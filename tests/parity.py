@@ -132,6 +132,8 @@ def _advance(wl, gpu, ora, rep, t0, steps, all_units, device, layer, host_inputs
             n = ora.count
             assert (s_gpu[:, n:] == 0).all()
             assert (s_gpu[ora.mask().reshape(nu, N) == 0] == 0).all()     # invalid slots score 0
+            m_gpu = gpu.mask().reshape(wl.units, N)[sel].cpu().numpy() if hasattr(gpu, "mask") else None
+            assert m_gpu is None or (m_gpu == ora.mask().reshape(nu, N)).all(), f"step {t}: validity differs"
             rel = np.abs(s_gpu[:, :n] - s_ref[:, :n]) / np.maximum(s_ref[:, :n], 1e-30)
             # fp32 result: 1e-5 relative, except where the score itself is below fp32 range
             ok = (rel <= 1e-5) | (s_ref[:, :n] < 1e-35)
