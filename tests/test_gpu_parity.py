@@ -619,3 +619,38 @@ def test_batch_eviction_of_the_k_lowest_scores(name, dtype, B, Hq, Hkv, D, N, n_
     assert e.value.status == lf.LF_ERR_STATE
     fresh.close()
     gpu.close()
+
+
+# ------------------------------------------------------------------ save / resume
+
+@pytest.mark.parametrize("with_holes", [False, True], ids=["full", "holes"])
+def test_resume_from_saved_state_continues_bit_identically(with_holes):
+    # K/V buffers + validity + the last returned index are the whole state of a cache
+    wl = _small("resume", "bf16", 3, 16, 4, 128, 400, n_init=399, steps=1, seed=140)
+    k0, v0 = W.host_prefill(wl, 0)
+    a = lf.LongFlowCache(wl.batch, wl.q_heads, wl.kv_heads, wl.head_dim, wl.budget,
+                         k_init=W.to_torch(k0, wl, "cuda"), v_init=W.to_torch(v0, wl, "cuda"))
+    idx = None
+    for t in range(6):
+        q, k, v = (W.to_torch(x, wl, "cuda") for x in W.host_step(wl, t, 0))
+        _, idx = a.decode_step(q, k, v)
+    if with_holes:
+        a.evict_lowest(9)
+        for t in range(6, 9):                        # three of the nine holes refilled
+            q, k, v = (W.to_torch(x, wl, "cuda") for x in W.host_step(wl, t, 0))
+            _, idx = a.decode_step(q, k, v)
+    t0 = 9 if with_holes else 6
+    torch.cuda.synchronize()
+    b = lf.LongFlowCache(wl.batch, wl.q_heads, wl.kv_heads, wl.head_dim, wl.budget,
+                         k_init=a.k_cache.clone(), v_init=a.v_cache.clone())
+    b.set_pending(idx.clone())
+    if with_holes:
+        b.set_mask(a.mask())
+        assert int((a.mask() == 0).sum()) == 6 * wl.units
+    for t in range(t0, t0 + 20):
+        q, k, v = (W.to_torch(x, wl, "cuda") for x in W.host_step(wl, t, 0))
+        oa, ia = a.decode_step(q, k, v)
+        ob, ib = b.decode_step(q, k, v)
+        assert torch.equal(oa.view(torch.int16), ob.view(torch.int16)) and torch.equal(ia, ib), f"step {t}"
+    assert torch.equal(a.mask(), b.mask()) and bool(a.mask().all())
+    a.close(); b.close()
