@@ -64,7 +64,8 @@ inline SplitTailArgs<T> make_tail_args(const Plan &p, const StepIo &io, int n, i
     a.part_m = p.part_m; a.part_l = p.part_l; a.part_o = p.part_o;
     a.stash_w = p.stash_w; a.stash_m = p.stash_m;
     a.fin_m = p.fin_m; a.fin_l = p.fin_l;
-    a.lu = !(p.flags & 1u) ? p.lu : nullptr;
+    // the vector-ALU kernels need the side array only while an explicit mask is in force
+    a.lu = ((p.use_mfma || p.masked) && !(p.flags & 1u)) ? p.lu : nullptr;
     a.masked = p.masked ? 1 : 0;
     a.n = n; a.N = p.N; a.G = p.G; a.C = p.C; a.c_active = (n + p.L - 1) / p.L; a.ntiles = p.ntiles; a.L = p.L;
     a.attention_only = (p.flags & 1u) ? 1 : 0;
@@ -97,7 +98,8 @@ __device__ __forceinline__ int split_group_select(SplitTailArgs<T> &a, const Spl
         a.pending = t->pending; a.arrive = t->arrive;
         a.part_m = t->part_m; a.part_l = t->part_l; a.part_o = t->part_o;
         a.stash_w = t->stash_w; a.stash_m = t->stash_m;
-        a.fin_m = t->fin_m; a.fin_l = t->fin_l; a.lu = t->lu;
+        a.fin_m = t->fin_m; a.fin_l = t->fin_l;
+        a.lu = a.lu ? t->lu : nullptr; // whether it is used is this step's decision, not the table's
         a.q += ci * gr.q_stride;
         a.out += ci * gr.q_stride;
         if (a.k_new) a.k_new += ci * gr.kv_stride;

@@ -222,10 +222,12 @@ void split_table_entry(const Plan &p, void *dst)
     static_assert(sizeof(SplitTailArgs<float>) == sizeof(SplitTailArgs<bf16_t>), "one table layout for both element types");
     const StepIo none = {nullptr, nullptr, nullptr, nullptr, nullptr};
     if (p.dtype == 0) {
-        const SplitTailArgs<float> a = make_tail_args<float>(p, none, p.N);
+        SplitTailArgs<float> a = make_tail_args<float>(p, none, p.N);
+        a.lu = p.lu; // a mask may come into force after the table was written
         memcpy(dst, &a, sizeof(a));
     } else {
-        const SplitTailArgs<bf16_t> a = make_tail_args<bf16_t>(p, none, p.N);
+        SplitTailArgs<bf16_t> a = make_tail_args<bf16_t>(p, none, p.N);
+        a.lu = p.lu;
         memcpy(dst, &a, sizeof(a));
     }
 }
