@@ -459,6 +459,30 @@ def test_group_member_against_oracle(B, Hq, Hkv, N):
         c.close()
 
 
+def test_cfg3_grouped_full_size_sampled_units():
+    # the grouped launch at the benchmark's geometry: three full-size layer caches in one grid,
+    # one of them followed by the oracle on sampled units
+    wl = W.CONFIGS[3]
+    members = []
+    for layer in range(3):
+        k0, v0 = W.device_prefill(wl, "cuda", layer)
+        members.append(lf.LongFlowCache(wl.batch, wl.q_heads, wl.kv_heads, wl.head_dim, wl.budget, k_init=k0, v_init=v0))
+        del k0, v0
+    group = lf.LongFlowGroup(members)
+    rng = np.random.default_rng(wl.seed + 1)
+    units = np.sort(rng.choice(wl.units, size=48, replace=False))
+    # run_lockstep prefills its oracle from `layer`: follow that member
+    rep, _, _ = run_lockstep(wl, steps=3, host_inputs=False, units=units, layer=1,
+                             gpu_cache=_GroupMember(group, 1, wl, seed=6))
+    print(f"\ncfg3 grouped: decisions {rep.decisions} near-ties {rep.near_ties} max|dout| {rep.max_out_err:.2e}")
+    assert rep.steps == 3
+    group.close()
+    for c in members:
+        c.close()
+    del members, group
+    torch.cuda.empty_cache()
+
+
 def test_group_attention_only_and_errors():
     wl = _small("group-att", "bf16", 4, 16, 4, 128, 512, n_init=512, steps=2, seed=93)
     att = _make_caches(wl, 2, lf.LF_FLAG_ATTENTION_ONLY)
