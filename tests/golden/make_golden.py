@@ -35,6 +35,8 @@ def cfg0_evict_sequence():
 if __name__ == "__main__":
     seq = cfg0_evict_sequence()
     with open(os.path.join(HERE, "cfg0_evict_idx.txt"), "w") as f:
-        f.write("# oracle evict_idx per decode step, workload cfg0 (written by make_golden.py)\n")
+        f.write("# oracle evict_idx per decode step, workload cfg0 (written by make_golden.py): the slot\n"
+                "# count while the cache fills, then argmin of the LongFlowScore (eq. 6; Sec. 3.2 last\n"
+                "# paragraph; Alg. 1 post-processing). Not a value printed in the paper.\n")
         f.write("\n".join(str(i) for i in seq) + "\n")
     print("wrote", len(seq), "indices")
