@@ -34,6 +34,11 @@
  *     of the last error of the calling thread is in longflow_last_error().
  *   - Calls on one handle must be serialised by the caller; different handles
  *     are independent (one handle = one layer's cache).
+ *   - A decode step of a full cache is a fixed sequence of kernel launches with fixed
+ *     arguments (Sec. 3.4: static memory, consistent workload), so it may be captured
+ *     into a HIP graph and replayed.  The capture holds the valid-slot count and the
+ *     cache's mode: capture only once the cache is full, and again after
+ *     longflow_set_mask or longflow_evict_lowest.
  */
 #ifndef LONGFLOW_H
 #define LONGFLOW_H
