@@ -269,6 +269,49 @@ def test_decode_steps_replayed_from_a_hip_graph_match_eager(flags):
     assert torch.equal(eager.k_cache.view(torch.int16), graphed.k_cache.view(torch.int16))
 
 
+def test_grouped_masked_steps_replayed_from_a_hip_graph_match_eager():
+    # one captured launch serving three caches that carry an explicit mask with a few holes:
+    # the replays fill the holes and go on evicting exactly as the eager calls do
+    wl = _small("graph-group", "bf16", 2, 16, 4, 128, 768, n_init=768, steps=1, seed=72)
+    mask = _random_mask(wl, 3, 0.995)
+    sets = []
+    for _ in range(2):
+        caches = _make_caches(wl, 3)
+        for c in caches:
+            c.set_pending(torch.zeros((wl.batch, wl.kv_heads), dtype=torch.int32))
+            c.set_mask(torch.as_tensor(mask))
+        sets.append((caches, lf.LongFlowGroup(caches)))
+    (ce, ge), (cg, gg) = sets
+    qs, ks, vs = (torch.stack([W.to_torch(x, wl, "cuda")] * 3) for x in W.host_step(wl, 0))
+
+    def load(t):
+        for j in range(3):
+            for dst, src in zip((qs, ks, vs), W.host_step(wl, t, j)):
+                dst[j].copy_(W.to_torch(src, wl, "cuda"))
+
+    load(0)
+    ge.decode_step(qs, ks, vs)
+    gg.decode_step(qs, ks, vs)                            # kernels loaded before the capture
+    torch.cuda.synchronize()
+    g = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(g):
+        gg.decode_step(qs, ks, vs)
+    for t in range(1, 14):
+        load(t)
+        o_e, i_e = ge.decode_step(qs, ks, vs)
+        o_e, i_e = o_e.clone(), i_e.clone()
+        g.replay()
+        torch.cuda.synchronize()
+        assert torch.equal(o_e.view(torch.int16), gg.out.view(torch.int16)), f"replay {t}"
+        assert torch.equal(i_e, gg.evict_idx), f"replay {t}"
+        assert torch.randn(1 << 18, device="cuda").sum().item() is not None   # unrelated eager work between replays
+    for a_, b_ in zip(ce, cg):
+        assert torch.equal(a_.mask(), b_.mask()) and bool(a_.mask().all())
+    ge.close(); gg.close()
+    for c in ce + cg:
+        c.close()
+
+
 # ------------------------------------------------------------------ newest token as eviction candidate
 
 @pytest.mark.parametrize("flags,B", [(0, 1), (lf.LF_FLAG_FORCE_UNIT, 1), (lf.LF_FLAG_FORCE_SPLIT, 1), (0, 40)],
