@@ -204,7 +204,7 @@ __global__ __launch_bounds__(512, 1) void unit_mfma_kernel(const UnitArgs a_in, 
     constexpr int D = 128, NW = 8, OPAD = D + 4;
     extern __shared__ __align__(16) unsigned char smem[];
     // dynamic LDS: [codes G*code_stride][refs (split_len/16)*G floats]; the O-merge area
-    // [NW][16][OPAD] floats starts at merge_off (0 = aliases the codes, used after them)
+    // [NW][G][OPAD] floats starts at merge_off (0 = aliases the codes, used after them)
     uint8_t *ls_code = smem;
     float *ls_ref = (float *)(smem + (size_t)a.G * a.code_stride);
     float *sm_o = (float *)(smem + a.merge_off);
@@ -304,9 +304,11 @@ __global__ __launch_bounds__(512, 1) void unit_mfma_kernel(const UnitArgs a_in, 
         // (single floats at this stride would pile 64 lanes onto a handful of LDS banks)
 #pragma unroll
         for (int v = 0; v < 4; ++v) {
-            float *row = sm_o + ((size_t)wave * 16 + 4 * g + v) * OPAD + 8 * r;
-            *(f32x4 *)row = f32x4{st.oacc[0][v] * a4[v], st.oacc[1][v] * a4[v], st.oacc[2][v] * a4[v], st.oacc[3][v] * a4[v]};
-            *(f32x4 *)(row + 4) = f32x4{st.oacc[4][v] * a4[v], st.oacc[5][v] * a4[v], st.oacc[6][v] * a4[v], st.oacc[7][v] * a4[v]};
+            if (4 * g + v < G) { // rows of the G real heads only: the area is sized for them
+                float *row = sm_o + ((size_t)wave * G + 4 * g + v) * OPAD + 8 * r;
+                *(f32x4 *)row = f32x4{st.oacc[0][v] * a4[v], st.oacc[1][v] * a4[v], st.oacc[2][v] * a4[v], st.oacc[3][v] * a4[v]};
+                *(f32x4 *)(row + 4) = f32x4{st.oacc[4][v] * a4[v], st.oacc[5][v] * a4[v], st.oacc[6][v] * a4[v], st.oacc[7][v] * a4[v]};
+            }
         }
     };
 
@@ -320,7 +322,7 @@ __global__ __launch_bounds__(512, 1) void unit_mfma_kernel(const UnitArgs a_in, 
             const int h = idx / D, d = idx % D;
             float acc = 0.f;
 #pragma unroll
-            for (int w = 0; w < NW; ++w) acc += sm_o[((size_t)w * 16 + h) * OPAD + d];
+            for (int w = 0; w < NW; ++w) acc += sm_o[((size_t)w * G + h) * OPAD + d];
             st_agent(&a.part_o[(pb * G + h) * D + d], acc);
         }
         if (tid < 16) { st_agent(&a.part_m[pb * 16 + tid], sM[tid]); st_agent(&a.part_l[pb * 16 + tid], sL[tid]); }
@@ -601,7 +603,7 @@ __global__ __launch_bounds__(512, 1) void unit_mfma_kernel(const UnitArgs a_in, 
             const int h = idx / D, d = idx % D;
             float acc = 0.f;
 #pragma unroll
-            for (int w = 0; w < NW; ++w) acc += sm_o[((size_t)w * 16 + h) * OPAD + d];
+            for (int w = 0; w < NW; ++w) acc += sm_o[((size_t)w * G + h) * OPAD + d];
             a.out[((size_t)u * G + h) * D + d] = (uint16_t)f32_to_bf16_bits(acc / sL[h]);
         }
     } else {
@@ -623,7 +625,8 @@ __global__ __launch_bounds__(512, 1) void unit_mfma_kernel(const UnitArgs a_in, 
 // ---------------------------------------------------------------------------------------
 // host side
 // ---------------------------------------------------------------------------------------
-static const size_t kMergeBytes = (size_t)8 * 16 * (128 + 4) * sizeof(float);
+// O-merge area: one row of 128 (+4 padding) floats per wave and query head of the group
+static size_t merge_bytes(int G) { return (size_t)8 * G * (128 + 4) * sizeof(float); }
 
 static size_t code_bytes(int slots, int G)
 {
@@ -650,10 +653,11 @@ int unit_mfma_split_len(int N, int S)
 
 size_t unit_mfma_lds_bytes(int N, int G, bool stash, int S)
 {
-    if (!stash) return kMergeBytes;
+    const size_t merge = merge_bytes(G);
+    if (!stash) return merge;
     const size_t codes = code_bytes(unit_mfma_split_len(N, S), G);
-    if (S == 1) return codes > kMergeBytes ? codes : kMergeBytes; // merge area aliases the codes
-    return (codes + 255) / 256 * 256 + kMergeBytes;
+    if (S == 1) return codes > merge ? codes : merge; // merge area aliases the codes
+    return (codes + 255) / 256 * 256 + merge;
 }
 
 // everything of a step's kernel arguments that depends on the cache and the fill level only
@@ -675,7 +679,7 @@ static UnitArgs unit_args_of(const Plan &p, int n, int S)
     a.gstride = p.ntiles * kTile;
     const bool stash = !(p.flags & 1u);
     const size_t lds = unit_mfma_lds_bytes(p.N, p.G, stash, S);
-    a.merge_off = (stash && S > 1) ? (int)(lds - kMergeBytes) : 0;
+    a.merge_off = (stash && S > 1) ? (int)(lds - merge_bytes(p.G)) : 0;
     a.scale_log2 = 1.4426950408889634f / sqrtf(128.f);
     return a;
 }
