@@ -347,10 +347,22 @@ __global__ __launch_bounds__(512, 1) void unit_mfma_kernel(const UnitArgs a_in, 
             }
             return;
         }
-        // ---- last arriver: merge the S partials into the unit-wide softmax state.
-        // Device-scope loads are issued in batches (all first, then used): each one is a
-        // round trip to the coherence point, and an acquire fence instead (an L2 invalidate
-        // for the whole XCD) measured slower still.
+        // ---- last arriver: merge the S partials into the unit-wide softmax state and the
+        // output.  Device-scope loads are issued in batches (all first, then used): each one
+        // is a round trip to the coherence point, and an acquire fence instead (an L2
+        // invalidate for the whole XCD) measured slower still.  The partial outputs are
+        // fetched in the same batch as the softmax states, so the output costs no trip of
+        // its own; it is stored right away (it does not depend on the eviction).
+        constexpr int kOutPer = (kMaxGroup * D + 511) / 512;
+        float po[kOutPer][8];
+#pragma unroll
+        for (int k = 0; k < kOutPer; ++k) {
+            const int idx = tid + 512 * k;
+#pragma unroll
+            for (int s2 = 0; s2 < 8; ++s2)
+                po[k][s2] = (idx < G * D && s2 < s_active)
+                                ? ld_agent(&a.part_o[((size_t)u * a.S + s2) * G * D + idx]) : 0.f;
+        }
         if (tid < 16) {
             float pm[8], pl[8];
 #pragma unroll
@@ -386,6 +398,17 @@ __global__ __launch_bounds__(512, 1) void unit_mfma_kernel(const UnitArgs a_in, 
         }
         __syncthreads();
         if (evicting) dumps_ok = s_flag != 0;
+#pragma unroll
+        for (int k = 0; k < kOutPer; ++k) {
+            const int idx = tid + 512 * k;
+            if (idx < G * D) {
+                const int h = idx / D;
+                float acc = 0.f;
+#pragma unroll
+                for (int s2 = 0; s2 < 8; ++s2) acc += sW[s2][h] * po[k][s2];
+                a.out[(size_t)u * G * D + idx] = (uint16_t)f32_to_bf16_bits(acc / sL[h]);
+            }
+        }
     }
     if (tid < G) {
         a.fin_m[(size_t)u * G + tid] = sM[tid];
@@ -606,18 +629,7 @@ __global__ __launch_bounds__(512, 1) void unit_mfma_kernel(const UnitArgs a_in, 
             for (int w = 0; w < NW; ++w) acc += sm_o[((size_t)w * G + h) * OPAD + d];
             a.out[((size_t)u * G + h) * D + d] = (uint16_t)f32_to_bf16_bits(acc / sL[h]);
         }
-    } else {
-        for (int idx = tid; idx < G * D; idx += 512) {
-            const int h = idx / D, d = idx % D;
-            float po[8];
-#pragma unroll
-            for (int s2 = 0; s2 < 8; ++s2)
-                po[s2] = (s2 < s_active) ? ld_agent(&a.part_o[(((size_t)u * a.S + s2) * G + h) * D + d]) : 0.f;
-            float acc = 0.f;
-#pragma unroll
-            for (int s2 = 0; s2 < 8; ++s2) acc += (s2 < s_active) ? sW[s2][h] * po[s2] : 0.f;
-            a.out[((size_t)u * G + h) * D + d] = (uint16_t)f32_to_bf16_bits(acc / sL[h]);
-        }
+    } else { // the output was stored with the merge
         if (tid == 0) { st_agent(&a.arrive[u], 0); st_agent(&a.dumped[u], 0); } // ready for the next step
     }
 }
