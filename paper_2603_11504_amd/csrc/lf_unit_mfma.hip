@@ -49,6 +49,7 @@ struct UnitArgs {
     int S, s_active, split_len;        // split_len: slots per workgroup, a multiple of 128
     int code_stride, gstride;          // LDS / dump row strides in bytes
     int merge_off;                     // byte offset of the O-merge area in dynamic LDS
+    int gather;                        // the deciding workgroup copies the other workgroups' dumps into LDS
     float scale_log2;
 };
 
@@ -435,6 +436,54 @@ __global__ __launch_bounds__(512, 1) void unit_mfma_kernel(const UnitArgs a_in, 
                 const int h = i % G;
                 ls_ref[i] = fast_exp2(kCodeBias + ls_ref[i] - sM[h]) / sL[h];
             }
+            // The other workgroups' codes, when they fit, are first copied into the LDS that
+            // held the O-merge area (dead since the partials were published): positions below
+            // `start` keep their index, those from `own_hi` on move down by the own length.
+            // All loads of the copy are in flight together, so it costs about one trip to the
+            // coherence point; decoding straight from the dumps pays one per 512 items
+            // (measured with 8 workgroups per unit of 16384 slots: screening 67 -> 39 kcycles).
+            const int own_hi = min(start + a.split_len, a.gstride);
+            const int own_len = own_hi - start;
+            const int rstride = a.gstride - own_len;
+            uint8_t *rem_code = smem + a.merge_off;
+            float *rem_ref = (float *)(rem_code + (size_t)G * rstride);
+            const bool gathered = COOP && a.gather && dumps_ok && s_active > 1;
+            if (COOP && gathered) {
+                constexpr int kBatch = 16;
+                const int per_h = rstride / 8; // 8-byte words per head
+                const int nw = G * per_h;
+                for (int i0 = 0; i0 < nw; i0 += 512 * kBatch) {
+                    unsigned long long v[kBatch];
+#pragma unroll
+                    for (int k = 0; k < kBatch; ++k) {
+                        const int i = min(i0 + k * 512 + tid, nw - 1);
+                        const int h = i / per_h, rp = 8 * (i % per_h);
+                        const int pos = rp < start ? rp : rp + own_len;
+                        v[k] = ld_agent((const unsigned long long *)(a.gcode + ((size_t)u * G + h) * a.gstride + pos));
+                    }
+#pragma unroll
+                    for (int k = 0; k < kBatch; ++k) {
+                        const int i = i0 + k * 512 + tid;
+                        if (i < nw) *(unsigned long long *)(rem_code + (size_t)(i / per_h) * rstride + 8 * (i % per_h)) = v[k];
+                    }
+                }
+                const int nr = (rstride / kTile) * G;
+                for (int i0 = 0; i0 < nr; i0 += 512 * kBatch) {
+                    float v[kBatch];
+#pragma unroll
+                    for (int k = 0; k < kBatch; ++k) {
+                        const int i = min(i0 + k * 512 + tid, nr - 1);
+                        const int rt = i / G, h = i % G;
+                        const int tile = rt < start / kTile ? rt : rt + own_len / kTile;
+                        v[k] = ld_agent(&a.gref[((size_t)u * a.ntiles + tile) * G + h]);
+                    }
+#pragma unroll
+                    for (int k = 0; k < kBatch; ++k) {
+                        const int i = i0 + k * 512 + tid;
+                        if (i < nr) rem_ref[i] = fast_exp2(kCodeBias + v[k] - sM[i % G]) / sL[i % G];
+                    }
+                }
+            }
             __syncthreads();
             // Decode every (head, slot) code once.  A decoded term is within 2^(+-1/8) of the
             // true one; code 0 has no upper bound, code 255 no lower bound.  Each thread keeps
@@ -446,18 +495,35 @@ __global__ __launch_bounds__(512, 1) void unit_mfma_kernel(const UnitArgs a_in, 
             const int iters = (items + 511) / 512;
             auto decode_item = [&](int item, float *ub4, float *lb4) {
                 const int tile = item >> 2;
-                const bool mine = tile * kTile >= start && tile * kTile < start + a.split_len;
 #pragma unroll
                 for (int e = 0; e < 4; ++e) ub4[e] = lb4[e] = 0.f;
-                if (!COOP) { // everything is in this workgroup's LDS
+                // where the item's codes and factors live in LDS, if they do
+                const uint8_t *cp = ls_code + 4 * item;
+                const float *fp = ls_ref + tile * G;
+                int cstride = a.code_stride;
+                bool local = true;
+                if (COOP) {
+                    if (4 * item >= start && 4 * item < own_hi) {
+                        cp = ls_code + (4 * item - start);
+                        fp = ls_ref + (tile - start / kTile) * G;
+                    } else if (gathered) {
+                        const int rp = 4 * item < start ? 4 * item : 4 * item - own_len;
+                        cp = rem_code + rp;
+                        fp = rem_ref + (rp / kTile) * G;
+                        cstride = rstride;
+                    } else {
+                        local = false;
+                    }
+                }
+                if (local) {
                     // Common case first: no code of the item sits at a clamp (0x00 or 0xff),
                     // so upper and lower bound share one sum.  The byte tests are the usual
                     // word-at-a-time ones; a hit anywhere sends the item through the exact
                     // two-sided sums below.
                     uint32_t clamped = 0u;
                     for (int h = 0; h < G; ++h) {
-                        const uint32_t c4 = *(const uint32_t *)(ls_code + (size_t)h * a.code_stride + 4 * item);
-                        const float f = ls_ref[tile * G + h];
+                        const uint32_t c4 = *(const uint32_t *)(cp + (size_t)h * cstride);
+                        const float f = fp[h];
                         clamped |= ((c4 - 0x01010101u) & ~c4) | ((~c4 - 0x01010101u) & c4);
 #pragma unroll
                         for (int e = 0; e < 4; ++e)
@@ -469,8 +535,8 @@ __global__ __launch_bounds__(512, 1) void unit_mfma_kernel(const UnitArgs a_in, 
 #pragma unroll
                         for (int e = 0; e < 4; ++e) ub4[e] = lb4[e] = 0.f;
                         for (int h = 0; h < G; ++h) {
-                            const uint32_t c4 = *(const uint32_t *)(ls_code + (size_t)h * a.code_stride + 4 * item);
-                            const float f = ls_ref[tile * G + h];
+                            const uint32_t c4 = *(const uint32_t *)(cp + (size_t)h * cstride);
+                            const float f = fp[h];
 #pragma unroll
                             for (int e = 0; e < 4; ++e) {
                                 const uint32_t c = (c4 >> (8 * e)) & 255u;
@@ -480,18 +546,10 @@ __global__ __launch_bounds__(512, 1) void unit_mfma_kernel(const UnitArgs a_in, 
                             }
                         }
                     }
-                }
-                uint32_t c4s[kMaxGroup];
-                float fs[kMaxGroup];
-                if (!COOP) {
-                } else if (mine) {
-#pragma unroll
-                    for (int h = 0; h < kMaxGroup; ++h)
-                        if (h < G) {
-                            c4s[h] = *(const uint32_t *)(ls_code + (size_t)h * a.code_stride + (4 * item - start));
-                            fs[h] = ls_ref[(tile - start / kTile) * G + h];
-                        }
-                } else { // another workgroup's dump: batch the device-scope loads, then use them
+                } else if (COOP) {
+                    // another workgroup's dump, too large to copy: batch the device-scope
+                    // loads of this item, then use them
+                    uint32_t c4s[kMaxGroup];
                     float refs[kMaxGroup];
 #pragma unroll
                     for (int h = 0; h < kMaxGroup; ++h)
@@ -500,18 +558,16 @@ __global__ __launch_bounds__(512, 1) void unit_mfma_kernel(const UnitArgs a_in, 
                             refs[h] = ld_agent(&a.gref[((size_t)u * a.ntiles + tile) * G + h]);
                         }
 #pragma unroll
-                    for (int h = 0; h < kMaxGroup; ++h)
-                        if (h < G) fs[h] = fast_exp2(kCodeBias + refs[h] - sM[h]) / sL[h];
-                }
+                    for (int h = 0; h < kMaxGroup; ++h) {
+                        if (h < G) {
+                            const float f = fast_exp2(kCodeBias + refs[h] - sM[h]) / sL[h];
 #pragma unroll
-                for (int h = 0; h < kMaxGroup; ++h) {
-                    if (COOP && h < G) {
-#pragma unroll
-                        for (int e = 0; e < 4; ++e) {
-                            const uint32_t c = (c4s[h] >> (8 * e)) & 255u;
-                            const float d = fast_exp2(-0.25f * (float)c) * fs[h];
-                            ub4[e] += (c == 0u) ? INFINITY : d;
-                            lb4[e] += (c == 255u) ? 0.f : d;
+                            for (int e = 0; e < 4; ++e) {
+                                const uint32_t c = (c4s[h] >> (8 * e)) & 255u;
+                                const float d = fast_exp2(-0.25f * (float)c) * f;
+                                ub4[e] += (c == 0u) ? INFINITY : d;
+                                lb4[e] += (c == 255u) ? 0.f : d;
+                            }
                         }
                     }
                 }
@@ -692,6 +748,7 @@ static UnitArgs unit_args_of(const Plan &p, int n, int S)
     const bool stash = !(p.flags & 1u);
     const size_t lds = unit_mfma_lds_bytes(p.N, p.G, stash, S);
     a.merge_off = (stash && S > 1) ? (int)(lds - merge_bytes(p.G)) : 0;
+    a.gather = 0;
     a.scale_log2 = 1.4426950408889634f / sqrtf(128.f);
     return a;
 }
@@ -729,6 +786,19 @@ static hipError_t launch_unit(const Plan &p, const StepIo &io, int n, const void
     ga.kv_stride = (long long)p.units * 128;
     ga.ev_stride = p.units;
     size_t lds = unit_mfma_lds_bytes(p.N, p.G, stash, S);
+    if (stash && S > 1) {
+        // Room, behind the own codes, for every other workgroup's codes and references?  The
+        // workgroup with the shortest own range (the last one) needs the most.  Only worth
+        // it from three workgroups per unit on (with two there is one batch either way).
+        const int s_full = (p.N + a.split_len - 1) / a.split_len;
+        const size_t rem_len = (size_t)(s_full - 1) * a.split_len;
+        const size_t rem = (size_t)p.G * rem_len + rem_len / kTile * p.G * sizeof(float);
+        const size_t want = (size_t)a.merge_off + std::max(rem, merge_bytes(p.G));
+        if (s_full >= 3 && want <= kUnitLdsLimit) {
+            a.gather = 1;
+            lds = want;
+        }
+    }
     // With at most a few workgroups per compute unit, ask for more than half of the
     // CU's LDS so that no CU is handed two of them while another one idles.
     const long long wgs = (long long)ga.wgs_per_cache * n_caches;
