@@ -49,7 +49,8 @@ struct UnitArgs {
     int S, s_active, split_len;        // split_len: slots per workgroup, a multiple of 128
     int code_stride, gstride;          // LDS / dump row strides in bytes
     int merge_off;                     // byte offset of the O-merge area in dynamic LDS
-    int gather;                        // the deciding workgroup copies the other workgroups' dumps into LDS
+    int chunk_len;                     // positions of the other workgroups' dumps the deciding one copies into
+                                       // LDS at a time (multiple of 2048; 0: it reads them in place)
     float scale_log2;
 };
 
@@ -182,7 +183,9 @@ __device__ bool fill_lowest_hole(const float *lu_u, int npos, int N, int ins_slo
 }
 
 // COOP: several workgroups may share a unit (s_active can exceed 1)
-template <bool HILO, int STASH, bool COOP, bool GROUPED, bool MASKED>
+// GATHER (with COOP): the deciding workgroup copies the others' code dumps into LDS chunk by
+// chunk before screening them; without it, it reads them in place, item by item
+template <bool HILO, int STASH, bool COOP, bool GROUPED, bool MASKED, bool GATHER>
 __global__ __launch_bounds__(512, 1) void unit_mfma_kernel(const UnitArgs a_in, const GroupArgs ga)
 {
     UnitArgs a = a_in;
@@ -436,54 +439,61 @@ __global__ __launch_bounds__(512, 1) void unit_mfma_kernel(const UnitArgs a_in, 
                 const int h = i % G;
                 ls_ref[i] = fast_exp2(kCodeBias + ls_ref[i] - sM[h]) / sL[h];
             }
-            // The other workgroups' codes, when they fit, are first copied into the LDS that
-            // held the O-merge area (dead since the partials were published): positions below
-            // `start` keep their index, those from `own_hi` on move down by the own length.
-            // All loads of the copy are in flight together, so it costs about one trip to the
-            // coherence point; decoding straight from the dumps pays one per 512 items
-            // (measured with 8 workgroups per unit of 16384 slots: screening 67 -> 39 kcycles).
+            // The other workgroups' dumps are screened from LDS too: the deciding workgroup
+            // copies them, a chunk of positions at a time, into the LDS that held the O-merge
+            // area (dead since the partials were published), every load of a chunk in flight
+            // together -- about one trip to the coherence point per chunk, where decoding
+            // straight from the dumps pays one per 512 items (measured with 8 workgroups per
+            // unit of 16384 slots: screening 67 -> 39 kcycles).  A chunk is a multiple of 2048
+            // positions, so that a thread's items (512 apart) fall into chunks as wholes.
             const int own_hi = min(start + a.split_len, a.gstride);
-            const int own_len = own_hi - start;
-            const int rstride = a.gstride - own_len;
+            const int chunk_len = (COOP && GATHER && s_active > 1) ? a.chunk_len : 0;
             uint8_t *rem_code = smem + a.merge_off;
-            float *rem_ref = (float *)(rem_code + (size_t)G * rstride);
-            const bool gathered = COOP && a.gather && dumps_ok && s_active > 1;
-            if (COOP && gathered) {
+            float *rem_ref = (float *)(rem_code + (size_t)G * chunk_len);
+            int chunk_base = 0;
+            auto gather_chunk = [&](int cb) {
                 constexpr int kBatch = 16;
-                const int per_h = rstride / 8; // 8-byte words per head
+                // the own range inside the chunk, [lo, hi) relative to cb, is skipped: its codes
+                // are in LDS already and its dump is stale
+                const int lo = min(max(start - cb, 0), chunk_len), hi = min(max(own_hi - cb, 0), chunk_len);
+                const int skip = hi - lo;
+                const int top = a.gstride - 8; // last 8-byte word of a dump row
+                const int per_h = (chunk_len - skip) / 8;
                 const int nw = G * per_h;
                 for (int i0 = 0; i0 < nw; i0 += 512 * kBatch) {
                     unsigned long long v[kBatch];
+                    int off[kBatch];
 #pragma unroll
                     for (int k = 0; k < kBatch; ++k) {
                         const int i = min(i0 + k * 512 + tid, nw - 1);
-                        const int h = i / per_h, rp = 8 * (i % per_h);
-                        const int pos = rp < start ? rp : rp + own_len;
-                        v[k] = ld_agent((const unsigned long long *)(a.gcode + ((size_t)u * G + h) * a.gstride + pos));
+                        const int h = i / per_h;
+                        int o = 8 * (i % per_h);
+                        if (o >= lo) o += skip;
+                        off[k] = h * chunk_len + o;
+                        v[k] = ld_agent((const unsigned long long *)(a.gcode + ((size_t)u * G + h) * a.gstride + min(cb + o, top)));
                     }
 #pragma unroll
-                    for (int k = 0; k < kBatch; ++k) {
-                        const int i = i0 + k * 512 + tid;
-                        if (i < nw) *(unsigned long long *)(rem_code + (size_t)(i / per_h) * rstride + 8 * (i % per_h)) = v[k];
-                    }
+                    for (int k = 0; k < kBatch; ++k)
+                        if (i0 + k * 512 + tid < nw) *(unsigned long long *)(rem_code + off[k]) = v[k];
                 }
-                const int nr = (rstride / kTile) * G;
+                const int tl = lo / kTile, tskip = skip / kTile;
+                const int nr = (chunk_len / kTile - tskip) * G;
                 for (int i0 = 0; i0 < nr; i0 += 512 * kBatch) {
                     float v[kBatch];
+                    int off[kBatch];
 #pragma unroll
                     for (int k = 0; k < kBatch; ++k) {
                         const int i = min(i0 + k * 512 + tid, nr - 1);
-                        const int rt = i / G, h = i % G;
-                        const int tile = rt < start / kTile ? rt : rt + own_len / kTile;
-                        v[k] = ld_agent(&a.gref[((size_t)u * a.ntiles + tile) * G + h]);
+                        int t = i / G;
+                        if (t >= tl) t += tskip;
+                        off[k] = t * G + i % G;
+                        v[k] = ld_agent(&a.gref[((size_t)u * a.ntiles + min(cb / kTile + t, a.ntiles - 1)) * G + i % G]);
                     }
 #pragma unroll
-                    for (int k = 0; k < kBatch; ++k) {
-                        const int i = i0 + k * 512 + tid;
-                        if (i < nr) rem_ref[i] = fast_exp2(kCodeBias + v[k] - sM[i % G]) / sL[i % G];
-                    }
+                    for (int k = 0; k < kBatch; ++k)
+                        if (i0 + k * 512 + tid < nr) rem_ref[off[k]] = fast_exp2(kCodeBias + v[k] - sM[off[k] % G]) / sL[off[k] % G];
                 }
-            }
+            };
             __syncthreads();
             // Decode every (head, slot) code once.  A decoded term is within 2^(+-1/8) of the
             // true one; code 0 has no upper bound, code 255 no lower bound.  Each thread keeps
@@ -506,11 +516,11 @@ __global__ __launch_bounds__(512, 1) void unit_mfma_kernel(const UnitArgs a_in, 
                     if (4 * item >= start && 4 * item < own_hi) {
                         cp = ls_code + (4 * item - start);
                         fp = ls_ref + (tile - start / kTile) * G;
-                    } else if (gathered) {
-                        const int rp = 4 * item < start ? 4 * item : 4 * item - own_len;
+                    } else if (GATHER) { // another workgroup's: in the chunk that is in LDS right now
+                        const int rp = 4 * item - chunk_base;
                         cp = rem_code + rp;
                         fp = rem_ref + (rp / kTile) * G;
-                        cstride = rstride;
+                        cstride = chunk_len;
                     } else {
                         local = false;
                     }
@@ -546,9 +556,9 @@ __global__ __launch_bounds__(512, 1) void unit_mfma_kernel(const UnitArgs a_in, 
                             }
                         }
                     }
-                } else if (COOP) {
-                    // another workgroup's dump, too large to copy: batch the device-scope
-                    // loads of this item, then use them
+                } else if (COOP && !GATHER) {
+                    // another workgroup's dump, read in place: batch the device-scope loads of
+                    // this item, then use them
                     uint32_t c4s[kMaxGroup];
                     float refs[kMaxGroup];
 #pragma unroll
@@ -602,37 +612,55 @@ __global__ __launch_bounds__(512, 1) void unit_mfma_kernel(const UnitArgs a_in, 
             } else if (iters <= kRegIters) {
                 float lbs[kRegIters][4];
 #pragma unroll
-                for (int it = 0; it < kRegIters; ++it) {
-                    const int item = it * 512 + tid;
+                for (int it = 0; it < kRegIters; ++it)
 #pragma unroll
                     for (int e = 0; e < 4; ++e) lbs[it][e] = INFINITY;
-                    if (it < iters && item < items) {
-                        float ub4[4];
-                        decode_item(item, ub4, lbs[it]);
-                        ub_min = fminf(ub_min, fminf(fminf(ub4[0], ub4[1]), fminf(ub4[2], ub4[3])));
+                // one pass over all items; with dumps to copy, chunk by chunk
+                const int span = chunk_len > 0 ? chunk_len : a.gstride;
+                for (int cb = 0; cb < a.gstride; cb += span) {
+                    if (chunk_len > 0) {
+                        __syncthreads(); // the previous chunk has been read by everyone
+                        chunk_base = cb;
+                        gather_chunk(cb);
+                        __syncthreads();
+                    }
+#pragma unroll
+                    for (int it = 0; it < kRegIters; ++it) {
+                        const int item = it * 512 + tid;
+                        if (it < iters && item < items && it * 2048 >= cb && it * 2048 < cb + span) {
+                            float ub4[4];
+                            decode_item(item, ub4, lbs[it]);
+                            ub_min = fminf(ub_min, fminf(fminf(ub4[0], ub4[1]), fminf(ub4[2], ub4[3])));
+                        }
                     }
                 }
                 const float thr = block_min(ub_min) * 1.1893f * 1.0001f;
 #pragma unroll
                 for (int it = 0; it < kRegIters; ++it)
                     if (it < iters) list_candidates(it * 512 + tid, lbs[it], thr);
-            } else { // budgets beyond the register window: decode twice
-                for (int it = 0; it < iters; ++it) {
-                    const int item = it * 512 + tid;
-                    if (item < items) {
-                        float ub4[4], lb4[4];
-                        decode_item(item, ub4, lb4);
-                        ub_min = fminf(ub_min, fminf(fminf(ub4[0], ub4[1]), fminf(ub4[2], ub4[3])));
+            } else { // budgets beyond the register window: decode twice (dump chunks are copied twice)
+                const int span = chunk_len > 0 ? chunk_len : a.gstride;
+                float thr = 0.f;
+                for (int pass = 0; pass < 2; ++pass) {
+                    for (int cb = 0; cb < a.gstride; cb += span) {
+                        if (chunk_len > 0) {
+                            __syncthreads(); // the previous chunk has been read by everyone
+                            chunk_base = cb;
+                            gather_chunk(cb);
+                            __syncthreads();
+                        }
+                        const int it_hi = min(iters, (cb + span + 2047) / 2048); // the last span may be ragged
+                        for (int it = cb / 2048; it < it_hi; ++it) {
+                            const int item = it * 512 + tid;
+                            if (item < items) {
+                                float ub4[4], lb4[4];
+                                decode_item(item, ub4, lb4);
+                                if (pass == 0) ub_min = fminf(ub_min, fminf(fminf(ub4[0], ub4[1]), fminf(ub4[2], ub4[3])));
+                                else list_candidates(item, lb4, thr);
+                            }
+                        }
                     }
-                }
-                const float thr = block_min(ub_min) * 1.1893f * 1.0001f;
-                for (int it = 0; it < iters; ++it) {
-                    const int item = it * 512 + tid;
-                    if (item < items) {
-                        float ub4[4], lb4[4];
-                        decode_item(item, ub4, lb4);
-                        list_candidates(item, lb4, thr);
-                    }
+                    if (pass == 0) thr = block_min(ub_min) * 1.1893f * 1.0001f;
                 }
             }
             __syncthreads();
@@ -748,7 +776,7 @@ static UnitArgs unit_args_of(const Plan &p, int n, int S)
     const bool stash = !(p.flags & 1u);
     const size_t lds = unit_mfma_lds_bytes(p.N, p.G, stash, S);
     a.merge_off = (stash && S > 1) ? (int)(lds - merge_bytes(p.G)) : 0;
-    a.gather = 0;
+    a.chunk_len = 0;
     a.scale_log2 = 1.4426950408889634f / sqrtf(128.f);
     return a;
 }
@@ -786,17 +814,23 @@ static hipError_t launch_unit(const Plan &p, const StepIo &io, int n, const void
     ga.kv_stride = (long long)p.units * 128;
     ga.ev_stride = p.units;
     size_t lds = unit_mfma_lds_bytes(p.N, p.G, stash, S);
-    if (stash && S > 1) {
-        // Room, behind the own codes, for every other workgroup's codes and references?  The
-        // workgroup with the shortest own range (the last one) needs the most.  Only worth
-        // it from three workgroups per unit on (with two there is one batch either way).
-        const int s_full = (p.N + a.split_len - 1) / a.split_len;
-        const size_t rem_len = (size_t)(s_full - 1) * a.split_len;
-        const size_t rem = (size_t)p.G * rem_len + rem_len / kTile * p.G * sizeof(float);
-        const size_t want = (size_t)a.merge_off + std::max(rem, merge_bytes(p.G));
-        if (s_full >= 3 && want <= kUnitLdsLimit) {
-            a.gather = 1;
-            lds = want;
+    bool gather = false;
+    if (stash && S > 1 && (p.N + a.split_len - 1) / a.split_len >= 3) {
+        // From three workgroups per unit on, the deciding one copies the others' dumps into
+        // LDS before screening them (with two, reading them in place is one batch of loads
+        // as well, and measured 2 us faster on cfg2).  Room behind the own codes: 1 byte per
+        // head and slot plus 4 bytes per head and 16 slots, in chunks of whole multiples of
+        // 2048 positions -- as much as fits, at least 2048 (that much the merge area alone holds).
+        const size_t per_pos4 = (size_t)p.G * 5; // bytes per 4 positions
+        const size_t avail = kUnitLdsLimit - (size_t)a.merge_off;
+        long long fit = (long long)(avail * 4 / per_pos4) / 2048 * 2048;
+        const long long all = ((long long)p.ntiles * kTile + 2047) / 2048 * 2048;
+        if (fit > all) fit = all;
+        if (fit >= 2048) {
+            gather = true;
+            a.chunk_len = (int)fit;
+            const size_t want = (size_t)a.merge_off + std::max((size_t)fit * per_pos4 / 4, merge_bytes(p.G));
+            if (want > lds) lds = want;
         }
     }
     // With at most a few workgroups per compute unit, ask for more than half of the
@@ -807,25 +841,29 @@ static hipError_t launch_unit(const Plan &p, const StepIo &io, int n, const void
     // the dynamic-LDS ceiling is a per-device function attribute: raise it once per device
     // and kernel instance (a benign race if two host threads get here together: both set it)
     constexpr int kMaxDevices = 64;
-    static bool attr_done_all[kMaxDevices][16] = {};
+    static bool attr_done_all[kMaxDevices][32] = {};
     int dev = 0;
     if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) return hipErrorInvalidDevice;
     bool *attr_done = attr_done_all[dev];
-#define LF_UNIT4(STASH, COOP, GROUPED, MASKED, IDX)                                                   \
+#define LF_UNIT5(STASH, COOP, GROUPED, MASKED, GATHER, IDX)                                           \
     do {                                                                                              \
         if (!attr_done[IDX]) {                                                                        \
-            hipError_t e = hipFuncSetAttribute((const void *)unit_mfma_kernel<true, STASH, COOP, GROUPED, MASKED>, \
+            hipError_t e = hipFuncSetAttribute((const void *)unit_mfma_kernel<true, STASH, COOP, GROUPED, MASKED, GATHER>, \
                                                hipFuncAttributeMaxDynamicSharedMemorySize, (int)kUnitLdsLimit); \
             if (e != hipSuccess) return e;                                                            \
             attr_done[IDX] = true;                                                                    \
         }                                                                                             \
-        hipLaunchKernelGGL((unit_mfma_kernel<true, STASH, COOP, GROUPED, MASKED>), dim3((unsigned)wgs), dim3(512), lds, s, a, ga); \
+        hipLaunchKernelGGL((unit_mfma_kernel<true, STASH, COOP, GROUPED, MASKED, GATHER>), dim3((unsigned)wgs), dim3(512), lds, s, a, ga); \
     } while (0)
-    // the mask only matters where slots are scored (an attention-only cache takes none)
+    // the mask only matters where slots are scored (an attention-only cache takes none), the
+    // gathering only where cooperating workgroups screen codes
 #define LF_UNIT(STASH, COOP, GROUPED, IDX)                                                            \
     do {                                                                                              \
-        if (p.masked && STASH == kStashLds) LF_UNIT4(STASH, COOP, GROUPED, true, 8 + IDX);            \
-        else LF_UNIT4(STASH, COOP, GROUPED, false, IDX);                                              \
+        if (STASH == kStashLds && COOP && gather) {                                                   \
+            if (p.masked) LF_UNIT5(STASH, COOP, GROUPED, true, true, 24 + IDX);                       \
+            else LF_UNIT5(STASH, COOP, GROUPED, false, true, 16 + IDX);                               \
+        } else if (p.masked && STASH == kStashLds) LF_UNIT5(STASH, COOP, GROUPED, true, false, 8 + IDX); \
+        else LF_UNIT5(STASH, COOP, GROUPED, false, false, IDX);                                       \
     } while (0)
     const bool coop = S > 1;
     if (table) {
@@ -835,7 +873,7 @@ static hipError_t launch_unit(const Plan &p, const StepIo &io, int n, const void
         if (stash) { if (coop) LF_UNIT(kStashLds, true, false, 0); else LF_UNIT(kStashLds, false, false, 1); }
         else       { if (coop) LF_UNIT(kStashNone, true, false, 2); else LF_UNIT(kStashNone, false, false, 3); }
     }
-#undef LF_UNIT4
+#undef LF_UNIT5
 #undef LF_UNIT
     return hipGetLastError();
 }
