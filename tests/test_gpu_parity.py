@@ -721,3 +721,105 @@ def test_resume_from_saved_state_continues_bit_identically(with_holes):
         assert torch.equal(oa.view(torch.int16), ob.view(torch.int16)) and torch.equal(ia, ib), f"step {t}"
     assert torch.equal(a.mask(), b.mask()) and bool(a.mask().all())
     a.close(); b.close()
+
+
+# ------------------------------------------------------------------ random operation sequences
+
+def _op_sequences(count, seed):
+    rng = np.random.default_rng(seed)
+    cases = []
+    for _ in range(count):
+        path = int(rng.choice([0, 0, lf.LF_FLAG_FORCE_SPLIT, lf.LF_FLAG_FORCE_UNIT, lf.LF_FLAG_FORCE_VALU]))
+        dtype = "f32" if (path == 0 and rng.random() < 0.25) else "bf16"
+        D = 64 if dtype == "f32" else 128
+        gmax = 8 if (dtype == "f32" or path == lf.LF_FLAG_FORCE_VALU) else 16
+        G = int(rng.integers(1, gmax + 1))
+        Hkv = int(rng.integers(1, 3))
+        B = int(rng.integers(1, 4))
+        N = int(rng.choice([int(rng.integers(40, 300)), int(rng.integers(600, 1500)), int(rng.integers(2000, 2600))]))
+        n_init = int(rng.integers(N // 2, N))
+        cases.append((dtype, B, G * Hkv, Hkv, D, N, n_init, path if dtype == "bf16" else 0, int(rng.integers(1 << 30))))
+    return cases
+
+
+@pytest.mark.parametrize("case", _op_sequences(10, 20260312), ids=lambda c: "-".join(str(x) for x in c[:8]))
+def test_random_operation_sequences(case):
+    # decode steps interleaved with batch evictions, re-masking and grouped steps, every
+    # result checked against the oracle taken through the same operations
+    dtype, B, Hq, Hkv, D, N, n_init, flags, seed = case
+    wl = W.Workload("ops", dtype, B, Hq, Hkv, D, N, n_init, 1, sink_scale=4.0 if seed & 1 else 1.0, seed=seed)
+    rng = np.random.default_rng(seed)
+    rep, gpu, ora = run_lockstep(wl, steps=3, flags=flags)
+    # a second cache of the same geometry rides along in the grouped steps (its content is not checked)
+    k0, v0 = W.host_prefill(wl, 1)
+    other = lf.LongFlowCache(B, Hq, Hkv, D, N, dtype=W.torch_dtype(wl), flags=flags,
+                             k_init=W.to_torch(k0, wl, "cuda"), v_init=W.to_torch(v0, wl, "cuda"))
+    for t in range(3):
+        other.decode_step(*(W.to_torch(x, wl, "cuda") for x in W.host_step(wl, t, 1)))
+    group = None
+    t = 3
+    units = wl.units
+    done = {"steps": 0, "evict": 0, "mask": 0, "group": 0}
+    for _ in range(14):
+        op = str(rng.choice(["steps", "steps", "evict", "mask", "group"]))
+        if op == "evict":
+            k = int(rng.integers(1, max(2, min(24, N // 8))))
+            sc = ora.scores().reshape(units, N)
+            valid = ora.mask().reshape(units, N).astype(bool)
+            ev = gpu.evict_lowest(k).cpu().numpy().reshape(units, k)
+            ev_ref = ora.evict_lowest(k).reshape(units, k)
+            steer = ora.mask().reshape(units, N).astype(bool)
+            for u in range(units):
+                got, want = set(ev[u][ev[u] >= 0].tolist()), set(ev_ref[u][ev_ref[u] >= 0].tolist())
+                assert len(got) == len(want)
+                if got != want:                       # only across a near-tie of the last score taken
+                    kth = np.sort(sc[u, valid[u]])[min(k, valid[u].sum()) - 1]
+                    odd = np.array(sorted(got ^ want))
+                    assert (np.abs(sc[u, odd] - kth) <= 1e-6 * kth).all()
+                    steer[u] = valid[u]
+                    steer[u, sorted(got)] = False
+            ora.set_mask(steer.reshape(units, 1, N))
+            if group is not None:                     # the rider must follow into mask mode
+                other.set_mask(torch.ones(B, Hkv, N))
+        elif op == "mask":
+            m = ora.mask().reshape(units, N).astype(bool)
+            drop = rng.random((units, N)) < rng.choice([0.01, 0.1])
+            drop[:, int(rng.integers(N))] = False
+            keep = m & ~drop
+            keep[np.arange(units), np.argmax(m, axis=1)] = True   # never empty
+            gpu.set_mask(torch.as_tensor(keep.reshape(B, Hkv, N)))
+            ora.set_mask(keep.reshape(units, 1, N))
+            other.set_mask(torch.ones(B, Hkv, N))
+        elif op == "group":
+            if group is None:
+                if gpu.valid_count != other.valid_count:
+                    continue
+                try:
+                    group = lf.LongFlowGroup([gpu, other])
+                except lf.LongFlowError:                # one masked, the other not
+                    other.set_mask(torch.ones(B, Hkv, N))
+                    if gpu.valid_count != other.valid_count:
+                        continue
+                    group = lf.LongFlowGroup([gpu, other])
+            n_steps = int(rng.integers(1, 4))
+            member = _GroupMember(group, 0, wl, seed=seed + t)
+            try:
+                rep, _, ora = run_lockstep(wl, steps=n_steps, gpu_cache=member, oracle_cache=ora, t0=t, report=rep,
+                                           check_scores_every=2)
+            except lf.LongFlowError as e:               # the members drifted apart in fill level or mode
+                assert e.status == lf.LF_ERR_STATE
+                continue
+            t += n_steps
+            done["group"] += n_steps
+            continue
+        else:
+            n_steps = int(rng.integers(1, 6))
+            rep, _, ora = run_lockstep(wl, steps=n_steps, gpu_cache=gpu, oracle_cache=ora, t0=t, report=rep,
+                                       check_scores_every=3)
+            t += n_steps
+        done[op] += 1
+    print(f"\nops {done} decisions {rep.decisions} near-ties {rep.near_ties}")
+    if group is not None:
+        group.close()
+    gpu.close()
+    other.close()
