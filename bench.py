@@ -231,6 +231,9 @@ def report(a):
     rows = [(W.CONFIGS[i], 0, DEFAULT_STEPS[i]) for i in range(5)]
     twin = W.scaled(W.CONFIGS[4], name="cfg4_uncompressed_twin_n81920", budget=81920, n_init=81920)
     rows.append((twin, lf.LF_FLAG_ATTENTION_ONLY, 10))
+    # the geometry of the paper's own kernel measurement (Fig. 1: Qwen3-8B, batch 128, 3200 slots)
+    rows.append((W.scaled(W.CONFIGS[4], name="paper_fig1_geometry_b128_32x8_n3200", q_heads=32, kv_heads=8,
+                          budget=3200, n_init=3199), 0, 100))
     # the small workloads again as 28 independent caches, for the one-launch-per-step column
     for i in range(3):
         rows.append((W.scaled(W.CONFIGS[i], name=W.CONFIGS[i].name + "_x28", layers=28), 0, DEFAULT_STEPS[i]))
