@@ -51,7 +51,6 @@ struct Layout {
 
 // Split-K geometry for a cache of `units` independent (batch, KV head) pairs.
 void choose_splits(int units, int N, int *L, int *C);
-Layout make_layout(int units, int Hq_total_elems_bytes, int G, int D, int C, int ntiles);
 
 // Kernel launchers (each returns the hipError_t of its launch).
 // One decode step on a split-K path (single launch: insert, stream, last-arriver finish).

@@ -37,10 +37,6 @@ void choose_splits(int units, int N, int *L, int *C)
     if (c > kMaxSplits) c = kMaxSplits;
     if (c < 1) c = 1;
     long l = (N + c - 1) / c;
-    if (const char *e = getenv("LONGFLOW_SPLIT_LEN")) {
-        const long v = atol(e);
-        if (v >= 16) l = v;
-    }
     l = (l + 255) / 256 * 256;
     while ((N + l - 1) / l > kMaxSplits) l += 256;
     *L = (int)l;
