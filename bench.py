@@ -258,7 +258,7 @@ def report(a):
 def main():
     a = parse()
     if a.gpus != 1:
-        print("bench.py: this build runs on ONE GPU (units are independent; see DESIGN.md on sharding); "
+        print("bench.py: this build runs on ONE GPU (the (batch, KV head) units are independent and would shard without exchange); "
               f"--gpus {a.gpus} is not supported", file=sys.stderr)
         sys.exit(2)
     from paper_2603_11504_amd import longflow as lf
