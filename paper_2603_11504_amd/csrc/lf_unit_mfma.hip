@@ -459,39 +459,47 @@ __global__ __launch_bounds__(512, 1) void unit_mfma_kernel(const UnitArgs a_in, 
                 const int skip = hi - lo;
                 const int top = a.gstride - 8; // last 8-byte word of a dump row
                 const int per_h = (chunk_len - skip) / 8;
-                const int nw = G * per_h;
+                const int nw = G * per_h;                             // 8-byte words of codes
+                const int tl = lo / kTile, tskip = skip / kTile;
+                const int nr = (chunk_len / kTile - tskip) * G;       // references, half as many
                 for (int i0 = 0; i0 < nw; i0 += 512 * kBatch) {
                     unsigned long long v[kBatch];
-                    int off[kBatch];
+                    float rv[kBatch];
+                    int off[kBatch], roff[kBatch];
+                    // codes and references of one round are all requested before any is used;
+                    // nothing is loaded past the end: device-scope loads are too dear to repeat
 #pragma unroll
                     for (int k = 0; k < kBatch; ++k) {
-                        const int i = min(i0 + k * 512 + tid, nw - 1);
-                        const int h = i / per_h;
-                        int o = 8 * (i % per_h);
-                        if (o >= lo) o += skip;
-                        off[k] = h * chunk_len + o;
-                        v[k] = ld_agent((const unsigned long long *)(a.gcode + ((size_t)u * G + h) * a.gstride + min(cb + o, top)));
+                        const int i = i0 + k * 512 + tid;
+                        v[k] = 0;
+                        off[k] = 0;
+                        if (i < nw) {
+                            const int h = i / per_h;
+                            int o = 8 * (i % per_h);
+                            if (o >= lo) o += skip;
+                            off[k] = h * chunk_len + o;
+                            v[k] = ld_agent((const unsigned long long *)(a.gcode + ((size_t)u * G + h) * a.gstride + min(cb + o, top)));
+                        }
+                    }
+#pragma unroll
+                    for (int k = 0; k < kBatch / 2; ++k) {
+                        const int i = i0 / 2 + k * 512 + tid;
+                        rv[k] = 0.f;
+                        roff[k] = 0;
+                        if (i < nr) {
+                            int t = i / G;
+                            if (t >= tl) t += tskip;
+                            roff[k] = t * G + i % G;
+                            rv[k] = ld_agent(&a.gref[((size_t)u * a.ntiles + min(cb / kTile + t, a.ntiles - 1)) * G + i % G]);
+                        }
                     }
 #pragma unroll
                     for (int k = 0; k < kBatch; ++k)
                         if (i0 + k * 512 + tid < nw) *(unsigned long long *)(rem_code + off[k]) = v[k];
-                }
-                const int tl = lo / kTile, tskip = skip / kTile;
-                const int nr = (chunk_len / kTile - tskip) * G;
-                for (int i0 = 0; i0 < nr; i0 += 512 * kBatch) {
-                    float v[kBatch];
-                    int off[kBatch];
 #pragma unroll
-                    for (int k = 0; k < kBatch; ++k) {
-                        const int i = min(i0 + k * 512 + tid, nr - 1);
-                        int t = i / G;
-                        if (t >= tl) t += tskip;
-                        off[k] = t * G + i % G;
-                        v[k] = ld_agent(&a.gref[((size_t)u * a.ntiles + min(cb / kTile + t, a.ntiles - 1)) * G + i % G]);
-                    }
-#pragma unroll
-                    for (int k = 0; k < kBatch; ++k)
-                        if (i0 + k * 512 + tid < nr) rem_ref[off[k]] = fast_exp2(kCodeBias + v[k] - sM[off[k] % G]) / sL[off[k] % G];
+                    for (int k = 0; k < kBatch / 2; ++k)
+                        if (i0 / 2 + k * 512 + tid < nr)
+                            rem_ref[roff[k]] = fast_exp2(kCodeBias + rv[k] - sM[roff[k] % G]) / sL[roff[k] % G];
                 }
             };
             __syncthreads();
