@@ -18,12 +18,15 @@
 // writes interleaved with the K/V read stream cost a quarter of the read bandwidth.
 //
 // Cooperation protocol for S > 1 (no workgroup ever waits for one that is not already
-// running): each workgroup publishes its partial, fences, and bumps arrive[u].  All but
-// the last then copy their codes to a small (L2-resident) dump area, fence, and bump
-// dumped[u].  The last one merges the partials, waits (bounded) until S-1 dumps are
-// in -- their authors passed arrive[u] before it did, so they are running or done -- and
-// decides the eviction from its own LDS codes plus the dumps.  If the bounded wait ever
-// expired it would re-score every slot exactly instead of trusting incomplete dumps.
+// running): each workgroup writes its partial through to the device-wide coherence point,
+// waits for its own stores, and bumps arrive[u].  All but the last then write their codes
+// to a dump area the same way and bump dumped[u].  The last one merges the partials (the
+// partial outputs come in the same batch of loads, the output is stored at once), waits
+// (bounded) until S-1 dumps are in -- their authors passed arrive[u] before it did, so they
+// are running or done -- and decides the eviction from its own LDS codes plus the dumps,
+// which it reads in place (S = 2) or copies into LDS chunk by chunk (S >= 3).  If the
+// bounded wait ever expired it would re-score every slot exactly instead of trusting
+// incomplete dumps.
 #include <algorithm>
 #include <cstring>
 
