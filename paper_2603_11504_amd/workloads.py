@@ -169,7 +169,7 @@ def to_f64(x) -> np.ndarray:
 def _torch_gen(wl: Workload, stream: int, layer: int, t: int, device):
     import torch
     g = torch.Generator(device=device)
-    g.manual_seed((wl.seed * 1000003 + stream * 7919 + layer) * 65537 + t)
+    g.manual_seed(((wl.seed * 1000003 + stream * 7919 + layer) * 65537 + t) % (1 << 63))  # any seed fits
     return g
 
 
