@@ -81,21 +81,30 @@ __global__ __launch_bounds__(256) void split_valu_kernel(const SplitTailArgs<T> 
         // NaN marks an invalid slot, which is then treated like a slot past the end
         float lu_mine = 0.f;
         if (ta.masked) lu_mine = ta.lu[(size_t)u * ntiles * kTile + base + j];
-        static_for<kTile>([&](auto ic) {
-            constexpr int jj = decltype(ic)::value;
-            const int slot = base + jj;
-            const float lu_jj = row16_bcast<tail_pos_of_slot(jj)>(lu_mine);
-            const bool valid = slot < end && lu_jj == lu_jj;
-            RowChunk<T, EPL> kr;
-            if (valid) kr.load(Ku + (size_t)slot * D + j * EPL); else kr.zero();
+        // Rows are fetched eight at a time, unconditionally (a slot past the end re-reads the
+        // last valid row and is discarded afterwards): eight loads in flight per lane instead
+        // of a load-wait-use chain per slot.
+        const int last = end - 1;
+        static_for<2>([&](auto hc) {
+            constexpr int half = decltype(hc)::value;
+            RowChunk<T, EPL> kr[8];
+            static_for<8>([&](auto ic) {
+                constexpr int jj = 8 * half + decltype(ic)::value;
+                kr[jj - 8 * half].load(Ku + (size_t)min(base + jj, last) * D + j * EPL);
+            });
+            static_for<8>([&](auto ic) {
+                constexpr int jj = 8 * half + decltype(ic)::value;
+                const float lu_jj = row16_bcast<tail_pos_of_slot(jj)>(lu_mine);
+                const bool valid = base + jj < end && lu_jj == lu_jj;
 #pragma unroll
-            for (int h = 0; h < G; ++h) {
-                float part = 0.f;
+                for (int h = 0; h < G; ++h) {
+                    float part = 0.f;
 #pragma unroll
-                for (int e = 0; e < EPL; ++e) part = fmaf(qf[h][e], kr.v[e], part);
-                part = row16_sum(part);
-                if (jj == j) t[h] = valid ? part * scale_log2 : -INFINITY;
-            }
+                    for (int e = 0; e < EPL; ++e) part = fmaf(qf[h][e], kr[jj - 8 * half].v[e], part);
+                    part = row16_sum(part);
+                    if (jj == j) t[h] = valid ? part * scale_log2 : -INFINITY;
+                }
+            });
         });
         // ---- fix the tile's reference, rescale the running state once
         float p[G];
@@ -112,24 +121,31 @@ __global__ __launch_bounds__(256) void split_valu_kernel(const SplitTailArgs<T> 
         }
         // ---- V phase
         float u_mine = 0.f;
-        static_for<kTile>([&](auto ic) {
-            constexpr int jj = decltype(ic)::value;
-            const int slot = base + jj;
-            const float lu_jj = row16_bcast<tail_pos_of_slot(jj)>(lu_mine);
-            const bool valid = slot < end && lu_jj == lu_jj;
-            RowChunk<T, EPL> vr;
-            if (valid) vr.load(Vu + (size_t)slot * D + j * EPL); else vr.zero();
-            float au = 0.f;
+        static_for<2>([&](auto hc) {
+            constexpr int half = decltype(hc)::value;
+            RowChunk<T, EPL> vr[8];
+            static_for<8>([&](auto ic) {
+                constexpr int jj = 8 * half + decltype(ic)::value;
+                vr[jj - 8 * half].load(Vu + (size_t)min(base + jj, last) * D + j * EPL);
+            });
+            static_for<8>([&](auto ic) {
+                constexpr int jj = 8 * half + decltype(ic)::value;
+                const float lu_jj = row16_bcast<tail_pos_of_slot(jj)>(lu_mine);
+                const bool valid = base + jj < end && lu_jj == lu_jj;
+                RowChunk<T, EPL> &row = vr[jj - 8 * half];
+                if (!valid) row.zero(); // p is 0 there, but the row itself may hold anything
+                float au = 0.f;
 #pragma unroll
-            for (int e = 0; e < EPL; ++e) au += fabsf(vr.v[e]);
-            au = row16_sum(au);
-            if (jj == j) u_mine = au;
+                for (int e = 0; e < EPL; ++e) au += fabsf(row.v[e]);
+                au = row16_sum(au);
+                if (jj == j) u_mine = au;
 #pragma unroll
-            for (int h = 0; h < G; ++h) {
-                const float pj = row16_bcast<jj>(p[h]);
+                for (int h = 0; h < G; ++h) {
+                    const float pj = row16_bcast<jj>(p[h]);
 #pragma unroll
-                for (int e = 0; e < EPL; ++e) o[h][e] = fmaf(pj, vr.v[e], o[h][e]);
-            }
+                    for (int e = 0; e < EPL; ++e) o[h][e] = fmaf(pj, row.v[e], o[h][e]);
+                }
+            });
         });
         if (write_stash) {
             const size_t rec = (size_t)u * ntiles + (size_t)(base / kTile);
