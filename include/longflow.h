@@ -195,7 +195,8 @@ typedef struct {
     int32_t path;                /* lf_path                                                        */
     int32_t workgroups_per_unit; /* at a full cache                                                 */
     int32_t slots_per_workgroup; /* slot range one workgroup streams                                */
-    int32_t launches_per_step;   /* 1, or 2 when a large split-K grid takes a separate finish launch */
+    int32_t launches_per_step;   /* 1, or 2 when a large split-K grid (several workgroups per unit) takes a
+                                    separate finish launch */
     int32_t threads_per_workgroup;
     uint32_t lds_bytes;          /* dynamic LDS per workgroup (0 on the split-K paths: static only) */
 } lf_plan_info;

@@ -82,7 +82,7 @@ hipError_t launch_split_mfma(const Plan &p, const StepIo &io, int n, hipStream_t
     else
         hipLaunchKernelGGL((split_mfma_kernel<true, kStashGlobal, false>), grid, dim3(256), 0, s, ta, scale_log2, gr);
     hipError_t e = hipGetLastError();
-    if (e == hipSuccess && !ta.fused_tail) e = launch_split_finish<bf16_t, 128>(ta, p.units, gr, n_caches, s);
+    if (e == hipSuccess && !ta.fused_tail && ta.c_active > 1) e = launch_split_finish<bf16_t, 128>(ta, p.units, gr, n_caches, s);
     return e;
 }
 

@@ -333,6 +333,14 @@ __device__ void split_finish_unit(const SplitTailArgs<T> &a, int u)
 template <typename T, int D>
 __device__ __forceinline__ void split_tail(const SplitTailArgs<T> &a, int u)
 {
+    if (a.c_active == 1) {
+        // the unit's only workgroup: nobody to wait for, and what it just wrote it reads back
+        // itself -- workgroup-level ordering is enough, no device-wide fence, no counter
+        __threadfence_block();
+        __syncthreads();
+        split_finish_unit<T, D>(a, u);
+        return;
+    }
     if (!a.fused_tail) return;
     __shared__ int s_last;
     __threadfence(); // this thread's partials/stash are visible device-wide ...

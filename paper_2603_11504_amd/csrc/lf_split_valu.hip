@@ -204,7 +204,7 @@ static hipError_t launch_one(const Plan &p, const StepIo &io, int n, hipStream_t
     hipLaunchKernelGGL((split_valu_kernel<T, D, G>), dim3(p.units * ta.c_active * n_caches), dim3(256), 0, s, ta,
                        scale_log2, gr);
     hipError_t e = hipGetLastError();
-    if (e == hipSuccess && !ta.fused_tail) e = launch_split_finish<T, D>(ta, p.units, gr, n_caches, s);
+    if (e == hipSuccess && !ta.fused_tail && ta.c_active > 1) e = launch_split_finish<T, D>(ta, p.units, gr, n_caches, s);
     return e;
 }
 

@@ -320,7 +320,8 @@ int longflow_plan_info(const lf_config *cfg, lf_plan_info *info)
         info->path = p.use_mfma ? LF_PATH_SPLIT_MFMA : LF_PATH_SPLIT_VALU;
         info->workgroups_per_unit = (p.N + p.L - 1) / p.L;
         info->slots_per_workgroup = p.L;
-        info->launches_per_step = (long long)p.units * info->workgroups_per_unit <= 256 ? 1 : 2;
+        info->launches_per_step =
+            (info->workgroups_per_unit == 1 || (long long)p.units * info->workgroups_per_unit <= 256) ? 1 : 2;
         info->threads_per_workgroup = 256;
         info->lds_bytes = 0;
     }
