@@ -578,16 +578,34 @@ __global__ __launch_bounds__(512, 1) void unit_mfma_kernel(const UnitArgs a_in, 
                             c4s[h] = ld_agent((const uint32_t *)(a.gcode + ((size_t)u * G + h) * a.gstride + 4 * item));
                             refs[h] = ld_agent(&a.gref[((size_t)u * a.ntiles + tile) * G + h]);
                         }
+                    // same two forms as above: one sum where no code is clamped, else both
+                    uint32_t clamped = 0u;
 #pragma unroll
                     for (int h = 0; h < kMaxGroup; ++h) {
                         if (h < G) {
-                            const float f = fast_exp2(kCodeBias + refs[h] - sM[h]) / sL[h];
+                            refs[h] = fast_exp2(kCodeBias + refs[h] - sM[h]) / sL[h];
+                            const uint32_t c4 = c4s[h];
+                            clamped |= ((c4 - 0x01010101u) & ~c4) | ((~c4 - 0x01010101u) & c4);
 #pragma unroll
-                            for (int e = 0; e < 4; ++e) {
-                                const uint32_t c = (c4s[h] >> (8 * e)) & 255u;
-                                const float d = fast_exp2(-0.25f * (float)c) * f;
-                                ub4[e] += (c == 0u) ? INFINITY : d;
-                                lb4[e] += (c == 255u) ? 0.f : d;
+                            for (int e = 0; e < 4; ++e)
+                                ub4[e] = fmaf(exp_tab[(c4 >> (8 * e)) & 255u], refs[h], ub4[e]);
+                        }
+                    }
+#pragma unroll
+                    for (int e = 0; e < 4; ++e) lb4[e] = ub4[e];
+                    if (clamped & 0x80808080u) {
+#pragma unroll
+                        for (int e = 0; e < 4; ++e) ub4[e] = lb4[e] = 0.f;
+#pragma unroll
+                        for (int h = 0; h < kMaxGroup; ++h) {
+                            if (h < G) {
+#pragma unroll
+                                for (int e = 0; e < 4; ++e) {
+                                    const uint32_t c = (c4s[h] >> (8 * e)) & 255u;
+                                    const float d = fast_exp2(-0.25f * (float)c) * refs[h];
+                                    ub4[e] += (c == 0u) ? INFINITY : d;
+                                    lb4[e] += (c == 255u) ? 0.f : d;
+                                }
                             }
                         }
                     }
