@@ -30,6 +30,18 @@
  * invalid slot while there is one (the same "fill before evicting" reading
  * as the prefix case), else the argmin.
  *
+ * Comparison rule (the unfused baseline the paper measures its kernel against:
+ * Fig. 1 "both methods evict one token after each attention computation";
+ * Sec. 4.1 describes H2O as ranking tokens by accumulated attention scores,
+ * Sec. 2.2 as keeping those scores as auxiliary per-token metadata).  With
+ * rule 1 the importance of a slot is the attention weight it has received,
+ * summed over the query heads of the group and over every step since the
+ * token in it was inserted:
+ *   5'. acc(i) <- acc(i) + sum_{h in group} alpha_h^i   (acc(slot) <- 0 at insert)
+ *   6'. pending <- argmin_i acc(i) once the cache is full.
+ * Steps 1-4 are unchanged.  Prefilled rows start at acc = 0 (no prompt
+ * attention is defined on this path).  Rule 1 takes no explicit mask.
+ *
  * The method reaches these plain definitions exactly (the fused kernel of
  * Alg. 1 is only a faster route), so the oracle IS the definitions written
  * out.  Max-subtraction inside the softmax is the textbook, exact-arithmetic
@@ -130,6 +142,8 @@ typedef struct lfo_cache {
     double *score;    /* [B][Hkv][N], last step; 0 for invalid slots */
     int32_t *pending; /* [B][Hkv] slot the next token's K/V will cover; -1 = none */
     uint8_t *mask;    /* NULL: valid slots are the prefix [0, count); else [B][Hkv][N], 1 = valid */
+    int rule;         /* 0: LongFlowScore of the last step (eq. 6); 1: accumulated attention weights */
+    double *acc;      /* rule 1: [B][Hkv][N] attention weight received since insertion */
 } lfo_cache;
 
 LFO_API lfo_cache *lfo_cache_create(int B, int Hq, int Hkv, int D, int N)
@@ -152,7 +166,24 @@ LFO_API lfo_cache *lfo_cache_create(int B, int Hq, int Hkv, int D, int N)
 LFO_API void lfo_cache_destroy(lfo_cache *c)
 {
     if (!c) return;
-    free(c->K); free(c->V); free(c->score); free(c->pending); free(c->mask); free(c);
+    free(c->K); free(c->V); free(c->score); free(c->pending); free(c->mask); free(c->acc); free(c);
+}
+
+/*
+ * Importance rule: 0 = LongFlowScore (eq. 6), 1 = accumulated attention weights
+ * (header, steps 5' and 6').  Choosing rule 1 clears the accumulators.
+ */
+LFO_API int lfo_cache_set_rule(lfo_cache *c, int rule)
+{
+    if (rule != 0 && rule != 1) return 1;
+    if (rule == 1 && c->mask) return 3;
+    c->rule = rule;
+    if (rule == 1) {
+        size_t n = (size_t)c->B * c->Hkv * c->N;
+        if (!c->acc) c->acc = (double *)malloc(sizeof(double) * n);
+        for (size_t i = 0; i < n; ++i) c->acc[i] = 0.0;
+    }
+    return 0;
 }
 
 /*
@@ -187,6 +218,7 @@ LFO_API int lfo_cache_init(lfo_cache *c, const double *k_init,
 LFO_API int lfo_cache_set_mask(lfo_cache *c, const uint8_t *mask)
 {
     size_t units = (size_t)c->B * c->Hkv;
+    if (c->rule == 1) return 3;
     if (!c->mask) c->mask = (uint8_t *)malloc(units * c->N);
     for (size_t i = 0; i < units * c->N; ++i) c->mask[i] = mask[i] ? 1 : 0;
     for (size_t u = 0; u < units; ++u)
@@ -219,6 +251,7 @@ LFO_API int lfo_cache_evict_lowest(lfo_cache *c, int k, int32_t *evicted)
     size_t units = (size_t)c->B * c->Hkv;
     const int N = c->N;
     if (k < 1 || k >= N) return 1;
+    if (c->rule == 1) return 3;
     if (!c->mask) { /* the prefix becomes an explicit mask */
         c->mask = (uint8_t *)malloc(units * N);
         for (size_t u = 0; u < units; ++u)
@@ -307,8 +340,23 @@ LFO_API int lfo_cache_step(lfo_cache *c, const double *q, const double *k_new,
         memcpy(Vu + (size_t)slot * D, v_new + (size_t)u * D, sizeof(double) * D);
         /* 2-5. attention and scores over the n valid rows (a prefix) */
         double *sc = c->score + (size_t)u * N;
-        lfo_attend_unit(n, D, G, q + (size_t)u * G * D, Ku, Vu,
-                        out + (size_t)u * G * D, NULL, sc);
+        if (c->rule == 1) {
+            /* 5'. the slot's history starts over; every valid slot then adds the weight
+             * this step's G query heads gave it, and that running sum is its score */
+            double *acc = c->acc + (size_t)u * N;
+            double *alpha = (double *)malloc(sizeof(double) * (size_t)G * n);
+            acc[slot] = 0.0;
+            lfo_attend_unit(n, D, G, q + (size_t)u * G * D, Ku, Vu,
+                            out + (size_t)u * G * D, alpha, sc);
+            for (int i = 0; i < n; ++i) {
+                for (int h = 0; h < G; ++h) acc[i] += alpha[(size_t)h * n + i];
+                sc[i] = acc[i];
+            }
+            free(alpha);
+        } else {
+            lfo_attend_unit(n, D, G, q + (size_t)u * G * D, Ku, Vu,
+                            out + (size_t)u * G * D, NULL, sc);
+        }
         for (int i = n; i < N; ++i) sc[i] = 0.0;
         /* 6. next slot: keep filling, else evict the minimum score */
         c->pending[u] = (n < N) ? n : lfo_argmin(N, sc);

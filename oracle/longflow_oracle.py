@@ -69,6 +69,8 @@ def lib():
         L.lfo_cache_get_mask.restype = ctypes.c_int
         L.lfo_cache_evict_lowest.argtypes = [ctypes.c_void_p, ctypes.c_int, _ip]
         L.lfo_cache_evict_lowest.restype = ctypes.c_int
+        L.lfo_cache_set_rule.argtypes = [ctypes.c_void_p, ctypes.c_int]
+        L.lfo_cache_set_rule.restype = ctypes.c_int
         L.lfo_num_threads.argtypes = []
         L.lfo_num_threads.restype = ctypes.c_int
         _lib = L
@@ -111,11 +113,15 @@ def num_threads() -> int:
 class OracleCache:
     """Static fixed-budget KV cache advanced one decode step at a time."""
 
-    def __init__(self, batch, q_heads, kv_heads, head_dim, budget):
+    RULES = {"longflow": 0, "accumulated_attention": 1}
+
+    def __init__(self, batch, q_heads, kv_heads, head_dim, budget, rule="longflow"):
         self.B, self.Hq, self.Hkv, self.D, self.N = batch, q_heads, kv_heads, head_dim, budget
         self._h = lib().lfo_cache_create(batch, q_heads, kv_heads, head_dim, budget)
         if not self._h:
             raise ValueError("invalid oracle geometry")
+        if lib().lfo_cache_set_rule(self._h, self.RULES[rule]):
+            raise ValueError("importance rule refused")
 
     def __del__(self):
         if getattr(self, "_h", None):
@@ -174,7 +180,8 @@ class OracleCache:
     def set_mask(self, mask):
         """Explicit validity mask [B,Hkv,N] (nonzero = valid); switches the cache to mask mode."""
         m = np.ascontiguousarray(np.asarray(mask) != 0, dtype=np.uint8).reshape(self.B, self.Hkv, self.N)
-        lib().lfo_cache_set_mask(self._h, m.ctypes.data_as(ctypes.POINTER(ctypes.c_uint8)))
+        if lib().lfo_cache_set_mask(self._h, m.ctypes.data_as(ctypes.POINTER(ctypes.c_uint8))):
+            raise ValueError("this importance rule takes no mask")
 
     def mask(self):
         m = np.empty((self.B, self.Hkv, self.N), dtype=np.uint8)
@@ -185,5 +192,5 @@ class OracleCache:
         """Drop the k lowest-scoring valid slots of every unit at once -> their slots [B,Hkv,k]."""
         ev = np.empty((self.B, self.Hkv, k), dtype=np.int32)
         if lib().lfo_cache_evict_lowest(self._h, int(k), ev.ctypes.data_as(_ip)):
-            raise ValueError("k out of range")
+            raise ValueError("k out of range, or not available under this importance rule")
         return ev

@@ -405,3 +405,111 @@ def test_evict_lowest_on_a_filling_cache_and_with_ties():
     np.testing.assert_array_equal(c.mask()[0, 0], np.isin(np.arange(N), [0, 1, 2, 3, 4]) & (np.arange(N) != ev[2]))
     with pytest.raises(ValueError):
         c.evict_lowest(N)
+
+
+# ---------------------------------------------------------------- comparison rule: accumulated attention
+# (the unfused baseline of Fig. 1; Sec. 4.1's description of H2O)
+
+def test_accumulated_rule_against_token_list_bookkeeping_with_library_softmax():
+    """A second procedure that knows nothing of slots: a Python list of live tokens, the
+    library softmax, per-token running sums; the token with the least sum leaves."""
+    rng = np.random.default_rng(77)
+    B, Hkv, G, D, N, T = 2, 2, 3, 16, 6, 25
+    c = oracle.OracleCache(B, Hkv * G, Hkv, D, N, rule="accumulated_attention")
+    c.init()
+    live = [[[] for _ in range(Hkv)] for _ in range(B)]      # per unit: list of dicts
+    slot_of = [[{} for _ in range(Hkv)] for _ in range(B)]   # token id -> slot
+    free = [[list(range(N)) for _ in range(Hkv)] for _ in range(B)]
+    for t in range(T):
+        q = rng.standard_normal((B, Hkv * G, D)) * 1.5
+        k = rng.standard_normal((B, Hkv, D))
+        v = rng.standard_normal((B, Hkv, D))
+        out, idx = c.step(q, k, v)
+        sc = c.scores()
+        for b in range(B):
+            for g in range(Hkv):
+                toks = live[b][g]
+                toks.append({"id": t, "k": k[b, g], "v": v[b, g], "acc": 0.0})
+                slot_of[b][g][t] = free[b][g].pop(0)
+                Km = np.stack([x["k"] for x in toks]); Vm = np.stack([x["v"] for x in toks])
+                w = scipy_softmax(q[b, g * G:(g + 1) * G] @ Km.T / math.sqrt(D), axis=1)
+                np.testing.assert_allclose(out[b, g * G:(g + 1) * G], w @ Vm, rtol=1e-11, atol=1e-13)
+                for j, x in enumerate(toks):
+                    x["acc"] += w[:, j].sum()
+                    np.testing.assert_allclose(sc[b, g, slot_of[b][g][x["id"]]], x["acc"], rtol=1e-12)
+                if len(toks) == N:
+                    j = min(range(N), key=lambda j: toks[j]["acc"])
+                    gone = toks.pop(j)
+                    s = slot_of[b][g].pop(gone["id"])
+                    assert idx[b, g] == s, (t, b, g)
+                    free[b][g].append(s)
+                else:
+                    assert idx[b, g] == len(toks)
+
+
+def test_accumulated_rule_closed_form_with_uniform_attention():
+    """All keys zero: every weight is 1/n.  While filling, the token inserted at step j
+    holds G (H_t - H_{j-1}) after step t (harmonic numbers); once full the newest token
+    has the least and its slot is recycled for ever, the others gaining G/N per step."""
+    G, D, N, T = 4, 8, 5, 12
+    rng = np.random.default_rng(3)
+    c = oracle.OracleCache(1, G, 1, D, N, rule="accumulated_attention")
+    c.init()
+    H = [0.0]
+    for s in range(1, N + 1):
+        H.append(H[-1] + 1.0 / s)
+    for t in range(1, T + 1):
+        out, idx = c.step(rng.standard_normal((1, G, D)), np.zeros((1, 1, D)), rng.standard_normal((1, 1, D)))
+        sc = c.scores().ravel()
+        if t <= N:
+            want = [G * (H[t] - H[j - 1]) for j in range(1, t + 1)] + [0.0] * (N - t)
+            assert idx.item() == (t if t < N else N - 1)
+        else:
+            want = [G * (H[N] - H[j - 1]) + G * (t - N) / N for j in range(1, N)] + [G / N]
+            assert idx.item() == N - 1
+        np.testing.assert_allclose(sc, want, rtol=1e-13)
+
+
+def test_accumulated_rule_conserves_attention_mass():
+    """Each step hands out exactly G units of weight (every head's weights sum to 1); what
+    leaves the books is what the recycled slot held."""
+    rng = np.random.default_rng(5)
+    B, Hkv, G, D, N = 1, 3, 5, 32, 9
+    c = oracle.OracleCache(B, Hkv * G, Hkv, D, N, rule="accumulated_attention")
+    k0 = rng.standard_normal((B, Hkv, 4, D)); v0 = rng.standard_normal((B, Hkv, 4, D))
+    c.init(k0, v0)
+    assert (c.scores() == 0).all()
+    prev = c.scores()
+    pend = c.pending()
+    for t in range(30):
+        c.step(rng.standard_normal((B, Hkv * G, D)) * 2, rng.standard_normal((B, Hkv, D)), rng.standard_normal((B, Hkv, D)))
+        now = c.scores()
+        lost = np.take_along_axis(prev, pend[..., None].astype(np.int64), axis=2)[..., 0]
+        np.testing.assert_allclose(now.sum(-1) - prev.sum(-1) + lost, G, rtol=1e-12)
+        prev, pend = now, c.pending()
+
+
+def test_accumulated_rule_leaves_the_longflow_rule_alone_and_takes_no_mask():
+    rng = np.random.default_rng(9)
+    B, Hkv, G, D, N = 1, 2, 2, 16, 4
+    a = oracle.OracleCache(B, Hkv * G, Hkv, D, N)
+    b = oracle.OracleCache(B, Hkv * G, Hkv, D, N, rule="accumulated_attention")
+    a.init(); b.init()
+    differ = False
+    for t in range(12):
+        q, k, v = rng.standard_normal((B, Hkv * G, D)), rng.standard_normal((B, Hkv, D)), rng.standard_normal((B, Hkv, D))
+        oa, ia = a.step(q, k, v)
+        ob, ib = b.step(q, k, v)
+        if t < N:      # same cache contents while filling: same attention output
+            np.testing.assert_array_equal(oa, ob)
+        differ |= bool((ia != ib).any())
+        # rule 0 is still eq. 6 on the cache rows
+        K, V = a.kv()
+        n = a.count
+        _, sc, _ = oracle.attend_unit(q[0, :G], K[0, 0, :n], V[0, 0, :n])
+        np.testing.assert_array_equal(a.scores()[0, 0, :n], sc)
+    assert differ                      # the two rules do not pick the same victims
+    with pytest.raises(ValueError):
+        b.set_mask(np.ones((B, Hkv, N)))
+    with pytest.raises(ValueError):
+        b.evict_lowest(1)
