@@ -43,6 +43,8 @@ def parse():
     ap.add_argument("--valu", action="store_true", help="bf16: vector-ALU kernel instead of matrix cores")
     ap.add_argument("--split", action="store_true", help="force the split-K path")
     ap.add_argument("--unit", action="store_true", help="force the one-workgroup-per-unit fused path")
+    ap.add_argument("--unfused", action="store_true",
+                    help="bf16/head_dim 128: the unfused comparison path (accumulated attention weights, Fig. 1)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run one 1 GiB device copy (a kernel of known traffic, to scale rocprofv3 byte counters)")
@@ -63,10 +65,11 @@ def kernel_name(wl, flags):
     """Which kernel family the library will run for this workload (asked of the library itself)."""
     from paper_2603_11504_amd import longflow as lf
     cfg = lf.make_config(wl.batch, wl.q_heads, wl.kv_heads, wl.head_dim, wl.budget, wl.dtype, flags)
-    return lf.PATH_KERNELS[lf.longflow_plan_info(cfg).path]
+    name = lf.PATH_KERNELS[lf.longflow_plan_info(cfg).path]
+    return "unfused+" + name if flags & lf.LF_FLAG_UNFUSED_ACCUM else name
 
 
-def cpu_baseline(wl, cache0, target_s=12.0):
+def cpu_baseline(wl, cache0, target_s=12.0, rule="longflow"):
     """The float64 oracle, as it stands, timed on this host on a bounded sample of units."""
     import numpy as np
     import torch
@@ -82,7 +85,7 @@ def cpu_baseline(wl, cache0, target_s=12.0):
     n = cache0.valid_count
     ku = cache0.k_cache.reshape(wl.units, N, D)[sel][:, : n - 1].reshape(nu, 1, n - 1, D)
     vu = cache0.v_cache.reshape(wl.units, N, D)[sel][:, : n - 1].reshape(nu, 1, n - 1, D)
-    ora = oracle.OracleCache(nu, G, 1, D, N)
+    ora = oracle.OracleCache(nu, G, 1, D, N, rule=rule)
     ora.init(W.to_f64(ku), W.to_f64(vu))
     g = np.random.default_rng(1)
     steps, t_total = 0, 0.0
@@ -217,7 +220,8 @@ def measure(wl, flags, steps, warmup, pool=0, with_cpu=False, calibrate_copy=Fal
         "ms_per_step_multi": ms_per_step_multi, "ms_per_step_grouped": ms_per_step_grouped,
     }
     if with_cpu:
-        res["cpu_baseline"] = cpu_baseline(wl, caches[0])
+        res["cpu_baseline"] = cpu_baseline(wl, caches[0], rule="accumulated_attention"
+                                           if flags & lf.LF_FLAG_UNFUSED_ACCUM else "longflow")
     for c in caches:
         c.close()
     del caches, inputs
@@ -234,21 +238,28 @@ def report(a):
     twin = W.scaled(W.CONFIGS[4], name="cfg4_uncompressed_twin_n81920", budget=81920, n_init=81920)
     rows.append((twin, lf.LF_FLAG_ATTENTION_ONLY, 10))
     # the geometry of the paper's own kernel measurement (Fig. 1: Qwen3-8B, batch 128, 3200 slots)
-    rows.append((W.scaled(W.CONFIGS[4], name="paper_fig1_geometry_b128_32x8_n3200", q_heads=32, kv_heads=8,
-                          budget=3200, n_init=3199), 0, 100))
+    fig1 = W.scaled(W.CONFIGS[4], name="paper_fig1_geometry_b128_32x8_n3200", q_heads=32, kv_heads=8,
+                    budget=3200, n_init=3199)
+    rows.append((fig1, 0, 100))
+    # the unfused comparison path of that figure (accumulated attention weights, one eviction per
+    # step: plain attention kernel, then separate importance kernels) on the same workloads
+    UNF = lf.LF_FLAG_UNFUSED_ACCUM
+    rows.append((W.scaled(fig1, name=fig1.name + "_unfused"), UNF, 100))
+    for i in (2, 3, 4):
+        rows.append((W.scaled(W.CONFIGS[i], name=W.CONFIGS[i].name + "_unfused"), UNF, DEFAULT_STEPS[i]))
     # the small workloads again as 28 independent caches, for the one-launch-per-step column
     for i in range(3):
         rows.append((W.scaled(W.CONFIGS[i], name=W.CONFIGS[i].name + "_x28", layers=28), 0, DEFAULT_STEPS[i]))
-    print(f"{'workload':38s} {'kernel':18s} {'us/step p10':>11s} {'median':>9s} {'p90':>9s} {'us/call':>9s} "
+    print(f"{'workload':44s} {'kernel':26s} {'us/step p10':>11s} {'median':>9s} {'p90':>9s} {'us/call':>9s} "
           f"{'GB/s step':>10s} {'% peak':>7s} {'GB/s kernel':>11s} {'% peak':>7s} {'tokens/s':>10s} "
           f"{'grouped us/call':>15s} {'% peak':>7s}")
     for wl, flags, steps in rows:
         if a.steps:
             steps = a.steps
-        r = measure(wl, flags, steps, a.warmup, per_step_times=True, also_grouped=wl.layers > 1)
+        r = measure(wl, flags, steps, a.warmup, per_step_times=True, also_grouped=wl.layers > 1 and not flags & lf.LF_FLAG_UNFUSED_ACCUM)
         s = r["step_us_sorted"]
         p10, med, p90 = s[len(s) // 10], s[len(s) // 2], s[(9 * len(s)) // 10]
-        print(f"{wl.name:38s} {r['kernel']:18s} {p10:11.1f} {med:9.1f} {p90:9.1f} {r['ms_per_step'] * 1e3 / wl.layers:9.1f} "
+        print(f"{wl.name:44s} {r['kernel']:26s} {p10:11.1f} {med:9.1f} {p90:9.1f} {r['ms_per_step'] * 1e3 / wl.layers:9.1f} "
               f"{r['step_GBs']:10.1f} {100 * r['step_GBs'] / HBM_PEAK_GBS:7.1f} {r['kernel_GBs']:11.1f} "
               f"{100 * r['kernel_GBs'] / HBM_PEAK_GBS:7.1f} {r['tokens_per_s']:10.0f} " + (
                   f"{g * 1e3 / wl.layers:15.1f} {100 * r['bytes_call'] * wl.layers / (g * 1e-3) / 1e9 / HBM_PEAK_GBS:7.1f}"
@@ -273,9 +284,10 @@ def main():
     flags = lf.LF_FLAG_FORCE_VALU if (a.valu and wl.dtype == "bf16") else 0
     flags |= lf.LF_FLAG_FORCE_SPLIT if a.split else 0
     flags |= lf.LF_FLAG_FORCE_UNIT if a.unit else 0
+    flags |= lf.LF_FLAG_UNFUSED_ACCUM if a.unfused else 0
     r = measure(wl, flags, steps, a.warmup, pool=a.pool, with_cpu=not a.no_cpu_baseline,
                 calibrate_copy=a.calibrate_copy, streams=a.streams, also_streams=a.also_streams if a.streams == 1 else 0,
-                also_grouped=a.streams == 1 and wl.layers > 1)
+                also_grouped=a.streams == 1 and wl.layers > 1 and not a.unfused)
     kname = r["kernel"]
     out = {
         "metric": "decode_tokens_per_s",
@@ -288,9 +300,11 @@ def main():
         "config": {"workload": wl.name, "batch": wl.batch, "q_heads": wl.q_heads, "kv_heads": wl.kv_heads,
                    "head_dim": wl.head_dim, "budget": wl.budget, "layers": wl.layers,
                    "calls_per_step": wl.layers, "streams": a.streams,
-                   "kernel_path": {"unit_mfma_kernel": "fused one-launch, matrix cores",
+                   "kernel_path": ("unfused comparison path (insert, attention, accumulate, decide) around: "
+                                   if a.unfused else "") +
+                                  {"unit_mfma_kernel": "fused one-launch, matrix cores",
                                    "split_mfma_kernel": "split-K, matrix cores",
-                                   "split_valu_kernel": "split-K, vector ALU"}[kname]},
+                                   "split_valu_kernel": "split-K, vector ALU"}[kname.split("+")[-1]]},
         "us_per_call": r["ms_per_step"] * 1e3 / wl.layers,
         "step_hbm_GBs": r["step_GBs"],
         "step_hbm_frac": r["step_GBs"] / HBM_PEAK_GBS,

@@ -77,6 +77,20 @@ typedef enum { LF_F32 = 0, LF_BF16 = 1 } lf_dtype;
 #define LF_FLAG_FORCE_SPLIT 4u    /* always split a unit over several workgroups              */
 #define LF_FLAG_FORCE_UNIT 8u     /* always one workgroup per unit, one fused launch; needs the
                                      matrix-core path and budget * group <= ~120k            */
+#define LF_FLAG_UNFUSED_ACCUM 16u /* comparison path, bf16 / head_dim 128 only: the baseline
+                                     the paper measures its kernel against (Fig. 1; Sec. 4.1,
+                                     "H2O": accumulated attention scores kept as per-token
+                                     metadata, Sec. 2.2).  A slot's importance is the attention
+                                     weight it has received, summed over the group's query heads
+                                     and over every step since its token was inserted (0 for
+                                     prefilled rows); the slot with the least is evicted, lowest
+                                     slot among equals.  Computed the unfused way: a plain
+                                     attention kernel, then separate kernels that re-derive the
+                                     weights from K and add them to a per-slot fp32 buffer.
+                                     longflow_decode_step keeps its meaning and arguments
+                                     (k_new, v_new 16-byte aligned), longflow_scores returns
+                                     the accumulated weights; masks, batch eviction and groups
+                                     are LF_ERR_UNSUPPORTED.                                  */
 
 typedef struct {
     int32_t batch;    /* B   >= 1                                            */

@@ -24,6 +24,7 @@ struct Plan {
     bool use_unit;     // unit-resident fused kernel: whole step in one launch
     int unit_S;        // ... with this many cooperating workgroups per unit
     bool masked;       // an explicit validity mask is in force (state, set by longflow_set_mask)
+    bool unfused;      // comparison path: plain attention kernel, then separate importance kernels
     // device pointers (caller-owned)
     void *k_cache, *v_cache;
     // carved out of the caller's workspace
@@ -42,11 +43,15 @@ struct Plan {
                        // (kept current by init and insert; NaN = slot invalid under an explicit
                        // mask; the vector-ALU kernels use it for validity only)
     int32_t *first_hole; // [units] scratch of the mask setter
+    // comparison path only
+    float *acc;          // [units][ntiles*kTile] attention weight received since insertion (position order)
+    float *acc_part_v;   // [units][CA] lowest accumulator of each span ...
+    int32_t *acc_part_i; // [units][CA] ... and its slot
 };
 
 struct Layout {
     size_t off_pending, off_arrive, off_dumped, off_hole, off_q, off_part_m, off_part_l, off_part_o, off_fin_m, off_fin_l,
-        off_stash_w, off_stash_m, off_lu, total;
+        off_stash_w, off_stash_m, off_lu, off_acc, off_acc_part_v, off_acc_part_i, total;
 };
 
 // Split-K geometry for a cache of `units` independent (batch, KV head) pairs.
@@ -79,6 +84,10 @@ size_t unit_mfma_table_entry_bytes();
 void unit_mfma_table_entry(const Plan &p, void *dst);
 hipError_t launch_unit_mfma_group(const Plan &p, const StepIo &io, int n, const void *table, int n_caches,
                                   hipStream_t s);
+// Comparison path (accumulated attention weights): insert, plain attention, accumulate, decide.
+void unfused_geometry(int units, int N, int *LA, int *CA);
+hipError_t launch_unfused_step(const Plan &p, const StepIo &io, int n, hipStream_t s);
+hipError_t launch_unfused_scores(const Plan &p, float *scores, hipStream_t s); // float [units][N]
 hipError_t launch_scores(const Plan &p, int n, float *scores, hipStream_t s);
 // Drop the k lowest-scoring valid slots of every unit (scores of the last step, in double
 // precision via `scratch`, device double [units][N]); they become holes of the explicit mask.

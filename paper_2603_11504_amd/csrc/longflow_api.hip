@@ -51,7 +51,8 @@ static int validate(const lf_config *cfg)
         return fail(LF_ERR_INVALID_ARG, "batch/heads/budget out of range");
     if (cfg->dtype != LF_F32 && cfg->dtype != LF_BF16)
         return fail(LF_ERR_INVALID_ARG, "unknown dtype %d", cfg->dtype);
-    if (cfg->flags & ~(LF_FLAG_ATTENTION_ONLY | LF_FLAG_FORCE_VALU | LF_FLAG_FORCE_SPLIT | LF_FLAG_FORCE_UNIT))
+    if (cfg->flags & ~(LF_FLAG_ATTENTION_ONLY | LF_FLAG_FORCE_VALU | LF_FLAG_FORCE_SPLIT | LF_FLAG_FORCE_UNIT |
+                       LF_FLAG_UNFUSED_ACCUM))
         return fail(LF_ERR_INVALID_ARG, "unknown flag bits 0x%x", cfg->flags);
     if (cfg->q_heads % cfg->kv_heads)
         return fail(LF_ERR_UNSUPPORTED, "q_heads %d is not a multiple of kv_heads %d", cfg->q_heads,
@@ -67,9 +68,16 @@ static int validate(const lf_config *cfg)
         return fail(LF_ERR_UNSUPPORTED, "batch*kv_heads > 2^20");
     if ((cfg->flags & LF_FLAG_FORCE_SPLIT) && (cfg->flags & LF_FLAG_FORCE_UNIT))
         return fail(LF_ERR_INVALID_ARG, "FORCE_SPLIT and FORCE_UNIT exclude each other");
+    if (cfg->flags & LF_FLAG_UNFUSED_ACCUM) {
+        if (cfg->flags & (LF_FLAG_ATTENTION_ONLY | LF_FLAG_FORCE_VALU))
+            return fail(LF_ERR_INVALID_ARG, "UNFUSED_ACCUM excludes ATTENTION_ONLY and FORCE_VALU");
+        if (!mfma) return fail(LF_ERR_UNSUPPORTED, "UNFUSED_ACCUM needs bf16 and head_dim 128");
+        if ((long long)cfg->batch * cfg->kv_heads * (cfg->budget + kTile) >= (1ll << 31))
+            return fail(LF_ERR_UNSUPPORTED, "UNFUSED_ACCUM: batch*kv_heads*budget >= 2^31");
+    }
     if (cfg->flags & LF_FLAG_FORCE_UNIT) {
         if (!mfma) return fail(LF_ERR_UNSUPPORTED, "FORCE_UNIT needs bf16, head_dim 128 and the matrix-core kernel");
-        if (unit_mfma_lds_bytes(cfg->budget, G, !(cfg->flags & LF_FLAG_ATTENTION_ONLY), 1) > kUnitLdsLimit)
+        if (unit_mfma_lds_bytes(cfg->budget, G, !(cfg->flags & (LF_FLAG_ATTENTION_ONLY | LF_FLAG_UNFUSED_ACCUM)), 1) > kUnitLdsLimit)
             return fail(LF_ERR_UNSUPPORTED, "FORCE_UNIT: budget %d x group %d does not fit one workgroup's LDS", cfg->budget, G);
     }
     return LF_OK;
@@ -81,12 +89,15 @@ static void fill_plan(const lf_config *cfg, Plan *p)
     p->B = cfg->batch; p->Hq = cfg->q_heads; p->Hkv = cfg->kv_heads; p->D = cfg->head_dim;
     p->N = cfg->budget; p->G = cfg->q_heads / cfg->kv_heads; p->units = cfg->batch * cfg->kv_heads;
     p->dtype = cfg->dtype; p->flags = cfg->flags;
+    // the comparison path runs the plain attention kernels: that is the flag they see
+    p->unfused = cfg->flags & LF_FLAG_UNFUSED_ACCUM;
+    if (p->unfused) p->flags = (cfg->flags & ~LF_FLAG_UNFUSED_ACCUM) | LF_FLAG_ATTENTION_ONLY;
     choose_splits(p->units, p->N, &p->L, &p->C);
     p->ntiles = (p->N + kTile - 1) / kTile;
     p->use_mfma = cfg->dtype == LF_BF16 && cfg->head_dim == 128 && !(cfg->flags & LF_FLAG_FORCE_VALU);
     // unit-resident kernel: as many cooperating workgroups per unit as it takes to fill the
     // chip, more if one workgroup's share of the codes would not fit its LDS
-    const bool stash = !(cfg->flags & LF_FLAG_ATTENTION_ONLY);
+    const bool stash = !(p->flags & LF_FLAG_ATTENTION_ONLY);
     int S = (cfg->flags & LF_FLAG_FORCE_UNIT) ? 1 : unit_mfma_splits(p->units, p->N);
     while (S < 8 && unit_mfma_lds_bytes(p->N, p->G, stash, S) > kUnitLdsLimit) ++S;
     const bool fits = unit_mfma_lds_bytes(p->N, p->G, stash, S) <= kUnitLdsLimit;
@@ -119,6 +130,11 @@ static Layout layout_of(const Plan &p)
     l.off_stash_m = take(stash ? sizeof(float) * (size_t)p.units * p.ntiles * p.G : 0);
     // per-slot side array: log2 ||v||_1 for the matrix-core kernels, validity under an explicit mask for all
     l.off_lu = take(!(p.flags & LF_FLAG_ATTENTION_ONLY) ? sizeof(float) * (size_t)p.units * p.ntiles * kTile : 0);
+    int la = 0, ca = 0;
+    if (p.unfused) unfused_geometry(p.units, p.N, &la, &ca);
+    l.off_acc = take(p.unfused ? sizeof(float) * (size_t)p.units * p.ntiles * kTile : 0);
+    l.off_acc_part_v = take(sizeof(float) * (size_t)p.units * ca);
+    l.off_acc_part_i = take(sizeof(int32_t) * (size_t)p.units * ca);
     l.total = off;
     return l;
 }
@@ -197,6 +213,9 @@ int longflow_init_cache(longflow_cache_t **out, const lf_config *cfg, void *k_ca
     p.stash_w = (uint16_t *)(ws + l.off_stash_w);
     p.stash_m = (float *)(ws + l.off_stash_m);
     p.lu = (float *)(ws + l.off_lu);
+    p.acc = (float *)(ws + l.off_acc);
+    p.acc_part_v = (float *)(ws + l.off_acc_part_v);
+    p.acc_part_i = (int32_t *)(ws + l.off_acc_part_i);
 
     hipStream_t s = (hipStream_t)hip_stream;
     if (n_init > 0) {
@@ -217,6 +236,10 @@ int longflow_init_cache(longflow_cache_t **out, const lf_config *cfg, void *k_ca
         hipError_t e = launch_fill_i32(p.arrive, p.units, 0, s);
         if (e == hipSuccess) e = launch_fill_i32(p.dumped, p.units, 0, s);
         if (e != hipSuccess) return fail(LF_ERR_HIP, "counter init: %s", hipGetErrorString(e));
+    }
+    if (p.unfused) { // prefilled rows start with no attention on their books
+        hipError_t e = launch_fill_i32((int32_t *)p.acc, p.units * p.ntiles * kTile, 0, s);
+        if (e != hipSuccess) return fail(LF_ERR_HIP, "accumulator init: %s", hipGetErrorString(e));
     }
     const bool filling = n_init < p.N;
     if (filling) {
@@ -240,11 +263,13 @@ int longflow_decode_step(longflow_cache_t *cache, const void *q, const void *k_n
     longflow_cache *c = checked(cache);
     if (!c) return fail(LF_ERR_STATE, "invalid or destroyed cache handle");
     const Plan &p = c->plan;
-    const bool attention_only = p.flags & LF_FLAG_ATTENTION_ONLY;
+    const bool attention_only = (p.flags & LF_FLAG_ATTENTION_ONLY) && !p.unfused;
     if (!q || !out) return fail(LF_ERR_INVALID_ARG, "q/out is NULL");
     if (!attention_only && (!k_new || !v_new)) return fail(LF_ERR_INVALID_ARG, "k_new/v_new is NULL");
     if (((uintptr_t)q & 15u) || ((uintptr_t)out & 15u))
         return fail(LF_ERR_INVALID_ARG, "q/out must be 16-byte aligned");
+    if (p.unfused && (((uintptr_t)k_new & 15u) || ((uintptr_t)v_new & 15u)))
+        return fail(LF_ERR_INVALID_ARG, "k_new/v_new must be 16-byte aligned");
     int n;
     if (attention_only) {
         if (c->count < 1) return fail(LF_ERR_STATE, "attention over an empty cache");
@@ -259,7 +284,10 @@ int longflow_decode_step(longflow_cache_t *cache, const void *q, const void *k_n
     if (c->prof_used < c->prof_cap) ev = &c->prof_events[2 * (size_t)c->prof_used++];
     if (ev) (void)hipEventRecord(ev[0], s);
     hipError_t e;
-    if (p.use_unit) {
+    if (p.unfused) {
+        const StepIo io = {q, k_new, v_new, out, evict_idx};
+        e = launch_unfused_step(p, io, n, s);
+    } else if (p.use_unit) {
         e = launch_unit_mfma(p, q, k_new, v_new, n, out, evict_idx, s);
     } else {
         const StepIo io = {q, k_new, v_new, out, evict_idx};
@@ -278,6 +306,11 @@ int longflow_scores(longflow_cache_t *cache, float *scores, void *hip_stream)
     if (!c) return fail(LF_ERR_STATE, "invalid or destroyed cache handle");
     if (!scores) return fail(LF_ERR_INVALID_ARG, "scores is NULL");
     if (!c->stepped) return fail(LF_ERR_STATE, "no decode step has run yet");
+    if (c->plan.unfused) { // the books themselves; slots never filled still hold their initial 0
+        hipError_t e = launch_unfused_scores(c->plan, scores, (hipStream_t)hip_stream);
+        if (e != hipSuccess) return fail(LF_ERR_HIP, "accumulator copy: %s", hipGetErrorString(e));
+        return LF_OK;
+    }
     if (c->plan.flags & LF_FLAG_ATTENTION_ONLY)
         return fail(LF_ERR_STATE, "scores are not defined for an attention-only cache");
     hipError_t e = launch_scores(c->plan, c->count, scores, (hipStream_t)hip_stream);
@@ -325,6 +358,7 @@ int longflow_plan_info(const lf_config *cfg, lf_plan_info *info)
         info->threads_per_workgroup = 256;
         info->lds_bytes = 0;
     }
+    if (p.unfused) info->launches_per_step += 3; // insert, accumulate, decide around the attention kernel
     return LF_OK;
 }
 
@@ -349,6 +383,7 @@ int longflow_group_create(longflow_group_t **group, longflow_cache_t *const *cac
     for (int i = 0; i < n_caches; ++i) {
         longflow_cache *c = checked(caches[i]);
         if (!c) return fail(LF_ERR_STATE, "member %d: invalid or destroyed cache handle", i);
+        if (c->plan.unfused) return fail(LF_ERR_UNSUPPORTED, "member %d: the unfused comparison path has no grouped launch", i);
         for (longflow_cache *m : members)
             if (m == c) return fail(LF_ERR_INVALID_ARG, "member %d appears twice", i);
         const Plan &a = c->plan, &b = (members.empty() ? c : members[0])->plan;
@@ -435,6 +470,7 @@ int longflow_set_mask(longflow_cache_t *cache, const uint8_t *mask, void *hip_st
     longflow_cache *c = checked(cache);
     if (!c) return fail(LF_ERR_STATE, "invalid or destroyed cache handle");
     if (!mask) return fail(LF_ERR_INVALID_ARG, "mask is NULL");
+    if (c->plan.unfused) return fail(LF_ERR_UNSUPPORTED, "the unfused comparison path takes no mask");
     if (c->plan.flags & LF_FLAG_ATTENTION_ONLY)
         return fail(LF_ERR_UNSUPPORTED, "an attention-only cache takes no mask");
     hipError_t e = launch_set_mask(c->plan, mask, (hipStream_t)hip_stream);
@@ -466,6 +502,7 @@ int longflow_evict_lowest(longflow_cache_t *cache, int32_t k, void *scratch, siz
     longflow_cache *c = checked(cache);
     if (!c) return fail(LF_ERR_STATE, "invalid or destroyed cache handle");
     const Plan &p = c->plan;
+    if (p.unfused) return fail(LF_ERR_UNSUPPORTED, "the unfused comparison path evicts one slot per step only");
     if (p.flags & LF_FLAG_ATTENTION_ONLY) return fail(LF_ERR_UNSUPPORTED, "an attention-only cache evicts nothing");
     if (!c->stepped) return fail(LF_ERR_STATE, "no decode step has run yet: there are no scores");
     if (k < 1 || k >= p.N) return fail(LF_ERR_INVALID_ARG, "k = %d outside [1, %d)", k, p.N);

@@ -20,6 +20,7 @@ LF_FLAG_ATTENTION_ONLY = 1
 LF_FLAG_FORCE_VALU = 2
 LF_FLAG_FORCE_SPLIT = 4
 LF_FLAG_FORCE_UNIT = 8
+LF_FLAG_UNFUSED_ACCUM = 16
 
 EXPORTS = ("longflow_workspace_bytes", "longflow_init_cache", "longflow_decode_step",
            "longflow_scores", "longflow_set_pending", "longflow_set_mask", "longflow_get_mask", "longflow_evict_scratch_bytes",

@@ -161,3 +161,21 @@ def test_group_calls_reject_bad_arguments_on_the_host():
     assert not g.value
     assert L.longflow_group_decode_step(None, fake, fake, fake, fake, None, None) == lf.LF_ERR_STATE
     assert L.longflow_group_destroy(None) == lf.LF_ERR_STATE
+
+
+def test_unfused_comparison_path_is_validated_on_the_host():
+    L = lf.lib()
+    UNF = lf.LF_FLAG_UNFUSED_ACCUM
+    fused = L.longflow_workspace_bytes(ctypes.byref(_cfg()))
+    unf = L.longflow_workspace_bytes(ctypes.byref(_cfg(flags=UNF)))
+    assert unf > 0 and fused > 0
+    # the per-slot fp32 books are part of its workspace
+    plain = L.longflow_workspace_bytes(ctypes.byref(_cfg(flags=lf.LF_FLAG_ATTENTION_ONLY)))
+    assert unf >= plain + 4 * 2 * 2 * 512
+    for bad in (_cfg(flags=UNF, head_dim=64), _cfg(flags=UNF, dtype="f32"),
+                _cfg(flags=UNF | lf.LF_FLAG_ATTENTION_ONLY), _cfg(flags=UNF | lf.LF_FLAG_FORCE_VALU)):
+        assert L.longflow_workspace_bytes(ctypes.byref(bad)) == 0
+    a = lf.longflow_plan_info(_cfg(flags=lf.LF_FLAG_ATTENTION_ONLY))
+    u = lf.longflow_plan_info(_cfg(flags=UNF))
+    assert u.launches_per_step == a.launches_per_step + 3
+    assert (u.path, u.workgroups_per_unit, u.slots_per_workgroup) == (a.path, a.workgroups_per_unit, a.slots_per_workgroup)
