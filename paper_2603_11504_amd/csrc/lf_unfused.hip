@@ -135,41 +135,28 @@ __global__ __launch_bounds__(256) void unfused_accumulate_kernel(const UnfusedAr
             if (r == 0) *(f32x4 *)(acc_u + base + 4 * g) = upd;
         };
 
-        // Four register tiles rotate; the steady-state body has no branch between a load and
-        // its use, so every wait covers the oldest tile only and three stay in flight.
-        KTile ta, tb, tc, td;
-        if (n_my >= 4) {
+        // Two register tiles rotate; the steady-state body has no branch between a load and
+        // its use, so every wait covers the older tile only.  Few registers, many waves: the
+        // loads in flight come from occupancy rather than from a deep per-wave pipeline.
+        KTile ta, tb;
+        if (n_my >= 2) {
             load(ta, 0);
             load(tb, 1);
-            load(tc, 2);
-            load(td, 3);
             int i = 0;
-            for (; i + 7 < n_my; i += 4) {
+            for (; i + 3 < n_my; i += 2) {
                 consume(ta, i);
-                load(ta, i + 4);
+                load(ta, i + 2);
                 consume(tb, i + 1);
-                load(tb, i + 5);
-                consume(tc, i + 2);
-                load(tc, i + 6);
-                consume(td, i + 3);
-                load(td, i + 7);
+                load(tb, i + 3);
             }
-            // 4 to 7 tiles remain; the first four are on their way
+            // 2 or 3 tiles remain; the first two are on their way
             consume(ta, i);
-            if (i + 4 < n_my) load(ta, i + 4);
+            if (i + 2 < n_my) load(ta, i + 2);
             consume(tb, i + 1);
-            if (i + 5 < n_my) load(tb, i + 5);
-            consume(tc, i + 2);
-            if (i + 6 < n_my) load(tc, i + 6);
-            consume(td, i + 3);
-            if (i + 4 < n_my) consume(ta, i + 4);
-            if (i + 5 < n_my) consume(tb, i + 5);
-            if (i + 6 < n_my) consume(tc, i + 6);
-        } else {
-            for (int i = 0; i < n_my; ++i) {
-                load(ta, i);
-                consume(ta, i);
-            }
+            if (i + 2 < n_my) consume(ta, i + 2);
+        } else if (n_my == 1) {
+            load(ta, 0);
+            consume(ta, 0);
         }
     }
 
