@@ -366,6 +366,26 @@ LFO_API int lfo_cache_step(lfo_cache *c, const double *q, const double *k_new,
     return 0;
 }
 
+/*
+ * Fill phase in bulk: the next T tokens of a cache that has room for them
+ * (count + T <= N).  By definition T consecutive decode steps -- token t's
+ * query attends to the rows present after its own insert, i.e. causally
+ * (Sec. 2.1: prefill caches K, V; decoding appends one token's K, V and
+ * attends over all of them).  q [T][B][Hq][D], k_new, v_new [T][B][Hkv][D],
+ * out [T][B][Hq][D]; evict_idx [B][Hkv] is the last step's.
+ */
+LFO_API int lfo_cache_fill(lfo_cache *c, int T, const double *q, const double *k_new,
+                           const double *v_new, double *out, int32_t *evict_idx)
+{
+    if (T < 1 || c->mask || c->count + T > c->N) return 1;
+    const size_t nq = (size_t)c->B * c->Hq * c->D, nk = (size_t)c->B * c->Hkv * c->D;
+    for (int t = 0; t < T; ++t) {
+        int rc = lfo_cache_step(c, q + t * nq, k_new + t * nk, v_new + t * nk, out + t * nq, evict_idx);
+        if (rc) return rc;
+    }
+    return 0;
+}
+
 LFO_API int lfo_cache_count(const lfo_cache *c) { return c->count; }
 
 LFO_API void lfo_cache_scores(const lfo_cache *c, double *scores)

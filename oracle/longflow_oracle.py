@@ -52,6 +52,8 @@ def lib():
         L.lfo_cache_init.restype = ctypes.c_int
         L.lfo_cache_step.argtypes = [ctypes.c_void_p, _dp, _dp, _dp, _dp, _ip]
         L.lfo_cache_step.restype = ctypes.c_int
+        L.lfo_cache_fill.argtypes = [ctypes.c_void_p, ctypes.c_int, _dp, _dp, _dp, _dp, _ip]
+        L.lfo_cache_fill.restype = ctypes.c_int
         L.lfo_cache_count.argtypes = [ctypes.c_void_p]
         L.lfo_cache_count.restype = ctypes.c_int
         L.lfo_cache_scores.argtypes = [ctypes.c_void_p, _dp]
@@ -150,6 +152,19 @@ class OracleCache:
                                   idx.ctypes.data_as(_ip))
         if rc:
             raise RuntimeError("cache is full and has no pending slot")
+        return out, idx
+
+    def fill(self, q, k_new, v_new):
+        """The next T tokens of a filling cache at once: q [T,B,Hq,D], k_new, v_new [T,B,Hkv,D]
+        -> (out [T,B,Hq,D], evict_idx [B,Hkv] of the last token)."""
+        T = int(np.shape(q)[0])
+        q = _d(q, (T, self.B, self.Hq, self.D))
+        k = _d(k_new, (T, self.B, self.Hkv, self.D))
+        v = _d(v_new, (T, self.B, self.Hkv, self.D))
+        out = np.empty((T, self.B, self.Hq, self.D))
+        idx = np.empty((self.B, self.Hkv), dtype=np.int32)
+        if lib().lfo_cache_fill(self._h, T, _ptr(q), _ptr(k), _ptr(v), _ptr(out), idx.ctypes.data_as(_ip)):
+            raise ValueError("T tokens do not fit the free slots of a prefix-mode cache")
         return out, idx
 
     @property

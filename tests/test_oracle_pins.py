@@ -513,3 +513,40 @@ def test_accumulated_rule_leaves_the_longflow_rule_alone_and_takes_no_mask():
         b.set_mask(np.ones((B, Hkv, N)))
     with pytest.raises(ValueError):
         b.evict_lowest(1)
+
+
+# ---------------------------------------------------------------- bulk fill = causal multi-query attention
+
+def test_bulk_fill_is_causal_library_attention_and_ends_like_single_steps():
+    rng = np.random.default_rng(21)
+    B, Hkv, G, D, N, n0 = 2, 2, 3, 16, 12, 3
+    k0 = rng.standard_normal((B, Hkv, n0, D)); v0 = rng.standard_normal((B, Hkv, n0, D))
+    for T in (1, 4, N - n0):
+        c = oracle.OracleCache(B, Hkv * G, Hkv, D, N)
+        c.init(k0, v0)
+        q = rng.standard_normal((T, B, Hkv * G, D)) * 1.5
+        k = rng.standard_normal((T, B, Hkv, D)); v = rng.standard_normal((T, B, Hkv, D))
+        out, idx = c.fill(q, k, v)
+        assert c.count == n0 + T
+        Kall = np.concatenate([k0, k.transpose(1, 2, 0, 3)], axis=2)      # [B,Hkv,n0+T,D]
+        Vall = np.concatenate([v0, v.transpose(1, 2, 0, 3)], axis=2)
+        for t in range(T):
+            n = n0 + t + 1                                               # token t sees itself and everything before
+            for b in range(B):
+                for g in range(Hkv):
+                    w = scipy_softmax(q[t, b, g * G:(g + 1) * G] @ Kall[b, g, :n].T / math.sqrt(D), axis=1)
+                    np.testing.assert_allclose(out[t, b, g * G:(g + 1) * G], w @ Vall[b, g, :n], rtol=1e-11, atol=1e-13)
+        Kc, Vc = c.kv()
+        np.testing.assert_array_equal(Kc[:, :, :n0 + T], Kall)
+        np.testing.assert_array_equal(Vc[:, :, :n0 + T], Vall)
+        if n0 + T < N:
+            assert (idx == n0 + T).all()
+        else:  # the cache just became full: the slot is the argmin of the last token's scores
+            sc = c.scores()
+            assert (idx == sc.argmin(-1)).all()
+            _, s_last, _ = oracle.attend_unit(q[-1, 0, :G], Kall[0, 0], Vall[0, 0])
+            np.testing.assert_allclose(sc[0, 0], s_last, rtol=1e-13)
+    c = oracle.OracleCache(B, Hkv * G, Hkv, D, N)
+    c.init(k0, v0)
+    with pytest.raises(ValueError):
+        c.fill(np.zeros((N, B, Hkv * G, D)), np.zeros((N, B, Hkv, D)), np.zeros((N, B, Hkv, D)))   # too many
