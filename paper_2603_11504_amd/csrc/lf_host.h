@@ -88,6 +88,11 @@ hipError_t launch_unit_mfma_group(const Plan &p, const StepIo &io, int n, const 
 void unfused_geometry(int units, int N, int *LA, int *CA);
 hipError_t launch_unfused_step(const Plan &p, const StepIo &io, int n, hipStream_t s);
 hipError_t launch_unfused_scores(const Plan &p, float *scores, hipStream_t s); // float [units][N]
+// Fill phase in bulk (bf16, head_dim 128): rows n0 .. n0 + Tb - 1 from k_new / v_new ([Tb][units][128]), then
+// causal attention of the Tb queries ([Tb][units][G][128]) -> out, fill_tokens_per_pass(G) tokens per pass over the cache.
+int fill_tokens_per_pass(int G);
+hipError_t launch_fill_bulk(const Plan &p, const void *q, const void *k_new, const void *v_new, void *out, int n0,
+                            int Tb, hipStream_t s);
 hipError_t launch_scores(const Plan &p, int n, float *scores, hipStream_t s);
 // Drop the k lowest-scoring valid slots of every unit (scores of the last step, in double
 // precision via `scratch`, device double [units][N]); they become holes of the explicit mask.

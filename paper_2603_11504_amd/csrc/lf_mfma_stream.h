@@ -79,7 +79,8 @@ __device__ __forceinline__ uint32_t pack_bf16x2(float lo, float hi)
 }
 
 // MASKED: an explicit validity mask may be in force (NaN entries of the side array)
-template <int NWAVES, bool HILO, int STASH, bool MASKED = false>
+// CAUSAL: every column (lane r) has its own row limit: it sees slots below `limit` only
+template <int NWAVES, bool HILO, int STASH, bool MASKED = false, bool CAUSAL = false>
 struct MfmaStreamer {
     static constexpr int D = 128;
     // per-wave state
@@ -90,6 +91,7 @@ struct MfmaStreamer {
     const uint16_t *Ku, *Vu;
     const float *lu_unit; // [ntiles * 16] log2 ||v||_1 in position order
     int start, end, G, g, r;
+    int limit; // CAUSAL: first slot column r does not see
     float scale_log2;
     // stash sinks
     uint16_t *gs_w;   // kStashGlobal: [tile][G][16 positions] bf16
@@ -107,6 +109,24 @@ struct MfmaStreamer {
             for (int b = 0; b < 2; ++b) {
                 qreg[L][b] = u32x4{0u, 0u, 0u, 0u};
                 if (r < G) qreg[L][b] = *(const u32x4 *)(q_unit + (size_t)r * D + 64 * L + 8 * (2 * g + b));
+            }
+#pragma unroll
+        for (int dd = 0; dd < 8; ++dd) oacc[dd] = f32x4{0.f, 0.f, 0.f, 0.f};
+        m = kNoRef;
+        l = 0.f;
+    }
+
+    // One column of a multi-query product: the query row at q_col (nullptr = unused column),
+    // which sees slots [0, limit_) only.
+    __device__ __forceinline__ void init_column(const uint16_t *q_col, int limit_, int lane, float scale)
+    {
+        G = 16; g = lane >> 4; r = lane & 15; scale_log2 = scale; limit = q_col ? limit_ : 0;
+#pragma unroll
+        for (int L = 0; L < 2; ++L)
+#pragma unroll
+            for (int b = 0; b < 2; ++b) {
+                qreg[L][b] = u32x4{0u, 0u, 0u, 0u};
+                if (q_col) qreg[L][b] = *(const u32x4 *)(q_col + 64 * L + 8 * (2 * g + b));
             }
 #pragma unroll
         for (int dd = 0; dd < 8; ++dd) oacc[dd] = f32x4{0.f, 0.f, 0.f, 0.f};
@@ -172,6 +192,11 @@ struct MfmaStreamer {
 #pragma unroll
             for (int e = 0; e < 4; ++e)
                 if (base + slot_off(e) >= end) s[e] = -INFINITY;
+        }
+        if (CAUSAL) {
+#pragma unroll
+            for (int e = 0; e < 4; ++e)
+                if (base + slot_off(e) >= limit) s[e] = -INFINITY;
         }
         // ---- explicit mask (Alg. 1's M): a slot whose side-array entry is NaN is invalid;
         // its logit becomes -inf, hence p = 0 (its V row is kept finite by the mask setter)

@@ -300,6 +300,41 @@ int longflow_decode_step(longflow_cache_t *cache, const void *q, const void *k_n
     return LF_OK;
 }
 
+int longflow_fill_steps(longflow_cache_t *cache, int32_t T, const void *q, const void *k_new, const void *v_new,
+                        void *out, int32_t *evict_idx, void *hip_stream)
+{
+    longflow_cache *c = checked(cache);
+    if (!c) return fail(LF_ERR_STATE, "invalid or destroyed cache handle");
+    const Plan &p = c->plan;
+    if (p.unfused) return fail(LF_ERR_UNSUPPORTED, "the unfused comparison path has no bulk fill");
+    if (p.flags & LF_FLAG_ATTENTION_ONLY) return fail(LF_ERR_UNSUPPORTED, "an attention-only cache takes no tokens");
+    if (p.masked) return fail(LF_ERR_UNSUPPORTED, "bulk fill needs a cache without an explicit mask");
+    if (!q || !k_new || !v_new || !out) return fail(LF_ERR_INVALID_ARG, "q/k_new/v_new/out is NULL");
+    if (((uintptr_t)q & 15u) || ((uintptr_t)out & 15u) || ((uintptr_t)k_new & 15u) || ((uintptr_t)v_new & 15u))
+        return fail(LF_ERR_INVALID_ARG, "q/k_new/v_new/out must be 16-byte aligned");
+    if (T < 1 || c->count + (long long)T > p.N)
+        return fail(LF_ERR_INVALID_ARG, "T = %d tokens do not fit: %d of %d slots are taken", T, c->count, p.N);
+    hipStream_t s = (hipStream_t)hip_stream;
+    const size_t esz = p.dtype == LF_F32 ? 4 : 2;
+    const size_t q_step = esz * (size_t)p.B * p.Hq * p.D, kv_step = esz * (size_t)p.B * p.Hkv * p.D;
+    // all but the last token in bulk where that pays; the last one takes the ordinary step, which
+    // also leaves what longflow_scores needs and makes the eviction decision if the cache is now full
+    int Tb = 0;
+    if (p.use_mfma && T - 1 >= fill_tokens_per_pass(p.G)) {
+        Tb = T - 1;
+        hipError_t e = launch_fill_bulk(p, q, k_new, v_new, out, c->count, Tb, s);
+        if (e == hipSuccess) e = launch_fill_i32(p.pending, p.units, c->count + Tb, s);
+        if (e != hipSuccess) return fail(LF_ERR_HIP, "bulk fill launch: %s", hipGetErrorString(e));
+        c->count += Tb;
+    }
+    for (int t = Tb; t < T; ++t) {
+        const int rc = longflow_decode_step(cache, (const char *)q + t * q_step, (const char *)k_new + t * kv_step,
+                                            (const char *)v_new + t * kv_step, (char *)out + t * q_step, evict_idx, hip_stream);
+        if (rc != LF_OK) return rc;
+    }
+    return LF_OK;
+}
+
 int longflow_scores(longflow_cache_t *cache, float *scores, void *hip_stream)
 {
     longflow_cache *c = checked(cache);

@@ -23,7 +23,7 @@ LF_FLAG_FORCE_UNIT = 8
 LF_FLAG_UNFUSED_ACCUM = 16
 
 EXPORTS = ("longflow_workspace_bytes", "longflow_init_cache", "longflow_decode_step",
-           "longflow_scores", "longflow_set_pending", "longflow_set_mask", "longflow_get_mask", "longflow_evict_scratch_bytes",
+           "longflow_fill_steps", "longflow_scores", "longflow_set_pending", "longflow_set_mask", "longflow_get_mask", "longflow_evict_scratch_bytes",
            "longflow_evict_lowest", "longflow_valid_count",
            "longflow_destroy_cache", "longflow_last_error", "longflow_profile_begin",
            "longflow_profile_end", "longflow_plan_info", "longflow_group_workspace_bytes", "longflow_group_create",
@@ -70,6 +70,8 @@ def lib():
         L.longflow_init_cache.restype = ctypes.c_int
         L.longflow_decode_step.argtypes = [vp] * 7
         L.longflow_decode_step.restype = ctypes.c_int
+        L.longflow_fill_steps.argtypes = [vp, i32, vp, vp, vp, vp, vp, vp]
+        L.longflow_fill_steps.restype = ctypes.c_int
         L.longflow_scores.argtypes = [vp, vp, vp]
         L.longflow_scores.restype = ctypes.c_int
         L.longflow_set_pending.argtypes = [vp, vp, vp]
@@ -168,6 +170,16 @@ class LongFlowCache:
         evict_idx = self.evict_idx if evict_idx is None else evict_idx
         _check(lib().longflow_decode_step(self._h, _ptr(q), _ptr(k_new), _ptr(v_new), _ptr(out),
                                           _ptr(evict_idx), _stream()))
+        return out, evict_idx
+
+    def fill_steps(self, q, k_new, v_new, out=None, evict_idx=None):
+        """The next T tokens of a filling cache at once: q [T,B,Hq,D], k_new, v_new [T,B,Hkv,D]
+        (contiguous) -> (out [T,B,Hq,D], evict_idx [B,Hkv] as after the last of them)."""
+        T = int(q.shape[0])
+        if out is None:
+            out = torch.empty((T, self.cfg.batch, self.cfg.q_heads, self.cfg.head_dim), dtype=self.dtype, device=self.device)
+        evict_idx = self.evict_idx if evict_idx is None else evict_idx
+        _check(lib().longflow_fill_steps(self._h, T, _ptr(q), _ptr(k_new), _ptr(v_new), _ptr(out), _ptr(evict_idx), _stream()))
         return out, evict_idx
 
     def scores(self):
