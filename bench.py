@@ -45,6 +45,9 @@ def parse():
     ap.add_argument("--unit", action="store_true", help="force the one-workgroup-per-unit fused path")
     ap.add_argument("--unfused", action="store_true",
                     help="bf16/head_dim 128: the unfused comparison path (accumulated attention weights, Fig. 1)")
+    ap.add_argument("--fill", action="store_true",
+                    help="time filling one empty cache of the workload's geometry to the brim: one longflow_fill_steps call "
+                         "against the same tokens as consecutive decode steps")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run one 1 GiB device copy (a kernel of known traffic, to scale rocprofv3 byte counters)")
@@ -229,6 +232,58 @@ def measure(wl, flags, steps, warmup, pool=0, with_cpu=False, calibrate_copy=Fal
     return res
 
 
+def fill_bench(a):
+    """Fill phase: N tokens into an empty cache, in bulk and step by step (one layer of the workload)."""
+    import torch
+    from paper_2603_11504_amd import longflow as lf
+    from paper_2603_11504_amd import workloads as W
+    wl = W.scaled(W.CONFIGS[int(a.workload.replace("cfg", ""))], layers=1, n_init=0)
+    dev = torch.device("cuda:0")
+    dt = W.torch_dtype(wl)
+    T = wl.budget
+    g = torch.Generator(device=dev).manual_seed(wl.seed)
+    q = torch.randn((T, wl.batch, wl.q_heads, wl.head_dim), device=dev, dtype=torch.float32, generator=g).to(dt)
+    k = torch.randn((T, wl.batch, wl.kv_heads, wl.head_dim), device=dev, dtype=torch.float32, generator=g).to(dt)
+    v = torch.randn((T, wl.batch, wl.kv_heads, wl.head_dim), device=dev, dtype=torch.float32, generator=g).to(dt)
+    out = torch.empty_like(q)
+
+    def fresh():
+        return lf.LongFlowCache(wl.batch, wl.q_heads, wl.kv_heads, wl.head_dim, wl.budget, dtype=dt, device=dev)
+
+    def timed(fn):
+        c = fresh()
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        fn(c)
+        torch.cuda.synchronize()
+        dt_s = time.perf_counter() - t0
+        assert c.valid_count == wl.budget
+        c.close()
+        return dt_s
+
+    def bulk(c):
+        c.fill_steps(q, k, v, out=out)
+
+    def steps(c):
+        for t in range(T):
+            c.decode_step(q[t], k[t], v[t], out=out[t])
+
+    timed(bulk)                                     # warm-up (code objects, allocator)
+    t_bulk = min(timed(bulk) for _ in range(3))
+    t_steps = timed(steps)
+    esz = wl.elem_bytes
+    row = 2 * wl.units * wl.head_dim * esz          # K and V row of every unit
+    bytes_steps = row * T * (T + 1) // 2            # step t reads t + 1 rows
+    print(json.dumps({
+        "metric": "fill_tokens_per_s", "unit": "tokens/s", "value": wl.batch * T / t_bulk,
+        "config": {"workload": wl.name + "_fill_from_empty", "batch": wl.batch, "q_heads": wl.q_heads,
+                   "kv_heads": wl.kv_heads, "head_dim": wl.head_dim, "budget": wl.budget, "tokens_per_sequence": T},
+        "bulk_s": t_bulk, "step_by_step_s": t_steps, "speedup": t_steps / t_bulk,
+        "step_by_step_tokens_per_s": wl.batch * T / t_steps,
+        "step_by_step_hbm_GBs": bytes_steps / t_steps / 1e9,
+        "dtype": "f32" if wl.dtype == "f32" else "bf16", "data": "synthetic", "n_gpus": 1}))
+
+
 def report(a):
     """Table over all BASELINE workloads plus the uncompressed twin of cfg4 (plain attention
     over all 81920 tokens, the kernel-level analogue of the paper's FullKV comparison)."""
@@ -277,6 +332,9 @@ def main():
 
     if a.report:
         report(a)
+        return
+    if a.fill:
+        fill_bench(a)
         return
     idx = int(a.workload.replace("cfg", ""))
     wl = W.CONFIGS[idx]

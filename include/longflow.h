@@ -145,7 +145,7 @@ LF_API int longflow_decode_step(longflow_cache_t *cache, const void *q,
  * While a cache is filling nothing is evicted, so the steps depend on each other
  * only through the appended rows: bf16 / head_dim 128 caches write all rows first
  * and take the queries through attention several at a time, reading the cache once
- * per 2 * floor(16 / (Hq/Hkv)) tokens; other caches run the T steps one by one.
+ * per 4 * floor(16 / (Hq/Hkv)) tokens; other caches run the T steps one by one.
  *   q           device [T][B][Hq][D]
  *   k_new,v_new device [T][B][Hkv][D]
  *   out         device [T][B][Hq][D]

@@ -6,8 +6,10 @@
 // through attention several at a time, each column of the S^T = K Q^T product carrying one
 // (token, head) pair with its own causal row limit.  A 16-column product holds floor(16 / G)
 // tokens, and a workgroup streams K and V once for NB such products: the cache is read
-// once per NB * floor(16 / G) tokens instead of once per token.  The matrix pipe, ~13 %
-// busy in the single-query kernel, has the room.
+// once per NB * floor(16 / G) tokens instead of once per token.  The matrix and vector
+// pipes, 13 % and 23 % busy in the single-query kernel, have the room: NB = 4 is where the
+// per-tile arithmetic of a wave catches up with its share of HBM bandwidth (it costs the
+// whole register file, one wave per SIMD; NB = 2 at two waves per SIMD is 25 % slower).
 #include "lf_mfma_stream.h"
 
 namespace lf {
@@ -45,7 +47,7 @@ __global__ __launch_bounds__(256) void fill_insert_kernel(const FillArgs a)
 // One workgroup = one (unit, group of NB * qpb consecutive tokens); its 4 waves share the
 // tiles of rows [0, n0 + last token + 1) and merge at the end.
 template <int NB>
-__global__ __launch_bounds__(256, 2) void fill_attend_kernel(const FillArgs a)
+__global__ __launch_bounds__(256) void fill_attend_kernel(const FillArgs a)
 {
     constexpr int D = 128;
     typedef MfmaStreamer<4, true, kStashNone, false, true> Streamer;
@@ -140,7 +142,7 @@ __global__ __launch_bounds__(256, 2) void fill_attend_kernel(const FillArgs a)
     }
 }
 
-int fill_tokens_per_pass(int G) { return 2 * (16 / G); }
+int fill_tokens_per_pass(int G) { return 4 * (16 / G); }
 
 hipError_t launch_fill_bulk(const Plan &p, const void *q, const void *k_new, const void *v_new, void *out, int n0,
                             int Tb, hipStream_t s)
@@ -159,7 +161,7 @@ hipError_t launch_fill_bulk(const Plan &p, const void *q, const void *k_new, con
     hipLaunchKernelGGL(fill_insert_kernel, dim3((unsigned)blocks), dim3(256), 0, s, a);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
-    constexpr int NB = 2;
+    constexpr int NB = 4;
     const int QW = NB * a.qpb;
     const long long wgs = (long long)((Tb + QW - 1) / QW) * p.units;
     hipLaunchKernelGGL((fill_attend_kernel<NB>), dim3((unsigned)wgs), dim3(256), 0, s, a);
