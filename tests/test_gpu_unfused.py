@@ -110,3 +110,35 @@ def test_unsupported_combinations_are_refused():
     info = lf.longflow_plan_info(c.cfg)
     assert info.launches_per_step >= 4
     torch.cuda.synchronize()
+
+
+def test_unfused_steps_replayed_from_a_hip_graph_match_eager():
+    # the four launches of a step are plain kernels: a caller may capture steady-state steps
+    wl = _wl("unf_graph", 4, 28, 4, 1024, n_init=1023, steps=8, seed=72)
+    k0, v0 = W.host_prefill(wl)
+    mk = lambda: lf.LongFlowCache(wl.batch, wl.q_heads, wl.kv_heads, wl.head_dim, wl.budget, flags=UNF,
+                                  k_init=W.to_torch(k0, wl, "cuda"), v_init=W.to_torch(v0, wl, "cuda"))
+    eager, graphed = mk(), mk()
+    qs, ks, vs = (torch.empty_like(W.to_torch(x, wl, "cuda")) for x in W.host_step(wl, 0))
+    for t in range(2):
+        for dst, src in zip((qs, ks, vs), W.host_step(wl, t)):
+            dst.copy_(W.to_torch(src, wl, "cuda"))
+        eager.decode_step(qs, ks, vs)
+        graphed.decode_step(qs, ks, vs)
+    torch.cuda.synchronize()
+    g = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(g):
+        graphed.decode_step(qs, ks, vs)
+    for t in range(2, 8):
+        for dst, src in zip((qs, ks, vs), W.host_step(wl, t)):
+            dst.copy_(W.to_torch(src, wl, "cuda"))
+        o_e, i_e = eager.decode_step(qs, ks, vs)
+        o_e, i_e = o_e.clone(), i_e.clone()
+        g.replay()
+        torch.cuda.synchronize()
+        assert torch.equal(o_e.view(torch.int16), graphed.out.view(torch.int16)), f"replay {t}"
+        assert torch.equal(i_e, graphed.evict_idx), f"replay {t}"
+        junk = torch.randn(1 << 20, device="cuda").sum().item()
+        assert junk == junk
+    assert torch.equal(eager.scores(), graphed.scores())
+    assert torch.equal(eager.k_cache.view(torch.int16), graphed.k_cache.view(torch.int16))
