@@ -760,13 +760,13 @@ static size_t code_bytes(int slots, int G)
 }
 
 // workgroups per unit: one when the units alone fill the chip, else enough to put a
-// workgroup on (about) every compute unit, each with at least 512 slots
+// workgroup on (about) every compute unit, each with at least 256 slots
 int unit_mfma_splits(int units, int N)
 {
     if (units >= 192) return 1;
     int S = 256 / units;
     if (S > 8) S = 8;
-    while (S > 1 && (N + S - 1) / S < 512) --S;
+    while (S > 1 && (N + S - 1) / S < 256) --S;
     return S < 1 ? 1 : S;
 }
 

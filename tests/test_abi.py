@@ -134,7 +134,7 @@ def test_plan_of_the_baseline_workloads():
     for wl in W.CONFIGS:
         i = lf.longflow_plan_info(lf.make_config(wl.batch, wl.q_heads, wl.kv_heads, wl.head_dim, wl.budget, wl.dtype, 0))
         got.append((lf.PATH_KERNELS[i.path], i.workgroups_per_unit, i.slots_per_workgroup))
-    assert got == [("split_valu_kernel", 1, 256), ("unit_mfma_kernel", 4, 512), ("unit_mfma_kernel", 2, 2048),
+    assert got == [("split_valu_kernel", 1, 256), ("unit_mfma_kernel", 8, 256), ("unit_mfma_kernel", 2, 2048),
                    ("unit_mfma_kernel", 1, 8192), ("unit_mfma_kernel", 1, 16384)]
 
 
