@@ -109,6 +109,7 @@ def test_cfg4_full_size_sampled_units():
     (48, 8, 4, 20000, 8),    # one workgroup per unit, more slots than its register window screens in one pass
     (1, 8, 2, 60000, None),  # eight workgroups per unit
     (1, 7, 1, 200000, None), # codes exceed LDS even eight ways: the split-K path is chosen by itself
+    (1, 2, 1, 1 << 24, None), # the largest budget the interface accepts (4 GiB of K, 4 GiB of V in one unit)
 ])
 def test_long_budgets(B, Hq, Hkv, N, sample):
     wl = _small(f"long_{N}", "bf16", B, Hq, Hkv, 128, N, n_init=N - 2, steps=5, sink_scale=4.0, seed=N)
