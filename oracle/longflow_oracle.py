@@ -126,9 +126,12 @@ class OracleCache:
             raise ValueError("importance rule refused")
 
     def __del__(self):
-        if getattr(self, "_h", None):
-            lib().lfo_cache_destroy(self._h)
-            self._h = None
+        try:
+            if getattr(self, "_h", None):
+                lib().lfo_cache_destroy(self._h)
+                self._h = None
+        except Exception:       # interpreter shutdown: module globals may already be gone
+            pass
 
     def init(self, k_init=None, v_init=None):
         n_init = 0 if k_init is None else int(np.shape(k_init)[2])
