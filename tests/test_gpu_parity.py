@@ -122,6 +122,18 @@ def test_long_budgets(B, Hq, Hkv, N, sample):
     torch.cuda.empty_cache()
 
 
+@pytest.mark.parametrize("flags", [0, lf.LF_FLAG_FORCE_SPLIT], ids=["unit", "split"])
+def test_largest_unit_count_the_interface_accepts(flags):
+    # 2^20 (batch, KV head) units of 16 slots: one workgroup each, 4 GiB of K and of V
+    wl = _small("max_units", "bf16", 131072, 8, 8, 128, 16, n_init=13, steps=8, sink_scale=4.0, seed=5)
+    units = np.unique(np.concatenate([[0, wl.units - 1], np.random.default_rng(1).choice(wl.units, 200)]))
+    rep, gpu, _ = run_lockstep(wl, host_inputs=False, check_scores_every=7, units=units, flags=flags)
+    assert rep.steps == 8
+    gpu.close()
+    del gpu
+    torch.cuda.empty_cache()
+
+
 # ------------------------------------------------------------------ edge cases
 
 @pytest.mark.parametrize("flags", [lf.LF_FLAG_FORCE_SPLIT, lf.LF_FLAG_FORCE_UNIT], ids=["split", "unit"])
