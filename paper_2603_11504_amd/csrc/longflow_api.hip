@@ -322,7 +322,14 @@ int longflow_fill_steps(longflow_cache_t *cache, int32_t T, const void *q, const
     int Tb = 0;
     if (p.use_mfma && T - 1 >= fill_tokens_per_pass(p.G)) {
         Tb = T - 1;
-        hipError_t e = launch_fill_bulk(p, q, k_new, v_new, out, c->count, Tb, s);
+        // one workgroup per (unit, group of tokens): keep each launch's grid below 2^30 workgroups
+        const long long per_launch = std::max(1ll, (1ll << 30) / p.units) * fill_tokens_per_pass(p.G);
+        hipError_t e = hipSuccess;
+        for (long long done = 0; done < Tb && e == hipSuccess; done += per_launch) {
+            const int Tc = (int)std::min<long long>(per_launch, Tb - done);
+            e = launch_fill_bulk(p, (const char *)q + done * q_step, (const char *)k_new + done * kv_step,
+                                 (const char *)v_new + done * kv_step, (char *)out + done * q_step, c->count + (int)done, Tc, s);
+        }
         if (e == hipSuccess) e = launch_fill_i32(p.pending, p.units, c->count + Tb, s);
         if (e != hipSuccess) return fail(LF_ERR_HIP, "bulk fill launch: %s", hipGetErrorString(e));
         c->count += Tb;
