@@ -436,6 +436,12 @@ int longflow_group_create(longflow_group_t **group, longflow_cache_t *const *cac
             return fail(LF_ERR_STATE, "member %d differs from member 0 in whether a mask is in force", i);
         members.push_back(c);
     }
+    {   // one grid serves all members: it must stay a valid launch
+        const Plan &p0 = members[0]->plan;
+        const long long per_cache = (long long)p0.units * std::max(p0.C, p0.unit_S);
+        if (per_cache * n_caches >= (1ll << 31))
+            return fail(LF_ERR_UNSUPPORTED, "%d caches of %d units are more workgroups than one launch takes", n_caches, p0.units);
+    }
     // one entry per member, in the layout of the kernel family its plan uses
     const bool unit = members[0]->plan.use_unit;
     const size_t eb = unit ? unit_mfma_table_entry_bytes() : split_table_entry_bytes();
