@@ -31,6 +31,9 @@ MEASURED_TRAFFIC = {
                                                             "source": "profiles/unit_mfma_kernel_cfg2.txt"},
     ("cfg4_bf16_b128_40x8_d128_n16384", "unit_mfma_kernel"): {"read_bytes": 8458713 * 1024, "write_bytes": 3264 * 1024,
                                                               "source": "profiles/unit_mfma_kernel_cfg4.txt"},
+    # the four launches of an unfused step together
+    ("cfg3_bf16_b64_28x4_d128_n8192_l28", "unfused+unit_mfma_kernel"): {
+        "read_bytes": 1585817 * 1024, "write_bytes": 9386 * 1024, "source": "profiles/unfused_comparison_path_cfg3_cfg4.txt"},
 }
 
 
