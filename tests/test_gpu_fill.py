@@ -156,3 +156,11 @@ def test_bulk_fill_argument_errors():
     with pytest.raises(lf.LongFlowError):
         ao.fill_steps(q[:1], kv[:1], kv[:1])
     torch.cuda.synchronize()
+
+
+def test_bulk_fill_of_degenerate_budgets():
+    for N in (1, 2, 3, 15, 16, 17):
+        wl = _wl(f"fill_tiny_{N}", "bf16", 2, 2, 2, 128, N, seed=300 + N)       # G = 1: 64 tokens per pass
+        _fill_and_compare(wl, [N], tail_steps=4)
+        if N > 2:
+            _fill_and_compare(wl, [1, N - 2, 1], tail_steps=2)

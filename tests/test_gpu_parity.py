@@ -136,6 +136,21 @@ def test_largest_unit_count_the_interface_accepts(flags):
 
 # ------------------------------------------------------------------ edge cases
 
+@pytest.mark.parametrize("dtype,D,flags", [("f32", 64, 0), ("f32", 128, 0), ("bf16", 64, 0), ("bf16", 128, lf.LF_FLAG_FORCE_UNIT),
+                                           ("bf16", 128, lf.LF_FLAG_FORCE_SPLIT), ("bf16", 128, lf.LF_FLAG_FORCE_VALU)],
+                         ids=["f32-64", "f32-128", "bf16-64", "unit", "split", "valu"])
+def test_degenerate_budgets_of_a_few_slots(dtype, D, flags):
+    # N = 1: every token replaces the only slot and attention returns its own value row;
+    # N = 2, 3: the argmin runs over a handful of slots; 15, 16, 17: around one tile
+    for N in (1, 2, 3, 15, 16, 17):
+        wl = _small(f"tiny_{N}", dtype, 2, 6, 2, D, N, steps=N + 12, sink_scale=4.0, seed=300 + N)
+        rep, gpu, ora = run_lockstep(wl, flags=flags, check_scores_every=1)
+        assert rep.steps == N + 12
+        if N == 1:
+            assert (gpu.evict_idx.cpu().numpy() == 0).all()
+
+
+
 @pytest.mark.parametrize("flags", [lf.LF_FLAG_FORCE_SPLIT, lf.LF_FLAG_FORCE_UNIT], ids=["split", "unit"])
 def test_deterministic_bitwise(flags):
     wl = _small("det", "bf16", 4, 28, 4, 128, 700, n_init=699, steps=20, seed=11)

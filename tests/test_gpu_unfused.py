@@ -142,3 +142,10 @@ def test_unfused_steps_replayed_from_a_hip_graph_match_eager():
         assert junk == junk
     assert torch.equal(eager.scores(), graphed.scores())
     assert torch.equal(eager.k_cache.view(torch.int16), graphed.k_cache.view(torch.int16))
+
+
+def test_degenerate_budgets_of_a_few_slots():
+    for N in (1, 2, 3, 15, 16, 17):
+        wl = _wl(f"unf_tiny_{N}", 2, 6, 2, N, steps=N + 12, sink_scale=4.0, seed=300 + N)
+        rep, gpu, _ = run_lockstep(wl, flags=UNF, rule=RULE, check_scores_every=1)
+        assert rep.steps == N + 12
