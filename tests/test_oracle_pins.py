@@ -550,3 +550,18 @@ def test_bulk_fill_is_causal_library_attention_and_ends_like_single_steps():
     c.init(k0, v0)
     with pytest.raises(ValueError):
         c.fill(np.zeros((N, B, Hkv * G, D)), np.zeros((N, B, Hkv, D)), np.zeros((N, B, Hkv, D)))   # too many
+
+
+@pytest.mark.parametrize("rule", ["longflow", "accumulated_attention"])
+def test_single_slot_budget_returns_the_new_value_row_and_recycles_slot_zero(rule):
+    rng = np.random.default_rng(13)
+    B, Hkv, G, D = 2, 2, 3, 8
+    c = oracle.OracleCache(B, Hkv * G, Hkv, D, 1, rule=rule)
+    c.init()
+    for t in range(5):
+        q = rng.standard_normal((B, Hkv * G, D)); k = rng.standard_normal((B, Hkv, D)); v = rng.standard_normal((B, Hkv, D))
+        out, idx = c.step(q, k, v)
+        assert (idx == 0).all() and c.count == 1
+        np.testing.assert_allclose(out.reshape(B, Hkv, G, D), np.broadcast_to(v[:, :, None], (B, Hkv, G, D)), rtol=1e-15)
+        want = G * np.abs(v).sum(-1) if rule == "longflow" else np.full((B, Hkv), float(G))   # one slot holds all the weight
+        np.testing.assert_allclose(c.scores()[..., 0], want, rtol=1e-14)
