@@ -72,6 +72,8 @@ def kernel_name(wl, flags):
     from paper_2603_11504_amd import longflow as lf
     cfg = lf.make_config(wl.batch, wl.q_heads, wl.kv_heads, wl.head_dim, wl.budget, wl.dtype, flags)
     name = lf.PATH_KERNELS[lf.longflow_plan_info(cfg).path]
+    if flags & lf.LF_FLAG_MAX_FREE:
+        name += "+max_free"
     return "unfused+" + name if flags & lf.LF_FLAG_UNFUSED_ACCUM else name
 
 
@@ -295,6 +297,13 @@ def report(a):
     rows = [(W.CONFIGS[i], 0, DEFAULT_STEPS[i]) for i in range(5)]
     twin = W.scaled(W.CONFIGS[4], name="cfg4_uncompressed_twin_n81920", budget=81920, n_init=81920)
     rows.append((twin, lf.LF_FLAG_ATTENTION_ONLY, 10))
+    # plain attention with the running softmax reference (default) and as Alg. 1 prints it (max-free), A/B
+    AO, MF = lf.LF_FLAG_ATTENTION_ONLY, lf.LF_FLAG_ATTENTION_ONLY | lf.LF_FLAG_MAX_FREE
+    c3 = W.CONFIGS[3]
+    for rep in range(2):
+        rows.append((W.scaled(c3, name=f"cfg3_plain_attention_run{rep}", n_init=c3.budget), AO, 64))
+        rows.append((W.scaled(c3, name=f"cfg3_plain_attention_max_free_run{rep}", n_init=c3.budget), MF, 64))
+    rows.append((W.scaled(twin, name="cfg4_uncompressed_twin_n81920_max_free"), MF, 10))
     # the geometry of the paper's own kernel measurement (Fig. 1: Qwen3-8B, batch 128, 3200 slots)
     fig1 = W.scaled(W.CONFIGS[4], name="paper_fig1_geometry_b128_32x8_n3200", q_heads=32, kv_heads=8,
                     budget=3200, n_init=3199)
@@ -314,7 +323,7 @@ def report(a):
     for wl, flags, steps in rows:
         if a.steps:
             steps = a.steps
-        r = measure(wl, flags, steps, a.warmup, per_step_times=True, also_grouped=wl.layers > 1 and not flags & lf.LF_FLAG_UNFUSED_ACCUM)
+        r = measure(wl, flags, steps, a.warmup, per_step_times=True, also_grouped=wl.layers > 1 and not flags & (lf.LF_FLAG_UNFUSED_ACCUM | lf.LF_FLAG_MAX_FREE))
         s = r["step_us_sorted"]
         p10, med, p90 = s[len(s) // 10], s[len(s) // 2], s[(9 * len(s)) // 10]
         print(f"{wl.name:44s} {r['kernel']:26s} {p10:11.1f} {med:9.1f} {p90:9.1f} {r['ms_per_step'] * 1e3 / wl.layers:9.1f} "

@@ -92,6 +92,13 @@ typedef enum { LF_F32 = 0, LF_BF16 = 1 } lf_dtype;
                                      the accumulated weights; masks, batch eviction and groups
                                      are LF_ERR_UNSUPPORTED.                                  */
 
+#define LF_FLAG_MAX_FREE 32u      /* with LF_FLAG_ATTENTION_ONLY, bf16 / head_dim 128, fused kernel:
+                                     the softmax exactly as Alg. 1 prints it (Sec. 3.4,
+                                     modification 2) -- no running reference, p = exp(s) in
+                                     fp32, normalised at the end.  Same value while every
+                                     |s| stays below ~88; non-finite output beyond.  For A/B
+                                     measurement against the default, which keeps a reference. */
+
 typedef struct {
     int32_t batch;    /* B   >= 1                                            */
     int32_t q_heads;  /* Hq, a multiple of kv_heads; Hq/Hkv <= 16 (f32: <= 8) */

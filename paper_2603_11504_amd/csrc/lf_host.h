@@ -25,6 +25,7 @@ struct Plan {
     int unit_S;        // ... with this many cooperating workgroups per unit
     bool masked;       // an explicit validity mask is in force (state, set by longflow_set_mask)
     bool unfused;      // comparison path: plain attention kernel, then separate importance kernels
+    bool max_free;     // attention only: softmax without a running reference (A/B measurement)
     // device pointers (caller-owned)
     void *k_cache, *v_cache;
     // carved out of the caller's workspace

@@ -80,7 +80,9 @@ __device__ __forceinline__ uint32_t pack_bf16x2(float lo, float hi)
 
 // MASKED: an explicit validity mask may be in force (NaN entries of the side array)
 // CAUSAL: every column (lane r) has its own row limit: it sees slots below `limit` only
-template <int NWAVES, bool HILO, int STASH, bool MASKED = false, bool CAUSAL = false>
+// MAXFREE: the softmax of Alg. 1 as printed (Sec. 3.4, modification 2): no running reference,
+//          p = 2^t in fp32; overflows once a logit passes 2^128.  For A/B measurement.
+template <int NWAVES, bool HILO, int STASH, bool MASKED = false, bool CAUSAL = false, bool MAXFREE = false>
 struct MfmaStreamer {
     static constexpr int D = 128;
     // per-wave state
@@ -112,7 +114,7 @@ struct MfmaStreamer {
             }
 #pragma unroll
         for (int dd = 0; dd < 8; ++dd) oacc[dd] = f32x4{0.f, 0.f, 0.f, 0.f};
-        m = kNoRef;
+        m = MAXFREE ? 0.f : kNoRef;
         l = 0.f;
     }
 
@@ -130,7 +132,7 @@ struct MfmaStreamer {
             }
 #pragma unroll
         for (int dd = 0; dd < 8; ++dd) oacc[dd] = f32x4{0.f, 0.f, 0.f, 0.f};
-        m = kNoRef;
+        m = MAXFREE ? 0.f : kNoRef;
         l = 0.f;
     }
 
@@ -206,7 +208,7 @@ struct MfmaStreamer {
         }
         // ---- online softmax with a lazily raised reference
         const float mx = fmaxf(fmaxf(s[0], s[1]), fmaxf(s[2], s[3])) * scale_log2;
-        if (__any(mx > m + kMaxSlack)) { // rare: first tile, or a logit far above everything so far
+        if (!MAXFREE && __any(mx > m + kMaxSlack)) { // rare: first tile, or a logit far above everything so far
             float mw = fmaxf(mx, __shfl_xor(mx, 16));
             mw = fmaxf(mw, __shfl_xor(mw, 32));
             const float m_new = (mw > m + kMaxSlack) ? mw : m;

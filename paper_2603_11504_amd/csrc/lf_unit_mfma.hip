@@ -188,7 +188,8 @@ __device__ bool fill_lowest_hole(const float *lu_u, int npos, int N, int ins_slo
 // COOP: several workgroups may share a unit (s_active can exceed 1)
 // GATHER (with COOP): the deciding workgroup copies the others' code dumps into LDS chunk by
 // chunk before screening them; without it, it reads them in place, item by item
-template <bool HILO, int STASH, bool COOP, bool GROUPED, bool MASKED, bool GATHER>
+// MAXFREE (attention only): softmax without a running reference, for A/B measurement
+template <bool HILO, int STASH, bool COOP, bool GROUPED, bool MASKED, bool GATHER, bool MAXFREE = false>
 __global__ __launch_bounds__(512, 1) void unit_mfma_kernel(const UnitArgs a_in, const GroupArgs ga)
 {
     UnitArgs a = a_in;
@@ -269,7 +270,7 @@ __global__ __launch_bounds__(512, 1) void unit_mfma_kernel(const UnitArgs a_in, 
     if (sp == 0)
         for (int i = tid; i < G * D; i += 512) a.q_last[(size_t)u * G * D + i] = qu[i];
 
-    MfmaStreamer<NW, HILO, STASH, MASKED> st;
+    MfmaStreamer<NW, HILO, STASH, MASKED, false, MAXFREE> st;
     st.init(qu, G, lane, a.scale_log2);
     st.Ku = Ku;
     st.Vu = Vu;
@@ -785,6 +786,47 @@ size_t unit_mfma_lds_bytes(int N, int G, bool stash, int S)
     return (codes + 255) / 256 * 256 + merge;
 }
 
+// One launch of one kernel instance.  The dynamic-LDS ceiling is a per-device function
+// attribute: it is raised once per device and instance (attr_done, indexed by idx).
+struct UnitLaunch {
+    bool *attr_done;
+    long long wgs;
+    size_t lds;
+    hipStream_t s;
+    const UnitArgs *a;
+    const GroupArgs *ga;
+    bool masked, gather;
+};
+
+template <int STASH, bool COOP, bool GROUPED, bool MASKED, bool GATHER, bool MAXFREE>
+static hipError_t launch_instance(const UnitLaunch &ul, int idx)
+{
+    auto kern = unit_mfma_kernel<true, STASH, COOP, GROUPED, MASKED, GATHER, MAXFREE>;
+    if (!ul.attr_done[idx]) {
+        hipError_t e = hipFuncSetAttribute((const void *)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)kUnitLdsLimit);
+        if (e != hipSuccess) return e;
+        ul.attr_done[idx] = true;
+    }
+    hipLaunchKernelGGL(kern, dim3((unsigned)ul.wgs), dim3(512), ul.lds, ul.s, *ul.a, *ul.ga);
+    return hipGetLastError();
+}
+
+// The instances a (STASH, COOP, GROUPED) family really has: MASKED only where slots are
+// scored, GATHER only where cooperating workgroups screen each other's codes.
+template <int STASH, bool COOP, bool GROUPED>
+static hipError_t launch_family(const UnitLaunch &ul, int idx)
+{
+    if constexpr (STASH == kStashLds) {
+        if constexpr (COOP) {
+            if (ul.gather)
+                return ul.masked ? launch_instance<STASH, COOP, GROUPED, true, true, false>(ul, 24 + idx)
+                                 : launch_instance<STASH, COOP, GROUPED, false, true, false>(ul, 16 + idx);
+        }
+        if (ul.masked) return launch_instance<STASH, COOP, GROUPED, true, false, false>(ul, 8 + idx);
+    }
+    return launch_instance<STASH, COOP, GROUPED, false, false, false>(ul, idx);
+}
+
 // everything of a step's kernel arguments that depends on the cache and the fill level only
 static UnitArgs unit_args_of(const Plan &p, int n, int S)
 {
@@ -870,41 +912,25 @@ static hipError_t launch_unit(const Plan &p, const StepIo &io, int n, const void
     // the dynamic-LDS ceiling is a per-device function attribute: raise it once per device
     // and kernel instance (a benign race if two host threads get here together: both set it)
     constexpr int kMaxDevices = 64;
-    static bool attr_done_all[kMaxDevices][32] = {};
+    static bool attr_done_all[kMaxDevices][34] = {};
     int dev = 0;
     if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) return hipErrorInvalidDevice;
     bool *attr_done = attr_done_all[dev];
-#define LF_UNIT5(STASH, COOP, GROUPED, MASKED, GATHER, IDX)                                           \
-    do {                                                                                              \
-        if (!attr_done[IDX]) {                                                                        \
-            hipError_t e = hipFuncSetAttribute((const void *)unit_mfma_kernel<true, STASH, COOP, GROUPED, MASKED, GATHER>, \
-                                               hipFuncAttributeMaxDynamicSharedMemorySize, (int)kUnitLdsLimit); \
-            if (e != hipSuccess) return e;                                                            \
-            attr_done[IDX] = true;                                                                    \
-        }                                                                                             \
-        hipLaunchKernelGGL((unit_mfma_kernel<true, STASH, COOP, GROUPED, MASKED, GATHER>), dim3((unsigned)wgs), dim3(512), lds, s, a, ga); \
-    } while (0)
     // the mask only matters where slots are scored (an attention-only cache takes none), the
     // gathering only where cooperating workgroups screen codes
-#define LF_UNIT(STASH, COOP, GROUPED, IDX)                                                            \
-    do {                                                                                              \
-        if (STASH == kStashLds && COOP && gather) {                                                   \
-            if (p.masked) LF_UNIT5(STASH, COOP, GROUPED, true, true, 24 + IDX);                       \
-            else LF_UNIT5(STASH, COOP, GROUPED, false, true, 16 + IDX);                               \
-        } else if (p.masked && STASH == kStashLds) LF_UNIT5(STASH, COOP, GROUPED, true, false, 8 + IDX); \
-        else LF_UNIT5(STASH, COOP, GROUPED, false, false, IDX);                                       \
-    } while (0)
+    const UnitLaunch ul = {attr_done, wgs, lds, s, &a, &ga, p.masked, gather};
     const bool coop = S > 1;
-    if (table) {
-        if (stash) { if (coop) LF_UNIT(kStashLds, true, true, 4); else LF_UNIT(kStashLds, false, true, 5); }
-        else       { if (coop) LF_UNIT(kStashNone, true, true, 6); else LF_UNIT(kStashNone, false, true, 7); }
-    } else {
-        if (stash) { if (coop) LF_UNIT(kStashLds, true, false, 0); else LF_UNIT(kStashLds, false, false, 1); }
-        else       { if (coop) LF_UNIT(kStashNone, true, false, 2); else LF_UNIT(kStashNone, false, false, 3); }
+    if (p.max_free) { // attention only, one cache (the API layer admits nothing else)
+        if (table || stash) return hipErrorInvalidValue;
+        return coop ? launch_instance<kStashNone, true, false, false, false, true>(ul, 32)
+                    : launch_instance<kStashNone, false, false, false, false, true>(ul, 33);
     }
-#undef LF_UNIT5
-#undef LF_UNIT
-    return hipGetLastError();
+    if (table) {
+        if (stash) return coop ? launch_family<kStashLds, true, true>(ul, 4) : launch_family<kStashLds, false, true>(ul, 5);
+        return coop ? launch_family<kStashNone, true, true>(ul, 6) : launch_family<kStashNone, false, true>(ul, 7);
+    }
+    if (stash) return coop ? launch_family<kStashLds, true, false>(ul, 0) : launch_family<kStashLds, false, false>(ul, 1);
+    return coop ? launch_family<kStashNone, true, false>(ul, 2) : launch_family<kStashNone, false, false>(ul, 3);
 }
 
 hipError_t launch_unit_mfma(const Plan &p, const void *q, const void *k_new, const void *v_new, int n,

@@ -52,7 +52,7 @@ static int validate(const lf_config *cfg)
     if (cfg->dtype != LF_F32 && cfg->dtype != LF_BF16)
         return fail(LF_ERR_INVALID_ARG, "unknown dtype %d", cfg->dtype);
     if (cfg->flags & ~(LF_FLAG_ATTENTION_ONLY | LF_FLAG_FORCE_VALU | LF_FLAG_FORCE_SPLIT | LF_FLAG_FORCE_UNIT |
-                       LF_FLAG_UNFUSED_ACCUM))
+                       LF_FLAG_UNFUSED_ACCUM | LF_FLAG_MAX_FREE))
         return fail(LF_ERR_INVALID_ARG, "unknown flag bits 0x%x", cfg->flags);
     if (cfg->q_heads % cfg->kv_heads)
         return fail(LF_ERR_UNSUPPORTED, "q_heads %d is not a multiple of kv_heads %d", cfg->q_heads,
@@ -75,6 +75,12 @@ static int validate(const lf_config *cfg)
         if ((long long)cfg->batch * cfg->kv_heads * (cfg->budget + kTile) >= (1ll << 31))
             return fail(LF_ERR_UNSUPPORTED, "UNFUSED_ACCUM: batch*kv_heads*budget >= 2^31");
     }
+    if (cfg->flags & LF_FLAG_MAX_FREE) {
+        if (!(cfg->flags & LF_FLAG_ATTENTION_ONLY))
+            return fail(LF_ERR_INVALID_ARG, "MAX_FREE is an attention-only variant: combine it with ATTENTION_ONLY");
+        if (!mfma || (cfg->flags & LF_FLAG_FORCE_SPLIT))
+            return fail(LF_ERR_UNSUPPORTED, "MAX_FREE needs bf16, head_dim 128 and the fused matrix-core kernel");
+    }
     if (cfg->flags & LF_FLAG_FORCE_UNIT) {
         if (!mfma) return fail(LF_ERR_UNSUPPORTED, "FORCE_UNIT needs bf16, head_dim 128 and the matrix-core kernel");
         if (unit_mfma_lds_bytes(cfg->budget, G, !(cfg->flags & (LF_FLAG_ATTENTION_ONLY | LF_FLAG_UNFUSED_ACCUM)), 1) > kUnitLdsLimit)
@@ -92,6 +98,7 @@ static void fill_plan(const lf_config *cfg, Plan *p)
     // the comparison path runs the plain attention kernels: that is the flag they see
     p->unfused = cfg->flags & LF_FLAG_UNFUSED_ACCUM;
     if (p->unfused) p->flags = (cfg->flags & ~LF_FLAG_UNFUSED_ACCUM) | LF_FLAG_ATTENTION_ONLY;
+    p->max_free = cfg->flags & LF_FLAG_MAX_FREE;
     choose_splits(p->units, p->N, &p->L, &p->C);
     p->ntiles = (p->N + kTile - 1) / kTile;
     p->use_mfma = cfg->dtype == LF_BF16 && cfg->head_dim == 128 && !(cfg->flags & LF_FLAG_FORCE_VALU);
@@ -426,6 +433,7 @@ int longflow_group_create(longflow_group_t **group, longflow_cache_t *const *cac
         longflow_cache *c = checked(caches[i]);
         if (!c) return fail(LF_ERR_STATE, "member %d: invalid or destroyed cache handle", i);
         if (c->plan.unfused) return fail(LF_ERR_UNSUPPORTED, "member %d: the unfused comparison path has no grouped launch", i);
+        if (c->plan.max_free) return fail(LF_ERR_UNSUPPORTED, "member %d: the max-free variant has no grouped launch", i);
         for (longflow_cache *m : members)
             if (m == c) return fail(LF_ERR_INVALID_ARG, "member %d appears twice", i);
         const Plan &a = c->plan, &b = (members.empty() ? c : members[0])->plan;

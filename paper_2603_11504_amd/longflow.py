@@ -21,6 +21,7 @@ LF_FLAG_FORCE_VALU = 2
 LF_FLAG_FORCE_SPLIT = 4
 LF_FLAG_FORCE_UNIT = 8
 LF_FLAG_UNFUSED_ACCUM = 16
+LF_FLAG_MAX_FREE = 32
 
 EXPORTS = ("longflow_workspace_bytes", "longflow_init_cache", "longflow_decode_step",
            "longflow_fill_steps", "longflow_scores", "longflow_set_pending", "longflow_set_mask", "longflow_get_mask", "longflow_evict_scratch_bytes",

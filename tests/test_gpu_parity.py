@@ -851,3 +851,44 @@ def test_random_operation_sequences(case):
         group.close()
     gpu.close()
     other.close()
+
+
+# ------------------------------------------------------------------ max-free softmax (Alg. 1 as printed), attention only
+
+def test_max_free_softmax_equals_the_referenced_one_until_it_overflows():
+    wl = _small("maxfree", "bf16", 4, 28, 4, 128, 3000, n_init=3000, steps=1, sink_scale=4.0, seed=17)
+    k0, v0 = W.device_prefill(wl, "cuda")
+    q, _, _ = W.device_step(wl, 0, "cuda")
+    mk = lambda flags, k: lf.LongFlowCache(wl.batch, wl.q_heads, wl.kv_heads, 128, wl.budget, flags=flags, k_init=k, v_init=v0)
+    AO = lf.LF_FLAG_ATTENTION_ONLY
+    ref, mf = mk(AO, k0), mk(AO | lf.LF_FLAG_MAX_FREE, k0)
+    o_ref, _ = ref.decode_step(q)
+    o_mf, _ = mf.decode_step(q)
+    torch.cuda.synchronize()
+    # both against the oracle on a few units, and against each other
+    G, D = wl.group, 128
+    for u in (0, 5, wl.units - 1):
+        out, _, _ = oracle.attend_unit(W.to_f64(q.reshape(wl.units, G, D)[u]), W.to_f64(k0.reshape(wl.units, -1, D)[u]),
+                                       W.to_f64(v0.reshape(wl.units, -1, D)[u]))
+        for o in (o_ref, o_mf):
+            assert np.abs(W.to_f64(o.reshape(wl.units, G, D)[u]) - out).max() <= 2e-2
+    assert (o_ref.float() - o_mf.float()).abs().max().item() <= 2 ** -7
+    # keys scaled until a logit passes the fp32 range of exp: the reference keeps the default finite
+    # and right, the printed form has nothing to hold on to
+    kbig = (k0.float() * 64).to(torch.bfloat16)
+    ref2, mf2 = mk(AO, kbig), mk(AO | lf.LF_FLAG_MAX_FREE, kbig)
+    o_ref2, _ = ref2.decode_step(q)
+    o_mf2, _ = mf2.decode_step(q)
+    torch.cuda.synchronize()
+    logits = (q.float().reshape(wl.batch, wl.kv_heads, G, D) @ kbig.float().transpose(-1, -2)) / np.sqrt(D)
+    assert logits.max().item() > 100
+    assert torch.isfinite(o_ref2.float()).all()
+    out, _, _ = oracle.attend_unit(W.to_f64(q.reshape(wl.units, G, D)[0]), W.to_f64(kbig.reshape(wl.units, -1, D)[0]),
+                                   W.to_f64(v0.reshape(wl.units, -1, D)[0]))
+    assert np.abs(W.to_f64(o_ref2.reshape(wl.units, G, D)[0]) - out).max() <= 2e-2
+    assert not torch.isfinite(o_mf2.float()).all()
+    # the variant exists for plain attention on the fused kernel only
+    with pytest.raises(lf.LongFlowError):
+        lf.LongFlowCache(1, 4, 1, 128, 64, flags=lf.LF_FLAG_MAX_FREE)
+    with pytest.raises(lf.LongFlowError):
+        lf.LongFlowCache(1, 4, 1, 64, 64, flags=AO | lf.LF_FLAG_MAX_FREE, k_init=k0[:1, :1, :8, :64].contiguous(), v_init=v0[:1, :1, :8, :64].contiguous())
