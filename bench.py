@@ -48,6 +48,8 @@ def parse():
     ap.add_argument("--unit", action="store_true", help="force the one-workgroup-per-unit fused path")
     ap.add_argument("--unfused", action="store_true",
                     help="bf16/head_dim 128: the unfused comparison path (accumulated attention weights, Fig. 1)")
+    ap.add_argument("--plain", action="store_true",
+                    help="plain decode attention over the full cache (LF_FLAG_ATTENTION_ONLY): no insert, score or eviction")
     ap.add_argument("--fill", action="store_true",
                     help="time filling one empty cache of the workload's geometry to the brim: one longflow_fill_steps call "
                          "against the same tokens as consecutive decode steps")
@@ -355,9 +357,12 @@ def main():
     flags |= lf.LF_FLAG_FORCE_SPLIT if a.split else 0
     flags |= lf.LF_FLAG_FORCE_UNIT if a.unit else 0
     flags |= lf.LF_FLAG_UNFUSED_ACCUM if a.unfused else 0
+    if a.plain:
+        flags |= lf.LF_FLAG_ATTENTION_ONLY
+        wl = W.scaled(wl, name=wl.name + "_plain_attention", n_init=wl.budget)
     r = measure(wl, flags, steps, a.warmup, pool=a.pool, with_cpu=not a.no_cpu_baseline,
                 calibrate_copy=a.calibrate_copy, streams=a.streams, also_streams=a.also_streams if a.streams == 1 else 0,
-                also_grouped=a.streams == 1 and wl.layers > 1 and not a.unfused)
+                also_grouped=a.streams == 1 and wl.layers > 1 and not a.unfused and not a.plain)
     kname = r["kernel"]
     out = {
         "metric": "decode_tokens_per_s",
@@ -371,7 +376,7 @@ def main():
                    "head_dim": wl.head_dim, "budget": wl.budget, "layers": wl.layers,
                    "calls_per_step": wl.layers, "streams": a.streams,
                    "kernel_path": ("unfused comparison path (insert, attention, accumulate, decide) around: "
-                                   if a.unfused else "") +
+                                   if a.unfused else "plain attention, no by-products: " if a.plain else "") +
                                   {"unit_mfma_kernel": "fused one-launch, matrix cores",
                                    "split_mfma_kernel": "split-K, matrix cores",
                                    "split_valu_kernel": "split-K, vector ALU"}[kname.split("+")[-1]]},
