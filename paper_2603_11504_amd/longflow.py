@@ -118,6 +118,17 @@ def _ptr(t):
     return None if t is None else ctypes.c_void_p(t.data_ptr())
 
 
+def _arg(t, numel, dtype, what):
+    """Device pointer of a tensor argument after checking what the C side cannot see: that it is a
+    contiguous device tensor of the element type and count the kernels will read or write."""
+    if t is None:
+        return None
+    if t.dtype is not dtype or t.numel() != numel or not t.is_contiguous() or not t.is_cuda:
+        raise ValueError(f"{what}: need a contiguous device tensor of {numel} {dtype} elements, got "
+                         f"{tuple(t.shape)} {t.dtype} on {t.device}{'' if t.is_contiguous() else ', not contiguous'}")
+    return ctypes.c_void_p(t.data_ptr())
+
+
 def _stream():
     return ctypes.c_void_p(torch.cuda.current_stream().cuda_stream)
 
@@ -158,19 +169,25 @@ class LongFlowCache:
             k_init = k_init.contiguous()
             v_init = v_init.contiguous()
         h = ctypes.c_void_p()
-        _check(lib().longflow_init_cache(ctypes.byref(h), ctypes.byref(self.cfg), _ptr(self.k_cache),
-                                         _ptr(self.v_cache), _ptr(k_init), _ptr(v_init), n_init,
+        n_cache = batch * kv_heads * budget * head_dim
+        n_rows = batch * kv_heads * n_init * head_dim
+        _check(lib().longflow_init_cache(ctypes.byref(h), ctypes.byref(self.cfg), _arg(self.k_cache, n_cache, dtype, "k_cache"),
+                                         _arg(self.v_cache, n_cache, dtype, "v_cache"), _arg(k_init, n_rows, dtype, "k_init"),
+                                         _arg(v_init, n_rows, dtype, "v_init"), n_init,
                                          _ptr(self.workspace), nbytes, _stream()))
         self._h = h
         self.out = torch.empty((batch, q_heads, head_dim), dtype=dtype, device=self.device)
         self.evict_idx = torch.empty((batch, kv_heads), dtype=torch.int32, device=self.device)
+        self._nq, self._nkv, self._nu = batch * q_heads * head_dim, batch * kv_heads * head_dim, batch * kv_heads
 
     def decode_step(self, q, k_new=None, v_new=None, out=None, evict_idx=None):
         """Asynchronous; returns (out, evict_idx) tensors owned by this object unless given."""
         out = self.out if out is None else out
         evict_idx = self.evict_idx if evict_idx is None else evict_idx
-        _check(lib().longflow_decode_step(self._h, _ptr(q), _ptr(k_new), _ptr(v_new), _ptr(out),
-                                          _ptr(evict_idx), _stream()))
+        dt = self.dtype
+        _check(lib().longflow_decode_step(self._h, _arg(q, self._nq, dt, "q"), _arg(k_new, self._nkv, dt, "k_new"),
+                                          _arg(v_new, self._nkv, dt, "v_new"), _arg(out, self._nq, dt, "out"),
+                                          _arg(evict_idx, self._nu, torch.int32, "evict_idx"), _stream()))
         return out, evict_idx
 
     def fill_steps(self, q, k_new, v_new, out=None, evict_idx=None):
@@ -180,7 +197,10 @@ class LongFlowCache:
         if out is None:
             out = torch.empty((T, self.cfg.batch, self.cfg.q_heads, self.cfg.head_dim), dtype=self.dtype, device=self.device)
         evict_idx = self.evict_idx if evict_idx is None else evict_idx
-        _check(lib().longflow_fill_steps(self._h, T, _ptr(q), _ptr(k_new), _ptr(v_new), _ptr(out), _ptr(evict_idx), _stream()))
+        dt = self.dtype
+        _check(lib().longflow_fill_steps(self._h, T, _arg(q, T * self._nq, dt, "q"), _arg(k_new, T * self._nkv, dt, "k_new"),
+                                         _arg(v_new, T * self._nkv, dt, "v_new"), _arg(out, T * self._nq, dt, "out"),
+                                         _arg(evict_idx, self._nu, torch.int32, "evict_idx"), _stream()))
         return out, evict_idx
 
     def scores(self):
@@ -267,8 +287,11 @@ class LongFlowGroup:
         """q/out: [n_caches, B, Hq, D]; k_new/v_new: [n_caches, B, Hkv, D], all contiguous."""
         out = self.out if out is None else out
         evict_idx = self.evict_idx if evict_idx is None else evict_idx
-        _check(lib().longflow_group_decode_step(self._h, _ptr(q), _ptr(k_new), _ptr(v_new), _ptr(out),
-                                                _ptr(evict_idx), _stream()))
+        c0, n = self.caches[0], len(self.caches)
+        dt = c0.dtype
+        _check(lib().longflow_group_decode_step(self._h, _arg(q, n * c0._nq, dt, "q"), _arg(k_new, n * c0._nkv, dt, "k_new"),
+                                                _arg(v_new, n * c0._nkv, dt, "v_new"), _arg(out, n * c0._nq, dt, "out"),
+                                                _arg(evict_idx, n * c0._nu, torch.int32, "evict_idx"), _stream()))
         return out, evict_idx
 
     def close(self):

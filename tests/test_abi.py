@@ -179,3 +179,14 @@ def test_unfused_comparison_path_is_validated_on_the_host():
     u = lf.longflow_plan_info(_cfg(flags=UNF))
     assert u.launches_per_step == a.launches_per_step + 3
     assert (u.path, u.workgroups_per_unit, u.slots_per_workgroup) == (a.path, a.workgroups_per_unit, a.slots_per_workgroup)
+
+
+def test_binding_checks_what_the_c_side_cannot_see():
+    import torch
+    bf = torch.bfloat16
+    ok = torch.zeros(2, 8, 128, dtype=bf)
+    # not on a device, wrong element count, wrong element type, not contiguous
+    for bad, n, dt in ((ok, 2048, bf), (ok, 1024, bf), (ok.float(), 2048, torch.float32), (ok.transpose(0, 1), 2048, bf)):
+        with pytest.raises(ValueError):
+            lf._arg(bad, n, dt, "q")
+    assert lf._arg(None, 5, bf, "k_new") is None
