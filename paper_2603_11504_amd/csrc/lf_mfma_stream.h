@@ -317,10 +317,17 @@ struct MfmaStreamer {
             if (i + 3 < n_my) compute_tile<false>(ta, wave + NWAVES * (i + 3));
             if (i + 4 < n_my) compute_tile<false>(tb, wave + NWAVES * (i + 4));
         } else {
-            for (int i = 0; i < n_my; ++i) {
-                load_tile<false>(ta, wave + NWAVES * i);
-                compute_tile<false>(ta, wave + NWAVES * i);
-            }
+            // one or two tiles (short spans: small caches split over many workgroups), plus
+            // possibly the ragged one: every load is issued before the first tile is consumed,
+            // one trip to memory instead of one per tile
+            const bool mine = ragged && wave == nfull % NWAVES;
+            if (n_my >= 1) load_tile<false>(ta, wave);
+            if (n_my >= 2) load_tile<false>(tb, wave + NWAVES);
+            if (mine) load_tile<true>(tc, nfull);
+            if (n_my >= 1) compute_tile<false>(ta, wave);
+            if (n_my >= 2) compute_tile<false>(tb, wave + NWAVES);
+            if (mine) compute_tile<true>(tc, nfull);
+            return;
         }
         if (ragged && wave == nfull % NWAVES) {
             load_tile<true>(ta, nfull);
