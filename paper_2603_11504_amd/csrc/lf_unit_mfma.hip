@@ -185,6 +185,10 @@ __device__ bool fill_lowest_hole(const float *lu_u, int npos, int N, int ins_slo
     return red[0] != 0x7fffffff;
 }
 
+// value of a unit's dump counter once its codes are no longer trusted (stays negative
+// whatever late dumps add to it)
+constexpr int kDumpsDistrusted = -(1 << 30);
+
 // COOP: several workgroups may share a unit (s_active can exceed 1)
 // GATHER (with COOP): the deciding workgroup copies the others' code dumps into LDS chunk by
 // chunk before screening them; without it, it reads them in place, item by item
@@ -396,10 +400,13 @@ __global__ __launch_bounds__(512, 1) void unit_mfma_kernel(const UnitArgs a_in, 
             sL[tid] = Ls;
         }
         if (evicting && tid == 0) { // bounded wait for the S-1 dumps (their authors are running or done)
+            // A negative count marks a unit whose wait once ran out: a dump may then have been
+            // counted after the counter was cleared, so the counter is never trusted again and
+            // every later step re-scores all slots (exact, slower) instead of reading dumps.
             int seen = 0;
             for (int it = 0; it < (1 << 22); ++it) {
                 seen = __hip_atomic_load(&a.dumped[u], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-                if (seen >= s_active - 1) break;
+                if (seen >= s_active - 1 || seen < 0) break;
                 __builtin_amdgcn_s_sleep(8);
             }
             s_flag = (seen >= s_active - 1);
@@ -744,7 +751,10 @@ __global__ __launch_bounds__(512, 1) void unit_mfma_kernel(const UnitArgs a_in, 
             a.out[((size_t)u * G + h) * D + d] = (uint16_t)f32_to_bf16_bits(acc / sL[h]);
         }
     } else { // the output was stored with the merge
-        if (tid == 0) { st_agent(&a.arrive[u], 0); st_agent(&a.dumped[u], 0); } // ready for the next step
+        if (tid == 0) { // ready for the next step
+            st_agent(&a.arrive[u], 0);
+            st_agent(&a.dumped[u], dumps_ok ? 0 : kDumpsDistrusted);
+        }
     }
 }
 
