@@ -367,17 +367,20 @@ LFO_API int lfo_cache_step(lfo_cache *c, const double *q, const double *k_new,
 }
 
 /*
- * Fill phase in bulk: the next T tokens of a cache that has room for them
- * (count + T <= N).  By definition T consecutive decode steps -- token t's
- * query attends to the rows present after its own insert, i.e. causally
- * (Sec. 2.1: prefill caches K, V; decoding appends one token's K, V and
- * attends over all of them).  q [T][B][Hq][D], k_new, v_new [T][B][Hkv][D],
- * out [T][B][Hq][D]; evict_idx [B][Hkv] is the last step's.
+ * The next T tokens in one call.  By definition T consecutive decode steps:
+ * while the cache has room, token t's query attends to the rows present after
+ * its own insert, i.e. causally (Sec. 2.1: prefill caches K, V; decoding
+ * appends one token's K, V and attends over all of them); once it is full every
+ * further token evicts as usual (Sec. 3.2) -- which is also how a prompt longer
+ * than the budget is taken in under the method's own rule (the paper hands
+ * that case to SnapKV, which it does not define: this build's reading).
+ * q [T][B][Hq][D], k_new, v_new [T][B][Hkv][D], out [T][B][Hq][D];
+ * evict_idx [B][Hkv] is the last step's.
  */
 LFO_API int lfo_cache_fill(lfo_cache *c, int T, const double *q, const double *k_new,
                            const double *v_new, double *out, int32_t *evict_idx)
 {
-    if (T < 1 || c->mask || c->count + T > c->N) return 1;
+    if (T < 1) return 1;
     const size_t nq = (size_t)c->B * c->Hq * c->D, nk = (size_t)c->B * c->Hkv * c->D;
     for (int t = 0; t < T; ++t) {
         int rc = lfo_cache_step(c, q + t * nq, k_new + t * nk, v_new + t * nk, out + t * nq, evict_idx);

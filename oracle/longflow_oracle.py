@@ -158,7 +158,7 @@ class OracleCache:
         return out, idx
 
     def fill(self, q, k_new, v_new):
-        """The next T tokens of a filling cache at once: q [T,B,Hq,D], k_new, v_new [T,B,Hkv,D]
+        """The next T tokens in one call (T consecutive steps): q [T,B,Hq,D], k_new, v_new [T,B,Hkv,D]
         -> (out [T,B,Hq,D], evict_idx [B,Hkv] of the last token)."""
         T = int(np.shape(q)[0])
         q = _d(q, (T, self.B, self.Hq, self.D))
@@ -167,7 +167,7 @@ class OracleCache:
         out = np.empty((T, self.B, self.Hq, self.D))
         idx = np.empty((self.B, self.Hkv), dtype=np.int32)
         if lib().lfo_cache_fill(self._h, T, _ptr(q), _ptr(k), _ptr(v), _ptr(out), idx.ctypes.data_as(_ip)):
-            raise ValueError("T tokens do not fit the free slots of a prefix-mode cache")
+            raise ValueError("T < 1, or a full cache without a pending slot")
         return out, idx
 
     @property

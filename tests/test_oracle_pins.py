@@ -546,10 +546,21 @@ def test_bulk_fill_is_causal_library_attention_and_ends_like_single_steps():
             assert (idx == sc.argmin(-1)).all()
             _, s_last, _ = oracle.attend_unit(q[-1, 0, :G], Kall[0, 0], Vall[0, 0])
             np.testing.assert_allclose(sc[0, 0], s_last, rtol=1e-13)
-    c = oracle.OracleCache(B, Hkv * G, Hkv, D, N)
-    c.init(k0, v0)
+    # more tokens than free slots: the surplus evicts, exactly as single steps do
+    a = oracle.OracleCache(B, Hkv * G, Hkv, D, N)
+    b = oracle.OracleCache(B, Hkv * G, Hkv, D, N)
+    a.init(k0, v0); b.init(k0, v0)
+    T = N + 5
+    q = rng.standard_normal((T, B, Hkv * G, D)); k = rng.standard_normal((T, B, Hkv, D)); v = rng.standard_normal((T, B, Hkv, D))
+    out_a, idx_a = a.fill(q, k, v)
+    for t in range(T):
+        out_b, idx_b = b.step(q[t], k[t], v[t])
+        np.testing.assert_array_equal(out_a[t], out_b)
+    np.testing.assert_array_equal(idx_a, idx_b)
+    np.testing.assert_array_equal(a.kv()[0], b.kv()[0])
+    assert a.count == N
     with pytest.raises(ValueError):
-        c.fill(np.zeros((N, B, Hkv * G, D)), np.zeros((N, B, Hkv, D)), np.zeros((N, B, Hkv, D)))   # too many
+        a.fill(q[:0], k[:0], v[:0])
 
 
 @pytest.mark.parametrize("rule", ["longflow", "accumulated_attention"])
