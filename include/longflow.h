@@ -145,21 +145,25 @@ LF_API int longflow_decode_step(longflow_cache_t *cache, const void *q,
                          void *out, int32_t *evict_idx, void *hip_stream);
 
 /*
- * Fill phase in bulk: the next T tokens of a cache that still has room for them
- * (valid count + T <= N), with the results of T consecutive longflow_decode_step
- * calls -- token t attends to the rows present after its own insert (Sec. 2.1:
- * prefill caches K and V, decoding appends one token's and attends over all).
- * While a cache is filling nothing is evicted, so the steps depend on each other
- * only through the appended rows: bf16 / head_dim 128 caches write all rows first
- * and take the queries through attention several at a time, reading the cache once
- * per 4 * floor(16 / (Hq/Hkv)) tokens; other caches run the T steps one by one.
+ * The next T tokens in one call, with the results of T consecutive
+ * longflow_decode_step calls -- token t attends to the rows present after its own
+ * insert (Sec. 2.1: prefill caches K and V, decoding appends one token's and
+ * attends over all).  While a cache is filling nothing is evicted, so the steps
+ * depend on each other only through the appended rows: for the tokens that find a
+ * free slot, bf16 / head_dim 128 caches write all rows first and take the queries
+ * through attention several at a time, reading the cache once per
+ * 4 * floor(16 / (Hq/Hkv)) tokens (the fill phase in bulk).  Tokens beyond the
+ * free slots -- a prompt longer than the budget, which the paper hands to an
+ * external method -- evict one slot each under the method's own rule (Sec. 3.2),
+ * as ordinary steps issued back to back; so do all tokens of caches without the
+ * batched kernel or with an explicit mask in force.
  *   q           device [T][B][Hq][D]
  *   k_new,v_new device [T][B][Hkv][D]
  *   out         device [T][B][Hq][D]
  *   evict_idx   device int32 [B][Hkv] or NULL: as after the last of the T steps
- * All pointers 16-byte aligned.  LF_ERR_INVALID_ARG if T < 1 or the tokens do not
- * fit; LF_ERR_UNSUPPORTED with LF_FLAG_ATTENTION_ONLY, LF_FLAG_UNFUSED_ACCUM or an
- * explicit mask in force.
+ * All pointers 16-byte aligned.  LF_ERR_INVALID_ARG if T < 1; LF_ERR_STATE for a
+ * full cache without a pending slot; LF_ERR_UNSUPPORTED with LF_FLAG_ATTENTION_ONLY
+ * or LF_FLAG_UNFUSED_ACCUM.
  */
 LF_API int longflow_fill_steps(longflow_cache_t *cache, int32_t T, const void *q,
                         const void *k_new, const void *v_new,

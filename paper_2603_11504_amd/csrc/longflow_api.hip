@@ -315,20 +315,24 @@ int longflow_fill_steps(longflow_cache_t *cache, int32_t T, const void *q, const
     const Plan &p = c->plan;
     if (p.unfused) return fail(LF_ERR_UNSUPPORTED, "the unfused comparison path has no bulk fill");
     if (p.flags & LF_FLAG_ATTENTION_ONLY) return fail(LF_ERR_UNSUPPORTED, "an attention-only cache takes no tokens");
-    if (p.masked) return fail(LF_ERR_UNSUPPORTED, "bulk fill needs a cache without an explicit mask");
     if (!q || !k_new || !v_new || !out) return fail(LF_ERR_INVALID_ARG, "q/k_new/v_new/out is NULL");
     if (((uintptr_t)q & 15u) || ((uintptr_t)out & 15u) || ((uintptr_t)k_new & 15u) || ((uintptr_t)v_new & 15u))
         return fail(LF_ERR_INVALID_ARG, "q/k_new/v_new/out must be 16-byte aligned");
-    if (T < 1 || c->count + (long long)T > p.N)
-        return fail(LF_ERR_INVALID_ARG, "T = %d tokens do not fit: %d of %d slots are taken", T, c->count, p.N);
+    if (T < 1) return fail(LF_ERR_INVALID_ARG, "T = %d", T);
+    if (!c->has_pending)
+        return fail(LF_ERR_STATE, "cache is full and no slot is pending: call longflow_set_pending");
     hipStream_t s = (hipStream_t)hip_stream;
     const size_t esz = p.dtype == LF_F32 ? 4 : 2;
     const size_t q_step = esz * (size_t)p.B * p.Hq * p.D, kv_step = esz * (size_t)p.B * p.Hkv * p.D;
-    // all but the last token in bulk where that pays; the last one takes the ordinary step, which
-    // also leaves what longflow_scores needs and makes the eviction decision if the cache is now full
+    // The tokens that find a free slot go in bulk where that pays, all but the last of them: that
+    // one takes the ordinary step, which also leaves what longflow_scores needs and makes the
+    // eviction decision if the cache is now full.  Tokens beyond the free slots are ordinary
+    // evicting steps, issued back to back.
+    const int room = p.masked ? 0 : p.N - c->count;
+    const int Tfill = std::min<int>(T, room);
     int Tb = 0;
-    if (p.use_mfma && T - 1 >= fill_tokens_per_pass(p.G)) {
-        Tb = T - 1;
+    if (p.use_mfma && Tfill - 1 >= fill_tokens_per_pass(p.G)) {
+        Tb = Tfill - 1;
         // one workgroup per (unit, group of tokens): keep each launch's grid below 2^30 workgroups
         const long long per_launch = std::max(1ll, (1ll << 30) / p.units) * fill_tokens_per_pass(p.G);
         hipError_t e = hipSuccess;

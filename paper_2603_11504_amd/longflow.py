@@ -191,8 +191,9 @@ class LongFlowCache:
         return out, evict_idx
 
     def fill_steps(self, q, k_new, v_new, out=None, evict_idx=None):
-        """The next T tokens of a filling cache at once: q [T,B,Hq,D], k_new, v_new [T,B,Hkv,D]
-        (contiguous) -> (out [T,B,Hq,D], evict_idx [B,Hkv] as after the last of them)."""
+        """The next T tokens in one call (= T decode steps; those that find a free slot go in bulk):
+        q [T,B,Hq,D], k_new, v_new [T,B,Hkv,D] (contiguous) -> (out [T,B,Hq,D], evict_idx [B,Hkv]
+        as after the last of them)."""
         T = int(q.shape[0])
         if out is None:
             out = torch.empty((T, self.cfg.batch, self.cfg.q_heads, self.cfg.head_dim), dtype=self.dtype, device=self.device)

@@ -53,7 +53,7 @@ def _fill_and_compare(wl, chunks, units=None, flags=0, tail_steps=8):
         rep.max_out_err = max(rep.max_out_err, err)
         assert err <= OUT_TOL[wl.dtype], f"chunk at t={t} of {T}: max |out - oracle| = {err:.3e}"
         t += T
-        assert gpu.valid_count == ora.count == wl.n_init + t
+        assert gpu.valid_count == ora.count == min(N, wl.n_init + t)
         i_gpu = idx_t.reshape(-1)[sel].cpu().numpy()
         full = np.full(nu, ora.count == N)
         if compare_indices(i_gpu, i_ref, ora.scores(), full, rep, where=f"{wl.name} after {t} tokens"):
@@ -136,21 +136,51 @@ def test_cfg3_geometry_bulk_fill_to_the_brim_sampled_units():
     torch.cuda.empty_cache()
 
 
+@pytest.mark.parametrize("Hq,Hkv,N,n_init,chunks,flags", [
+    (28, 4, 300, 100, [150, 120, 40], 0),                   # second chunk crosses the brim, third only evicts
+    (8, 2, 200, 0, [450], 0),                               # a "prompt" of 450 tokens into 200 slots in one call
+    (14, 2, 700, 690, [5, 30], lf.LF_FLAG_FORCE_SPLIT),     # too few free slots for the batched kernel
+], ids=lambda v: str(v).replace(" ", ""))
+def test_tokens_beyond_the_free_slots_evict_as_single_steps_do(Hq, Hkv, N, n_init, chunks, flags):
+    wl = _wl(f"over_{Hq}x{Hkv}_n{N}", "bf16", 2, Hq, Hkv, 128, N, n_init=n_init, sink_scale=4.0, seed=700 + N)
+    rep, gpu, ora = _fill_and_compare(wl, chunks, flags=flags, tail_steps=5)
+    assert gpu.valid_count == N
+
+
+def test_multi_token_call_on_a_masked_cache_runs_the_steps():
+    wl = _wl("fill_masked", "bf16", 2, 14, 2, 128, 400, n_init=400, seed=77)
+    k0, v0 = W.device_prefill(wl, "cuda")
+    gpu = lf.LongFlowCache(wl.batch, wl.q_heads, wl.kv_heads, 128, wl.budget, k_init=k0, v_init=v0)
+    ora = oracle.OracleCache(wl.units, wl.group, 1, 128, wl.budget)
+    ora.init(W.to_f64(k0.reshape(wl.units, 1, 400, 128)), W.to_f64(v0.reshape(wl.units, 1, 400, 128)))
+    mask = np.random.default_rng(4).random((wl.units, 400)) < 0.9
+    mask[:, 0] = True
+    gpu.set_pending(torch.zeros((wl.batch, wl.kv_heads), dtype=torch.int32))
+    ora.set_pending(np.zeros((wl.units, 1), dtype=np.int32))
+    gpu.set_mask(torch.as_tensor(mask.reshape(wl.batch, wl.kv_heads, 400)))
+    ora.set_mask(mask.reshape(wl.units, 1, 400))
+    T = 60                                                   # ~40 holes per unit get filled, then eviction
+    q, k, v = _stack_steps(wl, 0, T)
+    out_t, idx_t = gpu.fill_steps(q, k, v)
+    torch.cuda.synchronize()
+    o_ref, i_ref = ora.fill(W.to_f64(q.reshape(T, wl.units, wl.group, 128)), W.to_f64(k.reshape(T, wl.units, 1, 128)),
+                            W.to_f64(v.reshape(T, wl.units, 1, 128)))
+    assert np.abs(W.to_f64(out_t.reshape(T, wl.units, wl.group, 128)) - o_ref).max() <= OUT_TOL["bf16"]
+    assert (idx_t.reshape(-1).cpu().numpy() == i_ref.reshape(-1)).all()
+    assert (gpu.mask().reshape(wl.units, 400).cpu().numpy() == ora.mask().reshape(wl.units, 400)).all()
+
+
 def test_bulk_fill_argument_errors():
     c = lf.LongFlowCache(1, 4, 1, 128, 64)
     q = torch.zeros(65, 1, 4, 128, device="cuda", dtype=torch.bfloat16)
     kv = torch.zeros(65, 1, 1, 128, device="cuda", dtype=torch.bfloat16)
     with pytest.raises(lf.LongFlowError):
-        c.fill_steps(q, kv, kv)                              # 65 tokens into 64 slots
-    c.fill_steps(q[:64], kv[:64], kv[:64])
+        c.fill_steps(q[:0], kv[:0], kv[:0])                  # no token
+    c.fill_steps(q, kv, kv)                                  # 65 tokens into 64 slots: the last one evicts
     assert c.valid_count == 64
+    born_full = lf.LongFlowCache(1, 4, 1, 128, 64, k_init=kv[:64].reshape(1, 1, 64, 128), v_init=kv[:64].reshape(1, 1, 64, 128))
     with pytest.raises(lf.LongFlowError):
-        c.fill_steps(q[:1], kv[:1], kv[:1])                  # full
-    m = lf.LongFlowCache(1, 4, 1, 128, 64)
-    m.fill_steps(q[:8], kv[:8], kv[:8])
-    m.set_mask(torch.ones(1, 1, 64))
-    with pytest.raises(lf.LongFlowError):
-        m.fill_steps(q[:1], kv[:1], kv[:1])
+        born_full.fill_steps(q[:2], kv[:2], kv[:2])          # full and no slot named yet
     ao = lf.LongFlowCache(1, 4, 1, 128, 64, flags=lf.LF_FLAG_ATTENTION_ONLY, k_init=kv[:8].reshape(1, 1, 8, 128),
                           v_init=kv[:8].reshape(1, 1, 8, 128))
     with pytest.raises(lf.LongFlowError):
