@@ -31,7 +31,7 @@
  * as the prefix case), else the argmin.
  *
  * Comparison rule (the unfused baseline the paper measures its kernel against:
- * Fig. 1 "both methods evict one token after each attention computation";
+ * in Fig. 1 both sides drop one token per attention call;
  * Sec. 4.1 describes H2O as ranking tokens by accumulated attention scores,
  * Sec. 2.2 as keeping those scores as auxiliary per-token metadata).  With
  * rule 1 the importance of a slot is the attention weight it has received,
