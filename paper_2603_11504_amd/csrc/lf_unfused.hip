@@ -4,7 +4,7 @@
 // attention computation (Fig. 1), describes H2O as ranking tokens by accumulated attention
 // scores (Sec. 4.1) that it keeps as auxiliary per-token metadata (Sec. 2.2), and names the
 // cost of such designs: importance is evaluated outside the attention kernel, re-deriving
-// intermediates that kernel already had (Sec. 2.2, "poor compatibility with fused kernels").
+// intermediates that kernel already had (Sec. 2.2, the paragraph on compatibility with fused kernels).
 // This file is that structure with every stage written as well as the fused path's own:
 //
 //   1. insert      K[slot], V[slot] <- k_t, v_t; acc[slot] <- 0             (Fig. 2 left)
