@@ -311,6 +311,9 @@ __device__ void split_finish_unit(const SplitTailArgs<T> &a, int u)
                 const int src = __ffsll((long long)bal) - 1;
                 bal &= bal - 1;
                 const int cs = __shfl(slot, src);
+                // scores are >= 0 and ties go to the lower slot: behind an exact zero nothing can win
+                // (keeps a unit of zero-norm value rows, e.g. a padded sequence, from re-scoring every slot)
+                if (bv == 0.0 && cs > bi) continue;
                 const double v = tail_exact_score<T, D>(Ku + (size_t)cs * D, Vu + (size_t)cs * D, qu, G, sM, sL, lane);
                 if (v < bv || (v == bv && cs < bi)) { bv = v; bi = cs; }
             }

@@ -716,12 +716,32 @@ __global__ __launch_bounds__(512, 1) void unit_mfma_kernel(const UnitArgs a_in, 
                     if (v < bv || (v == bv && cs < bi)) { bv = v; bi = cs; }
                 }
             } else {
-                // far more candidates than the list holds (e.g. scores underflowing en masse):
-                // every wave re-scores its share of ALL slots; slow, but still exact
-                for (int cs = wave; cs < n; cs += NW) {
-                    const double v = exact_score_bf16(Ku + (size_t)cs * D, Vu + (size_t)cs * D, qs, G, sM, sL, lane,
-                                                      COOP && s_active > 1 && cs == ins_slot);
-                    if (v < bv || (v == bv && cs < bi)) { bv = v; bi = cs; }
+                // Far more candidates than the list holds: scores underflowing en masse, or many
+                // value rows of zero norm (a padded sequence).  Every wave takes its share of ALL
+                // slots, 64 at a time in ascending order.  A row with ||v||_1 = 0 scores exactly 0
+                // whatever its weight and needs no arithmetic (the side array says so; the row
+                // written by this very step is not trusted to have arrived there and is re-scored
+                // like any other); every other slot is re-scored exactly.  Scores are >= 0 and
+                // ties go to the lower slot, so a wave is done at its first exact zero.
+                for (int c0 = wave * 64; c0 < n && bv > 0.0; c0 += NW * 64) {
+                    const int mine = c0 + lane;
+                    bool zero = false;
+                    if (mine < n && mine != ins_slot) zero = lu_u[(mine & ~15) + pos_of_slot(mine & 15)] == -INFINITY;
+                    const unsigned long long zmask = __ballot(zero);
+                    unsigned long long todo = __ballot(mine < n && !zero);
+                    const int first_zero = zmask ? c0 + __ffsll((long long)zmask) - 1 : 0x7fffffff;
+                    while (todo) {
+                        const int cs = c0 + __ffsll((long long)todo) - 1;
+                        todo &= todo - 1;
+                        if (cs > first_zero) break; // cannot beat the zero in front of it
+                        // (the score is complete in every fourth lane only: lane 0's goes to all,
+                        // so that the exits below are taken by the whole wave)
+                        const double v = __shfl(exact_score_bf16(Ku + (size_t)cs * D, Vu + (size_t)cs * D, qs, G, sM, sL, lane,
+                                                                 COOP && s_active > 1 && cs == ins_slot), 0);
+                        if (v < bv || (v == bv && cs < bi)) { bv = v; bi = cs; }
+                        if (bv == 0.0) break;
+                    }
+                    if (zmask && (0.0 < bv || first_zero < bi)) { bv = 0.0; bi = first_zero; }
                 }
             }
             if (lane == 0) { best_v[wave] = bv; best_i[wave] = bi; }

@@ -7,7 +7,7 @@ from oracle import longflow_oracle as oracle
 from paper_2603_11504_amd import longflow as lf
 from paper_2603_11504_amd import workloads as W
 
-from parity import ParityReport, compare_indices, run_lockstep
+from parity import OUT_TOL, ParityReport, compare_indices, run_lockstep
 
 pytestmark = pytest.mark.gpu
 
@@ -913,3 +913,38 @@ def test_a_unit_whose_dump_counter_is_distrusted_keeps_deciding_exactly():
     torch.cuda.synchronize()
     assert rep.steps == 12
     assert int(counters[1]) < 0 and (counters[[0, 2, 3]] == 0).all()
+
+
+@pytest.mark.parametrize("dtype,D,flags", [("bf16", 128, 0), ("bf16", 128, lf.LF_FLAG_FORCE_SPLIT), ("f32", 64, 0)],
+                         ids=["unit", "split", "valu"])
+def test_a_padded_sequence_of_zero_rows_decides_exactly_and_quickly(dtype, D, flags):
+    # one sequence of the batch is padding: every K and V row zero, so every score is an exact 0 and the
+    # lowest slot goes each step; the other sequences are ordinary.  (All of its slots are eviction
+    # candidates -- the decision must not fall back to re-scoring each of them.)
+    wl = _small("padded", dtype, 3, 8, 2, D, 4096, n_init=4096, steps=6, sink_scale=4.0, seed=61)
+    k0, v0 = W.device_prefill(wl, "cuda")
+    k0[1] = 0
+    v0[1] = 0
+    gpu = lf.LongFlowCache(wl.batch, wl.q_heads, wl.kv_heads, D, wl.budget, dtype=W.torch_dtype(wl), flags=flags, k_init=k0, v_init=v0)
+    ora = oracle.OracleCache(wl.units, wl.group, 1, D, wl.budget)
+    ora.init(W.to_f64(k0.reshape(wl.units, 1, wl.budget, D)), W.to_f64(v0.reshape(wl.units, 1, wl.budget, D)))
+    first = torch.full((wl.batch, wl.kv_heads), 5, dtype=torch.int32)
+    gpu.set_pending(first)
+    ora.set_pending(first.numpy().reshape(wl.units, 1))
+    import time
+    times = []
+    for t in range(6):
+        q, k, v = W.device_step(wl, t, "cuda")
+        k[1] = 0
+        v[1] = 0
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        out, idx = gpu.decode_step(q, k, v)
+        torch.cuda.synchronize()
+        times.append(time.perf_counter() - t0)
+        o_ref, i_ref = ora.step(W.to_f64(q.reshape(wl.units, wl.group, D)), W.to_f64(k.reshape(wl.units, 1, D)),
+                                W.to_f64(v.reshape(wl.units, 1, D)))
+        assert np.abs(W.to_f64(out.reshape(wl.units, wl.group, D)) - o_ref).max() <= OUT_TOL[dtype]
+        assert (idx.reshape(-1).cpu().numpy() == i_ref.reshape(-1)).all(), f"step {t}"
+        assert (idx[1] == 0).all()                      # the padded sequence: lowest slot, every time
+    assert min(times[1:]) < 4e-4, times                # re-scoring 4096 slots one by one takes about a millisecond
