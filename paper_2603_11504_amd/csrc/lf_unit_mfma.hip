@@ -711,8 +711,9 @@ __global__ __launch_bounds__(512, 1) void unit_mfma_kernel(const UnitArgs a_in, 
             } else if (ncand <= kMaxCand) {
                 for (int c = wave; c < ncand; c += NW) {
                     const int cs = cand_list[c];
-                    const double v = exact_score_bf16(Ku + (size_t)cs * D, Vu + (size_t)cs * D, qs, G, sM, sL, lane,
-                                                      COOP && s_active > 1 && cs == ins_slot);
+                    if (bv == 0.0 && cs > bi) continue; // behind an exact zero nothing can win
+                    const double v = __shfl(exact_score_bf16(Ku + (size_t)cs * D, Vu + (size_t)cs * D, qs, G, sM, sL, lane,
+                                                             COOP && s_active > 1 && cs == ins_slot), 0);
                     if (v < bv || (v == bv && cs < bi)) { bv = v; bi = cs; }
                 }
             } else {
