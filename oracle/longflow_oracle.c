@@ -49,8 +49,9 @@
  *
  * Pins (tests, CPU only): naive softmax attention via a library routine,
  * sum(alpha)=1, eq. 6 at group size 1, closed-form argmin cases, the exact
- * leave-one-out identity and bound of App. A.1, a literal numpy rendering of
- * Alg. 1, brute-force argmin, slot-permutation equivariance, and the fill /
+ * leave-one-out identity and bound of App. A.1, invariance of the definitions
+ * under Alg. 1's route (any partition into pieces, exponentials without a
+ * maximum, normalisation deferred to the end), brute-force argmin, slot-permutation equivariance, and the fill /
  * one-row-changes-per-step invariants of the static cache (Sec. 3.4).
  * The GQA head-sum (step 5 at group size > 1) has no value in the paper to
  * pin it to: "parity unpinned" beyond its reduction to eq. 6 at G = 1.

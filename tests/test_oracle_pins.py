@@ -8,7 +8,7 @@ import numpy as np
 import pytest
 from scipy.special import softmax as scipy_softmax
 
-from oracle import alg1_blockwise, longflow_oracle as oracle
+from oracle import deferred_norm, longflow_oracle as oracle
 
 
 def _rand_unit(rng, n, D, G, kscale=1.0):
@@ -127,21 +127,21 @@ def test_leave_one_out_identity_and_bound(n):
         np.testing.assert_allclose(a_wo, alpha[keep] / (1 - alpha[i]), rtol=1e-10)
 
 
-# ---------------------------------------------------------------- Alg. 1 (blockwise, max-free, masked)
+# ---------------------------------------------------------------- Alg. 1's route: pieces, max-free, masked, normalised last
 
 @pytest.mark.parametrize("B_k", [1, 3, 16, 37])
-def test_blockwise_procedure_equals_definition(B_k):
+def test_deferred_normalisation_over_any_partition_equals_definition(B_k):
     rng = np.random.default_rng(200 + B_k)
     n, D = 37, 64
     q, K, V = _rand_unit(rng, n, D, 1)
     o, score, _ = oracle.attend_unit(q, K, V)
-    o2, s2, i2 = alg1_blockwise.fused_blockwise(q[0], K, V, np.ones(n), B_k)
+    o2, s2, i2 = deferred_norm.attend_in_pieces(q[0], K, V, np.ones(n), B_k)
     np.testing.assert_allclose(o2, o[0], rtol=1e-12, atol=1e-14)
     np.testing.assert_allclose(s2, score, rtol=1e-12)
     assert i2 == oracle.argmin(score)
 
 
-def test_blockwise_mask_equals_definition_on_live_rows():
+def test_deferred_normalisation_with_mask_equals_definition_on_live_rows():
     rng = np.random.default_rng(300)
     n, D, G = 48, 64, 4
     q, K, V = _rand_unit(rng, n, D, G)
@@ -151,7 +151,7 @@ def test_blockwise_mask_equals_definition_on_live_rows():
     K2[~M] = np.nan
     V2[~M] = np.nan                                       # dead rows must not leak
     o, score, _ = oracle.attend_unit(q, K[M], V[M])
-    o2, s2 = alg1_blockwise.fused_blockwise_group(q, K2, V2, M, 5)
+    o2, s2 = deferred_norm.attend_in_pieces_group(q, K2, V2, M, 5)
     np.testing.assert_allclose(o2, o, rtol=1e-12, atol=1e-14)
     np.testing.assert_allclose(s2[M], score, rtol=1e-12)
     assert np.all(s2[~M] == 0.0)
@@ -313,8 +313,8 @@ def test_masked_step_is_library_attention_over_the_valid_rows():
                     a = scipy_softmax(K[b, g, live] @ q[b, g * G + h] / math.sqrt(D))
                     np.testing.assert_allclose(out[b, g * G + h], a @ V[b, g, live], rtol=1e-12, atol=1e-14)
                 assert (sc[b, g, ~m[b, g]] == 0).all() and (sc[b, g, live] > 0).all()
-                # the blockwise procedure of Alg. 1 with the same mask agrees on everything
-                o2, s2 = alg1_blockwise.fused_blockwise_group(q[b, g * G:(g + 1) * G], K[b, g], V[b, g], m[b, g], 7)
+                # the deferred-normalisation route of Alg. 1 with the same mask agrees on everything
+                o2, s2 = deferred_norm.attend_in_pieces_group(q[b, g * G:(g + 1) * G], K[b, g], V[b, g], m[b, g], 7)
                 np.testing.assert_allclose(o2, out[b, g * G:(g + 1) * G], rtol=1e-12, atol=1e-14)
                 np.testing.assert_allclose(s2, sc[b, g], rtol=1e-12)
 
