@@ -22,8 +22,9 @@ sys.path.insert(0, ROOT)
 HBM_PEAK_GBS = 8000.0  # MI355X published peak HBM3E bandwidth
 DEFAULT_STEPS = {0: 512, 1: 1024, 2: 100, 3: 256, 4: 50}
 
-# HBM bytes per launch of the streaming kernel measured with rocprofv3 --pmc
-# (FETCH_SIZE / WRITE_SIZE, scaled by copy kernels of known size); see profiles/.
+# HBM bytes per launch of the streaming kernel as measured EARLIER with rocprofv3 --pmc
+# (FETCH_SIZE / WRITE_SIZE, scaled by copy kernels of known size) and recorded under profiles/.
+# A constant of this file, not a measurement of the run that prints it: the JSON line says so.
 MEASURED_TRAFFIC = {
     ("cfg3_bf16_b64_28x4_d128_n8192_l28", "unit_mfma_kernel"): {"read_bytes": 1058610 * 1024, "write_bytes": 1076 * 1024,
                                                                 "source": "profiles/unit_mfma_kernel_cfg3.txt"},
@@ -59,6 +60,8 @@ def parse():
     ap.add_argument("--pool", type=int, default=0,
                     help="distinct input steps cycled through (0 = one per executed step, no repeats)")
     ap.add_argument("--report", action="store_true", help="all workloads and the uncompressed twin, as a table")
+    ap.add_argument("--no-also", dest="also", action="store_false",
+                    help="default run (cfg3) only: skip the cfg4 block that is measured after it in the same process")
     ap.add_argument("--streams", type=int, default=1,
                     help="HIP streams the independent layer caches are spread over in the timed pass (default 1: "
                          "all calls back-to-back on one stream)")
@@ -79,8 +82,9 @@ def kernel_name(wl, flags):
     return "unfused+" + name if flags & lf.LF_FLAG_UNFUSED_ACCUM else name
 
 
-def cpu_baseline(wl, cache0, target_s=12.0, rule="longflow"):
-    """The float64 oracle, as it stands, timed on this host on a bounded sample of units."""
+def cpu_baseline(wl, cache0, t_next, dev, target_s=12.0, rule="longflow"):
+    """The float64 oracle, as it stands, timed on this host on a bounded sample of units, fed with
+    the workload's own seeded step inputs (W.device_step, steps t_next onwards, layer 0)."""
     import numpy as np
     import torch
     from oracle import longflow_oracle as oracle
@@ -95,24 +99,43 @@ def cpu_baseline(wl, cache0, target_s=12.0, rule="longflow"):
     n = cache0.valid_count
     ku = cache0.k_cache.reshape(wl.units, N, D)[sel][:, : n - 1].reshape(nu, 1, n - 1, D)
     vu = cache0.v_cache.reshape(wl.units, N, D)[sel][:, : n - 1].reshape(nu, 1, n - 1, D)
+
+    def inputs(t, pick):
+        q, k, v = W.device_step(wl, t, dev, 0)
+        return (W.to_f64(q.reshape(wl.units, G, D)[pick]), W.to_f64(k.reshape(wl.units, 1, D)[pick]),
+                W.to_f64(v.reshape(wl.units, 1, D)[pick]))
+
     ora = oracle.OracleCache(nu, G, 1, D, N, rule=rule)
     ora.init(W.to_f64(ku), W.to_f64(vu))
-    g = np.random.default_rng(1)
     steps, t_total = 0, 0.0
     while t_total < target_s and steps < 4096:
-        q = g.standard_normal((nu, G, D)); k = g.standard_normal((nu, 1, D)); v = g.standard_normal((nu, 1, D))
+        q, k, v = inputs(t_next + steps, sel)
         t0 = time.perf_counter()
         ora.step(q, k, v)
         t_total += time.perf_counter() - t0
         steps += 1
     full_step_s = t_total / (nu * steps) * wl.units * wl.layers      # linear extrapolation
+    # one unit alone: the oracle's loop over units has nothing to spread, so one core does the work
+    one = oracle.OracleCache(1, G, 1, D, N, rule=rule)
+    one.init(W.to_f64(ku[:1]), W.to_f64(vu[:1]))
+    s1, t1 = 0, 0.0
+    while t1 < target_s / 6 and s1 < 256:
+        q, k, v = inputs(t_next + s1, sel[:1])
+        t0 = time.perf_counter()
+        one.step(q, k, v)
+        t1 += time.perf_counter() - t0
+        s1 += 1
+    single_step_s = t1 / s1 * wl.units * wl.layers
     return {"value": wl.batch / full_step_s, "unit": "tokens/s", "cores": min(threads, nu), "kind": "oracle",
             "sample": f"{nu} of {wl.units * wl.layers} (layer,batch,kv-head) units x {steps} steps at n={n}, "
-                      f"{t_total:.1f} s, scaled linearly to the full step",
-            "ms_per_step": full_step_s * 1e3}
+                      f"the workload's seeded step inputs, {t_total:.1f} s, scaled linearly to the full step",
+            "ms_per_step": full_step_s * 1e3,
+            "single_core_ms_per_step": single_step_s * 1e3,
+            "single_core_tokens_per_s": wl.batch / single_step_s,
+            "single_core_sample": f"1 unit x {s1} steps, {t1:.1f} s, scaled linearly"}
 
 
-def measure(wl, flags, steps, warmup, pool=0, with_cpu=False, calibrate_copy=False, per_step_times=False,
+def measure(wl, flags, steps, warmup, pool=0, with_cpu=False, calibrate_copy=False,
             streams=1, also_streams=0, also_grouped=False):
     """Build the resident state, warm up, time `steps` steps, then the same again with kernel events."""
     import torch
@@ -147,16 +170,17 @@ def measure(wl, flags, steps, warmup, pool=0, with_cpu=False, calibrate_copy=Fal
         del per_layer
     torch.cuda.synchronize()
 
-    def run(nsteps, t0=0, events=None, nstreams=1):
+    def run(nsteps, t0=0, marks=None, nstreams=1):
+        # marks: nsteps + 1 events, recorded on the launch stream at every step boundary
         # the layer caches are independent: with nstreams > 1 their calls go round-robin to
         # several streams, so one call's tail overlaps the next call's start
         pool_s = [torch.cuda.Stream(device=dev) for _ in range(nstreams)] if nstreams > 1 else None
         if pool_s:
             for s_ in pool_s:
                 s_.wait_stream(torch.cuda.current_stream())
+        if marks is not None:
+            marks[0].record()
         for t in range(t0, t0 + nsteps):
-            if events is not None:
-                events[t - t0][0].record()
             for layer, c in enumerate(caches):
                 q, k, v = (x[layer] for x in inputs[t % npool])
                 if pool_s:
@@ -164,8 +188,8 @@ def measure(wl, flags, steps, warmup, pool=0, with_cpu=False, calibrate_copy=Fal
                         c.decode_step(q, k, v)
                 else:
                     c.decode_step(q, k, v)
-            if events is not None:
-                events[t - t0][1].record()
+            if marks is not None:
+                marks[t - t0 + 1].record()
         if pool_s:
             for s_ in pool_s:
                 torch.cuda.current_stream().wait_stream(s_)
@@ -180,25 +204,35 @@ def measure(wl, flags, steps, warmup, pool=0, with_cpu=False, calibrate_copy=Fal
         torch.cuda.synchronize()
         del src, dst
 
+    # ---- the timed pass: exactly `steps` steps between two synchronisations.  One event per step
+    # boundary on the launch stream gives the spread of the individual steps (p10 / median / p90).
+    marks = [torch.cuda.Event(enable_timing=True) for _ in range(steps + 1)] if streams == 1 else None
+    torch.cuda.synchronize()
     t0 = time.perf_counter()
-    run(steps, warm, nstreams=streams)
+    run(steps, warm, marks, nstreams=streams)
     torch.cuda.synchronize()
     ms_per_step = (time.perf_counter() - t0) / steps * 1e3
     calls = steps * wl.layers
+    step_us = sorted(marks[i].elapsed_time(marks[i + 1]) * 1e3 for i in range(steps)) if marks else None
 
-    # same number of steps again with HIP events around each launch (kernel durations)
+    # ---- the kernel pass: the same number of steps again with HIP events around every launch
+    # (recorded by the library on the launch stream).  Its own wall time is taken too: the kernel
+    # durations of a pass can only add up to less than the wall time of THAT pass.
     for c in caches:
         c.profile_begin(steps)
-    evs = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(steps)] \
-        if per_step_times else None
-    run(steps, warm + steps, evs)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    run(steps, warm + steps)
+    torch.cuda.synchronize()
+    kernel_pass_ms_per_step = (time.perf_counter() - t0) / steps * 1e3
     ksum = 0.0
     for c in caches:
         ms, n = c.profile_end()
         assert n == steps
         ksum += ms
     kernel_us = ksum / calls * 1e3
-    step_us = sorted(a.elapsed_time(b) * 1e3 for a, b in evs) if evs else None
+    assert kernel_us * wl.layers <= kernel_pass_ms_per_step * 1e3 * 1.0005, \
+        f"kernel time {kernel_us * wl.layers:.1f} us per step exceeds the wall time {kernel_pass_ms_per_step * 1e3:.1f} us of the same pass"
     ms_per_step_multi = None
     if also_streams > 1 and wl.layers > 1 and npool >= warm + 3 * steps:
         t0 = time.perf_counter()
@@ -227,16 +261,65 @@ def measure(wl, flags, steps, warmup, pool=0, with_cpu=False, calibrate_copy=Fal
         "bytes_call": bytes_call, "tokens_per_s": wl.batch / (ms_per_step * 1e-3),
         "step_GBs": bytes_call * wl.layers / (ms_per_step * 1e-3) / 1e9,
         "kernel_GBs": bytes_call / (kernel_us * 1e-6) / 1e9, "step_us_sorted": step_us,
+        "kernel_pass_ms_per_step": kernel_pass_ms_per_step,
         "ms_per_step_multi": ms_per_step_multi, "ms_per_step_grouped": ms_per_step_grouped,
     }
     if with_cpu:
-        res["cpu_baseline"] = cpu_baseline(wl, caches[0], rule="accumulated_attention"
+        res["cpu_baseline"] = cpu_baseline(wl, caches[0], npool, dev, rule="accumulated_attention"
                                            if flags & lf.LF_FLAG_UNFUSED_ACCUM else "longflow")
     for c in caches:
         c.close()
     del caches, inputs
     torch.cuda.empty_cache()
     return res
+
+
+KERNEL_PATHS = {"unit_mfma_kernel": "fused one-launch, matrix cores",
+                "split_mfma_kernel": "split-K, matrix cores",
+                "split_valu_kernel": "split-K, vector ALU"}
+
+
+def summary(wl, r):
+    """The per-workload figures of the JSON line: per-call time, spread of the steps, roofline block."""
+    kname = r["kernel"]
+    out = {
+        "us_per_call": r["ms_per_step"] * 1e3 / wl.layers,
+        "step_hbm_GBs": r["step_GBs"],
+        "step_hbm_frac": r["step_GBs"] / HBM_PEAK_GBS,
+    }
+    s = r.get("step_us_sorted")
+    if s:
+        out["us_per_step_p10"], out["us_per_step_median"], out["us_per_step_p90"] = \
+            s[len(s) // 10], s[len(s) // 2], s[(9 * len(s)) // 10]
+    # kernel durations come from a second pass of the same length (HIP events around every launch);
+    # that pass's own wall time stands beside them: kernel_us * calls_per_step <= it, by construction
+    out["kernel_us"] = r["kernel_us"]
+    out["kernel_pass"] = {"ms_per_step": r["kernel_pass_ms_per_step"],
+                          "kernel_ms_per_step": r["kernel_us"] * wl.layers * 1e-3,
+                          "kernel_le_wall": r["kernel_us"] * wl.layers * 1e-3 <= r["kernel_pass_ms_per_step"]}
+    roof = {"bound": "hbm", "kernel": kname, "achieved": r["kernel_GBs"], "peak": HBM_PEAK_GBS,
+            "unit": "GB/s", "frac": r["kernel_GBs"] / HBM_PEAK_GBS,
+            "bytes_per_launch": r["bytes_call"], "avg_launch_us": r["kernel_us"], "traffic": None}
+    t = MEASURED_TRAFFIC.get((wl.name, kname))
+    if t:
+        roof["traffic"] = t["read_bytes"] + t["write_bytes"]
+        roof["traffic_read_bytes"], roof["traffic_write_bytes"] = t["read_bytes"], t["write_bytes"]
+        roof["traffic_source"] = ("static: rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE of an earlier run of this command, "
+                                  "recorded in " + t["source"] + "; not measured by the run that prints this line")
+    out["roofline"] = roof
+    return out
+
+
+def gpu_clocks():
+    """Clocks as found (nothing is pinned): what rocm-smi reports right after the timed work, or None."""
+    import subprocess
+    try:
+        txt = subprocess.run(["rocm-smi", "--showclocks", "--json"], capture_output=True, text=True, timeout=20).stdout
+        card = next(iter(json.loads(txt).values()))
+        keep = {k: v for k, v in card.items() if "sclk" in k.lower() or "mclk" in k.lower() or "fclk" in k.lower()}
+        return keep or None
+    except Exception:
+        return None
 
 
 def fill_bench(a):
@@ -325,7 +408,7 @@ def report(a):
     for wl, flags, steps in rows:
         if a.steps:
             steps = a.steps
-        r = measure(wl, flags, steps, a.warmup, per_step_times=True, also_grouped=wl.layers > 1 and not flags & (lf.LF_FLAG_UNFUSED_ACCUM | lf.LF_FLAG_MAX_FREE))
+        r = measure(wl, flags, steps, a.warmup, also_grouped=wl.layers > 1 and not flags & (lf.LF_FLAG_UNFUSED_ACCUM | lf.LF_FLAG_MAX_FREE))
         s = r["step_us_sorted"]
         p10, med, p90 = s[len(s) // 10], s[len(s) // 2], s[(9 * len(s)) // 10]
         print(f"{wl.name:44s} {r['kernel']:26s} {p10:11.1f} {med:9.1f} {p90:9.1f} {r['ms_per_step'] * 1e3 / wl.layers:9.1f} "
@@ -377,18 +460,10 @@ def main():
                    "calls_per_step": wl.layers, "streams": a.streams,
                    "kernel_path": ("unfused comparison path (insert, attention, accumulate, decide) around: "
                                    if a.unfused else "plain attention, no by-products: " if a.plain else "") +
-                                  {"unit_mfma_kernel": "fused one-launch, matrix cores",
-                                   "split_mfma_kernel": "split-K, matrix cores",
-                                   "split_valu_kernel": "split-K, vector ALU"}[kname.split("+")[-1]]},
-        "us_per_call": r["ms_per_step"] * 1e3 / wl.layers,
-        "step_hbm_GBs": r["step_GBs"],
-        "step_hbm_frac": r["step_GBs"] / HBM_PEAK_GBS,
-        "kernel_us": r["kernel_us"],
-        "roofline": {"bound": "hbm", "kernel": kname, "achieved": r["kernel_GBs"], "peak": HBM_PEAK_GBS,
-                     "unit": "GB/s", "frac": r["kernel_GBs"] / HBM_PEAK_GBS,
-                     "bytes_per_launch": r["bytes_call"], "avg_launch_us": r["kernel_us"],
-                     "traffic": MEASURED_TRAFFIC.get((wl.name, kname))},
+                                  KERNEL_PATHS[kname.split("+")[-1]]},
     }
+    out.update(summary(wl, r))
+    out["gpu_clocks"] = gpu_clocks()
     if r.get("ms_per_step_multi"):
         # the same steps with the independent layer calls spread over several streams (tails overlap)
         out["also_streams"] = a.also_streams
@@ -400,6 +475,17 @@ def main():
         out["step_hbm_frac_grouped"] = r["bytes_call"] * wl.layers / (r["ms_per_step_grouped"] * 1e-3) / 1e9 / HBM_PEAK_GBS
     if "cpu_baseline" in r:
         out["cpu_baseline"] = r["cpu_baseline"]
+    if a.also and a.workload == "cfg3" and flags == 0 and a.streams == 1:
+        # the other workload the bandwidth target names, measured by this same process right after:
+        # one cache, batch 128, 16384 slots (8 GiB of K and V per call)
+        w4 = W.CONFIGS[4]
+        r4 = measure(w4, 0, DEFAULT_STEPS[4], a.warmup)
+        blk = {"workload": w4.name, "batch": w4.batch, "q_heads": w4.q_heads, "kv_heads": w4.kv_heads,
+               "head_dim": w4.head_dim, "budget": w4.budget, "layers": w4.layers, "steps": DEFAULT_STEPS[4],
+               "warmup": r4["warm"], "ms_per_step": r4["ms_per_step"], "tokens_per_s": r4["tokens_per_s"],
+               "kernel_path": KERNEL_PATHS[r4["kernel"].split("+")[-1]]}
+        blk.update(summary(w4, r4))
+        out["also"] = [blk]
     print(json.dumps(out))
 
 

@@ -101,7 +101,9 @@ typedef enum { LF_F32 = 0, LF_BF16 = 1 } lf_dtype;
 
 typedef struct {
     int32_t batch;    /* B   >= 1                                            */
-    int32_t q_heads;  /* Hq, a multiple of kv_heads; Hq/Hkv <= 16 (f32: <= 8) */
+    int32_t q_heads;  /* Hq, a multiple of kv_heads.  Hq/Hkv <= 16 for bf16 with head_dim 128
+                         (matrix-core kernels); <= 8 for fp32, for head_dim 64 and with
+                         LF_FLAG_FORCE_VALU (vector-ALU kernel): LF_ERR_UNSUPPORTED beyond */
     int32_t kv_heads; /* Hkv >= 1                                            */
     int32_t head_dim; /* D: 64 or 128                                        */
     int32_t budget;   /* N: slots of the static cache, 1 <= N <= 2^24        */
@@ -111,6 +113,21 @@ typedef struct {
 
 /* Bytes of device workspace a cache with this geometry needs (0 if cfg is invalid). */
 LF_API size_t longflow_workspace_bytes(const lf_config *cfg);
+
+/*
+ * How longflow_init_cache carves the workspace (host-only query; launches nothing, needs no
+ * GPU): the regions in address order, each with its byte offset from the (256-byte aligned)
+ * workspace base and the bytes the kernels may index in it.  With regions == NULL only the
+ * count is returned in *n_regions.  For bounds checks on the host: regions never overlap and
+ * end inside longflow_workspace_bytes(cfg).
+ */
+typedef struct {
+    char name[24];
+    uint64_t offset;
+    uint64_t bytes;
+} lf_region;
+LF_API int longflow_workspace_regions(const lf_config *cfg, lf_region *regions, int32_t max_regions,
+                                      int32_t *n_regions);
 
 /*
  * Create a cache over caller-owned storage (prefill stage of Sec. 2.1).
@@ -163,7 +180,9 @@ LF_API int longflow_decode_step(longflow_cache_t *cache, const void *q,
  *   evict_idx   device int32 [B][Hkv] or NULL: as after the last of the T steps
  * All pointers 16-byte aligned.  LF_ERR_INVALID_ARG if T < 1; LF_ERR_STATE for a
  * full cache without a pending slot; LF_ERR_UNSUPPORTED with LF_FLAG_ATTENTION_ONLY
- * or LF_FLAG_UNFUSED_ACCUM.
+ * or LF_FLAG_UNFUSED_ACCUM.  Those are found before anything is launched.  If a launch
+ * itself fails part-way (LF_ERR_HIP) the cache holds the tokens issued up to there and
+ * longflow_valid_count says how many rows that is.
  */
 LF_API int longflow_fill_steps(longflow_cache_t *cache, int32_t T, const void *q,
                         const void *k_new, const void *v_new,
@@ -177,8 +196,10 @@ LF_API int longflow_fill_steps(longflow_cache_t *cache, int32_t T, const void *q
  */
 LF_API int longflow_scores(longflow_cache_t *cache, float *scores, void *hip_stream);
 
-/* Name the slot the next call overwrites (resume, tests): device int32 [B][Hkv],
- * each in [0, N).  Only legal once the cache is full. */
+/* Name the slot the next call overwrites -- the "slot selected in the previous step" that the
+ * current K/V covers in Fig. 2 left, here chosen by the caller (resume from saved state, a cache
+ * created full, tests): device int32 [B][Hkv], each in [0, N).  Only legal once the cache is
+ * full; while it is filling the next slot is the valid count (Sec. 3.4, static memory). */
 LF_API int longflow_set_pending(longflow_cache_t *cache, const int32_t *slots, void *hip_stream);
 
 /*
@@ -262,8 +283,9 @@ LF_API int longflow_plan_info(const lf_config *cfg, lf_plan_info *info);
  *   longflow_group_workspace_bytes  device bytes a group of n_caches needs (0 if n_caches < 1)
  *   longflow_group_create   caches: host array of n_caches handles with identical lf_config
  *                           and the same valid count; workspace: device, 256-byte aligned,
- *                           owned by the caller, must outlive the group.  Copies a table of
- *                           per-cache pointers into it on hip_stream.
+ *                           owned by the caller, must outlive the group.  Writes a table of
+ *                           per-cache pointers into it with small kernels on hip_stream
+ *                           (asynchronous like every other call).
  *   longflow_group_decode_step  one decode step of every member.  q/out are device
  *                           [n_caches][B][Hq][D], k_new/v_new [n_caches][B][Hkv][D],
  *                           evict_idx int32 [n_caches][B][Hkv] or NULL; otherwise as

@@ -19,18 +19,26 @@ import numpy as np
 _HERE = os.path.dirname(os.path.abspath(__file__))
 _SRC = os.path.join(_HERE, "longflow_oracle.c")
 _LIB = os.path.join(_HERE, "liblongflow_oracle.so")
+_LIB_SANITIZED = os.path.join(_HERE, "liblongflow_oracle_san.so")
 
 _dp = ctypes.POINTER(ctypes.c_double)
 _ip = ctypes.POINTER(ctypes.c_int32)
 
 
-def build(force: bool = False) -> str:
-    """Compile the oracle with gcc (plain C, OpenMP over independent units)."""
-    if force or not os.path.exists(_LIB) or os.path.getmtime(_LIB) < os.path.getmtime(_SRC):
-        cmd = ["gcc", "-O2", "-std=c11", "-fopenmp", "-fPIC", "-shared",
-               "-fvisibility=hidden", "-o", _LIB, _SRC, "-lm"]
+def build(force: bool = False, sanitize: bool = False) -> str:
+    """Compile the oracle with gcc (plain C, OpenMP over independent units).
+
+    sanitize: the same file under AddressSanitizer + UndefinedBehaviorSanitizer (any report
+    aborts), as a library of its own; the process that loads it must have libasan preloaded.
+    """
+    out = _LIB_SANITIZED if sanitize else _LIB
+    if force or not os.path.exists(out) or os.path.getmtime(out) < os.path.getmtime(_SRC):
+        opt = ["-O1", "-g", "-fno-omit-frame-pointer", "-fsanitize=address,undefined",
+               "-fno-sanitize-recover=all"] if sanitize else ["-O2"]
+        cmd = ["gcc", *opt, "-std=c11", "-fopenmp", "-fPIC", "-shared",
+               "-fvisibility=hidden", "-o", out, _SRC, "-lm"]
         subprocess.run(cmd, check=True)
-    return _LIB
+    return out
 
 
 _lib = None
@@ -39,7 +47,8 @@ _lib = None
 def lib():
     global _lib
     if _lib is None:
-        L = ctypes.CDLL(build())
+        # LFO_SANITIZE=1: run everything through the sanitizer build (see tests/test_oracle_sanitized.py)
+        L = ctypes.CDLL(build(sanitize=os.environ.get("LFO_SANITIZE") == "1"))
         L.lfo_attend_unit.argtypes = [ctypes.c_int] * 3 + [_dp] * 6
         L.lfo_attend_unit.restype = None
         L.lfo_argmin.argtypes = [ctypes.c_int, _dp]

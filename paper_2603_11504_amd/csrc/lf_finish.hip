@@ -1,5 +1,7 @@
 // Kernels off the per-step path: value-norm side array at cache init, on-demand score
 // read-back, small fills.
+#include <cstring>
+
 #include "lf_device.h"
 #include "lf_host.h"
 #include "lf_split_tail.h"
@@ -40,6 +42,22 @@ __global__ void fill_i32_kernel(int32_t *dst, int count, int32_t value)
 hipError_t launch_fill_i32(int32_t *dst, int count, int32_t value, hipStream_t s)
 {
     hipLaunchKernelGGL(fill_i32_kernel, dim3((count + 255) / 256), dim3(256), 0, s, dst, count, value);
+    return hipGetLastError();
+}
+
+struct TableEntryBlob { uint32_t w[kTableEntryMax / 4]; };
+__global__ void table_entry_kernel(uint32_t *dst, const TableEntryBlob e, int words)
+{
+    const int i = threadIdx.x;
+    if (i < words) dst[i] = e.w[i];
+}
+hipError_t launch_table_entry(void *dst, const void *entry, size_t bytes, hipStream_t s)
+{
+    if (bytes > kTableEntryMax || (bytes & 3u)) return hipErrorInvalidValue;
+    TableEntryBlob e;
+    memset(&e, 0, sizeof(e));
+    memcpy(&e, entry, bytes);
+    hipLaunchKernelGGL(table_entry_kernel, dim3(1), dim3(kTableEntryMax / 4), 0, s, (uint32_t *)dst, e, (int)(bytes / 4));
     return hipGetLastError();
 }
 

@@ -53,6 +53,11 @@ struct Plan {
 struct Layout {
     size_t off_pending, off_arrive, off_dumped, off_hole, off_q, off_part_m, off_part_l, off_part_o, off_fin_m, off_fin_l,
         off_stash_w, off_stash_m, off_lu, off_acc, off_acc_part_v, off_acc_part_i, total;
+    // the same carving as a list (name, offset, bytes asked for), in order: longflow_workspace_regions
+    static constexpr int kMaxRegions = 24;
+    int n_regions;
+    const char *region_name[kMaxRegions];
+    size_t region_off[kMaxRegions], region_bytes[kMaxRegions];
 };
 
 // Split-K geometry for a cache of `units` independent (batch, KV head) pairs.
@@ -100,6 +105,10 @@ hipError_t launch_scores(const Plan &p, int n, float *scores, hipStream_t s);
 hipError_t launch_evict_lowest(const Plan &p, int n, int k, double *scratch, int32_t *evicted, hipStream_t s);
 hipError_t launch_l1norms(const Plan &p, int n_rows, hipStream_t s);
 hipError_t launch_fill_i32(int32_t *dst, int count, int32_t value, hipStream_t s);
+// A group's table entry (at most kTableEntryMax bytes, a multiple of 4) travels to dst as a kernel
+// argument: no host buffer has to outlive the call and nothing synchronises with the host.
+constexpr size_t kTableEntryMax = 256;
+hipError_t launch_table_entry(void *dst, const void *entry, size_t bytes, hipStream_t s);
 // Explicit mask (device uint8 [units][N], nonzero = valid): rewrites the side array, zeroes
 // the K/V rows of invalid slots and points `pending` of every unit that has an invalid
 // slot at its lowest one.

@@ -236,6 +236,7 @@ size_t split_table_entry_bytes() { return sizeof(SplitTailArgs<float>); }
 void split_table_entry(const Plan &p, void *dst)
 {
     static_assert(sizeof(SplitTailArgs<float>) == sizeof(SplitTailArgs<bf16_t>), "one table layout for both element types");
+    static_assert(sizeof(SplitTailArgs<float>) <= kTableEntryMax && sizeof(SplitTailArgs<float>) % 4 == 0, "entry travels as a kernel argument");
     const StepIo none = {nullptr, nullptr, nullptr, nullptr, nullptr};
     if (p.dtype == 0) {
         SplitTailArgs<float> a = make_tail_args<float>(p, none, p.N);

@@ -883,6 +883,7 @@ static UnitArgs unit_args_of(const Plan &p, int n, int S)
     return a;
 }
 
+static_assert(sizeof(UnitArgs) <= kTableEntryMax && sizeof(UnitArgs) % 4 == 0, "entry travels as a kernel argument");
 size_t unit_mfma_table_entry_bytes() { return sizeof(UnitArgs); }
 
 void unit_mfma_table_entry(const Plan &p, void *dst)

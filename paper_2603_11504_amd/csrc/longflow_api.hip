@@ -116,32 +116,39 @@ static void fill_plan(const lf_config *cfg, Plan *p)
 static Layout layout_of(const Plan &p)
 {
     Layout l;
+    l.n_regions = 0;
     const size_t esz = p.dtype == LF_F32 ? 4 : 2;
     size_t off = 0;
-    auto take = [&](size_t bytes) { size_t o = off; off = align_up(off + bytes, 256); return o; };
-    l.off_pending = take(sizeof(int32_t) * p.units);
-    l.off_arrive = take(sizeof(int32_t) * p.units);
-    l.off_dumped = take(sizeof(int32_t) * p.units);
-    l.off_hole = take(sizeof(int32_t) * p.units);
-    l.off_q = take(esz * (size_t)p.B * p.Hq * p.D);
-    l.off_part_m = take(sizeof(float) * (size_t)p.units * p.C * kMaxGroup);
-    l.off_part_l = take(sizeof(float) * (size_t)p.units * p.C * kMaxGroup);
-    l.off_part_o = take(sizeof(float) * (size_t)p.units * p.C * p.G * p.D);
-    l.off_fin_m = take(sizeof(float) * (size_t)p.units * p.G);
-    l.off_fin_l = take(sizeof(float) * (size_t)p.units * p.G);
+    auto take = [&](const char *name, size_t bytes) {
+        size_t o = off;
+        off = align_up(off + bytes, 256);
+        l.region_name[l.n_regions] = name; l.region_off[l.n_regions] = o; l.region_bytes[l.n_regions] = bytes;
+        ++l.n_regions;
+        return o;
+    };
+    l.off_pending = take("pending", sizeof(int32_t) * p.units);
+    l.off_arrive = take("arrive", sizeof(int32_t) * p.units);
+    l.off_dumped = take("dumped", sizeof(int32_t) * p.units);
+    l.off_hole = take("first_hole", sizeof(int32_t) * p.units);
+    l.off_q = take("q_last", esz * (size_t)p.B * p.Hq * p.D);
+    l.off_part_m = take("part_m", sizeof(float) * (size_t)p.units * p.C * kMaxGroup);
+    l.off_part_l = take("part_l", sizeof(float) * (size_t)p.units * p.C * kMaxGroup);
+    l.off_part_o = take("part_o", sizeof(float) * (size_t)p.units * p.C * p.G * p.D);
+    l.off_fin_m = take("fin_m", sizeof(float) * (size_t)p.units * p.G);
+    l.off_fin_l = take("fin_l", sizeof(float) * (size_t)p.units * p.G);
     // per-slot screening data in device memory: bf16 stash on the split path, 1-byte code
     // dumps when several workgroups share a unit, nothing when one workgroup owns it
     const bool stash = !(p.flags & LF_FLAG_ATTENTION_ONLY) && !(p.use_unit && p.unit_S == 1);
     const size_t per_slot = p.use_unit ? 1 : sizeof(uint16_t);
-    l.off_stash_w = take(stash ? per_slot * (size_t)p.units * p.ntiles * p.G * kTile : 0);
-    l.off_stash_m = take(stash ? sizeof(float) * (size_t)p.units * p.ntiles * p.G : 0);
+    l.off_stash_w = take("stash_w", stash ? per_slot * (size_t)p.units * p.ntiles * p.G * kTile : 0);
+    l.off_stash_m = take("stash_m", stash ? sizeof(float) * (size_t)p.units * p.ntiles * p.G : 0);
     // per-slot side array: log2 ||v||_1 for the matrix-core kernels, validity under an explicit mask for all
-    l.off_lu = take(!(p.flags & LF_FLAG_ATTENTION_ONLY) ? sizeof(float) * (size_t)p.units * p.ntiles * kTile : 0);
+    l.off_lu = take("lu", !(p.flags & LF_FLAG_ATTENTION_ONLY) ? sizeof(float) * (size_t)p.units * p.ntiles * kTile : 0);
     int la = 0, ca = 0;
     if (p.unfused) unfused_geometry(p.units, p.N, &la, &ca);
-    l.off_acc = take(p.unfused ? sizeof(float) * (size_t)p.units * p.ntiles * kTile : 0);
-    l.off_acc_part_v = take(sizeof(float) * (size_t)p.units * ca);
-    l.off_acc_part_i = take(sizeof(int32_t) * (size_t)p.units * ca);
+    l.off_acc = take("acc", p.unfused ? sizeof(float) * (size_t)p.units * p.ntiles * kTile : 0);
+    l.off_acc_part_v = take("acc_part_v", sizeof(float) * (size_t)p.units * ca);
+    l.off_acc_part_i = take("acc_part_i", sizeof(int32_t) * (size_t)p.units * ca);
     l.total = off;
     return l;
 }
@@ -183,6 +190,27 @@ size_t longflow_workspace_bytes(const lf_config *cfg)
     Plan p;
     fill_plan(cfg, &p);
     return layout_of(p).total;
+}
+
+int longflow_workspace_regions(const lf_config *cfg, lf_region *regions, int32_t max_regions, int32_t *n_regions)
+{
+    if (!n_regions) return fail(LF_ERR_INVALID_ARG, "n_regions is NULL");
+    *n_regions = 0;
+    const int rc = validate(cfg);
+    if (rc != LF_OK) return rc;
+    Plan p;
+    fill_plan(cfg, &p);
+    const Layout l = layout_of(p);
+    *n_regions = l.n_regions;
+    if (!regions) return LF_OK;
+    if (max_regions < l.n_regions) return fail(LF_ERR_INVALID_ARG, "%d regions, room for %d", l.n_regions, max_regions);
+    for (int i = 0; i < l.n_regions; ++i) {
+        memset(&regions[i], 0, sizeof(regions[i]));
+        strncpy(regions[i].name, l.region_name[i], sizeof(regions[i].name) - 1);
+        regions[i].offset = l.region_off[i];
+        regions[i].bytes = l.region_bytes[i];
+    }
+    return LF_OK;
 }
 
 int longflow_init_cache(longflow_cache_t **out, const lf_config *cfg, void *k_cache, void *v_cache,
@@ -335,15 +363,17 @@ int longflow_fill_steps(longflow_cache_t *cache, int32_t T, const void *q, const
         Tb = Tfill - 1;
         // one workgroup per (unit, group of tokens): keep each launch's grid below 2^30 workgroups
         const long long per_launch = std::max(1ll, (1ll << 30) / p.units) * fill_tokens_per_pass(p.G);
-        hipError_t e = hipSuccess;
-        for (long long done = 0; done < Tb && e == hipSuccess; done += per_launch) {
+        // (a launch failure leaves the cache at the last chunk that went through: count and the
+        // pending slot are advanced chunk by chunk)
+        const int n0 = c->count;
+        for (long long done = 0; done < Tb; done += per_launch) {
             const int Tc = (int)std::min<long long>(per_launch, Tb - done);
-            e = launch_fill_bulk(p, (const char *)q + done * q_step, (const char *)k_new + done * kv_step,
-                                 (const char *)v_new + done * kv_step, (char *)out + done * q_step, c->count + (int)done, Tc, s);
+            hipError_t e = launch_fill_bulk(p, (const char *)q + done * q_step, (const char *)k_new + done * kv_step,
+                                            (const char *)v_new + done * kv_step, (char *)out + done * q_step, n0 + (int)done, Tc, s);
+            if (e == hipSuccess) e = launch_fill_i32(p.pending, p.units, n0 + (int)done + Tc, s);
+            if (e != hipSuccess) return fail(LF_ERR_HIP, "bulk fill launch: %s", hipGetErrorString(e));
+            c->count = n0 + (int)done + Tc;
         }
-        if (e == hipSuccess) e = launch_fill_i32(p.pending, p.units, c->count + Tb, s);
-        if (e != hipSuccess) return fail(LF_ERR_HIP, "bulk fill launch: %s", hipGetErrorString(e));
-        c->count += Tb;
     }
     for (int t = Tb; t < T; ++t) {
         const int rc = longflow_decode_step(cache, (const char *)q + t * q_step, (const char *)k_new + t * kv_step,
@@ -457,14 +487,14 @@ int longflow_group_create(longflow_group_t **group, longflow_cache_t *const *cac
     // one entry per member, in the layout of the kernel family its plan uses
     const bool unit = members[0]->plan.use_unit;
     const size_t eb = unit ? unit_mfma_table_entry_bytes() : split_table_entry_bytes();
-    std::vector<char> host(eb * (size_t)n_caches);
-    for (int i = 0; i < n_caches; ++i) {
-        if (unit) unit_mfma_table_entry(members[i]->plan, host.data() + eb * i);
-        else      split_table_entry(members[i]->plan, host.data() + eb * i);
+    if (eb > kTableEntryMax) return fail(LF_ERR_UNSUPPORTED, "table entry of %zu bytes", eb);
+    for (int i = 0; i < n_caches; ++i) { // each entry travels as a kernel argument: asynchronous, nothing to keep alive
+        char entry[kTableEntryMax];
+        if (unit) unit_mfma_table_entry(members[i]->plan, entry);
+        else      split_table_entry(members[i]->plan, entry);
+        hipError_t e = launch_table_entry((char *)workspace + eb * i, entry, eb, (hipStream_t)hip_stream);
+        if (e != hipSuccess) return fail(LF_ERR_HIP, "group table write: %s", hipGetErrorString(e));
     }
-    hipError_t e = hipMemcpyAsync(workspace, host.data(), host.size(), hipMemcpyHostToDevice, (hipStream_t)hip_stream);
-    if (e == hipSuccess) e = hipStreamSynchronize((hipStream_t)hip_stream); // `host` goes out of scope
-    if (e != hipSuccess) return fail(LF_ERR_HIP, "group table copy: %s", hipGetErrorString(e));
     longflow_group *g = new longflow_group;
     g->magic = kGroupMagic;
     g->members = members;

@@ -23,7 +23,7 @@ LF_FLAG_FORCE_UNIT = 8
 LF_FLAG_UNFUSED_ACCUM = 16
 LF_FLAG_MAX_FREE = 32
 
-EXPORTS = ("longflow_workspace_bytes", "longflow_init_cache", "longflow_decode_step",
+EXPORTS = ("longflow_workspace_bytes", "longflow_workspace_regions", "longflow_init_cache", "longflow_decode_step",
            "longflow_fill_steps", "longflow_scores", "longflow_set_pending", "longflow_set_mask", "longflow_get_mask", "longflow_evict_scratch_bytes",
            "longflow_evict_lowest", "longflow_valid_count",
            "longflow_destroy_cache", "longflow_last_error", "longflow_profile_begin",
@@ -41,6 +41,10 @@ class lf_plan_info(ctypes.Structure):
     _fields_ = [("path", ctypes.c_int32), ("workgroups_per_unit", ctypes.c_int32),
                 ("slots_per_workgroup", ctypes.c_int32), ("launches_per_step", ctypes.c_int32),
                 ("threads_per_workgroup", ctypes.c_int32), ("lds_bytes", ctypes.c_uint32)]
+
+
+class lf_region(ctypes.Structure):
+    _fields_ = [("name", ctypes.c_char * 24), ("offset", ctypes.c_uint64), ("bytes", ctypes.c_uint64)]
 
 
 LF_PATH_SPLIT_VALU, LF_PATH_SPLIT_MFMA, LF_PATH_UNIT_MFMA = range(3)
@@ -66,6 +70,9 @@ def lib():
         vp, i32 = ctypes.c_void_p, ctypes.c_int32
         L.longflow_workspace_bytes.argtypes = [ctypes.POINTER(lf_config)]
         L.longflow_workspace_bytes.restype = ctypes.c_size_t
+        L.longflow_workspace_regions.argtypes = [ctypes.POINTER(lf_config), ctypes.POINTER(lf_region), i32,
+                                                 ctypes.POINTER(i32)]
+        L.longflow_workspace_regions.restype = ctypes.c_int
         L.longflow_init_cache.argtypes = [ctypes.POINTER(vp), ctypes.POINTER(lf_config), vp, vp, vp, vp,
                                           i32, vp, ctypes.c_size_t, vp]
         L.longflow_init_cache.restype = ctypes.c_int
@@ -140,6 +147,15 @@ def make_config(batch, q_heads, kv_heads, head_dim, budget, dtype, flags=0) -> l
 
 def longflow_workspace_bytes(cfg: lf_config) -> int:
     return int(lib().longflow_workspace_bytes(ctypes.byref(cfg)))
+
+
+def longflow_workspace_regions(cfg: lf_config):
+    """-> [(name, offset, bytes)] in address order: how the workspace is carved."""
+    n = ctypes.c_int32()
+    _check(lib().longflow_workspace_regions(ctypes.byref(cfg), None, 0, ctypes.byref(n)))
+    regs = (lf_region * n.value)()
+    _check(lib().longflow_workspace_regions(ctypes.byref(cfg), regs, n.value, ctypes.byref(n)))
+    return [(r.name.decode(), int(r.offset), int(r.bytes)) for r in regs]
 
 
 def longflow_plan_info(cfg: lf_config) -> lf_plan_info:

@@ -190,3 +190,61 @@ def test_binding_checks_what_the_c_side_cannot_see():
         with pytest.raises(ValueError):
             lf._arg(bad, n, dt, "q")
     assert lf._arg(None, 5, bf, "k_new") is None
+
+
+# ------------------------------------------------------------------ workspace carving (host logic)
+
+def test_workspace_regions_never_overlap_and_hold_every_index_the_kernels_form():
+    # Bounds checks on the host: for every accepted configuration the regions of the workspace are
+    # disjoint, aligned and inside longflow_workspace_bytes, and each is at least as large as the
+    # highest index its kernels form.  The index bounds below are written out from the kernels'
+    # addressing, independently of the library's own size computation:
+    #   counters, pending      one int32 per (batch, KV head) unit
+    #   q_last                 the step's query, [B][Hq][D] elements
+    #   part_m / part_l        fused kernel: [unit][workgroup of the unit][16] floats;
+    #                          split-K: [unit][split][G] floats
+    #   part_o                 [unit][workgroup or split][G][D] floats
+    #   stash_w                fused kernel, several workgroups per unit: 1-byte codes [unit][G][tiles*16];
+    #                          split-K: bf16 [unit][tile][G][16]
+    #   stash_m                [unit][tile][G] floats
+    #   lu                     [unit][tiles*16] floats
+    #   fin_m / fin_l          [unit][G] floats
+    checked = 0
+    for key, cfg, info in _plans():
+        dtype, D, G, Hkv, B, N, flags = key
+        units, esz, tiles = B * Hkv, (4 if dtype == "f32" else 2), (N + 15) // 16
+        regs = lf.longflow_workspace_regions(cfg)
+        total = lf.longflow_workspace_bytes(cfg)
+        names = [r[0] for r in regs]
+        assert len(set(names)) == len(names)
+        end = 0
+        for name, off, size in regs:
+            assert off % 256 == 0 and off >= end, (key, name)      # aligned, in order, no overlap
+            end = off + size
+        assert end <= total
+        have = {name: size for name, _, size in regs}
+        wgs = info.workgroups_per_unit
+        scoring = not flags & lf.LF_FLAG_ATTENTION_ONLY
+        need = {"pending": 4 * units, "arrive": 4 * units, "dumped": 4 * units, "first_hole": 4 * units,
+                "q_last": esz * B * G * Hkv * D, "fin_m": 4 * units * G, "fin_l": 4 * units * G,
+                "part_o": 4 * units * wgs * G * D}
+        if info.path == lf.LF_PATH_UNIT_MFMA:
+            need["part_m"] = need["part_l"] = 4 * units * wgs * 16
+            if scoring and wgs > 1:
+                need["stash_w"] = units * G * tiles * 16
+                need["stash_m"] = 4 * units * tiles * G
+        else:
+            need["part_m"] = need["part_l"] = 4 * units * wgs * G
+            if scoring:
+                need["stash_w"] = 2 * units * tiles * G * 16
+                need["stash_m"] = 4 * units * tiles * G
+        if scoring:
+            need["lu"] = 4 * units * tiles * 16
+        for name, size in need.items():
+            assert have[name] >= size, (key, name, have[name], size)
+        checked += 1
+    assert checked > 1000
+    # the comparison path's books
+    cfg = lf.make_config(4, 8, 2, 128, 1000, "bf16", lf.LF_FLAG_UNFUSED_ACCUM)
+    have = {name: size for name, _, size in lf.longflow_workspace_regions(cfg)}
+    assert have["acc"] >= 4 * 8 * 63 * 16 and have["acc_part_v"] > 0 and have["acc_part_i"] == have["acc_part_v"]
