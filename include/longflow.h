@@ -242,6 +242,22 @@ LF_API size_t longflow_evict_scratch_bytes(const lf_config *cfg);
 LF_API int longflow_evict_lowest(longflow_cache_t *cache, int32_t k, void *scratch, size_t scratch_bytes,
                                  int32_t *evicted, void *hip_stream);
 
+/*
+ * longflow_evict_lowest for callers that cannot allocate device memory or pass a scratch
+ * buffer: code under HIP graph capture, tight serving loops, harnesses that forbid
+ * hipMalloc.  Same arguments minus the scratch, same kernels, same results; the
+ * double-precision scores go to a device array built into the library (8 MiB, held by
+ * every GPU the library runs on until the process ends; its address on a GPU is resolved
+ * by longflow_init_cache on that GPU).  The call allocates and frees nothing.
+ *   limit    batch * kv_heads * budget <= LF_EVICT_STATIC_MAX_SLOTS, else LF_ERR_WORKSPACE
+ *            (nothing launched, cache untouched): use longflow_evict_lowest instead
+ * All calls on one GPU share the one array: calls whose work overlaps on a GPU (different
+ * streams, different caches) race on it and must be serialised by the caller.  Nothing in
+ * it needs clearing between calls: each call writes every entry it reads.
+ */
+#define LF_EVICT_STATIC_MAX_SLOTS (1u << 20)
+LF_API int longflow_evict_lowest_static(longflow_cache_t *cache, int32_t k, int32_t *evicted, void *hip_stream);
+
 /* Valid slots = min(tokens seen, N); negative on a NULL handle. */
 LF_API int longflow_valid_count(const longflow_cache_t *cache);
 

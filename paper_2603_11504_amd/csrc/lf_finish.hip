@@ -1,6 +1,7 @@
 // Kernels off the per-step path: value-norm side array at cache init, on-demand score
 // read-back, small fills.
 #include <cstring>
+#include <mutex>
 
 #include "lf_device.h"
 #include "lf_host.h"
@@ -299,6 +300,38 @@ hipError_t launch_evict_lowest(const Plan &p, int n, int k, double *scratch, int
     else              { if (p.D == 64) LF_EV(bf16_t, 64); else LF_EV(bf16_t, 128); }
 #undef LF_EV
     return hipGetLastError();
+}
+
+// ---------------------------------------------------------------------------------------
+// Score scratch for callers that cannot allocate (longflow_evict_lowest_static): the
+// double-precision scores of one batch eviction live in this file-scope device array
+// instead of a caller-supplied buffer.  Every GPU the library runs on holds its own copy at
+// its own address until the process ends; `scratch` itself is only the host-side stand-in
+// for the symbol, never a device address: the address is asked for once per device and kept.
+// The score kernel writes every entry the selection kernel reads, so nothing has to be
+// cleared between calls; calls that overlap on one GPU would race on it.
+// ---------------------------------------------------------------------------------------
+static __device__ __align__(256) double scratch[kStaticScoreSlots];
+
+hipError_t static_score_scratch(double **ptr)
+{
+    constexpr int kMaxDevices = 64;
+    static double *addr[kMaxDevices] = {};
+    static std::mutex mu;
+    int dev = 0;
+    hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess) return e;
+    if (dev < 0 || dev >= kMaxDevices) return hipErrorInvalidDevice;
+    std::lock_guard<std::mutex> lock(mu);
+    if (!addr[dev]) {
+        void *p = nullptr;
+        e = hipGetSymbolAddress(&p, HIP_SYMBOL(scratch));
+        if (e != hipSuccess) return e;
+        if (!p) return hipErrorInvalidSymbol;
+        addr[dev] = (double *)p;
+    }
+    if (ptr) *ptr = addr[dev];
+    return hipSuccess;
 }
 
 } // namespace lf

@@ -103,6 +103,12 @@ hipError_t launch_scores(const Plan &p, int n, float *scores, hipStream_t s);
 // Drop the k lowest-scoring valid slots of every unit (scores of the last step, in double
 // precision via `scratch`, device double [units][N]); they become holes of the explicit mask.
 hipError_t launch_evict_lowest(const Plan &p, int n, int k, double *scratch, int32_t *evicted, hipStream_t s);
+// Batch eviction without a caller-supplied scratch buffer: a file-scope device array of
+// kStaticScoreSlots doubles (one per slot of the cache) stands in.  static_score_scratch
+// resolves its address on the current device (once per device; later calls are a table
+// look-up) and stores it in *ptr if ptr is not null.
+constexpr size_t kStaticScoreSlots = (size_t)1 << 20; // 8 MiB per GPU
+hipError_t static_score_scratch(double **ptr);
 hipError_t launch_l1norms(const Plan &p, int n_rows, hipStream_t s);
 hipError_t launch_fill_i32(int32_t *dst, int count, int32_t value, hipStream_t s);
 // A group's table entry (at most kTableEntryMax bytes, a multiple of 4) travels to dst as a kernel

@@ -253,6 +253,12 @@ int longflow_init_cache(longflow_cache_t **out, const lf_config *cfg, void *k_ca
     p.acc_part_i = (int32_t *)(ws + l.off_acc_part_i);
 
     hipStream_t s = (hipStream_t)hip_stream;
+    {   // set-up for longflow_evict_lowest_static: its device array's address on this GPU is
+        // resolved here, so that the call itself (possibly made where nothing may allocate or
+        // query the runtime) only looks it up
+        hipError_t e = static_score_scratch(nullptr);
+        if (e != hipSuccess) return fail(LF_ERR_HIP, "static scratch address: %s", hipGetErrorString(e));
+    }
     if (n_init > 0) {
         const size_t esz = p.dtype == LF_F32 ? 4 : 2;
         const size_t row = esz * p.D;
@@ -604,6 +610,29 @@ int longflow_evict_lowest(longflow_cache_t *cache, int32_t k, void *scratch, siz
     c->plan.masked = true;
     c->count = p.N;
     c->has_pending = true; // every unit now has a hole, and its lowest one is pending
+    return LF_OK;
+}
+
+int longflow_evict_lowest_static(longflow_cache_t *cache, int32_t k, int32_t *evicted, void *hip_stream)
+{
+    longflow_cache *c = checked(cache);
+    if (!c) return fail(LF_ERR_STATE, "invalid or destroyed cache handle");
+    const Plan &p = c->plan;
+    if (p.unfused) return fail(LF_ERR_UNSUPPORTED, "the unfused comparison path evicts one slot per step only");
+    if (p.flags & LF_FLAG_ATTENTION_ONLY) return fail(LF_ERR_UNSUPPORTED, "an attention-only cache evicts nothing");
+    if ((size_t)p.units * p.N > kStaticScoreSlots)
+        return fail(LF_ERR_WORKSPACE, "batch*kv_heads*budget = %zu exceeds the %zu slots of the built-in scratch: "
+                    "use longflow_evict_lowest with a scratch buffer of your own", (size_t)p.units * p.N, kStaticScoreSlots);
+    if (!c->stepped) return fail(LF_ERR_STATE, "no decode step has run yet: there are no scores");
+    if (k < 1 || k >= p.N) return fail(LF_ERR_INVALID_ARG, "k = %d outside [1, %d)", k, p.N);
+    double *scores = nullptr;
+    hipError_t e = static_score_scratch(&scores);
+    if (e != hipSuccess) return fail(LF_ERR_HIP, "static scratch address: %s", hipGetErrorString(e));
+    e = launch_evict_lowest(p, c->count, k, scores, evicted, (hipStream_t)hip_stream);
+    if (e != hipSuccess) return fail(LF_ERR_HIP, "batch eviction launch: %s", hipGetErrorString(e));
+    c->plan.masked = true;
+    c->count = p.N;
+    c->has_pending = true;
     return LF_OK;
 }
 

@@ -22,10 +22,11 @@ LF_FLAG_FORCE_SPLIT = 4
 LF_FLAG_FORCE_UNIT = 8
 LF_FLAG_UNFUSED_ACCUM = 16
 LF_FLAG_MAX_FREE = 32
+LF_EVICT_STATIC_MAX_SLOTS = 1 << 20
 
 EXPORTS = ("longflow_workspace_bytes", "longflow_workspace_regions", "longflow_init_cache", "longflow_decode_step",
            "longflow_fill_steps", "longflow_scores", "longflow_set_pending", "longflow_set_mask", "longflow_get_mask", "longflow_evict_scratch_bytes",
-           "longflow_evict_lowest", "longflow_valid_count",
+           "longflow_evict_lowest", "longflow_evict_lowest_static", "longflow_valid_count",
            "longflow_destroy_cache", "longflow_last_error", "longflow_profile_begin",
            "longflow_profile_end", "longflow_plan_info", "longflow_group_workspace_bytes", "longflow_group_create",
            "longflow_group_decode_step", "longflow_group_destroy")
@@ -92,6 +93,8 @@ def lib():
         L.longflow_evict_scratch_bytes.restype = ctypes.c_size_t
         L.longflow_evict_lowest.argtypes = [vp, i32, vp, ctypes.c_size_t, vp, vp]
         L.longflow_evict_lowest.restype = ctypes.c_int
+        L.longflow_evict_lowest_static.argtypes = [vp, i32, vp, vp]
+        L.longflow_evict_lowest_static.restype = ctypes.c_int
         L.longflow_valid_count.argtypes = [vp]
         L.longflow_valid_count.restype = ctypes.c_int
         L.longflow_destroy_cache.argtypes = [vp]
@@ -252,6 +255,14 @@ class LongFlowCache:
         _check(lib().longflow_evict_lowest(self._h, k, _ptr(scratch), nbytes, _ptr(ev), _stream()))
         self._keep_scratch = scratch  # alive until the kernels that use it have run
         return ev
+
+    def evict_lowest_static(self, k, evicted=None):
+        """evict_lowest through the library's built-in scratch (no scratch buffer is passed or
+        allocated); `evicted` [B, Hkv, k] int32 may be given so that the call allocates nothing at all."""
+        if evicted is None:
+            evicted = torch.empty((self.cfg.batch, self.cfg.kv_heads, k), dtype=torch.int32, device=self.device)
+        _check(lib().longflow_evict_lowest_static(self._h, k, _arg(evicted, self._nu * k, torch.int32, "evicted"), _stream()))
+        return evicted
 
     def profile_begin(self, max_steps):
         _check(lib().longflow_profile_begin(self._h, max_steps))
