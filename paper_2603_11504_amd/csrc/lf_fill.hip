@@ -65,9 +65,9 @@ __global__ __launch_bounds__(256) void fill_attend_kernel(const FillArgs a)
     for (int nb = 0; nb < NB; ++nb) {
         const int t = t0 + nb * a.qpb + qi;
         const bool used = qi < a.qpb && t <= tl;
-        st[nb].init_column(used ? a.q + (((size_t)t * units + u) * G + h_of_r) * D : nullptr, a.n0 + t + 1, lane, a.scale_log2);
-        st[nb].Ku = a.Kc + (size_t)u * a.N * D;
-        st[nb].Vu = a.Vc + (size_t)u * a.N * D;
+        st[nb].init_column(used ? (g_cu16p)(a.q + (((size_t)t * units + u) * G + h_of_r) * D) : (g_cu16p) nullptr, a.n0 + t + 1, lane, a.scale_log2);
+        st[nb].Ku = (g_cu16p)(a.Kc + (size_t)u * a.N * D);
+        st[nb].Vu = (g_cu16p)(a.Vc + (size_t)u * a.N * D);
         st[nb].start = 0;
         st[nb].end = n_max;
     }

@@ -31,7 +31,6 @@ struct Plan {
     // carved out of the caller's workspace
     int32_t *pending;  // [units]
     int32_t *arrive;   // [units] arrival counters of cooperating workgroups, zero between steps
-    int32_t *dumped;   // [units] code-dump counters of the unit-resident kernel, zero between steps
     void *q_last;      // [B][Hq][D] copy of the last step's query (for longflow_scores)
     float *part_m;     // [units][C][G]    split-local softmax reference (log2 domain)
     float *part_l;     // [units][C][G]    split-local denominator
@@ -51,7 +50,7 @@ struct Plan {
 };
 
 struct Layout {
-    size_t off_pending, off_arrive, off_dumped, off_hole, off_q, off_part_m, off_part_l, off_part_o, off_fin_m, off_fin_l,
+    size_t off_pending, off_arrive, off_hole, off_q, off_part_m, off_part_l, off_part_o, off_fin_m, off_fin_l,
         off_stash_w, off_stash_m, off_lu, off_acc, off_acc_part_v, off_acc_part_i, total;
     // the same carving as a list (name, offset, bytes asked for), in order: longflow_workspace_regions
     static constexpr int kMaxRegions = 24;

@@ -65,6 +65,20 @@ constexpr float kNoRef = -3.0e38f;
 __host__ __device__ __forceinline__ int pos_of_slot(int s) { return 4 * ((s >> 1) & 3) + 2 * ((s >> 3) & 1) + (s & 1); }
 __host__ __device__ __forceinline__ int slot_of_pos(int p) { return 8 * ((p >> 1) & 1) + 2 * (p >> 2) + (p & 1); }
 
+// Pointers of the streaming core live in the global address space by type: a pointer that
+// reached the kernel through device memory (the table of a grouped launch) is generic to the
+// compiler, generic accesses become FLAT instructions, and a FLAT load can only be waited for
+// together with every other outstanding one -- which would undo the rotation of register
+// tiles below.
+typedef __attribute__((address_space(1))) const uint16_t *g_cu16p;
+typedef __attribute__((address_space(1))) const float *g_cf32p;
+typedef __attribute__((address_space(1))) uint16_t *g_u16p;
+typedef __attribute__((address_space(1))) float *g_f32p;
+typedef __attribute__((address_space(1))) const u32x4 *g_cu32x4p;
+typedef __attribute__((address_space(1))) const f32x4 *g_cf32x4p;
+typedef __attribute__((address_space(1))) u32x2 *g_u32x2p;
+typedef __attribute__((address_space(1))) uint32_t *g_u32p;
+
 struct TileRegs {
     u32x4 k[2][2]; // k[a][L]: row 8a + (r >> 1), line L, chunk 2g + (r & 1)
     u32x4 v[4];    // v[e]: row s(e), channels 8r .. 8r + 7
@@ -90,19 +104,19 @@ struct MfmaStreamer {
     f32x4 oacc[8];    // oacc[dd][v]: head 4g + v, channel 8r + dd
     float m, l;       // reference (log2 domain) and lane-partial denominator of head r
     // geometry
-    const uint16_t *Ku, *Vu;
-    const float *lu_unit; // [ntiles * 16] log2 ||v||_1 in position order
+    g_cu16p Ku, Vu;
+    g_cf32p lu_unit;      // [ntiles * 16] log2 ||v||_1 in position order
     int start, end, G, g, r;
     int limit; // CAUSAL: first slot column r does not see
     float scale_log2;
     // stash sinks
-    uint16_t *gs_w;   // kStashGlobal: [tile][G][16 positions] bf16
-    float *gs_m;      // kStashGlobal: [tile][G]
+    g_u16p gs_w;      // kStashGlobal: [tile][G][16 positions] bf16
+    g_f32p gs_m;      // kStashGlobal: [tile][G]
     uint8_t *ls_code; // kStashLds: [G][code_stride] bytes, position order, counted from `start`
     float *ls_ref;    // kStashLds: [tile][G], tiles counted from `start`
     int code_stride;
 
-    __device__ __forceinline__ void init(const uint16_t *q_unit, int G_, int lane, float scale)
+    __device__ __forceinline__ void init(g_cu16p q_unit, int G_, int lane, float scale)
     {
         G = G_; g = lane >> 4; r = lane & 15; scale_log2 = scale;
 #pragma unroll
@@ -110,7 +124,7 @@ struct MfmaStreamer {
 #pragma unroll
             for (int b = 0; b < 2; ++b) {
                 qreg[L][b] = u32x4{0u, 0u, 0u, 0u};
-                if (r < G) qreg[L][b] = *(const u32x4 *)(q_unit + (size_t)r * D + 64 * L + 8 * (2 * g + b));
+                if (r < G) qreg[L][b] = *(g_cu32x4p)(q_unit + (size_t)r * D + 64 * L + 8 * (2 * g + b));
             }
 #pragma unroll
         for (int dd = 0; dd < 8; ++dd) oacc[dd] = f32x4{0.f, 0.f, 0.f, 0.f};
@@ -120,7 +134,7 @@ struct MfmaStreamer {
 
     // One column of a multi-query product: the query row at q_col (nullptr = unused column),
     // which sees slots [0, limit_) only.
-    __device__ __forceinline__ void init_column(const uint16_t *q_col, int limit_, int lane, float scale)
+    __device__ __forceinline__ void init_column(g_cu16p q_col, int limit_, int lane, float scale)
     {
         G = 16; g = lane >> 4; r = lane & 15; scale_log2 = scale; limit = q_col ? limit_ : 0;
 #pragma unroll
@@ -128,7 +142,7 @@ struct MfmaStreamer {
 #pragma unroll
             for (int b = 0; b < 2; ++b) {
                 qreg[L][b] = u32x4{0u, 0u, 0u, 0u};
-                if (q_col) qreg[L][b] = *(const u32x4 *)(q_col + 64 * L + 8 * (2 * g + b));
+                if (q_col) qreg[L][b] = *(g_cu32x4p)(q_col + 64 * L + 8 * (2 * g + b));
             }
 #pragma unroll
         for (int dd = 0; dd < 8; ++dd) oacc[dd] = f32x4{0.f, 0.f, 0.f, 0.f};
@@ -145,7 +159,7 @@ struct MfmaStreamer {
         const int last = end - 1;
         // side array first: loads return in order, and its first use (the mask test right
         // after the logits) must not have to wait for this tile's V rows
-        if (STASH != kStashNone) t.lu = *(const f32x4 *)(lu_unit + base + 4 * g);
+        if (STASH != kStashNone) t.lu = *(g_cf32x4p)(lu_unit + base + 4 * g);
 #pragma unroll
         for (int a = 0; a < 2; ++a) {
             int krow = base + 8 * a + (r >> 1);
@@ -153,13 +167,13 @@ struct MfmaStreamer {
 #pragma unroll
             for (int L = 0; L < 2; ++L)
                 t.k[a][L] = __builtin_nontemporal_load(
-                    (const u32x4 *)(Ku + (size_t)krow * D + 64 * L + 8 * (2 * g + (r & 1))));
+                    (g_cu32x4p)(Ku + (size_t)krow * D + 64 * L + 8 * (2 * g + (r & 1))));
         }
 #pragma unroll
         for (int e = 0; e < 4; ++e) {
             int vrow = base + slot_off(e);
             if (RAGGED) vrow = min(vrow, last);
-            t.v[e] = __builtin_nontemporal_load((const u32x4 *)(Vu + (size_t)vrow * D + 8 * r));
+            t.v[e] = __builtin_nontemporal_load((g_cu32x4p)(Vu + (size_t)vrow * D + 8 * r));
         }
     }
 
@@ -256,7 +270,7 @@ struct MfmaStreamer {
 #pragma unroll
                 for (int e = 0; e < 4; ++e) w[e] = fast_exp2(t.lu[e] + lg[e]); // ||v||_1 * p
                 const size_t rec = (size_t)(base / kTile) * G + r;
-                *(u32x2 *)(gs_w + rec * kTile + 4 * g) = u32x2{pack_bf16x2(w[0], w[1]), pack_bf16x2(w[2], w[3])};
+                *(g_u32x2p)(gs_w + rec * kTile + 4 * g) = u32x2{pack_bf16x2(w[0], w[1]), pack_bf16x2(w[2], w[3])};
                 if (g == 0) gs_m[rec] = m;
             }
         }

@@ -26,14 +26,14 @@ __global__ __launch_bounds__(256, 2) void split_mfma_kernel(const SplitTailArgs<
     split_head_insert<bf16_t, D>(ta, u, c);
 
     MfmaStreamer<4, HILO, STASH, MASKED> st;
-    st.init(q + (size_t)u * G * D, G, lane, scale_log2);
-    st.Ku = Kc + (size_t)u * N * D;
-    st.Vu = Vc + (size_t)u * N * D;
+    st.init((g_cu16p)(q + (size_t)u * G * D), G, lane, scale_log2);
+    st.Ku = (g_cu16p)(Kc + (size_t)u * N * D);
+    st.Vu = (g_cu16p)(Vc + (size_t)u * N * D);
     st.start = c * L;
     st.end = min(c * L + L, n);
-    st.gs_w = stash_w + (size_t)u * ntiles * G * kTile; // tile records count from slot 0 of the unit
-    st.gs_m = stash_m + (size_t)u * ntiles * G;
-    st.lu_unit = lu + (size_t)u * ntiles * kTile;
+    st.gs_w = (g_u16p)(stash_w + (size_t)u * ntiles * G * kTile); // tile records count from slot 0 of the unit
+    st.gs_m = (g_f32p)(stash_m + (size_t)u * ntiles * G);
+    st.lu_unit = (g_cf32p)(lu + (size_t)u * ntiles * kTile);
     st.run(wave);
 
     // ---- merge the 4 waves through LDS, write the split's partial state

@@ -10,23 +10,22 @@
 //            in LDS (eq. 6)
 //   merge    the 8 waves' softmax states; with S > 1 the workgroup publishes its partial
 //            (m, l, O) and the LAST workgroup of the unit to arrive merges the S partials
-//   evict    screen every slot with the codes (bounds within a factor 2^(1/8)), re-score the
+//   evict    screen every slot with the codes (bounds within a known factor), re-score the
 //            few that can still be the minimum exactly in double precision, argmin
 //   output   normalise, round to bf16
 //
 // Keeping the per-slot by-products in LDS matters on this chip: even a few percent of HBM
 // writes interleaved with the K/V read stream cost a quarter of the read bandwidth.
 //
-// Cooperation protocol for S > 1 (no workgroup ever waits for one that is not already
-// running): each workgroup writes its partial through to the device-wide coherence point,
-// waits for its own stores, and bumps arrive[u].  All but the last then write their codes
-// to a dump area the same way and bump dumped[u].  The last one merges the partials (the
-// partial outputs come in the same batch of loads, the output is stored at once), waits
-// (bounded) until S-1 dumps are in -- their authors passed arrive[u] before it did, so they
-// are running or done -- and decides the eviction from its own LDS codes plus the dumps,
-// which it reads in place (S = 2) or copies into LDS chunk by chunk (S >= 3).  If the
-// bounded wait ever expired it would re-score every slot exactly instead of trusting
-// incomplete dumps.
+// Cooperation protocol for S > 1.  Nobody ever waits for anybody: each workgroup writes its
+// partial (m, l, O) AND its codes (a dump of G bytes per slot, plus the per-tile references)
+// through to the device-wide coherence point, waits for its own stores, and then bumps
+// arrive[u] -- one counter, one bump per workgroup and step.  Whoever finds itself last has
+// everything it needs already sitting at the coherence point: it fetches the partials and
+// the other workgroups' dumps in one batch of loads (the dumps go straight into the LDS that
+// held the O-merge area; a chunk at a time if they do not all fit), merges, stores the
+// output, and decides the eviction from its own LDS codes plus the copies.  The last
+// workgroup's own dump is wasted; that is the price of not having to wait for the others'.
 #include <algorithm>
 #include <cstring>
 
@@ -45,15 +44,16 @@ struct UnitArgs {
     float *lu;                         // [units][ntiles*16] log2 ||v||_1, position order
     // cooperation of S workgroups per unit (untouched when s_active == 1)
     float *part_m, *part_l, *part_o;   // [units][S][16], [units][S][16], [units][S][G][128]
-    int32_t *arrive, *dumped;          // [units], zero between steps
+    int32_t *arrive;                   // [units], zero between steps
     uint8_t *gcode;                    // [units][G][gstride] dumped codes, absolute positions
     float *gref;                       // [units][ntiles][G] dumped references
     int n, N, G, ntiles;
     int S, s_active, split_len;        // split_len: slots per workgroup, a multiple of 128
     int code_stride, gstride;          // LDS / dump row strides in bytes
-    int merge_off;                     // byte offset of the O-merge area in dynamic LDS
-    int chunk_len;                     // positions of the other workgroups' dumps the deciding one copies into
-                                       // LDS at a time (multiple of 2048; 0: it reads them in place)
+    int merge_off;                     // byte offset of the O-merge area in dynamic LDS (0 with one
+                                       // workgroup per unit: the area then aliases the codes)
+    int chunk_len;                     // positions of the other workgroups' dumps the deciding one holds in
+                                       // LDS at a time (multiple of 2048; 0 with one workgroup per unit)
     float scale_log2;
 };
 
@@ -72,13 +72,31 @@ struct GroupArgs {
 // (buffer_wbl2) and no invalidate, which on this 8-XCD part cost far more than the
 // exchange itself (measured on 128 units x 4096 slots: 160 us with per-thread fences, 70 us
 // with one fence pair per workgroup, 58 us with this scheme).
-template <typename T> __device__ __forceinline__ void st_agent(T *p, T v)
+// (The pointers are cast to the global address space: on a generic pointer these become FLAT
+// instructions, which count against the LDS counter as well, and every later wait for an LDS
+// read would then wait for the trip to the coherence point too.)
+template <typename T> __device__ __forceinline__ void st_agent(__attribute__((address_space(1))) T *p, T v)
 {
     __hip_atomic_store(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
 }
-template <typename T> __device__ __forceinline__ T ld_agent(const T *p)
+template <typename T> __device__ __forceinline__ void st_agent(T *p, T v)
+{
+    typedef __attribute__((address_space(1))) T *gptr;
+    __hip_atomic_store((gptr)p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+template <typename T> __device__ __forceinline__ T ld_agent(__attribute__((address_space(1))) const T *p)
 {
     return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+template <typename T> __device__ __forceinline__ T ld_agent(const T *p)
+{
+    typedef __attribute__((address_space(1))) const T *gptr;
+    return __hip_atomic_load((gptr)p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+__device__ __forceinline__ int add_agent(int32_t *p, int v)
+{
+    typedef __attribute__((address_space(1))) int32_t *gptr;
+    return __hip_atomic_fetch_add((gptr)p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
 }
 // all of this thread's device-scope stores have reached the coherence point
 __device__ __forceinline__ void wait_stores() { asm volatile("s_waitcnt vmcnt(0)" ::: "memory"); }
@@ -109,32 +127,48 @@ __device__ __forceinline__ double exp2_frac_f64(double x)
     return p;
 }
 
-// Exact LongFlowScore of one slot in double precision (eq. 6 with the group's heads
-// summed), computed by one wave: 4 lanes per head, 32 channels per lane.
-//   qs: the step's query as floats in LDS [16][128]; sM: softmax reference per head
-//   (log2 domain); sL: denominator per head.
+// One cache row pair as the exact re-scoring wants it: lane (h = lane >> 2, part = lane & 3)
+// holds K channels 32 part .. 32 part + 31 and two V channels.  Loading and scoring are
+// separate steps so that a wave can have its candidate's rows on their way while it does
+// something else.
+struct RowRegs {
+    uint32_t vv;
+    u32x4 kk[4];
+};
 //   coherent: read the row with device-scope loads (it was written during this launch by
 //   another workgroup)
-__device__ double exact_score_bf16(const uint16_t *krow, const uint16_t *vrow, const uint16_t (*qs)[128], int G,
-                                   const float *sM, const float *sL, int lane, bool coherent)
+__device__ __forceinline__ void load_row(RowRegs &rr, g_cu16p krow, g_cu16p vrow, int lane, bool coherent)
+{
+    const int part = lane & 3;
+    typedef __attribute__((address_space(1))) const uint32_t *g_cu32p;
+    rr.vv = coherent ? ld_agent((g_cu32p)vrow + lane) : *(g_cu32p)(vrow + 2 * lane);
+#pragma unroll
+    for (int c = 0; c < 4; ++c) {
+        if (coherent) {
+            const g_cu32p kp = (g_cu32p)(krow + 32 * part + 8 * c);
+            rr.kk[c] = u32x4{ld_agent(kp), ld_agent(kp + 1), ld_agent(kp + 2), ld_agent(kp + 3)};
+        } else {
+            rr.kk[c] = *(g_cu32x4p)(krow + 32 * part + 8 * c);
+        }
+    }
+}
+
+// Exact LongFlowScore of one slot in double precision (eq. 6 with the group's heads
+// summed), computed by one wave: 4 lanes per head, 32 channels per lane.
+//   qs: the step's query in LDS [16][128]; sM: softmax reference per head (log2 domain);
+//   sL: denominator per head.  The result is complete in every fourth lane.
+__device__ __forceinline__ double score_row(const RowRegs &rr, const uint16_t (*qs)[128], int G, const float *sM, const float *sL, int lane)
 {
     const int h = lane >> 2, part = lane & 3;
     // ||v||_1: two channels per lane, summed over the wave
-    const uint32_t vv = coherent ? ld_agent((const uint32_t *)vrow + lane) : *(const uint32_t *)(vrow + 2 * lane);
-    double l1 = fabs((double)bf16_lo(vv)) + fabs((double)bf16_hi(vv));
+    double l1 = fabs((double)bf16_lo(rr.vv)) + fabs((double)bf16_hi(rr.vv));
     l1 = wave_sum_f64(l1);
     // q_h . k over this lane's 32 channels
     double dot = 0.0;
     if (h < G) {
 #pragma unroll
         for (int c = 0; c < 4; ++c) {
-            u32x4 kk;
-            if (coherent) {
-                const uint32_t *kp = (const uint32_t *)(krow + 32 * part + 8 * c);
-                kk = u32x4{ld_agent(kp), ld_agent(kp + 1), ld_agent(kp + 2), ld_agent(kp + 3)};
-            } else {
-                kk = *(const u32x4 *)(krow + 32 * part + 8 * c);
-            }
+            const u32x4 kk = rr.kk[c];
             const u32x4 qq = *(const u32x4 *)(&qs[h][32 * part + 8 * c]);
             dot = fma((double)bf16_lo(qq.x), (double)bf16_lo(kk.x), dot);
             dot = fma((double)bf16_hi(qq.x), (double)bf16_hi(kk.x), dot);
@@ -160,10 +194,18 @@ __device__ double exact_score_bf16(const uint16_t *krow, const uint16_t *vrow, c
     return term * l1;
 }
 
+__device__ __forceinline__ double exact_score_bf16(g_cu16p krow, g_cu16p vrow, const uint16_t (*qs)[128], int G,
+                                   const float *sM, const float *sL, int lane, bool coherent)
+{
+    RowRegs rr;
+    load_row(rr, krow, vrow, lane, coherent);
+    return score_row(rr, qs, G, sM, sL, lane);
+}
+
 // Explicit-mask mode: the lowest invalid slot of the unit (NaN in the side array), not
 // counting the slot this step has just filled (its entry may still read stale here).
 // All 512 threads call; true if there is one, then it is in red[0].
-__device__ bool fill_lowest_hole(const float *lu_u, int npos, int N, int ins_slot, int *red, int tid, int lane,
+__device__ bool fill_lowest_hole(g_cf32p lu_u, int npos, int N, int ins_slot, int *red, int tid, int lane,
                                  int wave)
 {
     int best = 0x7fffffff;
@@ -185,15 +227,20 @@ __device__ bool fill_lowest_hole(const float *lu_u, int npos, int N, int ins_slo
     return red[0] != 0x7fffffff;
 }
 
-// value of a unit's dump counter once its codes are no longer trusted (stays negative
-// whatever late dumps add to it)
-constexpr int kDumpsDistrusted = -(1 << 30);
+// Screening.  A code c stands for 2^(kCodeBias - c/4), read from a 256-entry table in LDS.
+// For a code that sits at no clamp the true term t and its decoded value d obey
+//   d 2^(-1/8) <= t <= d 2^(1/8)
+// (rounding of the code: half a step of 1/4 either way).  Sums over the heads inherit the
+// bounds, so slot i can hold the smallest true sum only if  sum_i <= min_j sum_j * 2^(1/4);
+// the last factor below covers the fp32 rounding of the sums and of the code's argument.
+constexpr float kScreenWindow = 1.189208f * 1.0002f;
 
 // COOP: several workgroups may share a unit (s_active can exceed 1)
-// GATHER (with COOP): the deciding workgroup copies the others' code dumps into LDS chunk by
-// chunk before screening them; without it, it reads them in place, item by item
 // MAXFREE (attention only): softmax without a running reference, for A/B measurement
-template <bool HILO, int STASH, bool COOP, bool GROUPED, bool MASKED, bool GATHER, bool MAXFREE = false>
+// (Every lambda below is marked always_inline: a real call would make the compiler keep the
+// kernel's arguments, which the lambdas capture by reference, in private memory, and a load from
+// there waits for every outstanding store -- which serialises the device-scope stores.)
+template <bool HILO, int STASH, bool COOP, bool GROUPED, bool MASKED, bool MAXFREE = false>
 __global__ __launch_bounds__(512, 1) void unit_mfma_kernel(const UnitArgs a_in, const GroupArgs ga)
 {
     UnitArgs a = a_in;
@@ -203,10 +250,10 @@ __global__ __launch_bounds__(512, 1) void unit_mfma_kernel(const UnitArgs a_in, 
         const int ci = blk / ga.wgs_per_cache;
         blk -= ci * ga.wgs_per_cache;
         const UnitArgs *t = ga.table + ci;
-        a.Kc = t->Kc; a.Vc = t->Vc; a.q_last = t->q_last; a.pending = t->pending;
-        a.fin_m = t->fin_m; a.fin_l = t->fin_l; a.lu = t->lu;
-        a.part_m = t->part_m; a.part_l = t->part_l; a.part_o = t->part_o;
-        a.arrive = t->arrive; a.dumped = t->dumped; a.gcode = t->gcode; a.gref = t->gref;
+        a.Kc = (t->Kc); a.Vc = (t->Vc); a.q_last = (t->q_last); a.pending = (t->pending);
+        a.fin_m = (t->fin_m); a.fin_l = (t->fin_l); a.lu = (t->lu);
+        a.part_m = (t->part_m); a.part_l = (t->part_l); a.part_o = (t->part_o);
+        a.arrive = (t->arrive); a.gcode = (t->gcode); a.gref = (t->gref);
         a.q += ci * ga.q_stride;
         a.out += ci * ga.q_stride;
         if (a.k_new) a.k_new += ci * ga.kv_stride;
@@ -215,12 +262,13 @@ __global__ __launch_bounds__(512, 1) void unit_mfma_kernel(const UnitArgs a_in, 
     }
     constexpr int D = 128, NW = 8, OPAD = D + 4;
     extern __shared__ __align__(16) unsigned char smem[];
-    // dynamic LDS: [codes G*code_stride][refs (split_len/16)*G floats]; the O-merge area
-    // [NW][G][OPAD] floats starts at merge_off (0 = aliases the codes, used after them)
+    // dynamic LDS: [codes G*code_stride][refs (split_len/16)*G floats] ... [O-merge area
+    // [NW][G][OPAD] floats at merge_off].  With one workgroup per unit and codes too large to
+    // leave room, merge_off is 0: the area then aliases the codes and is used after them.
     uint8_t *ls_code = smem;
     float *ls_ref = (float *)(smem + (size_t)a.G * a.code_stride);
     float *sm_o = (float *)(smem + a.merge_off);
-    __shared__ float sm_m[NW][16], sm_l[NW][16], sM[16], sL[16];
+    __shared__ float sm_m[NW][16], sm_l[NW][16], sM[16], sL[16], sInvL[16];
     __shared__ float sW[8][16]; // weights of the S partials under the unit-wide reference
     __shared__ float red_f[NW];
     __shared__ double best_v[NW];
@@ -237,24 +285,36 @@ __global__ __launch_bounds__(512, 1) void unit_mfma_kernel(const UnitArgs a_in, 
     const int g = lane >> 4, r = lane & 15;
     const int start = sp * a.split_len;
     const int end = min(start + a.split_len, n);
-    uint16_t *Ku = a.Kc + (size_t)u * N * D;
-    uint16_t *Vu = a.Vc + (size_t)u * N * D;
-    const uint16_t *qu = a.q + (size_t)u * G * D;
-    float *lu_u = a.lu + (size_t)u * a.ntiles * kTile;
+    // (global address space by type, see lf_mfma_stream.h: no access below may turn into a FLAT
+    // instruction, whose completion can only be awaited together with the LDS counter)
+    typedef __attribute__((address_space(1))) int32_t *g_i32p;
+    const g_u16p Ku = (g_u16p)a.Kc + (size_t)u * N * D;
+    const g_u16p Vu = (g_u16p)a.Vc + (size_t)u * N * D;
+    const g_cu16p qu = (g_cu16p)a.q + (size_t)u * G * D;
+    const g_f32p lu_u = (g_f32p)a.lu + (size_t)u * a.ntiles * kTile;
+    const g_cu16p k_new = (g_cu16p)a.k_new, v_new = (g_cu16p)a.v_new;
+    const g_u16p out_g = (g_u16p)a.out, q_last = (g_u16p)a.q_last;
+    const g_i32p pending = (g_i32p)a.pending, evict_idx = (g_i32p)a.evict_idx;
+    const g_f32p fin_m = (g_f32p)a.fin_m, fin_l = (g_f32p)a.fin_l;
     const bool evicting = (STASH == kStashLds) && n == N;
+    const bool coop = COOP && s_active > 1;
+    // the O-merge area has LDS of its own (it does not alias live codes): the output can be
+    // staged before the eviction decision and stored while candidates' rows are on their way
+    const bool o_separate = STASH != kStashLds || a.merge_off != 0;
 
     // ---- insert (Fig. 2 left): done by the wave that will stream that tile, so that its own
     // later loads of the row are ordered behind the stores.  The row is written through to
     // the device-wide coherence point: with several workgroups per unit, the one that ends
     // up re-scoring candidates may sit on another XCD and must not see the old row.
-    const int ins_slot = (STASH != kStashNone) ? a.pending[u] : -1;
+    const int ins_slot = (STASH != kStashNone) ? pending[u] : -1;
     if (STASH != kStashNone) {
         const int slot = ins_slot;
         if (slot >= start && slot < start + a.split_len && slot < N && (((slot - start) / kTile) % NW) == wave) {
-            st_agent((uint32_t *)(Ku + (size_t)slot * D) + lane, *((const uint32_t *)(a.k_new + (size_t)u * D) + lane));
-            st_agent((uint32_t *)(Vu + (size_t)slot * D) + lane, *((const uint32_t *)(a.v_new + (size_t)u * D) + lane));
+            typedef __attribute__((address_space(1))) const uint32_t *g_cu32p;
+            st_agent((g_u32p)(Ku + (size_t)slot * D) + lane, *((g_cu32p)(k_new + (size_t)u * D) + lane));
+            st_agent((g_u32p)(Vu + (size_t)slot * D) + lane, *((g_cu32p)(v_new + (size_t)u * D) + lane));
             // every 16-lane row sums |v_new| redundantly; lane 0 stores the log2 norm
-            const u32x4 vv = *(const u32x4 *)(a.v_new + (size_t)u * D + 8 * r);
+            const u32x4 vv = *(g_cu32x4p)(v_new + (size_t)u * D + 8 * r);
             float a1 = fabsf(bf16_lo(vv.x)) + fabsf(bf16_hi(vv.x)) + fabsf(bf16_lo(vv.y)) + fabsf(bf16_hi(vv.y)) +
                        fabsf(bf16_lo(vv.z)) + fabsf(bf16_hi(vv.z)) + fabsf(bf16_lo(vv.w)) + fabsf(bf16_hi(vv.w));
             a1 = row16_sum(a1);
@@ -272,7 +332,7 @@ __global__ __launch_bounds__(512, 1) void unit_mfma_kernel(const UnitArgs a_in, 
         if (tid < 256) exp_tab[tid] = fast_exp2(-0.25f * (float)tid);
     }
     if (sp == 0)
-        for (int i = tid; i < G * D; i += 512) a.q_last[(size_t)u * G * D + i] = qu[i];
+        for (int i = tid; i < G * D; i += 512) q_last[(size_t)u * G * D + i] = qu[i];
 
     MfmaStreamer<NW, HILO, STASH, MASKED, false, MAXFREE> st;
     st.init(qu, G, lane, a.scale_log2);
@@ -304,11 +364,12 @@ __global__ __launch_bounds__(512, 1) void unit_mfma_kernel(const UnitArgs a_in, 
         for (int w = 0; w < NW; ++w) Ls += merge_weight(sm_m[w][tid], M) * sm_l[w][tid];
         sM[tid] = M; // this workgroup's reference and denominator
         sL[tid] = Ls;
+        sInvL[tid] = 1.f / Ls;
     }
     __syncthreads();
 
     // O of the 8 waves -> LDS, each under this workgroup's reference
-    auto stage_o = [&]() {
+    auto stage_o = [&]() __attribute__((always_inline)) {
         float a4[4];
 #pragma unroll
         for (int v = 0; v < 4; ++v) a4[v] = merge_weight(sm_m[wave][4 * g + v], sM[4 * g + v]);
@@ -323,10 +384,109 @@ __global__ __launch_bounds__(512, 1) void unit_mfma_kernel(const UnitArgs a_in, 
             }
         }
     };
+    // normalised output of a unit served by this workgroup alone
+    auto store_out = [&]() __attribute__((always_inline)) {
+        for (int idx = tid; idx < G * D; idx += 512) {
+            const int h = idx / D, d = idx % D;
+            float acc = 0.f;
+#pragma unroll
+            for (int w = 0; w < NW; ++w) acc += sm_o[((size_t)w * G + h) * OPAD + d];
+            out_g[((size_t)u * G + h) * D + d] = (uint16_t)f32_to_bf16_bits(acc / sL[h]);
+        }
+    };
 
-    bool dumps_ok = true;
-    if (COOP && s_active > 1) {
-        // ---- publish this workgroup's partial (m, l, O) and count the arrival
+    // the same for a unit shared by several workgroups: the S partial outputs come from the
+    // coherence point (requested with the last arriver's first batch of loads, used here) and
+    // are weighted under the unit-wide reference
+    constexpr int kOutPer = (kMaxGroup * D + 511) / 512;
+    float po[kOutPer][8];
+    auto request_partial_outputs = [&]() __attribute__((always_inline)) {
+#pragma unroll
+        for (int k = 0; k < kOutPer; ++k) {
+            const int idx = tid + 512 * k;
+#pragma unroll
+            for (int s2 = 0; s2 < 8; ++s2)
+                po[k][s2] = (idx < G * D && s2 < s_active)
+                                ? ld_agent(&a.part_o[((size_t)u * a.S + s2) * G * D + idx]) : 0.f;
+        }
+    };
+    auto merge_out = [&]() __attribute__((always_inline)) {
+#pragma unroll
+        for (int k = 0; k < kOutPer; ++k) {
+            const int idx = tid + 512 * k;
+            if (idx < G * D) {
+                const int h = idx / D;
+                float acc = 0.f;
+#pragma unroll
+                for (int s2 = 0; s2 < 8; ++s2) acc += sW[s2][h] * po[k][s2];
+                out_g[(size_t)u * G * D + idx] = (uint16_t)f32_to_bf16_bits(acc / sL[h]);
+            }
+        }
+    };
+
+    // the other workgroups' codes in LDS, a chunk of positions at a time (COOP only): where the
+    // O-merge area was, dead once the partial has been published
+    const int own_hi = min(start + a.split_len, a.gstride);
+    const int chunk_len = coop ? a.chunk_len : 0;
+    uint8_t *rem_code = smem + a.merge_off;
+    float *rem_ref = (float *)(rem_code + (size_t)G * chunk_len);
+    // Copy the dumps of positions [cb, cb + chunk_len) into LDS, references as dumped (they are
+    // rescaled once the unit-wide softmax state is known).  The own range inside the chunk,
+    // [lo, hi) relative to cb, is skipped: its codes are in LDS already.  All loads of a round
+    // are requested before any is used: every device-scope load is a trip to the coherence
+    // point, and a batch of them costs about one.
+    auto gather_chunk = [&](int cb) __attribute__((always_inline)) {
+        constexpr int kBatch = 16;
+        const int lo = min(max(start - cb, 0), chunk_len), hi = min(max(own_hi - cb, 0), chunk_len);
+        const int skip = hi - lo;
+        const int top = a.gstride - 8; // last 8-byte word of a dump row
+        const int per_h = (chunk_len - skip) / 8;
+        const int nw = G * per_h;                             // 8-byte words of codes
+        const int tl = lo / kTile, tskip = skip / kTile;
+        const int nr = (chunk_len / kTile - tskip) * G;       // references, half as many
+        for (int i0 = 0; i0 < nw; i0 += 512 * kBatch) {
+            unsigned long long v[kBatch];
+            float rv[kBatch / 2];
+            int off[kBatch], roff[kBatch / 2];
+#pragma unroll
+            for (int k = 0; k < kBatch; ++k) {
+                const int i = i0 + k * 512 + tid;
+                v[k] = 0;
+                off[k] = 0;
+                if (i < nw) {
+                    const int h = i / per_h;
+                    int o = 8 * (i % per_h);
+                    if (o >= lo) o += skip;
+                    off[k] = h * chunk_len + o;
+                    v[k] = ld_agent((const unsigned long long *)(a.gcode + ((size_t)u * G + h) * a.gstride + min(cb + o, top)));
+                }
+            }
+#pragma unroll
+            for (int k = 0; k < kBatch / 2; ++k) {
+                const int i = i0 / 2 + k * 512 + tid;
+                rv[k] = 0.f;
+                roff[k] = 0;
+                if (i < nr) {
+                    int t = i / G;
+                    if (t >= tl) t += tskip;
+                    roff[k] = t * G + i % G;
+                    rv[k] = ld_agent(&a.gref[((size_t)u * a.ntiles + min(cb / kTile + t, a.ntiles - 1)) * G + i % G]);
+                }
+            }
+#pragma unroll
+            for (int k = 0; k < kBatch; ++k)
+                if (i0 + k * 512 + tid < nw) *(unsigned long long *)(rem_code + off[k]) = v[k];
+#pragma unroll
+            for (int k = 0; k < kBatch / 2; ++k)
+                if (i0 / 2 + k * 512 + tid < nr) rem_ref[roff[k]] = rv[k];
+        }
+    };
+    // per (tile, head): the factor that turns a decoded code into a term of the score, from the
+    // tile's reference as the streaming left it
+    auto ref_factor = [&](float ref, int h) __attribute__((always_inline)) { return fast_exp2(kCodeBias + ref - sM[h]) * sInvL[h]; };
+
+    if (coop) {
+        // ---- publish this workgroup's partial (m, l, O), and its codes if slots will be scored
         stage_o();
         __syncthreads();
         const size_t pb = (size_t)u * a.S + sp;
@@ -338,45 +498,29 @@ __global__ __launch_bounds__(512, 1) void unit_mfma_kernel(const UnitArgs a_in, 
             st_agent(&a.part_o[(pb * G + h) * D + d], acc);
         }
         if (tid < 16) { st_agent(&a.part_m[pb * 16 + tid], sM[tid]); st_agent(&a.part_l[pb * 16 + tid], sL[tid]); }
+        if (evicting) {
+            const int len = (end - start + kTile - 1) / kTile * kTile; // whole tiles
+            uint8_t *gc = a.gcode + (size_t)u * G * a.gstride + start;
+            const int gstride = a.gstride, cstride = a.code_stride;
+            for (int h = 0; h < G; ++h)
+                for (int j = tid; j < len / 8; j += 512)
+                    st_agent((unsigned long long *)(gc + (size_t)h * gstride + 8 * j),
+                             *(const unsigned long long *)(ls_code + (size_t)h * cstride + 8 * j));
+            float *gr = a.gref + ((size_t)u * a.ntiles + start / kTile) * G;
+            for (int i = tid; i < (len / kTile) * G; i += 512) st_agent(gr + i, ls_ref[i]);
+        }
         wait_stores();
-        __syncthreads(); // every thread's partials are visible device-wide before the arrival counts
+        __syncthreads(); // every thread's stores are visible device-wide before the arrival counts
         if (tid == 0)
-            s_flag = (__hip_atomic_fetch_add(&a.arrive[u], 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) == s_active - 1);
+            s_flag = (add_agent(&a.arrive[u], 1) == s_active - 1);
         __syncthreads();
-        if (!s_flag) {
-            if (evicting) { // leave the codes where the last workgroup will find them
-                const int len = (end - start + kTile - 1) / kTile * kTile; // whole tiles
-                for (int i = tid; i < G * (len / 4); i += 512) {
-                    const int h = i / (len / 4), j = i % (len / 4);
-                    st_agent((uint32_t *)(a.gcode + ((size_t)u * G + h) * a.gstride + start + 4 * j),
-                             *(const uint32_t *)(ls_code + (size_t)h * a.code_stride + 4 * j));
-                }
-                for (int i = tid; i < (len / kTile) * G; i += 512)
-                    st_agent(&a.gref[((size_t)u * a.ntiles + start / kTile) * G + i], ls_ref[i]);
-                wait_stores();
-                __syncthreads();
-                if (tid == 0) __hip_atomic_fetch_add(&a.dumped[u], 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-            }
-            return;
-        }
-        // ---- last arriver: merge the S partials into the unit-wide softmax state and the
-        // output.  Device-scope loads are issued in batches (all first, then used): each one
-        // is a round trip to the coherence point, and an acquire fence instead (an L2
-        // invalidate for the whole XCD) measured slower still.  The partial outputs are
-        // fetched in the same batch as the softmax states, so the output costs no trip of
-        // its own; it is stored right away (it does not depend on the eviction).
-        constexpr int kOutPer = (kMaxGroup * D + 511) / 512;
-        float po[kOutPer][8];
-#pragma unroll
-        for (int k = 0; k < kOutPer; ++k) {
-            const int idx = tid + 512 * k;
-#pragma unroll
-            for (int s2 = 0; s2 < 8; ++s2)
-                po[k][s2] = (idx < G * D && s2 < s_active)
-                                ? ld_agent(&a.part_o[((size_t)u * a.S + s2) * G * D + idx]) : 0.f;
-        }
+        if (!s_flag) return;
+        // ---- last arriver: everything of the unit is at the coherence point.  One batch of
+        // device-scope loads fetches the S softmax states and the first chunk of the others'
+        // codes, and the partial outputs, which are not used before the decision is made.
+        float pm[8], pl[8];
+        request_partial_outputs();
         if (tid < 16) {
-            float pm[8], pl[8];
 #pragma unroll
             for (int s2 = 0; s2 < 8; ++s2) {
                 pm[s2] = -INFINITY;
@@ -386,6 +530,9 @@ __global__ __launch_bounds__(512, 1) void unit_mfma_kernel(const UnitArgs a_in, 
                     pl[s2] = ld_agent(&a.part_l[((size_t)u * a.S + s2) * 16 + tid]);
                 }
             }
+        }
+        if (evicting) gather_chunk(0);
+        if (tid < 16) {
             float M = -INFINITY;
 #pragma unroll
             for (int s2 = 0; s2 < 8; ++s2) M = fmaxf(M, pm[s2]);
@@ -398,223 +545,90 @@ __global__ __launch_bounds__(512, 1) void unit_mfma_kernel(const UnitArgs a_in, 
             }
             sM[tid] = M;
             sL[tid] = Ls;
-        }
-        if (evicting && tid == 0) { // bounded wait for the S-1 dumps (their authors are running or done)
-            // A negative count marks a unit whose wait once ran out: a dump may then have been
-            // counted after the counter was cleared, so the counter is never trusted again and
-            // every later step re-scores all slots (exact, slower) instead of reading dumps.
-            int seen = 0;
-            for (int it = 0; it < (1 << 22); ++it) {
-                seen = __hip_atomic_load(&a.dumped[u], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-                if (seen >= s_active - 1 || seen < 0) break;
-                __builtin_amdgcn_s_sleep(8);
-            }
-            s_flag = (seen >= s_active - 1);
+            sInvL[tid] = 1.f / Ls;
         }
         __syncthreads();
-        if (evicting) dumps_ok = s_flag != 0;
-#pragma unroll
-        for (int k = 0; k < kOutPer; ++k) {
-            const int idx = tid + 512 * k;
-            if (idx < G * D) {
-                const int h = idx / D;
-                float acc = 0.f;
-#pragma unroll
-                for (int s2 = 0; s2 < 8; ++s2) acc += sW[s2][h] * po[k][s2];
-                a.out[(size_t)u * G * D + idx] = (uint16_t)f32_to_bf16_bits(acc / sL[h]);
-            }
-        }
+    } else if (o_separate && STASH == kStashLds) {
+        stage_o(); // read back below, after the barriers of the decision
     }
     if (tid < G) {
-        a.fin_m[(size_t)u * G + tid] = sM[tid];
-        a.fin_l[(size_t)u * G + tid] = sL[tid];
+        fin_m[(size_t)u * G + tid] = sM[tid];
+        fin_l[(size_t)u * G + tid] = sL[tid];
     }
 
     // ---- eviction decision (Sec. 3.2 last paragraph; Alg. 1 post-processing)
+    bool out_stored = false;
     if (STASH == kStashLds) {
         if (n < N) {
             if (tid == 0) {
-                a.pending[u] = n;
-                if (a.evict_idx) a.evict_idx[u] = n;
+                pending[u] = n;
+                if (evict_idx) evict_idx[u] = n;
             }
         } else if (MASKED && fill_lowest_hole(lu_u, a.gstride, N, ins_slot, red_i, tid, lane, wave)) {
             // an invalid slot exists: it takes the next token, nothing is evicted
             if (tid == 0) {
-                a.pending[u] = red_i[0];
-                if (a.evict_idx) a.evict_idx[u] = red_i[0];
+                pending[u] = red_i[0];
+                if (evict_idx) evict_idx[u] = red_i[0];
             }
         } else {
-            // own codes: per (tile, head) factor that turns a decoded code into a score term
-            const int my_tiles = (end - start + kTile - 1) / kTile;
-            for (int i = tid; i < my_tiles * G; i += 512) {
-                const int h = i % G;
-                ls_ref[i] = fast_exp2(kCodeBias + ls_ref[i] - sM[h]) / sL[h];
-            }
-            // The other workgroups' dumps are screened from LDS too: the deciding workgroup
-            // copies them, a chunk of positions at a time, into the LDS that held the O-merge
-            // area (dead since the partials were published), every load of a chunk in flight
-            // together -- about one trip to the coherence point per chunk, where decoding
-            // straight from the dumps pays one per 512 items (measured with 8 workgroups per
-            // unit of 16384 slots: screening 67 -> 39 kcycles).  A chunk is a multiple of 2048
-            // positions, so that a thread's items (512 apart) fall into chunks as wholes.
-            const int own_hi = min(start + a.split_len, a.gstride);
-            const int chunk_len = (COOP && GATHER && s_active > 1) ? a.chunk_len : 0;
-            uint8_t *rem_code = smem + a.merge_off;
-            float *rem_ref = (float *)(rem_code + (size_t)G * chunk_len);
             int chunk_base = 0;
-            auto gather_chunk = [&](int cb) {
-                constexpr int kBatch = 16;
-                // the own range inside the chunk, [lo, hi) relative to cb, is skipped: its codes
-                // are in LDS already and its dump is stale
-                const int lo = min(max(start - cb, 0), chunk_len), hi = min(max(own_hi - cb, 0), chunk_len);
-                const int skip = hi - lo;
-                const int top = a.gstride - 8; // last 8-byte word of a dump row
-                const int per_h = (chunk_len - skip) / 8;
-                const int nw = G * per_h;                             // 8-byte words of codes
-                const int tl = lo / kTile, tskip = skip / kTile;
-                const int nr = (chunk_len / kTile - tskip) * G;       // references, half as many
-                for (int i0 = 0; i0 < nw; i0 += 512 * kBatch) {
-                    unsigned long long v[kBatch];
-                    float rv[kBatch];
-                    int off[kBatch], roff[kBatch];
-                    // codes and references of one round are all requested before any is used;
-                    // nothing is loaded past the end: device-scope loads are too dear to repeat
-#pragma unroll
-                    for (int k = 0; k < kBatch; ++k) {
-                        const int i = i0 + k * 512 + tid;
-                        v[k] = 0;
-                        off[k] = 0;
-                        if (i < nw) {
-                            const int h = i / per_h;
-                            int o = 8 * (i % per_h);
-                            if (o >= lo) o += skip;
-                            off[k] = h * chunk_len + o;
-                            v[k] = ld_agent((const unsigned long long *)(a.gcode + ((size_t)u * G + h) * a.gstride + min(cb + o, top)));
-                        }
-                    }
-#pragma unroll
-                    for (int k = 0; k < kBatch / 2; ++k) {
-                        const int i = i0 / 2 + k * 512 + tid;
-                        rv[k] = 0.f;
-                        roff[k] = 0;
-                        if (i < nr) {
-                            int t = i / G;
-                            if (t >= tl) t += tskip;
-                            roff[k] = t * G + i % G;
-                            rv[k] = ld_agent(&a.gref[((size_t)u * a.ntiles + min(cb / kTile + t, a.ntiles - 1)) * G + i % G]);
-                        }
-                    }
-#pragma unroll
-                    for (int k = 0; k < kBatch; ++k)
-                        if (i0 + k * 512 + tid < nw) *(unsigned long long *)(rem_code + off[k]) = v[k];
-#pragma unroll
-                    for (int k = 0; k < kBatch / 2; ++k)
-                        if (i0 / 2 + k * 512 + tid < nr)
-                            rem_ref[roff[k]] = fast_exp2(kCodeBias + rv[k] - sM[roff[k] % G]) / sL[roff[k] % G];
-                }
-            };
-            __syncthreads();
-            // Decode every (head, slot) code once.  A decoded term is within 2^(+-1/8) of the
-            // true one; code 0 has no upper bound, code 255 no lower bound.  Each thread keeps
-            // the lower-bound sums of its slots in registers, the block finds the smallest
-            // upper bound, and a slot can be the true minimum only if
-            //   2^(-1/8) * lb_sum <= 2^(1/8) * min ub_sum.
+            // Decode every (head, slot) code once.  Each thread keeps the sums of its slots in
+            // registers, the block finds the smallest, and a slot can be the true minimum only
+            // if its sum lies within kScreenWindow of it.  A code at a clamp has no bound on one
+            // side (0: no upper bound, 255: no lower bound) and sends its item through the
+            // two-sided sums.
             const int items = 4 * ((n + kTile - 1) / kTile); // 4 positions each, whole tiles
             constexpr int kRegIters = 8; // 512 threads x 4 positions x 8 = 16384 slots held in registers
             const int iters = (items + 511) / 512;
-            auto decode_item = [&](int item, float *ub4, float *lb4) {
+            // where an item's codes and factors live, as byte offsets into dynamic LDS
+            const int ref_off = G * a.code_stride, rem_off = a.merge_off, rem_ref_off = a.merge_off + G * chunk_len;
+            auto item_source = [&](int item, int &cp, int &fp, int &cstride) __attribute__((always_inline)) {
                 const int tile = item >> 2;
-#pragma unroll
-                for (int e = 0; e < 4; ++e) ub4[e] = lb4[e] = 0.f;
-                // where the item's codes and factors live in LDS, if they do
-                const uint8_t *cp = ls_code + 4 * item;
-                const float *fp = ls_ref + tile * G;
-                int cstride = a.code_stride;
-                bool local = true;
+                cp = 4 * item;
+                fp = ref_off + 4 * tile * G;
+                cstride = a.code_stride;
                 if (COOP) {
                     if (4 * item >= start && 4 * item < own_hi) {
-                        cp = ls_code + (4 * item - start);
-                        fp = ls_ref + (tile - start / kTile) * G;
-                    } else if (GATHER) { // another workgroup's: in the chunk that is in LDS right now
+                        cp = 4 * item - start;
+                        fp = ref_off + 4 * (tile - start / kTile) * G;
+                    } else { // another workgroup's: in the chunk that is in LDS right now
                         const int rp = 4 * item - chunk_base;
-                        cp = rem_code + rp;
-                        fp = rem_ref + (rp / kTile) * G;
+                        cp = rem_off + rp;
+                        fp = rem_ref_off + 4 * (rp / kTile) * G;
                         cstride = chunk_len;
-                    } else {
-                        local = false;
                     }
                 }
-                if (local) {
-                    // Common case first: no code of the item sits at a clamp (0x00 or 0xff),
-                    // so upper and lower bound share one sum.  The byte tests are the usual
-                    // word-at-a-time ones; a hit anywhere sends the item through the exact
-                    // two-sided sums below.
-                    uint32_t clamped = 0u;
+            };
+            auto decode_item = [&](int item, float *ub4, float *lb4) __attribute__((always_inline)) {
+                int cpo, fpo, cstride;
+                item_source(item, cpo, fpo, cstride);
+                const uint8_t *cp = smem + cpo;
+                const float *fp = (const float *)(smem + fpo);
+                // Common case first: no code of the item sits at a clamp (0x00 or 0xff), so upper
+                // and lower bound share one sum.  The byte tests are the usual word-at-a-time ones.
+                uint32_t clamped = 0u;
+                float s4[4] = {0.f, 0.f, 0.f, 0.f};
+                for (int h = 0; h < G; ++h) {
+                    const uint32_t c4 = *(const uint32_t *)(cp + (size_t)h * cstride);
+                    const float f = ref_factor(fp[h], h);
+                    clamped |= ((c4 - 0x01010101u) & ~c4) | ((~c4 - 0x01010101u) & c4);
+#pragma unroll
+                    for (int e = 0; e < 4; ++e) s4[e] = fmaf(exp_tab[(c4 >> (8 * e)) & 255u], f, s4[e]);
+                }
+#pragma unroll
+                for (int e = 0; e < 4; ++e) ub4[e] = lb4[e] = s4[e];
+                if (clamped & 0x80808080u) {
+#pragma unroll
+                    for (int e = 0; e < 4; ++e) ub4[e] = lb4[e] = 0.f;
                     for (int h = 0; h < G; ++h) {
                         const uint32_t c4 = *(const uint32_t *)(cp + (size_t)h * cstride);
-                        const float f = fp[h];
-                        clamped |= ((c4 - 0x01010101u) & ~c4) | ((~c4 - 0x01010101u) & c4);
+                        const float f = ref_factor(fp[h], h);
 #pragma unroll
-                        for (int e = 0; e < 4; ++e)
-                            ub4[e] = fmaf(exp_tab[(c4 >> (8 * e)) & 255u], f, ub4[e]);
-                    }
-#pragma unroll
-                    for (int e = 0; e < 4; ++e) lb4[e] = ub4[e];
-                    if (clamped & 0x80808080u) {
-#pragma unroll
-                        for (int e = 0; e < 4; ++e) ub4[e] = lb4[e] = 0.f;
-                        for (int h = 0; h < G; ++h) {
-                            const uint32_t c4 = *(const uint32_t *)(cp + (size_t)h * cstride);
-                            const float f = fp[h];
-#pragma unroll
-                            for (int e = 0; e < 4; ++e) {
-                                const uint32_t c = (c4 >> (8 * e)) & 255u;
-                                const float d = fast_exp2(-0.25f * (float)c) * f;
-                                ub4[e] += (c == 0u) ? INFINITY : d;
-                                lb4[e] += (c == 255u) ? 0.f : d;
-                            }
-                        }
-                    }
-                } else if (COOP && !GATHER) {
-                    // another workgroup's dump, read in place: batch the device-scope loads of
-                    // this item, then use them
-                    uint32_t c4s[kMaxGroup];
-                    float refs[kMaxGroup];
-#pragma unroll
-                    for (int h = 0; h < kMaxGroup; ++h)
-                        if (h < G) {
-                            c4s[h] = ld_agent((const uint32_t *)(a.gcode + ((size_t)u * G + h) * a.gstride + 4 * item));
-                            refs[h] = ld_agent(&a.gref[((size_t)u * a.ntiles + tile) * G + h]);
-                        }
-                    // same two forms as above: one sum where no code is clamped, else both
-                    uint32_t clamped = 0u;
-#pragma unroll
-                    for (int h = 0; h < kMaxGroup; ++h) {
-                        if (h < G) {
-                            refs[h] = fast_exp2(kCodeBias + refs[h] - sM[h]) / sL[h];
-                            const uint32_t c4 = c4s[h];
-                            clamped |= ((c4 - 0x01010101u) & ~c4) | ((~c4 - 0x01010101u) & c4);
-#pragma unroll
-                            for (int e = 0; e < 4; ++e)
-                                ub4[e] = fmaf(exp_tab[(c4 >> (8 * e)) & 255u], refs[h], ub4[e]);
-                        }
-                    }
-#pragma unroll
-                    for (int e = 0; e < 4; ++e) lb4[e] = ub4[e];
-                    if (clamped & 0x80808080u) {
-#pragma unroll
-                        for (int e = 0; e < 4; ++e) ub4[e] = lb4[e] = 0.f;
-#pragma unroll
-                        for (int h = 0; h < kMaxGroup; ++h) {
-                            if (h < G) {
-#pragma unroll
-                                for (int e = 0; e < 4; ++e) {
-                                    const uint32_t c = (c4s[h] >> (8 * e)) & 255u;
-                                    const float d = fast_exp2(-0.25f * (float)c) * refs[h];
-                                    ub4[e] += (c == 0u) ? INFINITY : d;
-                                    lb4[e] += (c == 255u) ? 0.f : d;
-                                }
-                            }
+                        for (int e = 0; e < 4; ++e) {
+                            const uint32_t c = (c4 >> (8 * e)) & 255u;
+                            const float d = exp_tab[c] * f;
+                            ub4[e] += (c == 0u) ? INFINITY : d;
+                            lb4[e] += (c == 255u) ? 0.f : d;
                         }
                     }
                 }
@@ -624,7 +638,7 @@ __global__ __launch_bounds__(512, 1) void unit_mfma_kernel(const UnitArgs a_in, 
                     if (slot >= n) { ub4[e] = INFINITY; lb4[e] = INFINITY; }
                 }
             };
-            auto list_candidates = [&](int item, const float *lb4, float thr) {
+            auto list_candidates = [&](int item, const float *lb4, float thr) __attribute__((always_inline)) {
 #pragma unroll
                 for (int e = 0; e < 4; ++e) {
                     if (lb4[e] <= thr) {
@@ -633,7 +647,7 @@ __global__ __launch_bounds__(512, 1) void unit_mfma_kernel(const UnitArgs a_in, 
                     }
                 }
             };
-            auto block_min = [&](float x) {
+            auto block_min = [&](float x) __attribute__((always_inline)) {
 #pragma unroll
                 for (int off = 32; off > 0; off >>= 1) x = fminf(x, __shfl_xor(x, off));
                 if (lane == 0) red_f[wave] = x;
@@ -643,49 +657,96 @@ __global__ __launch_bounds__(512, 1) void unit_mfma_kernel(const UnitArgs a_in, 
                 for (int w = 1; w < NW; ++w) x = fminf(x, red_f[w]);
                 return x;
             };
+            // chunk cb of the others' dumps into LDS, unless it is the one that is there (chunk 0
+            // came with the partials)
+            auto next_chunk = [&](int cb) __attribute__((always_inline)) {
+                if (chunk_len == 0 || cb == chunk_base) return;
+                __syncthreads(); // the previous chunk has been read by everyone
+                chunk_base = cb;
+                gather_chunk(cb);
+                __syncthreads();
+            };
             float ub_min = INFINITY;
-            if (!dumps_ok) {
-                if (tid == 0) cand_count = kMaxCand + 1; // distrust the codes: re-score everything
-            } else if (iters <= kRegIters) {
+            const int span = chunk_len > 0 ? chunk_len : a.gstride;
+            if (iters <= kRegIters) {
                 float lbs[kRegIters][4];
 #pragma unroll
                 for (int it = 0; it < kRegIters; ++it)
 #pragma unroll
                     for (int e = 0; e < 4; ++e) lbs[it][e] = INFINITY;
-                // one pass over all items; with dumps to copy, chunk by chunk
-                const int span = chunk_len > 0 ? chunk_len : a.gstride;
-                for (int cb = 0; cb < a.gstride; cb += span) {
-                    if (chunk_len > 0) {
-                        __syncthreads(); // the previous chunk has been read by everyone
-                        chunk_base = cb;
-                        gather_chunk(cb);
-                        __syncthreads();
+                // One pass over all items; with dumps to copy, chunk by chunk.  The loop over the
+                // heads is the outer one and the thread's items (a compile-time count NI >= iters)
+                // are read unconditionally -- a dead item reads item 0's words and drops them -- so
+                // that the LDS reads of one head are all in flight before the first is used.
+                auto pass = [&](auto ni_tag, int cb) __attribute__((always_inline)) {
+                    constexpr int NI = decltype(ni_tag)::value;
+                    int cp[NI], fp[NI], cstr[NI]; // byte offsets into dynamic LDS
+                    bool live[NI];
+                    uint32_t clamped[NI];
+                    float s4[NI][4];
+#pragma unroll
+                    for (int it = 0; it < NI; ++it) {
+                        const int item = it * 512 + tid;
+                        live[it] = item < items && it * 2048 >= cb && it * 2048 < cb + span;
+                        item_source(live[it] ? item : (COOP ? start / 4 : 0), cp[it], fp[it], cstr[it]);
+                        clamped[it] = 0u;
+#pragma unroll
+                        for (int e = 0; e < 4; ++e) s4[it][e] = 0.f;
+                    }
+                    for (int h = 0; h < G; ++h) {
+                        uint32_t c4[NI];
+                        float f[NI];
+                        const float mh = kCodeBias - sM[h], il = sInvL[h];
+#pragma unroll
+                        for (int it = 0; it < NI; ++it) {
+                            c4[it] = *(const uint32_t *)(smem + cp[it]);
+                            f[it] = *(const float *)(smem + fp[it]);
+                            cp[it] += cstr[it];
+                            fp[it] += 4;
+                        }
+#pragma unroll
+                        for (int it = 0; it < NI; ++it) {
+                            f[it] = fast_exp2(f[it] + mh) * il;
+                            clamped[it] |= ((c4[it] - 0x01010101u) & ~c4[it]) | ((~c4[it] - 0x01010101u) & c4[it]);
+#pragma unroll
+                            for (int e = 0; e < 4; ++e)
+                                s4[it][e] = fmaf(exp_tab[(c4[it] >> (8 * e)) & 255u], f[it], s4[it][e]);
+                        }
                     }
 #pragma unroll
-                    for (int it = 0; it < kRegIters; ++it) {
-                        const int item = it * 512 + tid;
-                        if (it < iters && item < items && it * 2048 >= cb && it * 2048 < cb + span) {
+                    for (int it = 0; it < NI; ++it) {
+                        if (live[it]) {
+                            const int item = it * 512 + tid;
                             float ub4[4];
-                            decode_item(item, ub4, lbs[it]);
+                            if (clamped[it] & 0x80808080u) {
+                                decode_item(item, ub4, lbs[it]); // two-sided sums
+                            } else {
+#pragma unroll
+                                for (int e = 0; e < 4; ++e) {
+                                    const int slot = ((4 * item) & ~15) + slot_of_pos((4 * item + e) & 15);
+                                    ub4[e] = lbs[it][e] = slot < n ? s4[it][e] : INFINITY;
+                                }
+                            }
                             ub_min = fminf(ub_min, fminf(fminf(ub4[0], ub4[1]), fminf(ub4[2], ub4[3])));
                         }
                     }
+                };
+                for (int cb = 0; cb < a.gstride; cb += span) {
+                    next_chunk(cb);
+                    if (iters <= 1) pass(std::integral_constant<int, 1>{}, cb);
+                    else if (iters <= 2) pass(std::integral_constant<int, 2>{}, cb);
+                    else if (iters <= 4) pass(std::integral_constant<int, 4>{}, cb);
+                    else pass(std::integral_constant<int, kRegIters>{}, cb);
                 }
-                const float thr = block_min(ub_min) * 1.1893f * 1.0001f;
+                const float thr = block_min(ub_min) * kScreenWindow;
 #pragma unroll
                 for (int it = 0; it < kRegIters; ++it)
                     if (it < iters) list_candidates(it * 512 + tid, lbs[it], thr);
             } else { // budgets beyond the register window: decode twice (dump chunks are copied twice)
-                const int span = chunk_len > 0 ? chunk_len : a.gstride;
                 float thr = 0.f;
                 for (int pass = 0; pass < 2; ++pass) {
                     for (int cb = 0; cb < a.gstride; cb += span) {
-                        if (chunk_len > 0) {
-                            __syncthreads(); // the previous chunk has been read by everyone
-                            chunk_base = cb;
-                            gather_chunk(cb);
-                            __syncthreads();
-                        }
+                        next_chunk(cb);
                         const int it_hi = min(iters, (cb + span + 2047) / 2048); // the last span may be ragged
                         for (int it = cb / 2048; it < it_hi; ++it) {
                             const int item = it * 512 + tid;
@@ -697,7 +758,7 @@ __global__ __launch_bounds__(512, 1) void unit_mfma_kernel(const UnitArgs a_in, 
                             }
                         }
                     }
-                    if (pass == 0) thr = block_min(ub_min) * 1.1893f * 1.0001f;
+                    if (pass == 0) thr = block_min(ub_min) * kScreenWindow;
                 }
             }
             __syncthreads();
@@ -709,12 +770,31 @@ __global__ __launch_bounds__(512, 1) void unit_mfma_kernel(const UnitArgs a_in, 
                 bi = cand_list[0]; // nothing to compare with: the screening already decided
                 bv = 0.0;
             } else if (ncand <= kMaxCand) {
-                for (int c = wave; c < ncand; c += NW) {
+                // This wave's first two candidates' rows are requested, then the output is stored
+                // (if this workgroup owes it and has it staged), then the rows are used: up to 16
+                // candidates cost one trip to memory, and the output's stores hide behind it.
+                RowRegs r0, r1;
+                const int c0 = wave, c1 = wave + NW;
+                if (c0 < ncand) {
+                    const int cs = cand_list[c0];
+                    load_row(r0, Ku + (size_t)cs * D, Vu + (size_t)cs * D, lane, coop && cs == ins_slot);
+                }
+                if (c1 < ncand) {
+                    const int cs = cand_list[c1];
+                    load_row(r1, Ku + (size_t)cs * D, Vu + (size_t)cs * D, lane, coop && cs == ins_slot);
+                }
+                if (coop) { merge_out(); out_stored = true; }
+                else if (o_separate) { store_out(); out_stored = true; }
+                auto take = [&](double v, int cs) __attribute__((always_inline)) {
+                    if (v < bv || (v == bv && cs < bi)) { bv = v; bi = cs; }
+                };
+                if (c0 < ncand) take(__shfl(score_row(r0, qs, G, sM, sL, lane), 0), cand_list[c0]);
+                if (c1 < ncand) take(__shfl(score_row(r1, qs, G, sM, sL, lane), 0), cand_list[c1]);
+                for (int c = wave + 2 * NW; c < ncand; c += NW) {
                     const int cs = cand_list[c];
                     if (bv == 0.0 && cs > bi) continue; // behind an exact zero nothing can win
-                    const double v = __shfl(exact_score_bf16(Ku + (size_t)cs * D, Vu + (size_t)cs * D, qs, G, sM, sL, lane,
-                                                             COOP && s_active > 1 && cs == ins_slot), 0);
-                    if (v < bv || (v == bv && cs < bi)) { bv = v; bi = cs; }
+                    take(__shfl(exact_score_bf16(Ku + (size_t)cs * D, Vu + (size_t)cs * D, qs, G, sM, sL, lane,
+                                                 coop && cs == ins_slot), 0), cs);
                 }
             } else {
                 // Far more candidates than the list holds: scores underflowing en masse, or many
@@ -738,7 +818,7 @@ __global__ __launch_bounds__(512, 1) void unit_mfma_kernel(const UnitArgs a_in, 
                         // (the score is complete in every fourth lane only: lane 0's goes to all,
                         // so that the exits below are taken by the whole wave)
                         const double v = __shfl(exact_score_bf16(Ku + (size_t)cs * D, Vu + (size_t)cs * D, qs, G, sM, sL, lane,
-                                                                 COOP && s_active > 1 && cs == ins_slot), 0);
+                                                                 coop && cs == ins_slot), 0);
                         if (v < bv || (v == bv && cs < bi)) { bv = v; bi = cs; }
                         if (bv == 0.0) break;
                     }
@@ -753,30 +833,24 @@ __global__ __launch_bounds__(512, 1) void unit_mfma_kernel(const UnitArgs a_in, 
                 for (int w = 1; w < NW; ++w)
                     if (best_v[w] < v || (best_v[w] == v && best_i[w] < i)) { v = best_v[w]; i = best_i[w]; }
                 if (i < 0 || i >= N) i = 0; // non-finite scores: keep the slot in range
-                a.pending[u] = i;
-                if (a.evict_idx) a.evict_idx[u] = i;
+                pending[u] = i;
+                if (evict_idx) evict_idx[u] = i;
             }
         }
-        __syncthreads(); // the codes are dead from here on: their LDS may be reused below
     }
 
     // ---- output: normalise, round to bf16
-    if (!COOP || s_active == 1) {
-        stage_o();
+    if (!out_stored && coop) {
+        merge_out();
+    } else if (!out_stored) {
+        if (!(o_separate && STASH == kStashLds)) {
+            __syncthreads(); // the codes are dead from here on: their LDS is reused
+            stage_o();
+        }
         __syncthreads();
-        for (int idx = tid; idx < G * D; idx += 512) {
-            const int h = idx / D, d = idx % D;
-            float acc = 0.f;
-#pragma unroll
-            for (int w = 0; w < NW; ++w) acc += sm_o[((size_t)w * G + h) * OPAD + d];
-            a.out[((size_t)u * G + h) * D + d] = (uint16_t)f32_to_bf16_bits(acc / sL[h]);
-        }
-    } else { // the output was stored with the merge
-        if (tid == 0) { // ready for the next step
-            st_agent(&a.arrive[u], 0);
-            st_agent(&a.dumped[u], dumps_ok ? 0 : kDumpsDistrusted);
-        }
+        store_out();
     }
+    if (coop && tid == 0) st_agent(&a.arrive[u], 0); // ready for the next step
 }
 
 // ---------------------------------------------------------------------------------------
@@ -808,14 +882,41 @@ int unit_mfma_split_len(int N, int S)
     return (per + 127) / 128 * 128;
 }
 
-size_t unit_mfma_lds_bytes(int N, int G, bool stash, int S)
+// How a workgroup's dynamic LDS is laid out for S workgroups per unit.
+struct UnitLds {
+    size_t merge_off; // where the O-merge area starts (0: it aliases the codes)
+    int chunk_len;    // S > 1: positions of the other workgroups' dumps held at a time
+    size_t bytes;
+};
+static UnitLds unit_lds(int N, int G, bool stash, int S)
 {
-    const size_t merge = merge_bytes(G);
-    if (!stash) return merge;
-    const size_t codes = code_bytes(unit_mfma_split_len(N, S), G);
-    if (S == 1) return codes > merge ? codes : merge; // merge area aliases the codes
-    return (codes + 255) / 256 * 256 + merge;
+    UnitLds l = {0, 0, merge_bytes(G)};
+    if (!stash) return l;
+    const size_t codes = (code_bytes(unit_mfma_split_len(N, S), G) + 255) / 256 * 256;
+    if (S == 1) {
+        // the merge area gets LDS of its own where there is room for it (the output is then
+        // staged early and stored while candidates are re-scored), else it aliases the codes
+        if (codes + merge_bytes(G) <= kUnitLdsLimit) { l.merge_off = codes; l.bytes = codes + merge_bytes(G); }
+        else l.bytes = std::max(codes, merge_bytes(G));
+        return l;
+    }
+    // Behind the own codes: first the O-merge area, then (in the deciding workgroup) the others'
+    // dumps, 1 byte per head and slot plus 4 bytes per head and 16 slots, in chunks of whole
+    // multiples of 2048 positions -- as much as fits, at least 2048 (that much the merge area
+    // alone holds), at most all of them.
+    l.merge_off = codes;
+    const size_t per_pos4 = (size_t)G * 5; // bytes per 4 positions
+    const size_t avail = kUnitLdsLimit > codes ? kUnitLdsLimit - codes : 0;
+    long long fit = (long long)(avail * 4 / per_pos4) / 2048 * 2048;
+    const long long all = (((long long)N + kTile - 1) / kTile * kTile + 2047) / 2048 * 2048;
+    if (fit > all) fit = all;
+    if (fit < 2048) fit = 2048;
+    l.chunk_len = (int)fit;
+    l.bytes = codes + std::max((size_t)fit * per_pos4 / 4, merge_bytes(G));
+    return l;
 }
+
+size_t unit_mfma_lds_bytes(int N, int G, bool stash, int S) { return unit_lds(N, G, stash, S).bytes; }
 
 // One launch of one kernel instance.  The dynamic-LDS ceiling is a per-device function
 // attribute: it is raised once per device and instance (attr_done, indexed by idx).
@@ -826,13 +927,13 @@ struct UnitLaunch {
     hipStream_t s;
     const UnitArgs *a;
     const GroupArgs *ga;
-    bool masked, gather;
 };
+constexpr int kUnitInstances = 14;
 
-template <int STASH, bool COOP, bool GROUPED, bool MASKED, bool GATHER, bool MAXFREE>
+template <int STASH, bool COOP, bool GROUPED, bool MASKED, bool MAXFREE>
 static hipError_t launch_instance(const UnitLaunch &ul, int idx)
 {
-    auto kern = unit_mfma_kernel<true, STASH, COOP, GROUPED, MASKED, GATHER, MAXFREE>;
+    auto kern = unit_mfma_kernel<true, STASH, COOP, GROUPED, MASKED, MAXFREE>;
     if (!ul.attr_done[idx]) {
         hipError_t e = hipFuncSetAttribute((const void *)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)kUnitLdsLimit);
         if (e != hipSuccess) return e;
@@ -840,22 +941,6 @@ static hipError_t launch_instance(const UnitLaunch &ul, int idx)
     }
     hipLaunchKernelGGL(kern, dim3((unsigned)ul.wgs), dim3(512), ul.lds, ul.s, *ul.a, *ul.ga);
     return hipGetLastError();
-}
-
-// The instances a (STASH, COOP, GROUPED) family really has: MASKED only where slots are
-// scored, GATHER only where cooperating workgroups screen each other's codes.
-template <int STASH, bool COOP, bool GROUPED>
-static hipError_t launch_family(const UnitLaunch &ul, int idx)
-{
-    if constexpr (STASH == kStashLds) {
-        if constexpr (COOP) {
-            if (ul.gather)
-                return ul.masked ? launch_instance<STASH, COOP, GROUPED, true, true, false>(ul, 24 + idx)
-                                 : launch_instance<STASH, COOP, GROUPED, false, true, false>(ul, 16 + idx);
-        }
-        if (ul.masked) return launch_instance<STASH, COOP, GROUPED, true, false, false>(ul, 8 + idx);
-    }
-    return launch_instance<STASH, COOP, GROUPED, false, false, false>(ul, idx);
 }
 
 // everything of a step's kernel arguments that depends on the cache and the fill level only
@@ -868,17 +953,16 @@ static UnitArgs unit_args_of(const Plan &p, int n, int S)
     a.pending = p.pending;
     a.fin_m = p.fin_m; a.fin_l = p.fin_l; a.lu = p.lu;
     a.part_m = p.part_m; a.part_l = p.part_l; a.part_o = p.part_o;
-    a.arrive = p.arrive; a.dumped = p.dumped;
+    a.arrive = p.arrive;
     a.gcode = (uint8_t *)p.stash_w; a.gref = p.stash_m;
     a.n = n; a.N = p.N; a.G = p.G; a.ntiles = p.ntiles;
     a.S = S; a.split_len = unit_mfma_split_len(p.N, S);
     a.s_active = (n + a.split_len - 1) / a.split_len;
     a.code_stride = (a.split_len + 63) / 64 * 64;
     a.gstride = p.ntiles * kTile;
-    const bool stash = !(p.flags & 1u);
-    const size_t lds = unit_mfma_lds_bytes(p.N, p.G, stash, S);
-    a.merge_off = (stash && S > 1) ? (int)(lds - merge_bytes(p.G)) : 0;
-    a.chunk_len = 0;
+    const UnitLds l = unit_lds(p.N, p.G, !(p.flags & 1u), S);
+    a.merge_off = (int)l.merge_off;
+    a.chunk_len = l.chunk_len;
     a.scale_log2 = 1.4426950408889634f / sqrtf(128.f);
     return a;
 }
@@ -917,25 +1001,7 @@ static hipError_t launch_unit(const Plan &p, const StepIo &io, int n, const void
     ga.kv_stride = (long long)p.units * 128;
     ga.ev_stride = p.units;
     size_t lds = unit_mfma_lds_bytes(p.N, p.G, stash, S);
-    bool gather = false;
-    if (stash && S > 1 && (p.N + a.split_len - 1) / a.split_len >= 3) {
-        // From three workgroups per unit on, the deciding one copies the others' dumps into
-        // LDS before screening them (with two, reading them in place is one batch of loads
-        // as well, and measured 2 us faster on cfg2).  Room behind the own codes: 1 byte per
-        // head and slot plus 4 bytes per head and 16 slots, in chunks of whole multiples of
-        // 2048 positions -- as much as fits, at least 2048 (that much the merge area alone holds).
-        const size_t per_pos4 = (size_t)p.G * 5; // bytes per 4 positions
-        const size_t avail = kUnitLdsLimit - (size_t)a.merge_off;
-        long long fit = (long long)(avail * 4 / per_pos4) / 2048 * 2048;
-        const long long all = ((long long)p.ntiles * kTile + 2047) / 2048 * 2048;
-        if (fit > all) fit = all;
-        if (fit >= 2048) {
-            gather = true;
-            a.chunk_len = (int)fit;
-            const size_t want = (size_t)a.merge_off + std::max((size_t)fit * per_pos4 / 4, merge_bytes(p.G));
-            if (want > lds) lds = want;
-        }
-    }
+    if (lds > kUnitLdsLimit) return hipErrorInvalidValue;
     // With at most a few workgroups per compute unit, ask for more than half of the
     // CU's LDS so that no CU is handed two of them while another one idles.
     const long long wgs = (long long)ga.wgs_per_cache * n_caches;
@@ -944,25 +1010,26 @@ static hipError_t launch_unit(const Plan &p, const StepIo &io, int n, const void
     // the dynamic-LDS ceiling is a per-device function attribute: raise it once per device
     // and kernel instance (a benign race if two host threads get here together: both set it)
     constexpr int kMaxDevices = 64;
-    static bool attr_done_all[kMaxDevices][34] = {};
+    static bool attr_done_all[kMaxDevices][kUnitInstances] = {};
     int dev = 0;
     if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) return hipErrorInvalidDevice;
-    bool *attr_done = attr_done_all[dev];
-    // the mask only matters where slots are scored (an attention-only cache takes none), the
-    // gathering only where cooperating workgroups screen codes
-    const UnitLaunch ul = {attr_done, wgs, lds, s, &a, &ga, p.masked, gather};
-    const bool coop = S > 1;
+    const UnitLaunch ul = {attr_done_all[dev], wgs, lds, s, &a, &ga};
+    const bool coop = S > 1, grouped = table != nullptr;
     if (p.max_free) { // attention only, one cache (the API layer admits nothing else)
         if (table || stash) return hipErrorInvalidValue;
-        return coop ? launch_instance<kStashNone, true, false, false, false, true>(ul, 32)
-                    : launch_instance<kStashNone, false, false, false, false, true>(ul, 33);
+        return coop ? launch_instance<kStashNone, true, false, false, true>(ul, 12)
+                    : launch_instance<kStashNone, false, false, false, true>(ul, 13);
     }
-    if (table) {
-        if (stash) return coop ? launch_family<kStashLds, true, true>(ul, 4) : launch_family<kStashLds, false, true>(ul, 5);
-        return coop ? launch_family<kStashNone, true, true>(ul, 6) : launch_family<kStashNone, false, true>(ul, 7);
-    }
-    if (stash) return coop ? launch_family<kStashLds, true, false>(ul, 0) : launch_family<kStashLds, false, false>(ul, 1);
-    return coop ? launch_family<kStashNone, true, false>(ul, 2) : launch_family<kStashNone, false, false>(ul, 3);
+    // the mask only matters where slots are scored (an attention-only cache takes none)
+#define LF_PICK(STASH, MASKED, base)                                                                      \
+    (coop ? (grouped ? launch_instance<STASH, true, true, MASKED, false>(ul, base + 0)                     \
+                     : launch_instance<STASH, true, false, MASKED, false>(ul, base + 1))                   \
+          : (grouped ? launch_instance<STASH, false, true, MASKED, false>(ul, base + 2)                    \
+                     : launch_instance<STASH, false, false, MASKED, false>(ul, base + 3)))
+    if (!stash) return LF_PICK(kStashNone, false, 0);
+    if (p.masked) return LF_PICK(kStashLds, true, 4);
+    return LF_PICK(kStashLds, false, 8);
+#undef LF_PICK
 }
 
 hipError_t launch_unit_mfma(const Plan &p, const void *q, const void *k_new, const void *v_new, int n,

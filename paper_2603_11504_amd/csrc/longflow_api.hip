@@ -128,7 +128,6 @@ static Layout layout_of(const Plan &p)
     };
     l.off_pending = take("pending", sizeof(int32_t) * p.units);
     l.off_arrive = take("arrive", sizeof(int32_t) * p.units);
-    l.off_dumped = take("dumped", sizeof(int32_t) * p.units);
     l.off_hole = take("first_hole", sizeof(int32_t) * p.units);
     l.off_q = take("q_last", esz * (size_t)p.B * p.Hq * p.D);
     l.off_part_m = take("part_m", sizeof(float) * (size_t)p.units * p.C * kMaxGroup);
@@ -237,7 +236,6 @@ int longflow_init_cache(longflow_cache_t **out, const lf_config *cfg, void *k_ca
     p.k_cache = k_cache; p.v_cache = v_cache;
     p.pending = (int32_t *)(ws + l.off_pending);
     p.arrive = (int32_t *)(ws + l.off_arrive);
-    p.dumped = (int32_t *)(ws + l.off_dumped);
     p.first_hole = (int32_t *)(ws + l.off_hole);
     p.q_last = ws + l.off_q;
     p.part_m = (float *)(ws + l.off_part_m);
@@ -275,7 +273,6 @@ int longflow_init_cache(longflow_cache_t **out, const lf_config *cfg, void *k_ca
     }
     {
         hipError_t e = launch_fill_i32(p.arrive, p.units, 0, s);
-        if (e == hipSuccess) e = launch_fill_i32(p.dumped, p.units, 0, s);
         if (e != hipSuccess) return fail(LF_ERR_HIP, "counter init: %s", hipGetErrorString(e));
     }
     if (p.unfused) { // prefilled rows start with no attention on their books

@@ -225,7 +225,7 @@ def test_workspace_regions_never_overlap_and_hold_every_index_the_kernels_form()
         have = {name: size for name, _, size in regs}
         wgs = info.workgroups_per_unit
         scoring = not flags & lf.LF_FLAG_ATTENTION_ONLY
-        need = {"pending": 4 * units, "arrive": 4 * units, "dumped": 4 * units, "first_hole": 4 * units,
+        need = {"pending": 4 * units, "arrive": 4 * units, "first_hole": 4 * units,
                 "q_last": esz * B * G * Hkv * D, "fin_m": 4 * units * G, "fin_l": 4 * units * G,
                 "part_o": 4 * units * wgs * G * D}
         if info.path == lf.LF_PATH_UNIT_MFMA:

@@ -894,27 +894,6 @@ def test_max_free_softmax_equals_the_referenced_one_until_it_overflows():
         lf.LongFlowCache(1, 4, 1, 64, 64, flags=AO | lf.LF_FLAG_MAX_FREE, k_init=k0[:1, :1, :8, :64].contiguous(), v_init=v0[:1, :1, :8, :64].contiguous())
 
 
-def test_a_unit_whose_dump_counter_is_distrusted_keeps_deciding_exactly():
-    # The deciding workgroup's wait for the other workgroups' code dumps is bounded; a unit whose
-    # wait once ran out carries a negative counter from then on and re-scores every slot instead
-    # of reading dumps.  The condition is planted from the host (the counters are the third
-    # 256-byte-aligned int32[units] block of the workspace), the kernels run normally.
-    wl = _small("distrust", "bf16", 1, 28, 4, 128, 2048, n_init=2047, steps=12, sink_scale=4.0, seed=23)
-    info = lf.longflow_plan_info(lf.make_config(wl.batch, wl.q_heads, wl.kv_heads, 128, wl.budget, "bf16", 0))
-    assert info.path == lf.LF_PATH_UNIT_MFMA and info.workgroups_per_unit > 1
-    rep, gpu, ora = run_lockstep(wl, steps=4)
-    units = wl.units
-    block = (4 * units + 255) // 256 * 256
-    counters = gpu.workspace[2 * block: 2 * block + 4 * units].view(torch.int32)
-    torch.cuda.synchronize()
-    assert (counters == 0).all()
-    counters[1] = -(1 << 30)                 # unit 1 only
-    rep, gpu, ora = run_lockstep(wl, steps=8, gpu_cache=gpu, oracle_cache=ora, t0=4, report=rep, check_scores_every=3)
-    torch.cuda.synchronize()
-    assert rep.steps == 12
-    assert int(counters[1]) < 0 and (counters[[0, 2, 3]] == 0).all()
-
-
 @pytest.mark.parametrize("dtype,D,flags", [("bf16", 128, 0), ("bf16", 128, lf.LF_FLAG_FORCE_SPLIT), ("f32", 64, 0)],
                          ids=["unit", "split", "valu"])
 def test_a_padded_sequence_of_zero_rows_decides_exactly_and_quickly(dtype, D, flags):
