@@ -5,11 +5,11 @@
 // own insert (Sec. 2.1).  All rows are therefore written first, and the queries then go
 // through attention several at a time, each column of the S^T = K Q^T product carrying one
 // (token, head) pair with its own causal row limit.  A 16-column product holds floor(16 / G)
-// tokens, and a workgroup streams K and V once for NB such products: the cache is read
-// once per NB * floor(16 / G) tokens instead of once per token.  The matrix and vector
-// pipes, 13 % and 23 % busy in the single-query kernel, have the room: NB = 4 is where the
-// per-tile arithmetic of a wave catches up with its share of HBM bandwidth (it costs the
-// whole register file, one wave per SIMD; NB = 2 at two waves per SIMD is 25 % slower).
+// tokens, a wave takes NB = 4 such products through every tile it loads (that costs the whole
+// register file, one wave per SIMD), and the four waves of a workgroup walk the same tiles for
+// four different sets of tokens: HBM delivers the cache once per 16 * floor(16 / G) tokens
+// instead of once per token, and the kernel is bound by arithmetic, not by memory.  Being so, it
+// loads K in the natural operand layout (half the matrix instructions for the logits).
 #include "lf_mfma_stream.h"
 
 namespace lf {
@@ -44,20 +44,25 @@ __global__ __launch_bounds__(256) void fill_insert_kernel(const FillArgs a)
     }
 }
 
-// One workgroup = one (unit, group of NB * qpb consecutive tokens); its 4 waves share the
-// tiles of rows [0, n0 + last token + 1) and merge at the end.
+// One workgroup = one (unit, group of 4 * NB * qpb consecutive tokens).  Each of its 4 waves owns
+// NB * qpb of those tokens outright and streams every tile of the rows they see: the four waves
+// read the same K/V lines at about the same time, so the cache hierarchy serves three of the four
+// reads and HBM sees the rows once per 4 * NB * qpb tokens (32 at G = 7), while no wave ever has
+// to merge with another -- there is no LDS traffic and no barrier in this kernel.
 template <int NB>
 __global__ __launch_bounds__(256) void fill_attend_kernel(const FillArgs a)
 {
     constexpr int D = 128;
-    typedef MfmaStreamer<4, true, kStashNone, false, true> Streamer;
+    typedef MfmaStreamer<1, true, kStashNone, false, true, false, true> Streamer; // causal columns, natural K layout
     const int G = a.G, units = a.units, QW = NB * a.qpb;
-    const int ngroups = (a.Tb + QW - 1) / QW;
+    const int ngroups = (a.Tb + 4 * QW - 1) / (4 * QW);
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, g = lane >> 4, r = lane & 15;
     // late tokens see the most rows: their groups go first
     const int qg = ngroups - 1 - (int)(blockIdx.x / units), u = blockIdx.x % units;
-    const int t0 = qg * QW, tl = min(t0 + QW, a.Tb) - 1;
+    const int t0 = (qg * 4 + wave) * QW;
+    if (t0 >= a.Tb) return; // the last group may be short of waves
+    const int tl = min(t0 + QW, a.Tb) - 1;
     const int n_max = a.n0 + tl + 1;
-    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, g = lane >> 4, r = lane & 15;
     const int qi = r / G, h_of_r = r % G;
 
     Streamer st[NB];
@@ -72,73 +77,60 @@ __global__ __launch_bounds__(256) void fill_attend_kernel(const FillArgs a)
         st[nb].end = n_max;
     }
 
-    // ---- stream: wave w owns tiles w, w + 4, ...; two register tiles rotate
+    // ---- stream every tile of rows [0, n_max); two register tiles rotate
     {
         const int nfull = n_max / kTile;
-        const int n_my = (nfull > wave) ? (nfull - wave + 3) / 4 : 0;
         TileRegs ta, tb;
-        auto compute = [&](TileRegs &t, int ti) {
+        auto compute = [&](TileRegs &t, int ti) __attribute__((always_inline)) {
 #pragma unroll
             for (int nb = 0; nb < NB; ++nb) st[nb].template compute_tile<false>(t, ti);
         };
-        if (n_my >= 2) {
-            st[0].template load_tile<false>(ta, wave);
-            st[0].template load_tile<false>(tb, wave + 4);
+        if (nfull >= 2) {
+            st[0].template load_tile<false>(ta, 0);
+            st[0].template load_tile<false>(tb, 1);
             int i = 0;
-            for (; i + 3 < n_my; i += 2) {
-                compute(ta, wave + 4 * i);
-                st[0].template load_tile<false>(ta, wave + 4 * (i + 2));
-                compute(tb, wave + 4 * (i + 1));
-                st[0].template load_tile<false>(tb, wave + 4 * (i + 3));
+            for (; i + 3 < nfull; i += 2) {
+                compute(ta, i);
+                st[0].template load_tile<false>(ta, i + 2);
+                compute(tb, i + 1);
+                st[0].template load_tile<false>(tb, i + 3);
             }
-            compute(ta, wave + 4 * i);
-            if (i + 2 < n_my) st[0].template load_tile<false>(ta, wave + 4 * (i + 2));
-            compute(tb, wave + 4 * (i + 1));
-            if (i + 2 < n_my) compute(ta, wave + 4 * (i + 2));
-        } else if (n_my == 1) {
-            st[0].template load_tile<false>(ta, wave);
-            compute(ta, wave);
+            compute(ta, i);
+            if (i + 2 < nfull) st[0].template load_tile<false>(ta, i + 2);
+            compute(tb, i + 1);
+            if (i + 2 < nfull) compute(ta, i + 2);
+        } else if (nfull == 1) {
+            st[0].template load_tile<false>(ta, 0);
+            compute(ta, 0);
         }
-        if (n_max % kTile != 0 && wave == nfull % 4) {
+        if (n_max % kTile != 0) {
             st[0].template load_tile<true>(ta, nfull);
 #pragma unroll
             for (int nb = 0; nb < NB; ++nb) st[nb].template compute_tile<true>(ta, nfull);
         }
     }
 
-    // ---- merge the 4 waves through LDS, one 16-column product at a time
-    __shared__ float sm_m[4][16], sm_l[4][16];
-    __shared__ __align__(16) float sm_o[4][16][D + 4];
+    // ---- normalise and store: a lane holds channels 8r .. 8r+7 of columns 4g .. 4g+3; the
+    // denominator of column c is complete in lane c once the four lane-partials are added
+    typedef __attribute__((address_space(1))) u32x4 *g_u32x4p;
 #pragma unroll
     for (int nb = 0; nb < NB; ++nb) {
         float l = st[nb].l;
         l += __shfl_xor(l, 16);
         l += __shfl_xor(l, 32);
-        if (g == 0) { sm_m[wave][r] = st[nb].m; sm_l[wave][r] = l; }
-        // a lane holds channels 8r .. 8r+7 of columns 4g .. 4g+3: two 16-byte stores per column
 #pragma unroll
         for (int v = 0; v < 4; ++v) {
-            float *row = &sm_o[wave][4 * g + v][8 * r];
-            *(f32x4 *)row = f32x4{st[nb].oacc[0][v], st[nb].oacc[1][v], st[nb].oacc[2][v], st[nb].oacc[3][v]};
-            *(f32x4 *)(row + 4) = f32x4{st[nb].oacc[4][v], st[nb].oacc[5][v], st[nb].oacc[6][v], st[nb].oacc[7][v]};
-        }
-        __syncthreads();
-        for (int idx = tid; idx < 16 * D; idx += 256) {
-            const int col = idx / D, d = idx % D;
+            const int col = 4 * g + v;
+            const float inv = 1.f / __shfl(l, col);
             const int t = t0 + nb * a.qpb + col / G;
             if (col / G < a.qpb && t <= tl) {
-                const float M = fmaxf(fmaxf(sm_m[0][col], sm_m[1][col]), fmaxf(sm_m[2][col], sm_m[3][col]));
-                float acc = 0.f, lacc = 0.f;
-#pragma unroll
-                for (int w = 0; w < 4; ++w) {
-                    const float wgt = fast_exp2(sm_m[w][col] - M); // a wave that saw no row of this column: 2^(-3e38) = 0
-                    acc += wgt * sm_o[w][col][d];
-                    lacc += wgt * sm_l[w][col];
-                }
-                a.out[(((size_t)t * units + u) * G + col % G) * D + d] = (uint16_t)f32_to_bf16_bits(acc / lacc);
+                const u32x4 o = {pack_bf16x2(st[nb].oacc[0][v] * inv, st[nb].oacc[1][v] * inv),
+                                 pack_bf16x2(st[nb].oacc[2][v] * inv, st[nb].oacc[3][v] * inv),
+                                 pack_bf16x2(st[nb].oacc[4][v] * inv, st[nb].oacc[5][v] * inv),
+                                 pack_bf16x2(st[nb].oacc[6][v] * inv, st[nb].oacc[7][v] * inv)};
+                *(g_u32x4p)(a.out + (((size_t)t * units + u) * G + col % G) * D + 8 * r) = o;
             }
         }
-        __syncthreads();
     }
 }
 
@@ -162,7 +154,7 @@ hipError_t launch_fill_bulk(const Plan &p, const void *q, const void *k_new, con
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
     constexpr int NB = 4;
-    const int QW = NB * a.qpb;
+    const int QW = 4 * NB * a.qpb; // tokens per workgroup
     const long long wgs = (long long)((Tb + QW - 1) / QW) * p.units;
     hipLaunchKernelGGL((fill_attend_kernel<NB>), dim3((unsigned)wgs), dim3(256), 0, s, a);
     return hipGetLastError();

@@ -92,12 +92,19 @@ __device__ __forceinline__ uint32_t pack_bf16x2(float lo, float hi)
     return __builtin_bit_cast(uint32_t, b);
 }
 
+// KNAT: K in the natural A-operand layout -- lane (g, r) reads row r of the tile, channels
+//       32c + 8g .. +7 for c = 0..3 (16 rows x 64 B per instruction: half lines), one product of
+//       four MFMAs gives the whole logit, and a lane's four slots are 4g .. 4g + 3.  Half the
+//       matrix instructions of the full-line scheme and no joining adds, at the price of the
+//       half-line loads: right for the multi-query kernel, which is bound by arithmetic and not
+//       by a compute unit's request rate.  (No per-slot side data exists in that layout.)
 // MASKED: an explicit validity mask may be in force (NaN entries of the side array)
 // CAUSAL: every column (lane r) has its own row limit: it sees slots below `limit` only
 // MAXFREE: the softmax of Alg. 1 as printed (Sec. 3.4, modification 2): no running reference,
 //          p = 2^t in fp32; overflows once a logit passes 2^128.  For A/B measurement.
-template <int NWAVES, bool HILO, int STASH, bool MASKED = false, bool CAUSAL = false, bool MAXFREE = false>
+template <int NWAVES, bool HILO, int STASH, bool MASKED = false, bool CAUSAL = false, bool MAXFREE = false, bool KNAT = false>
 struct MfmaStreamer {
+    static_assert(!KNAT || STASH == kStashNone, "the natural K layout keeps no per-slot side data");
     static constexpr int D = 128;
     // per-wave state
     u32x4 qreg[2][2]; // qreg[L][b]: head r, channels 64L + 8(2g + b) .. +7
@@ -142,7 +149,8 @@ struct MfmaStreamer {
 #pragma unroll
             for (int b = 0; b < 2; ++b) {
                 qreg[L][b] = u32x4{0u, 0u, 0u, 0u};
-                if (q_col) qreg[L][b] = *(g_cu32x4p)(q_col + 64 * L + 8 * (2 * g + b));
+                // KNAT: qreg[c >> 1][c & 1] holds channels 32c + 8g .. +7
+                if (q_col) qreg[L][b] = *(g_cu32x4p)(q_col + (KNAT ? 32 * (2 * L + b) + 8 * g : 64 * L + 8 * (2 * g + b)));
             }
 #pragma unroll
         for (int dd = 0; dd < 8; ++dd) oacc[dd] = f32x4{0.f, 0.f, 0.f, 0.f};
@@ -150,7 +158,15 @@ struct MfmaStreamer {
         l = 0.f;
     }
 
-    __device__ __forceinline__ int slot_off(int e) const { return 8 * (e >> 1) + 2 * g + (e & 1); }
+    __device__ __forceinline__ int slot_off(int e) const { return KNAT ? 4 * g + e : 8 * (e >> 1) + 2 * g + (e & 1); }
+
+    // K/V are read once and never again by a decode step: non-temporal.  The multi-query
+    // (CAUSAL) kernel has several waves walk the same rows: ordinary loads, so that the caches
+    // keep the lines for the other waves.
+    static __device__ __forceinline__ u32x4 stream_load(g_cu32x4p p)
+    {
+        return CAUSAL ? *p : __builtin_nontemporal_load(p);
+    }
 
     // RAGGED clamps rows to the valid prefix (a full tile needs no clamp)
     template <bool RAGGED> __device__ __forceinline__ void load_tile(TileRegs &t, int ti) const
@@ -160,20 +176,26 @@ struct MfmaStreamer {
         // side array first: loads return in order, and its first use (the mask test right
         // after the logits) must not have to wait for this tile's V rows
         if (STASH != kStashNone) t.lu = *(g_cf32x4p)(lu_unit + base + 4 * g);
-#pragma unroll
-        for (int a = 0; a < 2; ++a) {
-            int krow = base + 8 * a + (r >> 1);
+        if (KNAT) {
+            int krow = base + r;
             if (RAGGED) krow = min(krow, last);
 #pragma unroll
-            for (int L = 0; L < 2; ++L)
-                t.k[a][L] = __builtin_nontemporal_load(
-                    (g_cu32x4p)(Ku + (size_t)krow * D + 64 * L + 8 * (2 * g + (r & 1))));
+            for (int c = 0; c < 4; ++c) t.k[c >> 1][c & 1] = stream_load((g_cu32x4p)(Ku + (size_t)krow * D + 32 * c + 8 * g));
+        } else {
+#pragma unroll
+            for (int a = 0; a < 2; ++a) {
+                int krow = base + 8 * a + (r >> 1);
+                if (RAGGED) krow = min(krow, last);
+#pragma unroll
+                for (int L = 0; L < 2; ++L)
+                    t.k[a][L] = stream_load((g_cu32x4p)(Ku + (size_t)krow * D + 64 * L + 8 * (2 * g + (r & 1))));
+            }
         }
 #pragma unroll
         for (int e = 0; e < 4; ++e) {
             int vrow = base + slot_off(e);
             if (RAGGED) vrow = min(vrow, last);
-            t.v[e] = __builtin_nontemporal_load((g_cu32x4p)(Vu + (size_t)vrow * D + 8 * r));
+            t.v[e] = stream_load((g_cu32x4p)(Vu + (size_t)vrow * D + 8 * r));
         }
     }
 
@@ -182,17 +204,30 @@ struct MfmaStreamer {
     {
         const int base = start + ti * kTile;
         if (RAGGED) {
+            if (KNAT) {
+                if (base + r >= end) t.k[0][0] = t.k[0][1] = t.k[1][0] = t.k[1][1] = u32x4{0u, 0u, 0u, 0u};
+            } else {
 #pragma unroll
-            for (int a = 0; a < 2; ++a)
-                if (base + 8 * a + (r >> 1) >= end) t.k[a][0] = t.k[a][1] = u32x4{0u, 0u, 0u, 0u};
+                for (int a = 0; a < 2; ++a)
+                    if (base + 8 * a + (r >> 1) >= end) t.k[a][0] = t.k[a][1] = u32x4{0u, 0u, 0u, 0u};
+            }
 #pragma unroll
             for (int e = 0; e < 4; ++e)
                 if (base + slot_off(e) >= end) t.v[e] = u32x4{0u, 0u, 0u, 0u};
         }
         // ---- S^T = K Q^T: per 8-row group, one product per chunk parity b
         float s[4];
+        if (KNAT) {
+            f32x4 d = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
-        for (int a = 0; a < 2; ++a) {
+            for (int c = 0; c < 4; ++c)
+                d = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, t.k[c >> 1][c & 1]),
+                                                            __builtin_bit_cast(bf16x8, qreg[c >> 1][c & 1]), d, 0, 0, 0);
+            // accumulator rows 4g + v are slots 4g + v
+            s[0] = d[0]; s[1] = d[1]; s[2] = d[2]; s[3] = d[3];
+        }
+#pragma unroll
+        for (int a = 0; a < (KNAT ? 0 : 2); ++a) {
             f32x4 d0 = {0.f, 0.f, 0.f, 0.f}, d1 = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
             for (int L = 0; L < 2; ++L) {
