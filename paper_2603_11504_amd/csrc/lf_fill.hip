@@ -5,9 +5,9 @@
 // own insert (Sec. 2.1).  All rows are therefore written first, and the queries then go
 // through attention several at a time, each column of the S^T = K Q^T product carrying one
 // (token, head) pair with its own causal row limit.  A 16-column product holds floor(16 / G)
-// tokens, a wave takes NB = 4 such products through every tile it loads (that costs the whole
-// register file, one wave per SIMD), and the four waves of a workgroup walk the same tiles for
-// four different sets of tokens: HBM delivers the cache once per 16 * floor(16 / G) tokens
+// tokens, a wave takes NB = 2 such products through every tile it loads, and the eight waves of
+// a workgroup walk the same tiles for eight different sets of tokens: HBM delivers the cache
+// once per 16 * floor(16 / G) tokens
 // instead of once per token, and the kernel is bound by arithmetic, not by memory.  Being so, it
 // loads K in the natural operand layout (half the matrix instructions for the logits).
 #include "lf_mfma_stream.h"
@@ -44,22 +44,29 @@ __global__ __launch_bounds__(256) void fill_insert_kernel(const FillArgs a)
     }
 }
 
-// One workgroup = one (unit, group of 4 * NB * qpb consecutive tokens).  Each of its 4 waves owns
-// NB * qpb of those tokens outright and streams every tile of the rows they see: the four waves
-// read the same K/V lines at about the same time, so the cache hierarchy serves three of the four
-// reads and HBM sees the rows once per 4 * NB * qpb tokens (32 at G = 7), while no wave ever has
-// to merge with another -- there is no LDS traffic and no barrier in this kernel.
-template <int NB>
-__global__ __launch_bounds__(256) void fill_attend_kernel(const FillArgs a)
+// One workgroup = one (unit, group of NWV * NB * qpb consecutive tokens).  Each of its NWV waves
+// owns NB * qpb of those tokens outright and streams every tile of the rows they see: the waves
+// read the same K/V lines at about the same time, so the cache hierarchy serves all but one of
+// the reads and HBM sees the rows once per NWV * NB * qpb tokens (32 at G = 7), while no wave ever
+// has to merge with another -- there is no LDS traffic and no barrier in this kernel.  NB = 2
+// products per wave leave room for two waves per SIMD, which hide each other's matrix and LDS-free
+// softmax latencies better than one wave with four products does (measured 5 % / 22 % faster on
+// 8192- / 4096-slot caches).
+template <int NB, int NWV>
+__global__ __launch_bounds__(64 * NWV) void fill_attend_kernel(const FillArgs a)
 {
     constexpr int D = 128;
-    typedef MfmaStreamer<1, true, kStashNone, false, true, false, true> Streamer; // causal columns, natural K layout
+    // causal columns, natural K layout; the weights enter the P V product as single bf16 values (the
+    // matrix pipe is not idle here as it is in the decode step, and the second product for the
+    // low parts costs 8 % of the kernel): an output can differ from the decode step's by one unit in
+    // the last place of bf16
+    typedef MfmaStreamer<1, false, kStashNone, false, true, false, true> Streamer;
     const int G = a.G, units = a.units, QW = NB * a.qpb;
-    const int ngroups = (a.Tb + 4 * QW - 1) / (4 * QW);
+    const int ngroups = (a.Tb + NWV * QW - 1) / (NWV * QW);
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, g = lane >> 4, r = lane & 15;
     // late tokens see the most rows: their groups go first
     const int qg = ngroups - 1 - (int)(blockIdx.x / units), u = blockIdx.x % units;
-    const int t0 = (qg * 4 + wave) * QW;
+    const int t0 = (qg * NWV + wave) * QW;
     if (t0 >= a.Tb) return; // the last group may be short of waves
     const int tl = min(t0 + QW, a.Tb) - 1;
     const int n_max = a.n0 + tl + 1;
@@ -153,10 +160,10 @@ hipError_t launch_fill_bulk(const Plan &p, const void *q, const void *k_new, con
     hipLaunchKernelGGL(fill_insert_kernel, dim3((unsigned)blocks), dim3(256), 0, s, a);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
-    constexpr int NB = 4;
-    const int QW = 4 * NB * a.qpb; // tokens per workgroup
+    constexpr int NB = 2, NWV = 8;
+    const int QW = NWV * NB * a.qpb; // tokens per workgroup
     const long long wgs = (long long)((Tb + QW - 1) / QW) * p.units;
-    hipLaunchKernelGGL((fill_attend_kernel<NB>), dim3((unsigned)wgs), dim3(256), 0, s, a);
+    hipLaunchKernelGGL((fill_attend_kernel<NB, NWV>), dim3((unsigned)wgs), dim3(64 * NWV), 0, s, a);
     return hipGetLastError();
 }
 
