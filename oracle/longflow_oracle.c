@@ -42,6 +42,11 @@
  * Steps 1-4 are unchanged.  Prefilled rows start at acc = 0 (no prompt
  * attention is defined on this path).  Rule 1 takes no explicit mask.
  *
+ * Prompt compression (lfo_compress_prompt): a prompt longer than the budget is
+ * cut to the budget once, before decoding, by the observation-window voting of
+ * SnapKV, which the paper names for this (Sec. 4.1) without restating it; the
+ * reading taken is written out at the function.
+ *
  * The method reaches these plain definitions exactly (the fused kernel of
  * Alg. 1 is only a faster route), so the oracle IS the definitions written
  * out.  Max-subtraction inside the softmax is the textbook, exact-arithmetic
@@ -421,6 +426,100 @@ LFO_API void lfo_cache_get_kv(const lfo_cache *c, double *K, double *V)
     size_t n = (size_t)c->B * c->Hkv * c->N * c->D;
     memcpy(K, c->K, sizeof(double) * n);
     memcpy(V, c->V, sizeof(double) * n);
+}
+
+/* ------------------------------------------------------------------ */
+/* A prompt longer than the budget (Sec. 4.1, implementation details)   */
+/* ------------------------------------------------------------------ */
+
+/*
+ * The paper compresses such a prompt to the budget before decoding starts and
+ * names the published SnapKV procedure for it without restating it.  The
+ * reading taken, with that procedure's parameters as arguments, for one KV
+ * head and its G query heads:
+ *   - the last W prompt positions are the observation window; window query j
+ *     (prompt position T-W+j) attends causally, i.e. over positions
+ *     0 .. T-W+j, with the softmax of eq. 1;
+ *   - vote(i) = sum over the W window queries and the G heads of alpha(i),
+ *     for the prefix positions i < T-W;
+ *   - pooled(i) = (sum of vote over the `pool` positions centred on i, those
+ *     outside the prefix counting as 0) / pool   (pool odd; 1 = no pooling);
+ *   - kept: the keep-W prefix positions with the largest pooled vote (lowest
+ *     position first among equals), in ascending position order, followed by
+ *     the W window positions.
+ *   q_window [W][G][D], K [T][D]; pooled [T-W] (may be NULL), kept [keep].
+ * Returns nonzero if the arguments are out of range (1 <= W <= keep <= T,
+ * pool odd and >= 1).
+ */
+LFO_API int lfo_compress_prompt_unit(int T, int W, int keep, int pool, int D, int G,
+                                     const double *q_window, const double *K,
+                                     double *pooled_out, int32_t *kept)
+{
+    if (W < 1 || keep < W || keep > T || pool < 1 || (pool & 1) == 0) return 1;
+    const int P = T - W; /* prefix positions */
+    double *vote = (double *)calloc((size_t)(P > 0 ? P : 1), sizeof(double));
+    double *a = (double *)malloc(sizeof(double) * (size_t)T);
+    for (int j = 0; j < W; ++j) {
+        const int n = P + j + 1; /* positions this query sees */
+        for (int h = 0; h < G; ++h) {
+            const double *qh = q_window + ((size_t)j * G + h) * D;
+            double smax = -INFINITY, Z = 0.0;
+            for (int i = 0; i < n; ++i) {
+                double dot = 0.0;
+                for (int l = 0; l < D; ++l) dot += qh[l] * K[(size_t)i * D + l];
+                a[i] = dot / sqrt((double)D);
+                if (a[i] > smax) smax = a[i];
+            }
+            for (int i = 0; i < n; ++i) { a[i] = exp(a[i] - smax); Z += a[i]; }
+            for (int i = 0; i < P; ++i) vote[i] += a[i] / Z;
+        }
+    }
+    double *pooled = (double *)malloc(sizeof(double) * (size_t)(P > 0 ? P : 1));
+    for (int i = 0; i < P; ++i) {
+        double sum = 0.0;
+        for (int d = -(pool / 2); d <= pool / 2; ++d)
+            if (i + d >= 0 && i + d < P) sum += vote[i + d];
+        pooled[i] = sum / pool;
+    }
+    /* the keep-W largest, lowest position first among equals: pick them one by one */
+    const int kp = keep - W;
+    uint8_t *taken = (uint8_t *)calloc((size_t)(P > 0 ? P : 1), 1);
+    for (int r = 0; r < kp; ++r) {
+        int best = -1;
+        for (int i = 0; i < P; ++i)
+            if (!taken[i] && (best < 0 || pooled[i] > pooled[best])) best = i;
+        taken[best] = 1;
+    }
+    int d = 0;
+    for (int i = 0; i < P; ++i)
+        if (taken[i]) kept[d++] = i;
+    for (int j = 0; j < W; ++j) kept[d++] = P + j;
+    if (pooled_out) memcpy(pooled_out, pooled, sizeof(double) * (size_t)P);
+    free(vote); free(a); free(pooled); free(taken);
+    return 0;
+}
+
+/* the same for every (batch, KV head) unit: q_window [W][B][Hq][D], K [B][Hkv][T][D],
+ * pooled [B][Hkv][T-W] (may be NULL), kept [B][Hkv][keep] */
+LFO_API int lfo_compress_prompt(int B, int Hq, int Hkv, int D, int T, int W, int keep, int pool,
+                                const double *q_window, const double *K, double *pooled, int32_t *kept)
+{
+    if (B < 1 || Hkv < 1 || Hq % Hkv) return 1;
+    const int G = Hq / Hkv;
+    int bad = 0;
+#pragma omp parallel for schedule(dynamic, 1)
+    for (int u = 0; u < B * Hkv; ++u) {
+        const int b = u / Hkv, g = u % Hkv;
+        double *qw = (double *)malloc(sizeof(double) * (size_t)W * G * D);
+        for (int j = 0; j < W; ++j)
+            memcpy(qw + (size_t)j * G * D, q_window + (((size_t)j * B + b) * Hq + (size_t)g * G) * D,
+                   sizeof(double) * (size_t)G * D);
+        if (lfo_compress_prompt_unit(T, W, keep, pool, D, G, qw, K + (size_t)u * T * D,
+                                     pooled ? pooled + (size_t)u * (T - W) : NULL, kept + (size_t)u * keep))
+            bad = 1;
+        free(qw);
+    }
+    return bad;
 }
 
 LFO_API int lfo_num_threads(void)

@@ -82,6 +82,8 @@ def lib():
         L.lfo_cache_evict_lowest.restype = ctypes.c_int
         L.lfo_cache_set_rule.argtypes = [ctypes.c_void_p, ctypes.c_int]
         L.lfo_cache_set_rule.restype = ctypes.c_int
+        L.lfo_compress_prompt.argtypes = [ctypes.c_int] * 8 + [_dp, _dp, _dp, _ip]
+        L.lfo_compress_prompt.restype = ctypes.c_int
         L.lfo_num_threads.argtypes = []
         L.lfo_num_threads.restype = ctypes.c_int
         _lib = L
@@ -115,6 +117,22 @@ def attend_unit(q, K, V, want_alpha=False):
 def argmin(x):
     x = _d(x)
     return int(lib().lfo_argmin(x.size, _ptr(x)))
+
+
+def compress_prompt(q_window, K, keep, pool=1):
+    """A prompt longer than the budget, cut to `keep` rows by observation-window voting.
+    q_window [W,B,Hq,D] (queries of the last W prompt positions), K [B,Hkv,T,D]
+    -> (pooled votes [B,Hkv,T-W], kept positions [B,Hkv,keep] ascending)."""
+    q_window = _d(q_window); K = _d(K)
+    W, B, Hq, D = q_window.shape
+    _, Hkv, T, _ = K.shape
+    assert K.shape == (B, Hkv, T, D)
+    pooled = np.empty((B, Hkv, T - W))
+    kept = np.empty((B, Hkv, keep), dtype=np.int32)
+    if lib().lfo_compress_prompt(B, Hq, Hkv, D, T, W, int(keep), int(pool), _ptr(q_window), _ptr(K),
+                                 _ptr(pooled), kept.ctypes.data_as(_ip)):
+        raise ValueError("need 1 <= W <= keep <= T and an odd pool width")
+    return pooled, kept
 
 
 def num_threads() -> int:

@@ -576,3 +576,67 @@ def test_single_slot_budget_returns_the_new_value_row_and_recycles_slot_zero(rul
         np.testing.assert_allclose(out.reshape(B, Hkv, G, D), np.broadcast_to(v[:, :, None], (B, Hkv, G, D)), rtol=1e-15)
         want = G * np.abs(v).sum(-1) if rule == "longflow" else np.full((B, Hkv), float(G))   # one slot holds all the weight
         np.testing.assert_allclose(c.scores()[..., 0], want, rtol=1e-14)
+
+
+# ---------------------------------------------------------------- a prompt longer than the budget (Sec. 4.1)
+
+def _votes_by_library(qw, K):
+    """Observation-window votes with scipy's softmax: qw [W,G,D], K [T,D] -> [T-W]."""
+    W, G, D = qw.shape
+    T = K.shape[0]
+    P = T - W
+    vote = np.zeros(P)
+    for j in range(W):
+        for h in range(G):
+            a = scipy_softmax(K[: P + j + 1] @ qw[j, h] / math.sqrt(D))
+            vote += a[:P]
+    return vote
+
+
+@pytest.mark.parametrize("pool", [1, 3, 7])
+def test_prompt_compression_votes_pooling_and_selection(pool):
+    rng = np.random.default_rng(4000 + pool)
+    B, Hq, Hkv, D, T, W, keep = 2, 6, 2, 16, 61, 5, 23
+    G = Hq // Hkv
+    qw = rng.standard_normal((W, B, Hq, D))
+    K = rng.standard_normal((B, Hkv, T, D))
+    pooled, kept = oracle.compress_prompt(qw, K, keep, pool)
+    for b in range(B):
+        for g in range(Hkv):
+            vote = _votes_by_library(qw[:, b, g * G:(g + 1) * G], K[b, g])
+            # every window query hands out one unit of weight per head, part of it inside the window
+            assert vote.sum() <= W * G + 1e-9
+            ref = np.convolve(vote, np.ones(pool), mode="same") / pool      # zero padding at both ends
+            np.testing.assert_allclose(pooled[b, g], ref, rtol=1e-12, atol=1e-15)
+            k = kept[b, g]
+            assert (np.diff(k) > 0).all()                                   # original order
+            assert (k[-W:] == np.arange(T - W, T)).all()                    # the window is always kept
+            order = np.lexsort((np.arange(T - W), -ref))                    # largest first, lowest position among equals
+            assert set(k[:-W].tolist()) == set(order[: keep - W].tolist())
+
+
+def test_prompt_compression_closed_forms_and_edges():
+    rng = np.random.default_rng(4100)
+    B, Hq, Hkv, D, T, W = 1, 2, 1, 8, 40, 4
+    qw = rng.standard_normal((W, B, Hq, D))
+    # all keys equal: every position a query sees gets the same weight, so prefix votes are all equal
+    # (sum over j of 1/(P+j+1) per head) and ties go to the lowest positions
+    K = np.tile(rng.standard_normal((1, 1, 1, D)), (1, 1, T, 1))
+    pooled, kept = oracle.compress_prompt(qw, K, 10, 1)
+    P = T - W
+    expect = Hq * sum(1.0 / (P + j + 1) for j in range(W))
+    np.testing.assert_allclose(pooled[0, 0], expect, rtol=1e-12)
+    assert kept[0, 0].tolist() == list(range(6)) + list(range(P, T))
+    # one prefix key aligned with every query and scaled up: it takes (nearly) all the votes and is kept first
+    K2 = rng.standard_normal((1, 1, T, D)) * 0.01
+    K2[0, 0, 17] = 50.0 * qw[:, 0].sum((0, 1))
+    pooled, kept = oracle.compress_prompt(qw, K2, W + 1, 1)
+    assert kept[0, 0, 0] == 17 and pooled[0, 0, 17] > 0.9 * W * Hq
+    # keep == T keeps everything; keep == W keeps the window only; bad arguments are refused
+    _, kept = oracle.compress_prompt(qw, K2, T, 3)
+    assert kept[0, 0].tolist() == list(range(T))
+    _, kept = oracle.compress_prompt(qw, K2, W, 3)
+    assert kept[0, 0].tolist() == list(range(P, T))
+    for bad in (dict(keep=W - 1), dict(keep=T + 1), dict(pool=2), dict(pool=0)):
+        with pytest.raises(ValueError):
+            oracle.compress_prompt(qw, K2, bad.get("keep", 10), bad.get("pool", 1))
