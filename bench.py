@@ -54,6 +54,12 @@ def parse():
     ap.add_argument("--fill", action="store_true",
                     help="time filling one empty cache of the workload's geometry to the brim: one longflow_fill_steps call "
                          "against the same tokens as consecutive decode steps")
+    ap.add_argument("--compress", action="store_true",
+                    help="time longflow_compress_prompt: a prompt of --prompt-len tokens into one empty cache of the "
+                         "workload's geometry (observation window --window, pooling width --pool-width)")
+    ap.add_argument("--prompt-len", type=int, default=0, help="--compress: prompt tokens (default 4 x budget)")
+    ap.add_argument("--window", type=int, default=32)
+    ap.add_argument("--pool-width", type=int, default=7)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run one 1 GiB device copy (a kernel of known traffic, to scale rocprofv3 byte counters)")
@@ -374,6 +380,44 @@ def fill_bench(a):
         "dtype": "f32" if wl.dtype == "f32" else "bf16", "data": "synthetic", "n_gpus": 1}))
 
 
+def compress_bench(a):
+    """One-shot compression of a prompt longer than the budget (one layer of the workload's geometry).
+    The dominant kernels are the two multi-query passes over the prompt's keys (softmax states, then
+    votes); their arithmetic is the logits, 2 x T x head_dim x (window x group) multiply-adds per unit and pass."""
+    import torch
+    from paper_2603_11504_amd import longflow as lf
+    from paper_2603_11504_amd import workloads as W
+    wl = W.scaled(W.CONFIGS[int(a.workload.replace("cfg", ""))], layers=1, n_init=0)
+    dev = torch.device("cuda:0")
+    T = a.prompt_len or 4 * wl.budget
+    Wn, keep = a.window, wl.budget - 1
+    qw, kp, vp = W.device_prompt(wl, T, Wn, dev)
+    times = []
+    for it in range(1 + max(a.steps or 5, 1)):
+        c = lf.LongFlowCache(wl.batch, wl.q_heads, wl.kv_heads, wl.head_dim, wl.budget, dtype=W.torch_dtype(wl), device=dev)
+        torch.cuda.synchronize()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        c.compress_prompt(qw, kp, vp, keep, a.pool_width, want_pooled=False)
+        e1.record()
+        torch.cuda.synchronize()
+        assert c.valid_count == keep
+        if it:
+            times.append(e0.elapsed_time(e1))
+        c.close()
+    ms = sorted(times)[len(times) // 2]
+    flops = 2 * 2.0 * T * wl.head_dim * Wn * wl.group * wl.units          # both passes
+    print(json.dumps({
+        "metric": "prompt_tokens_per_s", "unit": "tokens/s", "value": wl.batch * T / (ms * 1e-3),
+        "config": {"workload": wl.name + "_compress_prompt", "batch": wl.batch, "q_heads": wl.q_heads, "kv_heads": wl.kv_heads,
+                   "head_dim": wl.head_dim, "budget": wl.budget, "prompt_tokens": T, "window": Wn, "pool": a.pool_width, "keep": keep},
+        "ms_per_call": ms, "ms_min": min(times), "calls": len(times),
+        "roofline": {"bound": "mfma", "kernel": "compress_stats_kernel + compress_votes_kernel", "achieved": flops / (ms * 1e-3) / 1e12,
+                     "peak": 2500.0, "unit": "TFLOP/s", "frac": flops / (ms * 1e-3) / 1e12 / 2500.0,
+                     "flops_per_call": flops, "note": "whole call (six kernels) in the denominator; see profiles/ for the split"},
+        "dtype": "bf16", "data": "synthetic", "n_gpus": 1}))
+
+
 def report(a):
     """Table over all BASELINE workloads plus the uncompressed twin of cfg4 (plain attention
     over all 81920 tokens, the kernel-level analogue of the paper's FullKV comparison)."""
@@ -432,6 +476,9 @@ def main():
         return
     if a.fill:
         fill_bench(a)
+        return
+    if a.compress:
+        compress_bench(a)
         return
     idx = int(a.workload.replace("cfg", ""))
     wl = W.CONFIGS[idx]

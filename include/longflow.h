@@ -192,6 +192,40 @@ LF_API int longflow_fill_steps(longflow_cache_t *cache, int32_t T, const void *q
                         void *out, int32_t *evict_idx, void *hip_stream);
 
 /*
+ * A prompt longer than the budget, cut down once before decoding starts.  The paper does this
+ * with SnapKV and does not restate it (Sec. 4.1, implementation details); the reading built
+ * here, per (batch, KV head) with its Hq/Hkv query heads, T prompt rows, the last W of them the
+ * observation window, P = T - W the prefix:
+ *   - window query j (prompt row P + j) attends causally, over rows 0 .. P + j, with the softmax
+ *     of eq. 1;
+ *   - vote(i) = sum over the W window queries and the group's query heads of the attention
+ *     weight of prefix row i;
+ *   - pooled(i) = (sum of vote over the `pool` rows centred on i, rows outside the prefix
+ *     counting as 0) / pool;
+ *   - kept: the keep - W prefix rows with the largest pooled vote (lowest row among equals), in
+ *     prompt order, then the W window rows; they become slots 0 .. keep - 1 of the cache.
+ * Afterwards the cache holds `keep` valid rows and goes on exactly as one created with
+ * longflow_init_cache(n_init = keep): it keeps filling if keep < N, and with keep == N needs
+ * longflow_set_pending before the first step.
+ *   q_window  device [W][B][Hq][D]: the queries of the last W prompt rows
+ *   k_prompt, v_prompt  device [B][Hkv][T][D]; read only
+ *   keep      W <= keep <= min(T, N);  pool: odd, 1 (no pooling) .. 1023
+ *   scratch   device, >= longflow_compress_scratch_bytes(cfg, T, W), 256-byte aligned, free for
+ *             reuse once the call's work on hip_stream has run
+ *   pooled    device float [B][Hkv][T - W] or NULL: the pooled votes (fp32 arithmetic)
+ *   kept      device int32 [B][Hkv][keep] or NULL: the prompt rows now in slots 0 .. keep - 1
+ * All pointers 16-byte aligned.  LF_ERR_STATE unless the cache is empty (created with
+ * n_init = 0, no step, no mask); LF_ERR_UNSUPPORTED for fp32 or head_dim 64 caches, with
+ * LF_FLAG_ATTENTION_ONLY / LF_FLAG_FORCE_VALU / LF_FLAG_UNFUSED_ACCUM, for W * Hq/Hkv > 4096 and
+ * for B * Hkv * T >= 2^27.  Errors are found before anything is launched.
+ */
+LF_API size_t longflow_compress_scratch_bytes(const lf_config *cfg, int32_t T, int32_t W);
+LF_API int longflow_compress_prompt(longflow_cache_t *cache, int32_t T, int32_t W, int32_t keep, int32_t pool,
+                                    const void *q_window, const void *k_prompt, const void *v_prompt,
+                                    void *scratch, size_t scratch_bytes, float *pooled, int32_t *kept,
+                                    void *hip_stream);
+
+/*
  * LongFlowScore of every slot as of the most recent decode step (the vector
  * S_final_loss of Alg. 1): device float [B][Hkv][N], 0 for invalid slots.
  * Recomputed on demand from the cache and that step's query; not part of the

@@ -98,6 +98,16 @@ hipError_t launch_unfused_scores(const Plan &p, float *scores, hipStream_t s); /
 int fill_tokens_per_pass(int G);
 hipError_t launch_fill_bulk(const Plan &p, const void *q, const void *k_new, const void *v_new, void *out, int n0,
                             int Tb, hipStream_t s);
+// One-shot compression of a prompt of T rows to `keep` rows (observation window of W rows, votes pooled over
+// `pool` rows): fills slots [0, keep) of the cache and its side array.  Scratch as carved by compress_layout
+// (keep_max = the cache's budget); pooled votes float [units][T - W] and kept rows int32 [units][keep] stay there.
+struct CompressLayout {
+    size_t off_part_m, off_part_l, off_cq, off_votes, off_pooled, off_kept, total;
+};
+void compress_geometry(int units, int T, int *LS, int *nspans);
+CompressLayout compress_layout(int units, int G, int T, int W, int keep_max);
+hipError_t launch_compress_prompt(const Plan &p, int T, int W, int keep, int pool, const void *q_window,
+                                  const void *k_prompt, const void *v_prompt, void *scratch, hipStream_t s);
 hipError_t launch_scores(const Plan &p, int n, float *scores, hipStream_t s);
 // Drop the k lowest-scoring valid slots of every unit (scores of the last step, in double
 // precision via `scratch`, device double [units][N]); they become holes of the explicit mask.

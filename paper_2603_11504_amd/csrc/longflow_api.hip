@@ -386,6 +386,61 @@ int longflow_fill_steps(longflow_cache_t *cache, int32_t T, const void *q, const
     return LF_OK;
 }
 
+size_t longflow_compress_scratch_bytes(const lf_config *cfg, int32_t T, int32_t W)
+{
+    if (validate(cfg) != LF_OK) return 0;
+    if (T < 1 || T > (1 << 24) || W < 1 || W > T) return 0;
+    const int G = cfg->q_heads / cfg->kv_heads;
+    if ((long long)W * G > 4096) return 0;
+    return compress_layout(cfg->batch * cfg->kv_heads, G, T, W, cfg->budget).total;
+}
+
+int longflow_compress_prompt(longflow_cache_t *cache, int32_t T, int32_t W, int32_t keep, int32_t pool,
+                             const void *q_window, const void *k_prompt, const void *v_prompt, void *scratch,
+                             size_t scratch_bytes, float *pooled, int32_t *kept, void *hip_stream)
+{
+    longflow_cache *c = checked(cache);
+    if (!c) return fail(LF_ERR_STATE, "invalid or destroyed cache handle");
+    const Plan &p = c->plan;
+    if (p.unfused) return fail(LF_ERR_UNSUPPORTED, "the unfused comparison path has no prompt compression");
+    if (p.flags & LF_FLAG_ATTENTION_ONLY) return fail(LF_ERR_UNSUPPORTED, "an attention-only cache takes no tokens");
+    if (!p.use_mfma) return fail(LF_ERR_UNSUPPORTED, "prompt compression needs bf16, head_dim 128 and the matrix-core kernels");
+    if (c->count != 0 || p.masked || c->stepped)
+        return fail(LF_ERR_STATE, "prompt compression starts from an empty cache (this one holds %d rows)", c->count);
+    if (c->groups > 0) return fail(LF_ERR_STATE, "cache is a member of a live group");
+    if (!q_window || !k_prompt || !v_prompt) return fail(LF_ERR_INVALID_ARG, "q_window/k_prompt/v_prompt is NULL");
+    if (((uintptr_t)q_window & 15u) || ((uintptr_t)k_prompt & 15u) || ((uintptr_t)v_prompt & 15u))
+        return fail(LF_ERR_INVALID_ARG, "q_window/k_prompt/v_prompt must be 16-byte aligned");
+    if (T < 1 || T > (1 << 24)) return fail(LF_ERR_INVALID_ARG, "T = %d outside [1, 2^24]", T);
+    if (W < 1 || keep < W || keep > T) return fail(LF_ERR_INVALID_ARG, "need 1 <= W <= keep <= T (W %d, keep %d, T %d)", W, keep, T);
+    if (keep > p.N) return fail(LF_ERR_INVALID_ARG, "keep %d exceeds the budget %d", keep, p.N);
+    if (pool < 1 || !(pool & 1) || pool > 1023) return fail(LF_ERR_INVALID_ARG, "pool %d is not an odd number in [1, 1023]", pool);
+    if ((long long)W * p.G > 4096) return fail(LF_ERR_UNSUPPORTED, "window %d x group %d: more than 4096 query columns", W, p.G);
+    if ((long long)p.units * T >= (1ll << 31) / 16) // grids of one 16-lane row per element stay valid launches
+        return fail(LF_ERR_UNSUPPORTED, "batch*kv_heads*T >= 2^27");
+    const CompressLayout l = compress_layout(p.units, p.G, T, W, p.N);
+    if (!scratch || ((uintptr_t)scratch & 255u)) return fail(LF_ERR_INVALID_ARG, "scratch is NULL or not 256-byte aligned");
+    if (scratch_bytes < l.total) return fail(LF_ERR_WORKSPACE, "scratch has %zu bytes, %zu needed", scratch_bytes, l.total);
+    hipStream_t s = (hipStream_t)hip_stream;
+    hipError_t e = launch_compress_prompt(p, T, W, keep, pool, q_window, k_prompt, v_prompt, scratch, s);
+    if (e != hipSuccess) return fail(LF_ERR_HIP, "prompt compression launch: %s", hipGetErrorString(e));
+    if (pooled && T > W) {
+        e = hipMemcpyAsync(pooled, (char *)scratch + l.off_pooled, sizeof(float) * (size_t)p.units * (T - W), hipMemcpyDeviceToDevice, s);
+        if (e != hipSuccess) return fail(LF_ERR_HIP, "pooled votes copy: %s", hipGetErrorString(e));
+    }
+    if (kept) {
+        e = hipMemcpyAsync(kept, (char *)scratch + l.off_kept, sizeof(int32_t) * (size_t)p.units * keep, hipMemcpyDeviceToDevice, s);
+        if (e != hipSuccess) return fail(LF_ERR_HIP, "kept rows copy: %s", hipGetErrorString(e));
+    }
+    c->count = keep;
+    c->has_pending = keep < p.N;
+    if (c->has_pending) {
+        e = launch_fill_i32(p.pending, p.units, keep, s);
+        if (e != hipSuccess) return fail(LF_ERR_HIP, "pending init: %s", hipGetErrorString(e));
+    }
+    return LF_OK;
+}
+
 int longflow_scores(longflow_cache_t *cache, float *scores, void *hip_stream)
 {
     longflow_cache *c = checked(cache);

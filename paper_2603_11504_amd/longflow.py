@@ -25,7 +25,7 @@ LF_FLAG_MAX_FREE = 32
 LF_EVICT_STATIC_MAX_SLOTS = 1 << 20
 
 EXPORTS = ("longflow_workspace_bytes", "longflow_workspace_regions", "longflow_init_cache", "longflow_decode_step",
-           "longflow_fill_steps", "longflow_scores", "longflow_set_pending", "longflow_set_mask", "longflow_get_mask", "longflow_evict_scratch_bytes",
+           "longflow_fill_steps", "longflow_compress_scratch_bytes", "longflow_compress_prompt", "longflow_scores", "longflow_set_pending", "longflow_set_mask", "longflow_get_mask", "longflow_evict_scratch_bytes",
            "longflow_evict_lowest", "longflow_evict_lowest_static", "longflow_valid_count",
            "longflow_destroy_cache", "longflow_last_error", "longflow_profile_begin",
            "longflow_profile_end", "longflow_plan_info", "longflow_group_workspace_bytes", "longflow_group_create",
@@ -81,6 +81,10 @@ def lib():
         L.longflow_decode_step.restype = ctypes.c_int
         L.longflow_fill_steps.argtypes = [vp, i32, vp, vp, vp, vp, vp, vp]
         L.longflow_fill_steps.restype = ctypes.c_int
+        L.longflow_compress_scratch_bytes.argtypes = [ctypes.POINTER(lf_config), i32, i32]
+        L.longflow_compress_scratch_bytes.restype = ctypes.c_size_t
+        L.longflow_compress_prompt.argtypes = [vp, i32, i32, i32, i32, vp, vp, vp, vp, ctypes.c_size_t, vp, vp, vp]
+        L.longflow_compress_prompt.restype = ctypes.c_int
         L.longflow_scores.argtypes = [vp, vp, vp]
         L.longflow_scores.restype = ctypes.c_int
         L.longflow_set_pending.argtypes = [vp, vp, vp]
@@ -222,6 +226,22 @@ class LongFlowCache:
                                          _arg(v_new, T * self._nkv, dt, "v_new"), _arg(out, T * self._nq, dt, "out"),
                                          _arg(evict_idx, self._nu, torch.int32, "evict_idx"), _stream()))
         return out, evict_idx
+
+    def compress_prompt(self, q_window, k_prompt, v_prompt, keep, pool=1, want_pooled=True):
+        """A prompt longer than the budget into an empty cache: q_window [W,B,Hq,D], k_prompt, v_prompt
+        [B,Hkv,T,D] (contiguous) -> (pooled votes [B,Hkv,T-W] float32 or None, kept rows [B,Hkv,keep] int32)."""
+        W, T = int(q_window.shape[0]), int(k_prompt.shape[2])
+        cfg, dt = self.cfg, self.dtype
+        nbytes = int(lib().longflow_compress_scratch_bytes(ctypes.byref(cfg), T, W))
+        scratch = torch.empty(max(nbytes, 1), dtype=torch.uint8, device=self.device)
+        pooled = torch.empty((cfg.batch, cfg.kv_heads, T - W), dtype=torch.float32, device=self.device) if want_pooled else None
+        kept = torch.empty((cfg.batch, cfg.kv_heads, keep), dtype=torch.int32, device=self.device)
+        _check(lib().longflow_compress_prompt(self._h, T, W, int(keep), int(pool), _arg(q_window, W * self._nq, dt, "q_window"),
+                                              _arg(k_prompt, self._nu * T * cfg.head_dim, dt, "k_prompt"),
+                                              _arg(v_prompt, self._nu * T * cfg.head_dim, dt, "v_prompt"),
+                                              _ptr(scratch), nbytes, _ptr(pooled), _ptr(kept), _stream()))
+        self._keep_scratch = scratch  # alive until the kernels that use it have run
+        return pooled, kept
 
     def scores(self):
         s = torch.empty((self.cfg.batch, self.cfg.kv_heads, self.cfg.budget), dtype=torch.float32,

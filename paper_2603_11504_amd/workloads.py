@@ -210,3 +210,21 @@ def device_step(wl: Workload, t: int, device, layer: int = 0):
     if wl.n_init == 0 and t == 0:
         k = k * wl.sink_scale
     return q.to(dt), k.to(dt), v.to(dt)
+
+
+def device_prompt(wl: Workload, T: int, W: int, device, layer: int = 0):
+    """A prompt of T tokens in the workload's input structure, drawn on `device` in the storage
+    dtype: (q_window [W,B,Hq,D], the queries of the last W tokens; K, V [B,Hkv,T,D])."""
+    import torch
+    dt = torch_dtype(wl)
+    g = _torch_gen(wl, 4, layer, T, device)
+    scale = torch.from_numpy(key_channel_scale(wl, layer)).to(device)[:, None, :]
+    k = torch.empty((wl.batch, wl.kv_heads, T, wl.head_dim), dtype=dt, device=device)
+    v = torch.empty_like(k)
+    for b in range(wl.batch):
+        kb = torch.randn((wl.kv_heads, T, wl.head_dim), generator=g, device=device, dtype=torch.float32) * scale
+        kb[:, 0, :] *= wl.sink_scale
+        k[b] = kb.to(dt)
+        v[b] = torch.randn((wl.kv_heads, T, wl.head_dim), generator=g, device=device, dtype=torch.float32).to(dt)
+    q = torch.randn((W, wl.batch, wl.q_heads, wl.head_dim), generator=g, device=device, dtype=torch.float32).to(dt)
+    return q, k, v
