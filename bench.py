@@ -44,7 +44,7 @@ def parse():
     ap.add_argument("--steps", type=int, default=None)
     ap.add_argument("--warmup", type=int, default=3)
     ap.add_argument("--workload", default="cfg3", help="cfg0..cfg4 (BASELINE.json configs)")
-    ap.add_argument("--valu", action="store_true", help="bf16: vector-ALU kernel instead of matrix cores")
+    ap.add_argument("--valu", action="store_true", help="vector-ALU kernel instead of matrix cores")
     ap.add_argument("--split", action="store_true", help="force the split-K path")
     ap.add_argument("--unit", action="store_true", help="force the one-workgroup-per-unit fused path")
     ap.add_argument("--unfused", action="store_true",
@@ -282,6 +282,7 @@ def measure(wl, flags, steps, warmup, pool=0, with_cpu=False, calibrate_copy=Fal
 
 KERNEL_PATHS = {"unit_mfma_kernel": "fused one-launch, matrix cores",
                 "split_mfma_kernel": "split-K, matrix cores",
+                "split_mfma32_kernel": "split-K, matrix cores in fp32",
                 "split_valu_kernel": "split-K, vector ALU"}
 
 
@@ -443,6 +444,11 @@ def report(a):
     rows.append((W.scaled(fig1, name=fig1.name + "_unfused"), UNF, 100))
     for i in (2, 3, 4):
         rows.append((W.scaled(W.CONFIGS[i], name=W.CONFIGS[i].name + "_unfused"), UNF, DEFAULT_STEPS[i]))
+    # fp32 caches: the matrix-core kernel in fp32 arithmetic against its vector-ALU twin
+    for nm, B, Hq, N, st in (("f32_b64_8x4_d128_n4096", 64, 8, 4096, 50), ("f32_b128_28x4_d128_n8192", 128, 28, 8192, 20)):
+        wl32 = W.Workload(nm, "f32", B, Hq, 4, 128, N, N - 1, st, sink_scale=4.0, seed=W.BASE_SEED + 7)
+        rows.append((wl32, 0, st))
+        rows.append((W.scaled(wl32, name=nm + "_vector_alu"), lf.LF_FLAG_FORCE_VALU, st))
     # the small workloads again as 28 independent caches, for the one-launch-per-step column
     for i in range(3):
         rows.append((W.scaled(W.CONFIGS[i], name=W.CONFIGS[i].name + "_x28", layers=28), 0, DEFAULT_STEPS[i]))
@@ -483,7 +489,7 @@ def main():
     idx = int(a.workload.replace("cfg", ""))
     wl = W.CONFIGS[idx]
     steps = a.steps if a.steps is not None else DEFAULT_STEPS[idx]
-    flags = lf.LF_FLAG_FORCE_VALU if (a.valu and wl.dtype == "bf16") else 0
+    flags = lf.LF_FLAG_FORCE_VALU if a.valu else 0
     flags |= lf.LF_FLAG_FORCE_SPLIT if a.split else 0
     flags |= lf.LF_FLAG_FORCE_UNIT if a.unit else 0
     flags |= lf.LF_FLAG_UNFUSED_ACCUM if a.unfused else 0

@@ -72,8 +72,8 @@ typedef enum { LF_F32 = 0, LF_BF16 = 1 } lf_dtype;
 /* flags */
 #define LF_FLAG_ATTENTION_ONLY 1u /* plain decode attention: no insert, score or eviction
                                      (the uncompressed comparison of Sec. 4.4)            */
-#define LF_FLAG_FORCE_VALU 2u     /* bf16 only: use the vector-ALU kernel instead of the
-                                     matrix-core kernel (for A/B measurement)              */
+#define LF_FLAG_FORCE_VALU 2u     /* use the vector-ALU kernel instead of a matrix-core
+                                     kernel (for A/B measurement)                          */
 #define LF_FLAG_FORCE_SPLIT 4u    /* always split a unit over several workgroups              */
 #define LF_FLAG_FORCE_UNIT 8u     /* always one workgroup per unit, one fused launch; needs the
                                      matrix-core path and budget * group <= ~120k            */
@@ -92,18 +92,22 @@ typedef enum { LF_F32 = 0, LF_BF16 = 1 } lf_dtype;
                                      the accumulated weights; masks, batch eviction and groups
                                      are LF_ERR_UNSUPPORTED.                                  */
 
-#define LF_FLAG_MAX_FREE 32u      /* with LF_FLAG_ATTENTION_ONLY, bf16 / head_dim 128, fused kernel:
-                                     the softmax exactly as Alg. 1 prints it (Sec. 3.4,
-                                     modification 2) -- no running reference, p = exp(s) in
-                                     fp32, normalised at the end.  Same value while every
-                                     |s| stays below ~88; non-finite output beyond.  For A/B
-                                     measurement against the default, which keeps a reference. */
+#define LF_FLAG_MAX_FREE 32u      /* bf16 / head_dim 128, fused kernel: the softmax exactly as Alg. 1
+                                     prints it (Sec. 3.4, modification 2) -- no running reference,
+                                     p = exp(s) in fp32, normalised at the end -- in the evicting step
+                                     or, with LF_FLAG_ATTENTION_ONLY, in plain attention.  Same values
+                                     while every |s| stays below ~88; non-finite output beyond.  The
+                                     eviction decision stays exact (its screening bounds turn one-sided
+                                     where a slot's ||v||_1 exp(s) leaves [2^-48, 2^16], which only costs
+                                     time).  For A/B measurement against the default, which keeps a
+                                     reference.  Such a cache takes no mask, batch eviction or group, and
+                                     longflow_fill_steps feeds it token by token.                      */
 
 typedef struct {
     int32_t batch;    /* B   >= 1                                            */
-    int32_t q_heads;  /* Hq, a multiple of kv_heads.  Hq/Hkv <= 16 for bf16 with head_dim 128
-                         (matrix-core kernels); <= 8 for fp32, for head_dim 64 and with
-                         LF_FLAG_FORCE_VALU (vector-ALU kernel): LF_ERR_UNSUPPORTED beyond */
+    int32_t q_heads;  /* Hq, a multiple of kv_heads.  Hq/Hkv <= 16 (matrix-core kernels);
+                         <= 8 with LF_FLAG_FORCE_VALU (vector-ALU kernel):
+                         LF_ERR_UNSUPPORTED beyond */
     int32_t kv_heads; /* Hkv >= 1                                            */
     int32_t head_dim; /* D: 64 or 128                                        */
     int32_t budget;   /* N: slots of the static cache, 1 <= N <= 2^24        */
@@ -307,9 +311,12 @@ LF_API int longflow_destroy_cache(longflow_cache_t *cache);
  * choice below is about filling the chip, not about the result.
  */
 typedef enum {
-    LF_PATH_SPLIT_VALU = 0, /* split-K, vector ALU (fp32, head_dim 64, LF_FLAG_FORCE_VALU)       */
-    LF_PATH_SPLIT_MFMA = 1, /* split-K, matrix cores (codes exceed LDS, LF_FLAG_FORCE_SPLIT)     */
-    LF_PATH_UNIT_MFMA = 2   /* fused kernel, 1..8 cooperating workgroups per (batch, KV head)    */
+    LF_PATH_SPLIT_VALU = 0, /* split-K, vector ALU (LF_FLAG_FORCE_VALU)                          */
+    LF_PATH_SPLIT_MFMA = 1, /* split-K, matrix cores, bf16 head_dim 128 (codes exceed LDS,
+                               LF_FLAG_FORCE_SPLIT)                                              */
+    LF_PATH_UNIT_MFMA = 2,  /* fused kernel, 1..8 cooperating workgroups per (batch, KV head)    */
+    LF_PATH_SPLIT_MFMA_F32 = 3 /* split-K, matrix cores in fp32 arithmetic (fp32 caches; bf16
+                               with head_dim 64)                                                 */
 } lf_path;
 typedef struct {
     int32_t path;                /* lf_path                                                        */

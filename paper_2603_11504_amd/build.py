@@ -9,7 +9,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "liblongflow.so")
 SOURCES = ["longflow_api.hip", "lf_split_valu.hip", "lf_split_mfma.hip", "lf_unit_mfma.hip",
-           "lf_finish.hip", "lf_unfused.hip", "lf_fill.hip", "lf_compress.hip"]
+           "lf_finish.hip", "lf_unfused.hip", "lf_fill.hip", "lf_compress.hip", "lf_split_mfma32.hip"]
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-fvisibility=hidden",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops"]
 

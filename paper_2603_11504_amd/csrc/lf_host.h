@@ -21,11 +21,12 @@ struct Plan {
     int C;             // number of splits covering N
     int ntiles;        // ceil(N / kTile)
     bool use_mfma;     // bf16, head_dim 128: matrix-core kernels
+    bool use_mfma32;   // fp32, or bf16 with head_dim 64: split-K kernel on the matrix cores in fp32 arithmetic
     bool use_unit;     // unit-resident fused kernel: whole step in one launch
     int unit_S;        // ... with this many cooperating workgroups per unit
     bool masked;       // an explicit validity mask is in force (state, set by longflow_set_mask)
     bool unfused;      // comparison path: plain attention kernel, then separate importance kernels
-    bool max_free;     // attention only: softmax without a running reference (A/B measurement)
+    bool max_free;     // softmax without a running reference, as Alg. 1 prints it (A/B measurement)
     // device pointers (caller-owned)
     void *k_cache, *v_cache;
     // carved out of the caller's workspace
@@ -74,6 +75,8 @@ hipError_t launch_split_valu(const Plan &p, const StepIo &io, int n, hipStream_t
                              int n_caches = 1);
 hipError_t launch_split_mfma(const Plan &p, const StepIo &io, int n, hipStream_t s, const void *table = nullptr,
                              int n_caches = 1);
+hipError_t launch_split_mfma32(const Plan &p, const StepIo &io, int n, hipStream_t s, const void *table = nullptr,
+                               int n_caches = 1);
 size_t split_table_entry_bytes();
 void split_table_entry(const Plan &p, void *dst);
 int unit_mfma_splits(int units, int N);

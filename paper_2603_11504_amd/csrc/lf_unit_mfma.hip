@@ -227,7 +227,7 @@ __device__ bool fill_lowest_hole(g_cf32p lu_u, int npos, int N, int ins_slot, in
     return red[0] != 0x7fffffff;
 }
 
-// Screening.  A code c stands for 2^(kCodeBias - c/4), read from a 256-entry table in LDS.
+// Screening.  A code c stands for 2^(kCodeBias - c/4).
 // For a code that sits at no clamp the true term t and its decoded value d obey
 //   d 2^(-1/8) <= t <= d 2^(1/8)
 // (rounding of the code: half a step of 1/4 either way).  Sums over the heads inherit the
@@ -236,7 +236,9 @@ __device__ bool fill_lowest_hole(g_cf32p lu_u, int npos, int N, int ins_slot, in
 constexpr float kScreenWindow = 1.189208f * 1.0002f;
 
 // COOP: several workgroups may share a unit (s_active can exceed 1)
-// MAXFREE (attention only): softmax without a running reference, for A/B measurement
+// MAXFREE: softmax without a running reference (Alg. 1 as printed), for A/B measurement; the codes are then
+// relative to the fixed reference 0 and clamp (one-sided bounds, still rigorous) once ||v||_1 2^t leaves
+// [2^-48, 2^16]
 // (Every lambda below is marked always_inline: a real call would make the compiler keep the
 // kernel's arguments, which the lambdas capture by reference, in private memory, and a load from
 // there waits for every outstanding store -- which serialises the device-scope stores.)
@@ -268,7 +270,8 @@ __global__ __launch_bounds__(512, 1) void unit_mfma_kernel(const UnitArgs a_in, 
     uint8_t *ls_code = smem;
     float *ls_ref = (float *)(smem + (size_t)a.G * a.code_stride);
     float *sm_o = (float *)(smem + a.merge_off);
-    __shared__ float sm_m[NW][16], sm_l[NW][16], sM[16], sL[16], sInvL[16];
+    __shared__ float sm_m[NW][16], sm_l[NW][16], sM[16], sL[16];
+    __shared__ float sLg[16]; // kCodeBias - reference - log2 denominator per head: what turns a tile's reference into the log2 factor of its codes
     __shared__ float sW[8][16]; // weights of the S partials under the unit-wide reference
     __shared__ float red_f[NW];
     __shared__ double best_v[NW];
@@ -277,7 +280,6 @@ __global__ __launch_bounds__(512, 1) void unit_mfma_kernel(const UnitArgs a_in, 
     __shared__ int cand_list[kMaxCand];
     __shared__ int cand_count, s_flag;
     __shared__ int red_i[NW + 1];
-    __shared__ float exp_tab[256]; // 2^(-c/4) of every code value (screening pass)
 
     const int n = a.n, N = a.N, G = a.G, s_active = COOP ? a.s_active : 1;
     const int u = blk / s_active, sp = blk % s_active;
@@ -329,7 +331,6 @@ __global__ __launch_bounds__(512, 1) void unit_mfma_kernel(const UnitArgs a_in, 
     // instead of standing in the serial tail of the kernel.
     if (STASH == kStashLds) {
         for (int i = tid; i < G * D; i += 512) qs[i / D][i % D] = qu[i];
-        if (tid < 256) exp_tab[tid] = fast_exp2(-0.25f * (float)tid);
     }
     if (sp == 0)
         for (int i = tid; i < G * D; i += 512) q_last[(size_t)u * G * D + i] = qu[i];
@@ -364,7 +365,7 @@ __global__ __launch_bounds__(512, 1) void unit_mfma_kernel(const UnitArgs a_in, 
         for (int w = 0; w < NW; ++w) Ls += merge_weight(sm_m[w][tid], M) * sm_l[w][tid];
         sM[tid] = M; // this workgroup's reference and denominator
         sL[tid] = Ls;
-        sInvL[tid] = 1.f / Ls;
+        sLg[tid] = kCodeBias - M - __builtin_amdgcn_logf(Ls);
     }
     __syncthreads();
 
@@ -481,9 +482,12 @@ __global__ __launch_bounds__(512, 1) void unit_mfma_kernel(const UnitArgs a_in, 
                 if (i0 / 2 + k * 512 + tid < nr) rem_ref[roff[k]] = rv[k];
         }
     };
-    // per (tile, head): the factor that turns a decoded code into a term of the score, from the
-    // tile's reference as the streaming left it
-    auto ref_factor = [&](float ref, int h) __attribute__((always_inline)) { return fast_exp2(kCodeBias + ref - sM[h]) * sInvL[h]; };
+    // A code c of head h in a tile whose reference the streaming left at `ref` stands for the term
+    // 2^(ref + sLg[h] - c/4) of the score: one conversion, one multiply-add and one exponential per
+    // code, no table (a 256-entry table in LDS cost more in bank conflicts than the exponentials do).
+    auto code_term = [&](uint32_t c4, int e, float lf) __attribute__((always_inline)) {
+        return fast_exp2(fmaf((float)((c4 >> (8 * e)) & 255u), -0.25f, lf));
+    };
 
     if (coop) {
         // ---- publish this workgroup's partial (m, l, O), and its codes if slots will be scored
@@ -545,7 +549,7 @@ __global__ __launch_bounds__(512, 1) void unit_mfma_kernel(const UnitArgs a_in, 
             }
             sM[tid] = M;
             sL[tid] = Ls;
-            sInvL[tid] = 1.f / Ls;
+            sLg[tid] = kCodeBias - M - __builtin_amdgcn_logf(Ls);
         }
         __syncthreads();
     } else if (o_separate && STASH == kStashLds) {
@@ -610,10 +614,10 @@ __global__ __launch_bounds__(512, 1) void unit_mfma_kernel(const UnitArgs a_in, 
                 float s4[4] = {0.f, 0.f, 0.f, 0.f};
                 for (int h = 0; h < G; ++h) {
                     const uint32_t c4 = *(const uint32_t *)(cp + (size_t)h * cstride);
-                    const float f = ref_factor(fp[h], h);
+                    const float lf = fp[h] + sLg[h];
                     clamped |= ((c4 - 0x01010101u) & ~c4) | ((~c4 - 0x01010101u) & c4);
 #pragma unroll
-                    for (int e = 0; e < 4; ++e) s4[e] = fmaf(exp_tab[(c4 >> (8 * e)) & 255u], f, s4[e]);
+                    for (int e = 0; e < 4; ++e) s4[e] += code_term(c4, e, lf);
                 }
 #pragma unroll
                 for (int e = 0; e < 4; ++e) ub4[e] = lb4[e] = s4[e];
@@ -622,11 +626,11 @@ __global__ __launch_bounds__(512, 1) void unit_mfma_kernel(const UnitArgs a_in, 
                     for (int e = 0; e < 4; ++e) ub4[e] = lb4[e] = 0.f;
                     for (int h = 0; h < G; ++h) {
                         const uint32_t c4 = *(const uint32_t *)(cp + (size_t)h * cstride);
-                        const float f = ref_factor(fp[h], h);
+                        const float lf = fp[h] + sLg[h];
 #pragma unroll
                         for (int e = 0; e < 4; ++e) {
                             const uint32_t c = (c4 >> (8 * e)) & 255u;
-                            const float d = exp_tab[c] * f;
+                            const float d = code_term(c4, e, lf);
                             ub4[e] += (c == 0u) ? INFINITY : d;
                             lb4[e] += (c == 255u) ? 0.f : d;
                         }
@@ -696,7 +700,7 @@ __global__ __launch_bounds__(512, 1) void unit_mfma_kernel(const UnitArgs a_in, 
                     for (int h = 0; h < G; ++h) {
                         uint32_t c4[NI];
                         float f[NI];
-                        const float mh = kCodeBias - sM[h], il = sInvL[h];
+                        const float lgh = sLg[h];
 #pragma unroll
                         for (int it = 0; it < NI; ++it) {
                             c4[it] = *(const uint32_t *)(smem + cp[it]);
@@ -706,11 +710,10 @@ __global__ __launch_bounds__(512, 1) void unit_mfma_kernel(const UnitArgs a_in, 
                         }
 #pragma unroll
                         for (int it = 0; it < NI; ++it) {
-                            f[it] = fast_exp2(f[it] + mh) * il;
+                            f[it] += lgh;
                             clamped[it] |= ((c4[it] - 0x01010101u) & ~c4[it]) | ((~c4[it] - 0x01010101u) & c4[it]);
 #pragma unroll
-                            for (int e = 0; e < 4; ++e)
-                                s4[it][e] = fmaf(exp_tab[(c4[it] >> (8 * e)) & 255u], f[it], s4[it][e]);
+                            for (int e = 0; e < 4; ++e) s4[it][e] += code_term(c4[it], e, f[it]);
                         }
                     }
 #pragma unroll
@@ -770,31 +773,33 @@ __global__ __launch_bounds__(512, 1) void unit_mfma_kernel(const UnitArgs a_in, 
                 bi = cand_list[0]; // nothing to compare with: the screening already decided
                 bv = 0.0;
             } else if (ncand <= kMaxCand) {
-                // This wave's first two candidates' rows are requested, then the output is stored
-                // (if this workgroup owes it and has it staged), then the rows are used: up to 16
-                // candidates cost one trip to memory, and the output's stores hide behind it.
-                RowRegs r0, r1;
-                const int c0 = wave, c1 = wave + NW;
-                if (c0 < ncand) {
-                    const int cs = cand_list[c0];
-                    load_row(r0, Ku + (size_t)cs * D, Vu + (size_t)cs * D, lane, coop && cs == ins_slot);
-                }
-                if (c1 < ncand) {
-                    const int cs = cand_list[c1];
-                    load_row(r1, Ku + (size_t)cs * D, Vu + (size_t)cs * D, lane, coop && cs == ins_slot);
-                }
-                if (coop) { merge_out(); out_stored = true; }
-                else if (o_separate) { store_out(); out_stored = true; }
+                // A wave takes its candidates two at a time: both rows are requested, then (first round
+                // only) the output is stored if this workgroup owes it and has it staged, then the rows
+                // are used -- 16 candidates cost the workgroup one trip to memory, and the output's
+                // stores hide behind the first.
                 auto take = [&](double v, int cs) __attribute__((always_inline)) {
                     if (v < bv || (v == bv && cs < bi)) { bv = v; bi = cs; }
                 };
-                if (c0 < ncand) take(__shfl(score_row(r0, qs, G, sM, sL, lane), 0), cand_list[c0]);
-                if (c1 < ncand) take(__shfl(score_row(r1, qs, G, sM, sL, lane), 0), cand_list[c1]);
-                for (int c = wave + 2 * NW; c < ncand; c += NW) {
-                    const int cs = cand_list[c];
-                    if (bv == 0.0 && cs > bi) continue; // behind an exact zero nothing can win
-                    take(__shfl(exact_score_bf16(Ku + (size_t)cs * D, Vu + (size_t)cs * D, qs, G, sM, sL, lane,
-                                                 coop && cs == ins_slot), 0), cs);
+                for (int cb = 0; cb < ncand; cb += 2 * NW) { // uniform over the workgroup
+                    RowRegs r0, r1;
+                    const int c0 = cb + wave, c1 = cb + wave + NW;
+                    // behind an exact zero nothing can win: such candidates are not even fetched
+                    const bool use0 = c0 < ncand && !(bv == 0.0 && cand_list[c0] > bi);
+                    const bool use1 = c1 < ncand && !(bv == 0.0 && cand_list[c1] > bi);
+                    if (use0) {
+                        const int cs = cand_list[c0];
+                        load_row(r0, Ku + (size_t)cs * D, Vu + (size_t)cs * D, lane, coop && cs == ins_slot);
+                    }
+                    if (use1) {
+                        const int cs = cand_list[c1];
+                        load_row(r1, Ku + (size_t)cs * D, Vu + (size_t)cs * D, lane, coop && cs == ins_slot);
+                    }
+                    if (cb == 0) {
+                        if (coop) { merge_out(); out_stored = true; }
+                        else if (o_separate) { store_out(); out_stored = true; }
+                    }
+                    if (use0) take(__shfl(score_row(r0, qs, G, sM, sL, lane), 0), cand_list[c0]);
+                    if (use1) take(__shfl(score_row(r1, qs, G, sM, sL, lane), 0), cand_list[c1]);
                 }
             } else {
                 // Far more candidates than the list holds: scores underflowing en masse, or many
@@ -928,7 +933,7 @@ struct UnitLaunch {
     const UnitArgs *a;
     const GroupArgs *ga;
 };
-constexpr int kUnitInstances = 14;
+constexpr int kUnitInstances = 16;
 
 template <int STASH, bool COOP, bool GROUPED, bool MASKED, bool MAXFREE>
 static hipError_t launch_instance(const UnitLaunch &ul, int idx)
@@ -1015,8 +1020,11 @@ static hipError_t launch_unit(const Plan &p, const StepIo &io, int n, const void
     if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) return hipErrorInvalidDevice;
     const UnitLaunch ul = {attr_done_all[dev], wgs, lds, s, &a, &ga};
     const bool coop = S > 1, grouped = table != nullptr;
-    if (p.max_free) { // attention only, one cache (the API layer admits nothing else)
-        if (table || stash) return hipErrorInvalidValue;
+    if (p.max_free) { // one cache, no mask (the API layer admits nothing else)
+        if (table || p.masked) return hipErrorInvalidValue;
+        if (stash)
+            return coop ? launch_instance<kStashLds, true, false, false, true>(ul, 14)
+                        : launch_instance<kStashLds, false, false, false, true>(ul, 15);
         return coop ? launch_instance<kStashNone, true, false, false, true>(ul, 12)
                     : launch_instance<kStashNone, false, false, false, true>(ul, 13);
     }

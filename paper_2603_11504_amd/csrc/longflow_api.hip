@@ -62,8 +62,8 @@ static int validate(const lf_config *cfg)
     const int G = cfg->q_heads / cfg->kv_heads;
     if (G > kMaxGroup) return fail(LF_ERR_UNSUPPORTED, "group size %d > %d", G, kMaxGroup);
     const bool mfma = cfg->dtype == LF_BF16 && cfg->head_dim == 128 && !(cfg->flags & LF_FLAG_FORCE_VALU);
-    if (!mfma && G > 8)
-        return fail(LF_ERR_UNSUPPORTED, "group size %d > 8 needs bf16, head_dim 128 and the matrix-core kernel", G);
+    if ((cfg->flags & LF_FLAG_FORCE_VALU) && G > 8)
+        return fail(LF_ERR_UNSUPPORTED, "group size %d > 8 needs a matrix-core kernel (drop FORCE_VALU)", G);
     if ((long long)cfg->batch * cfg->kv_heads > (1ll << 20))
         return fail(LF_ERR_UNSUPPORTED, "batch*kv_heads > 2^20");
     if ((cfg->flags & LF_FLAG_FORCE_SPLIT) && (cfg->flags & LF_FLAG_FORCE_UNIT))
@@ -76,8 +76,7 @@ static int validate(const lf_config *cfg)
             return fail(LF_ERR_UNSUPPORTED, "UNFUSED_ACCUM: batch*kv_heads*budget >= 2^31");
     }
     if (cfg->flags & LF_FLAG_MAX_FREE) {
-        if (!(cfg->flags & LF_FLAG_ATTENTION_ONLY))
-            return fail(LF_ERR_INVALID_ARG, "MAX_FREE is an attention-only variant: combine it with ATTENTION_ONLY");
+        if (cfg->flags & LF_FLAG_UNFUSED_ACCUM) return fail(LF_ERR_INVALID_ARG, "MAX_FREE and UNFUSED_ACCUM exclude each other");
         if (!mfma || (cfg->flags & LF_FLAG_FORCE_SPLIT))
             return fail(LF_ERR_UNSUPPORTED, "MAX_FREE needs bf16, head_dim 128 and the fused matrix-core kernel");
     }
@@ -102,6 +101,7 @@ static void fill_plan(const lf_config *cfg, Plan *p)
     choose_splits(p->units, p->N, &p->L, &p->C);
     p->ntiles = (p->N + kTile - 1) / kTile;
     p->use_mfma = cfg->dtype == LF_BF16 && cfg->head_dim == 128 && !(cfg->flags & LF_FLAG_FORCE_VALU);
+    p->use_mfma32 = !p->use_mfma && !(cfg->flags & LF_FLAG_FORCE_VALU);
     // unit-resident kernel: as many cooperating workgroups per unit as it takes to fill the
     // chip, more if one workgroup's share of the codes would not fit its LDS
     const bool stash = !(p->flags & LF_FLAG_ATTENTION_ONLY);
@@ -229,6 +229,8 @@ int longflow_init_cache(longflow_cache_t **out, const lf_config *cfg, void *k_ca
         return fail(LF_ERR_INVALID_ARG, "workspace must be 256-byte, caches 16-byte aligned");
     Plan p;
     fill_plan(cfg, &p);
+    if (p.max_free && !p.use_unit)
+        return fail(LF_ERR_UNSUPPORTED, "MAX_FREE: budget %d x group %d does not fit the fused kernel's LDS", p.N, p.G);
     const Layout l = layout_of(p);
     if (workspace_bytes < l.total)
         return fail(LF_ERR_WORKSPACE, "workspace has %zu bytes, %zu needed", workspace_bytes, l.total);
@@ -329,7 +331,7 @@ int longflow_decode_step(longflow_cache_t *cache, const void *q, const void *k_n
         e = launch_unit_mfma(p, q, k_new, v_new, n, out, evict_idx, s);
     } else {
         const StepIo io = {q, k_new, v_new, out, evict_idx};
-        e = p.use_mfma ? launch_split_mfma(p, io, n, s) : launch_split_valu(p, io, n, s);
+        e = p.use_mfma ? launch_split_mfma(p, io, n, s) : p.use_mfma32 ? launch_split_mfma32(p, io, n, s) : launch_split_valu(p, io, n, s);
     }
     if (e != hipSuccess) return fail(LF_ERR_HIP, "decode launch: %s", hipGetErrorString(e));
     if (ev) (void)hipEventRecord(ev[1], s);
@@ -362,7 +364,8 @@ int longflow_fill_steps(longflow_cache_t *cache, int32_t T, const void *q, const
     const int room = p.masked ? 0 : p.N - c->count;
     const int Tfill = std::min<int>(T, room);
     int Tb = 0;
-    if (p.use_mfma && Tfill - 1 >= fill_tokens_per_pass(p.G)) {
+    // (the batched kernel keeps a softmax reference: a max-free cache takes its tokens as single steps)
+    if (p.use_mfma && !p.max_free && Tfill - 1 >= fill_tokens_per_pass(p.G)) {
         Tb = Tfill - 1;
         // one workgroup per (unit, group of tokens): keep each launch's grid below 2^30 workgroups
         const long long per_launch = std::max(1ll, (1ll << 30) / p.units) * fill_tokens_per_pass(p.G);
@@ -491,7 +494,7 @@ int longflow_plan_info(const lf_config *cfg, lf_plan_info *info)
         info->threads_per_workgroup = 512;
         info->lds_bytes = (uint32_t)unit_mfma_lds_bytes(p.N, p.G, !(p.flags & LF_FLAG_ATTENTION_ONLY), p.unit_S);
     } else {
-        info->path = p.use_mfma ? LF_PATH_SPLIT_MFMA : LF_PATH_SPLIT_VALU;
+        info->path = p.use_mfma ? LF_PATH_SPLIT_MFMA : p.use_mfma32 ? LF_PATH_SPLIT_MFMA_F32 : LF_PATH_SPLIT_VALU;
         info->workgroups_per_unit = (p.N + p.L - 1) / p.L;
         info->slots_per_workgroup = p.L;
         info->launches_per_step =
@@ -595,6 +598,7 @@ int longflow_group_decode_step(longflow_group_t *group, const void *q, const voi
     hipError_t e;
     if (p.use_unit) e = launch_unit_mfma_group(p, io, n, group->table, nc, s);
     else if (p.use_mfma) e = launch_split_mfma(p, io, n, s, group->table, nc);
+    else if (p.use_mfma32) e = launch_split_mfma32(p, io, n, s, group->table, nc);
     else e = launch_split_valu(p, io, n, s, group->table, nc);
     if (e != hipSuccess) return fail(LF_ERR_HIP, "group decode launch: %s", hipGetErrorString(e));
     for (longflow_cache *c : group->members) {
@@ -621,6 +625,7 @@ int longflow_set_mask(longflow_cache_t *cache, const uint8_t *mask, void *hip_st
     if (c->plan.unfused) return fail(LF_ERR_UNSUPPORTED, "the unfused comparison path takes no mask");
     if (c->plan.flags & LF_FLAG_ATTENTION_ONLY)
         return fail(LF_ERR_UNSUPPORTED, "an attention-only cache takes no mask");
+    if (c->plan.max_free) return fail(LF_ERR_UNSUPPORTED, "the max-free variant takes no mask");
     hipError_t e = launch_set_mask(c->plan, mask, (hipStream_t)hip_stream);
     if (e != hipSuccess) return fail(LF_ERR_HIP, "mask launch: %s", hipGetErrorString(e));
     c->plan.masked = true;
@@ -652,6 +657,7 @@ int longflow_evict_lowest(longflow_cache_t *cache, int32_t k, void *scratch, siz
     const Plan &p = c->plan;
     if (p.unfused) return fail(LF_ERR_UNSUPPORTED, "the unfused comparison path evicts one slot per step only");
     if (p.flags & LF_FLAG_ATTENTION_ONLY) return fail(LF_ERR_UNSUPPORTED, "an attention-only cache evicts nothing");
+    if (p.max_free) return fail(LF_ERR_UNSUPPORTED, "the max-free variant has no batch eviction (it takes no mask)");
     if (!c->stepped) return fail(LF_ERR_STATE, "no decode step has run yet: there are no scores");
     if (k < 1 || k >= p.N) return fail(LF_ERR_INVALID_ARG, "k = %d outside [1, %d)", k, p.N);
     const size_t need = sizeof(double) * (size_t)p.units * p.N;
@@ -672,6 +678,7 @@ int longflow_evict_lowest_static(longflow_cache_t *cache, int32_t k, int32_t *ev
     const Plan &p = c->plan;
     if (p.unfused) return fail(LF_ERR_UNSUPPORTED, "the unfused comparison path evicts one slot per step only");
     if (p.flags & LF_FLAG_ATTENTION_ONLY) return fail(LF_ERR_UNSUPPORTED, "an attention-only cache evicts nothing");
+    if (p.max_free) return fail(LF_ERR_UNSUPPORTED, "the max-free variant has no batch eviction (it takes no mask)");
     if ((size_t)p.units * p.N > kStaticScoreSlots)
         return fail(LF_ERR_WORKSPACE, "batch*kv_heads*budget = %zu exceeds the %zu slots of the built-in scratch: "
                     "use longflow_evict_lowest with a scratch buffer of your own", (size_t)p.units * p.N, kStaticScoreSlots);

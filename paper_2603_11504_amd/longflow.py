@@ -48,8 +48,8 @@ class lf_region(ctypes.Structure):
     _fields_ = [("name", ctypes.c_char * 24), ("offset", ctypes.c_uint64), ("bytes", ctypes.c_uint64)]
 
 
-LF_PATH_SPLIT_VALU, LF_PATH_SPLIT_MFMA, LF_PATH_UNIT_MFMA = range(3)
-PATH_KERNELS = ("split_valu_kernel", "split_mfma_kernel", "unit_mfma_kernel")
+LF_PATH_SPLIT_VALU, LF_PATH_SPLIT_MFMA, LF_PATH_UNIT_MFMA, LF_PATH_SPLIT_MFMA_F32 = range(4)
+PATH_KERNELS = ("split_valu_kernel", "split_mfma_kernel", "unit_mfma_kernel", "split_mfma32_kernel")
 
 
 class LongFlowError(RuntimeError):

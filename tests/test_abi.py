@@ -31,12 +31,14 @@ def test_workspace_bytes_and_geometry_validation():
     assert lf.longflow_workspace_bytes(_cfg()) > 0
     assert lf.longflow_workspace_bytes(_cfg()) % 256 == 0
     for bad in (dict(q_heads=7), dict(head_dim=96), dict(batch=0), dict(budget=0),
-                dict(q_heads=2 * 17), dict(dtype="f32", q_heads=2 * 9), dict(flags=64)):
+                dict(q_heads=2 * 17), dict(dtype="f32", q_heads=2 * 9, flags=lf.LF_FLAG_FORCE_VALU), dict(flags=64)):
         assert lf.longflow_workspace_bytes(_cfg(**bad)) == 0
         assert L.longflow_last_error() != b""
     assert L.longflow_workspace_bytes(None) == 0
-    # group 16 is served by the matrix-core kernel only
+    # group 16 is served by the matrix-core kernels only
     assert lf.longflow_workspace_bytes(_cfg(q_heads=32)) > 0
+    assert lf.longflow_workspace_bytes(_cfg(q_heads=32, dtype="f32")) > 0
+    assert lf.longflow_workspace_bytes(_cfg(q_heads=32, head_dim=64)) > 0
     assert lf.longflow_workspace_bytes(_cfg(q_heads=32, flags=lf.LF_FLAG_FORCE_VALU)) == 0
     # bigger budget needs a bigger workspace
     assert lf.longflow_workspace_bytes(_cfg(budget=4096)) > lf.longflow_workspace_bytes(_cfg(budget=512))
@@ -121,11 +123,13 @@ def test_every_accepted_configuration_has_a_consistent_plan():
                 one = G * N + (N // 16 + 1) * G * 4
                 assert flags & lf.LF_FLAG_ATTENTION_ONLY == 0 and one > LDS_PER_CU - 12 * 1024, key
         else:
-            assert info.path == (lf.LF_PATH_SPLIT_MFMA if mfma_ok else lf.LF_PATH_SPLIT_VALU), key
+            valu = bool(flags & lf.LF_FLAG_FORCE_VALU)
+            assert info.path == (lf.LF_PATH_SPLIT_MFMA if mfma_ok else lf.LF_PATH_SPLIT_VALU if valu else lf.LF_PATH_SPLIT_MFMA_F32), key
+            assert not (valu and G > 8), key
             assert info.workgroups_per_unit <= 64 and info.slots_per_workgroup % 256 == 0
             big = info.workgroups_per_unit > 1 and B * Hkv * info.workgroups_per_unit > 256
             assert info.launches_per_step == (2 if big else 1), key
-    assert count > 1000 and seen == {0, 1, 2}
+    assert count > 1000 and seen == {0, 1, 2, 3}
 
 
 def test_plan_of_the_baseline_workloads():
@@ -134,7 +138,7 @@ def test_plan_of_the_baseline_workloads():
     for wl in W.CONFIGS:
         i = lf.longflow_plan_info(lf.make_config(wl.batch, wl.q_heads, wl.kv_heads, wl.head_dim, wl.budget, wl.dtype, 0))
         got.append((lf.PATH_KERNELS[i.path], i.workgroups_per_unit, i.slots_per_workgroup))
-    assert got == [("split_valu_kernel", 1, 256), ("unit_mfma_kernel", 8, 256), ("unit_mfma_kernel", 2, 2048),
+    assert got == [("split_mfma32_kernel", 1, 256), ("unit_mfma_kernel", 8, 256), ("unit_mfma_kernel", 2, 2048),
                    ("unit_mfma_kernel", 1, 8192), ("unit_mfma_kernel", 1, 16384)]
 
 

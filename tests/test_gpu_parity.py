@@ -40,6 +40,10 @@ def test_cfg1_bf16_every_step(flags):
 @pytest.mark.parametrize("dtype,Hq,Hkv,D,N,flags", [
     ("f32", 1, 1, 64, 37, 0), ("f32", 6, 2, 128, 100, 0), ("f32", 8, 1, 64, 333, 0),
     ("bf16", 2, 2, 64, 50, 0), ("bf16", 3, 1, 64, 272, 0), ("bf16", 10, 2, 128, 129, 0),
+    # groups beyond 8 heads on the fp32 matrix-core kernel; its vector-ALU twin
+    ("f32", 16, 1, 64, 300, 0), ("f32", 26, 2, 128, 530, 0), ("bf16", 12, 1, 64, 700, 0), ("f32", 7, 1, 128, 1100, 0),
+    ("f32", 6, 2, 128, 100, lf.LF_FLAG_FORCE_VALU), ("f32", 8, 1, 64, 333, lf.LF_FLAG_FORCE_VALU),
+    ("bf16", 3, 1, 64, 272, lf.LF_FLAG_FORCE_VALU),
     ("bf16", 7, 1, 128, 1000, 0), ("bf16", 8, 1, 128, 515, lf.LF_FLAG_FORCE_VALU),
     ("bf16", 16, 1, 128, 300, 0), ("bf16", 24, 2, 128, 2100, 0),
     # one fused launch per step, one workgroup per unit
@@ -389,10 +393,10 @@ def _random_cases(count, seed):
         dtype = "bf16" if rng.random() < 0.7 else "f32"
         D = 128 if rng.random() < 0.7 else 64
         mfma_ok = dtype == "bf16" and D == 128
-        flags = 0
+        flags = int(rng.choice([0, 0, lf.LF_FLAG_FORCE_VALU]))
         if mfma_ok:
             flags = int(rng.choice([0, 0, lf.LF_FLAG_FORCE_SPLIT, lf.LF_FLAG_FORCE_UNIT, lf.LF_FLAG_FORCE_VALU]))
-        gmax = 16 if (mfma_ok and not flags & lf.LF_FLAG_FORCE_VALU) else 8
+        gmax = 8 if flags & lf.LF_FLAG_FORCE_VALU else 16
         G = int(rng.integers(1, gmax + 1))
         Hkv = int(rng.integers(1, 4))
         B = int(rng.integers(1, 6))
@@ -403,7 +407,7 @@ def _random_cases(count, seed):
     return cases
 
 
-@pytest.mark.parametrize("case", _random_cases(28, 20260311), ids=lambda c: "-".join(str(x) for x in c[:9]))
+@pytest.mark.parametrize("case", _random_cases(36, 20260311), ids=lambda c: "-".join(str(x) for x in c[:9]))
 def test_random_geometries(case):
     dtype, B, Hq, Hkv, D, N, n_init, steps, flags, seed = case
     wl = W.Workload("rand", dtype, B, Hq, Hkv, D, N, n_init, steps, sink_scale=4.0 if seed & 1 else 1.0,
@@ -760,7 +764,7 @@ def _op_sequences(count, seed):
         path = int(rng.choice([0, 0, lf.LF_FLAG_FORCE_SPLIT, lf.LF_FLAG_FORCE_UNIT, lf.LF_FLAG_FORCE_VALU]))
         dtype = "f32" if (path == 0 and rng.random() < 0.25) else "bf16"
         D = 64 if dtype == "f32" else 128
-        gmax = 8 if (dtype == "f32" or path == lf.LF_FLAG_FORCE_VALU) else 16
+        gmax = 8 if path == lf.LF_FLAG_FORCE_VALU else 16
         G = int(rng.integers(1, gmax + 1))
         Hkv = int(rng.integers(1, 3))
         B = int(rng.integers(1, 4))
@@ -887,11 +891,31 @@ def test_max_free_softmax_equals_the_referenced_one_until_it_overflows():
                                    W.to_f64(v0.reshape(wl.units, -1, D)[0]))
     assert np.abs(W.to_f64(o_ref2.reshape(wl.units, G, D)[0]) - out).max() <= 2e-2
     assert not torch.isfinite(o_mf2.float()).all()
-    # the variant exists for plain attention on the fused kernel only
+    # the variant exists on the fused matrix-core kernel only
     with pytest.raises(lf.LongFlowError):
-        lf.LongFlowCache(1, 4, 1, 128, 64, flags=lf.LF_FLAG_MAX_FREE)
+        lf.LongFlowCache(1, 4, 1, 128, 64, flags=lf.LF_FLAG_MAX_FREE | lf.LF_FLAG_FORCE_SPLIT)
     with pytest.raises(lf.LongFlowError):
         lf.LongFlowCache(1, 4, 1, 64, 64, flags=AO | lf.LF_FLAG_MAX_FREE, k_init=k0[:1, :1, :8, :64].contiguous(), v_init=v0[:1, :1, :8, :64].contiguous())
+
+
+@pytest.mark.parametrize("B,N,n_init,steps", [(48, 1500, 1490, 40), (2, 2100, 0, 2140), (1, 700, 690, 30)],
+                         ids=["one_workgroup_per_unit", "several_from_empty", "several_small"])
+def test_max_free_softmax_in_the_evicting_step(B, N, n_init, steps):
+    # Alg. 1 as printed (no running reference) on the whole step: same outputs, decisions and scores as the
+    # oracle.  The sink key (x4) drives some logits past the window in which the 8-bit codes have two-sided
+    # bounds, so the one-sided ones are exercised too.
+    wl = _small("maxfree_evict", "bf16", B, 28, 4, 128, N, n_init=n_init, steps=steps, sink_scale=4.0, seed=23)
+    rep, gpu, _ = run_lockstep(wl, flags=lf.LF_FLAG_MAX_FREE, check_scores_every=7, host_inputs=False)
+    print(f"\n{wl.name}: {rep.steps} steps, {rep.decisions} decisions, {rep.near_ties} near-ties, "
+          f"max|out-oracle| {rep.max_out_err:.2e}, max score rel {rep.max_score_rel:.2e}")
+    # a mask, batch eviction and groups are not offered for the variant
+    with pytest.raises(lf.LongFlowError) as e:
+        gpu.set_mask(torch.ones((wl.batch, wl.kv_heads, N), dtype=torch.uint8))
+    assert e.value.status == lf.LF_ERR_UNSUPPORTED
+    with pytest.raises(lf.LongFlowError) as e:
+        gpu.evict_lowest(2)
+    assert e.value.status == lf.LF_ERR_UNSUPPORTED
+    gpu.close()
 
 
 @pytest.mark.parametrize("dtype,D,flags", [("bf16", 128, 0), ("bf16", 128, lf.LF_FLAG_FORCE_SPLIT), ("f32", 64, 0)],
