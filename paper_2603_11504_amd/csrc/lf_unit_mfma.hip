@@ -101,11 +101,29 @@ __device__ __forceinline__ int add_agent(int32_t *p, int v)
 // all of this thread's device-scope stores have reached the coherence point
 __device__ __forceinline__ void wait_stores() { asm volatile("s_waitcnt vmcnt(0)" ::: "memory"); }
 
+// Reductions of doubles for the exact re-scoring.  Inside a row of 16 lanes they go through DPP
+// (a few cycles a level); only the two levels across rows take the cross-lane permute, whose
+// latency is an order of magnitude more and stands in the serial tail of the kernel.
+template <int CTRL> __device__ __forceinline__ double dpp_f64(double x)
+{
+    const long long b = __double_as_longlong(x);
+    const int lo = __builtin_amdgcn_update_dpp(0, (int)b, CTRL, 0xf, 0xf, true);
+    const int hi = __builtin_amdgcn_update_dpp(0, (int)(b >> 32), CTRL, 0xf, 0xf, true);
+    return __longlong_as_double(((long long)hi << 32) | (unsigned int)lo);
+}
+__device__ __forceinline__ double rows_sum_f64(double x) // over the four rows: same position in each
+{
+    x += __shfl_xor(x, 16);
+    x += __shfl_xor(x, 32);
+    return x;
+}
 __device__ __forceinline__ double wave_sum_f64(double x)
 {
-#pragma unroll
-    for (int off = 32; off > 0; off >>= 1) x += __shfl_xor(x, off);
-    return x;
+    x += dpp_f64<0x128>(x); // row_ror:8
+    x += dpp_f64<0x124>(x); // row_ror:4
+    x += dpp_f64<0x122>(x); // row_ror:2
+    x += dpp_f64<0x121>(x); // row_ror:1
+    return rows_sum_f64(x);
 }
 
 // 2^x for |x| <= 0.5 in double precision: Taylor series of exp(x ln 2), error < 1e-14
@@ -180,8 +198,8 @@ __device__ __forceinline__ double score_row(const RowRegs &rr, const uint16_t (*
             dot = fma((double)bf16_hi(qq.w), (double)bf16_hi(kk.w), dot);
         }
     }
-    dot += __shfl_xor(dot, 1);
-    dot += __shfl_xor(dot, 2);
+    dot += dpp_f64<0xB1>(dot); // quad_perm [1,0,3,2]: the neighbour in the pair
+    dot += dpp_f64<0x4E>(dot); // quad_perm [2,3,0,1]: the other pair of the four lanes of a head
     double term = 0.0;
     if (h < G && part == 0) {
         const double scale_log2 = 1.4426950408889634074 / 11.313708498984760390; // log2(e) / sqrt(128)
@@ -189,9 +207,11 @@ __device__ __forceinline__ double score_row(const RowRegs &rr, const uint16_t (*
         const double nint = rint(d);
         term = ldexp(exp2_frac_f64(d - nint), (int)nint) / (double)sL[h];
     }
-#pragma unroll
-    for (int off = 4; off < 64; off <<= 1) term += __shfl_xor(term, off);
-    return term * l1;
+    // the heads' terms sit in every fourth lane (zeros between them): rotations by 4 and 8 add up
+    // the four heads of a row in each of those lanes, then the rows
+    term += dpp_f64<0x124>(term); // row_ror:4
+    term += dpp_f64<0x128>(term); // row_ror:8
+    return rows_sum_f64(term) * l1;
 }
 
 __device__ __forceinline__ double exact_score_bf16(g_cu16p krow, g_cu16p vrow, const uint16_t (*qs)[128], int G,
