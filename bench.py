@@ -26,11 +26,11 @@ DEFAULT_STEPS = {0: 512, 1: 1024, 2: 100, 3: 256, 4: 50}
 # (FETCH_SIZE / WRITE_SIZE, scaled by copy kernels of known size) and recorded under profiles/.
 # A constant of this file, not a measurement of the run that prints it: the JSON line says so.
 MEASURED_TRAFFIC = {
-    ("cfg3_bf16_b64_28x4_d128_n8192_l28", "unit_mfma_kernel"): {"read_bytes": 1058610 * 1024, "write_bytes": 1076 * 1024,
+    ("cfg3_bf16_b64_28x4_d128_n8192_l28", "unit_mfma_kernel"): {"read_bytes": 1058613 * 1024, "write_bytes": 1076 * 1024,
                                                                 "source": "profiles/unit_mfma_kernel_cfg3.txt"},
-    ("cfg2_bf16_b32_28x4_d128_n4096", "unit_mfma_kernel"): {"read_bytes": 268735 * 1024, "write_bytes": 3722 * 1024,
+    ("cfg2_bf16_b32_28x4_d128_n4096", "unit_mfma_kernel"): {"read_bytes": 268756 * 1024, "write_bytes": 5955 * 1024,
                                                             "source": "profiles/unit_mfma_kernel_cfg2.txt"},
-    ("cfg4_bf16_b128_40x8_d128_n16384", "unit_mfma_kernel"): {"read_bytes": 8458735 * 1024, "write_bytes": 3264 * 1024,
+    ("cfg4_bf16_b128_40x8_d128_n16384", "unit_mfma_kernel"): {"read_bytes": 8458888 * 1024, "write_bytes": 3264 * 1024,
                                                               "source": "profiles/unit_mfma_kernel_cfg4.txt"},
     # the four launches of an unfused step together
     ("cfg3_bf16_b64_28x4_d128_n8192_l28", "unfused+unit_mfma_kernel"): {
@@ -318,15 +318,19 @@ def summary(wl, r):
 
 
 def gpu_clocks():
-    """Clocks as found (nothing is pinned): what rocm-smi reports right after the timed work, or None."""
-    import subprocess
+    """Clocks as found (nothing is pinned), right after the timed work: the current levels in the
+    driver's sysfs tables (plain file reads: no child process is started from a process that holds the GPU)."""
+    import glob
+    out = {}
     try:
-        txt = subprocess.run(["rocm-smi", "--showclocks", "--json"], capture_output=True, text=True, timeout=20).stdout
-        card = next(iter(json.loads(txt).values()))
-        keep = {k: v for k, v in card.items() if "sclk" in k.lower() or "mclk" in k.lower() or "fclk" in k.lower()}
-        return keep or None
+        for name in ("pp_dpm_sclk", "pp_dpm_mclk", "pp_dpm_fclk"):
+            for path in sorted(glob.glob("/sys/class/drm/card*/device/" + name))[:1]:
+                cur = [ln.split(":", 1)[1].replace("*", "").strip() for ln in open(path).read().splitlines() if ln.strip().endswith("*")]
+                if cur:
+                    out[name[len("pp_dpm_"):]] = cur[0]
     except Exception:
         return None
+    return out or None
 
 
 def fill_bench(a):
