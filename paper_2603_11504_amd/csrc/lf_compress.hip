@@ -42,13 +42,13 @@ struct CompressArgs {
     float scale_log2;
 };
 
-// Query rows of a wave's blocks as A operands: lane (g, r) holds column 16 qb + r, channels 32 c + 8 g .. + 7.
-struct QueryBlocks {
-    u32x4 q[kCBlocks][4];
+// Query rows of a wave's NB blocks as A operands: lane (g, r) holds column 16 qb + r, channels 32 c + 8 g .. + 7.
+template <int NB> struct QueryBlocks {
+    u32x4 q[NB][4];
     __device__ __forceinline__ void load(const CompressArgs &a, int u, int qb0, int g, int r)
     {
 #pragma unroll
-        for (int b = 0; b < kCBlocks; ++b) {
+        for (int b = 0; b < NB; ++b) {
             const int col = 16 * (qb0 + b) + r;
 #pragma unroll
             for (int c = 0; c < 4; ++c) {
@@ -71,36 +71,33 @@ __device__ __forceinline__ void load_rows(KRows &t, const uint16_t *Ku, int base
     for (int c = 0; c < 4; ++c) t.k[c] = *(const u32x4 *)(Ku + (size_t)row * kCD + 32 * c + 8 * g);
 }
 
-// logits of (query 4g + v of block b, row r of the tile), unscaled
-__device__ __forceinline__ f32x4 block_logits(const QueryBlocks &Q, int b, const KRows &t)
+// logits of (query 4g + v of a block, row r of the tile), unscaled
+__device__ __forceinline__ f32x4 block_logits(const u32x4 (&q)[4], const KRows &t)
 {
     f32x4 d = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
     for (int c = 0; c < 4; ++c)
-        d = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, Q.q[b][c]), __builtin_bit_cast(bf16x8, t.k[c]), d, 0, 0, 0);
+        d = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, q[c]), __builtin_bit_cast(bf16x8, t.k[c]), d, 0, 0, 0);
     return d;
 }
 
-// ---- pass 1: softmax state of every column over one span of rows
-// grid: units x nspans x rounds; workgroup = 4 waves x 4 blocks x 16 columns
-__global__ __launch_bounds__(64 * kCWaves) void compress_stats_kernel(const CompressArgs a)
+// number of live 16-column blocks among the kCBlocks a wave is responsible for, starting at block qb0
+__device__ __forceinline__ int live_blocks(const CompressArgs &a, int qb0)
 {
-    const int rounds = (a.colsP + kColsPerRound - 1) / kColsPerRound;
-    int bid = blockIdx.x;
-    const int round = bid % rounds; bid /= rounds;
-    const int sp = bid % a.nspans;
-    const int u = bid / a.nspans;
-    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6, g = lane >> 4, r = lane & 15;
-    const int qb0 = (round * kCWaves + wave) * kCBlocks;
-    if (16 * qb0 >= a.cols) return; // nothing to do for this wave (no barrier in this kernel)
+    return min(max((a.cols + 15) / 16 - qb0, 0), kCBlocks);
+}
 
-    QueryBlocks Q;
+// ---- pass 1: softmax state of NB blocks of columns over one span of rows
+template <int NB>
+__device__ __forceinline__ void stats_span(const CompressArgs &a, int u, int sp, int qb0, int g, int r)
+{
+    QueryBlocks<NB> Q;
     Q.load(a, u, qb0, g, r);
     // column 16 (qb0 + b) + 4 g + v sees rows below lim[b][v]; an unused column sees none
-    int lim[kCBlocks][4];
-    float m[kCBlocks][4], l[kCBlocks][4];
+    int lim[NB][4];
+    float m[NB][4], l[NB][4];
 #pragma unroll
-    for (int b = 0; b < kCBlocks; ++b)
+    for (int b = 0; b < NB; ++b)
 #pragma unroll
         for (int v = 0; v < 4; ++v) {
             const int col = 16 * (qb0 + b) + 4 * g + v;
@@ -113,22 +110,45 @@ __global__ __launch_bounds__(64 * kCWaves) void compress_stats_kernel(const Comp
     const int start = sp * a.LS, end = min(start + a.LS, a.T);
     const int nt = (end - start + kTile - 1) / kTile;
     auto consume = [&](const KRows &t, int ti) __attribute__((always_inline)) {
-        const int row = start + ti * kTile + r;
+        const int base = start + ti * kTile;
+        float x[NB][4];
 #pragma unroll
-        for (int b = 0; b < kCBlocks; ++b) {
-            const f32x4 d = block_logits(Q, b, t);
+        for (int b = 0; b < NB; ++b) {
+            const f32x4 d = block_logits(Q.q[b], t);
 #pragma unroll
-            for (int v = 0; v < 4; ++v) {
-                const float x = row < lim[b][v] ? d[v] * a.scale_log2 : -INFINITY;
-                // the reference of a lane's share is raised only when a logit passes it by more than
-                // kMaxSlack: weights stay below 2^kMaxSlack and the common case costs one exponential
-                if (x > m[b][v] + kMaxSlack) {
-                    l[b][v] *= fast_exp2(m[b][v] - x);
-                    m[b][v] = x;
-                }
-                l[b][v] += fast_exp2(x - m[b][v]);
-            }
+            for (int v = 0; v < 4; ++v) x[b][v] = d[v] * a.scale_log2;
         }
+        // Every used column sees every prefix row, so a tile that lies inside the prefix needs no
+        // masking (an unused column collects garbage nobody reads); tiles that touch the window or the
+        // ragged end take the per-column row limit.
+        if (base + kTile > a.P) {
+#pragma unroll
+            for (int b = 0; b < NB; ++b)
+#pragma unroll
+                for (int v = 0; v < 4; ++v)
+                    if (base + r >= lim[b][v]) x[b][v] = -INFINITY;
+        }
+        // The reference of a lane's share is raised only when a logit passes it by more than kMaxSlack
+        // (weights stay below 2^kMaxSlack); one wave-wide test keeps the common case branch-free.
+        bool raise = false;
+#pragma unroll
+        for (int b = 0; b < NB; ++b)
+#pragma unroll
+            for (int v = 0; v < 4; ++v) raise |= x[b][v] > m[b][v] + kMaxSlack;
+        if (__any(raise)) {
+#pragma unroll
+            for (int b = 0; b < NB; ++b)
+#pragma unroll
+                for (int v = 0; v < 4; ++v)
+                    if (x[b][v] > m[b][v] + kMaxSlack) {
+                        l[b][v] *= fast_exp2(m[b][v] - x[b][v]);
+                        m[b][v] = x[b][v];
+                    }
+        }
+#pragma unroll
+        for (int b = 0; b < NB; ++b)
+#pragma unroll
+            for (int v = 0; v < 4; ++v) l[b][v] += fast_exp2(x[b][v] - m[b][v]);
     };
     KRows ta, tb;
     if (nt >= 1) load_rows(ta, Ku, start, a.T - 1, g, r);
@@ -136,25 +156,44 @@ __global__ __launch_bounds__(64 * kCWaves) void compress_stats_kernel(const Comp
     for (; i + 1 < nt; i += 2) {
         load_rows(tb, Ku, start + (i + 1) * kTile, a.T - 1, g, r);
         consume(ta, i);
-        if (i + 2 < nt) load_rows(ta, Ku, start + (i + 2) * kTile, a.T - 1, g, r);
+        load_rows(ta, Ku, start + min(i + 2, nt - 1) * kTile, a.T - 1, g, r); // past the end: re-read, never used
         consume(tb, i + 1);
     }
     if (i < nt) consume(ta, i);
 
     // the 16 lanes of a row group hold the shares of the same four queries
 #pragma unroll
-    for (int b = 0; b < kCBlocks; ++b)
+    for (int b = 0; b < NB; ++b)
 #pragma unroll
         for (int v = 0; v < 4; ++v) {
             const float M = row16_max(m[b][v]);
             const float L = row16_sum(l[b][v] * fast_exp2(m[b][v] - M));
             const int col = 16 * (qb0 + b) + 4 * g + v;
-            if (r == 0 && col < a.colsP) {
+            if (r == 0 && col < a.cols) {
                 const size_t at = ((size_t)u * a.nspans + sp) * a.colsP + col;
                 a.part_m[at] = M;
                 a.part_l[at] = L;
             }
         }
+}
+
+// grid: units x nspans x rounds; workgroup = 4 waves x (up to) 4 blocks x 16 columns
+__global__ __launch_bounds__(64 * kCWaves) void compress_stats_kernel(const CompressArgs a)
+{
+    const int rounds = (a.colsP + kColsPerRound - 1) / kColsPerRound;
+    int bid = blockIdx.x;
+    const int round = bid % rounds; bid /= rounds;
+    const int sp = bid % a.nspans;
+    const int u = bid / a.nspans;
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6, g = lane >> 4, r = lane & 15;
+    const int qb0 = (round * kCWaves + wave) * kCBlocks;
+    switch (live_blocks(a, qb0)) { // no barrier in this kernel: a wave without columns just leaves
+    case 4: stats_span<4>(a, u, sp, qb0, g, r); break;
+    case 3: stats_span<3>(a, u, sp, qb0, g, r); break;
+    case 2: stats_span<2>(a, u, sp, qb0, g, r); break;
+    case 1: stats_span<1>(a, u, sp, qb0, g, r); break;
+    default: break;
+    }
 }
 
 // ---- per column: reference + log2 denominator over all spans (+inf for an unused column)
@@ -177,7 +216,46 @@ __global__ __launch_bounds__(256) void compress_norm_kernel(const CompressArgs a
     a.cq[idx] = out;
 }
 
-// ---- pass 2: votes of the prefix rows of one span
+// ---- pass 2: votes of the prefix rows of one span, from NB blocks of columns, added into `mine`
+template <int NB>
+__device__ __forceinline__ void votes_span(const CompressArgs &a, int u, int qb0, int start, int nt, __attribute__((address_space(3))) float *mine, int g, int r)
+{
+    QueryBlocks<NB> Q;
+    Q.load(a, u, qb0, g, r);
+    float cq[NB][4];
+#pragma unroll
+    for (int b = 0; b < NB; ++b)
+#pragma unroll
+        for (int v = 0; v < 4; ++v) {
+            const int col = 16 * (qb0 + b) + 4 * g + v;
+            cq[b][v] = col < a.colsP ? a.cq[(size_t)u * a.colsP + col] : INFINITY; // +inf for an unused column: weight 0
+        }
+    const uint16_t *Ku = a.Kp + (size_t)u * a.T * kCD;
+    auto consume = [&](const KRows &t, int ti) __attribute__((always_inline)) {
+        float w = 0.f;
+#pragma unroll
+        for (int b = 0; b < NB; ++b) {
+            const f32x4 d = block_logits(Q.q[b], t);
+#pragma unroll
+            for (int v = 0; v < 4; ++v) w += fast_exp2(fmaf(d[v], a.scale_log2, -cq[b][v])); // alpha, eq. 1
+        }
+        // every prefix row is seen by every window query.  The four lanes that hold shares of row r add
+        // them to the wave's own LDS row with a no-return LDS add: nothing to wait for (a cross-lane sum
+        // and a read-modify-write here cost the pass half its time in waits)
+        __hip_atomic_fetch_add(&mine[ti * kTile + r], w, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WAVEFRONT);
+    };
+    KRows ta, tb;
+    if (nt >= 1) load_rows(ta, Ku, start, a.P - 1, g, r);
+    int i = 0;
+    for (; i + 1 < nt; i += 2) {
+        load_rows(tb, Ku, start + (i + 1) * kTile, a.P - 1, g, r);
+        consume(ta, i);
+        load_rows(ta, Ku, start + min(i + 2, nt - 1) * kTile, a.P - 1, g, r); // past the end: re-read, never used
+        consume(tb, i + 1);
+    }
+    if (i < nt) consume(ta, i);
+}
+
 // grid: units x nspans2; the workgroup takes every round of columns through its span, each wave
 // adding into a row of LDS of its own, and the waves' rows are summed in a fixed order at the end
 __global__ __launch_bounds__(64 * kCWaves) void compress_votes_kernel(const CompressArgs a)
@@ -188,46 +266,19 @@ __global__ __launch_bounds__(64 * kCWaves) void compress_votes_kernel(const Comp
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6, g = lane >> 4, r = lane & 15;
     const int start = sp * a.LS, end = min(start + a.LS, a.P);
     const int nt = (end - start + kTile - 1) / kTile;
-    float *mine = wave_votes + (size_t)wave * a.LS;
+    __attribute__((address_space(3))) float *mine = (__attribute__((address_space(3))) float *)wave_votes + (size_t)wave * a.LS;
     for (int i = lane; i < a.LS; i += 64) mine[i] = 0.f;
 
-    const uint16_t *Ku = a.Kp + (size_t)u * a.T * kCD;
     const int rounds = (a.colsP + kColsPerRound - 1) / kColsPerRound;
     for (int round = 0; round < rounds; ++round) {
         const int qb0 = (round * kCWaves + wave) * kCBlocks;
-        if (16 * qb0 >= a.cols) break;
-        QueryBlocks Q;
-        Q.load(a, u, qb0, g, r);
-        float cq[kCBlocks][4];
-#pragma unroll
-        for (int b = 0; b < kCBlocks; ++b)
-#pragma unroll
-            for (int v = 0; v < 4; ++v) {
-                const int col = 16 * (qb0 + b) + 4 * g + v;
-                cq[b][v] = col < a.colsP ? a.cq[(size_t)u * a.colsP + col] : INFINITY;
-            }
-        auto consume = [&](const KRows &t, int ti) __attribute__((always_inline)) {
-            float w = 0.f;
-#pragma unroll
-            for (int b = 0; b < kCBlocks; ++b) {
-                const f32x4 d = block_logits(Q, b, t);
-#pragma unroll
-                for (int v = 0; v < 4; ++v) w += fast_exp2(fmaf(d[v], a.scale_log2, -cq[b][v])); // alpha, eq. 1
-            }
-            w += __shfl_xor(w, 16);
-            w += __shfl_xor(w, 32);
-            if (g == 0) mine[ti * kTile + r] += w; // every prefix row is seen by every window query
-        };
-        KRows ta, tb;
-        if (nt >= 1) load_rows(ta, Ku, start, a.P - 1, g, r);
-        int i = 0;
-        for (; i + 1 < nt; i += 2) {
-            load_rows(tb, Ku, start + (i + 1) * kTile, a.P - 1, g, r);
-            consume(ta, i);
-            if (i + 2 < nt) load_rows(ta, Ku, start + (i + 2) * kTile, a.P - 1, g, r);
-            consume(tb, i + 1);
+        switch (live_blocks(a, qb0)) {
+        case 4: votes_span<4>(a, u, qb0, start, nt, mine, g, r); break;
+        case 3: votes_span<3>(a, u, qb0, start, nt, mine, g, r); break;
+        case 2: votes_span<2>(a, u, qb0, start, nt, mine, g, r); break;
+        case 1: votes_span<1>(a, u, qb0, start, nt, mine, g, r); break;
+        default: break;
         }
-        if (i < nt) consume(ta, i);
     }
     __syncthreads();
     for (int i = threadIdx.x; i < end - start; i += 64 * kCWaves) {
