@@ -252,3 +252,19 @@ def test_workspace_regions_never_overlap_and_hold_every_index_the_kernels_form()
     cfg = lf.make_config(4, 8, 2, 128, 1000, "bf16", lf.LF_FLAG_UNFUSED_ACCUM)
     have = {name: size for name, _, size in lf.longflow_workspace_regions(cfg)}
     assert have["acc"] >= 4 * 8 * 63 * 16 and have["acc_part_v"] > 0 and have["acc_part_i"] == have["acc_part_v"]
+
+
+def test_compress_scratch_bytes_host_query():
+    import ctypes
+    L = lf.lib()
+    cfg = _cfg(batch=4, q_heads=28, kv_heads=4, budget=1024)
+    f = lambda T, W, c=cfg: int(L.longflow_compress_scratch_bytes(ctypes.byref(c), T, W))
+    base = f(5000, 32)
+    assert base > 0 and base % 256 == 0
+    # votes and pooled votes (4 bytes per prefix row and unit each) and the kept rows must fit
+    units = 16
+    assert base >= 2 * 4 * units * (5000 - 32) + 4 * units * 1024
+    assert f(10000, 32) > base and f(5000, 64) > base          # more rows, more query columns
+    for T, W in ((0, 1), (10, 0), (10, 11), ((1 << 24) + 1, 32), (5000, 4096)):   # 4096 x 7 columns: too many
+        assert f(T, W) == 0
+    assert f(5000, 32, _cfg(head_dim=96)) == 0                  # invalid geometry
