@@ -88,9 +88,15 @@ __global__ __launch_bounds__(64 * NWV) void fill_attend_kernel(const FillArgs a)
     {
         const int nfull = n_max / kTile;
         TileRegs ta, tb;
+        // Per tile the V operands are built once for all the wave's products, and the causal test is
+        // skipped on tiles that every one of the wave's tokens sees whole (all but the last few): both
+        // come out of the vector-instruction budget that bounds this kernel.
+        const int first_limit = a.n0 + t0 + 1; // rows the wave's first token sees; later tokens see more
         auto compute = [&](TileRegs &t, int ti) __attribute__((always_inline)) {
+            Streamer::build_v_in_place(t);
+            const bool cmask_now = (ti + 1) * kTile > first_limit;
 #pragma unroll
-            for (int nb = 0; nb < NB; ++nb) st[nb].template compute_tile<false>(t, ti);
+            for (int nb = 0; nb < NB; ++nb) st[nb].template compute_core<false, true, true>(t, ti, cmask_now);
         };
         if (nfull >= 2) {
             st[0].template load_tile<false>(ta, 0);
@@ -112,8 +118,10 @@ __global__ __launch_bounds__(64 * NWV) void fill_attend_kernel(const FillArgs a)
         }
         if (n_max % kTile != 0) {
             st[0].template load_tile<true>(ta, nfull);
+            st[0].template zero_ragged<true>(ta, nfull);
+            Streamer::build_v_in_place(ta);
 #pragma unroll
-            for (int nb = 0; nb < NB; ++nb) st[nb].template compute_tile<true>(ta, nfull);
+            for (int nb = 0; nb < NB; ++nb) st[nb].template compute_core<true, true, true>(ta, nfull);
         }
     }
 

@@ -199,8 +199,30 @@ struct MfmaStreamer {
         }
     }
 
+    // B operand of P V product dd (channel 8r + dd): v_perm picks, from a lane's four V rows, the bf16 pairs of
+    // positions (4g, 4g + 1) and (4g + 2, 4g + 3)
+    static __device__ __forceinline__ s16x4 v_operand(const TileRegs &t, int dd)
+    {
+        const uint32_t sel = (dd & 1) ? 0x07060302u : 0x05040100u;
+        const int w = dd >> 1;
+        const uint32_t v01 = __builtin_amdgcn_perm(t.v[1][w], t.v[0][w], sel);
+        const uint32_t v23 = __builtin_amdgcn_perm(t.v[3][w], t.v[2][w], sel);
+        return __builtin_bit_cast(s16x4, u32x2{v01, v23});
+    }
+    // The eight operands built once, in place of the V rows they come from (same number of registers):
+    // afterwards t.v[i] holds the operands of products 2i and 2i + 1.  For kernels that take several
+    // products through one tile (compute_core<.., .., VPRE = true>).
+    static __device__ __forceinline__ void build_v_in_place(TileRegs &t)
+    {
+        u32x2 vb[8];
+#pragma unroll
+        for (int dd = 0; dd < 8; ++dd) vb[dd] = __builtin_bit_cast(u32x2, v_operand(t, dd));
+#pragma unroll
+        for (int i = 0; i < 4; ++i) t.v[i] = u32x4{vb[2 * i].x, vb[2 * i].y, vb[2 * i + 1].x, vb[2 * i + 1].y};
+    }
+
     // RAGGED: the tile may reach past `end`; rows loaded from the clamped address are zeroed
-    template <bool RAGGED> __device__ __forceinline__ void compute_tile(TileRegs &t, int ti)
+    template <bool RAGGED> __device__ __forceinline__ void zero_ragged(TileRegs &t, int ti) const
     {
         const int base = start + ti * kTile;
         if (RAGGED) {
@@ -215,6 +237,21 @@ struct MfmaStreamer {
             for (int e = 0; e < 4; ++e)
                 if (base + slot_off(e) >= end) t.v[e] = u32x4{0u, 0u, 0u, 0u};
         }
+    }
+
+    template <bool RAGGED> __device__ __forceinline__ void compute_tile(TileRegs &t, int ti)
+    {
+        zero_ragged<RAGGED>(t, ti);
+        compute_core<RAGGED, CAUSAL, false>(t, ti);
+    }
+
+    // One tile of one product, from rows already cleaned (zero_ragged).
+    // CMASK: the column's causal row limit may apply; `cmask_now` (uniform over the wave) says whether this tile
+    //        needs the test at all -- tiles that every column of the wave sees whole skip it
+    // VPRE:  t.v already holds the P V operands (build_v_in_place)
+    template <bool RAGGED, bool CMASK, bool VPRE> __device__ __forceinline__ void compute_core(const TileRegs &t, int ti, bool cmask_now = true)
+    {
+        const int base = start + ti * kTile;
         // ---- S^T = K Q^T: per 8-row group, one product per chunk parity b
         float s[4];
         if (KNAT) {
@@ -244,7 +281,7 @@ struct MfmaStreamer {
             for (int e = 0; e < 4; ++e)
                 if (base + slot_off(e) >= end) s[e] = -INFINITY;
         }
-        if (CAUSAL) {
+        if (CMASK && cmask_now) {
 #pragma unroll
             for (int e = 0; e < 4; ++e)
                 if (base + slot_off(e) >= limit) s[e] = -INFINITY;
@@ -291,11 +328,8 @@ struct MfmaStreamer {
         // ---- O += P V, channel 8r + dd per product; contraction index 4g + e = position
 #pragma unroll
         for (int dd = 0; dd < 8; ++dd) {
-            const uint32_t sel = (dd & 1) ? 0x07060302u : 0x05040100u;
-            const int w = dd >> 1;
-            const uint32_t v01 = __builtin_amdgcn_perm(t.v[1][w], t.v[0][w], sel);
-            const uint32_t v23 = __builtin_amdgcn_perm(t.v[3][w], t.v[2][w], sel);
-            const s16x4 vb = __builtin_bit_cast(s16x4, u32x2{v01, v23});
+            const s16x4 vb = VPRE ? __builtin_bit_cast(s16x4, u32x2{t.v[dd >> 1][2 * (dd & 1)], t.v[dd >> 1][2 * (dd & 1) + 1]})
+                                  : v_operand(t, dd);
             oacc[dd] = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(p_hi, vb, oacc[dd], 0, 0, 0);
             if (HILO) oacc[dd] = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(p_lo, vb, oacc[dd], 0, 0, 0);
         }
