@@ -64,12 +64,65 @@ struct KRows {
     u32x4 k[4]; // row base + r, channels 32 c + 8 g .. + 7: the B operand of one 16-row tile
 };
 
-__device__ __forceinline__ void load_rows(KRows &t, const uint16_t *Ku, int base, int last, int g, int r)
-{
-    const int row = min(base + r, last);
+// K tiles of a span, staged through LDS.  The four waves of a workgroup want the same 16-row tiles as
+// operands; if each fetched them for itself, the compute unit's vector-memory path would be the limit of
+// both passes (counters: TA_TA_BUSY 85 % / 60 %).  Instead the 256 threads fetch a tile once, 16 bytes per
+// thread, park it in a ring of four LDS slots (rows padded to 272 bytes, so that the 16-byte operand reads
+// of eight neighbouring lanes fall into distinct banks), and every wave reads its operands from there.
+// One barrier per tile; the fetch of tile i + 4 is in flight while tile i is used.
+struct KRing {
+    static constexpr int RS = 272, SLOT = kTile * RS, NSLOT = 4;
+    unsigned char *ring;   // NSLOT * SLOT bytes of LDS
+    const uint16_t *src;   // this thread's 16 bytes of row 0 of the unit's K
+    int st_row, st_off, first, last_tile, last_row, g, r;
+    __device__ __forceinline__ void init(unsigned char *lds, const uint16_t *Ku, int start, int nt, int last_row_, int tid, int g_, int r_)
+    {
+        ring = lds; g = g_; r = r_;
+        st_row = tid >> 4;
+        src = Ku + (tid & 15) * 8;
+        st_off = st_row * RS + (tid & 15) * 16;
+        first = start; last_tile = nt - 1; last_row = last_row_;
+    }
+    // rows past the last one: that row again (never used as such)
+    __device__ __forceinline__ u32x4 fetch(int ti) const
+    {
+        return *(const u32x4 *)(src + (size_t)min(first + min(ti, last_tile) * kTile + st_row, last_row) * kCD);
+    }
+    __device__ __forceinline__ void park(int ti, u32x4 v) const { *(u32x4 *)(ring + (ti % NSLOT) * SLOT + st_off) = v; }
+    __device__ __forceinline__ void operands(KRows &t, int ti) const
+    {
+        const unsigned char *base = ring + (ti % NSLOT) * SLOT + r * RS + 16 * g;
 #pragma unroll
-    for (int c = 0; c < 4; ++c) t.k[c] = *(const u32x4 *)(Ku + (size_t)row * kCD + 32 * c + 8 * g);
-}
+        for (int c = 0; c < 4; ++c) t.k[c] = *(const u32x4 *)(base + 64 * c);
+    }
+    // every thread of the workgroup runs the same nt rounds; use(t, ti) consumes tile ti
+    template <typename F> __device__ __forceinline__ void run(int nt, F &&use) const
+    {
+        if (nt < 1) return;
+        u32x4 q0 = fetch(0), q1 = fetch(1);
+        park(0, q0);
+        park(1, q1);
+        q0 = fetch(2);
+        q1 = fetch(3);
+        __syncthreads();
+        KRows ta, tb;
+        operands(ta, 0);
+        for (int i = 0; i < nt; i += 2) {
+            park(i + 2, q0); // fetched two rounds ago
+            q0 = fetch(i + 4);
+            operands(tb, i + 1);
+            use(ta, i);
+            __syncthreads();
+            if (i + 1 < nt) {
+                park(i + 3, q1);
+                q1 = fetch(i + 5);
+                operands(ta, i + 2);
+                use(tb, i + 1);
+                __syncthreads();
+            }
+        }
+    }
+};
 
 // logits of (query 4g + v of a block, row r of the tile), unscaled
 __device__ __forceinline__ f32x4 block_logits(const u32x4 (&q)[4], const KRows &t)
@@ -87,17 +140,19 @@ __device__ __forceinline__ int live_blocks(const CompressArgs &a, int qb0)
     return min(max((a.cols + 15) / 16 - qb0, 0), kCBlocks);
 }
 
-// ---- pass 1: softmax state of NB blocks of columns over one span of rows
+// ---- pass 1: softmax state of NB blocks of columns over one span of rows (NB = 0: a wave without
+// columns, which only helps staging the tiles)
 template <int NB>
-__device__ __forceinline__ void stats_span(const CompressArgs &a, int u, int sp, int qb0, int g, int r)
+__device__ __forceinline__ void stats_span(const CompressArgs &a, int u, int sp, int qb0, int g, int r, unsigned char *lds)
 {
-    QueryBlocks<NB> Q;
-    Q.load(a, u, qb0, g, r);
+    constexpr int NBA = NB > 0 ? NB : 1;
+    QueryBlocks<NBA> Q;
+    if (NB > 0) Q.load(a, u, qb0, g, r);
     // column 16 (qb0 + b) + 4 g + v sees rows below lim[b][v]; an unused column sees none
-    int lim[NB][4];
-    float m[NB][4], l[NB][4];
+    int lim[NBA][4];
+    float m[NBA][4], l[NBA][4];
 #pragma unroll
-    for (int b = 0; b < NB; ++b)
+    for (int b = 0; b < NBA; ++b)
 #pragma unroll
         for (int v = 0; v < 4; ++v) {
             const int col = 16 * (qb0 + b) + 4 * g + v;
@@ -106,14 +161,14 @@ __device__ __forceinline__ void stats_span(const CompressArgs &a, int u, int sp,
             l[b][v] = 0.f;
         }
 
-    const uint16_t *Ku = a.Kp + (size_t)u * a.T * kCD;
     const int start = sp * a.LS, end = min(start + a.LS, a.T);
     const int nt = (end - start + kTile - 1) / kTile;
     auto consume = [&](const KRows &t, int ti) __attribute__((always_inline)) {
+        if (NB == 0) return;
         const int base = start + ti * kTile;
-        float x[NB][4];
+        float x[NBA][4];
 #pragma unroll
-        for (int b = 0; b < NB; ++b) {
+        for (int b = 0; b < NBA; ++b) {
             const f32x4 d = block_logits(Q.q[b], t);
 #pragma unroll
             for (int v = 0; v < 4; ++v) x[b][v] = d[v] * a.scale_log2;
@@ -123,7 +178,7 @@ __device__ __forceinline__ void stats_span(const CompressArgs &a, int u, int sp,
         // ragged end take the per-column row limit.
         if (base + kTile > a.P) {
 #pragma unroll
-            for (int b = 0; b < NB; ++b)
+            for (int b = 0; b < NBA; ++b)
 #pragma unroll
                 for (int v = 0; v < 4; ++v)
                     if (base + r >= lim[b][v]) x[b][v] = -INFINITY;
@@ -132,12 +187,12 @@ __device__ __forceinline__ void stats_span(const CompressArgs &a, int u, int sp,
         // (weights stay below 2^kMaxSlack); one wave-wide test keeps the common case branch-free.
         bool raise = false;
 #pragma unroll
-        for (int b = 0; b < NB; ++b)
+        for (int b = 0; b < NBA; ++b)
 #pragma unroll
             for (int v = 0; v < 4; ++v) raise |= x[b][v] > m[b][v] + kMaxSlack;
         if (__any(raise)) {
 #pragma unroll
-            for (int b = 0; b < NB; ++b)
+            for (int b = 0; b < NBA; ++b)
 #pragma unroll
                 for (int v = 0; v < 4; ++v)
                     if (x[b][v] > m[b][v] + kMaxSlack) {
@@ -146,24 +201,18 @@ __device__ __forceinline__ void stats_span(const CompressArgs &a, int u, int sp,
                     }
         }
 #pragma unroll
-        for (int b = 0; b < NB; ++b)
+        for (int b = 0; b < NBA; ++b)
 #pragma unroll
             for (int v = 0; v < 4; ++v) l[b][v] += fast_exp2(x[b][v] - m[b][v]);
     };
-    KRows ta, tb;
-    if (nt >= 1) load_rows(ta, Ku, start, a.T - 1, g, r);
-    int i = 0;
-    for (; i + 1 < nt; i += 2) {
-        load_rows(tb, Ku, start + (i + 1) * kTile, a.T - 1, g, r);
-        consume(ta, i);
-        load_rows(ta, Ku, start + min(i + 2, nt - 1) * kTile, a.T - 1, g, r); // past the end: re-read, never used
-        consume(tb, i + 1);
-    }
-    if (i < nt) consume(ta, i);
+    KRing ring;
+    ring.init(lds, a.Kp + (size_t)u * a.T * kCD, start, nt, a.T - 1, threadIdx.x, g, r);
+    ring.run(nt, consume);
+    if (NB == 0) return;
 
     // the 16 lanes of a row group hold the shares of the same four queries
 #pragma unroll
-    for (int b = 0; b < NB; ++b)
+    for (int b = 0; b < NBA; ++b)
 #pragma unroll
         for (int v = 0; v < 4; ++v) {
             const float M = row16_max(m[b][v]);
@@ -187,12 +236,13 @@ __global__ __launch_bounds__(64 * kCWaves) void compress_stats_kernel(const Comp
     const int u = bid / a.nspans;
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6, g = lane >> 4, r = lane & 15;
     const int qb0 = (round * kCWaves + wave) * kCBlocks;
-    switch (live_blocks(a, qb0)) { // no barrier in this kernel: a wave without columns just leaves
-    case 4: stats_span<4>(a, u, sp, qb0, g, r); break;
-    case 3: stats_span<3>(a, u, sp, qb0, g, r); break;
-    case 2: stats_span<2>(a, u, sp, qb0, g, r); break;
-    case 1: stats_span<1>(a, u, sp, qb0, g, r); break;
-    default: break;
+    __shared__ __align__(16) unsigned char k_ring[KRing::NSLOT * KRing::SLOT];
+    switch (live_blocks(a, qb0)) { // (uniform over a wave; every wave runs the same barriers inside)
+    case 4: stats_span<4>(a, u, sp, qb0, g, r, k_ring); break;
+    case 3: stats_span<3>(a, u, sp, qb0, g, r, k_ring); break;
+    case 2: stats_span<2>(a, u, sp, qb0, g, r, k_ring); break;
+    case 1: stats_span<1>(a, u, sp, qb0, g, r, k_ring); break;
+    default: stats_span<0>(a, u, sp, qb0, g, r, k_ring); break;
     }
 }
 
@@ -217,43 +267,37 @@ __global__ __launch_bounds__(256) void compress_norm_kernel(const CompressArgs a
 }
 
 // ---- pass 2: votes of the prefix rows of one span, from NB blocks of columns, added into `mine`
+// (NB = 0: a wave without columns in this round, which only helps staging the tiles)
 template <int NB>
-__device__ __forceinline__ void votes_span(const CompressArgs &a, int u, int qb0, int start, int nt, __attribute__((address_space(3))) float *mine, int g, int r)
+__device__ __forceinline__ void votes_span(const CompressArgs &a, int u, int qb0, int start, int nt, __attribute__((address_space(3))) float *mine, int g, int r, unsigned char *lds)
 {
-    QueryBlocks<NB> Q;
-    Q.load(a, u, qb0, g, r);
-    float cq[NB][4];
+    constexpr int NBA = NB > 0 ? NB : 1;
+    QueryBlocks<NBA> Q;
+    if (NB > 0) Q.load(a, u, qb0, g, r);
+    float cq[NBA][4];
 #pragma unroll
-    for (int b = 0; b < NB; ++b)
+    for (int b = 0; b < NBA; ++b)
 #pragma unroll
         for (int v = 0; v < 4; ++v) {
             const int col = 16 * (qb0 + b) + 4 * g + v;
             cq[b][v] = col < a.colsP ? a.cq[(size_t)u * a.colsP + col] : INFINITY; // +inf for an unused column: weight 0
         }
-    const uint16_t *Ku = a.Kp + (size_t)u * a.T * kCD;
     auto consume = [&](const KRows &t, int ti) __attribute__((always_inline)) {
+        if (NB == 0) return;
         float w = 0.f;
 #pragma unroll
-        for (int b = 0; b < NB; ++b) {
+        for (int b = 0; b < NBA; ++b) {
             const f32x4 d = block_logits(Q.q[b], t);
 #pragma unroll
             for (int v = 0; v < 4; ++v) w += fast_exp2(fmaf(d[v], a.scale_log2, -cq[b][v])); // alpha, eq. 1
         }
         // every prefix row is seen by every window query.  The four lanes that hold shares of row r add
-        // them to the wave's own LDS row with a no-return LDS add: nothing to wait for (a cross-lane sum
-        // and a read-modify-write here cost the pass half its time in waits)
+        // them to the wave's own LDS row with a no-return LDS add: nothing to wait for
         __hip_atomic_fetch_add(&mine[ti * kTile + r], w, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WAVEFRONT);
     };
-    KRows ta, tb;
-    if (nt >= 1) load_rows(ta, Ku, start, a.P - 1, g, r);
-    int i = 0;
-    for (; i + 1 < nt; i += 2) {
-        load_rows(tb, Ku, start + (i + 1) * kTile, a.P - 1, g, r);
-        consume(ta, i);
-        load_rows(ta, Ku, start + min(i + 2, nt - 1) * kTile, a.P - 1, g, r); // past the end: re-read, never used
-        consume(tb, i + 1);
-    }
-    if (i < nt) consume(ta, i);
+    KRing ring;
+    ring.init(lds, a.Kp + (size_t)u * a.T * kCD, start, nt, a.P - 1, threadIdx.x, g, r);
+    ring.run(nt, consume);
 }
 
 // grid: units x nspans2; the workgroup takes every round of columns through its span, each wave
@@ -261,6 +305,7 @@ __device__ __forceinline__ void votes_span(const CompressArgs &a, int u, int qb0
 __global__ __launch_bounds__(64 * kCWaves) void compress_votes_kernel(const CompressArgs a)
 {
     extern __shared__ float wave_votes[]; // [kCWaves][LS]
+    __shared__ __align__(16) unsigned char k_ring[KRing::NSLOT * KRing::SLOT];
     const int nspans2 = (a.P + a.LS - 1) / a.LS;
     const int sp = blockIdx.x % nspans2, u = blockIdx.x / nspans2;
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6, g = lane >> 4, r = lane & 15;
@@ -272,13 +317,14 @@ __global__ __launch_bounds__(64 * kCWaves) void compress_votes_kernel(const Comp
     const int rounds = (a.colsP + kColsPerRound - 1) / kColsPerRound;
     for (int round = 0; round < rounds; ++round) {
         const int qb0 = (round * kCWaves + wave) * kCBlocks;
-        switch (live_blocks(a, qb0)) {
-        case 4: votes_span<4>(a, u, qb0, start, nt, mine, g, r); break;
-        case 3: votes_span<3>(a, u, qb0, start, nt, mine, g, r); break;
-        case 2: votes_span<2>(a, u, qb0, start, nt, mine, g, r); break;
-        case 1: votes_span<1>(a, u, qb0, start, nt, mine, g, r); break;
-        default: break;
+        switch (live_blocks(a, qb0)) { // (uniform over a wave; every wave runs the same barriers inside)
+        case 4: votes_span<4>(a, u, qb0, start, nt, mine, g, r, k_ring); break;
+        case 3: votes_span<3>(a, u, qb0, start, nt, mine, g, r, k_ring); break;
+        case 2: votes_span<2>(a, u, qb0, start, nt, mine, g, r, k_ring); break;
+        case 1: votes_span<1>(a, u, qb0, start, nt, mine, g, r, k_ring); break;
+        default: votes_span<0>(a, u, qb0, start, nt, mine, g, r, k_ring); break;
         }
+        __syncthreads(); // the ring is reused by the next round of columns
     }
     __syncthreads();
     for (int i = threadIdx.x; i < end - start; i += 64 * kCWaves) {

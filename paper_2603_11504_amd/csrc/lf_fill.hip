@@ -5,11 +5,11 @@
 // own insert (Sec. 2.1).  All rows are therefore written first, and the queries then go
 // through attention several at a time, each column of the S^T = K Q^T product carrying one
 // (token, head) pair with its own causal row limit.  A 16-column product holds floor(16 / G)
-// tokens, a wave takes NB = 2 such products through every tile it loads, and the eight waves of
-// a workgroup walk the same tiles for eight different sets of tokens: HBM delivers the cache
-// once per 16 * floor(16 / G) tokens
+// tokens, a wave takes NB = 2 such products through every tile, and the eight waves of
+// a workgroup take eight different sets of tokens through the same tiles, staged once in LDS: HBM
+// delivers the cache once per 16 * floor(16 / G) tokens
 // instead of once per token, and the kernel is bound by arithmetic, not by memory.  Being so, it
-// loads K in the natural operand layout (half the matrix instructions for the logits).
+// takes K in the natural operand layout (half the matrix instructions for the logits).
 #include "lf_mfma_stream.h"
 
 namespace lf {
@@ -44,86 +44,98 @@ __global__ __launch_bounds__(256) void fill_insert_kernel(const FillArgs a)
     }
 }
 
-// One workgroup = one (unit, group of NWV * NB * qpb consecutive tokens).  Each of its NWV waves
-// owns NB * qpb of those tokens outright and streams every tile of the rows they see: the waves
-// read the same K/V lines at about the same time, so the cache hierarchy serves all but one of
-// the reads and HBM sees the rows once per NWV * NB * qpb tokens (32 at G = 7), while no wave ever
-// has to merge with another -- there is no LDS traffic and no barrier in this kernel.  NB = 2
-// products per wave leave room for two waves per SIMD, which hide each other's matrix and LDS-free
-// softmax latencies better than one wave with four products does (measured 5 % / 22 % faster on
-// 8192- / 4096-slot caches).
+// One workgroup = one (unit, group of NWV * NB * qpb consecutive tokens).  Each of its NWV waves owns
+// NB * qpb of those tokens outright (no wave ever merges with another) and takes them through every tile
+// of the rows they see.  The tiles are staged through LDS: the 512 threads of the workgroup fetch each
+// K/V tile from device memory once (16 bytes per thread and tile), park it in a ring of four LDS slots,
+// and every wave takes its MFMA operands from there.  (When every wave fetched every tile for itself the
+// caches served seven of the eight fetches, but each still went through the compute unit's vector-memory
+// path, and the counters showed that path -- TA_TA_BUSY 94 % -- not HBM or the matrix pipe as the limit:
+// 6.7 M tokens/s against 9.9 M this way on a 64 x 4 x 8192-slot cache.)  Rows are padded to 272 bytes in LDS so that the 16-byte operand reads of eight
+// neighbouring lanes fall into distinct banks.  One barrier per tile; the fetch of tile i + 4 is issued
+// while tile i is computed, two registers of a thread carry the two fetches in flight.
 template <int NB, int NWV>
 __global__ __launch_bounds__(64 * NWV) void fill_attend_kernel(const FillArgs a)
 {
-    constexpr int D = 128;
-    // causal columns, natural K layout; the weights enter the P V product as single bf16 values (the
-    // matrix pipe is not idle here as it is in the decode step, and the second product for the
-    // low parts costs 8 % of the kernel): an output can differ from the decode step's by one unit in
-    // the last place of bf16
+    static_assert(NWV == 8, "one 16-byte fetch per thread and tile: 512 threads for 8 KiB of K and V");
+    constexpr int D = 128, RS = 272, SLOT = 2 * kTile * RS, NSLOT = 4;
     typedef MfmaStreamer<1, false, kStashNone, false, true, false, true> Streamer;
+    __shared__ __align__(16) unsigned char ring[NSLOT * SLOT];
     const int G = a.G, units = a.units, QW = NB * a.qpb;
     const int ngroups = (a.Tb + NWV * QW - 1) / (NWV * QW);
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, g = lane >> 4, r = lane & 15;
     // late tokens see the most rows: their groups go first
     const int qg = ngroups - 1 - (int)(blockIdx.x / units), u = blockIdx.x % units;
     const int t0 = (qg * NWV + wave) * QW;
-    if (t0 >= a.Tb) return; // the last group may be short of waves
+    const bool has_tokens = t0 < a.Tb; // the last group may be short of waves: those only help staging
     const int tl = min(t0 + QW, a.Tb) - 1;
-    const int n_max = a.n0 + tl + 1;
+    const int n_max = has_tokens ? a.n0 + tl + 1 : 0;                  // rows this wave's tokens see
+    const int wg_nmax = a.n0 + min((qg + 1) * NWV * QW, a.Tb);         // rows the workgroup's last token sees
+    const int nt = (wg_nmax + kTile - 1) / kTile;
     const int qi = r / G, h_of_r = r % G;
 
     Streamer st[NB];
 #pragma unroll
     for (int nb = 0; nb < NB; ++nb) {
         const int t = t0 + nb * a.qpb + qi;
-        const bool used = qi < a.qpb && t <= tl;
+        const bool used = has_tokens && qi < a.qpb && t <= tl;
         st[nb].init_column(used ? (g_cu16p)(a.q + (((size_t)t * units + u) * G + h_of_r) * D) : (g_cu16p) nullptr, a.n0 + t + 1, lane, a.scale_log2);
-        st[nb].Ku = (g_cu16p)(a.Kc + (size_t)u * a.N * D);
-        st[nb].Vu = (g_cu16p)(a.Vc + (size_t)u * a.N * D);
         st[nb].start = 0;
         st[nb].end = n_max;
     }
 
-    // ---- stream every tile of rows [0, n_max); two register tiles rotate
+    // staging role of this thread: 16 bytes of row st_row of the K tile (threads 0..255) or the V tile
+    const int st_row = (tid & 255) >> 4, st_chunk = tid & 15;
+    const g_cu16p src = (g_cu16p)((tid < 256 ? a.Kc : a.Vc) + (size_t)u * a.N * D) + st_chunk * 8;
+    const int st_off = (tid < 256 ? 0 : kTile * RS) + st_row * RS + st_chunk * 16;
+    auto fetch = [&](int ti) __attribute__((always_inline)) { // rows past the last one the workgroup sees: that row again
+        return *(g_cu32x4p)(src + (size_t)min(min(ti, nt - 1) * kTile + st_row, wg_nmax - 1) * D);
+    };
+    auto park = [&](int ti, u32x4 v) __attribute__((always_inline)) { *(u32x4 *)(ring + (ti % NSLOT) * SLOT + st_off) = v; };
+    // operands of tile ti from LDS, in the layouts the streaming core computes from (natural K layout)
+    auto operands = [&](TileRegs &t, int ti) __attribute__((always_inline)) {
+        const unsigned char *base = ring + (ti % NSLOT) * SLOT;
+#pragma unroll
+        for (int c = 0; c < 4; ++c) t.k[c >> 1][c & 1] = *(const u32x4 *)(base + r * RS + 64 * c + 16 * g);
+#pragma unroll
+        for (int e = 0; e < 4; ++e) t.v[e] = *(const u32x4 *)(base + (kTile + 4 * g + e) * RS + 16 * r);
+    };
+    const int first_limit = a.n0 + t0 + 1; // rows the wave's first token sees; later tokens see more
+    auto compute = [&](TileRegs &t, int ti) __attribute__((always_inline)) {
+        if (ti * kTile >= n_max) return; // past what this wave's tokens see (uniform over the wave)
+        Streamer::build_v_in_place(t);
+        const bool cmask_now = (ti + 1) * kTile > first_limit;
+#pragma unroll
+        for (int nb = 0; nb < NB; ++nb) st[nb].template compute_core<false, true, true>(t, ti, cmask_now);
+    };
+
+    // ---- every thread of the workgroup runs the same nt rounds (one barrier each)
     {
-        const int nfull = n_max / kTile;
+        u32x4 q0 = fetch(0), q1 = fetch(1);
+        park(0, q0);
+        park(1, q1);
+        q0 = fetch(2);
+        q1 = fetch(3);
+        __syncthreads();
         TileRegs ta, tb;
-        // Per tile the V operands are built once for all the wave's products, and the causal test is
-        // skipped on tiles that every one of the wave's tokens sees whole (all but the last few): both
-        // come out of the vector-instruction budget that bounds this kernel.
-        const int first_limit = a.n0 + t0 + 1; // rows the wave's first token sees; later tokens see more
-        auto compute = [&](TileRegs &t, int ti) __attribute__((always_inline)) {
-            Streamer::build_v_in_place(t);
-            const bool cmask_now = (ti + 1) * kTile > first_limit;
-#pragma unroll
-            for (int nb = 0; nb < NB; ++nb) st[nb].template compute_core<false, true, true>(t, ti, cmask_now);
-        };
-        if (nfull >= 2) {
-            st[0].template load_tile<false>(ta, 0);
-            st[0].template load_tile<false>(tb, 1);
-            int i = 0;
-            for (; i + 3 < nfull; i += 2) {
-                compute(ta, i);
-                st[0].template load_tile<false>(ta, i + 2);
-                compute(tb, i + 1);
-                st[0].template load_tile<false>(tb, i + 3);
-            }
+        operands(ta, 0);
+        for (int i = 0; i < nt; i += 2) {
+            // round i: tile i + 2 goes to LDS (its fetch was issued two rounds ago), tile i + 4 is requested
+            park(i + 2, q0);
+            q0 = fetch(i + 4);
+            operands(tb, i + 1); // parked a round ago, barrier since
             compute(ta, i);
-            if (i + 2 < nfull) st[0].template load_tile<false>(ta, i + 2);
-            compute(tb, i + 1);
-            if (i + 2 < nfull) compute(ta, i + 2);
-        } else if (nfull == 1) {
-            st[0].template load_tile<false>(ta, 0);
-            compute(ta, 0);
-        }
-        if (n_max % kTile != 0) {
-            st[0].template load_tile<true>(ta, nfull);
-            st[0].template zero_ragged<true>(ta, nfull);
-            Streamer::build_v_in_place(ta);
-#pragma unroll
-            for (int nb = 0; nb < NB; ++nb) st[nb].template compute_core<true, true, true>(ta, nfull);
+            __syncthreads();
+            if (i + 1 < nt) {
+                park(i + 3, q1);
+                q1 = fetch(i + 5);
+                operands(ta, i + 2);
+                compute(tb, i + 1);
+                __syncthreads();
+            }
         }
     }
+    if (!has_tokens) return;
 
     // ---- normalise and store: a lane holds channels 8r .. 8r+7 of columns 4g .. 4g+3; the
     // denominator of column c is complete in lane c once the four lane-partials are added
