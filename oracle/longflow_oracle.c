@@ -45,7 +45,10 @@
  * Prompt compression (lfo_compress_prompt): a prompt longer than the budget is
  * cut to the budget once, before decoding, by the observation-window voting of
  * SnapKV, which the paper names for this (Sec. 4.1) without restating it; the
- * reading taken is written out at the function.
+ * reading taken is written out at the function.  The paper prints nothing this
+ * step could be checked against: "parity unpinned" by the paper; the function is
+ * pinned to the reading (library softmax per window query, numpy convolution for
+ * the pooling, a stable sort for the selection, a closed form for equal keys).
  *
  * The method reaches these plain definitions exactly (the fused kernel of
  * Alg. 1 is only a faster route), so the oracle IS the definitions written
