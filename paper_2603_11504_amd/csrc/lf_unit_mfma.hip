@@ -328,23 +328,7 @@ __global__ __launch_bounds__(512, 1) void unit_mfma_kernel(const UnitArgs a_in, 
     // later loads of the row are ordered behind the stores.  The row is written through to
     // the device-wide coherence point: with several workgroups per unit, the one that ends
     // up re-scoring candidates may sit on another XCD and must not see the old row.
-    const int ins_slot = (STASH != kStashNone) ? pending[u] : -1;
-    if (STASH != kStashNone) {
-        const int slot = ins_slot;
-        if (slot >= start && slot < start + a.split_len && slot < N && (((slot - start) / kTile) % NW) == wave) {
-            typedef __attribute__((address_space(1))) const uint32_t *g_cu32p;
-            st_agent((g_u32p)(Ku + (size_t)slot * D) + lane, *((g_cu32p)(k_new + (size_t)u * D) + lane));
-            st_agent((g_u32p)(Vu + (size_t)slot * D) + lane, *((g_cu32p)(v_new + (size_t)u * D) + lane));
-            // every 16-lane row sums |v_new| redundantly; lane 0 stores the log2 norm
-            const u32x4 vv = *(g_cu32x4p)(v_new + (size_t)u * D + 8 * r);
-            float a1 = fabsf(bf16_lo(vv.x)) + fabsf(bf16_hi(vv.x)) + fabsf(bf16_lo(vv.y)) + fabsf(bf16_hi(vv.y)) +
-                       fabsf(bf16_lo(vv.z)) + fabsf(bf16_hi(vv.z)) + fabsf(bf16_lo(vv.w)) + fabsf(bf16_hi(vv.w));
-            a1 = row16_sum(a1);
-            if (lane == 0) lu_u[(slot & ~15) + pos_of_slot(slot & 15)] = __builtin_amdgcn_logf(a1);
-            __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
-            asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
-        }
-    }
+    const int ins_slot = (STASH != kStashNone) ? pending[u] : -1; // requested first, used after the query loads below have been issued
 
     // Copies of the query -- LDS for the exact re-scoring, device memory for a later
     // longflow_scores() -- are made now: their load latency hides behind the streaming
@@ -365,6 +349,24 @@ __global__ __launch_bounds__(512, 1) void unit_mfma_kernel(const UnitArgs a_in, 
     st.ls_code = ls_code;
     st.ls_ref = ls_ref;
     st.code_stride = a.code_stride;
+
+    if (STASH != kStashNone) {
+        const int slot = ins_slot;
+        if (slot >= start && slot < start + a.split_len && slot < N && (((slot - start) / kTile) % NW) == wave) {
+            typedef __attribute__((address_space(1))) const uint32_t *g_cu32p;
+            st_agent((g_u32p)(Ku + (size_t)slot * D) + lane, *((g_cu32p)(k_new + (size_t)u * D) + lane));
+            st_agent((g_u32p)(Vu + (size_t)slot * D) + lane, *((g_cu32p)(v_new + (size_t)u * D) + lane));
+            // every 16-lane row sums |v_new| redundantly; lane 0 stores the log2 norm
+            const u32x4 vv = *(g_cu32x4p)(v_new + (size_t)u * D + 8 * r);
+            float a1 = fabsf(bf16_lo(vv.x)) + fabsf(bf16_hi(vv.x)) + fabsf(bf16_lo(vv.y)) + fabsf(bf16_hi(vv.y)) +
+                       fabsf(bf16_lo(vv.z)) + fabsf(bf16_hi(vv.z)) + fabsf(bf16_lo(vv.w)) + fabsf(bf16_hi(vv.w));
+            a1 = row16_sum(a1);
+            if (lane == 0) lu_u[(slot & ~15) + pos_of_slot(slot & 15)] = __builtin_amdgcn_logf(a1);
+            __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
+            asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+        }
+    }
+
     st.run(wave);
 
     // ---- merge the softmax states of the 8 waves
