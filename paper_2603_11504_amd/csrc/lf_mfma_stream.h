@@ -370,18 +370,41 @@ struct MfmaStreamer {
     // Three register tiles rotate: while one is consumed the other two are in flight; the
     // steady-state body has no branch between a load and its use, so each wait covers
     // exactly the oldest tile.
+    // The first three tiles of a wave's share can be requested ahead of run() (a kernel that has other
+    // latencies to sit out before streaming, such as finding out which slot to insert into): returns
+    // whether it did (only shares of at least three full tiles are started this way).  The caller
+    // re-requests a tile whose rows it changes afterwards.
+    __device__ __forceinline__ bool request_first_tiles(int wave, TileRegs &ta, TileRegs &tb, TileRegs &tc) const
+    {
+        const int nfull = (end - start) / kTile;
+        const int n_my = (nfull > wave) ? (nfull - wave + NWAVES - 1) / NWAVES : 0;
+        if (n_my < 3) return false;
+        load_tile<false>(ta, wave);
+        load_tile<false>(tb, wave + NWAVES);
+        load_tile<false>(tc, wave + NWAVES * 2);
+        return true;
+    }
+
     __device__ __forceinline__ void run(int wave)
+    {
+        TileRegs ta, tb, tc;
+        run(wave, ta, tb, tc, false);
+    }
+
+    // requested: ta, tb, tc already hold (requests for) the wave's first three tiles
+    __device__ __forceinline__ void run(int wave, TileRegs &ta, TileRegs &tb, TileRegs &tc, bool requested)
     {
         const int nfull = (end - start) / kTile;
         const bool ragged = (end - start) % kTile != 0;
         const int n_my = (nfull > wave) ? (nfull - wave + NWAVES - 1) / NWAVES : 0;
-        TileRegs ta, tb, tc;
         if (n_my >= 3) {
             // prologue loads are unconditional inside this branch: the waits in the loop
             // then cover exactly the oldest tile and leave the younger loads in flight
-            load_tile<false>(ta, wave);
-            load_tile<false>(tb, wave + NWAVES);
-            load_tile<false>(tc, wave + NWAVES * 2);
+            if (!requested) {
+                load_tile<false>(ta, wave);
+                load_tile<false>(tb, wave + NWAVES);
+                load_tile<false>(tc, wave + NWAVES * 2);
+            }
             int i = 0;
             for (; i + 5 < n_my; i += 3) {
                 compute_tile<false>(ta, wave + NWAVES * i);

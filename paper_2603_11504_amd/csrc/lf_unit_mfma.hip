@@ -349,6 +349,10 @@ __global__ __launch_bounds__(512, 1) void unit_mfma_kernel(const UnitArgs a_in, 
     st.ls_code = ls_code;
     st.ls_ref = ls_ref;
     st.code_stride = a.code_stride;
+    // the wave's first tiles are requested before anything waits for the pending slot: one trip to
+    // memory for slot, query and tiles together at the start of the kernel instead of two
+    TileRegs ta, tb, tc;
+    const bool requested = st.request_first_tiles(wave, ta, tb, tc);
 
     if (STASH != kStashNone) {
         const int slot = ins_slot;
@@ -364,10 +368,17 @@ __global__ __launch_bounds__(512, 1) void unit_mfma_kernel(const UnitArgs a_in, 
             if (lane == 0) lu_u[(slot & ~15) + pos_of_slot(slot & 15)] = __builtin_amdgcn_logf(a1);
             __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
             asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+            // a tile requested above may hold the row as it was: ask for it again, behind the stores
+            if (requested) {
+                const int ti = (slot - start) / kTile;
+                if (ti == wave) st.template load_tile<false>(ta, ti);
+                else if (ti == wave + NW) st.template load_tile<false>(tb, ti);
+                else if (ti == wave + 2 * NW) st.template load_tile<false>(tc, ti);
+            }
         }
     }
 
-    st.run(wave);
+    st.run(wave, ta, tb, tc, requested);
 
     // ---- merge the softmax states of the 8 waves
     {

@@ -195,6 +195,46 @@ def test_insert_lands_in_named_slot_at_tile_and_split_edges(flags):
         np.testing.assert_array_equal(W.to_f64(gpu.k_cache).reshape(Kc.shape), Kc)
 
 
+@pytest.mark.parametrize("flags", [0, lf.LF_FLAG_FORCE_UNIT, lf.LF_FLAG_FORCE_SPLIT], ids=["default", "unit", "split"])
+def test_a_dominant_new_token_is_attended_in_whatever_tile_it_lands(flags):
+    # The heads of a group share one query, the new token's key is that query scaled up, its value is a
+    # constant: the output must be that constant.  A kernel that streamed the slot's old row (say from a
+    # tile it had requested before the insert) would return the cache's average instead.  The slots lie in
+    # a wave's first, second and third tile, just behind them, and at the ends.
+    wl = _small("dominant", "bf16", 3, 14, 2, 128, 1024, n_init=1023, steps=1, seed=41)
+    rep, gpu, ora = run_lockstep(wl, steps=1, flags=flags)
+    G, D = wl.group, 128
+    def put(slot, t, dominant):
+        pend = np.full((wl.units, 1), slot, dtype=np.int32)
+        gpu.set_pending(torch.from_numpy(pend.reshape(wl.batch, wl.kv_heads)))
+        ora.set_pending(pend)
+        q, k, v = W.host_step(wl, t)
+        if dominant:
+            q = np.repeat(q.reshape(wl.batch, wl.kv_heads, G, D)[:, :, :1], G, axis=2).reshape(q.shape)
+            k = W.round_to_storage(4.0 * q.reshape(wl.batch, wl.kv_heads, G, D)[:, :, 0], "bf16").reshape(k.shape)
+            v = np.full_like(v, 3.0)
+        return q, k, v
+
+    prev = None
+    for t, slot in enumerate([5, 16 * 8 + 3, 16 * 9 + 1, 16 * 23 + 15, 16 * 24, 16 * 30 + 7, 0, 1023], start=1):
+        if prev is not None:   # an ordinary token takes the last dominant one's place first
+            q, k, v = put(prev, 100 + t, False)
+            gpu.decode_step(*(W.to_torch(x, wl, "cuda") for x in (q, k, v)))
+            ora.step(q.astype(np.float64).reshape(wl.units, G, D), k.astype(np.float64).reshape(wl.units, 1, D),
+                     v.astype(np.float64).reshape(wl.units, 1, D))
+        prev = slot
+        q, k, v = put(slot, t, True)
+        out, idx = gpu.decode_step(*(W.to_torch(x, wl, "cuda") for x in (q, k, v)))
+        torch.cuda.synchronize()
+        o_ref, i_ref = ora.step(q.astype(np.float64).reshape(wl.units, G, D), k.astype(np.float64).reshape(wl.units, 1, D),
+                                v.astype(np.float64).reshape(wl.units, 1, D))
+        o_gpu = W.to_f64(out).reshape(o_ref.shape)
+        assert np.abs(o_ref - 3.0).max() < 0.3                       # the construction works: the new token takes the weight
+        assert np.abs(o_gpu - o_ref).max() <= 2e-2, f"slot {slot}"
+        compare_indices(idx.cpu().numpy(), i_ref, ora.scores(), True, rep, where=f"slot {slot}")
+    gpu.close()
+
+
 @pytest.mark.parametrize("flags", [lf.LF_FLAG_FORCE_SPLIT, lf.LF_FLAG_FORCE_UNIT], ids=["split", "unit"])
 def test_exact_ties_evict_the_lowest_index(flags):
     # two bit-identical rows that are jointly the least important: the tie is exact in
