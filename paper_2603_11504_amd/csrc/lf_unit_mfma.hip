@@ -749,22 +749,40 @@ __global__ __launch_bounds__(512, 1) void unit_mfma_kernel(const UnitArgs a_in, 
                             for (int e = 0; e < 4; ++e) s4[it][e] += code_term(c4[it], e, f[it]);
                         }
                     }
+                    uint32_t redo = 0u; // items with a code at a clamp
 #pragma unroll
                     for (int it = 0; it < NI; ++it) {
                         if (live[it]) {
                             const int item = it * 512 + tid;
-                            float ub4[4];
                             if (clamped[it] & 0x80808080u) {
-                                decode_item(item, ub4, lbs[it]); // two-sided sums
+                                redo |= 1u << it;
                             } else {
+                                float ub4[4];
 #pragma unroll
                                 for (int e = 0; e < 4; ++e) {
                                     const int slot = ((4 * item) & ~15) + slot_of_pos((4 * item + e) & 15);
                                     ub4[e] = lbs[it][e] = slot < n ? s4[it][e] : INFINITY;
                                 }
+                                ub_min = fminf(ub_min, fminf(fminf(ub4[0], ub4[1]), fminf(ub4[2], ub4[3])));
                             }
-                            ub_min = fminf(ub_min, fminf(fminf(ub4[0], ub4[1]), fminf(ub4[2], ub4[3])));
                         }
+                    }
+                    // The rare items take the two-sided sums in a loop of their own, so that the kernel
+                    // holds that code once per pass and not once per item (the tail of a workgroup runs
+                    // once, out of a cold instruction cache: its size is its cost).
+#pragma nounroll
+                    while (redo) {
+                        const int it = __ffs(redo) - 1;
+                        redo &= redo - 1u;
+                        float ub4[4], lb4[4];
+                        decode_item(it * 512 + tid, ub4, lb4);
+#pragma unroll
+                        for (int j = 0; j < NI; ++j) { // selects, not an indexed store: lbs stays in registers
+                            const bool hit = j == it;
+#pragma unroll
+                            for (int e = 0; e < 4; ++e) lbs[j][e] = hit ? lb4[e] : lbs[j][e];
+                        }
+                        ub_min = fminf(ub_min, fminf(fminf(ub4[0], ub4[1]), fminf(ub4[2], ub4[3])));
                     }
                 };
                 for (int cb = 0; cb < a.gstride; cb += span) {
