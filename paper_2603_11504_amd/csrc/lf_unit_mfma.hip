@@ -793,9 +793,22 @@ __global__ __launch_bounds__(512, 1) void unit_mfma_kernel(const UnitArgs a_in, 
                     else pass(std::integral_constant<int, kRegIters>{}, cb);
                 }
                 const float thr = block_min(ub_min) * kScreenWindow;
+                // one bit per position of the thread that may hold the minimum; the (few) set bits are
+                // listed by one loop, so the kernel holds the listing code once and not per register
+                uint32_t hits = 0u;
 #pragma unroll
                 for (int it = 0; it < kRegIters; ++it)
-                    if (it < iters) list_candidates(it * 512 + tid, lbs[it], thr);
+#pragma unroll
+                    for (int e = 0; e < 4; ++e)
+                        if (it < iters && lbs[it][e] <= thr) hits |= 1u << (4 * it + e);
+#pragma nounroll
+                while (hits) {
+                    const int b = __ffs(hits) - 1;
+                    hits &= hits - 1u;
+                    const int pos = 4 * ((b >> 2) * 512 + tid) + (b & 3);
+                    const int k = atomicAdd(&cand_count, 1);
+                    if (k < kMaxCand) cand_list[k] = (pos & ~15) + slot_of_pos(pos & 15);
+                }
             } else { // budgets beyond the register window: decode twice (dump chunks are copied twice)
                 float thr = 0.f;
                 for (int pass = 0; pass < 2; ++pass) {
@@ -849,8 +862,16 @@ __global__ __launch_bounds__(512, 1) void unit_mfma_kernel(const UnitArgs a_in, 
                         if (coop) { merge_out(); out_stored = true; }
                         else if (o_separate) { store_out(); out_stored = true; }
                     }
-                    if (use0) take(__shfl(score_row(r0, qs, G, sM, sL, lane), 0), cand_list[c0]);
-                    if (use1) take(__shfl(score_row(r1, qs, G, sM, sL, lane), 0), cand_list[c1]);
+                    // (both rows through one copy of the scoring code: the second moves into the first's registers)
+                    bool use = use0;
+                    int c = c0;
+#pragma nounroll
+                    for (int k = 0; k < 2; ++k) {
+                        if (use) take(__shfl(score_row(r0, qs, G, sM, sL, lane), 0), cand_list[c]);
+                        r0 = r1;
+                        use = use1;
+                        c = c1;
+                    }
                 }
             } else {
                 // Far more candidates than the list holds: scores underflowing en masse, or many
