@@ -48,7 +48,7 @@ struct UnitArgs {
     uint8_t *gcode;                    // [units][G][gstride] dumped codes, absolute positions
     float *gref;                       // [units][ntiles][G] dumped references
     int n, N, G, ntiles;
-    int S, s_active, split_len;        // split_len: slots per workgroup, a multiple of 128
+    int S, s_active, split_len;        // split_len: slots per workgroup, a multiple of 256
     int code_stride, gstride;          // LDS / dump row strides in bytes
     int merge_off;                     // byte offset of the O-merge area in dynamic LDS (0 with one
                                        // workgroup per unit: the area then aliases the codes)
@@ -98,6 +98,10 @@ __device__ __forceinline__ int add_agent(int32_t *p, int v)
     typedef __attribute__((address_space(1))) int32_t *gptr;
     return __hip_atomic_fetch_add((gptr)p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
 }
+// cache-policy operand of the loads that write LDS directly: the sc1 bit, i.e. device scope, what
+// ld_agent's loads carry (the data comes from the coherence point, not from this XCD's L2)
+constexpr int kAuxDeviceScope = 16;
+typedef __attribute__((address_space(1))) const uint32_t *g_cu32p;
 // all of this thread's device-scope stores have reached the coherence point
 __device__ __forceinline__ void wait_stores() { asm volatile("s_waitcnt vmcnt(0)" ::: "memory"); }
 
@@ -158,7 +162,6 @@ struct RowRegs {
 __device__ __forceinline__ void load_row(RowRegs &rr, g_cu16p krow, g_cu16p vrow, int lane, bool coherent)
 {
     const int part = lane & 3;
-    typedef __attribute__((address_space(1))) const uint32_t *g_cu32p;
     rr.vv = coherent ? ld_agent((g_cu32p)vrow + lane) : *(g_cu32p)(vrow + 2 * lane);
 #pragma unroll
     for (int c = 0; c < 4; ++c) {
@@ -357,7 +360,6 @@ __global__ __launch_bounds__(512, 1) void unit_mfma_kernel(const UnitArgs a_in, 
     if (STASH != kStashNone) {
         const int slot = ins_slot;
         if (slot >= start && slot < start + a.split_len && slot < N && (((slot - start) / kTile) % NW) == wave) {
-            typedef __attribute__((address_space(1))) const uint32_t *g_cu32p;
             st_agent((g_u32p)(Ku + (size_t)slot * D) + lane, *((g_cu32p)(k_new + (size_t)u * D) + lane));
             st_agent((g_u32p)(Vu + (size_t)slot * D) + lane, *((g_cu32p)(v_new + (size_t)u * D) + lane));
             // every 16-lane row sums |v_new| redundantly; lane 0 stores the log2 norm
@@ -464,57 +466,38 @@ __global__ __launch_bounds__(512, 1) void unit_mfma_kernel(const UnitArgs a_in, 
     const int chunk_len = coop ? a.chunk_len : 0;
     uint8_t *rem_code = smem + a.merge_off;
     float *rem_ref = (float *)(rem_code + (size_t)G * chunk_len);
-    // Copy the dumps of positions [cb, cb + chunk_len) into LDS, references as dumped (they are
-    // rescaled once the unit-wide softmax state is known).  The own range inside the chunk,
-    // [lo, hi) relative to cb, is skipped: its codes are in LDS already.  All loads of a round
-    // are requested before any is used: every device-scope load is a trip to the coherence
-    // point, and a batch of them costs about one.
+    // Copy the dumps of positions [cb, cb + chunk_len) into LDS, references as dumped.  The own range
+    // inside the chunk, [lo, hi) relative to cb, is skipped for the codes (they are in LDS already);
+    // the references, a quarter of the volume, are copied whole.  The loads write LDS directly
+    // (`global_load_lds_dword`, device scope): a wave instruction moves 256 consecutive bytes, no
+    // register holds anything, so ONE short loop has every load of the chunk in flight at once --
+    // every device-scope load is a trip to the coherence point and a batch of them costs about one --
+    // and the code is a few dozen instructions where a register-staged batch took over a thousand
+    // (this runs once per launch, in the serial tail of the deciding workgroup: its instruction count
+    // is its cost).  Ranges are whole runs: split_len and chunk_len are multiples of 256.
+    // gather_wait() before the barrier behind which the chunk is read.
+    typedef __attribute__((address_space(3))) void *lds_vp;
+    typedef __attribute__((address_space(1))) const uint8_t *g_cu8p;
     auto gather_chunk = [&](int cb) __attribute__((always_inline)) {
-        constexpr int kBatch = 16;
-        const int lo = min(max(start - cb, 0), chunk_len), hi = min(max(own_hi - cb, 0), chunk_len);
+        const int lo = min(max(start - cb, 0), chunk_len), hi = min(max(start + a.split_len - cb, 0), chunk_len);
         const int skip = hi - lo;
-        const int top = a.gstride - 8; // last 8-byte word of a dump row
-        const int per_h = (chunk_len - skip) / 8;
-        const int nw = G * per_h;                             // 8-byte words of codes
-        const int tl = lo / kTile, tskip = skip / kTile;
-        const int nr = (chunk_len / kTile - tskip) * G;       // references, half as many
-        for (int i0 = 0; i0 < nw; i0 += 512 * kBatch) {
-            unsigned long long v[kBatch];
-            float rv[kBatch / 2];
-            int off[kBatch], roff[kBatch / 2];
-#pragma unroll
-            for (int k = 0; k < kBatch; ++k) {
-                const int i = i0 + k * 512 + tid;
-                v[k] = 0;
-                off[k] = 0;
-                if (i < nw) {
-                    const int h = i / per_h;
-                    int o = 8 * (i % per_h);
-                    if (o >= lo) o += skip;
-                    off[k] = h * chunk_len + o;
-                    v[k] = ld_agent((const unsigned long long *)(a.gcode + ((size_t)u * G + h) * a.gstride + min(cb + o, top)));
-                }
+        const int runs_per_h = (chunk_len - skip) / 256;
+        const int last = a.gstride - 4; // last word of a dump row: positions beyond it are dead
+        for (int h = 0; h < G; ++h) {
+            const g_cu8p row = (g_cu8p)a.gcode + ((size_t)u * G + h) * a.gstride;
+            for (int j = wave; j < runs_per_h; j += NW) {
+                int o = 256 * j;
+                if (o >= lo) o += skip;
+                __builtin_amdgcn_global_load_lds((g_cu32p)(row + min(cb + o + 4 * lane, last)),
+                                                 (lds_vp)(rem_code + (size_t)h * chunk_len + o), 4, 0, kAuxDeviceScope);
             }
-#pragma unroll
-            for (int k = 0; k < kBatch / 2; ++k) {
-                const int i = i0 / 2 + k * 512 + tid;
-                rv[k] = 0.f;
-                roff[k] = 0;
-                if (i < nr) {
-                    int t = i / G;
-                    if (t >= tl) t += tskip;
-                    roff[k] = t * G + i % G;
-                    rv[k] = ld_agent(&a.gref[((size_t)u * a.ntiles + min(cb / kTile + t, a.ntiles - 1)) * G + i % G]);
-                }
-            }
-#pragma unroll
-            for (int k = 0; k < kBatch; ++k)
-                if (i0 + k * 512 + tid < nw) *(unsigned long long *)(rem_code + off[k]) = v[k];
-#pragma unroll
-            for (int k = 0; k < kBatch / 2; ++k)
-                if (i0 / 2 + k * 512 + tid < nr) rem_ref[roff[k]] = rv[k];
         }
+        const int have = (a.ntiles - cb / kTile) * G; // references from cb to the end of the unit
+        const g_cf32p src = (g_cf32p)a.gref + ((size_t)u * a.ntiles + cb / kTile) * G;
+        for (int j = wave; 64 * j < (chunk_len / kTile) * G; j += NW)
+            __builtin_amdgcn_global_load_lds(src + min(64 * j + lane, have - 1), (lds_vp)(rem_ref + 64 * j), 4, 0, kAuxDeviceScope);
     };
+    auto gather_wait = [&]() __attribute__((always_inline)) { asm volatile("s_waitcnt vmcnt(0)" ::: "memory"); };
     // A code c of head h in a tile whose reference the streaming left at `ref` stands for the term
     // 2^(ref + sLg[h] - c/4) of the score: one conversion, one multiply-add and one exponential per
     // code, no table (a 256-entry table in LDS cost more in bank conflicts than the exponentials do).
@@ -584,6 +567,7 @@ __global__ __launch_bounds__(512, 1) void unit_mfma_kernel(const UnitArgs a_in, 
             sL[tid] = Ls;
             sLg[tid] = kCodeBias - M - __builtin_amdgcn_logf(Ls);
         }
+        gather_wait();
         __syncthreads();
     } else if (o_separate && STASH == kStashLds) {
         stage_o(); // read back below, after the barriers of the decision
@@ -701,6 +685,7 @@ __global__ __launch_bounds__(512, 1) void unit_mfma_kernel(const UnitArgs a_in, 
                 __syncthreads(); // the previous chunk has been read by everyone
                 chunk_base = cb;
                 gather_chunk(cb);
+                gather_wait();
                 __syncthreads();
             };
             float ub_min = INFINITY;
@@ -956,7 +941,7 @@ int unit_mfma_splits(int units, int N)
 int unit_mfma_split_len(int N, int S)
 {
     const int per = (N + S - 1) / S;
-    return (per + 127) / 128 * 128;
+    return (per + 255) / 256 * 256; // whole rounds of the 8 waves' tiles, and whole 256-byte runs of the code exchange
 }
 
 // How a workgroup's dynamic LDS is laid out for S workgroups per unit.
@@ -983,13 +968,14 @@ static UnitLds unit_lds(int N, int G, bool stash, int S)
     // alone holds), at most all of them.
     l.merge_off = codes;
     const size_t per_pos4 = (size_t)G * 5; // bytes per 4 positions
-    const size_t avail = kUnitLdsLimit > codes ? kUnitLdsLimit - codes : 0;
+    constexpr size_t kRefSlack = 256;      // the references arrive in runs of 64: the last one may overshoot
+    const size_t avail = kUnitLdsLimit > codes + kRefSlack ? kUnitLdsLimit - codes - kRefSlack : 0;
     long long fit = (long long)(avail * 4 / per_pos4) / 2048 * 2048;
     const long long all = (((long long)N + kTile - 1) / kTile * kTile + 2047) / 2048 * 2048;
     if (fit > all) fit = all;
     if (fit < 2048) fit = 2048;
     l.chunk_len = (int)fit;
-    l.bytes = codes + std::max((size_t)fit * per_pos4 / 4, merge_bytes(G));
+    l.bytes = codes + std::max((size_t)fit * per_pos4 / 4 + kRefSlack, merge_bytes(G));
     return l;
 }
 
