@@ -348,7 +348,10 @@ struct MfmaStreamer {
 #pragma unroll
             for (int e = 0; e < 4; ++e) {
                 // 4 * (bias - log2(u p)), rounded, clamped to a byte
-                const float c = __builtin_amdgcn_fmed3f(rintf(fmaf(t.lu[e] + lg[e], -4.f, 4.f * kCodeBias)), 0.f, 255.f);
+                float c = __builtin_amdgcn_fmed3f(rintf(fmaf(t.lu[e] + lg[e], -4.f, 4.f * kCodeBias)), 0.f, 255.f);
+                // a position past the last slot carries the clamp code whatever its side-array entry holds:
+                // the screening sends clamped codes through its exact path, which knows the slot count
+                if (RAGGED && base + slot_off(e) >= end) c = 255.f;
                 code = __builtin_amdgcn_cvt_pk_u8_f32(c, e, code);
             }
             if (r < G) {

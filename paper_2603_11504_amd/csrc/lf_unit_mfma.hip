@@ -738,17 +738,14 @@ __global__ __launch_bounds__(512, 1) void unit_mfma_kernel(const UnitArgs a_in, 
 #pragma unroll
                     for (int it = 0; it < NI; ++it) {
                         if (live[it]) {
-                            const int item = it * 512 + tid;
                             if (clamped[it] & 0x80808080u) {
                                 redo |= 1u << it;
                             } else {
-                                float ub4[4];
+                                // (a position past the last slot carries the clamp code 255 -- the streaming
+                                // writes it so -- and has sent its item down the other branch)
 #pragma unroll
-                                for (int e = 0; e < 4; ++e) {
-                                    const int slot = ((4 * item) & ~15) + slot_of_pos((4 * item + e) & 15);
-                                    ub4[e] = lbs[it][e] = slot < n ? s4[it][e] : INFINITY;
-                                }
-                                ub_min = fminf(ub_min, fminf(fminf(ub4[0], ub4[1]), fminf(ub4[2], ub4[3])));
+                                for (int e = 0; e < 4; ++e) lbs[it][e] = s4[it][e];
+                                ub_min = fminf(ub_min, fminf(fminf(s4[it][0], s4[it][1]), fminf(s4[it][2], s4[it][3])));
                             }
                         }
                     }
@@ -770,13 +767,18 @@ __global__ __launch_bounds__(512, 1) void unit_mfma_kernel(const UnitArgs a_in, 
                         ub_min = fminf(ub_min, fminf(fminf(ub4[0], ub4[1]), fminf(ub4[2], ub4[3])));
                     }
                 };
-                for (int cb = 0; cb < a.gstride; cb += span) {
-                    next_chunk(cb);
-                    if (iters <= 1) pass(std::integral_constant<int, 1>{}, cb);
-                    else if (iters <= 2) pass(std::integral_constant<int, 2>{}, cb);
-                    else if (iters <= 4) pass(std::integral_constant<int, 4>{}, cb);
-                    else pass(std::integral_constant<int, kRegIters>{}, cb);
-                }
+                // (the item count is dispatched on outside the loop over chunks: inside it, the compiler
+                // hoists every instantiation's invariants in front of the loop and all of them are paid)
+                auto all_chunks = [&](auto ni_tag) __attribute__((always_inline)) {
+                    for (int cb = 0; cb < a.gstride; cb += span) {
+                        next_chunk(cb);
+                        pass(ni_tag, cb);
+                    }
+                };
+                if (iters <= 1) all_chunks(std::integral_constant<int, 1>{});
+                else if (iters <= 2) all_chunks(std::integral_constant<int, 2>{});
+                else if (iters <= 4) all_chunks(std::integral_constant<int, 4>{});
+                else all_chunks(std::integral_constant<int, kRegIters>{});
                 const float thr = block_min(ub_min) * kScreenWindow;
                 // one bit per position of the thread that may hold the minimum; the (few) set bits are
                 // listed by one loop, so the kernel holds the listing code once and not per register
