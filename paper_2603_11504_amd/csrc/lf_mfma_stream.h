@@ -77,6 +77,7 @@ typedef __attribute__((address_space(1))) float *g_f32p;
 typedef __attribute__((address_space(1))) const u32x4 *g_cu32x4p;
 typedef __attribute__((address_space(1))) const f32x4 *g_cf32x4p;
 typedef __attribute__((address_space(1))) u32x2 *g_u32x2p;
+typedef __attribute__((address_space(1))) const u32x2 *g_cu32x2p;
 typedef __attribute__((address_space(1))) uint32_t *g_u32p;
 
 struct TileRegs {

@@ -331,16 +331,28 @@ __global__ __launch_bounds__(512, 1) void unit_mfma_kernel(const UnitArgs a_in, 
     // later loads of the row are ordered behind the stores.  The row is written through to
     // the device-wide coherence point: with several workgroups per unit, the one that ends
     // up re-scoring candidates may sit on another XCD and must not see the old row.
-    const int ins_slot = (STASH != kStashNone) ? pending[u] : -1; // requested first, used after the query loads below have been issued
-
-    // Copies of the query -- LDS for the exact re-scoring, device memory for a later
-    // longflow_scores() -- are made now: their load latency hides behind the streaming
-    // instead of standing in the serial tail of the kernel.
-    if (STASH == kStashLds) {
-        for (int i = tid; i < G * D; i += 512) qs[i / D][i % D] = qu[i];
+    // Everything the kernel needs from memory before it can stream is requested in one go, and nothing
+    // is used before all of it has been asked for: the pending slot, the query (once for the copies
+    // below, once as the matrix operand), the wave's first three tiles.  One trip to memory at the start
+    // of the kernel, where a load followed by its use, three times over, had cost three.  (No loop may
+    // stand between a request and its use: the compiler drains every outstanding load in front of one.)
+    // (the unit index goes through a vector register the compiler cannot see through: a load it knows to
+    // be uniform it moves to a scalar register at once, which waits for it on the spot)
+    int u_vec = u;
+    asm volatile("" : "+v"(u_vec));
+    const int ins_slot = (STASH != kStashNone) ? pending[u_vec] : -1;
+    // the query, 4 elements a thread: G * D <= 2048 = 512 x 4
+    const bool q_mine = 4 * tid < G * D;
+    u32x2 q4 = {0u, 0u};
+    if (q_mine) q4 = *(g_cu32x2p)(qu + 4 * tid);
+    // the new token's row, by every wave: which one inserts it is known only when the pending slot is
+    uint32_t new_k = 0u, new_v = 0u;
+    u32x4 new_vv = {0u, 0u, 0u, 0u};
+    if (STASH != kStashNone && k_new && v_new) {
+        new_k = *((g_cu32p)(k_new + (size_t)u * D) + lane);
+        new_v = *((g_cu32p)(v_new + (size_t)u * D) + lane);
+        new_vv = *(g_cu32x4p)(v_new + (size_t)u * D + 8 * r);
     }
-    if (sp == 0)
-        for (int i = tid; i < G * D; i += 512) q_last[(size_t)u * G * D + i] = qu[i];
 
     MfmaStreamer<NW, HILO, STASH, MASKED, false, MAXFREE> st;
     st.init(qu, G, lane, a.scale_log2);
@@ -352,18 +364,24 @@ __global__ __launch_bounds__(512, 1) void unit_mfma_kernel(const UnitArgs a_in, 
     st.ls_code = ls_code;
     st.ls_ref = ls_ref;
     st.code_stride = a.code_stride;
-    // the wave's first tiles are requested before anything waits for the pending slot: one trip to
-    // memory for slot, query and tiles together at the start of the kernel instead of two
     TileRegs ta, tb, tc;
     const bool requested = st.request_first_tiles(wave, ta, tb, tc);
+
+    // Copies of the query -- LDS for the exact re-scoring, device memory for a later
+    // longflow_scores() -- made at the start: their latency hides behind the streaming instead of
+    // standing in the serial tail of the kernel.
+    if (q_mine) {
+        if (STASH == kStashLds) *(u32x2 *)(&qs[0][0] + 4 * tid) = q4;
+        if (sp == 0) *(g_u32x2p)(q_last + (size_t)u * G * D + 4 * tid) = q4;
+    }
 
     if (STASH != kStashNone) {
         const int slot = ins_slot;
         if (slot >= start && slot < start + a.split_len && slot < N && (((slot - start) / kTile) % NW) == wave) {
-            st_agent((g_u32p)(Ku + (size_t)slot * D) + lane, *((g_cu32p)(k_new + (size_t)u * D) + lane));
-            st_agent((g_u32p)(Vu + (size_t)slot * D) + lane, *((g_cu32p)(v_new + (size_t)u * D) + lane));
+            st_agent((g_u32p)(Ku + (size_t)slot * D) + lane, new_k);
+            st_agent((g_u32p)(Vu + (size_t)slot * D) + lane, new_v);
             // every 16-lane row sums |v_new| redundantly; lane 0 stores the log2 norm
-            const u32x4 vv = *(g_cu32x4p)(v_new + (size_t)u * D + 8 * r);
+            const u32x4 vv = new_vv;
             float a1 = fabsf(bf16_lo(vv.x)) + fabsf(bf16_hi(vv.x)) + fabsf(bf16_lo(vv.y)) + fabsf(bf16_hi(vv.y)) +
                        fabsf(bf16_lo(vv.z)) + fabsf(bf16_hi(vv.z)) + fabsf(bf16_lo(vv.w)) + fabsf(bf16_hi(vv.w));
             a1 = row16_sum(a1);
