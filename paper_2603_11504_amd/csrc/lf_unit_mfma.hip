@@ -269,6 +269,10 @@ template <bool HILO, int STASH, bool COOP, bool GROUPED, bool MASKED, bool MAXFR
 __global__ __launch_bounds__(512, 1) void unit_mfma_kernel(const UnitArgs a_in, const GroupArgs ga)
 {
     UnitArgs a = a_in;
+    // (every argument the start of the kernel reads is asked for here, in one batch of scalar loads:
+    // left alone, the compiler fetches them in two, the second behind the first's wait)
+    asm volatile("" ::"s"(a.Kc), "s"(a.pending), "s"(a.lu), "s"(a.n), "s"(a.split_len), "s"(a.code_stride), "s"(a.merge_off),
+                 "s"(a.scale_log2));
     int blk = blockIdx.x;
     if (GROUPED) {
         // which cache this workgroup serves; the geometry and the step's scalars are common
