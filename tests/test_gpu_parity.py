@@ -111,7 +111,8 @@ def test_cfg4_full_size_sampled_units():
 
 @pytest.mark.parametrize("B,Hq,Hkv,N,sample", [
     (48, 8, 4, 20000, 8),    # one workgroup per unit, more slots than its register window screens in one pass
-    (1, 8, 2, 60000, None),  # eight workgroups per unit
+    (1, 8, 2, 60000, None),  # eight workgroups per unit, their codes copied a chunk at a time, decoded twice
+    (1, 32, 2, 16000, None), # the same with 16 heads a group inside the register window: chunks, one decode pass
     (1, 7, 1, 200000, None), # codes exceed LDS even eight ways: the split-K path is chosen by itself
     (1, 2, 1, 1 << 24, None), # the largest budget the interface accepts (4 GiB of K, 4 GiB of V in one unit)
 ])
