@@ -105,8 +105,13 @@ __global__ __launch_bounds__(64 * NWV) void fill_attend_kernel(const FillArgs a)
         if (ti * kTile >= n_max) return; // past what this wave's tokens see (uniform over the wave)
         Streamer::build_v_in_place(t);
         const bool cmask_now = (ti + 1) * kTile > first_limit;
+        // the logits of every product go to the matrix pipe before the vector work of the first begins (+1 %;
+        // going further and issuing the NEXT tile's logits before this tile's vector work bought nothing)
+        float s[NB][4];
 #pragma unroll
-        for (int nb = 0; nb < NB; ++nb) st[nb].template compute_core<false, true, true>(t, ti, cmask_now);
+        for (int nb = 0; nb < NB; ++nb) st[nb].logits(t, s[nb]);
+#pragma unroll
+        for (int nb = 0; nb < NB; ++nb) st[nb].template finish_tile<false, true, true>(t, ti, s[nb], cmask_now);
     };
 
     // ---- every thread of the workgroup runs the same nt rounds (one barrier each)

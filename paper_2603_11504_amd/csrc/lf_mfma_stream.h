@@ -246,15 +246,11 @@ struct MfmaStreamer {
         compute_core<RAGGED, CAUSAL, false>(t, ti);
     }
 
-    // One tile of one product, from rows already cleaned (zero_ragged).
-    // CMASK: the column's causal row limit may apply; `cmask_now` (uniform over the wave) says whether this tile
-    //        needs the test at all -- tiles that every column of the wave sees whole skip it
-    // VPRE:  t.v already holds the P V operands (build_v_in_place)
-    template <bool RAGGED, bool CMASK, bool VPRE> __device__ __forceinline__ void compute_core(const TileRegs &t, int ti, bool cmask_now = true)
+    // The two halves of a tile (logits, then everything else), callable apart so that a kernel with several products per wave can have
+    // the logits of all of them on the matrix pipe before the vector work of the first begins.
+    __device__ __forceinline__ void logits(const TileRegs &t, float (&s)[4]) const
     {
-        const int base = start + ti * kTile;
         // ---- S^T = K Q^T: per 8-row group, one product per chunk parity b
-        float s[4];
         if (KNAT) {
             f32x4 d = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
@@ -277,6 +273,23 @@ struct MfmaStreamer {
             s[2 * a + 0] = d0[0] + d1[1];
             s[2 * a + 1] = d0[2] + d1[3];
         }
+    }
+
+    // One tile of one product, from rows already cleaned (zero_ragged).
+    // CMASK: the column's causal row limit may apply; `cmask_now` (uniform over the wave) says whether this tile
+    //        needs the test at all -- tiles that every column of the wave sees whole skip it
+    // VPRE:  t.v already holds the P V operands (build_v_in_place)
+    template <bool RAGGED, bool CMASK, bool VPRE> __device__ __forceinline__ void compute_core(const TileRegs &t, int ti, bool cmask_now = true)
+    {
+        float s[4];
+        logits(t, s);
+        finish_tile<RAGGED, CMASK, VPRE>(t, ti, s, cmask_now);
+    }
+
+    template <bool RAGGED, bool CMASK, bool VPRE>
+    __device__ __forceinline__ void finish_tile(const TileRegs &t, int ti, float (&s)[4], bool cmask_now = true)
+    {
+        const int base = start + ti * kTile;
         if (RAGGED) {
 #pragma unroll
             for (int e = 0; e < 4; ++e)
