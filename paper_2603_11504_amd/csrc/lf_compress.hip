@@ -67,11 +67,11 @@ struct KRows {
 // K tiles of a span, staged through LDS.  The four waves of a workgroup want the same 16-row tiles as
 // operands; if each fetched them for itself, the compute unit's vector-memory path would be the limit of
 // both passes (counters: TA_TA_BUSY 85 % / 60 %).  Instead the 256 threads fetch a tile once, 16 bytes per
-// thread, park it in a ring of four LDS slots (rows padded to 272 bytes, so that the 16-byte operand reads
-// of eight neighbouring lanes fall into distinct banks), and every wave reads its operands from there.
+// thread, park it in a ring of four LDS slots (rows padded to 288 bytes: the stride at which the 16-byte operand
+// reads run at the full LDS rate), and every wave reads its operands from there.
 // One barrier per tile; the fetch of tile i + 4 is in flight while tile i is used.
 struct KRing {
-    static constexpr int RS = 272, SLOT = kTile * RS, NSLOT = 4;
+    static constexpr int RS = 288, SLOT = kTile * RS, NSLOT = 4; // 288: the stride at which this read pattern runs at the full LDS rate (timed: two thirds of it at 272, 304, 320)
     unsigned char *ring;   // NSLOT * SLOT bytes of LDS
     const uint16_t *src;   // this thread's 16 bytes of row 0 of the unit's K
     int st_row, st_off, first, last_tile, last_row, g, r;

@@ -51,14 +51,17 @@ __global__ __launch_bounds__(256) void fill_insert_kernel(const FillArgs a)
 // and every wave takes its MFMA operands from there.  (When every wave fetched every tile for itself the
 // caches served seven of the eight fetches, but each still went through the compute unit's vector-memory
 // path, and the counters showed that path -- TA_TA_BUSY 94 % -- not HBM or the matrix pipe as the limit:
-// 6.7 M tokens/s against 9.9 M this way on a 64 x 4 x 8192-slot cache.)  Rows are padded to 272 bytes in LDS so that the 16-byte operand reads of eight
-// neighbouring lanes fall into distinct banks.  One barrier per tile; the fetch of tile i + 4 is issued
+// 6.7 M tokens/s against 9.9 M this way on a 64 x 4 x 8192-slot cache.)  Rows are padded in LDS (288 bytes for K, 320 for V: see the constants)
+// so that the 16-byte operand reads run at the full LDS rate.  One barrier per tile; the fetch of tile i + 4 is issued
 // while tile i is computed, two registers of a thread carry the two fetches in flight.
 template <int NB, int NWV>
 __global__ __launch_bounds__(64 * NWV) void fill_attend_kernel(const FillArgs a)
 {
     static_assert(NWV == 8, "one 16-byte fetch per thread and tile: 512 threads for 8 KiB of K and V");
-    constexpr int D = 128, RS = 272, SLOT = 2 * kTile * RS, NSLOT = 4;
+    // row strides in LDS, found by timing the two operand read patterns on this chip (ds_read_b128, eight waves): the K
+    // pattern (16 rows x 16 bytes per quarter-wave) runs at full LDS rate at 288 bytes and at two thirds of it at 272,
+    // 304, 320 ...; the V pattern (256 contiguous bytes per quarter-wave, quarter-waves four rows apart) at 320 only
+    constexpr int D = 128, RSK = 288, RSV = 320, VOFF = kTile * RSK, SLOT = kTile * (RSK + RSV), NSLOT = 4;
     typedef MfmaStreamer<1, false, kStashNone, false, true, false, true> Streamer;
     __shared__ __align__(16) unsigned char ring[NSLOT * SLOT];
     const int G = a.G, units = a.units, QW = NB * a.qpb;
@@ -87,7 +90,7 @@ __global__ __launch_bounds__(64 * NWV) void fill_attend_kernel(const FillArgs a)
     // staging role of this thread: 16 bytes of row st_row of the K tile (threads 0..255) or the V tile
     const int st_row = (tid & 255) >> 4, st_chunk = tid & 15;
     const g_cu16p src = (g_cu16p)((tid < 256 ? a.Kc : a.Vc) + (size_t)u * a.N * D) + st_chunk * 8;
-    const int st_off = (tid < 256 ? 0 : kTile * RS) + st_row * RS + st_chunk * 16;
+    const int st_off = (tid < 256 ? st_row * RSK : VOFF + st_row * RSV) + st_chunk * 16;
     auto fetch = [&](int ti) __attribute__((always_inline)) { // rows past the last one the workgroup sees: that row again
         return *(g_cu32x4p)(src + (size_t)min(min(ti, nt - 1) * kTile + st_row, wg_nmax - 1) * D);
     };
@@ -96,9 +99,9 @@ __global__ __launch_bounds__(64 * NWV) void fill_attend_kernel(const FillArgs a)
     auto operands = [&](TileRegs &t, int ti) __attribute__((always_inline)) {
         const unsigned char *base = ring + (ti % NSLOT) * SLOT;
 #pragma unroll
-        for (int c = 0; c < 4; ++c) t.k[c >> 1][c & 1] = *(const u32x4 *)(base + r * RS + 64 * c + 16 * g);
+        for (int c = 0; c < 4; ++c) t.k[c >> 1][c & 1] = *(const u32x4 *)(base + r * RSK + 64 * c + 16 * g);
 #pragma unroll
-        for (int e = 0; e < 4; ++e) t.v[e] = *(const u32x4 *)(base + (kTile + 4 * g + e) * RS + 16 * r);
+        for (int e = 0; e < 4; ++e) t.v[e] = *(const u32x4 *)(base + VOFF + (4 * g + e) * RSV + 16 * r);
     };
     const int first_limit = a.n0 + t0 + 1; // rows the wave's first token sees; later tokens see more
     auto compute = [&](TileRegs &t, int ti) __attribute__((always_inline)) {
