@@ -104,20 +104,30 @@ __global__ __launch_bounds__(64 * NWV) void fill_attend_kernel(const FillArgs a)
         for (int e = 0; e < 4; ++e) t.v[e] = *(const u32x4 *)(base + VOFF + (4 * g + e) * RSV + 16 * r);
     };
     const int first_limit = a.n0 + t0 + 1; // rows the wave's first token sees; later tokens see more
-    auto compute = [&](TileRegs &t, int ti) __attribute__((always_inline)) {
+    // Two tiles at a time: the logits of both tiles and both products go to the matrix pipe first, then the
+    // weights of the first tile, of the second (which may still move the reference: it rescales the first's),
+    // and one P V product over the 32 slots of the pair.
+    auto compute_pair = [&](TileRegs &t0r, TileRegs &t1r, int ti) __attribute__((always_inline)) {
         if (ti * kTile >= n_max) return; // past what this wave's tokens see (uniform over the wave)
-        Streamer::build_v_in_place(t);
-        const bool cmask_now = (ti + 1) * kTile > first_limit;
-        // the logits of every product go to the matrix pipe before the vector work of the first begins (+1 %;
-        // going further and issuing the NEXT tile's logits before this tile's vector work bought nothing)
-        float s[NB][4];
+        float s0[NB][4], s1[NB][4];
 #pragma unroll
-        for (int nb = 0; nb < NB; ++nb) st[nb].logits(t, s[nb]);
+        for (int nb = 0; nb < NB; ++nb) { st[nb].logits(t0r, s0[nb]); st[nb].logits(t1r, s1[nb]); }
+        Streamer::build_v_in_place(t0r);
+        Streamer::build_v_in_place(t1r);
+        const bool cm0 = (ti + 1) * kTile > first_limit, cm1 = (ti + 2) * kTile > first_limit;
 #pragma unroll
-        for (int nb = 0; nb < NB; ++nb) st[nb].template finish_tile<false, true, true>(t, ti, s[nb], cmask_now);
+        for (int nb = 0; nb < NB; ++nb) {
+            float p0[4], p1[4];
+            st[nb].tile_weights(ti, s0[nb], cm0, p0, nullptr);
+            st[nb].tile_weights(ti + 1, s1[nb], cm1, p1, p0);
+            st[nb].pv_pair(t0r, t1r, p0, p1);
+        }
     };
 
-    // ---- every thread of the workgroup runs the same nt rounds (one barrier each)
+    // ---- every thread of the workgroup runs the same rounds, two tiles and one barrier each: while the pair
+    // in two of the four ring slots is computed, the next pair (fetched a round ago) goes into the other two
+    // and the pair after that is requested.  A tile past the last one the workgroup sees is that tile again
+    // (fetch clamps), masked out by the causal limits.
     {
         u32x4 q0 = fetch(0), q1 = fetch(1);
         park(0, q0);
@@ -125,22 +135,16 @@ __global__ __launch_bounds__(64 * NWV) void fill_attend_kernel(const FillArgs a)
         q0 = fetch(2);
         q1 = fetch(3);
         __syncthreads();
-        TileRegs ta, tb;
-        operands(ta, 0);
         for (int i = 0; i < nt; i += 2) {
-            // round i: tile i + 2 goes to LDS (its fetch was issued two rounds ago), tile i + 4 is requested
             park(i + 2, q0);
+            park(i + 3, q1);
             q0 = fetch(i + 4);
-            operands(tb, i + 1); // parked a round ago, barrier since
-            compute(ta, i);
+            q1 = fetch(i + 5);
+            TileRegs ta, tb;
+            operands(ta, i);
+            operands(tb, i + 1);
+            compute_pair(ta, tb, i);
             __syncthreads();
-            if (i + 1 < nt) {
-                park(i + 3, q1);
-                q1 = fetch(i + 5);
-                operands(ta, i + 2);
-                compute(tb, i + 1);
-                __syncthreads();
-            }
         }
     }
     if (!has_tokens) return;

@@ -275,6 +275,56 @@ struct MfmaStreamer {
         }
     }
 
+    // Two tiles per P V product (multi-query kernels; single bf16 weights, t.v built in place).  The weights of
+    // a tile are left in fp32 so that the second tile of a pair can still move the reference: it rescales the
+    // first tile's pending weights along with the sums.  Then ONE matrix instruction per 16 channels contracts
+    // over the 32 slots of both tiles (v_mfma_f32_16x16x32_bf16: lane (g, r) supplies k = 8g .. 8g+7, taken
+    // here as slots 4g .. 4g+3 of the first tile followed by the same slots of the second, for both operands)
+    // where the one-tile form needs two half-rate 16x16x16 instructions.
+    __device__ __forceinline__ void tile_weights(int ti, float (&s)[4], bool cmask_now, float (&p)[4], float *p_prev)
+    {
+        const int base = start + ti * kTile;
+        if (cmask_now) {
+#pragma unroll
+            for (int e = 0; e < 4; ++e)
+                if (base + slot_off(e) >= limit) s[e] = -INFINITY;
+        }
+        const float mx = fmaxf(fmaxf(s[0], s[1]), fmaxf(s[2], s[3])) * scale_log2;
+        if (!MAXFREE && __any(mx > m + kMaxSlack)) {
+            float mw = fmaxf(mx, __shfl_xor(mx, 16));
+            mw = fmaxf(mw, __shfl_xor(mw, 32));
+            const float m_new = (mw > m + kMaxSlack) ? mw : m;
+            const float a = fast_exp2(m - m_new);
+            l *= a;
+            if (p_prev) { // weights of the pair's first tile, this lane's own column
+#pragma unroll
+                for (int e = 0; e < 4; ++e) p_prev[e] *= a;
+            }
+#pragma unroll
+            for (int v = 0; v < 4; ++v) {
+                const float av = __shfl(a, 4 * g + v);
+#pragma unroll
+                for (int dd = 0; dd < 8; ++dd) oacc[dd][v] *= av;
+            }
+            m = m_new;
+        }
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+            p[e] = fast_exp2(fmaf(s[e], scale_log2, -m));
+            l += p[e];
+        }
+    }
+    __device__ __forceinline__ void pv_pair(const TileRegs &t0, const TileRegs &t1, const float (&p0)[4], const float (&p1)[4])
+    {
+        const u32x4 pa = {pack_bf16x2(p0[0], p0[1]), pack_bf16x2(p0[2], p0[3]), pack_bf16x2(p1[0], p1[1]), pack_bf16x2(p1[2], p1[3])};
+#pragma unroll
+        for (int dd = 0; dd < 8; ++dd) {
+            const int i = dd >> 1, j = 2 * (dd & 1);
+            const u32x4 vb = {t0.v[i][j], t0.v[i][j + 1], t1.v[i][j], t1.v[i][j + 1]};
+            oacc[dd] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, pa), __builtin_bit_cast(bf16x8, vb), oacc[dd], 0, 0, 0);
+        }
+    }
+
     // One tile of one product, from rows already cleaned (zero_ragged).
     // CMASK: the column's causal row limit may apply; `cmask_now` (uniform over the wave) says whether this tile
     //        needs the test at all -- tiles that every column of the wave sees whole skip it
