@@ -173,7 +173,7 @@ LF_API int longflow_decode_step(longflow_cache_t *cache, const void *q,
  * depend on each other only through the appended rows: for the tokens that find a
  * free slot, bf16 / head_dim 128 caches write all rows first and take the queries
  * through attention several at a time, reading the cache once per
- * 16 * floor(16 / (Hq/Hkv)) tokens (the fill phase in bulk; there the weights enter the
+ * 24 * floor(16 / (Hq/Hkv)) tokens (the fill phase in bulk; there the weights enter the
  * P V product rounded to bf16, as fused attention kernels commonly do, so an attention
  * output can differ from the single step's by one unit in the last place of bf16 -- rows,
  * decision and scores are the same).  Tokens beyond the
