@@ -29,6 +29,7 @@
 #include <algorithm>
 #include <cstring>
 
+#include <atomic>
 #include "lf_mfma_stream.h"
 
 namespace lf {
@@ -1008,7 +1009,7 @@ size_t unit_mfma_lds_bytes(int N, int G, bool stash, int S) { return unit_lds(N,
 // One launch of one kernel instance.  The dynamic-LDS ceiling is a per-device function
 // attribute: it is raised once per device and instance (attr_done, indexed by idx).
 struct UnitLaunch {
-    bool *attr_done;
+    std::atomic<bool> *attr_done;
     long long wgs;
     size_t lds;
     hipStream_t s;
@@ -1021,10 +1022,10 @@ template <int STASH, bool COOP, bool GROUPED, bool MASKED, bool MAXFREE>
 static hipError_t launch_instance(const UnitLaunch &ul, int idx)
 {
     auto kern = unit_mfma_kernel<true, STASH, COOP, GROUPED, MASKED, MAXFREE>;
-    if (!ul.attr_done[idx]) {
+    if (!ul.attr_done[idx].load(std::memory_order_acquire)) {
         hipError_t e = hipFuncSetAttribute((const void *)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)kUnitLdsLimit);
         if (e != hipSuccess) return e;
-        ul.attr_done[idx] = true;
+        ul.attr_done[idx].store(true, std::memory_order_release);
     }
     hipLaunchKernelGGL(kern, dim3((unsigned)ul.wgs), dim3(512), ul.lds, ul.s, *ul.a, *ul.ga);
     return hipGetLastError();
@@ -1095,9 +1096,10 @@ static hipError_t launch_unit(const Plan &p, const StepIo &io, int n, const void
     if (wgs <= 2 * 256 && lds < 81 * 1024) lds = 81 * 1024;
     if (wgs > 0x7fffffffll) return hipErrorInvalidValue;
     // the dynamic-LDS ceiling is a per-device function attribute: raise it once per device
-    // and kernel instance (a benign race if two host threads get here together: both set it)
+    // and kernel instance (two host threads that get here together both set it: the call is idempotent, the
+    // flags are atomic)
     constexpr int kMaxDevices = 64;
-    static bool attr_done_all[kMaxDevices][kUnitInstances] = {};
+    static std::atomic<bool> attr_done_all[kMaxDevices][kUnitInstances] = {};
     int dev = 0;
     if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) return hipErrorInvalidDevice;
     const UnitLaunch ul = {attr_done_all[dev], wgs, lds, s, &a, &ga};
